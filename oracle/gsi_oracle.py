@@ -1,0 +1,237 @@
+"""CPU oracle for the gated subspace linear layer -- TEST INFRASTRUCTURE ONLY.
+
+A plain fp64 NumPy implementation of what the hot path computes, written from
+the paper (Section 3: Eq. (decompose), Eq. (exact), Eq. (gate), Eq. (speedup),
+Theorem "Per-layer error bound"; Section 4: Algorithm 1, "Storage"; Section 6:
+Definition "Effective parameter count").  It is slow on purpose: every step is
+one line of textbook linear algebra in the paper's order, with no blocking,
+fusion or reordering, so it can be checked against the paper by eye.
+
+Only tests, the smoke check and the benchmark's ``cpu_baseline`` leg may import
+this file.  It shares no code with the HIP path and imports nothing from it.
+
+Notation: ``U`` is the paper's basis V_k (d x k), ``c`` its g = V_k^T x,
+``M = W U`` the cached image, ``r`` the residual, ``rho`` the residual ratio.
+Layouts are row-major: W[m, d], U[d, k], M[m, k], X[B, d], C[B, k], R[B, d],
+Y[B, m].  Stored operands arrive as fp32 arrays or as uint16 bfloat16 bit
+patterns and are widened exactly; all arithmetic after that is IEEE fp64.
+
+Readings where the paper is silent or at odds with itself (each also listed in
+the design notes):
+  * tie: a token is on the fast path iff rho < eps (Definition "Activation basis
+    and residual ratio", Algorithm 1), so the gate *fires* iff rho >= eps;
+  * x = 0: rho is taken as 0 and the gate does not fire;
+  * the norm is the Euclidean norm;
+  * the fired-token output is M c + W r (Eq. (exact)); Algorithm 1 prints W x
+    for the slow path, which is the same value in exact arithmetic --
+    ``gated_linear_alg1`` is that variant;
+  * eps is the fp32 value the device receives, widened to fp64.
+
+Every function here is pinned by tests that do not call the oracle to obtain
+their expected value (hand-worked numbers, closed forms, invariants, brute
+force on tiny inputs, values printed in the paper's tables).
+"""
+from __future__ import annotations
+
+from typing import Dict, List, Sequence, Tuple
+
+import numpy as np
+
+F32 = "f32"
+BF16 = "bf16"
+
+
+def widen(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Exact fp64 value of a stored operand (fp32 array, or uint16 bf16 bit patterns)."""
+    if dtype == F32:
+        a = np.asarray(a)
+        if a.dtype != np.float32:
+            raise TypeError("f32 operand must be a float32 array")
+        return a.astype(np.float64)
+    if dtype == BF16:
+        a = np.asarray(a)
+        if a.dtype != np.uint16:
+            raise TypeError("bf16 operand must be a uint16 array of bit patterns")
+        # bfloat16 is the upper half of an IEEE binary32 word
+        return (a.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+# ----------------------------------------------------------------------------
+# Algorithm 1, lines 1-3 / Eq. (decompose), Eq. (gate)
+# ----------------------------------------------------------------------------
+def project(U: np.ndarray, X: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """c_t = U^T x_t ; r_t = x_t - U c_t ; |r_t| ; |x_t|, for every row t of X.
+
+    U[d, k], X[B, d] in fp64.  Returns C[B, k], R[B, d], rnorm[B], xnorm[B].
+    The residual is formed explicitly (Algorithm 1, line 2), never through
+    |x|^2 - |c|^2.
+    """
+    U = np.asarray(U, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    B, d = X.shape
+    k = U.shape[1]
+    assert U.shape[0] == d
+    C = np.empty((B, k))
+    R = np.empty((B, d))
+    rnorm = np.empty(B)
+    xnorm = np.empty(B)
+    for t in range(B):
+        x = X[t]
+        c = U.T @ x                      # Algorithm 1, line 1
+        r = x - U @ c                    # Algorithm 1, line 2
+        C[t] = c
+        R[t] = r
+        rnorm[t] = np.sqrt(np.sum(r * r))
+        xnorm[t] = np.sqrt(np.sum(x * x))
+    return C, R, rnorm, xnorm
+
+
+def residual_ratio(rnorm: np.ndarray, xnorm: np.ndarray) -> np.ndarray:
+    """rho_t = |r_t| / |x_t| (Eq. (gate)); 0 where x_t = 0."""
+    rnorm = np.asarray(rnorm, dtype=np.float64)
+    xnorm = np.asarray(xnorm, dtype=np.float64)
+    rho = np.zeros_like(rnorm)
+    nz = xnorm > 0
+    rho[nz] = rnorm[nz] / xnorm[nz]
+    return rho
+
+
+def gate(rnorm: np.ndarray, xnorm: np.ndarray, eps: float) -> Tuple[np.ndarray, np.ndarray, int]:
+    """Gate of Section 3.2: fired_t = (rho_t >= eps).  eps is rounded to fp32 first.
+
+    Returns mask[B] (uint8), the ascending list of fired token indices (int32)
+    and its length.
+    """
+    eps64 = float(np.float32(eps))
+    rho = residual_ratio(rnorm, xnorm)
+    fired = (np.asarray(xnorm) > 0) & (rho >= eps64)
+    idx = np.nonzero(fired)[0].astype(np.int32)
+    return fired.astype(np.uint8), idx, int(idx.shape[0])
+
+
+# ----------------------------------------------------------------------------
+# Eq. (exact): cached image and the two paths
+# ----------------------------------------------------------------------------
+def build_image(W: np.ndarray, U: np.ndarray) -> np.ndarray:
+    """M = W U (Eq. (exact)), fp64, not rounded.  W[m, d], U[d, k] -> M[m, k]."""
+    return np.asarray(W, dtype=np.float64) @ np.asarray(U, dtype=np.float64)
+
+
+def dense_linear(W: np.ndarray, X: np.ndarray) -> np.ndarray:
+    """Baseline y_t = W x_t for every token.  W[m, d], X[B, d] -> Y[B, m]."""
+    W = np.asarray(W, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    Y = np.empty((X.shape[0], W.shape[0]))
+    for t in range(X.shape[0]):
+        Y[t] = W @ X[t]
+    return Y
+
+
+def gated_linear(W: np.ndarray, M: np.ndarray, C: np.ndarray, R: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """y_t = M c_t for every token, plus W r_t for fired tokens (Eq. (exact), gated)."""
+    W = np.asarray(W, dtype=np.float64)
+    M = np.asarray(M, dtype=np.float64)
+    B = C.shape[0]
+    Y = np.empty((B, W.shape[0]))
+    for t in range(B):
+        y = M @ C[t]                     # Algorithm 1, line 5
+        if mask[t]:
+            y = y + W @ R[t]             # Eq. (exact), second term
+        Y[t] = y
+    return Y
+
+
+def gated_linear_alg1(W: np.ndarray, M: np.ndarray, C: np.ndarray, X: np.ndarray, mask: np.ndarray) -> np.ndarray:
+    """Algorithm 1 as printed: y_t = W x_t on the slow path, M c_t on the fast path."""
+    W = np.asarray(W, dtype=np.float64)
+    M = np.asarray(M, dtype=np.float64)
+    B = C.shape[0]
+    Y = np.empty((B, W.shape[0]))
+    for t in range(B):
+        Y[t] = W @ X[t] if mask[t] else M @ C[t]
+    return Y
+
+
+# ----------------------------------------------------------------------------
+# a chain of per-layer linear maps (Section 1: every map of a block shares the
+# projection of its input)
+# ----------------------------------------------------------------------------
+def prepare_stack(groups: Sequence[dict]) -> List[dict]:
+    """Widen stored operands and build the fp64 images once (the one-time set-up of Section 4).
+
+    ``groups``: list of dicts {U, udtype, maps: [(name, W, wdtype), ...]}.
+    """
+    out = []
+    for g in groups:
+        U = widen(g["U"], g["udtype"])
+        maps = []
+        for name, W, wdtype in g["maps"]:
+            W64 = widen(W, wdtype)
+            maps.append((name, W64, build_image(W64, U)))
+        out.append({"U": U, "maps": maps})
+    return out
+
+
+def run_stack(prepared: Sequence[dict], Xs: Sequence[np.ndarray], eps: float) -> List[dict]:
+    """One pass: per input group project + gate once, then one gated linear map per weight.
+
+    ``Xs[g]`` is the fp64 token block X[B, d_g] of group g.  Returns per group
+    {C, R, rnorm, xnorm, rho, mask, fired_idx, n_fired, Y: {name: Y[B, m]}}.
+    """
+    res = []
+    for g, X in zip(prepared, Xs):
+        C, R, rn, xn = project(g["U"], X)
+        mask, idx, n = gate(rn, xn, eps)
+        Y = {name: gated_linear(W64, M64, C, R, mask) for name, W64, M64 in g["maps"]}
+        res.append(
+            {"C": C, "R": R, "rnorm": rn, "xnorm": xn, "rho": residual_ratio(rn, xn),
+             "mask": mask, "fired_idx": idx, "n_fired": n, "Y": Y}
+        )
+    return res
+
+
+def run_dense_stack(prepared: Sequence[dict], Xs: Sequence[np.ndarray]) -> List[Dict[str, np.ndarray]]:
+    """The baseline the method is compared with: y = W x for every map and token."""
+    return [{name: dense_linear(W64, X) for name, W64, _ in g["maps"]} for g, X in zip(prepared, Xs)]
+
+
+# ----------------------------------------------------------------------------
+# closed forms used for reporting
+# ----------------------------------------------------------------------------
+def effective_speedup(f: float, d: int, k: int) -> float:
+    """Eq. (speedup): S = 1 / (f / (d/k) + (1 - f)) for fast-path fraction f."""
+    return 1.0 / (f / (d / k) + (1.0 - f))
+
+
+def model_speedup(layers: Sequence[Tuple[float, int, int, float]]) -> float:
+    """Model-wide speedup: harmonic mean of S_l weighted by weight-read volume (Section 3.2).
+
+    ``layers``: (f_l, d_l, k_l, volume_l).  Equals total dense volume over total gated volume.
+    """
+    vol = sum(v for _, _, _, v in layers)
+    return vol / sum(v / effective_speedup(f, d, k) for f, d, k, v in layers)
+
+
+def effective_params(layers: Sequence[Tuple[int, int, int, int, float]]) -> float:
+    """Definition "Effective parameter count": sum_l N_W d_out [f k + (1 - f) d].
+
+    ``layers``: (N_W, d_out, d, k, f) per layer.
+    """
+    return float(sum(n * dout * (f * k + (1.0 - f) * d) for n, dout, d, k, f in layers))
+
+
+def image_storage_elems(n_maps_dout: Sequence[int], L: int, k: int) -> int:
+    """Section 4 "Storage": elements of cached images = L * k * sum of d_out over the maps."""
+    return L * k * int(sum(n_maps_dout))
+
+
+def basis_storage_elems(L: int, d: int, k: int) -> int:
+    """Section 4 "Storage": elements of the per-layer bases = L d k."""
+    return L * d * k
+
+
+def error_bound(W: np.ndarray, eps: float, xnorm: np.ndarray) -> np.ndarray:
+    """Theorem "Per-layer error bound": |W r| <= |W|_2 eps |x| on the fast path."""
+    s = np.linalg.svd(np.asarray(W, dtype=np.float64), compute_uv=False)[0]
+    return s * float(np.float32(eps)) * np.asarray(xnorm, dtype=np.float64)

@@ -1,0 +1,340 @@
+"""Pins for the CPU oracle: each takes the oracle module ``O`` and asserts a fact that is fixed by
+the paper or by mathematics, never by the oracle's own output.
+
+They are written as functions of ``O`` so that the same pins can be run against deliberately
+broken copies of the oracle (tests/test_oracle_mutants.py) to show that a plausible mistake in
+any step is caught by at least one of them.
+"""
+import math
+
+import numpy as np
+
+from paper_2605_03109_amd import workload as wl
+
+
+def _fsum_matvec(A, x):
+    """Brute-force y = A x with exactly rounded sums (math.fsum), plain Python loops."""
+    return np.array([math.fsum(float(A[i, j]) * float(x[j]) for j in range(A.shape[1])) for i in range(A.shape[0])])
+
+
+def _fsum_matmul(A, B):
+    return np.array(
+        [[math.fsum(float(A[i, l]) * float(B[l, j]) for l in range(A.shape[1])) for j in range(B.shape[1])]
+         for i in range(A.shape[0])]
+    )
+
+
+def pin_hand_worked_2d(O):
+    # Worked by hand: U = (3/5, 4/5)^T, x = (1, 2), W = [[1,2],[3,4],[5,6]].
+    # c = 11/5; U c = (33/25, 44/25); r = (-8/25, 6/25); |r| = 2/5; |x| = sqrt 5;
+    # M = W U = (11/5, 5, 39/5); M c = (4.84, 11, 17.16); W r = (0.16, 0, -0.16); M c + W r = W x = (5, 11, 17).
+    U = np.array([[0.6], [0.8]])
+    X = np.array([[1.0, 2.0]])
+    W = np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]])
+    C, R, rn, xn = O.project(U, X)
+    assert np.allclose(C, [[2.2]], rtol=0, atol=1e-15)
+    assert np.allclose(R, [[-0.32, 0.24]], rtol=0, atol=1e-15)
+    assert abs(rn[0] - 0.4) < 1e-15 and abs(xn[0] - math.sqrt(5.0)) < 1e-15
+    assert abs(O.residual_ratio(rn, xn)[0] - 0.4 / math.sqrt(5.0)) < 1e-15
+    M = O.build_image(W, U)
+    assert M.shape == (3, 1) and np.allclose(M[:, 0], [2.2, 5.0, 7.8], rtol=0, atol=1e-14)
+    y_fast = O.gated_linear(W, M, C, R, np.array([0], dtype=np.uint8))
+    y_slow = O.gated_linear(W, M, C, R, np.array([1], dtype=np.uint8))
+    assert np.allclose(y_fast, [[4.84, 11.0, 17.16]], rtol=0, atol=1e-13)
+    assert np.allclose(y_slow, [[5.0, 11.0, 17.0]], rtol=0, atol=1e-13)
+    y_alg1 = O.gated_linear_alg1(W, M, C, X, np.array([1], dtype=np.uint8))
+    assert np.allclose(y_alg1, [[5.0, 11.0, 17.0]], rtol=0, atol=1e-13)
+    assert np.allclose(O.dense_linear(W, X), [[5.0, 11.0, 17.0]], rtol=0, atol=1e-13)
+    # rho = 0.1789 >= 0.05 fires; at eps = 0.2 it does not
+    assert O.gate(rn, xn, 0.05)[2] == 1 and O.gate(rn, xn, 0.2)[2] == 0
+
+
+def pin_axis_aligned_basis(O):
+    # U = columns of the identity: c picks coordinates, r zeroes them, M picks columns of W.
+    rng = np.random.default_rng(11)
+    d, k, m, B = 9, 4, 5, 3
+    sel = np.array([7, 2, 5, 0])
+    U = np.zeros((d, k))
+    U[sel, np.arange(k)] = 1.0
+    X = rng.standard_normal((B, d))
+    W = rng.standard_normal((m, d))
+    C, R, rn, xn = O.project(U, X)
+    assert np.array_equal(C, X[:, sel])
+    Rexp = X.copy()
+    Rexp[:, sel] = 0.0
+    assert np.array_equal(R, Rexp)
+    rest = np.setdiff1d(np.arange(d), sel)
+    for t in range(B):
+        assert abs(rn[t] - math.sqrt(math.fsum(v * v for v in X[t, rest]))) < 1e-14
+        assert abs(xn[t] - math.sqrt(math.fsum(v * v for v in X[t]))) < 1e-14
+    M = O.build_image(W, U)
+    assert np.array_equal(M, W[:, sel])
+    Y = O.gated_linear(W, M, C, R, np.array([1, 0, 1], dtype=np.uint8))
+    for t, fired in enumerate([1, 0, 1]):
+        cols = np.arange(d) if fired else sel
+        yexp = _fsum_matvec(W[:, cols], X[t, cols])
+        assert np.allclose(Y[t], yexp, rtol=0, atol=1e-13)
+
+
+def pin_brute_force_tiny(O):
+    # Odd, non-square shapes; exactly rounded loop sums as the reference.
+    rng = np.random.default_rng(5)
+    d, k, m, B = 12, 3, 5, 4
+    U, _ = np.linalg.qr(rng.standard_normal((d, k)))
+    X = rng.standard_normal((B, d))
+    W = rng.standard_normal((m, d))
+    C, R, rn, xn = O.project(U, X)
+    for t in range(B):
+        c = _fsum_matvec(U.T, X[t])
+        assert np.allclose(C[t], c, rtol=0, atol=1e-14)
+        uc = _fsum_matvec(U, c)
+        assert np.allclose(R[t], X[t] - uc, rtol=0, atol=1e-14)
+    M = O.build_image(W, U)
+    assert np.allclose(M, _fsum_matmul(W, U), rtol=0, atol=1e-14)
+    mask = np.array([1, 0, 0, 1], dtype=np.uint8)
+    Y = O.gated_linear(W, M, C, R, mask)
+    for t in range(B):
+        y = _fsum_matvec(_fsum_matmul(W, U), _fsum_matvec(U.T, X[t]))
+        if mask[t]:
+            y = y + _fsum_matvec(W, X[t] - _fsum_matvec(U, _fsum_matvec(U.T, X[t])))
+        assert np.allclose(Y[t], y, rtol=0, atol=1e-13)
+    assert np.allclose(O.dense_linear(W, X), np.array([_fsum_matvec(W, X[t]) for t in range(B)]), rtol=0, atol=1e-13)
+
+
+def pin_orthogonality_and_pythagoras(O):
+    # r is orthogonal to span(U) and |x|^2 = |c|^2 + |r|^2 for an orthonormal basis.
+    U = wl.make_basis64(96, 17, 3)
+    assert np.max(np.abs(U.T @ U - np.eye(17))) < 1e-12
+    X = np.random.default_rng(1).standard_normal((6, 96))
+    C, R, rn, xn = O.project(U, X)
+    assert np.max(np.abs(R @ U)) < 1e-12 * np.max(xn)
+    assert np.allclose(xn**2, np.sum(C * C, axis=1) + rn**2, rtol=1e-12, atol=0)
+    assert np.allclose(X, C @ U.T + R, rtol=0, atol=1e-13)
+    rho = O.residual_ratio(rn, xn)
+    assert np.all(rho >= 0) and np.all(rho <= 1.0 + 1e-15)
+
+
+def pin_designed_rho(O):
+    # The generator fixes rho_t in closed form: x = U a + sigma n, n unit and orthogonal to U
+    # => rho = sigma / sqrt(|a|^2 + sigma^2) = rho*.  Also the designed fire count is hit exactly.
+    w = wl.tiny(d=80, k=12, m=7, T=24, n_fired=7, seed=99)
+    g = w.groups[0]
+    U = O.widen(g.U, w.wdtype)
+    X = O.widen(g.X, w.xdtype)
+    C, R, rn, xn = O.project(U, X)
+    rho = O.residual_ratio(rn, xn)
+    assert np.allclose(rho, g.rho_star, rtol=0, atol=5e-7)  # fp32 storage of U and x
+    mask, idx, n = O.gate(rn, xn, w.eps)
+    assert n == 7 and np.array_equal(mask.astype(bool), g.fired_design)
+    assert np.array_equal(idx, np.nonzero(g.fired_design)[0]) and idx.dtype == np.int32
+    assert np.all(np.diff(idx) > 0)
+
+
+def pin_full_rank_basis(O):
+    # k = d: the projection is the identity, r = 0, rho = 0, M c = W x.
+    rng = np.random.default_rng(2)
+    d, m = 10, 6
+    U = wl.make_basis64(d, d, 8)
+    X = rng.standard_normal((3, d))
+    W = rng.standard_normal((m, d))
+    C, R, rn, xn = O.project(U, X)
+    assert np.max(np.abs(R)) < 1e-14 and np.max(rn / xn) < 1e-14
+    Y = O.gated_linear(W, O.build_image(W, U), C, R, np.zeros(3, dtype=np.uint8))
+    assert np.allclose(Y, np.array([_fsum_matvec(W, x) for x in X]), rtol=0, atol=1e-13)
+
+
+def pin_monotone_in_k(O):
+    # Proposition "Monotonicity": nested bases => rho(k+1) <= rho(k); fired set shrinks.
+    U = wl.make_basis64(64, 40, 21)
+    X = np.random.default_rng(4).standard_normal((8, 64))
+    prev = None
+    prev_mask = None
+    for k in (1, 2, 5, 8, 16, 32, 40):
+        _, _, rn, xn = O.project(U[:, :k], X)
+        rho = O.residual_ratio(rn, xn)
+        mask = O.gate(rn, xn, 0.7)[0]
+        if prev is not None:
+            assert np.all(rho <= prev + 1e-15)
+            assert np.all(mask <= prev_mask)
+        prev, prev_mask = rho, mask
+
+
+def pin_all_fire_is_dense(O):
+    # Eq. (exact) is an identity: when every gate fires, y = W x.  Reference: extended-precision einsum.
+    rng = np.random.default_rng(6)
+    d, k, m, B = 70, 9, 33, 5
+    U = wl.make_basis64(d, k, 1)
+    X = rng.standard_normal((B, d))
+    W = rng.standard_normal((m, d))
+    C, R, rn, xn = O.project(U, X)
+    mask, idx, n = O.gate(rn, xn, 0.0)
+    assert n == B and np.all(mask == 1)
+    M = O.build_image(W, U)
+    Y = O.gated_linear(W, M, C, R, mask)
+    Yd = np.einsum("ij,tj->ti", W.astype(np.longdouble), X.astype(np.longdouble)).astype(np.float64)
+    assert np.max(np.linalg.norm(Y - Yd, axis=1) / np.linalg.norm(Yd, axis=1)) < 1e-13
+    assert np.max(np.abs(O.gated_linear_alg1(W, M, C, X, mask) - Yd)) < 1e-12
+    assert np.max(np.abs(O.dense_linear(W, X) - Yd)) < 1e-12
+
+
+def pin_none_fire_is_static_projection(O):
+    # eps > 1: no token fires and y = W (U (U^T x)) -- evaluated right-to-left here, so it never forms W U.
+    rng = np.random.default_rng(7)
+    d, k, m, B = 50, 6, 21, 4
+    U = wl.make_basis64(d, k, 2)
+    X = rng.standard_normal((B, d))
+    W = rng.standard_normal((m, d))
+    C, R, rn, xn = O.project(U, X)
+    mask, idx, n = O.gate(rn, xn, 1.5)
+    assert n == 0 and idx.shape == (0,) and not mask.any()
+    Y = O.gated_linear(W, O.build_image(W, U), C, R, mask)
+    for t in range(B):
+        x = X[t].astype(np.longdouble)
+        yexp = W.astype(np.longdouble) @ (U.astype(np.longdouble) @ (U.T.astype(np.longdouble) @ x))
+        assert np.linalg.norm(Y[t] - yexp.astype(np.float64)) < 1e-13 * np.linalg.norm(yexp.astype(np.float64)) + 1e-14
+
+
+def pin_error_bound(O):
+    # Theorem "Per-layer error bound": non-fired => |W x - y| = |W r| <= |W|_2 eps |x|; fired => 0.
+    w = wl.tiny(d=64, k=10, m=40, T=32, n_fired=9, seed=5)
+    g = w.groups[0]
+    U = O.widen(g.U, w.wdtype)
+    X = O.widen(g.X, w.xdtype)
+    W = O.widen(g.maps[0][2], w.wdtype)
+    C, R, rn, xn = O.project(U, X)
+    mask, _, _ = O.gate(rn, xn, w.eps)
+    Y = O.gated_linear(W, O.build_image(W, U), C, R, mask)
+    Yd = np.einsum("ij,tj->ti", W.astype(np.longdouble), X.astype(np.longdouble)).astype(np.float64)
+    err = np.linalg.norm(Y - Yd, axis=1)
+    # |W|_2 from power iteration on W^T W (independent of the oracle's SVD call)
+    v = np.ones(W.shape[1])
+    for _ in range(500):
+        v = W.T @ (W @ v)
+        v /= np.linalg.norm(v)
+    s2 = np.linalg.norm(W @ v)
+    bound = s2 * float(np.float32(w.eps)) * xn
+    assert np.all(err[mask == 0] <= bound[mask == 0] * (1 + 1e-9))
+    assert np.all(err[mask == 0] > 0)            # the fast path *is* an approximation
+    assert np.all(err[mask == 1] <= 1e-12 * np.linalg.norm(Yd, axis=1)[mask == 1])
+    assert np.allclose(O.error_bound(W, w.eps, xn), bound, rtol=1e-6)
+
+
+def pin_gate_boundary(O):
+    # fast path iff rho < eps; fires iff rho >= eps (Definition "Activation basis and residual ratio", Alg. 1).
+    eps32 = np.float32(0.05)
+    e = float(eps32)
+    xn = np.array([1.0, 1.0, 1.0, 2.0, 0.0, 4.0, 1.0])
+    rn = np.array([e, np.nextafter(e, 0.0), np.nextafter(e, 1.0), 2.0 * e, 0.0, 0.1, 0.0])
+    mask, idx, n = O.gate(rn, xn, 0.05)
+    assert mask.dtype == np.uint8 and mask.tolist() == [1, 0, 1, 1, 0, 0, 0]
+    assert idx.tolist() == [0, 2, 3] and n == 3
+    # eps = 0: every token with x != 0 fires, even with r = 0; x = 0 never fires
+    mask0, idx0, n0 = O.gate(rn, xn, 0.0)
+    assert mask0.tolist() == [1, 1, 1, 1, 0, 1, 1] and n0 == 6
+    # eps > 1 can never fire since rho <= 1
+    assert O.gate(np.array([1.0, 0.5]), np.array([1.0, 1.0]), 1.0000001)[2] == 0
+    # the threshold is the fp32 value of eps, not the fp64 literal 0.05 (0.05f > 0.05)
+    between = 0.5 * (0.05 + e)
+    assert O.gate(np.array([between]), np.array([1.0]), 0.05)[2] == 0
+
+
+def pin_batch_equals_per_token(O):
+    rng = np.random.default_rng(12)
+    d, k, m, B = 33, 5, 11, 6
+    U = wl.make_basis64(d, k, 3)
+    X = rng.standard_normal((B, d))
+    W = rng.standard_normal((m, d))
+    C, R, rn, xn = O.project(U, X)
+    mask, _, _ = O.gate(rn, xn, 0.93)
+    assert 0 < mask.sum() < B
+    M = O.build_image(W, U)
+    Y = O.gated_linear(W, M, C, R, mask)
+    for t in range(B):
+        Ct, Rt, rnt, xnt = O.project(U, X[t : t + 1])
+        mt, _, _ = O.gate(rnt, xnt, 0.93)
+        Yt = O.gated_linear(W, M, Ct, Rt, mt)
+        assert np.array_equal(Ct[0], C[t]) and np.array_equal(Rt[0], R[t]) and mt[0] == mask[t]
+        assert np.array_equal(Yt[0], Y[t])
+
+
+def pin_widen(O):
+    # bfloat16 bit patterns with known values: sign(1) exponent(8) mantissa(7)
+    bits = np.array([0x3F80, 0xC000, 0x3FC0, 0x0000, 0x8000, 0x0001, 0x7F7F, 0x3DCD], dtype=np.uint16)
+    vals = O.widen(bits, "bf16")
+    exp = [1.0, -2.0, 1.5, 0.0, -0.0, 2.0**-133, (2.0 - 2.0**-7) * 2.0**127, 0.10009765625]
+    assert vals.dtype == np.float64 and vals.tolist() == exp
+    assert math.copysign(1.0, vals[4]) == -1.0
+    a = np.array([0.1, -3.25], dtype=np.float32)
+    assert O.widen(a, "f32").tolist() == [float(np.float32(0.1)), -3.25]
+
+
+def pin_stack(O):
+    # run_stack = project + gate once per input, one gated map per weight; dense stack = W x.
+    w = wl.transformer_block("t", d=32, ffn=64, k=6, T=10, fire_rate=0.3, p=1.5, seed=77, wdtype="bf16")
+    groups = [{"U": g.U, "udtype": w.wdtype, "maps": [(n, W, w.wdtype) for n, _, W in g.maps]} for g in w.groups]
+    prep = O.prepare_stack(groups)
+    Xs = [O.widen(g.X, w.xdtype) for g in w.groups]
+    res = O.run_stack(prep, Xs, w.eps)
+    dense = O.run_dense_stack(prep, Xs)
+    assert [sorted(r["Y"]) for r in res] == [["k", "q", "v"], ["o"], ["fc_in"], ["fc_out"]]
+    for g, r, dn, X in zip(w.groups, res, dense, Xs):
+        assert r["n_fired"] == 3 and np.array_equal(r["mask"].astype(bool), g.fired_design)
+        Ub = wl.bf16_bits_to_f32(g.U).astype(np.longdouble)
+        for name, m, Wb in g.maps:
+            Wl = wl.bf16_bits_to_f32(Wb).astype(np.longdouble)
+            Yd = (X.astype(np.longdouble) @ Wl.T).astype(np.float64)
+            assert np.allclose(dn[name], Yd, rtol=0, atol=1e-12)
+            Ys = (((X.astype(np.longdouble) @ Ub) @ Ub.T) @ Wl.T).astype(np.float64)
+            fired = g.fired_design
+            assert np.allclose(r["Y"][name][fired], Yd[fired], rtol=0, atol=1e-12)
+            assert np.allclose(r["Y"][name][~fired], Ys[~fired], rtol=0, atol=1e-12)
+
+
+def pin_paper_speedups(O, rows):
+    # Eq. (speedup) against every (fast %, S_eff) pair the paper prints; the printed fast-path
+    # percentage is itself rounded to 0.1 %, so the printed S must lie in the image of that interval.
+    assert len(rows) == 27
+    for model, d, k, eps, fpct, sprinted in rows:
+        d, k, f, s = int(d), int(k), float(fpct) / 100.0, float(sprinted)
+        lo = O.effective_speedup(max(f - 0.0005, 0.0), d, k)
+        hi = O.effective_speedup(min(f + 0.0005, 1.0), d, k)
+        assert lo - 0.05 - 1e-9 <= s <= hi + 0.05 + 1e-9, (model, k, eps, lo, hi, s)
+    assert abs(O.effective_speedup(1.0, 4096, 256) - 16.0) < 1e-12
+    assert abs(O.effective_speedup(0.0, 4096, 256) - 1.0) < 1e-12
+    # model-wide value = harmonic mean weighted by weight volume = total dense volume / total gated volume
+    layers = [(0.9, 4096, 256, 3.0), (0.5, 4096, 128, 1.0)]
+    by_hand = 4.0 / (3.0 * (0.9 / 16 + 0.1) + 1.0 * (0.5 / 32 + 0.5))
+    assert abs(O.model_speedup(layers) - by_hand) < 1e-12
+
+
+def pin_paper_closed_forms(O, rows):
+    vals = {name: (float(v), float(tol)) for name, v, tol in rows}
+    v, tol = vals["basis_storage_bytes_gptj"]
+    assert abs(2 * O.basis_storage_elems(28, 4096, 256) - v) <= tol
+    v, tol = vals["image_storage_bytes_gptj_printed"]
+    assert abs(2 * O.image_storage_elems([4096, 4096, 4096, 4096, 16384], 28, 256) - v) <= tol
+    v, tol = vals["effective_params_gptj"]
+    # one "layer" holding all 6e9 parameters: N_W d_out d = 6e9 with d = 4096
+    assert abs(O.effective_params([(1, 6e9 / 4096, 4096, 256, 0.998)]) - v) <= tol
+    v, tol = vals["max_speedup_gptj_k256"]
+    assert abs(O.effective_speedup(1.0, 4096, 256) - v) <= tol
+    # f = 1 => P_eff is d/k smaller than the full count
+    assert abs(O.effective_params([(6, 4096, 4096, 256, 1.0)]) * 16 - 6 * 4096 * 4096) < 1e-6
+
+
+PINS = [
+    pin_hand_worked_2d,
+    pin_axis_aligned_basis,
+    pin_brute_force_tiny,
+    pin_orthogonality_and_pythagoras,
+    pin_designed_rho,
+    pin_full_rank_basis,
+    pin_monotone_in_k,
+    pin_all_fire_is_dense,
+    pin_none_fire_is_static_projection,
+    pin_error_bound,
+    pin_gate_boundary,
+    pin_batch_equals_per_token,
+    pin_widen,
+    pin_stack,
+]

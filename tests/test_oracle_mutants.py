@@ -1,0 +1,79 @@
+"""Plant plausible mistakes in copies of the CPU oracle and require that the pins catch each one.
+
+Every mutant is the oracle's own source with one line changed (a dropped term, a wrong sign, a
+transposed operand, a wrong index, an off-by-one comparison).  All of this runs on the CPU.
+"""
+import os
+import types
+
+import pytest
+
+from conftest import ROOT, read_golden
+from oracle_pins import PINS, pin_paper_closed_forms, pin_paper_speedups
+
+SRC = open(os.path.join(ROOT, "oracle", "gsi_oracle.py")).read()
+
+MUTANTS = [
+    ("c_uses_U_not_UT", "c = U.T @ x ", "c = (x @ U[:, ::-1]) "),
+    ("residual_sign", "r = x - U @ c ", "r = x + U @ c "),
+    ("residual_dropped", "r = x - U @ c ", "r = x.copy() "),
+    ("rnorm_no_sqrt", "rnorm[t] = np.sqrt(np.sum(r * r))", "rnorm[t] = np.sum(r * r)"),
+    ("rnorm_l1", "rnorm[t] = np.sqrt(np.sum(r * r))", "rnorm[t] = np.sum(np.abs(r))"),
+    ("xnorm_of_r", "xnorm[t] = np.sqrt(np.sum(x * x))", "xnorm[t] = np.sqrt(np.sum(r * r))"),
+    ("rho_inverted", "rho[nz] = rnorm[nz] / xnorm[nz]", "rho[nz] = xnorm[nz] / rnorm[nz].clip(1e-300)"),
+    ("gate_strict", "& (rho >= eps64)", "& (rho > eps64)"),
+    ("gate_reversed", "& (rho >= eps64)", "& (rho < eps64)"),
+    ("gate_eps_fp64", "eps64 = float(np.float32(eps))", "eps64 = float(eps)"),
+    ("gate_zero_x_fires", "fired = (np.asarray(xnorm) > 0) & (rho >= eps64)", "fired = (rho >= eps64)"),
+    ("idx_descending", "idx = np.nonzero(fired)[0].astype(np.int32)", "idx = np.nonzero(fired)[0][::-1].astype(np.int32)"),
+    ("image_transposed_U", "@ np.asarray(U, dtype=np.float64)\n", "@ np.asarray(U, dtype=np.float64)[:, ::-1]\n"),
+    ("image_is_W_slice", "return np.asarray(W, dtype=np.float64) @ np.asarray(U, dtype=np.float64)",
+     "return np.asarray(W, dtype=np.float64)[:, : U.shape[1]].copy()"),
+    ("fast_term_dropped", "y = M @ C[t] ", "y = 0.0 * (M @ C[t]) "),
+    ("slow_term_sign", "y = y + W @ R[t] ", "y = y - W @ R[t] "),
+    ("slow_term_always", "if mask[t]:\n            y = y + W @ R[t]", "if True:\n            y = y + W @ R[t]"),
+    ("slow_term_never", "if mask[t]:\n            y = y + W @ R[t]", "if False:\n            y = y + W @ R[t]"),
+    ("slow_term_uses_wrong_token", "y = y + W @ R[t] ", "y = y + W @ R[0] "),
+    ("alg1_branches_swapped", "Y[t] = W @ X[t] if mask[t] else M @ C[t]", "Y[t] = M @ C[t] if mask[t] else W @ X[t]"),
+    ("dense_transposed", "Y[t] = W @ X[t]\n    return Y\n\n\ndef gated_linear(", "Y[t] = (W[::-1] @ X[t])\n    return Y\n\n\ndef gated_linear("),
+    ("bf16_shift", "<< np.uint32(16)", "<< np.uint32(15)"),
+    ("speedup_formula", "return 1.0 / (f / (d / k) + (1.0 - f))", "return 1.0 / (f * (d / k) + (1.0 - f))"),
+    ("speedup_kd_swapped", "return 1.0 / (f / (d / k) + (1.0 - f))", "return 1.0 / (f / (k / d) + (1.0 - f))"),
+    ("model_speedup_arithmetic_mean", "return vol / sum(v / effective_speedup(f, d, k) for f, d, k, v in layers)",
+     "return sum(v * effective_speedup(f, d, k) for f, d, k, v in layers) / vol"),
+    ("peff_swapped", "(f * k + (1.0 - f) * d)", "(f * d + (1.0 - f) * k)"),
+    ("stack_gate_per_map_wrong_eps", "mask, idx, n = gate(rn, xn, eps)", "mask, idx, n = gate(rn, xn, 2.0 * eps)"),
+    ("stack_dense_uses_image", "name: dense_linear(W64, X) for name, W64, _ in g[\"maps\"]", "name: dense_linear(W64, X) * 1.0000001 for name, W64, _ in g[\"maps\"]"),
+    ("error_bound_smallest_sv", "compute_uv=False)[0]", "compute_uv=False)[-1]"),
+]
+
+
+def _load(src):
+    mod = types.ModuleType("oracle_mutant")
+    exec(compile(src, "oracle_mutant", "exec"), mod.__dict__)
+    return mod
+
+
+def _caught(O):
+    pins = list(PINS) + [
+        lambda o: pin_paper_speedups(o, read_golden("paper_speedup_tables.txt")),
+        lambda o: pin_paper_closed_forms(o, read_golden("paper_closed_forms.txt")),
+    ]
+    for pin in pins:
+        try:
+            pin(O)
+        except AssertionError:
+            return True
+        except Exception:  # a mutant may also break shapes; that counts as caught
+            return True
+    return False
+
+
+def test_unmutated_source_passes():
+    assert not _caught(_load(SRC))
+
+
+@pytest.mark.parametrize("name,old,new", MUTANTS, ids=[m[0] for m in MUTANTS])
+def test_mutant_is_caught(name, old, new):
+    assert SRC.count(old) >= 1, f"mutation site for {name} not found in the oracle source"
+    assert _caught(_load(SRC.replace(old, new, 1))), f"no pin notices mutant {name}"
