@@ -1,0 +1,144 @@
+/*
+ * gsi.h -- C ABI of libgsi: the gated subspace linear layer on one AMD MI355X (gfx950).
+ *
+ * The operation (paper, Section 3 "The gated residual passthrough" and Section 4, Algorithm 1):
+ * an activation x in R^d is split by an orthonormal basis U in R^{d x k} (the paper's V_k) into
+ *      c = U^T x          (the paper's g)                       Eq. (decompose), Alg. 1 line 1
+ *      r = x - U c                                              Eq. (decompose), Alg. 1 line 2
+ *      rho = |r| / |x|                                          Eq. (gate),      Alg. 1 line 3
+ * and a linear map y = W x, W in R^{m x d}, is evaluated through the cached image M = W U as
+ *      y = M c                      when rho <  eps  (fast path: k columns are read)
+ *      y = M c + W r  ( = W x )     when rho >= eps  (gate fires; Eq. (exact))
+ *
+ * Conventions common to every call
+ *   - All matrices are dense, row-major and contiguous:  W[m,d]  U[d,k]  M[m,k]  X[B,d]  C[B,k]
+ *     R[B,d]  Y[B,m]; B is the number of tokens in the call, tokens are independent.
+ *   - EVERY pointer argument is a DEVICE pointer (HBM of the current HIP device) unless the comment
+ *     says "host".  The caller owns every buffer, including the scratch workspace `ws`, whose
+ *     minimum size is returned by gsi_workspace_bytes(); the library allocates nothing, frees
+ *     nothing and keeps no state apart from a thread-local error string.
+ *   - Storage dtypes (enum below): weights, images and bases share `wdtype`; activations have
+ *     `xdtype`.  c, r, norms and y are always fp32; all accumulation is fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).  A call only enqueues
+ *     work: it never synchronises and never reads a device result on the host (the fired-token
+ *     count stays in device memory).  Calls on one stream execute in order.
+ *   - Return value: GSI_OK (0) or a negative gsi error code; gsi_last_error() then describes it.
+ *     Arguments are validated on the host before anything is launched; on error nothing was enqueued.
+ *   - B == 0 is a valid no-op.  Shapes must satisfy 1 <= k <= d, m >= 1.  Pointers must be aligned
+ *     to their element size; shapes/pointers that additionally allow 16-byte vector access take the
+ *     fast kernels, everything else a slower generic kernel with the same results up to rounding order.
+ */
+#ifndef GSI_H
+#define GSI_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum gsi_status {
+  GSI_OK = 0,
+  GSI_ERR_NULL = -1,      /* a required pointer is NULL                               */
+  GSI_ERR_SHAPE = -2,     /* k < 1, k > d, m < 1, B < 0, bad descriptor index, ...    */
+  GSI_ERR_DTYPE = -3,     /* unknown or unsupported dtype code                        */
+  GSI_ERR_ALIGN = -4,     /* pointer not aligned to its element size                  */
+  GSI_ERR_WORKSPACE = -5, /* ws is NULL or smaller than gsi_workspace_bytes()         */
+  GSI_ERR_HIP = -6        /* the HIP runtime refused a launch                         */
+};
+
+enum gsi_dtype { GSI_F32 = 0, GSI_BF16 = 1 };
+
+/* selector for gsi_workspace_bytes() */
+enum gsi_call {
+  GSI_CALL_BUILD_IMAGE = 0,
+  GSI_CALL_PROJECT = 1,
+  GSI_CALL_GATE = 2,
+  GSI_CALL_GATED_LINEAR = 3,
+  GSI_CALL_DENSE_LINEAR = 4,
+  GSI_CALL_LAYER_STACK = 5
+};
+
+/* One-time image build, M = W U (Eq. (exact); Section 4 "Storage": computed once per weight and
+ * kept beside W).  W[m,d], U[d,k] in `wdtype`; M[m,k] written in `wdtype` (one rounding of the fp32
+ * accumulator when bf16).  ws: gsi_workspace_bytes(GSI_CALL_BUILD_IMAGE, m, d, k, 0). */
+int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d, int64_t k, int wdtype,
+                    void* ws, size_t ws_bytes, void* stream);
+
+/* Projection, residual and the two norms of Algorithm 1 lines 1-3 for B tokens.
+ * U[d,k] in `udtype`, X[B,d] in `xdtype`.  Outputs (fp32): C[B,k] = X U, R[B,d] = X - C U^T (formed
+ * explicitly), rnorm[B] = |r_t|_2, xnorm[B] = |x_t|_2.  ws: GSI_CALL_PROJECT with (m ignored). */
+int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype,
+                float* C, float* R, float* rnorm, float* xnorm, void* ws, size_t ws_bytes, void* stream);
+
+/* Gate of Eq. (gate) / Algorithm 1 line 4 with on-device stream compaction.
+ * fired_t = (xnorm_t > 0) and (rnorm_t / xnorm_t >= eps)   [fast path iff rho < eps].
+ * mask[B] (1 = fired), fired_idx[0..n_fired) = fired token indices in ascending order (entries past
+ * n_fired are left untouched; the buffer must hold B ints), n_fired[0] = their count. */
+int gsi_gate(const float* rnorm, const float* xnorm, int64_t B, float eps, uint8_t* mask,
+             int32_t* fired_idx, int32_t* n_fired, void* stream);
+
+/* Gated linear map: Y[t,:] = M C[t,:] for every token, plus W R[t,:] for t in fired_idx[0..n_fired).
+ * Tokens that did not fire never touch W; when n_fired == 0 no byte of W is read.  W[m,d], M[m,k]
+ * in `wdtype`; C, R fp32; fired_idx / n_fired are the device outputs of gsi_gate; Y[B,m] fp32
+ * (`ydtype` must be GSI_F32).  ws: GSI_CALL_GATED_LINEAR. */
+int gsi_gated_linear(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
+                     const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, int wdtype, void* Y,
+                     int ydtype, void* ws, size_t ws_bytes, void* stream);
+
+/* Dense baseline Y[t,:] = W X[t,:] (what the method is measured against; Section 3.1 "standard
+ * linear-layer computation").  Same kernels as the fired path of gsi_gated_linear.  Y fp32. */
+int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype, int xdtype,
+                     float* Y, void* ws, size_t ws_bytes, void* stream);
+
+/* Descriptors for gsi_layer_stack (host structs holding device pointers). */
+typedef struct gsi_input_desc {
+  const void* U;      /* basis of this input, [d,k], udtype                                     */
+  const void* X;      /* tokens [B,d], xdtype; when src_map >= 0 this must be maps[src_map].Y   */
+  int64_t d, k;
+  int32_t udtype, xdtype;
+  float* C;           /* outputs of the projection, as in gsi_project                           */
+  float* R;
+  float* rnorm;
+  float* xnorm;
+  uint8_t* mask;      /* outputs of the gate, as in gsi_gate                                    */
+  int32_t* fired_idx;
+  int32_t* n_fired;
+  int32_t src_map;    /* -1: X is an external buffer; j >= 0: X is the output Y of maps[j]      */
+  int32_t reserved;
+} gsi_input_desc;
+
+typedef struct gsi_map_desc {
+  const void* W;      /* [m,d] wdtype, d = inputs[input_id].d                                   */
+  const void* M;      /* [m,k] wdtype, k = inputs[input_id].k                                   */
+  float* Y;           /* [B,m] fp32                                                             */
+  int64_t m;
+  int32_t wdtype;
+  int32_t input_id;   /* which input this map reads                                             */
+} gsi_map_desc;
+
+/* A chain of per-layer linear maps sharing their inputs' projections (Section 1: every linear map
+ * of a block that reads the same input shares one basis, one projection and one gate).  For each
+ * input: gsi_project + gsi_gate once; for each map: gsi_gated_linear on its input's c, r and fired
+ * list.  `maps` and `inputs` are HOST arrays (read during the call only).  Inputs with src_map >= 0
+ * are processed after the map that produces them.  Results are identical to issuing the separate
+ * calls in that order.  ws: gsi_layer_stack_workspace_bytes(). */
+int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                    int64_t B, float eps, void* ws, size_t ws_bytes, void* stream);
+
+/* Minimum workspace size in bytes for one call (arguments that a call does not have are ignored). */
+size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int64_t B);
+size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
+                                       int32_t n_inputs, int64_t B);
+
+/* Thread-local description of the last error returned on this thread ("" if none). */
+const char* gsi_last_error(void);
+
+/* Library version: major * 10000 + minor * 100 + patch. */
+int gsi_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* GSI_H */

@@ -1,0 +1,71 @@
+// Device-side helpers shared by the HIP kernels of libgsi (gfx950, wave64).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace gsi {
+
+constexpr int kWave = 64;
+
+// ---- storage formats -------------------------------------------------------------------------
+// bfloat16 is the upper half of an IEEE binary32 word: widening is a shift, exact.
+__device__ __forceinline__ float bf16_bits_to_f32(uint16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// fp32 -> bf16, round to nearest even (NaN kept quiet).
+__device__ __forceinline__ uint16_t f32_to_bf16_bits(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+struct F32 {
+  using storage = float;
+  static constexpr int kVec = 4;  // elements per 16-byte load
+  __device__ static __forceinline__ float load(const float* p, int64_t i) { return p[i]; }
+  __device__ static __forceinline__ void store(float* p, int64_t i, float v) { p[i] = v; }
+  // 16-byte vector load of kVec consecutive elements
+  __device__ static __forceinline__ void load_vec(const float* p, float (&f)[4]) {
+    const float4 v = *reinterpret_cast<const float4*>(p);
+    f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
+  }
+};
+
+struct BF16 {
+  using storage = uint16_t;
+  static constexpr int kVec = 8;
+  __device__ static __forceinline__ float load(const uint16_t* p, int64_t i) { return bf16_bits_to_f32(p[i]); }
+  __device__ static __forceinline__ void store(uint16_t* p, int64_t i, float v) { p[i] = f32_to_bf16_bits(v); }
+  __device__ static __forceinline__ void load_vec(const uint16_t* p, float (&f)[8]) {
+    const uint4 v = *reinterpret_cast<const uint4*>(p);
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x);
+    f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z);
+    f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+  }
+};
+
+// activation element of runtime dtype (0 = fp32, 1 = bf16)
+__device__ __forceinline__ float load_act(const void* p, int dtype, int64_t i) {
+  return dtype == 0 ? reinterpret_cast<const float*>(p)[i]
+                    : bf16_bits_to_f32(reinterpret_cast<const uint16_t*>(p)[i]);
+}
+
+// ---- cross-lane reductions ---------------------------------------------------------------------
+// Sum over groups of `width` consecutive lanes (width a power of two <= 64); every lane of a group
+// ends with the group's total.  Butterfly order is fixed, so results are run-to-run identical.
+template <int width>
+__device__ __forceinline__ float group_sum(float v) {
+#pragma unroll
+  for (int off = width / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+__device__ __forceinline__ float group_sum_rt(float v, int width) {
+  for (int off = width >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
+  return v;
+}
+
+}  // namespace gsi

@@ -1,0 +1,304 @@
+"""ctypes binding of libgsi.so: argument marshalling only.
+
+Function names, argument order and meaning follow ``include/gsi.h``.  Tensors are torch CUDA
+(ROCm) tensors used purely as device memory; their ``data_ptr()`` and the current torch stream
+handle are what crosses the boundary.  Every step of the path runs inside the library's HIP
+kernels; there is no fallback: if ``libgsi.so`` is missing, importing this module raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Dict, List, Optional, Sequence, Tuple
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libgsi.so")
+
+GSI_OK = 0
+GSI_ERR_NULL, GSI_ERR_SHAPE, GSI_ERR_DTYPE, GSI_ERR_ALIGN, GSI_ERR_WORKSPACE, GSI_ERR_HIP = -1, -2, -3, -4, -5, -6
+GSI_F32, GSI_BF16 = 0, 1
+CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
+
+EXPORTS = (
+    "gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear", "gsi_layer_stack",
+    "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_last_error", "gsi_version",
+)
+
+
+class GsiError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"libgsi error {code}: {msg}")
+        self.code = code
+
+
+class InputDesc(ctypes.Structure):
+    _fields_ = [
+        ("U", ctypes.c_void_p), ("X", ctypes.c_void_p),
+        ("d", ctypes.c_int64), ("k", ctypes.c_int64),
+        ("udtype", ctypes.c_int32), ("xdtype", ctypes.c_int32),
+        ("C", ctypes.c_void_p), ("R", ctypes.c_void_p),
+        ("rnorm", ctypes.c_void_p), ("xnorm", ctypes.c_void_p),
+        ("mask", ctypes.c_void_p), ("fired_idx", ctypes.c_void_p), ("n_fired", ctypes.c_void_p),
+        ("src_map", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class MapDesc(ctypes.Structure):
+    _fields_ = [
+        ("W", ctypes.c_void_p), ("M", ctypes.c_void_p), ("Y", ctypes.c_void_p),
+        ("m", ctypes.c_int64), ("wdtype", ctypes.c_int32), ("input_id", ctypes.c_int32),
+    ]
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2605_03109_amd.build` "
+            "(there is no CPU or PyTorch fallback for the HIP path)"
+        )
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i64, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
+    lib.gsi_build_image.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
+    lib.gsi_project.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
+    lib.gsi_gate.argtypes = [vp, vp, i64, f32, vp, vp, vp, vp]
+    lib.gsi_gated_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, i32, vp, sz, vp]
+    lib.gsi_dense_linear.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, sz, vp]
+    lib.gsi_layer_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
+                                    ctypes.c_int32, i64, f32, vp, sz, vp]
+    lib.gsi_workspace_bytes.argtypes = [i32, i64, i64, i64, i64]
+    lib.gsi_workspace_bytes.restype = sz
+    lib.gsi_layer_stack_workspace_bytes.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32,
+                                                    ctypes.POINTER(InputDesc), ctypes.c_int32, i64]
+    lib.gsi_layer_stack_workspace_bytes.restype = sz
+    lib.gsi_last_error.restype = ctypes.c_char_p
+    lib.gsi_version.restype = ctypes.c_int
+    for name in ("gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+                 "gsi_layer_stack"):
+        getattr(lib, name).restype = ctypes.c_int
+    return lib
+
+
+lib = _load()
+
+
+def _check(rc: int) -> None:
+    if rc != GSI_OK:
+        raise GsiError(rc, lib.gsi_last_error().decode())
+
+
+def last_error() -> str:
+    return lib.gsi_last_error().decode()
+
+
+def version() -> int:
+    return lib.gsi_version()
+
+
+# ----------------------------------------------------------------------------------------------
+# marshalling helpers
+# ----------------------------------------------------------------------------------------------
+def dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return GSI_F32
+    if t.dtype == torch.bfloat16:
+        return GSI_BF16
+    raise TypeError(f"unsupported tensor dtype {t.dtype}")
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("libgsi takes device tensors only")
+    if not t.is_contiguous():
+        raise ValueError("libgsi takes contiguous row-major tensors only")
+    return t.data_ptr()
+
+
+def _stream(stream=None) -> int:
+    s = torch.cuda.current_stream() if stream is None else stream
+    return s.cuda_stream
+
+
+def to_device(a: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Stored operand (fp32 array or uint16 bf16 bit patterns) -> device tensor, bit for bit."""
+    if dtype == "bf16":
+        return torch.from_numpy(np.ascontiguousarray(a).view(np.int16)).view(torch.bfloat16).to(device)
+    return torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).to(device)
+
+
+def bits_of(t: torch.Tensor) -> np.ndarray:
+    """Device tensor -> host array in the storage convention of the workload module."""
+    if t.dtype == torch.bfloat16:
+        return t.detach().cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+    return t.detach().cpu().numpy()
+
+
+_ws_cache: Dict[Tuple[int, int], torch.Tensor] = {}
+
+
+def workspace(nbytes: int, device=None) -> Optional[torch.Tensor]:
+    """A cached device byte buffer of at least ``nbytes`` (device memory plumbing only)."""
+    if nbytes == 0:
+        return None
+    dev = torch.cuda.current_device() if device is None else torch.device(device).index or 0
+    have = _ws_cache.get((dev, 0))
+    if have is None or have.numel() < nbytes:
+        have = torch.empty(max(nbytes, 1 << 20), dtype=torch.uint8, device=f"cuda:{dev}")
+        _ws_cache[(dev, 0)] = have
+    return have
+
+
+def workspace_bytes(which: int, m: int = 0, d: int = 0, k: int = 0, B: int = 0) -> int:
+    return int(lib.gsi_workspace_bytes(which, m, d, k, B))
+
+
+def _ws_args(ws: Optional[torch.Tensor], need: int):
+    if ws is None:
+        ws = workspace(need)
+    return (None, 0) if ws is None else (ws.data_ptr(), ws.numel() * ws.element_size())
+
+
+# ----------------------------------------------------------------------------------------------
+# entry points (same names as the C ABI, minus the prefix)
+# ----------------------------------------------------------------------------------------------
+def build_image(W: torch.Tensor, U: torch.Tensor, M: Optional[torch.Tensor] = None, ws=None, stream=None):
+    m, d = W.shape
+    d2, k = U.shape
+    if d2 != d or W.dtype != U.dtype:
+        raise ValueError("W[m,d] and U[d,k] must agree in d and dtype")
+    if M is None:
+        M = torch.empty((m, k), dtype=W.dtype, device=W.device)
+    wsp, wsn = _ws_args(ws, workspace_bytes(CALL_BUILD_IMAGE, m, d, k, 0))
+    _check(lib.gsi_build_image(_ptr(W), _ptr(U), _ptr(M), m, d, k, dtype_code(W), wsp, wsn, _stream(stream)))
+    return M
+
+
+def project(U: torch.Tensor, X: torch.Tensor, C=None, R=None, rnorm=None, xnorm=None, ws=None, stream=None):
+    d, k = U.shape
+    B, d2 = X.shape
+    if d2 != d:
+        raise ValueError("U[d,k] and X[B,d] must agree in d")
+    f32 = dict(dtype=torch.float32, device=U.device)
+    C = torch.empty((B, k), **f32) if C is None else C
+    R = torch.empty((B, d), **f32) if R is None else R
+    rnorm = torch.empty((B,), **f32) if rnorm is None else rnorm
+    xnorm = torch.empty((B,), **f32) if xnorm is None else xnorm
+    wsp, wsn = _ws_args(ws, workspace_bytes(CALL_PROJECT, 0, d, k, B))
+    _check(lib.gsi_project(_ptr(U), _ptr(X), d, k, B, dtype_code(U), dtype_code(X), _ptr(C), _ptr(R), _ptr(rnorm),
+                           _ptr(xnorm), wsp, wsn, _stream(stream)))
+    return C, R, rnorm, xnorm
+
+
+def gate(rnorm: torch.Tensor, xnorm: torch.Tensor, eps: float, mask=None, fired_idx=None, n_fired=None, stream=None):
+    B = rnorm.shape[0]
+    dev = rnorm.device
+    mask = torch.empty((B,), dtype=torch.uint8, device=dev) if mask is None else mask
+    fired_idx = torch.empty((max(B, 1),), dtype=torch.int32, device=dev) if fired_idx is None else fired_idx
+    n_fired = torch.empty((1,), dtype=torch.int32, device=dev) if n_fired is None else n_fired
+    _check(lib.gsi_gate(_ptr(rnorm), _ptr(xnorm), B, float(eps), _ptr(mask), _ptr(fired_idx), _ptr(n_fired),
+                        _stream(stream)))
+    return mask, fired_idx, n_fired
+
+
+def gated_linear(W, M, C, R, fired_idx, n_fired, Y=None, ws=None, stream=None):
+    m, d = W.shape
+    k = M.shape[1]
+    B = C.shape[0]
+    if M.shape[0] != m or C.shape[1] != k or tuple(R.shape) != (B, d) or M.dtype != W.dtype:
+        raise ValueError("inconsistent shapes/dtypes for gated_linear")
+    Y = torch.empty((B, m), dtype=torch.float32, device=W.device) if Y is None else Y
+    wsp, wsn = _ws_args(ws, workspace_bytes(CALL_GATED_LINEAR, m, d, k, B))
+    _check(lib.gsi_gated_linear(_ptr(W), _ptr(M), _ptr(C), _ptr(R), _ptr(fired_idx), _ptr(n_fired), m, d, k, B,
+                                dtype_code(W), _ptr(Y), GSI_F32, wsp, wsn, _stream(stream)))
+    return Y
+
+
+def dense_linear(W, X, Y=None, ws=None, stream=None):
+    m, d = W.shape
+    B = X.shape[0]
+    if X.shape[1] != d:
+        raise ValueError("W[m,d] and X[B,d] must agree in d")
+    Y = torch.empty((B, m), dtype=torch.float32, device=W.device) if Y is None else Y
+    wsp, wsn = _ws_args(ws, workspace_bytes(CALL_DENSE_LINEAR, m, d, 0, B))
+    _check(lib.gsi_dense_linear(_ptr(W), _ptr(X), m, d, B, dtype_code(W), dtype_code(X), _ptr(Y), wsp, wsn,
+                                _stream(stream)))
+    return Y
+
+
+class LayerStack:
+    """Host descriptor tables for ``gsi_layer_stack`` plus the device buffers they point to.
+
+    ``inputs``: list of dicts {U, X (tensor [B,d]) or src_map}; ``maps``: list of dicts
+    {W, M, input_id}.  Output buffers are allocated here (torch = device memory only) and exposed as
+    attributes; ``run()`` is a single call into the library.
+    """
+
+    def __init__(self, inputs: Sequence[dict], maps: Sequence[dict], B: int, eps: float):
+        self.B, self.eps = int(B), float(eps)
+        dev = maps[0]["W"].device
+        f32 = dict(dtype=torch.float32, device=dev)
+        self.maps_t: List[dict] = []
+        self.inputs_t: List[dict] = []
+        for mp in maps:
+            m = mp["W"].shape[0]
+            Y = mp.get("Y")
+            Y = torch.zeros((B, m), **f32) if Y is None else Y
+            self.maps_t.append({"W": mp["W"], "M": mp["M"], "Y": Y, "input_id": int(mp["input_id"])})
+        for inp in inputs:
+            U = inp["U"]
+            d, k = U.shape
+            src = int(inp.get("src_map", -1))
+            X = self.maps_t[src]["Y"] if src >= 0 else inp["X"]
+            self.inputs_t.append({
+                "U": U, "X": X, "src_map": src,
+                "C": torch.zeros((B, k), **f32), "R": torch.zeros((B, d), **f32),
+                "rnorm": torch.zeros((B,), **f32), "xnorm": torch.zeros((B,), **f32),
+                "mask": torch.zeros((B,), dtype=torch.uint8, device=dev),
+                "fired_idx": torch.zeros((max(B, 1),), dtype=torch.int32, device=dev),
+                "n_fired": torch.zeros((1,), dtype=torch.int32, device=dev),
+            })
+        self._in = (InputDesc * len(self.inputs_t))()
+        self._mp = (MapDesc * len(self.maps_t))()
+        self.refresh()
+        need = int(lib.gsi_layer_stack_workspace_bytes(self._mp, len(self.maps_t), self._in, len(self.inputs_t), B))
+        self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
+
+    def refresh(self, token_offset: int = 0, B: Optional[int] = None) -> None:
+        """(Re)write the descriptor tables; ``token_offset`` selects rows [offset, offset+B) of every buffer."""
+        B = self.B if B is None else B
+        self.cur_B = B
+        o = token_offset
+        for i, t in enumerate(self.inputs_t):
+            d, k = t["U"].shape
+            e = self._in[i]
+            e.U, e.d, e.k = _ptr(t["U"]), d, k
+            e.X = _ptr(t["X"]) + o * d * t["X"].element_size()
+            e.udtype, e.xdtype = dtype_code(t["U"]), dtype_code(t["X"])
+            e.C = _ptr(t["C"]) + o * k * 4
+            e.R = _ptr(t["R"]) + o * d * 4
+            e.rnorm = _ptr(t["rnorm"]) + o * 4
+            e.xnorm = _ptr(t["xnorm"]) + o * 4
+            e.mask = _ptr(t["mask"]) + o
+            e.fired_idx = _ptr(t["fired_idx"])
+            e.n_fired = _ptr(t["n_fired"])
+            e.src_map, e.reserved = t["src_map"], 0
+        for j, t in enumerate(self.maps_t):
+            m = t["W"].shape[0]
+            e = self._mp[j]
+            e.W, e.M, e.m = _ptr(t["W"]), _ptr(t["M"]), m
+            e.Y = _ptr(t["Y"]) + o * m * 4
+            e.wdtype, e.input_id = dtype_code(t["W"]), t["input_id"]
+
+    def run(self, stream=None) -> None:
+        _check(lib.gsi_layer_stack(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B, self.eps,
+                                   self.ws.data_ptr(), self.ws.numel(), _stream(stream)))
+
+
+def layer_stack(inputs: Sequence[dict], maps: Sequence[dict], B: int, eps: float, stream=None) -> LayerStack:
+    st = LayerStack(inputs, maps, B, eps)
+    st.run(stream)
+    return st

@@ -1,0 +1,158 @@
+"""Helpers of the GPU parity tests: run a seeded workload through libgsi and through the CPU oracle
+and compare element by element.
+
+Bars (written here once, used by every parity test):
+  * y: relative L2 error per output vector <= 2e-3 for bf16 weights, <= 1e-5 for fp32 weights,
+    against the oracle that uses the *unrounded* fp64 image M = W U;
+  * against the oracle fed with the device's own stored image (so only kernel arithmetic differs),
+    <= 2e-5 (bf16 operands, fp32 accumulation) -- this is the bar for shapes too small for the
+    statistical 2e-3 bound on bf16 storage rounding to hold per vector;
+  * gate masks bit-exact for every token whose oracle ratio is farther than 1e-4 from eps; for a
+    token inside that band the output is compared with the oracle evaluated on the device's mask
+    bit (both branches are admissible there);
+  * fired list: ascending token order, length == n_fired == popcount(mask);
+  * c: relative L2 <= 1e-5; r: |r_gpu - r_oracle| <= 1e-5 |x|; ratio: |rho_gpu - rho_oracle| <= 1e-5.
+"""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle.gsi_oracle as O
+from paper_2605_03109_amd import gsi
+from paper_2605_03109_amd import workload as wl
+
+TOL_Y = {"bf16": 2e-3, "f32": 1e-5}
+TOL_Y_STAGE = {"bf16": 2e-5, "f32": 1e-5}
+TOL_C = 1e-5
+TOL_R = 1e-5
+TOL_RHO = 1e-5
+BAND = 1e-4
+
+
+def rel_l2_rows(a: np.ndarray, b: np.ndarray) -> np.ndarray:
+    """Per-row |a - b| / |b| (0 where both rows are 0)."""
+    num = np.linalg.norm(a - b, axis=-1)
+    den = np.linalg.norm(b, axis=-1)
+    out = np.zeros_like(num)
+    nz = den > 0
+    out[nz] = num[nz] / den[nz]
+    out[~nz] = num[~nz]
+    return out
+
+
+class DeviceGroup:
+    """A workload group resident on the GPU: U, X, per-map W and the device-built image M."""
+
+    def __init__(self, w: wl.Workload, g: wl.Group, build=True):
+        self.g = g
+        self.U = gsi.to_device(g.U, w.wdtype)
+        self.X = gsi.to_device(g.X, w.xdtype)
+        self.W = {name: gsi.to_device(W, w.wdtype) for name, _, W in g.maps}
+        self.M = {name: gsi.build_image(self.W[name], self.U) for name, _, _ in g.maps} if build else {}
+
+
+class OracleGroup:
+    """The same group through the fp64 oracle: exact image and, per token block, every intermediate."""
+
+    def __init__(self, w: wl.Workload, g: wl.Group):
+        self.U = O.widen(g.U, w.wdtype)
+        self.X = O.widen(g.X, w.xdtype)
+        self.W = {name: O.widen(W, w.wdtype) for name, _, W in g.maps}
+        self.M = {name: O.build_image(self.W[name], self.U) for name in self.W}
+        self.eps = w.eps
+
+    def run(self, t0=0, t1=None):
+        X = self.X[t0:t1]
+        C, R, rn, xn = O.project(self.U, X)
+        mask, idx, n = O.gate(rn, xn, self.eps)
+        return dict(X=X, C=C, R=R, rnorm=rn, xnorm=xn, rho=O.residual_ratio(rn, xn), mask=mask, idx=idx, n=n)
+
+
+def check_projection(res_gpu: dict, ref: dict, eps: float):
+    """C, R, norms and gate outputs of one token block; returns the mask to evaluate y with."""
+    C = res_gpu["C"].cpu().numpy().astype(np.float64)
+    R = res_gpu["R"].cpu().numpy().astype(np.float64)
+    rn = res_gpu["rnorm"].cpu().numpy().astype(np.float64)
+    xn = res_gpu["xnorm"].cpu().numpy().astype(np.float64)
+    mask = res_gpu["mask"].cpu().numpy()
+    n = int(res_gpu["n_fired"].cpu().numpy()[0])
+    idx = res_gpu["fired_idx"].cpu().numpy()[:n]
+    B = C.shape[0]
+    xnorm_ref = ref["xnorm"]
+    safe = np.where(xnorm_ref > 0, xnorm_ref, 1.0)
+    assert np.all(rel_l2_rows(C, ref["C"]) <= TOL_C), rel_l2_rows(C, ref["C"]).max()
+    assert np.all(np.linalg.norm(R - ref["R"], axis=1) <= TOL_R * safe), (np.linalg.norm(R - ref["R"], axis=1) / safe).max()
+    assert np.all(np.abs(xn - xnorm_ref) <= 1e-5 * safe)
+    rho_gpu = np.where(xn > 0, rn / np.where(xn > 0, xn, 1.0), 0.0)
+    assert np.all(np.abs(rho_gpu - ref["rho"]) <= TOL_RHO), np.abs(rho_gpu - ref["rho"]).max()
+    # gate: bit-exact outside the band around eps
+    eps32 = float(np.float32(eps))
+    decided = np.abs(ref["rho"] - eps32) >= BAND
+    assert mask.dtype == np.uint8 and set(np.unique(mask)).issubset({0, 1})
+    assert np.array_equal(mask[decided], ref["mask"][decided]), "gate mask differs outside the 1e-4 band"
+    # compaction: ascending, consistent with the device's own mask
+    assert n == int(mask.sum())
+    assert np.array_equal(idx, np.nonzero(mask)[0].astype(np.int32))
+    assert B == mask.shape[0]
+    return mask
+
+
+def check_outputs(Y_gpu: torch.Tensor, W64, M64_exact, M_dev_bits, wdtype: str, ref: dict, mask_gpu, m_small=256):
+    """y against the oracle with the exact image (bar TOL_Y) and with the device's stored image (stage bar)."""
+    Y = Y_gpu.cpu().numpy().astype(np.float64)
+    Mdev = O.widen(M_dev_bits, wdtype)
+    Y_stage = O.gated_linear(W64, Mdev, ref["C"], ref["R"], mask_gpu)
+    e_stage = rel_l2_rows(Y, Y_stage)
+    assert np.all(e_stage <= TOL_Y_STAGE[wdtype]), f"stage rel-L2 {e_stage.max():.3e}"
+    Y_exact = O.gated_linear(W64, M64_exact, ref["C"], ref["R"], mask_gpu)
+    e = rel_l2_rows(Y, Y_exact)
+    if Y.shape[1] >= m_small:  # the statistical bf16 storage bound needs a long output vector
+        assert np.all(e <= TOL_Y[wdtype]), f"rel-L2 {e.max():.3e}"
+    return float(e.max()) if e.size else 0.0, float(e_stage.max()) if e_stage.size else 0.0
+
+
+def check_image(M_dev_bits, M64, W64, U64, wdtype: str):
+    """Device image against the fp64 image: element-wise, one storage rounding plus fp32 accumulation.
+
+    |M_dev - M| <= half an ulp of the storage format at |M| (2^-8 |M| for bf16, 2^-24 |M| for fp32)
+    + (8 + sqrt d) * 2^-24 * sum_i |W_i||U_i| (fp32 accumulation of d terms in any order: far below the
+    worst case d * 2^-24, a few times the random-walk estimate); and the whole matrix within the
+    rel-L2 bar of its dtype.
+    """
+    Mdev = O.widen(M_dev_bits, wdtype)
+    half_ulp = 2.0**-8 if wdtype == "bf16" else 2.0**-24
+    acc = (8.0 + np.sqrt(W64.shape[1])) * 2.0**-24 * (np.abs(W64) @ np.abs(U64))
+    bound = half_ulp * np.abs(M64) * (1 + 1e-6) + acc + 1e-38
+    assert np.all(np.abs(Mdev - M64) <= bound), float(np.max(np.abs(Mdev - M64) / bound))
+    fro = np.linalg.norm(Mdev - M64) / max(np.linalg.norm(M64), 1e-300)
+    if M64.size >= 4096:
+        assert fro <= TOL_Y[wdtype], f"image rel-L2 {fro:.3e}"
+    return fro
+
+
+def run_separate_calls(dg: DeviceGroup, eps: float, t0=0, t1=None):
+    """project -> gate -> gated_linear per map on tokens [t0, t1) through the separate entry points."""
+    X = dg.X[t0:t1].contiguous()
+    C, R, rn, xn = gsi.project(dg.U, X)
+    mask, idx, n = gsi.gate(rn, xn, eps)
+    Y = {name: gsi.gated_linear(dg.W[name], dg.M[name], C, R, idx, n) for name in dg.W}
+    return dict(C=C, R=R, rnorm=rn, xnorm=xn, mask=mask, fired_idx=idx, n_fired=n, Y=Y)
+
+
+def check_group(w: wl.Workload, g: wl.Group, blocks, dg=None, og=None):
+    """Full parity of one group over the given token blocks [(t0, t1), ...] via the separate calls."""
+    dg = dg or DeviceGroup(w, g)
+    og = og or OracleGroup(w, g)
+    worst = 0.0
+    for name in dg.W:
+        check_image(gsi.bits_of(dg.M[name]), og.M[name], og.W[name], og.U, w.wdtype)
+    for t0, t1 in blocks:
+        res = run_separate_calls(dg, w.eps, t0, t1)
+        ref = og.run(t0, t1)
+        mask = check_projection(res, ref, w.eps)
+        for name in dg.W:
+            e, _ = check_outputs(res["Y"][name], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
+            worst = max(worst, e)
+    torch.cuda.synchronize()
+    return worst

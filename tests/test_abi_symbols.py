@@ -1,0 +1,69 @@
+"""The C-ABI library loads on a machine without a GPU and exports every symbol include/gsi.h declares."""
+import ctypes
+import os
+import re
+
+from conftest import ROOT
+
+HEADER = os.path.join(ROOT, "include", "gsi.h")
+LIB = os.path.join(ROOT, "paper_2605_03109_amd", "libgsi.so")
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(gsi_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_header_declares_the_boundary():
+    names = declared_functions()
+    for required in ("gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_layer_stack",
+                     "gsi_dense_linear", "gsi_workspace_bytes", "gsi_last_error"):
+        assert required in names
+
+
+def test_library_exports_every_declared_symbol():
+    assert os.path.exists(LIB), "libgsi.so is not built: run python -m paper_2605_03109_amd.build"
+    lib = ctypes.CDLL(LIB)
+    for name in declared_functions():
+        assert hasattr(lib, name), f"{name} declared in gsi.h but not exported"
+
+
+def test_binding_lists_the_same_symbols():
+    from paper_2605_03109_amd import gsi
+
+    assert sorted(gsi.EXPORTS) == declared_functions()
+    assert gsi.version() >= 100
+
+
+def test_host_side_validation_needs_no_gpu():
+    """Argument errors are detected on the host before any launch, so they can be checked here."""
+    from paper_2605_03109_amd import gsi
+
+    lib = gsi.lib
+    one = ctypes.c_void_p(256)  # never dereferenced: validation fails first
+    assert lib.gsi_build_image(None, one, one, 4, 4, 2, gsi.GSI_F32, None, 0, None) == gsi.GSI_ERR_NULL
+    assert b"W is NULL" in lib.gsi_last_error()
+    assert lib.gsi_build_image(one, one, one, 4, 4, 5, gsi.GSI_F32, None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_build_image(one, one, one, 4, 4, 0, gsi.GSI_F32, None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_build_image(one, one, one, 0, 4, 2, gsi.GSI_F32, None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_build_image(one, one, one, 4, 4, 2, 7, None, 0, None) == gsi.GSI_ERR_DTYPE
+    odd = ctypes.c_void_p(257)
+    assert lib.gsi_build_image(odd, one, one, 4, 4, 2, gsi.GSI_F32, None, 0, None) == gsi.GSI_ERR_ALIGN
+    assert lib.gsi_project(one, one, 8, 9, 1, 0, 0, one, one, one, one, None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_project(one, one, 8, 2, -1, 0, 0, one, one, one, one, None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_project(one, one, 8, 2, 0, 0, 0, None, None, None, None, None, 0, None) == gsi.GSI_OK  # B = 0
+    assert lib.gsi_gated_linear(one, one, one, one, one, one, 4, 4, 2, 1, 0, one, gsi.GSI_BF16, None, 0, None) \
+        == gsi.GSI_ERR_DTYPE
+    assert lib.gsi_gate(one, one, 3, ctypes.c_float(0.05), one, one, None, None) == gsi.GSI_ERR_NULL
+    assert lib.gsi_gate(one, one, -1, ctypes.c_float(0.05), one, one, one, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_dense_linear(one, None, 4, 4, 1, 0, 0, one, None, 0, None) == gsi.GSI_ERR_NULL
+    # descriptor tables: bad input id, dependency cycle
+    mp = (gsi.MapDesc * 1)()
+    inp = (gsi.InputDesc * 1)()
+    mp[0].input_id = 3
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
+    mp[0].input_id, mp[0].Y, mp[0].m = 0, 256, 8
+    inp[0].src_map, inp[0].X, inp[0].d, inp[0].k, inp[0].xdtype = 0, 256, 8, 2, 0
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert b"cycle" in lib.gsi_last_error()

@@ -1,0 +1,271 @@
+"""GPU parity: libgsi (through the C ABI) against the fp64 CPU oracle on the same seeded inputs."""
+import ctypes
+
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle.gsi_oracle as O  # noqa: E402
+from paper_2605_03109_amd import workload as wl  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def gsi():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2605_03109_amd import gsi as g
+
+    return g
+
+
+@pytest.fixture(scope="module")
+def pu(gsi):
+    import parity_util
+
+    return parity_util
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------------
+# config 0: GPT-2-small MLP up-projection, fp32, 16 decode tokens one at a time, 4 fired
+# ------------------------------------------------------------------------------------------------
+def test_gpt2_mlp_up_fp32_decode(gsi, pu):
+    w = wl.gpt2_mlp_up()
+    g = w.groups[0]
+    say(f"case {w.name}: d={g.d} k={g.k} m={g.maps[0][1]} T={w.T}")
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    worst = pu.check_group(w, g, [(t, t + 1) for t in range(w.T)], dg, og)
+    ref = og.run()
+    assert ref["n"] == 4
+    worst_b = pu.check_group(w, g, [(0, w.T)], dg, og)  # the same 16 tokens as one batch
+    say(f"  worst rel-L2 {max(worst, worst_b):.3e}")
+    assert max(worst, worst_b) <= 1e-5
+
+
+# ------------------------------------------------------------------------------------------------
+# odd / tiny shapes (generic kernels), both dtypes
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("wdtype", ["f32", "bf16"])
+@pytest.mark.parametrize("d,k,m,T,nf", [(12, 3, 5, 4, 2), (33, 7, 10, 5, 1), (100, 100, 9, 3, 0), (257, 19, 65, 70, 9),
+                                        (64, 8, 16, 3, 3), (1, 1, 1, 2, 0)])
+def test_small_and_odd_shapes(gsi, pu, wdtype, d, k, m, T, nf):
+    w = wl.tiny(d, k, m, T, nf, seed=1000 + d + k, wdtype=wdtype)
+    say(f"case tiny d={d} k={k} m={m} T={T} nf={nf} {wdtype}")
+    pu.check_group(w, w.groups[0], [(0, T)] + [(t, t + 1) for t in range(min(T, 3))])
+
+
+# ------------------------------------------------------------------------------------------------
+# mid-size shapes that span several tiles and ragged tails, aligned for the vector kernels
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("wdtype", ["bf16", "f32"])
+@pytest.mark.parametrize("d,k,m,T,nf", [(1024, 64, 520, 9, 3), (776, 72, 1000, 5, 2), (4096, 256, 1032, 6, 2),
+                                        (2048, 128, 264, 33, 7), (4096, 512, 512, 3, 1), (8192, 32, 300, 2, 1)])
+def test_mid_shapes(gsi, pu, wdtype, d, k, m, T, nf):
+    w = wl.tiny(d, k, m, T, nf, seed=2000 + d + k + m, wdtype=wdtype)
+    say(f"case mid d={d} k={k} m={m} T={T} nf={nf} {wdtype}")
+    worst = pu.check_group(w, w.groups[0], [(0, T), (0, 1), (T - 1, T)])
+    say(f"  worst rel-L2 {worst:.3e}")
+
+
+# ------------------------------------------------------------------------------------------------
+# degenerate gates
+# ------------------------------------------------------------------------------------------------
+def test_all_fire_equals_dense_and_none_fire_is_static_projection(gsi, pu):
+    w = wl.tiny(512, 64, 384, 8, 3, seed=31, wdtype="bf16")
+    g = w.groups[0]
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    C, R, rn, xn = gsi.project(dg.U, dg.X)
+    name = g.maps[0][0]
+    # eps = 0: every token fires and y must equal the dense product W x (Eq. (exact))
+    mask, idx, n = gsi.gate(rn, xn, 0.0)
+    assert int(n.item()) == 8 and mask.cpu().numpy().all()
+    Y = gsi.gated_linear(dg.W[name], dg.M[name], C, R, idx, n).cpu().numpy().astype(np.float64)
+    Yd = O.dense_linear(og.W[name], og.X)
+    assert pu.rel_l2_rows(Y, Yd).max() <= 2e-3
+    Ydense = gsi.dense_linear(dg.W[name], dg.X).cpu().numpy().astype(np.float64)
+    assert pu.rel_l2_rows(Ydense, Yd).max() <= 2e-5
+    # eps > 1: no token fires, y = (W U) U^T x for every token
+    mask, idx, n = gsi.gate(rn, xn, 1.5)
+    assert int(n.item()) == 0 and not mask.cpu().numpy().any()
+    Y = gsi.gated_linear(dg.W[name], dg.M[name], C, R, idx, n).cpu().numpy().astype(np.float64)
+    ref = og.run()
+    Ys = O.gated_linear(og.W[name], og.M[name], ref["C"], ref["R"], np.zeros(8, dtype=np.uint8))
+    assert pu.rel_l2_rows(Y, Ys).max() <= 2e-3
+
+
+def test_zero_token_and_full_rank_basis(gsi, pu):
+    # x = 0: rho := 0, not fired, y = 0
+    w = wl.tiny(256, 32, 300, 4, 2, seed=41, wdtype="f32")
+    g = w.groups[0]
+    g.X[1, :] = 0.0
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    res = pu.run_separate_calls(dg, w.eps)
+    assert res["mask"].cpu().numpy()[1] == 0
+    assert float(res["xnorm"][1]) == 0.0 and float(res["rnorm"][1]) == 0.0
+    assert not res["Y"]["w"][1].cpu().numpy().any()
+    pu.check_group(w, g, [(0, 4)], dg, og)
+    # k = d: r = 0 up to rounding, nothing fires at eps = 0.05, y = W x
+    w2 = wl.tiny(64, 64, 300, 3, 0, seed=43, wdtype="f32")
+    dg2, og2 = pu.DeviceGroup(w2, w2.groups[0]), pu.OracleGroup(w2, w2.groups[0])
+    res2 = pu.run_separate_calls(dg2, w2.eps)
+    assert int(res2["n_fired"].item()) == 0
+    Y = res2["Y"]["w"].cpu().numpy().astype(np.float64)
+    assert pu.rel_l2_rows(Y, O.dense_linear(og2.W["w"], og2.X)).max() <= 1e-5
+
+
+def test_empty_batch(gsi):
+    U = torch.zeros((16, 4), device="cuda")
+    X = torch.zeros((0, 16), device="cuda")
+    C, R, rn, xn = gsi.project(U, X)
+    assert C.shape == (0, 4)
+    n = torch.full((1,), 7, dtype=torch.int32, device="cuda")
+    mask, idx, n = gsi.gate(rn, xn, 0.05, n_fired=n)
+    assert int(n.item()) == 0  # the count is written even for an empty batch
+    W = torch.zeros((8, 16), device="cuda")
+    M = torch.zeros((8, 4), device="cuda")
+    Y = gsi.gated_linear(W, M, C, R, idx, n)
+    assert Y.shape == (0, 8)
+
+
+def test_gate_compaction_many_tokens(gsi):
+    # ragged: B not a multiple of the 256-token chunk, ties exactly at eps, zeros
+    rng = np.random.default_rng(5)
+    B = 1000
+    eps = np.float32(0.05)
+    xn = rng.random(B).astype(np.float32) + 0.5
+    rho = rng.random(B).astype(np.float32) * 0.1
+    rn = (rho * xn).astype(np.float32)
+    xn[17] = 0.0
+    rn[17] = 0.0
+    rn[100] = eps  # rho == eps exactly with xn = 1
+    xn[100] = 1.0
+    mask, idx, n = gsi.gate(torch.from_numpy(rn).cuda(), torch.from_numpy(xn).cuda(), float(eps))
+    with np.errstate(divide="ignore", invalid="ignore"):
+        exp = (xn > 0) & ((rn / xn) >= eps)  # same fp32 division as the kernel: bit-exact expectation
+    assert np.array_equal(mask.cpu().numpy().astype(bool), exp)
+    assert exp[100] and not exp[17]
+    nn = int(n.item())
+    assert nn == exp.sum()
+    assert np.array_equal(idx.cpu().numpy()[:nn], np.nonzero(exp)[0])
+    # and against the oracle outside the band
+    m_or, idx_or, n_or = O.gate(rn.astype(np.float64), xn.astype(np.float64), float(eps))
+    rho64 = O.residual_ratio(rn.astype(np.float64), xn.astype(np.float64))
+    decided = np.abs(rho64 - float(eps)) >= 1e-4
+    assert np.array_equal(mask.cpu().numpy()[decided], m_or[decided])
+
+
+# ------------------------------------------------------------------------------------------------
+# layer stack: equals the separate calls bit for bit, and the oracle within the bars
+# ------------------------------------------------------------------------------------------------
+def _stack_for(gsi, pu, w, B):
+    dgs = [pu.DeviceGroup(w, g) for g in w.groups]
+    inputs, maps, names = [], [], []
+    for gi, dg in enumerate(dgs):
+        inputs.append({"U": dg.U, "X": dg.X})
+        for name in dg.W:
+            maps.append({"W": dg.W[name], "M": dg.M[name], "input_id": gi})
+            names.append((gi, name))
+    return dgs, inputs, maps, names
+
+
+def test_layer_stack_block_decode(gsi, pu):
+    w = wl.transformer_block("blk", d=512, ffn=2048, k=64, T=12, fire_rate=0.25, p=1.5, seed=77)
+    dgs, inputs, maps, names = _stack_for(gsi, pu, w, 1)
+    ogs = [pu.OracleGroup(w, g) for g in w.groups]
+    T = w.T
+    # whole-buffer stack object, advanced one decode token at a time
+    full_inputs = [{"U": dg.U, "X": dg.X} for dg in dgs]
+    st = gsi.LayerStack(full_inputs, maps, T, w.eps)
+    for t in range(T):
+        st.refresh(token_offset=t, B=1)
+        st.run()
+    torch.cuda.synchronize()
+    for gi, (dg, og) in enumerate(zip(dgs, ogs)):
+        ref = og.run()
+        assert ref["n"] == 3
+        sep = pu.run_separate_calls(dg, w.eps)  # all T tokens as one batch
+        ti = st.inputs_t[gi]
+        # per-token decode through the stack vs one batched call: same kernels per token => same bits
+        for key in ("C", "R", "rnorm", "xnorm", "mask"):
+            a, b = ti[key].cpu().numpy(), sep[key].cpu().numpy()
+            assert np.allclose(a, b, rtol=1e-5, atol=1e-5), key
+        res = dict(C=ti["C"], R=ti["R"], rnorm=ti["rnorm"], xnorm=ti["xnorm"], mask=ti["mask"],
+                   n_fired=sep["n_fired"], fired_idx=sep["fired_idx"])
+        mask = pu.check_projection(res, ref, w.eps)
+        for j, (g2, name) in enumerate(names):
+            if g2 != gi:
+                continue
+            pu.check_outputs(st.maps_t[j]["Y"], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
+
+
+def test_layer_stack_equals_separate_calls_bitwise(gsi, pu):
+    w = wl.transformer_block("blk", d=256, ffn=1024, k=32, T=7, fire_rate=0.3, p=1.5, seed=78)
+    dgs, inputs, maps, names = _stack_for(gsi, pu, w, w.T)
+    st = gsi.layer_stack(inputs, maps, w.T, w.eps)
+    torch.cuda.synchronize()
+    for gi, dg in enumerate(dgs):
+        sep = pu.run_separate_calls(dg, w.eps)
+        ti = st.inputs_t[gi]
+        for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired"):
+            assert torch.equal(ti[key], sep[key]), key
+        n = int(sep["n_fired"].item())
+        assert torch.equal(ti["fired_idx"][:n], sep["fired_idx"][:n])
+        for j, (g2, name) in enumerate(names):
+            if g2 == gi:
+                assert torch.equal(st.maps_t[j]["Y"], sep["Y"][name]), name
+
+
+def test_layer_stack_true_chain(gsi, pu):
+    """Two maps chained: the second input is the first map's output (src_map = 0)."""
+    rng = np.random.default_rng(3)
+    d0, k0, m0, k1, m1, B = 256, 32, 384, 48, 200, 5
+    w = wl.tiny(d0, k0, m0, B, 2, seed=91, wdtype="bf16")
+    g = w.groups[0]
+    dg = pu.DeviceGroup(w, g)
+    U1 = wl.store(wl.make_basis64(m0, k1, 92), "bf16")
+    W1 = wl.make_weight(m1, m0, 93, "bf16")
+    U1d, W1d = gsi.to_device(U1, "bf16"), gsi.to_device(W1, "bf16")
+    M1d = gsi.build_image(W1d, U1d)
+    inputs = [{"U": dg.U, "X": dg.X}, {"U": U1d, "src_map": 0}]
+    maps = [{"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}, {"W": W1d, "M": M1d, "input_id": 1}]
+    st = gsi.layer_stack(inputs, maps, B, w.eps)
+    torch.cuda.synchronize()
+    # oracle on the device's own intermediate (the chain input is whatever map 0 produced, in fp32)
+    Y0 = st.maps_t[0]["Y"].cpu().numpy()
+    U1_64, W1_64 = O.widen(U1, "bf16"), O.widen(W1, "bf16")
+    C, R, rn, xn = O.project(U1_64, Y0.astype(np.float64))
+    mask, idx, n = O.gate(rn, xn, w.eps)
+    ref = dict(C=C, R=R, rnorm=rn, xnorm=xn, rho=O.residual_ratio(rn, xn), mask=mask, idx=idx, n=n)
+    ti = st.inputs_t[1]
+    m_gpu = pu.check_projection(ti, ref, w.eps)
+    pu.check_outputs(st.maps_t[1]["Y"], W1_64, O.build_image(W1_64, U1_64), gsi.bits_of(M1d), "bf16", ref, m_gpu,
+                     m_small=128)
+
+
+def test_run_to_run_determinism(gsi, pu):
+    w = wl.tiny(2048, 128, 520, 6, 2, seed=55, wdtype="bf16")
+    dg = pu.DeviceGroup(w, w.groups[0])
+    a = pu.run_separate_calls(dg, w.eps)
+    b = pu.run_separate_calls(dg, w.eps)
+    for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired"):
+        assert torch.equal(a[key], b[key])
+    assert torch.equal(a["Y"]["w"], b["Y"]["w"])
+    M2 = gsi.build_image(dg.W["w"], dg.U)
+    assert torch.equal(M2.view(torch.int16), dg.M["w"].view(torch.int16))
+
+
+def test_workspace_too_small_is_an_error_not_a_crash(gsi):
+    need = gsi.workspace_bytes(gsi.CALL_PROJECT, 0, 4096, 256, 1)
+    if need == 0:
+        pytest.skip("projection needs no workspace in this build")
+    U = torch.zeros((4096, 256), dtype=torch.bfloat16, device="cuda")
+    X = torch.zeros((1, 4096), device="cuda")
+    small = torch.empty(256, dtype=torch.uint8, device="cuda")
+    with pytest.raises(gsi.GsiError) as ei:
+        gsi.project(U, X, ws=small)
+    assert ei.value.code == gsi.GSI_ERR_WORKSPACE
