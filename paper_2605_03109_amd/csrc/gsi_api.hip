@@ -6,6 +6,7 @@
 #include <cstring>
 #include <vector>
 
+#include "gsi_decode.h"
 #include "gsi_internal.h"
 
 namespace {
@@ -23,6 +24,8 @@ int fail(int code, const char* fmt, ...) {
 int hip_fail(hipError_t e, const char* what) {
   return fail(GSI_ERR_HIP, "%s: %s", what, hipGetErrorString(e));
 }
+
+constexpr int64_t kDecodeMaxB = 128;  // above this token count the slab-partial scheme is not used
 
 bool dtype_ok(int dt) { return dt == GSI_F32 || dt == GSI_BF16; }
 bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) % a) == 0; }
@@ -64,8 +67,20 @@ const char* gsi_last_error(void) { return g_err; }
 int gsi_version(void) { return 100; }
 
 size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int64_t B) {
-  (void)m; (void)d; (void)k; (void)B;
+  (void)m;
   switch (which_call) {
+    case GSI_CALL_PROJECT: {
+      // the slab partials of the vector projection kernels; sized for the wider of the two dtypes so
+      // that the query does not depend on the dtype (generic kernels need none)
+      if (d < 1 || k < 1 || k > d || B < 1 || B > kDecodeMaxB) return 0;
+      size_t need = 0;
+      for (int dt = 0; dt < 2; ++dt) {
+        if (!gsi::decode_project_ok(d, k, dt, nullptr)) continue;
+        const size_t w = gsi::decode_project_ws(d, k, B, dt);
+        if (w > need) need = w;
+      }
+      return need;
+    }
     default:
       return 0;
   }
@@ -90,46 +105,95 @@ int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d,
   return GSI_OK;
 }
 
+// argument checks shared by the stand-alone entry points and by gsi_layer_stack
+static int check_project_args(const char* fn, const void* U, const void* X, int64_t d, int64_t k, int64_t B,
+                              int udtype, int xdtype, const float* C, const float* R, const float* rnorm,
+                              const float* xnorm) {
+  if (!dtype_ok(udtype) || !dtype_ok(xdtype))
+    return fail(GSI_ERR_DTYPE, "%s: unknown dtype (udtype %d, xdtype %d)", fn, udtype, xdtype);
+  if (int rc = check_shape(fn, 1, d, k, B)) return rc;
+  if (B == 0) return GSI_OK;
+  if (!U || !X || !C || !R || !rnorm || !xnorm)
+    return fail(GSI_ERR_NULL, "%s: a projection pointer (U, X, C, R, rnorm, xnorm) is NULL", fn);
+  if (!aligned(U, gsi::elem_size(udtype)) || !aligned(X, gsi::elem_size(xdtype)) || !aligned(C, 4) ||
+      !aligned(R, 4) || !aligned(rnorm, 4) || !aligned(xnorm, 4))
+    return fail(GSI_ERR_ALIGN, "%s: a projection pointer is not aligned to its element size", fn);
+  return GSI_OK;
+}
+
+static int check_gate_args(const char* fn, const float* rnorm, const float* xnorm, int64_t B, float eps,
+                           const uint8_t* mask, const int32_t* fired_idx, const int32_t* n_fired) {
+  if (B < 0 || B > (1ll << 30)) return fail(GSI_ERR_SHAPE, "%s: B = %lld out of range", fn, (long long)B);
+  if (!(eps == eps)) return fail(GSI_ERR_SHAPE, "%s: eps is NaN", fn);
+  if (!n_fired) return fail(GSI_ERR_NULL, "%s: n_fired is NULL", fn);
+  if (!aligned(n_fired, 4)) return fail(GSI_ERR_ALIGN, "%s: n_fired is not 4-byte aligned", fn);
+  if (B > 0) {
+    if (!rnorm || !xnorm || !mask || !fired_idx)
+      return fail(GSI_ERR_NULL, "%s: a gate pointer (rnorm, xnorm, mask, fired_idx) is NULL", fn);
+    if (!aligned(rnorm, 4) || !aligned(xnorm, 4) || !aligned(fired_idx, 4))
+      return fail(GSI_ERR_ALIGN, "%s: a gate pointer is not 4-byte aligned", fn);
+  }
+  return GSI_OK;
+}
+
+static int check_gated_args(const char* fn, const void* W, const void* M, const float* C, const float* R,
+                            const int32_t* fired_idx, const int32_t* n_fired, int64_t m, int64_t d, int64_t k,
+                            int64_t B, int wdtype, const void* Y, int ydtype) {
+  if (!dtype_ok(wdtype)) return fail(GSI_ERR_DTYPE, "%s: unknown wdtype %d", fn, wdtype);
+  if (ydtype != GSI_F32) return fail(GSI_ERR_DTYPE, "%s: ydtype must be GSI_F32, got %d", fn, ydtype);
+  if (int rc = check_shape(fn, m, d, k, B)) return rc;
+  if (B == 0) return GSI_OK;
+  if (!W || !M || !C || !R || !fired_idx || !n_fired || !Y)
+    return fail(GSI_ERR_NULL, "%s: a pointer (W, M, C, R, fired_idx, n_fired, Y) is NULL", fn);
+  const size_t es = gsi::elem_size(wdtype);
+  if (!aligned(W, es) || !aligned(M, es) || !aligned(C, 4) || !aligned(R, 4) || !aligned(fired_idx, 4) ||
+      !aligned(n_fired, 4) || !aligned(Y, 4))
+    return fail(GSI_ERR_ALIGN, "%s: a pointer is not aligned to its element size", fn);
+  return GSI_OK;
+}
+
+static bool project_vector_path(int64_t d, int64_t k, int64_t B, int udtype, const void* U) {
+  return B <= kDecodeMaxB && gsi::decode_project_ok(d, k, udtype, U);
+}
+
+static void fill_proj_task(gsi::ProjTask& t, const void* U, const void* X, int64_t d, int64_t k, int64_t B,
+                           int udtype, int xdtype, float* C, float* R, float* rnorm, float* xnorm, void* ws) {
+  t.U = U; t.X = X; t.C = C; t.R = R; t.rnorm = rnorm; t.xnorm = xnorm;
+  t.udtype = udtype; t.xdtype = xdtype;
+  gsi::decode_project_fill(t, d, k, B, ws);
+}
+
+static void fill_lin_task(gsi::LinTask& t, const void* W, const void* M, const float* C, const float* R,
+                          const int32_t* fired_idx, const int32_t* n_fired, int64_t m, int64_t d, int64_t k,
+                          float* Y) {
+  t.W = W; t.M = M; t.C = C; t.R = R; t.fired_idx = fired_idx; t.n_fired = n_fired; t.Y = Y;
+  t.m = (int)m; t.d = (int)d; t.k = (int)k;
+}
+
 int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype, float* C,
                 float* R, float* rnorm, float* xnorm, void* ws, size_t ws_bytes, void* stream) {
-  if (!dtype_ok(udtype) || !dtype_ok(xdtype))
-    return fail(GSI_ERR_DTYPE, "gsi_project: unknown dtype (udtype %d, xdtype %d)", udtype, xdtype);
-  if (int rc = check_shape("gsi_project", 1, d, k, B)) return rc;
+  if (int rc = check_project_args("gsi_project", U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm)) return rc;
   if (B == 0) return GSI_OK;
-  GSI_REQUIRE_PTR(U);
-  GSI_REQUIRE_PTR(X);
-  GSI_REQUIRE_PTR(C);
-  GSI_REQUIRE_PTR(R);
-  GSI_REQUIRE_PTR(rnorm);
-  GSI_REQUIRE_PTR(xnorm);
-  GSI_REQUIRE_ALIGNED(U, gsi::elem_size(udtype));
-  GSI_REQUIRE_ALIGNED(X, gsi::elem_size(xdtype));
-  GSI_REQUIRE_ALIGNED(C, 4);
-  GSI_REQUIRE_ALIGNED(R, 4);
-  GSI_REQUIRE_ALIGNED(rnorm, 4);
-  GSI_REQUIRE_ALIGNED(xnorm, 4);
   if (int rc = check_ws("gsi_project", ws, ws_bytes, gsi_workspace_bytes(GSI_CALL_PROJECT, 0, d, k, B))) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = gsi::generic_project(U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, s);
+  hipError_t e;
+  if (project_vector_path(d, k, B, udtype, U)) {
+    gsi::ProjBatch pb;
+    std::memset(&pb, 0, sizeof(pb));
+    pb.n = 1;
+    pb.B = (int)B;
+    fill_proj_task(pb.t[0], U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, ws);
+    e = gsi::decode_project_launch(pb, udtype, false, 0.f, s);
+  } else {
+    e = gsi::generic_project(U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "gsi_project");
   return GSI_OK;
 }
 
 int gsi_gate(const float* rnorm, const float* xnorm, int64_t B, float eps, uint8_t* mask, int32_t* fired_idx,
              int32_t* n_fired, void* stream) {
-  if (B < 0 || B > (1ll << 30)) return fail(GSI_ERR_SHAPE, "gsi_gate: B = %lld out of range", (long long)B);
-  if (!(eps == eps)) return fail(GSI_ERR_SHAPE, "gsi_gate: eps is NaN");
-  GSI_REQUIRE_PTR(n_fired);
-  GSI_REQUIRE_ALIGNED(n_fired, 4);
-  if (B > 0) {
-    GSI_REQUIRE_PTR(rnorm);
-    GSI_REQUIRE_PTR(xnorm);
-    GSI_REQUIRE_PTR(mask);
-    GSI_REQUIRE_PTR(fired_idx);
-    GSI_REQUIRE_ALIGNED(rnorm, 4);
-    GSI_REQUIRE_ALIGNED(xnorm, 4);
-    GSI_REQUIRE_ALIGNED(fired_idx, 4);
-  }
+  if (int rc = check_gate_args("gsi_gate", rnorm, xnorm, B, eps, mask, fired_idx, n_fired)) return rc;
   // B == 0 still launches: the count must read 0 afterwards.
   hipError_t e = gsi::launch_gate(rnorm, xnorm, B, eps, mask, fired_idx, n_fired, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "gsi_gate");
@@ -139,29 +203,23 @@ int gsi_gate(const float* rnorm, const float* xnorm, int64_t B, float eps, uint8
 int gsi_gated_linear(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
                      const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, int wdtype, void* Y,
                      int ydtype, void* ws, size_t ws_bytes, void* stream) {
-  if (!dtype_ok(wdtype)) return fail(GSI_ERR_DTYPE, "gsi_gated_linear: unknown wdtype %d", wdtype);
-  if (ydtype != GSI_F32) return fail(GSI_ERR_DTYPE, "gsi_gated_linear: ydtype must be GSI_F32, got %d", ydtype);
-  if (int rc = check_shape("gsi_gated_linear", m, d, k, B)) return rc;
+  if (int rc = check_gated_args("gsi_gated_linear", W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, Y, ydtype))
+    return rc;
   if (B == 0) return GSI_OK;
-  GSI_REQUIRE_PTR(W);
-  GSI_REQUIRE_PTR(M);
-  GSI_REQUIRE_PTR(C);
-  GSI_REQUIRE_PTR(R);
-  GSI_REQUIRE_PTR(fired_idx);
-  GSI_REQUIRE_PTR(n_fired);
-  GSI_REQUIRE_PTR(Y);
-  const size_t es = gsi::elem_size(wdtype);
-  GSI_REQUIRE_ALIGNED(W, es);
-  GSI_REQUIRE_ALIGNED(M, es);
-  GSI_REQUIRE_ALIGNED(C, 4);
-  GSI_REQUIRE_ALIGNED(R, 4);
-  GSI_REQUIRE_ALIGNED(fired_idx, 4);
-  GSI_REQUIRE_ALIGNED(n_fired, 4);
-  GSI_REQUIRE_ALIGNED(Y, 4);
   if (int rc = check_ws("gsi_gated_linear", ws, ws_bytes, gsi_workspace_bytes(GSI_CALL_GATED_LINEAR, m, d, k, B)))
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = gsi::generic_gated_linear(W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, (float*)Y, s);
+  hipError_t e;
+  if (gsi::decode_linear_ok(m, d, k, wdtype, W, M)) {
+    gsi::LinBatch lb;
+    std::memset(&lb, 0, sizeof(lb));
+    lb.n = 1;
+    lb.B = (int)B;
+    fill_lin_task(lb.t[0], W, M, C, R, fired_idx, n_fired, m, d, k, (float*)Y);
+    e = gsi::decode_gated_launch(lb, wdtype, s);
+  } else {
+    e = gsi::generic_gated_linear(W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, (float*)Y, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "gsi_gated_linear");
   return GSI_OK;
 }
@@ -181,83 +239,170 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
   if (int rc = check_ws("gsi_dense_linear", ws, ws_bytes, gsi_workspace_bytes(GSI_CALL_DENSE_LINEAR, m, d, 0, B)))
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = gsi::generic_dense_linear(W, X, m, d, B, wdtype, xdtype, Y, s);
+  hipError_t e;
+  if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr)) {
+    gsi::LinBatch lb;
+    std::memset(&lb, 0, sizeof(lb));
+    lb.n = 1;
+    lb.B = (int)B;
+    gsi::LinTask& t = lb.t[0];
+    t.W = W; t.X = X; t.xdtype = xdtype; t.Y = Y;
+    t.m = (int)m; t.d = (int)d; t.k = 0;
+    e = gsi::decode_dense_launch(lb, wdtype, s);
+  } else {
+    e = gsi::generic_dense_linear(W, X, m, d, B, wdtype, xdtype, Y, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "gsi_dense_linear");
   return GSI_OK;
 }
 
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                                        int32_t n_inputs, int64_t B) {
-  if (!maps || !inputs || n_maps < 0 || n_inputs < 0) return 0;
+  (void)maps; (void)n_maps;
+  if (!inputs || n_inputs < 0) return 0;
+  // projections of independent inputs share a launch, so every input has its own region
   size_t need = 0;
-  for (int i = 0; i < n_inputs; ++i) {
-    const size_t w = gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B);
-    if (w > need) need = w;
-  }
-  for (int j = 0; j < n_maps; ++j) {
-    const int id = maps[j].input_id;
-    if (id < 0 || id >= n_inputs) continue;
-    const size_t w = gsi_workspace_bytes(GSI_CALL_GATED_LINEAR, maps[j].m, inputs[id].d, inputs[id].k, B);
-    if (w > need) need = w;
-  }
+  for (int i = 0; i < n_inputs; ++i)
+    need += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
   return need;
 }
 
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream) {
-  if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "gsi_layer_stack: negative count");
+  const char* fn = "gsi_layer_stack";
+  if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
   if (n_maps > 0) GSI_REQUIRE_PTR(maps);
   if (n_inputs > 0) GSI_REQUIRE_PTR(inputs);
-  if (B < 0) return fail(GSI_ERR_SHAPE, "gsi_layer_stack: B = %lld < 0", (long long)B);
+  if (B < 0) return fail(GSI_ERR_SHAPE, "%s: B = %lld < 0", fn, (long long)B);
   for (int j = 0; j < n_maps; ++j) {
     const int id = maps[j].input_id;
-    if (id < 0 || id >= n_inputs)
-      return fail(GSI_ERR_SHAPE, "gsi_layer_stack: maps[%d].input_id = %d out of range", j, id);
+    if (id < 0 || id >= n_inputs) return fail(GSI_ERR_SHAPE, "%s: maps[%d].input_id = %d out of range", fn, j, id);
   }
   for (int i = 0; i < n_inputs; ++i) {
     const int sm = inputs[i].src_map;
-    if (sm < -1 || sm >= n_maps)
-      return fail(GSI_ERR_SHAPE, "gsi_layer_stack: inputs[%d].src_map = %d out of range", i, sm);
+    if (sm < -1 || sm >= n_maps) return fail(GSI_ERR_SHAPE, "%s: inputs[%d].src_map = %d out of range", fn, i, sm);
     if (sm >= 0) {
       if (inputs[i].X != (const void*)maps[sm].Y)
-        return fail(GSI_ERR_SHAPE, "gsi_layer_stack: inputs[%d].X must be maps[%d].Y", i, sm);
+        return fail(GSI_ERR_SHAPE, "%s: inputs[%d].X must be maps[%d].Y", fn, i, sm);
       if (inputs[i].xdtype != GSI_F32 || inputs[i].d != maps[sm].m)
-        return fail(GSI_ERR_SHAPE, "gsi_layer_stack: inputs[%d] does not match the output of maps[%d]", i, sm);
+        return fail(GSI_ERR_SHAPE, "%s: inputs[%d] does not match the output of maps[%d]", fn, i, sm);
     }
   }
-  if (int rc = check_ws("gsi_layer_stack", ws, ws_bytes,
-                        gsi_layer_stack_workspace_bytes(maps, n_maps, inputs, n_inputs, B)))
+  // validate everything before the first launch
+  for (int i = 0; i < n_inputs; ++i) {
+    const gsi_input_desc& in = inputs[i];
+    if (int rc = check_project_args(fn, in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
+                                    in.xnorm))
+      return rc;
+    if (int rc = check_gate_args(fn, in.rnorm, in.xnorm, B, eps, in.mask, in.fired_idx, in.n_fired)) return rc;
+  }
+  for (int j = 0; j < n_maps; ++j) {
+    const gsi_map_desc& mp = maps[j];
+    const gsi_input_desc& in = inputs[mp.input_id];
+    if (int rc = check_gated_args(fn, mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
+                                  mp.wdtype, mp.Y, GSI_F32))
+      return rc;
+  }
+  if (int rc = check_ws(fn, ws, ws_bytes, gsi_layer_stack_workspace_bytes(maps, n_maps, inputs, n_inputs, B)))
     return rc;
+  hipStream_t s = static_cast<hipStream_t>(stream);
 
-  // Schedule: an input is ready when its producer map has been enqueued; a map when its input has.
+  std::vector<size_t> ws_off(n_inputs, 0);
+  {
+    size_t off = 0;
+    for (int i = 0; i < n_inputs; ++i) {
+      ws_off[i] = off;
+      off += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
+    }
+  }
+
+  // Schedule in waves: an input is ready when its producer map has been enqueued, a map when its
+  // input has.  Ready inputs (maps) of one dtype that qualify for the vector kernels share a launch.
   std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0);
   int remaining = n_inputs + n_maps;
   while (remaining > 0) {
     int progressed = 0;
-    for (int i = 0; i < n_inputs; ++i) {
-      if (in_done[i]) continue;
+    std::vector<int> ready;
+    for (int i = 0; i < n_inputs; ++i)
+      if (!in_done[i] && (inputs[i].src_map < 0 || map_done[inputs[i].src_map])) ready.push_back(i);
+    for (int dt = 0; dt < 2; ++dt) {
+      gsi::ProjBatch pb;
+      std::memset(&pb, 0, sizeof(pb));
+      pb.B = (int)B;
+      auto flush = [&]() -> hipError_t {
+        if (pb.n == 0) return hipSuccess;
+        hipError_t e = gsi::decode_project_launch(pb, dt, true, eps, s);
+        std::memset(&pb, 0, sizeof(pb));
+        pb.B = (int)B;
+        return e;
+      };
+      for (int i : ready) {
+        const gsi_input_desc& in = inputs[i];
+        if (in.udtype != dt || B == 0 || !project_vector_path(in.d, in.k, B, in.udtype, in.U)) continue;
+        gsi::ProjTask& t = pb.t[pb.n++];
+        fill_proj_task(t, in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm, in.xnorm,
+                       reinterpret_cast<char*>(ws) + ws_off[i]);
+        t.mask = in.mask; t.fired_idx = in.fired_idx; t.n_fired = in.n_fired;
+        in_done[i] = 2;
+        if (pb.n == gsi::kMaxTasks)
+          if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+      }
+      if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+    }
+    for (int i : ready) {
       const gsi_input_desc& in = inputs[i];
-      if (in.src_map >= 0 && !map_done[in.src_map]) continue;
-      if (int rc = gsi_project(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm, in.xnorm, ws,
-                               ws_bytes, stream))
-        return rc;
-      if (int rc = gsi_gate(in.rnorm, in.xnorm, B, eps, in.mask, in.fired_idx, in.n_fired, stream)) return rc;
+      if (in_done[i] != 2) {  // generic kernels, one input at a time
+        if (B > 0) {
+          hipError_t e = gsi::generic_project(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
+                                              in.xnorm, s);
+          if (e != hipSuccess) return hip_fail(e, fn);
+        }
+        hipError_t e = gsi::launch_gate(in.rnorm, in.xnorm, B, eps, in.mask, in.fired_idx, in.n_fired, s);
+        if (e != hipSuccess) return hip_fail(e, fn);
+      }
       in_done[i] = 1;
       --remaining;
       ++progressed;
     }
-    for (int j = 0; j < n_maps; ++j) {
-      if (map_done[j] || !in_done[maps[j].input_id]) continue;
+
+    std::vector<int> mready;
+    for (int j = 0; j < n_maps; ++j)
+      if (!map_done[j] && in_done[maps[j].input_id] == 1) mready.push_back(j);
+    for (int dt = 0; dt < 2; ++dt) {
+      gsi::LinBatch lb;
+      std::memset(&lb, 0, sizeof(lb));
+      lb.B = (int)B;
+      auto flush = [&]() -> hipError_t {
+        if (lb.n == 0) return hipSuccess;
+        hipError_t e = gsi::decode_gated_launch(lb, dt, s);
+        std::memset(&lb, 0, sizeof(lb));
+        lb.B = (int)B;
+        return e;
+      };
+      for (int j : mready) {
+        const gsi_map_desc& mp = maps[j];
+        const gsi_input_desc& in = inputs[mp.input_id];
+        if (mp.wdtype != dt || B == 0 || !gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M)) continue;
+        fill_lin_task(lb.t[lb.n++], mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, mp.Y);
+        map_done[j] = 2;
+        if (lb.n == gsi::kMaxTasks)
+          if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+      }
+      if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+    }
+    for (int j : mready) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
-      if (int rc = gsi_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
-                                    mp.wdtype, mp.Y, GSI_F32, ws, ws_bytes, stream))
-        return rc;
+      if (map_done[j] != 2 && B > 0) {
+        hipError_t e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k,
+                                                 B, mp.wdtype, mp.Y, s);
+        if (e != hipSuccess) return hip_fail(e, fn);
+      }
       map_done[j] = 1;
       --remaining;
       ++progressed;
     }
-    if (!progressed) return fail(GSI_ERR_SHAPE, "gsi_layer_stack: src_map dependencies form a cycle");
+    if (!progressed) return fail(GSI_ERR_SHAPE, "%s: src_map dependencies form a cycle", fn);
   }
   return GSI_OK;
 }

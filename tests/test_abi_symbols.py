@@ -63,7 +63,10 @@ def test_host_side_validation_needs_no_gpu():
     inp = (gsi.InputDesc * 1)()
     mp[0].input_id = 3
     assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
-    mp[0].input_id, mp[0].Y, mp[0].m = 0, 256, 8
+    mp[0].input_id, mp[0].Y, mp[0].m, mp[0].W, mp[0].M = 0, 256, 8, 256, 256
     inp[0].src_map, inp[0].X, inp[0].d, inp[0].k, inp[0].xdtype = 0, 256, 8, 2, 0
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_NULL
+    for f in ("U", "C", "R", "rnorm", "xnorm", "mask", "fired_idx", "n_fired"):
+        setattr(inp[0], f, 256)
     assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
     assert b"cycle" in lib.gsi_last_error()
