@@ -127,6 +127,21 @@ typedef struct gsi_map_desc {
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream);
 
+/* Instrumented variant for measurements: identical to gsi_layer_stack, and in addition records the
+ * HIP events ev_linear_begin / ev_linear_end (hipEvent_t passed as void*, created by the caller with
+ * timing enabled) on `stream` immediately before and after the launch of the linear-map kernels of
+ * every scheduling wave, so that the caller can read that kernel's duration with
+ * hipEventElapsedTime.  With chained inputs the events bracket the last wave. */
+int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                          int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
+                          void* ev_linear_end);
+
+/* Dense baseline for a whole stack: Y = W X for every map, all maps in one launch (Section 3.1,
+ * the computation the method replaces).  Uses only W, Y, m, wdtype, input_id of each map and X, d,
+ * xdtype of each input (src_map must be -1).  Needs no workspace. */
+int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                    int64_t B, void* stream);
+
 /* Minimum workspace size in bytes for one call (arguments that a call does not have are ignored). */
 size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int64_t B);
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,

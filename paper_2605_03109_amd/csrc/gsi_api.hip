@@ -163,11 +163,9 @@ static void fill_proj_task(gsi::ProjTask& t, const void* U, const void* X, int64
   gsi::decode_project_fill(t, d, k, B, ws);
 }
 
-static void fill_lin_task(gsi::LinTask& t, const void* W, const void* M, const float* C, const float* R,
-                          const int32_t* fired_idx, const int32_t* n_fired, int64_t m, int64_t d, int64_t k,
-                          float* Y) {
-  t.W = W; t.M = M; t.C = C; t.R = R; t.fired_idx = fired_idx; t.n_fired = n_fired; t.Y = Y;
-  t.m = (int)m; t.d = (int)d; t.k = (int)k;
+static void clear(gsi::LinBatch& lb, int64_t B) {
+  std::memset(&lb, 0, sizeof(lb));
+  lb.B = (int)B;
 }
 
 int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype, float* C,
@@ -183,7 +181,7 @@ int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, i
     pb.n = 1;
     pb.B = (int)B;
     fill_proj_task(pb.t[0], U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, ws);
-    e = gsi::decode_project_launch(pb, udtype, false, 0.f, s);
+    e = gsi::decode_project_launch(pb, udtype, true, false, 0.f, s);
   } else {
     e = gsi::generic_project(U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, s);
   }
@@ -212,11 +210,12 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
   hipError_t e;
   if (gsi::decode_linear_ok(m, d, k, wdtype, W, M)) {
     gsi::LinBatch lb;
-    std::memset(&lb, 0, sizeof(lb));
-    lb.n = 1;
-    lb.B = (int)B;
-    fill_lin_task(lb.t[0], W, M, C, R, fired_idx, n_fired, m, d, k, (float*)Y);
-    e = gsi::decode_gated_launch(lb, wdtype, s);
+    clear(lb, B);
+    lb.n = lb.ng = 1;
+    lb.g[0].C = C; lb.g[0].R = R; lb.g[0].fired_idx = fired_idx; lb.g[0].n_fired = n_fired;
+    lb.g[0].d = (int)d; lb.g[0].k = (int)k;
+    lb.t[0].W = W; lb.t[0].M = M; lb.t[0].Y = (float*)Y; lb.t[0].m = (int)m; lb.t[0].group = 0;
+    e = gsi::decode_linear_launch(lb, wdtype, s);
   } else {
     e = gsi::generic_gated_linear(W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, (float*)Y, s);
   }
@@ -242,13 +241,12 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
   hipError_t e;
   if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr)) {
     gsi::LinBatch lb;
-    std::memset(&lb, 0, sizeof(lb));
-    lb.n = 1;
-    lb.B = (int)B;
-    gsi::LinTask& t = lb.t[0];
-    t.W = W; t.X = X; t.xdtype = xdtype; t.Y = Y;
-    t.m = (int)m; t.d = (int)d; t.k = 0;
-    e = gsi::decode_dense_launch(lb, wdtype, s);
+    clear(lb, B);
+    lb.n = lb.ng = 1;
+    lb.dense = 1;
+    lb.g[0].X = X; lb.g[0].xdtype = xdtype; lb.g[0].d = (int)d;
+    lb.t[0].W = W; lb.t[0].Y = Y; lb.t[0].m = (int)m; lb.t[0].group = 0;
+    e = gsi::decode_linear_launch(lb, wdtype, s);
   } else {
     e = gsi::generic_dense_linear(W, X, m, d, B, wdtype, xdtype, Y, s);
   }
@@ -267,9 +265,125 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
   return need;
 }
 
+// Adds map `mp` (reading group description `gd`) to the batch, flushing first when the batch is full or
+// its LDS budget would be exceeded.  `gkey` identifies the input so maps of one input share a group slot.
+namespace {
+struct LinBatcher {
+  gsi::LinBatch lb;
+  int gkeys[gsi::kMaxTasks];
+  int wdtype;
+  hipStream_t s;
+  int64_t B;
+  void reset(int64_t B_, int dense, int inline_gate, float eps) {
+    B = B_;
+    clear(lb, B_);
+    lb.dense = dense; lb.inline_gate = inline_gate; lb.eps = eps;
+  }
+  hipError_t flush() {
+    if (lb.n == 0) return hipSuccess;
+    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s);
+    const int dense = lb.dense, ig = lb.inline_gate;
+    const float eps = lb.eps;
+    reset(B, dense, ig, eps);
+    return e;
+  }
+  hipError_t add(int gkey, const gsi::LinGroup& gd, const void* W, const void* M, float* Y, int64_t m) {
+    for (int attempt = 0; attempt < 2; ++attempt) {
+      int gi = -1;
+      for (int i = 0; i < lb.ng; ++i)
+        if (gkeys[i] == gkey) gi = i;
+      gsi::LinBatch trial = lb;
+      if (gi < 0) {
+        if (trial.ng == gsi::kMaxTasks) gi = -2;
+        else { gi = trial.ng++; trial.g[gi] = gd; }
+      }
+      if (gi >= 0 && trial.n < gsi::kMaxTasks) {
+        gsi::LinTask& t = trial.t[trial.n++];
+        t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi;
+        if (gsi::decode_linear_fits(trial)) {
+          if (gi == lb.ng) gkeys[gi] = gkey;
+          lb = trial;
+          return hipSuccess;
+        }
+      }
+      if (hipError_t e = flush(); e != hipSuccess) return e;  // start a new launch and try once more
+    }
+    return hipErrorInvalidValue;  // a single map that passed decode_linear_ok always fits an empty batch
+  }
+};
+}  // namespace
+
+static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
+                            int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
+                            hipEvent_t ev_begin, hipEvent_t ev_end);
+
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream) {
-  const char* fn = "gsi_layer_stack";
+  return layer_stack_impl("gsi_layer_stack", maps, n_maps, inputs, n_inputs, B, eps, ws, ws_bytes, stream, nullptr,
+                          nullptr);
+}
+
+int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                          int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
+                          void* ev_linear_end) {
+  if (!ev_linear_begin || !ev_linear_end) return fail(GSI_ERR_NULL, "gsi_layer_stack_timed: an event is NULL");
+  return layer_stack_impl("gsi_layer_stack_timed", maps, n_maps, inputs, n_inputs, B, eps, ws, ws_bytes, stream,
+                          static_cast<hipEvent_t>(ev_linear_begin), static_cast<hipEvent_t>(ev_linear_end));
+}
+
+int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                    int64_t B, void* stream) {
+  const char* fn = "gsi_dense_stack";
+  if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
+  if (n_maps > 0) GSI_REQUIRE_PTR(maps);
+  if (n_inputs > 0) GSI_REQUIRE_PTR(inputs);
+  if (B < 0) return fail(GSI_ERR_SHAPE, "%s: B = %lld < 0", fn, (long long)B);
+  for (int j = 0; j < n_maps; ++j) {
+    const gsi_map_desc& mp = maps[j];
+    if (mp.input_id < 0 || mp.input_id >= n_inputs)
+      return fail(GSI_ERR_SHAPE, "%s: maps[%d].input_id = %d out of range", fn, j, mp.input_id);
+    const gsi_input_desc& in = inputs[mp.input_id];
+    if (in.src_map != -1) return fail(GSI_ERR_SHAPE, "%s: chained inputs are not supported", fn);
+    if (!dtype_ok(mp.wdtype) || !dtype_ok(in.xdtype)) return fail(GSI_ERR_DTYPE, "%s: unknown dtype", fn);
+    if (int rc = check_shape(fn, mp.m, in.d, 1, B)) return rc;
+    if (B > 0) {
+      if (!mp.W || !in.X || !mp.Y) return fail(GSI_ERR_NULL, "%s: W, X or Y of maps[%d] is NULL", fn, j);
+      if (!aligned(mp.W, gsi::elem_size(mp.wdtype)) || !aligned(in.X, gsi::elem_size(in.xdtype)) || !aligned(mp.Y, 4))
+        return fail(GSI_ERR_ALIGN, "%s: a pointer of maps[%d] is not aligned to its element size", fn, j);
+    }
+  }
+  if (B == 0) return GSI_OK;
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<char> done(n_maps, 0);
+  for (int dt = 0; dt < 2; ++dt) {
+    LinBatcher bt;
+    bt.wdtype = dt; bt.s = s;
+    bt.reset(B, 1, 0, 0.f);
+    for (int j = 0; j < n_maps; ++j) {
+      const gsi_map_desc& mp = maps[j];
+      const gsi_input_desc& in = inputs[mp.input_id];
+      if (mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr)) continue;
+      gsi::LinGroup gd;
+      std::memset(&gd, 0, sizeof(gd));
+      gd.X = in.X; gd.xdtype = in.xdtype; gd.d = (int)in.d;
+      if (hipError_t e = bt.add(mp.input_id, gd, mp.W, nullptr, mp.Y, mp.m); e != hipSuccess) return hip_fail(e, fn);
+      done[j] = 1;
+    }
+    if (hipError_t e = bt.flush(); e != hipSuccess) return hip_fail(e, fn);
+  }
+  for (int j = 0; j < n_maps; ++j) {
+    if (done[j]) continue;
+    const gsi_map_desc& mp = maps[j];
+    const gsi_input_desc& in = inputs[mp.input_id];
+    hipError_t e = gsi::generic_dense_linear(mp.W, in.X, mp.m, in.d, B, mp.wdtype, in.xdtype, mp.Y, s);
+    if (e != hipSuccess) return hip_fail(e, fn);
+  }
+  return GSI_OK;
+}
+
+static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
+                            int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
+                            hipEvent_t ev_begin, hipEvent_t ev_end) {
   if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
   if (n_maps > 0) GSI_REQUIRE_PTR(maps);
   if (n_inputs > 0) GSI_REQUIRE_PTR(inputs);
@@ -316,8 +430,34 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     }
   }
 
+  // How each input is processed.  kVecInline: vector projection kernels, norms and gate evaluated
+  // inside the single-token linear kernel (possible when B == 1 and every map reading the input takes
+  // that kernel).  kVecGate: vector projection kernels followed by the fused norm + gate kernel.
+  // kGeneric: generic projection kernels and the stand-alone gate kernel.
+  enum { kGeneric = 0, kVecGate = 1, kVecInline = 2 };
+  std::vector<int> mode(n_inputs, kGeneric);
+  std::vector<gsi::ProjTask> ptask(n_inputs);
+  for (int i = 0; i < n_inputs; ++i) {
+    const gsi_input_desc& in = inputs[i];
+    std::memset(&ptask[i], 0, sizeof(gsi::ProjTask));
+    if (B == 0 || !project_vector_path(in.d, in.k, B, in.udtype, in.U)) continue;
+    mode[i] = kVecGate;
+    fill_proj_task(ptask[i], in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm, in.xnorm,
+                   reinterpret_cast<char*>(ws) + ws_off[i]);
+    ptask[i].mask = in.mask; ptask[i].fired_idx = in.fired_idx; ptask[i].n_fired = in.n_fired;
+    if (B != 1) continue;
+    int readers = 0;
+    bool all_stream = true;
+    for (int j = 0; j < n_maps; ++j) {
+      if (maps[j].input_id != i) continue;
+      ++readers;
+      if (!gsi::decode_linear_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M)) all_stream = false;
+    }
+    if (readers > 0 && all_stream) mode[i] = kVecInline;
+  }
+
   // Schedule in waves: an input is ready when its producer map has been enqueued, a map when its
-  // input has.  Ready inputs (maps) of one dtype that qualify for the vector kernels share a launch.
+  // input has.  Ready inputs (maps) of one dtype that take the same kernels share a launch.
   std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0);
   int remaining = n_inputs + n_maps;
   while (remaining > 0) {
@@ -325,33 +465,30 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     std::vector<int> ready;
     for (int i = 0; i < n_inputs; ++i)
       if (!in_done[i] && (inputs[i].src_map < 0 || map_done[inputs[i].src_map])) ready.push_back(i);
-    for (int dt = 0; dt < 2; ++dt) {
-      gsi::ProjBatch pb;
-      std::memset(&pb, 0, sizeof(pb));
-      pb.B = (int)B;
-      auto flush = [&]() -> hipError_t {
-        if (pb.n == 0) return hipSuccess;
-        hipError_t e = gsi::decode_project_launch(pb, dt, true, eps, s);
+    for (int md = kVecGate; md <= kVecInline; ++md) {
+      for (int dt = 0; dt < 2; ++dt) {
+        gsi::ProjBatch pb;
         std::memset(&pb, 0, sizeof(pb));
         pb.B = (int)B;
-        return e;
-      };
-      for (int i : ready) {
-        const gsi_input_desc& in = inputs[i];
-        if (in.udtype != dt || B == 0 || !project_vector_path(in.d, in.k, B, in.udtype, in.U)) continue;
-        gsi::ProjTask& t = pb.t[pb.n++];
-        fill_proj_task(t, in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm, in.xnorm,
-                       reinterpret_cast<char*>(ws) + ws_off[i]);
-        t.mask = in.mask; t.fired_idx = in.fired_idx; t.n_fired = in.n_fired;
-        in_done[i] = 2;
-        if (pb.n == gsi::kMaxTasks)
-          if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+        auto flush = [&]() -> hipError_t {
+          if (pb.n == 0) return hipSuccess;
+          hipError_t e = gsi::decode_project_launch(pb, dt, md == kVecGate, md == kVecGate, eps, s);
+          std::memset(&pb, 0, sizeof(pb));
+          pb.B = (int)B;
+          return e;
+        };
+        for (int i : ready) {
+          if (mode[i] != md || inputs[i].udtype != dt) continue;
+          pb.t[pb.n++] = ptask[i];
+          if (pb.n == gsi::kMaxTasks)
+            if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+        }
+        if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
       }
-      if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
     }
     for (int i : ready) {
       const gsi_input_desc& in = inputs[i];
-      if (in_done[i] != 2) {  // generic kernels, one input at a time
+      if (mode[i] == kGeneric) {
         if (B > 0) {
           hipError_t e = gsi::generic_project(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
                                               in.xnorm, s);
@@ -368,27 +505,34 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     std::vector<int> mready;
     for (int j = 0; j < n_maps; ++j)
       if (!map_done[j] && in_done[maps[j].input_id] == 1) mready.push_back(j);
-    for (int dt = 0; dt < 2; ++dt) {
-      gsi::LinBatch lb;
-      std::memset(&lb, 0, sizeof(lb));
-      lb.B = (int)B;
-      auto flush = [&]() -> hipError_t {
-        if (lb.n == 0) return hipSuccess;
-        hipError_t e = gsi::decode_gated_launch(lb, dt, s);
-        std::memset(&lb, 0, sizeof(lb));
-        lb.B = (int)B;
-        return e;
-      };
-      for (int j : mready) {
-        const gsi_map_desc& mp = maps[j];
-        const gsi_input_desc& in = inputs[mp.input_id];
-        if (mp.wdtype != dt || B == 0 || !gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M)) continue;
-        fill_lin_task(lb.t[lb.n++], mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, mp.Y);
-        map_done[j] = 2;
-        if (lb.n == gsi::kMaxTasks)
-          if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+    if (ev_begin && !mready.empty())
+      if (hipError_t e = hipEventRecord(ev_begin, s); e != hipSuccess) return hip_fail(e, fn);
+    for (int ig = 1; ig >= 0; --ig) {
+      for (int dt = 0; dt < 2; ++dt) {
+        LinBatcher bt;
+        bt.wdtype = dt; bt.s = s;
+        bt.reset(B, 0, ig, eps);
+        for (int j : mready) {
+          const gsi_map_desc& mp = maps[j];
+          const gsi_input_desc& in = inputs[mp.input_id];
+          if (map_done[j] || mp.wdtype != dt || B == 0) continue;
+          if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
+          if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M)) continue;
+          gsi::LinGroup gd;
+          std::memset(&gd, 0, sizeof(gd));
+          gd.C = in.C; gd.R = in.R; gd.fired_idx = in.fired_idx; gd.n_fired = in.n_fired;
+          gd.d = (int)in.d; gd.k = (int)in.k;
+          if (ig) {
+            const gsi::ProjTask& pt = ptask[mp.input_id];
+            gd.part_n = pt.part_n; gd.b_slabs = pt.b_slabs;
+            gd.rnorm = in.rnorm; gd.xnorm = in.xnorm; gd.mask = in.mask;
+            gd.fired_idx_out = in.fired_idx; gd.n_fired_out = in.n_fired;
+          }
+          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m); e != hipSuccess) return hip_fail(e, fn);
+          map_done[j] = 2;
+        }
+        if (hipError_t e = bt.flush(); e != hipSuccess) return hip_fail(e, fn);
       }
-      if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
     }
     for (int j : mready) {
       const gsi_map_desc& mp = maps[j];
@@ -402,6 +546,8 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
       --remaining;
       ++progressed;
     }
+    if (ev_end && !mready.empty())
+      if (hipError_t e = hipEventRecord(ev_end, s); e != hipSuccess) return hip_fail(e, fn);
     if (!progressed) return fail(GSI_ERR_SHAPE, "%s: src_map dependencies form a cycle", fn);
   }
   return GSI_OK;

@@ -1,16 +1,21 @@
-// Task tables and host entry points of the decode-time kernels (see gsi_decode.hip).
+// Task tables and host entry points of the decode-time kernels (gsi_project.hip, gsi_linear.hip).
+//
+// Every kernel is launched over a small table of tasks passed by value in the kernel arguments, so
+// the projections of several inputs, or the linear maps of several weights, share one launch.
 #pragma once
 #include "gsi_internal.h"
 
 namespace gsi {
 
-constexpr int kMaxTasks = 8;        // tasks per launch (passed by value in the kernel arguments)
+constexpr int kMaxTasks = 8;        // tasks (and input groups) per launch
 constexpr int kTokTile = 4;         // tokens processed together by the projection / image kernels
-constexpr int kMaxSlabRows = 256;   // rows of U per workgroup, upper bound
-constexpr int kTargetSlabs = 128;   // row slabs per input the slab height aims for
+constexpr int kColBlock = 64;       // columns of U per workgroup in the partial projection
+constexpr int kPartSlabs = 32;      // row slabs of U per input in the partial projection (= partials per c_j)
+constexpr int kMaxResSlabs = 256;   // row slabs per input in the residual kernel, upper bound
 constexpr int kMaxK = 512;          // largest rank the vector projection kernels take
-constexpr int kRowsPerBlock = 16;   // output rows per workgroup in the linear-map kernels
-constexpr int kMaxLinD = 16384;     // floats of LDS the linear-map kernels may use for one vector
+constexpr int kRowsPerBlock = 16;   // output rows per workgroup in the batched-token linear kernels
+constexpr int kMaxLinD = 16384;     // floats of LDS one activation vector may take in the linear kernels
+constexpr int kMaxSumK = 2048;      // floats of LDS all projection coefficients of a launch may take
 
 struct ProjTask {
   const void* U;
@@ -22,47 +27,69 @@ struct ProjTask {
   uint8_t* mask;       // gate outputs, used only when the gate is fused into the norm kernel
   int32_t* fired_idx;
   int32_t* n_fired;
-  float* part_c;       // [nslab][B][k]
-  float* part_n;       // [nslab][B][2]
-  int d, k, nslab, slab_rows;
+  float* part_c;       // [a_slabs][B][k]  partial projections, one per row slab
+  float* part_n;       // [b_slabs][B][2]  partial |r|^2, |x|^2, one per residual slab
+  int d, k;
+  int a_rows, a_slabs, a_cblocks;  // partial projection: rows per slab, slabs, column blocks
+  int b_rows, b_slabs;             // residual: rows per slab, slabs
   int udtype, xdtype;
 };
 
 struct ProjBatch {
   ProjTask t[kMaxTasks];
-  int blk_begin[kMaxTasks];
+  int a_begin[kMaxTasks];  // first workgroup of each task in the partial-projection launch
+  int b_begin[kMaxTasks];  // ... in the residual launch
   int n, B;
+};
+
+// One input group as seen by the linear kernels: its projection outputs and its gate.
+struct LinGroup {
+  const float* C;
+  const float* R;
+  const void* X;                 // dense baseline only (xdtype)
+  const int32_t* fired_idx;      // read when the gate is not evaluated in the kernel
+  const int32_t* n_fired;
+  // gate evaluated inside the single-token kernel from the residual kernel's partial norms:
+  const float* part_n;
+  float* rnorm;
+  float* xnorm;
+  uint8_t* mask;
+  int32_t* fired_idx_out;
+  int32_t* n_fired_out;
+  int d, k, b_slabs, xdtype;
 };
 
 struct LinTask {
   const void* W;
   const void* M;
-  const float* C;
-  const float* R;
-  const void* X;       // dense baseline only
-  const int32_t* fired_idx;
-  const int32_t* n_fired;
   float* Y;
-  int m, d, k, xdtype;
+  int m, group;
 };
 
 struct LinBatch {
+  LinGroup g[kMaxTasks];
   LinTask t[kMaxTasks];
-  int blk_begin[kMaxTasks];
-  int n, B;
+  int blk_begin[kMaxTasks];  // batched-token kernels only
+  int n, ng, B;
+  int inline_gate;           // single-token kernel: evaluate the gate from part_n (and publish it)
+  int dense;                 // y = W x, no image term
+  float eps;
 };
 
 // eligibility of the vector kernels for a shape / alignment (else the generic kernels run)
 bool decode_project_ok(int64_t d, int64_t k, int udtype, const void* U);
 bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M);
 
-int decode_slab_rows(int64_t d, int64_t k, int udtype);
 size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype);
 // fills d, k, slab geometry and the two workspace pointers of a task whose other fields are set
 void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws);
 
-hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_gate, float eps, hipStream_t s);
-hipError_t decode_gated_launch(LinBatch& lb, int wdtype, hipStream_t s);
-hipError_t decode_dense_launch(LinBatch& lb, int wdtype, hipStream_t s);
+// partial projection + residual (+ norms, + gate): with_norms = false leaves the norms to the
+// single-token linear kernel (which reads part_n itself)
+hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
+                                 hipStream_t s);
+// can a set of tasks share one single-token launch (LDS budget)?
+bool decode_linear_fits(const LinBatch& lb);
+hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s);
 
 }  // namespace gsi

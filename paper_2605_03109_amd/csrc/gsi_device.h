@@ -68,4 +68,26 @@ __device__ __forceinline__ float group_sum_rt(float v, int width) {
   return v;
 }
 
+// ---- gate -----------------------------------------------------------------------------------------
+// fast path iff rho < eps (Algorithm 1, line 4); x = 0 never fires.  IEEE division and square root.
+__device__ __forceinline__ bool gate_fires(float rnorm, float xnorm, float eps) {
+  return (xnorm > 0.f) && (rnorm / xnorm >= eps);
+}
+
+// Sums over the residual kernel's slab shares part_n[slab][B][2] of token t: lane l adds slabs
+// l, l + 64, ... in order, then a butterfly over the wave.  Every lane gets both sums; the order
+// depends on nslab only, so every kernel that calls this gets the same bits.
+__device__ __forceinline__ void wave_norm_sums(const float* __restrict__ part_n, int nslab, int B, int t, float& sr,
+                                               float& sx) {
+  const int lane = threadIdx.x % kWave;
+  float ar = 0.f, ax = 0.f;
+  for (int s = lane; s < nslab; s += kWave) {
+    const float2 v = *reinterpret_cast<const float2*>(part_n + ((int64_t)s * B + t) * 2);
+    ar += v.x;
+    ax += v.y;
+  }
+  sr = group_sum<kWave>(ar);
+  sx = group_sum<kWave>(ax);
+}
+
 }  // namespace gsi

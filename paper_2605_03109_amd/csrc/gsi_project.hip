@@ -1,0 +1,349 @@
+// Projection kernels of libgsi for small token counts (decode): Algorithm 1, lines 1-3.
+//
+//   proj_partial   one workgroup per (input, 64-column block of U, row slab): partial
+//                  c_j = sum over the slab's rows of U[i,j] x[i]; 128-byte row segments per load group,
+//                  fp32 accumulation, the row groups of the workgroup combined through LDS in a
+//                  fixed order.  kPartSlabs partials per coefficient.
+//   proj_residual  one workgroup per (input, row slab): rebuilds c from the partials (fixed slab
+//                  order), forms r = x - U c on its rows, writes R and the slab's share of |r|^2, |x|^2.
+//                  The slab of U is requested before the partials so both latencies overlap.
+//   proj_norms     |r|, |x| from the slab shares; optionally the gate and the ordered compaction.
+//
+// All reductions have a fixed order: results are bit-identical run to run.
+#include "gsi_decode.h"
+#include "gsi_device.h"
+
+namespace gsi {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / kWave;
+
+__device__ __forceinline__ int find_task(const int* begin, int n, int b) {
+  int t = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxTasks; ++i)
+    if (i < n && b >= begin[i]) t = i;
+  return t;
+}
+
+template <class T>
+__global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
+  constexpr int V = T::kVec;
+  __shared__ float red[kBlock * kTokTile * V];  // [row group][token][column of the block]
+
+  const int ti = find_task(pb.a_begin, pb.n, blockIdx.x);
+  const ProjTask& p = pb.t[ti];
+  const int local = blockIdx.x - pb.a_begin[ti];
+  const int cb = local % p.a_cblocks, slab = local / p.a_cblocks;
+  const int d = p.d, k = p.k, B = pb.B;
+  const int cbw = k < kColBlock ? k : kColBlock;  // columns of this block
+  const int lps = cbw / V;                        // lanes per row segment
+  const int rps = kBlock / lps;                   // rows per step
+  const int l = threadIdx.x % lps, ro = threadIdx.x / lps;
+  const int col0 = cb * kColBlock + l * V;
+  const int row0 = slab * p.a_rows;
+  const int rows = min(p.a_rows, d - row0);
+  const typename T::storage* U = reinterpret_cast<const typename T::storage*>(p.U) + (int64_t)row0 * k + col0;
+
+  for (int t0 = 0; t0 < B; t0 += kTokTile) {
+    const int nt = min(kTokTile, B - t0);
+    float acc[kTokTile][V];
+#pragma unroll
+    for (int tt = 0; tt < kTokTile; ++tt)
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[tt][e] = 0.f;
+    int i = ro;
+    // four row steps at a time: all loads of the batch are issued before the first use
+    for (; i + 3 * rps < rows; i += 4 * rps) {
+      float u[4][V], xv[4][kTokTile];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) T::load_vec(U + (int64_t)(i + q * rps) * k, u[q]);
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int tt = 0; tt < kTokTile; ++tt)
+          xv[q][tt] = tt < nt ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i + q * rps) : 0.f;
+#pragma unroll
+      for (int q = 0; q < 4; ++q)
+#pragma unroll
+        for (int tt = 0; tt < kTokTile; ++tt)
+#pragma unroll
+          for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[q][e], xv[q][tt], acc[tt][e]);
+    }
+    for (; i < rows; i += rps) {
+      float u[V];
+      T::load_vec(U + (int64_t)i * k, u);
+#pragma unroll
+      for (int tt = 0; tt < kTokTile; ++tt) {
+        const float xv = tt < nt ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i) : 0.f;
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[e], xv, acc[tt][e]);
+      }
+    }
+#pragma unroll
+    for (int tt = 0; tt < kTokTile; ++tt)
+#pragma unroll
+      for (int e = 0; e < V; ++e) red[(ro * kTokTile + tt) * cbw + l * V + e] = acc[tt][e];
+    __syncthreads();
+    for (int idx = threadIdx.x; idx < nt * cbw; idx += kBlock) {
+      const int tt = idx / cbw, j = idx % cbw;
+      float s = 0.f;
+      for (int g = 0; g < rps; ++g) s += red[(g * kTokTile + tt) * cbw + j];
+      p.part_c[((int64_t)slab * B + t0 + tt) * k + cb * kColBlock + j] = s;
+    }
+    __syncthreads();
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
+  constexpr int V = T::kVec;
+  constexpr int PF = 4;  // row steps of U held in registers
+  __shared__ __align__(16) float cs[kTokTile][kMaxK];
+  __shared__ float nr[kWaves][kTokTile], nx[kWaves][kTokTile];
+
+  const int ti = find_task(pb.b_begin, pb.n, blockIdx.x);
+  const ProjTask& p = pb.t[ti];
+  const int slab = blockIdx.x - pb.b_begin[ti];
+  const int d = p.d, k = p.k, B = pb.B;
+  const int cpr = k / V;         // 16-byte chunks per row (power of two, <= 64)
+  const int rps = kBlock / cpr;  // rows per step
+  const int cc = threadIdx.x % cpr, ro = threadIdx.x / cpr;
+  const int row0 = slab * p.b_rows;
+  const int rows = min(p.b_rows, d - row0);
+  const int steps = (rows + rps - 1) / rps;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const typename T::storage* U = reinterpret_cast<const typename T::storage*>(p.U) + (int64_t)row0 * k + cc * V;
+
+  // the slab of U goes in flight first ...
+  float upf[PF][V];
+#pragma unroll
+  for (int q = 0; q < PF; ++q) {
+    const int i = q * rps + ro;
+    if (i < rows) {
+      T::load_vec(U + (int64_t)i * k, upf[q]);
+    } else {
+#pragma unroll
+      for (int e = 0; e < V; ++e) upf[q][e] = 0.f;
+    }
+  }
+
+  for (int t0 = 0; t0 < B; t0 += kTokTile) {
+    const int nt = min(kTokTile, B - t0);
+    // ... with the slab's activations ...
+    float xpf[PF][kTokTile];
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+#pragma unroll
+      for (int tt = 0; tt < kTokTile; ++tt) {
+        const int i = q * rps + ro;
+        xpf[q][tt] = (i < rows && tt < nt) ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i) : 0.f;
+      }
+    // ... then the partials: c_j = sum over slabs, slab order fixed
+    for (int idx = threadIdx.x; idx < nt * k; idx += kBlock) {
+      const int tt = idx / k, j = idx % k;
+      const float* pc = p.part_c + (int64_t)(t0 + tt) * k + j;
+      const int64_t stride = (int64_t)B * k;
+      float s = 0.f;
+      int sl = 0;
+      for (; sl + 8 <= p.a_slabs; sl += 8) {
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = pc[(sl + q) * stride];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += v[q];
+      }
+      for (; sl < p.a_slabs; ++sl) s += pc[sl * stride];
+      cs[tt][j] = s;
+      if (slab == 0) p.C[(int64_t)(t0 + tt) * k + j] = s;
+    }
+    __syncthreads();
+    float c[kTokTile][V];
+#pragma unroll
+    for (int tt = 0; tt < kTokTile; ++tt)
+#pragma unroll
+      for (int e = 0; e < V; ++e) c[tt][e] = cs[tt][cc * V + e];
+    float ar[kTokTile], ax[kTokTile];
+#pragma unroll
+    for (int tt = 0; tt < kTokTile; ++tt) ar[tt] = ax[tt] = 0.f;
+    // every lane of a row group walks the same steps, so the cross-lane sums are convergent
+    auto row_step = [&](const float (&u)[V], const float (&xv)[kTokTile], int st) {
+      const int i = st * rps + ro;
+      const bool live = i < rows;
+#pragma unroll
+      for (int tt = 0; tt < kTokTile; ++tt) {
+        if (tt < nt) {
+          float s = 0.f;
+#pragma unroll
+          for (int e = 0; e < V; ++e) s = fmaf(u[e], c[tt][e], s);
+          s = group_sum_rt(s, cpr);
+          if (live && cc == 0) {
+            const int64_t off = (int64_t)(t0 + tt) * d + row0 + i;
+            const float x = xv[tt];
+            const float r = x - s;
+            p.R[off] = r;
+            ar[tt] = fmaf(r, r, ar[tt]);
+            ax[tt] = fmaf(x, x, ax[tt]);
+          }
+        }
+      }
+    };
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+      if (q < steps) row_step(upf[q], xpf[q], q);
+    for (int st = PF; st < steps; ++st) {
+      const int i = st * rps + ro;
+      float u[V], xv[kTokTile];
+      if (i < rows) {
+        T::load_vec(U + (int64_t)i * k, u);
+      } else {
+#pragma unroll
+        for (int e = 0; e < V; ++e) u[e] = 0.f;
+      }
+#pragma unroll
+      for (int tt = 0; tt < kTokTile; ++tt)
+        xv[tt] = (i < rows && tt < nt) ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i) : 0.f;
+      row_step(u, xv, st);
+    }
+#pragma unroll
+    for (int tt = 0; tt < kTokTile; ++tt) {
+      const float sr = group_sum<kWave>(ar[tt]);
+      const float sx = group_sum<kWave>(ax[tt]);
+      if (lane == 0) {
+        nr[wave][tt] = sr;
+        nx[wave][tt] = sx;
+      }
+    }
+    __syncthreads();
+    if (threadIdx.x < nt) {
+      float sr = 0.f, sx = 0.f;
+      for (int w = 0; w < kWaves; ++w) {
+        sr += nr[w][threadIdx.x];
+        sx += nx[w][threadIdx.x];
+      }
+      float* pn = p.part_n + ((int64_t)slab * B + t0 + threadIdx.x) * 2;
+      pn[0] = sr;
+      pn[1] = sx;
+    }
+    __syncthreads();
+  }
+}
+
+// |r_t|, |x_t| (and the gate): one workgroup per input; each wave takes tokens w, w + 4, ... of a
+// 256-token chunk, then the chunk is compacted exactly as in the stand-alone gate kernel.
+__global__ __launch_bounds__(kBlock) void proj_norms(const ProjBatch pb, int do_gate, float eps) {
+  __shared__ int wave_count[kWaves];
+  __shared__ unsigned char flag[kBlock];
+  const ProjTask& p = pb.t[blockIdx.x];
+  const int B = pb.B;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  int base = 0;
+  for (int t0 = 0; t0 < B; t0 += kBlock) {
+    const int tend = min(B, t0 + kBlock);
+    for (int t = t0 + wave; t < tend; t += kWaves) {
+      float sr, sx;
+      wave_norm_sums(p.part_n, p.b_slabs, B, t, sr, sx);
+      if (lane == 0) {
+        const float rn = sqrtf(sr), xn = sqrtf(sx);
+        p.rnorm[t] = rn;
+        p.xnorm[t] = xn;
+        flag[t - t0] = gate_fires(rn, xn, eps) ? 1 : 0;
+      }
+    }
+    if (do_gate) {
+      __syncthreads();
+      const int t = t0 + threadIdx.x;
+      const bool fired = t < B && flag[threadIdx.x];
+      if (t < B) p.mask[t] = fired ? 1 : 0;
+      const unsigned long long ballot = __ballot(fired);
+      const int rank_in_wave = __popcll(ballot & ((1ull << lane) - 1ull));
+      if (lane == 0) wave_count[wave] = __popcll(ballot);
+      __syncthreads();
+      int before = 0, total = 0;
+#pragma unroll
+      for (int w = 0; w < kWaves; ++w) {
+        const int c = wave_count[w];
+        if (w < wave) before += c;
+        total += c;
+      }
+      if (fired) p.fired_idx[base + before + rank_in_wave] = t;
+      base += total;
+      __syncthreads();
+    }
+  }
+  if (do_gate && threadIdx.x == 0) p.n_fired[0] = base;
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+bool decode_project_ok(int64_t d, int64_t k, int udtype, const void* U) {
+  const int V = udtype == GSI_BF16 ? 8 : 4;
+  if (k % V) return false;
+  const int64_t cpr = k / V;
+  if (cpr > kWave || (cpr & (cpr - 1))) return false;  // chunks per row: power of two, one wave at most
+  if (k > kMaxK || d > (1 << 24)) return false;
+  return (reinterpret_cast<uintptr_t>(U) % 16) == 0;
+}
+
+namespace {
+struct ProjGeom {
+  int a_rows, a_slabs, a_cblocks, b_rows, b_slabs;
+};
+ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
+  const int V = udtype == GSI_BF16 ? 8 : 4;
+  ProjGeom g;
+  const int cbw = (int)(k < kColBlock ? k : kColBlock);
+  const int rps_a = kBlock / (cbw / V);
+  g.a_cblocks = (int)ceil_div(k, kColBlock);
+  g.a_rows = (int)(ceil_div(ceil_div(d, kPartSlabs), rps_a) * rps_a);
+  g.a_slabs = (int)ceil_div(d, g.a_rows);
+  const int rps_b = kBlock / (int)(k / V);
+  int64_t br = ceil_div(d, kMaxResSlabs);
+  if (br < 4 * rps_b) br = 4 * rps_b;
+  g.b_rows = (int)(ceil_div(br, rps_b) * rps_b);
+  g.b_slabs = (int)ceil_div(d, g.b_rows);
+  return g;
+}
+}  // namespace
+
+size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype) {
+  const ProjGeom g = proj_geom(d, k, udtype);
+  return align_up((size_t)g.a_slabs * B * k * 4, 256) + align_up((size_t)g.b_slabs * B * 2 * 4, 256);
+}
+
+void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws) {
+  const ProjGeom g = proj_geom(d, k, t.udtype);
+  t.d = (int)d;
+  t.k = (int)k;
+  t.a_rows = g.a_rows; t.a_slabs = g.a_slabs; t.a_cblocks = g.a_cblocks;
+  t.b_rows = g.b_rows; t.b_slabs = g.b_slabs;
+  t.part_c = reinterpret_cast<float*>(ws);
+  t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up((size_t)g.a_slabs * B * k * 4, 256));
+}
+
+hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
+                                 hipStream_t s) {
+  int ta = 0, tb = 0;
+  for (int i = 0; i < pb.n; ++i) {
+    pb.a_begin[i] = ta;
+    pb.b_begin[i] = tb;
+    ta += pb.t[i].a_slabs * pb.t[i].a_cblocks;
+    tb += pb.t[i].b_slabs;
+  }
+  if (ta == 0 || pb.B == 0) return hipSuccess;
+  if (udtype == GSI_BF16) {
+    proj_partial<BF16><<<ta, kBlock, 0, s>>>(pb);
+    proj_residual<BF16><<<tb, kBlock, 0, s>>>(pb);
+  } else {
+    proj_partial<F32><<<ta, kBlock, 0, s>>>(pb);
+    proj_residual<F32><<<tb, kBlock, 0, s>>>(pb);
+  }
+  if (with_norms) proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
+  return hipGetLastError();
+}
+
+}  // namespace gsi

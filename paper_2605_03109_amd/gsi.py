@@ -24,6 +24,7 @@ CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR,
 
 EXPORTS = (
     "gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear", "gsi_layer_stack",
+    "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_last_error", "gsi_version",
 )
 
@@ -68,6 +69,10 @@ def _load() -> ctypes.CDLL:
     lib.gsi_dense_linear.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, sz, vp]
     lib.gsi_layer_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                     ctypes.c_int32, i64, f32, vp, sz, vp]
+    lib.gsi_layer_stack_timed.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
+                                          ctypes.c_int32, i64, f32, vp, sz, vp, vp, vp]
+    lib.gsi_dense_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
+                                    ctypes.c_int32, i64, vp]
     lib.gsi_workspace_bytes.argtypes = [i32, i64, i64, i64, i64]
     lib.gsi_workspace_bytes.restype = sz
     lib.gsi_layer_stack_workspace_bytes.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32,
@@ -76,7 +81,7 @@ def _load() -> ctypes.CDLL:
     lib.gsi_last_error.restype = ctypes.c_char_p
     lib.gsi_version.restype = ctypes.c_int
     for name in ("gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
-                 "gsi_layer_stack"):
+                 "gsi_layer_stack", "gsi_layer_stack_timed", "gsi_dense_stack"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
 
@@ -263,9 +268,8 @@ class LayerStack:
             })
         self._in = (InputDesc * len(self.inputs_t))()
         self._mp = (MapDesc * len(self.maps_t))()
+        self.ws = torch.empty(256, dtype=torch.uint8, device=dev)
         self.refresh()
-        need = int(lib.gsi_layer_stack_workspace_bytes(self._mp, len(self.maps_t), self._in, len(self.inputs_t), B))
-        self.ws = torch.empty(max(need, 256), dtype=torch.uint8, device=dev)
 
     def refresh(self, token_offset: int = 0, B: Optional[int] = None) -> None:
         """(Re)write the descriptor tables; ``token_offset`` selects rows [offset, offset+B) of every buffer."""
@@ -292,10 +296,24 @@ class LayerStack:
             e.W, e.M, e.m = _ptr(t["W"]), _ptr(t["M"]), m
             e.Y = _ptr(t["Y"]) + o * m * 4
             e.wdtype, e.input_id = dtype_code(t["W"]), t["input_id"]
+        need = int(lib.gsi_layer_stack_workspace_bytes(self._mp, len(self.maps_t), self._in, len(self.inputs_t), B))
+        if need > self.ws.numel():  # the workspace depends on the token count of the call
+            self.ws = torch.empty(need, dtype=torch.uint8, device=self.ws.device)
 
     def run(self, stream=None) -> None:
         _check(lib.gsi_layer_stack(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B, self.eps,
                                    self.ws.data_ptr(), self.ws.numel(), _stream(stream)))
+
+    def run_timed(self, ev_begin: int, ev_end: int, stream=None) -> None:
+        """As run(), with raw hipEvent_t handles recorded around the linear-map kernel launch."""
+        _check(lib.gsi_layer_stack_timed(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B,
+                                         self.eps, self.ws.data_ptr(), self.ws.numel(), _stream(stream), ev_begin,
+                                         ev_end))
+
+    def run_dense(self, stream=None) -> None:
+        """The dense baseline Y = W X over the same descriptor tables (one launch for all maps)."""
+        _check(lib.gsi_dense_stack(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B,
+                                   _stream(stream)))
 
 
 def layer_stack(inputs: Sequence[dict], maps: Sequence[dict], B: int, eps: float, stream=None) -> LayerStack:
