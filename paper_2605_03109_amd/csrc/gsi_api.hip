@@ -208,7 +208,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (gsi::decode_linear_ok(m, d, k, wdtype, W, M)) {
+  if (gsi::decode_linear_ok(m, d, k, wdtype, W, M) && aligned(C, 16) && aligned(R, 16)) {
     gsi::LinBatch lb;
     clear(lb, B);
     lb.n = lb.ng = 1;
@@ -239,7 +239,7 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr)) {
+  if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr) && aligned(X, 16)) {
     gsi::LinBatch lb;
     clear(lb, B);
     lb.n = lb.ng = 1;
@@ -362,7 +362,8 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     for (int j = 0; j < n_maps; ++j) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
-      if (mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr)) continue;
+      if (mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr) || !aligned(in.X, 16))
+        continue;
       gsi::LinGroup gd;
       std::memset(&gd, 0, sizeof(gd));
       gd.X = in.X; gd.xdtype = in.xdtype; gd.d = (int)in.d;
@@ -451,7 +452,9 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     for (int j = 0; j < n_maps; ++j) {
       if (maps[j].input_id != i) continue;
       ++readers;
-      if (!gsi::decode_linear_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M)) all_stream = false;
+      if (!gsi::decode_linear_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M) ||
+          !aligned(in.C, 16) || !aligned(in.R, 16))
+        all_stream = false;
     }
     if (readers > 0 && all_stream) mode[i] = kVecInline;
   }
@@ -517,7 +520,9 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           const gsi_input_desc& in = inputs[mp.input_id];
           if (map_done[j] || mp.wdtype != dt || B == 0) continue;
           if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
-          if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M)) continue;
+          if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
+              !aligned(in.R, 16))
+            continue;
           gsi::LinGroup gd;
           std::memset(&gd, 0, sizeof(gd));
           gd.C = in.C; gd.R = in.R; gd.fired_idx = in.fired_idx; gd.n_fired = in.n_fired;

@@ -69,7 +69,8 @@ struct LinTask {
 struct LinBatch {
   LinGroup g[kMaxTasks];
   LinTask t[kMaxTasks];
-  int blk_begin[kMaxTasks];  // batched-token kernels only
+  int blk_begin[kMaxTasks];        // several-token kernels: first workgroup of each task
+  int short_begin[kMaxTasks + 1];  // single-token kernel: first image-row item of each task
   int n, ng, B;
   int inline_gate;           // single-token kernel: evaluate the gate from part_n (and publish it)
   int dense;                 // y = W x, no image term
@@ -91,5 +92,9 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
 // can a set of tasks share one single-token launch (LDS budget)?
 bool decode_linear_fits(const LinBatch& lb);
 hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s);
+
+// single-token persistent kernel (gsi_stream.hip)
+size_t stream_smem_bytes(const LinBatch& lb);
+hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s);
 
 }  // namespace gsi

@@ -77,6 +77,18 @@ __device__ __forceinline__ bool gate_fires(float rnorm, float xnorm, float eps) 
 // Sums over the residual kernel's slab shares part_n[slab][B][2] of token t: lane l adds slabs
 // l, l + 64, ... in order, then a butterfly over the wave.  Every lane gets both sums; the order
 // depends on nslab only, so every kernel that calls this gets the same bits.
+// per-lane part of the sums below (lets a caller put the loads of several inputs in flight together)
+__device__ __forceinline__ void wave_norm_partial(const float* __restrict__ part_n, int nslab, float& ar, float& ax) {
+  const int lane = threadIdx.x % kWave;
+  ar = 0.f;
+  ax = 0.f;
+  for (int s = lane; s < nslab; s += kWave) {
+    const float2 v = *reinterpret_cast<const float2*>(part_n + (int64_t)s * 2);
+    ar += v.x;
+    ax += v.y;
+  }
+}
+
 __device__ __forceinline__ void wave_norm_sums(const float* __restrict__ part_n, int nslab, int B, int t, float& sr,
                                                float& sx) {
   const int lane = threadIdx.x % kWave;

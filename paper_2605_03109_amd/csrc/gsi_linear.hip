@@ -1,19 +1,9 @@
-// Linear-map kernels of libgsi for small token counts (decode): Algorithm 1 lines 4-7 in the
-// y = M c (+ W r when the gate fires) form of Eq. (exact), and the dense baseline y = W x.
+// Linear-map kernels of libgsi for a few tokens per call (decode batches): Algorithm 1 lines 4-7 in
+// the y = M c (+ W r when the gate fires) form of Eq. (exact), and the dense baseline y = W x.
 //
-// stream_rows (one token): a persistent grid of a few workgroups per CU.  Every wave first learns
-//   the gate of every input group (either from the published count, or by reducing the residual
-//   kernel's partial norms itself -- identical arithmetic in every wave, so the decision is uniform
-//   across the grid without any communication).  The projection coefficients of all groups are
-//   staged in LDS once.  Rows of maps whose input did not fire are "short" (k elements of the image M,
-//   several rows per 1-KB wave load); rows of fired maps are "long" (d elements of W plus the row of
-//   M), one row per wave with four 16-byte loads in flight per lane and the activation vector in LDS.
-//   Rows are dealt round-robin over all waves of the grid, so concurrently running waves stream
-//   neighbouring rows.  Every output element is written exactly once, by one wave.
-//   A map whose input did not fire never issues a load from W.
-//
-// gated_rows / dense_rows (several tokens): one workgroup per tile of 16 output rows; token tiles of
-//   four for the image term, one fired token at a time (from the device-side list) for the W term.
+// gated_rows / dense_rows: one workgroup per tile of 16 output rows; token tiles of four for the image
+//   term, one fired token at a time (from the device-side list) for the W term.  The single-token
+//   case is served by the persistent streaming kernel in gsi_stream.hip.
 #include <cstdlib>
 
 #include "gsi_decode.h"
@@ -48,166 +38,6 @@ __device__ __forceinline__ float dotv(const float (&a)[V], const float (&b)[V], 
 #pragma unroll
   for (int e = 0; e < V; ++e) acc = fmaf(a[e], b[e], acc);
   return acc;
-}
-
-// ------------------------------------------------------------------------------------------------
-// single token
-// ------------------------------------------------------------------------------------------------
-template <class T, int UNR>
-__global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
-  constexpr int V = T::kVec;
-  extern __shared__ __align__(16) float smem[];  // [coefficients of every group][one activation vector]
-  using S = typename T::storage;
-
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int gw = blockIdx.x * kWaves + wave;  // this wave's index in the grid
-  const int GW = gridDim.x * kWaves;
-
-  // ---- gate of every group, identical in every wave --------------------------------------------
-  unsigned fired_mask = 0;
-  int sumk = 0;
-  auto coff = [&](int gi) {  // offset of group gi's coefficients in LDS
-    int o = 0;
-    for (int i = 0; i < gi; ++i) o += lb.g[i].k;
-    return o;
-  };
-  for (int gi = 0; gi < kMaxTasks; ++gi) {
-    if (gi < lb.ng) {
-      const LinGroup& g = lb.g[gi];
-      bool f;
-      if (lb.dense) {
-        f = true;
-      } else if (lb.inline_gate) {
-        float sr, sx;
-        wave_norm_sums(g.part_n, g.b_slabs, 1, 0, sr, sx);
-        const float rn = sqrtf(sr), xn = sqrtf(sx);
-        f = gate_fires(rn, xn, lb.eps);
-        if (blockIdx.x == 0 && threadIdx.x == 0) {  // publish, as the stand-alone norm + gate kernels would
-          g.rnorm[0] = rn;
-          g.xnorm[0] = xn;
-          g.mask[0] = f ? 1 : 0;
-          if (f) g.fired_idx_out[0] = 0;
-          g.n_fired_out[0] = f ? 1 : 0;
-        }
-      } else {
-        f = g.n_fired[0] > 0;
-      }
-      if (f) fired_mask |= 1u << gi;
-      if (!lb.dense) sumk += g.k;
-    }
-  }
-  float* xs = smem + sumk;
-
-  // ---- image rows of the maps that did not fire --------------------------------------------------
-  if (!lb.dense) {
-    for (int gi = 0; gi < lb.ng; ++gi) {
-      const LinGroup& g = lb.g[gi];
-      const int co = coff(gi);
-      for (int idx = threadIdx.x; idx < g.k; idx += kBlock) smem[co + idx] = g.C[idx];
-    }
-    __syncthreads();
-  }
-  int off = 0;  // running item offset, so the round-robin deal continues across tasks
-  if (!lb.dense) {
-    for (int ti = 0; ti < lb.n; ++ti) {
-      const LinTask& t = lb.t[ti];
-      if ((fired_mask >> t.group) & 1u) continue;
-      const int k = lb.g[t.group].k, m = t.m;
-      const float* cv = smem + coff(t.group);
-      const S* M = reinterpret_cast<const S*>(t.M);
-      const int chunks = k / V;
-      int lpr = kWave;
-      while (lpr / 2 >= chunks && lpr > 1) lpr >>= 1;  // lanes per row: smallest power of two >= chunks
-      const int rpw = kWave / lpr, sub = lane / lpr, l = lane % lpr;
-      const int ri = 4 * rpw;  // rows per item: four loads per lane
-      const int items = (m + ri - 1) / ri;
-      int it = (gw - off % GW + GW) % GW;
-      for (; it < items; it += GW) {
-        const int rb = it * ri + sub;
-        float acc[4] = {0.f, 0.f, 0.f, 0.f};
-        for (int c = l; c < chunks; c += lpr) {
-          float w[4][V], cvv[V];
-#pragma unroll
-          for (int u = 0; u < 4; ++u) {
-            const int row = rb + u * rpw;
-            if (row < m) {
-              T::load_vec(M + (int64_t)row * k + c * V, w[u]);
-            } else {
-#pragma unroll
-              for (int e = 0; e < V; ++e) w[u][e] = 0.f;
-            }
-          }
-          lds_vec<V>(cv + c * V, cvv);
-#pragma unroll
-          for (int u = 0; u < 4; ++u) acc[u] = dotv<V>(w[u], cvv, acc[u]);
-        }
-#pragma unroll
-        for (int u = 0; u < 4; ++u) {
-          const float s = group_sum_rt(acc[u], lpr);
-          const int row = rb + u * rpw;
-          if (l == 0 && row < m) t.Y[row] = s;
-        }
-      }
-      off += items;
-    }
-  }
-
-  // ---- rows of fired maps (or every map in the dense baseline), one input group at a time ---------
-  for (int gi = 0; gi < lb.ng; ++gi) {
-    if (!((fired_mask >> gi) & 1u)) continue;  // uniform across the grid
-    const LinGroup& g = lb.g[gi];
-    const int d = g.d, k = g.k;
-    __syncthreads();
-    if (lb.dense) {
-      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(g.X, g.xdtype, idx);
-    } else {
-      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = g.R[idx];
-    }
-    __syncthreads();
-    const int chunks = d / V;
-    const int kchunks = lb.dense ? 0 : k / V;
-    const float* cv = smem + coff(gi);
-    for (int ti = 0; ti < lb.n; ++ti) {
-      const LinTask& t = lb.t[ti];
-      if (t.group != gi) continue;
-      const S* W = reinterpret_cast<const S*>(t.W);
-      const S* M = reinterpret_cast<const S*>(t.M);
-      const int m = t.m;
-      int row = (gw - off % GW + GW) % GW;
-      for (; row < m; row += GW) {
-        const S* wr = W + (int64_t)row * d;
-        float acc = 0.f;
-        // the row of the image goes in flight together with the first loads of W
-        for (int c = lane; c < kchunks; c += kWave) {
-          float mv[V], cvv[V];
-          T::load_vec(M + (int64_t)row * k + c * V, mv);
-          lds_vec<V>(cv + c * V, cvv);
-          acc = dotv<V>(mv, cvv, acc);
-        }
-        int c = lane;
-        for (; c + (UNR - 1) * kWave < chunks; c += UNR * kWave) {
-          float w[UNR][V];
-#pragma unroll
-          for (int u = 0; u < UNR; ++u) T::load_vec(wr + (int64_t)(c + u * kWave) * V, w[u]);
-#pragma unroll
-          for (int u = 0; u < UNR; ++u) {
-            float xv[V];
-            lds_vec<V>(xs + (c + u * kWave) * V, xv);
-            acc = dotv<V>(w[u], xv, acc);
-          }
-        }
-        for (; c < chunks; c += kWave) {
-          float w[V], xv[V];
-          T::load_vec(wr + (int64_t)c * V, w);
-          lds_vec<V>(xs + c * V, xv);
-          acc = dotv<V>(w, xv, acc);
-        }
-        acc = group_sum<kWave>(acc);
-        if (lane == 0) t.Y[row] = acc;
-      }
-      off += m;
-    }
-  }
 }
 
 // ------------------------------------------------------------------------------------------------
@@ -347,32 +177,6 @@ __global__ __launch_bounds__(kBlock) void dense_rows(const LinBatch lb) {
   }
 }
 
-int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  if (!v || !*v) return dflt;
-  const int x = std::atoi(v);
-  return x > 0 ? x : dflt;
-}
-
-int num_cus() {
-  static const int n = [] {
-    int dev = 0, cu = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return 256;
-    if (hipDeviceGetAttribute(&cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cu <= 0) return 256;
-    return cu;
-  }();
-  return n;
-}
-
-size_t stream_smem(const LinBatch& lb) {
-  size_t sumk = 0, maxd = 0;
-  for (int i = 0; i < lb.ng; ++i) {
-    if (!lb.dense) sumk += (size_t)lb.g[i].k;
-    if ((size_t)lb.g[i].d > maxd) maxd = (size_t)lb.g[i].d;
-  }
-  return (sumk + maxd) * sizeof(float);
-}
-
 size_t tile_smem(const LinBatch& lb) {
   size_t fl = 0;
   for (int i = 0; i < lb.ng; ++i) {
@@ -389,6 +193,7 @@ bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   if (d % V || (k > 0 && k % V)) return false;
   if (d > kMaxLinD || kTokTile * k > kMaxLinD || k > kMaxSumK) return false;
+  if (k / V > kWave) return false;  // one 16-byte chunk of an image row per lane
   if (reinterpret_cast<uintptr_t>(W) % 16) return false;
   if (M && reinterpret_cast<uintptr_t>(M) % 16) return false;
   return m < (1ll << 30);
@@ -398,42 +203,14 @@ bool decode_linear_fits(const LinBatch& lb) {
   if (lb.B == 1) {
     size_t sumk = 0;
     for (int i = 0; i < lb.ng; ++i) sumk += (size_t)lb.g[i].k;
-    return sumk <= (size_t)kMaxSumK && stream_smem(lb) <= (size_t)(kMaxLinD + kMaxSumK) * sizeof(float);
+    return sumk <= (size_t)kMaxSumK && stream_smem_bytes(lb) <= (size_t)(kMaxLinD + kMaxSumK) * sizeof(float);
   }
   return tile_smem(lb) <= (size_t)kMaxLinD * sizeof(float);
 }
 
 hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s) {
   if (lb.n == 0 || lb.B == 0) return hipSuccess;
-  if (lb.B == 1) {
-    // persistent grid: a few workgroups per CU, never more waves than rows
-    static const int per_cu = env_int("GSI_LIN_WGS_PER_CU", 2);
-    static const int unr8 = env_int("GSI_LIN_UNROLL", 4) == 8;
-    int64_t rows = 0;
-    for (int i = 0; i < lb.n; ++i) rows += lb.t[i].m;
-    int64_t grid = (int64_t)per_cu * num_cus();
-    if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
-    if (grid < 1) grid = 1;
-    const size_t smem = stream_smem(lb);
-    static const hipError_t attr = [] {  // the kernels may use more than the default 64 KB of dynamic LDS
-      const int cap = (kMaxLinD + kMaxSumK) * (int)sizeof(float);
-      hipError_t e = hipSuccess, r;
-      r = hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<BF16, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, cap); if (r != hipSuccess) e = r;
-      r = hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<BF16, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, cap); if (r != hipSuccess) e = r;
-      r = hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<F32, 4>), hipFuncAttributeMaxDynamicSharedMemorySize, cap); if (r != hipSuccess) e = r;
-      r = hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<F32, 8>), hipFuncAttributeMaxDynamicSharedMemorySize, cap); if (r != hipSuccess) e = r;
-      return e;
-    }();
-    if (attr != hipSuccess) return attr;
-    if (wdtype == GSI_BF16) {
-      if (unr8) stream_rows<BF16, 8><<<(unsigned)grid, kBlock, smem, s>>>(lb);
-      else stream_rows<BF16, 4><<<(unsigned)grid, kBlock, smem, s>>>(lb);
-    } else {
-      if (unr8) stream_rows<F32, 8><<<(unsigned)grid, kBlock, smem, s>>>(lb);
-      else stream_rows<F32, 4><<<(unsigned)grid, kBlock, smem, s>>>(lb);
-    }
-    return hipGetLastError();
-  }
+  if (lb.B == 1) return stream_rows_launch(lb, wdtype, s);
   int total = 0;
   for (int i = 0; i < lb.n; ++i) {
     lb.blk_begin[i] = total;
