@@ -11,7 +11,7 @@ constexpr int kMaxTasks = 8;        // tasks (and input groups) per launch
 constexpr int kTokTile = 4;         // tokens processed together by the projection / image kernels
 constexpr int kColBlock = 64;       // columns of U per workgroup in the partial projection
 constexpr int kPartSlabs = 32;      // row slabs of U per input in the partial projection (= partials per c_j)
-constexpr int kMaxResSlabs = 256;   // row slabs per input in the residual kernel, upper bound
+constexpr int kMaxResSlabs = 512;   // row slabs per input in the residual kernel, upper bound
 constexpr int kMaxK = 512;          // largest rank the vector projection kernels take
 constexpr int kRowsPerBlock = 16;   // output rows per workgroup in the batched-token linear kernels
 constexpr int kMaxLinD = 16384;     // floats of LDS one activation vector may take in the linear kernels

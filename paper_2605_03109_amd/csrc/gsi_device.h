@@ -31,6 +31,10 @@ struct F32 {
     const float4 v = *reinterpret_cast<const float4*>(p);
     f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w;
   }
+  // widen 16 raw bytes (as loaded) to kVec floats
+  __device__ static __forceinline__ void widen(const uint4& v, float (&f)[4]) {
+    f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
+  }
 };
 
 struct BF16 {
@@ -45,6 +49,12 @@ struct BF16 {
     f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z);
     f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
   }
+  __device__ static __forceinline__ void widen(const uint4& v, float (&f)[8]) {
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x);
+    f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z);
+    f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+  }
 };
 
 // activation element of runtime dtype (0 = fp32, 1 = bf16)
@@ -54,18 +64,38 @@ __device__ __forceinline__ float load_act(const void* p, int dtype, int64_t i) {
 }
 
 // ---- cross-lane reductions ---------------------------------------------------------------------
-// Sum over groups of `width` consecutive lanes (width a power of two <= 64); every lane of a group
-// ends with the group's total.  Butterfly order is fixed, so results are run-to-run identical.
-template <int width>
-__device__ __forceinline__ float group_sum(float v) {
-#pragma unroll
-  for (int off = width / 2; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+// Sums over aligned groups of `width` consecutive lanes (width a power of two <= 64); every lane of a
+// group ends with the group's total.  Steps inside a row of 16 lanes are DPP adds (no LDS round
+// trip); rows are combined through four lane reads.  The order of additions is fixed, so results
+// are identical run to run and between kernels.
+template <int ctrl>
+__device__ __forceinline__ float dpp_move(float v) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), ctrl, 0xf, 0xf, false));
 }
 
+// Branch-free for a run-time width: every step is executed, steps beyond the width add zero.
 __device__ __forceinline__ float group_sum_rt(float v, int width) {
-  for (int off = width >> 1; off > 0; off >>= 1) v += __shfl_xor(v, off, kWave);
-  return v;
+  float t;
+  t = dpp_move<0xB1>(v);   // quad_perm [1,0,3,2]: lane ^ 1
+  v += width >= 2 ? t : 0.f;
+  t = dpp_move<0x4E>(v);   // quad_perm [2,3,0,1]: lane ^ 2
+  v += width >= 4 ? t : 0.f;
+  t = dpp_move<0x141>(v);  // row_half_mirror: lane i <-> 7 - i of each half row
+  v += width >= 8 ? t : 0.f;
+  t = dpp_move<0x140>(v);  // row_mirror: lane i <-> 15 - i of each row
+  v += width >= 16 ? t : 0.f;
+  const float r0 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 0));
+  const float r1 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 16));
+  const float r2 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 32));
+  const float r3 = __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), 48));
+  const float lo = r0 + r1, hi = r2 + r3;
+  const float half = (threadIdx.x & 32) ? hi : lo;
+  return width >= 64 ? lo + hi : (width >= 32 ? half : v);
+}
+
+template <int width>
+__device__ __forceinline__ float group_sum(float v) {
+  return group_sum_rt(v, width);
 }
 
 // ---- gate -----------------------------------------------------------------------------------------

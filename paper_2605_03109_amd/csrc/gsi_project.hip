@@ -13,6 +13,11 @@
 #include "gsi_decode.h"
 #include "gsi_device.h"
 
+// Phase markers: empty in the library; a profiling build may define GSI_MARK(i) to record a timestamp.
+#ifndef GSI_MARK
+#define GSI_MARK(i)
+#endif
+
 namespace gsi {
 namespace {
 
@@ -27,10 +32,10 @@ __device__ __forceinline__ int find_task(const int* begin, int n, int b) {
   return t;
 }
 
-template <class T>
+template <class T, int TB>
 __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
   constexpr int V = T::kVec;
-  __shared__ float red[kBlock * kTokTile * V];  // [row group][token][column of the block]
+  __shared__ float red[kBlock * TB * V];  // [row group][token][column of the block]
 
   const int ti = find_task(pb.a_begin, pb.n, blockIdx.x);
   const ProjTask& p = pb.t[ti];
@@ -38,70 +43,109 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
   const int cb = local % p.a_cblocks, slab = local / p.a_cblocks;
   const int d = p.d, k = p.k, B = pb.B;
   const int cbw = k < kColBlock ? k : kColBlock;  // columns of this block
-  const int lps = cbw / V;                        // lanes per row segment
+  const int lps = cbw / V;                        // lanes per row segment (a power of two)
   const int rps = kBlock / lps;                   // rows per step
-  const int l = threadIdx.x % lps, ro = threadIdx.x / lps;
+  const int lsh = __builtin_ctz(lps);
+  const int l = threadIdx.x & (lps - 1), ro = threadIdx.x >> lsh;
   const int col0 = cb * kColBlock + l * V;
   const int row0 = slab * p.a_rows;
   const int rows = min(p.a_rows, d - row0);
   const typename T::storage* U = reinterpret_cast<const typename T::storage*>(p.U) + (int64_t)row0 * k + col0;
 
-  for (int t0 = 0; t0 < B; t0 += kTokTile) {
-    const int nt = min(kTokTile, B - t0);
-    float acc[kTokTile][V];
+  GSI_MARK(0);
+  for (int t0 = 0; t0 < B; t0 += TB) {
+    const int nt = min(TB, B - t0);
+    // token rows of X read by this tile (clamped: loads are unconditional, surplus tokens are dropped below)
+    int64_t xoff[TB];
 #pragma unroll
-    for (int tt = 0; tt < kTokTile; ++tt)
+    for (int tt = 0; tt < TB; ++tt) xoff[tt] = (int64_t)min(t0 + tt, B - 1) * d + row0;
+    float acc[TB][V];
+#pragma unroll
+    for (int tt = 0; tt < TB; ++tt)
 #pragma unroll
       for (int e = 0; e < V; ++e) acc[tt][e] = 0.f;
     int i = ro;
-    // four row steps at a time: all loads of the batch are issued before the first use
+    // eight row steps at a time: all loads of the batch are issued before the first use
+    for (; i + 7 * rps < rows; i += 8 * rps) {
+      uint4 raw[8];
+      float xv[8][TB];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+#pragma unroll
+      for (int q = 0; q < 8; ++q)
+#pragma unroll
+        for (int tt = 0; tt < TB; ++tt) xv[q][tt] = load_act(p.X, p.xdtype, xoff[tt] + i + q * rps);
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        float u[V];
+        T::widen(raw[q], u);
+#pragma unroll
+        for (int tt = 0; tt < TB; ++tt)
+#pragma unroll
+          for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[e], xv[q][tt], acc[tt][e]);
+      }
+    }
     for (; i + 3 * rps < rows; i += 4 * rps) {
-      float u[4][V], xv[4][kTokTile];
+      uint4 raw[4];
+      float xv[4][TB];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) T::load_vec(U + (int64_t)(i + q * rps) * k, u[q]);
-#pragma unroll
-      for (int q = 0; q < 4; ++q)
-#pragma unroll
-        for (int tt = 0; tt < kTokTile; ++tt)
-          xv[q][tt] = tt < nt ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i + q * rps) : 0.f;
+      for (int q = 0; q < 4; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
 #pragma unroll
       for (int q = 0; q < 4; ++q)
 #pragma unroll
-        for (int tt = 0; tt < kTokTile; ++tt)
+        for (int tt = 0; tt < TB; ++tt) xv[q][tt] = load_act(p.X, p.xdtype, xoff[tt] + i + q * rps);
 #pragma unroll
-          for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[q][e], xv[q][tt], acc[tt][e]);
+      for (int q = 0; q < 4; ++q) {
+        float u[V];
+        T::widen(raw[q], u);
+#pragma unroll
+        for (int tt = 0; tt < TB; ++tt)
+#pragma unroll
+          for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[e], xv[q][tt], acc[tt][e]);
+      }
     }
     for (; i < rows; i += rps) {
       float u[V];
       T::load_vec(U + (int64_t)i * k, u);
 #pragma unroll
-      for (int tt = 0; tt < kTokTile; ++tt) {
-        const float xv = tt < nt ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i) : 0.f;
+      for (int tt = 0; tt < TB; ++tt) {
+        const float xv = load_act(p.X, p.xdtype, xoff[tt] + i);
 #pragma unroll
         for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[e], xv, acc[tt][e]);
       }
     }
+    GSI_MARK(1);
 #pragma unroll
-    for (int tt = 0; tt < kTokTile; ++tt)
+    for (int tt = 0; tt < TB; ++tt)
 #pragma unroll
-      for (int e = 0; e < V; ++e) red[(ro * kTokTile + tt) * cbw + l * V + e] = acc[tt][e];
+      for (int e = 0; e < V; ++e) red[(ro * TB + tt) * cbw + l * V + e] = acc[tt][e];
     __syncthreads();
+    GSI_MARK(2);
     for (int idx = threadIdx.x; idx < nt * cbw; idx += kBlock) {
       const int tt = idx / cbw, j = idx % cbw;
+      const float* rp = red + tt * cbw + j;
+      const int gstride = TB * cbw;
       float s = 0.f;
-      for (int g = 0; g < rps; ++g) s += red[(g * kTokTile + tt) * cbw + j];
+      for (int g = 0; g < rps; g += 8) {  // rps is a multiple of 8: eight LDS reads in flight, fixed order of adds
+        float v[8];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) v[q] = rp[(g + q) * gstride];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) s += v[q];
+      }
       p.part_c[((int64_t)slab * B + t0 + tt) * k + cb * kColBlock + j] = s;
     }
     __syncthreads();
   }
+  GSI_MARK(3);
 }
 
-template <class T>
+template <class T, int TB>
 __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
   constexpr int V = T::kVec;
   constexpr int PF = 4;  // row steps of U held in registers
-  __shared__ __align__(16) float cs[kTokTile][kMaxK];
-  __shared__ float nr[kWaves][kTokTile], nx[kWaves][kTokTile];
+  __shared__ __align__(16) float cs[TB][kMaxK];
+  __shared__ float nr[kWaves][TB], nx[kWaves][TB];
 
   const int ti = find_task(pb.b_begin, pb.n, blockIdx.x);
   const ProjTask& p = pb.t[ti];
@@ -109,37 +153,28 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
   const int d = p.d, k = p.k, B = pb.B;
   const int cpr = k / V;         // 16-byte chunks per row (power of two, <= 64)
   const int rps = kBlock / cpr;  // rows per step
-  const int cc = threadIdx.x % cpr, ro = threadIdx.x / cpr;
+  const int cc = threadIdx.x & (cpr - 1), ro = threadIdx.x >> __builtin_ctz(cpr);
   const int row0 = slab * p.b_rows;
   const int rows = min(p.b_rows, d - row0);
   const int steps = (rows + rps - 1) / rps;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const typename T::storage* U = reinterpret_cast<const typename T::storage*>(p.U) + (int64_t)row0 * k + cc * V;
 
-  // the slab of U goes in flight first ...
+  GSI_MARK(4);
+  // the slab of U goes in flight first (row index clamped: loads are unconditional) ...
   float upf[PF][V];
 #pragma unroll
-  for (int q = 0; q < PF; ++q) {
-    const int i = q * rps + ro;
-    if (i < rows) {
-      T::load_vec(U + (int64_t)i * k, upf[q]);
-    } else {
-#pragma unroll
-      for (int e = 0; e < V; ++e) upf[q][e] = 0.f;
-    }
-  }
+  for (int q = 0; q < PF; ++q) T::load_vec(U + (int64_t)min(q * rps + ro, rows - 1) * k, upf[q]);
 
-  for (int t0 = 0; t0 < B; t0 += kTokTile) {
-    const int nt = min(kTokTile, B - t0);
+  for (int t0 = 0; t0 < B; t0 += TB) {
+    const int nt = min(TB, B - t0);
     // ... with the slab's activations ...
-    float xpf[PF][kTokTile];
+    float xpf[PF][TB];
 #pragma unroll
     for (int q = 0; q < PF; ++q)
 #pragma unroll
-      for (int tt = 0; tt < kTokTile; ++tt) {
-        const int i = q * rps + ro;
-        xpf[q][tt] = (i < rows && tt < nt) ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i) : 0.f;
-      }
+      for (int tt = 0; tt < TB; ++tt)
+        xpf[q][tt] = load_act(p.X, p.xdtype, (int64_t)min(t0 + tt, B - 1) * d + row0 + min(q * rps + ro, rows - 1));
     // ... then the partials: c_j = sum over slabs, slab order fixed
     for (int idx = threadIdx.x; idx < nt * k; idx += kBlock) {
       const int tt = idx / k, j = idx % k;
@@ -158,34 +193,33 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
       cs[tt][j] = s;
       if (slab == 0) p.C[(int64_t)(t0 + tt) * k + j] = s;
     }
+    GSI_MARK(5);
     __syncthreads();
-    float c[kTokTile][V];
+    GSI_MARK(6);
+    float c[TB][V];
 #pragma unroll
-    for (int tt = 0; tt < kTokTile; ++tt)
+    for (int tt = 0; tt < TB; ++tt)
 #pragma unroll
       for (int e = 0; e < V; ++e) c[tt][e] = cs[tt][cc * V + e];
-    float ar[kTokTile], ax[kTokTile];
+    float ar[TB], ax[TB];
 #pragma unroll
-    for (int tt = 0; tt < kTokTile; ++tt) ar[tt] = ax[tt] = 0.f;
+    for (int tt = 0; tt < TB; ++tt) ar[tt] = ax[tt] = 0.f;
     // every lane of a row group walks the same steps, so the cross-lane sums are convergent
-    auto row_step = [&](const float (&u)[V], const float (&xv)[kTokTile], int st) {
+    auto row_step = [&](const float (&u)[V], const float (&xv)[TB], int st) {
       const int i = st * rps + ro;
       const bool live = i < rows;
 #pragma unroll
-      for (int tt = 0; tt < kTokTile; ++tt) {
-        if (tt < nt) {
-          float s = 0.f;
+      for (int tt = 0; tt < TB; ++tt) {
+        float s = 0.f;
 #pragma unroll
-          for (int e = 0; e < V; ++e) s = fmaf(u[e], c[tt][e], s);
-          s = group_sum_rt(s, cpr);
-          if (live && cc == 0) {
-            const int64_t off = (int64_t)(t0 + tt) * d + row0 + i;
-            const float x = xv[tt];
-            const float r = x - s;
-            p.R[off] = r;
-            ar[tt] = fmaf(r, r, ar[tt]);
-            ax[tt] = fmaf(x, x, ax[tt]);
-          }
+        for (int e = 0; e < V; ++e) s = fmaf(u[e], c[tt][e], s);
+        s = group_sum_rt(s, cpr);
+        if (live && cc == 0 && tt < nt) {
+          const float x = xv[tt];
+          const float r = x - s;
+          p.R[(int64_t)(t0 + tt) * d + row0 + i] = r;
+          ar[tt] = fmaf(r, r, ar[tt]);
+          ax[tt] = fmaf(x, x, ax[tt]);
         }
       }
     };
@@ -193,21 +227,16 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
     for (int q = 0; q < PF; ++q)
       if (q < steps) row_step(upf[q], xpf[q], q);
     for (int st = PF; st < steps; ++st) {
-      const int i = st * rps + ro;
-      float u[V], xv[kTokTile];
-      if (i < rows) {
-        T::load_vec(U + (int64_t)i * k, u);
-      } else {
+      const int i = min(st * rps + ro, rows - 1);
+      float u[V], xv[TB];
+      T::load_vec(U + (int64_t)i * k, u);
 #pragma unroll
-        for (int e = 0; e < V; ++e) u[e] = 0.f;
-      }
-#pragma unroll
-      for (int tt = 0; tt < kTokTile; ++tt)
-        xv[tt] = (i < rows && tt < nt) ? load_act(p.X, p.xdtype, (int64_t)(t0 + tt) * d + row0 + i) : 0.f;
+      for (int tt = 0; tt < TB; ++tt) xv[tt] = load_act(p.X, p.xdtype, (int64_t)min(t0 + tt, B - 1) * d + row0 + i);
       row_step(u, xv, st);
     }
+    GSI_MARK(7);
 #pragma unroll
-    for (int tt = 0; tt < kTokTile; ++tt) {
+    for (int tt = 0; tt < TB; ++tt) {
       const float sr = group_sum<kWave>(ar[tt]);
       const float sx = group_sum<kWave>(ax[tt]);
       if (lane == 0) {
@@ -228,6 +257,7 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
     }
     __syncthreads();
   }
+  GSI_MARK(8);
 }
 
 // |r_t|, |x_t| (and the gate): one workgroup per input; each wave takes tokens w, w + 4, ... of a
@@ -302,7 +332,7 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
   g.a_rows = (int)(ceil_div(ceil_div(d, kPartSlabs), rps_a) * rps_a);
   g.a_slabs = (int)ceil_div(d, g.a_rows);
   const int rps_b = kBlock / (int)(k / V);
-  int64_t br = ceil_div(d, kMaxResSlabs);
+  int64_t br = ceil_div(d, kMaxResSlabs);  // four row steps per workgroup unless that needs too many slabs
   if (br < 4 * rps_b) br = 4 * rps_b;
   g.b_rows = (int)(ceil_div(br, rps_b) * rps_b);
   g.b_slabs = (int)ceil_div(d, g.b_rows);
@@ -336,11 +366,21 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
   }
   if (ta == 0 || pb.B == 0) return hipSuccess;
   if (udtype == GSI_BF16) {
-    proj_partial<BF16><<<ta, kBlock, 0, s>>>(pb);
-    proj_residual<BF16><<<tb, kBlock, 0, s>>>(pb);
+    if (pb.B == 1) {
+      proj_partial<BF16, 1><<<ta, kBlock, 0, s>>>(pb);
+      proj_residual<BF16, 1><<<tb, kBlock, 0, s>>>(pb);
+    } else {
+      proj_partial<BF16, kTokTile><<<ta, kBlock, 0, s>>>(pb);
+      proj_residual<BF16, kTokTile><<<tb, kBlock, 0, s>>>(pb);
+    }
   } else {
-    proj_partial<F32><<<ta, kBlock, 0, s>>>(pb);
-    proj_residual<F32><<<tb, kBlock, 0, s>>>(pb);
+    if (pb.B == 1) {
+      proj_partial<F32, 1><<<ta, kBlock, 0, s>>>(pb);
+      proj_residual<F32, 1><<<tb, kBlock, 0, s>>>(pb);
+    } else {
+      proj_partial<F32, kTokTile><<<ta, kBlock, 0, s>>>(pb);
+      proj_residual<F32, kTokTile><<<tb, kBlock, 0, s>>>(pb);
+    }
   }
   if (with_norms) proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
   return hipGetLastError();

@@ -20,6 +20,11 @@
 #include "gsi_decode.h"
 #include "gsi_device.h"
 
+// Phase markers: empty in the library; a profiling build may define GSI_MARK(i) to record a timestamp.
+#ifndef GSI_MARK
+#define GSI_MARK(i)
+#endif
+
 namespace gsi {
 namespace {
 
@@ -66,127 +71,170 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   using S = typename T::storage;
   extern __shared__ __align__(16) float smem[];  // [coefficients of every group][one activation vector]
 
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);  // wave-uniform by construction
   const int gw = blockIdx.x * kWaves + wave;  // this wave's index in the grid
   const int GW = gridDim.x * kWaves;
   const int ng = lb.ng, n = lb.n;
+  GSI_MARK(0);
 
-  // ---- 1. gates --------------------------------------------------------------------------------
-  unsigned fired_mask = 0;
-  if constexpr (DENSE) {
-    fired_mask = (1u << ng) - 1u;
-  } else if (lb.inline_gate) {
-    // all partial-norm loads of all groups go in flight together (clamped, masked by selects)
-    float ar[kMaxTasks], ax[kMaxTasks];
-#pragma unroll
-    for (int gi = 0; gi < kMaxTasks; ++gi) {
-      const LinGroup& g = lb.g[gi < ng ? gi : ng - 1];
-      const float2* pn = reinterpret_cast<const float2*>(g.part_n);
-      const int ns = g.b_slabs;
-      float2 v[kMaxResSlabs / kWave];
-#pragma unroll
-      for (int q = 0; q < kMaxResSlabs / kWave; ++q) {
-        const int s = lane + q * kWave;
-        v[q] = pn[s < ns ? s : ns - 1];
-      }
-      ar[gi] = 0.f;
-      ax[gi] = 0.f;
-#pragma unroll
-      for (int q = 0; q < kMaxResSlabs / kWave; ++q) {
-        const bool ok = lane + q * kWave < ns;
-        ar[gi] += ok ? v[q].x : 0.f;
-        ax[gi] += ok ? v[q].y : 0.f;
-      }
-    }
-#pragma unroll
-    for (int gi = 0; gi < kMaxTasks; ++gi) {
-      const float rn = sqrtf(group_sum<kWave>(ar[gi])), xn = sqrtf(group_sum<kWave>(ax[gi]));
-      const bool f = gi < ng && gate_fires(rn, xn, lb.eps);
-      if (f) fired_mask |= 1u << gi;
-      if (gi < ng && blockIdx.x == 0 && threadIdx.x == 0) {  // publish what the norm and gate kernels would write
-        const LinGroup& g = lb.g[gi];
-        g.rnorm[0] = rn;
-        g.xnorm[0] = xn;
-        g.mask[0] = f ? 1 : 0;
-        if (f) g.fired_idx_out[0] = 0;
-        g.n_fired_out[0] = f ? 1 : 0;
-      }
-    }
-  } else {
-    int nf[kMaxTasks];
-#pragma unroll
-    for (int gi = 0; gi < kMaxTasks; ++gi) nf[gi] = lb.g[gi < ng ? gi : ng - 1].n_fired[0];
-#pragma unroll
-    for (int gi = 0; gi < kMaxTasks; ++gi)
-      if (gi < ng && nf[gi] > 0) fired_mask |= 1u << gi;
-  }
-
-  // ---- 2. coefficients of every group into LDS ------------------------------------------------------
+  // ---- 0. the first two image-row items of this wave go in flight before anything else ------------
+  // (they do not depend on the gate; an item of a map that turns out to have fired is dropped)
+  struct Item {
+    const S* base;  // this lane's chunk in row 0 of the task's image
+    float* y;
+    int row0, rpw, lpr, m, k, coff, group, live;
+  };
   auto coff = [&](int gi) {
     int o = 0;
     for (int i = 0; i < gi; ++i) o += lb.g[i].k;
     return o;
   };
+  const int total_items = DENSE ? 0 : lb.short_begin[n];
+  auto locate = [&](int v) {
+    Item it;
+    it.live = v < total_items;
+    v = it.live ? v : total_items - 1;
+    int ti = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxTasks; ++i)
+      if (i < n && v >= lb.short_begin[i]) ti = i;
+    const LinTask& t = lb.t[ti];
+    it.group = t.group;
+    it.k = lb.g[t.group].k;
+    it.m = t.m;
+    const int chunks = it.k / V;
+    const int lsh = chunks <= 1 ? 0 : 32 - __builtin_clz(chunks - 1);
+    it.lpr = 1 << lsh;  // lanes per row: smallest power of two >= chunks
+    it.rpw = kWave >> lsh;
+    it.row0 = (v - lb.short_begin[ti]) * kSU * it.rpw + (lane >> lsh);
+    const int l = lane & (it.lpr - 1);
+    const int col = l * V < it.k ? l * V : it.k - V;
+    it.live = it.live && (l * V < it.k);
+    it.base = reinterpret_cast<const S*>(t.M) + col;
+    it.y = t.Y;
+    it.coff = coff(t.group) + col;
+    return it;
+  };
+  auto issue = [&](const Item& it, Raw<T> (&buf)[kSU]) {
+#pragma unroll
+    for (int u = 0; u < kSU; ++u) {
+      const int row = it.row0 + u * it.rpw;
+      buf[u].load(it.base + (int64_t)(row < it.m ? row : it.m - 1) * it.k);
+    }
+  };
+  auto consume = [&](const Item& it, const Raw<T> (&buf)[kSU], unsigned fired) {
+    float cvv[V];
+    lds_vec<V>(smem + it.coff, cvv);
+    const bool live = it.live && !((fired >> it.group) & 1u);
+    const bool head = (lane & (it.lpr - 1)) == 0;
+#pragma unroll
+    for (int u = 0; u < kSU; ++u) {
+      float w[V];
+      buf[u].widen(w);
+      float s = live ? dotv<V>(w, cvv, 0.f) : 0.f;
+      s = group_sum_rt(s, it.lpr);
+      const int row = it.row0 + u * it.rpw;
+      if (live && head && row < it.m) it.y[row] = s;
+    }
+  };
+  Raw<T> bufA[kSU], bufB[kSU];
+  Item itA, itB;
+  if constexpr (!DENSE) {
+    if (total_items > 0) {
+      itA = locate(gw);
+      itB = locate(gw + GW);
+      issue(itA, bufA);
+      issue(itB, bufB);
+    }
+  }
+
+  GSI_MARK(1);
+  // ---- 1. gates: one wave per group in every workgroup (identical arithmetic in every workgroup, hence
+  //         the same decision across the grid without communication) -----------------------------------
+  __shared__ unsigned s_fired_g[kMaxTasks];
+  if constexpr (!DENSE) {
+    for (int gi = wave; gi < ng; gi += kWaves) {  // wave gi evaluates the gate of group gi
+      const LinGroup& g = lb.g[gi];
+      bool f;
+      if (lb.inline_gate) {
+        const float2* pn = reinterpret_cast<const float2*>(g.part_n);
+        const int ns = g.b_slabs;
+        float2 v[kMaxResSlabs / kWave];
+#pragma unroll
+        for (int q = 0; q < kMaxResSlabs / kWave; ++q) {  // clamped: the loads are unconditional
+          const int sl = lane + q * kWave;
+          v[q] = pn[sl < ns ? sl : ns - 1];
+        }
+        float ar = 0.f, ax = 0.f;
+#pragma unroll
+        for (int q = 0; q < kMaxResSlabs / kWave; ++q) {
+          const bool ok = lane + q * kWave < ns;
+          ar += ok ? v[q].x : 0.f;
+          ax += ok ? v[q].y : 0.f;
+        }
+        const float rn = sqrtf(group_sum<kWave>(ar)), xn = sqrtf(group_sum<kWave>(ax));
+        f = gate_fires(rn, xn, lb.eps);
+        if (blockIdx.x == 0 && lane == 0) {  // publish what the norm and gate kernels would write
+          g.rnorm[0] = rn;
+          g.xnorm[0] = xn;
+          g.mask[0] = f ? 1 : 0;
+          if (f) g.fired_idx_out[0] = 0;
+          g.n_fired_out[0] = f ? 1 : 0;
+        }
+      } else {
+        f = g.n_fired[0] > 0;
+      }
+      if (lane == 0) s_fired_g[gi] = f ? 1u : 0u;
+    }
+  }
+
+  GSI_MARK(2);
+  // ---- 2. coefficients of every group into LDS: the last waves of the workgroup stage them while the
+  //         first ones evaluate the gates (group gi is staged by wave kWaves - 1 - gi) -----------------
   int sumk = 0;
   if constexpr (!DENSE) {
-    float4 cv[kMaxTasks];
-#pragma unroll
-    for (int gi = 0; gi < kMaxTasks; ++gi) {  // k <= 512: at most one float4 per thread and group
-      const LinGroup& g = lb.g[gi < ng ? gi : ng - 1];
-      const int i4 = threadIdx.x * 4;
-      cv[gi] = *reinterpret_cast<const float4*>(g.C + (i4 < g.k ? i4 : g.k - 4));
+    for (int gi = 0; gi < ng; ++gi) sumk += lb.g[gi].k;
+    for (int gi = kWaves - 1 - wave; gi < ng; gi += kWaves) {
+      const LinGroup& g = lb.g[gi];
+      const int k = g.k;  // <= 512: at most two float4 per lane
+      float* dst = smem + coff(gi);
+      const int i0 = lane * 4, i1 = lane * 4 + kWave * 4;
+      const float4 a = *reinterpret_cast<const float4*>(g.C + (i0 < k ? i0 : k - 4));
+      const float4 b2 = *reinterpret_cast<const float4*>(g.C + (i1 < k ? i1 : k - 4));
+      if (i0 < k) *reinterpret_cast<float4*>(dst + i0) = a;
+      if (i1 < k) *reinterpret_cast<float4*>(dst + i1) = b2;
     }
-#pragma unroll
-    for (int gi = 0; gi < kMaxTasks; ++gi) {
-      if (gi < ng) {
-        const int k = lb.g[gi].k;
-        if (threadIdx.x * 4 < k) *reinterpret_cast<float4*>(smem + sumk + threadIdx.x * 4) = cv[gi];
-        sumk += k;
-      }
-    }
-    __syncthreads();
+  }
+  GSI_MARK(3);
+  __syncthreads();
+  GSI_MARK(4);
+  unsigned fired_mask = 0;
+  if constexpr (DENSE) {
+    fired_mask = (1u << ng) - 1u;
+  } else {
+    for (int gi = 0; gi < ng; ++gi) fired_mask |= s_fired_g[gi] << gi;
+    fired_mask = __builtin_amdgcn_readfirstlane(fired_mask);
   }
   float* xs = smem + sumk;
 
   // ---- 3. short phase: image rows of maps whose input did not fire --------------------------------------
   if constexpr (!DENSE) {
-    const int total = lb.short_begin[n];
-    for (int v = gw; v < total; v += GW) {
-      int ti = 0;
-#pragma unroll
-      for (int i = 1; i < kMaxTasks; ++i)
-        if (i < n && v >= lb.short_begin[i]) ti = i;
-      const LinTask& t = lb.t[ti];
-      if ((fired_mask >> t.group) & 1u) continue;  // uniform in the wave
-      const int k = lb.g[t.group].k, m = t.m;
-      const int chunks = k / V;
-      const int lpr = chunks <= 1 ? 1 : 1 << (32 - __builtin_clz(chunks - 1));  // lanes per row
-      const int rpw = kWave / lpr;
-      const int l = lane % lpr;
-      const int col = l * V < k ? l * V : k - V;
-      const int row0 = (v - lb.short_begin[ti]) * kSU * rpw + lane / lpr;
-      const S* base = reinterpret_cast<const S*>(t.M) + col;
-      Raw<T> buf[kSU];
-#pragma unroll
-      for (int u = 0; u < kSU; ++u) {
-        const int row = row0 + u * rpw;
-        buf[u].load(base + (int64_t)(row < m ? row : m - 1) * k);
-      }
-      float cvv[V];
-      lds_vec<V>(smem + coff(t.group) + col, cvv);
-      const bool live = l * V < k;
-#pragma unroll
-      for (int u = 0; u < kSU; ++u) {
-        float w[V];
-        buf[u].widen(w);
-        float s = live ? dotv<V>(w, cvv, 0.f) : 0.f;
-        s = group_sum_rt(s, lpr);
-        const int row = row0 + u * rpw;
-        if (l == 0 && row < m) t.Y[row] = s;
+    if (total_items > 0) {
+      consume(itA, bufA, fired_mask);
+      consume(itB, bufB, fired_mask);
+      for (int v = gw + 2 * GW; v < total_items; v += 2 * GW) {  // only when the grid is small for the maps
+        itA = locate(v);
+        itB = locate(v + GW);
+        issue(itA, bufA);
+        issue(itB, bufB);
+        consume(itA, bufA, fired_mask);
+        consume(itB, bufB, fired_mask);
       }
     }
   }
 
+  GSI_MARK(5);
   // ---- 4. long phase: rows of W of fired maps (every map in the dense baseline) ------------------------
   for (int gi = 0; gi < ng; ++gi) {
     if (!((fired_mask >> gi) & 1u)) continue;  // uniform across the grid
@@ -276,6 +324,7 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
       first = (first - m % GW + GW) % GW;
     }
   }
+  GSI_MARK(6);
 }
 
 int env_int(const char* name, int dflt) {
