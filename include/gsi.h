@@ -127,11 +127,12 @@ typedef struct gsi_map_desc {
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream);
 
-/* Instrumented variant for measurements: identical to gsi_layer_stack, and in addition records the
- * HIP events ev_linear_begin / ev_linear_end (hipEvent_t passed as void*, created by the caller with
- * timing enabled) on `stream` immediately before and after the launch of the linear-map kernels of
- * every scheduling wave, so that the caller can read that kernel's duration with
- * hipEventElapsedTime.  With chained inputs the events bracket the last wave. */
+/* Instrumented variant for measurements: identical to gsi_layer_stack; in addition the two HIP events
+ * (hipEvent_t passed as void*, created by the caller with timing enabled) take the start and stop
+ * timestamps of the dispatch of the single-token linear-map kernel (the launch that evaluates every
+ * map of the call for B == 1), so hipEventElapsedTime(begin, end) is that kernel's execution time as
+ * a profiler reports it.  If the maps of a call need several such launches the events time the last
+ * one; for B != 1 the events are not recorded. */
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                           int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
                           void* ev_linear_end);

@@ -274,6 +274,7 @@ struct LinBatcher {
   int wdtype;
   hipStream_t s;
   int64_t B;
+  hipEvent_t e0 = nullptr, e1 = nullptr;  // optional dispatch-timestamp events for the launches of this batcher
   void reset(int64_t B_, int dense, int inline_gate, float eps) {
     B = B_;
     clear(lb, B_);
@@ -281,7 +282,7 @@ struct LinBatcher {
   }
   hipError_t flush() {
     if (lb.n == 0) return hipSuccess;
-    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s);
+    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s, e0, e1);
     const int dense = lb.dense, ig = lb.inline_gate;
     const float eps = lb.eps;
     reset(B, dense, ig, eps);
@@ -508,12 +509,11 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     std::vector<int> mready;
     for (int j = 0; j < n_maps; ++j)
       if (!map_done[j] && in_done[maps[j].input_id] == 1) mready.push_back(j);
-    if (ev_begin && !mready.empty())
-      if (hipError_t e = hipEventRecord(ev_begin, s); e != hipSuccess) return hip_fail(e, fn);
     for (int ig = 1; ig >= 0; --ig) {
       for (int dt = 0; dt < 2; ++dt) {
         LinBatcher bt;
         bt.wdtype = dt; bt.s = s;
+        bt.e0 = ev_begin; bt.e1 = ev_end;
         bt.reset(B, 0, ig, eps);
         for (int j : mready) {
           const gsi_map_desc& mp = maps[j];
@@ -551,8 +551,6 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       --remaining;
       ++progressed;
     }
-    if (ev_end && !mready.empty())
-      if (hipError_t e = hipEventRecord(ev_end, s); e != hipSuccess) return hip_fail(e, fn);
     if (!progressed) return fail(GSI_ERR_SHAPE, "%s: src_map dependencies form a cycle", fn);
   }
   return GSI_OK;

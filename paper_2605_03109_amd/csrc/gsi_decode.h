@@ -91,10 +91,13 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
                                  hipStream_t s);
 // can a set of tasks share one single-token launch (LDS budget)?
 bool decode_linear_fits(const LinBatch& lb);
-hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s);
+// e0 / e1 (optional): events that take the start / stop timestamps of the single-token kernel's dispatch
+hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0 = nullptr,
+                                hipEvent_t e1 = nullptr);
 
 // single-token persistent kernel (gsi_stream.hip)
 size_t stream_smem_bytes(const LinBatch& lb);
-hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s);
+hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0 = nullptr,
+                              hipEvent_t e1 = nullptr);
 
 }  // namespace gsi

@@ -208,9 +208,9 @@ bool decode_linear_fits(const LinBatch& lb) {
   return tile_smem(lb) <= (size_t)kMaxLinD * sizeof(float);
 }
 
-hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s) {
+hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   if (lb.n == 0 || lb.B == 0) return hipSuccess;
-  if (lb.B == 1) return stream_rows_launch(lb, wdtype, s);
+  if (lb.B == 1) return stream_rows_launch(lb, wdtype, s, e0, e1);
   int total = 0;
   for (int i = 0; i < lb.n; ++i) {
     lb.blk_begin[i] = total;

@@ -15,6 +15,8 @@
 // buffers, all loads unconditional with clamped addresses) so that a wave always has loads in flight.
 // Every output element is written exactly once, by one lane.  A map whose input did not fire never
 // issues a load from W.
+#include <hip/hip_ext.h>
+
 #include <cstdlib>
 
 #include "gsi_decode.h"
@@ -345,19 +347,25 @@ int num_cus() {
 }
 
 template <class T, bool DENSE, bool TAIL>
-hipError_t launch_one(const LinBatch& lb, unsigned grid, size_t smem, hipStream_t s) {
+hipError_t launch_one(const LinBatch& lb, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   static const hipError_t attr =  // the kernel may use more than the default 64 KB of dynamic LDS
       hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<T, DENSE, TAIL>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (kMaxLinD + kMaxSumK) * (int)sizeof(float));
   if (attr != hipSuccess) return attr;
-  stream_rows<T, DENSE, TAIL><<<grid, kBlock, smem, s>>>(lb);
+  if (e0 && e1) {  // the events take the dispatch's own start and stop timestamps
+    hipExtLaunchKernelGGL((stream_rows<T, DENSE, TAIL>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, lb);
+  } else {
+    stream_rows<T, DENSE, TAIL><<<grid, kBlock, smem, s>>>(lb);
+  }
   return hipGetLastError();
 }
 
 template <class T>
-hipError_t launch_dtype(const LinBatch& lb, bool tail, unsigned grid, size_t smem, hipStream_t s) {
-  if (lb.dense) return tail ? launch_one<T, true, true>(lb, grid, smem, s) : launch_one<T, true, false>(lb, grid, smem, s);
-  return tail ? launch_one<T, false, true>(lb, grid, smem, s) : launch_one<T, false, false>(lb, grid, smem, s);
+hipError_t launch_dtype(const LinBatch& lb, bool tail, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0,
+                        hipEvent_t e1) {
+  if (lb.dense)
+    return tail ? launch_one<T, true, true>(lb, grid, smem, s, e0, e1) : launch_one<T, true, false>(lb, grid, smem, s, e0, e1);
+  return tail ? launch_one<T, false, true>(lb, grid, smem, s, e0, e1) : launch_one<T, false, false>(lb, grid, smem, s, e0, e1);
 }
 
 }  // namespace
@@ -371,7 +379,7 @@ size_t stream_smem_bytes(const LinBatch& lb) {
   return (sumk + maxd) * sizeof(float);
 }
 
-hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s) {
+hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   // persistent grid: a few workgroups per CU, never more waves than rows
   static const int per_cu = env_int("GSI_LIN_WGS_PER_CU", 2);
@@ -395,8 +403,8 @@ hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s) {
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
   const size_t smem = stream_smem_bytes(lb);
-  return wdtype == GSI_BF16 ? launch_dtype<BF16>(lb, tail, (unsigned)grid, smem, s)
-                            : launch_dtype<F32>(lb, tail, (unsigned)grid, smem, s);
+  return wdtype == GSI_BF16 ? launch_dtype<BF16>(lb, tail, (unsigned)grid, smem, s, e0, e1)
+                            : launch_dtype<F32>(lb, tail, (unsigned)grid, smem, s, e0, e1);
 }
 
 }  // namespace gsi

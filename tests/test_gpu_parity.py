@@ -269,3 +269,91 @@ def test_workspace_too_small_is_an_error_not_a_crash(gsi):
     with pytest.raises(gsi.GsiError) as ei:
         gsi.project(U, X, ws=small)
     assert ei.value.code == gsi.GSI_ERR_WORKSPACE
+
+
+# ------------------------------------------------------------------------------------------------
+# full-size GPT-J-shaped block in the launch configuration the benchmark times:
+# one gsi_layer_stack call per decode token (B = 1), four inputs, six maps, k = 256, bf16
+# ------------------------------------------------------------------------------------------------
+def test_gptj_block_full_size_decode(gsi, pu):
+    T = 6
+    w = wl.gptj_block(T=T, k=256, fire_rate=0.34)  # 2 of 6 tokens fire per input (seeded positions)
+    say(f"case {w.name}: T={T} k=256, full shapes")
+    dgs, inputs, maps, names = _stack_for(gsi, pu, w, 1)
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X} for dg in dgs], maps, T, w.eps)
+    for t in range(T):
+        st.refresh(token_offset=t, B=1)
+        st.run()
+    torch.cuda.synchronize()
+    n_fired_total = 0
+    for gi, (g, dg) in enumerate(zip(w.groups, dgs)):
+        say(f"  input {g.name}: d={g.d}")
+        og = pu.OracleGroup(w, g)
+        ref = og.run()
+        n_fired_total += ref["n"]
+        ti = st.inputs_t[gi]
+        mask_dev = ti["mask"].cpu().numpy()
+        res = dict(C=ti["C"], R=ti["R"], rnorm=ti["rnorm"], xnorm=ti["xnorm"], mask=ti["mask"],
+                   n_fired=torch.tensor([int(mask_dev.sum())], dtype=torch.int32),
+                   fired_idx=torch.from_numpy(np.nonzero(mask_dev)[0].astype(np.int32)))
+        mask = pu.check_projection(res, ref, w.eps)
+        assert np.array_equal(mask.astype(bool), g.fired_design)
+        for j, (g2, name) in enumerate(names):
+            if g2 != gi:
+                continue
+            pu.check_image(gsi.bits_of(dg.M[name]), og.M[name], og.W[name], og.U, w.wdtype)
+            e, es = pu.check_outputs(st.maps_t[j]["Y"], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype,
+                                     ref, mask)
+            say(f"    map {name}: rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
+        del og
+    assert n_fired_total == 8
+    # the dense baseline the benchmark divides by: same descriptors, y = W x
+    st.refresh(token_offset=0, B=1)
+    st.run_dense()
+    torch.cuda.synchronize()
+    for j, (gi, name) in enumerate(names):
+        g = w.groups[gi]
+        W64 = O.widen(dict((n, W) for n, _, W in g.maps)[name], w.wdtype)
+        yd = O.dense_linear(W64, O.widen(g.X[:1], w.xdtype))
+        y = st.maps_t[j]["Y"][:1].cpu().numpy().astype(np.float64)
+        assert pu.rel_l2_rows(y, yd).max() <= 2e-5, name
+
+
+def test_timed_stack_and_dense_stack_match_plain_calls(gsi, pu):
+    """gsi_layer_stack_timed == gsi_layer_stack bit for bit; gsi_dense_stack == gsi_dense_linear per map."""
+    import ctypes as ct
+
+    w = wl.transformer_block("blk", d=512, ffn=2048, k=64, T=3, fire_rate=0.34, p=1.5, seed=79)
+    dgs, inputs, maps, names = _stack_for(gsi, pu, w, 1)
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X} for dg in dgs], maps, w.T, w.eps)
+    hip = ct.CDLL("libamdhip64.so")
+    hip.hipEventCreate.argtypes = [ct.POINTER(ct.c_void_p)]
+    hip.hipEventElapsedTime.argtypes = [ct.POINTER(ct.c_float), ct.c_void_p, ct.c_void_p]
+    e0, e1 = ct.c_void_p(), ct.c_void_p()
+    assert hip.hipEventCreate(ct.byref(e0)) == 0 and hip.hipEventCreate(ct.byref(e1)) == 0
+    for t in range(w.T):
+        st.refresh(token_offset=t, B=1)
+        st.run()
+    torch.cuda.synchronize()
+    plain = [m["Y"].clone() for m in st.maps_t]
+    plain_c = [i["C"].clone() for i in st.inputs_t]
+    for m in st.maps_t:
+        m["Y"].zero_()
+    for t in range(w.T):
+        st.refresh(token_offset=t, B=1)
+        st.run_timed(e0, e1)
+    torch.cuda.synchronize()
+    ms = ct.c_float()
+    assert hip.hipEventElapsedTime(ct.byref(ms), e0, e1) == 0 and 0.0 < ms.value < 50.0
+    for a, m in zip(plain, st.maps_t):
+        assert torch.equal(a, m["Y"])
+    for a, i in zip(plain_c, st.inputs_t):
+        assert torch.equal(a, i["C"])
+    # dense stack, one token and a batch
+    for B in (1, 3):
+        st.refresh(token_offset=0, B=B)
+        st.run_dense()
+        torch.cuda.synchronize()
+        for j, (gi, name) in enumerate(names):
+            Yd = gsi.dense_linear(dgs[gi].W[name], dgs[gi].X[:B].contiguous())
+            assert torch.equal(st.maps_t[j]["Y"][:B], Yd), (B, name)
