@@ -8,6 +8,7 @@
 
 #include "gsi_decode.h"
 #include "gsi_internal.h"
+#include "gsi_mfma.h"
 
 namespace {
 
@@ -66,13 +67,26 @@ const char* gsi_last_error(void) { return g_err; }
 
 int gsi_version(void) { return 100; }
 
+// ---- eligibility of the matrix-core paths (bf16 operands, K dimensions multiples of 32) -----------------
+static bool mfma_image_ok(int64_t m, int64_t d, int64_t k) { return d % 32 == 0 && m < (1ll << 30) && k < (1ll << 30); }
+static bool mfma_batch_ok(int64_t d, int64_t k, int64_t B) {
+  return B > kDecodeMaxB && d % 32 == 0 && k % 32 == 0 && B < (1ll << 30);
+}
+static size_t mfma_project_ws(int64_t d, int64_t k, int64_t B) {
+  return gsi::align_up((size_t)k * d * 2, 256) + gsi::align_up((size_t)gsi::mfma_res_tiles(d) * B * 2 * 4, 256);
+}
+
 size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int64_t B) {
-  (void)m;
   switch (which_call) {
+    case GSI_CALL_BUILD_IMAGE:
+      // the transposed basis of the matrix-core build (bf16 operands); generic kernels need none
+      if (m < 1 || d < 1 || k < 1 || k > d || !mfma_image_ok(m, d, k)) return 0;
+      return gsi::align_up((size_t)k * d * 2, 256);
     case GSI_CALL_PROJECT: {
+      if (d < 1 || k < 1 || k > d || B < 1) return 0;
+      if (B > kDecodeMaxB) return mfma_batch_ok(d, k, B) ? mfma_project_ws(d, k, B) : 0;
       // the slab partials of the vector projection kernels; sized for the wider of the two dtypes so
       // that the query does not depend on the dtype (generic kernels need none)
-      if (d < 1 || k < 1 || k > d || B < 1 || B > kDecodeMaxB) return 0;
       size_t need = 0;
       for (int dt = 0; dt < 2; ++dt) {
         if (!gsi::decode_project_ok(d, k, dt, nullptr)) continue;
@@ -100,7 +114,22 @@ int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d,
   if (int rc = check_ws("gsi_build_image", ws, ws_bytes, gsi_workspace_bytes(GSI_CALL_BUILD_IMAGE, m, d, k, 0)))
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
-  hipError_t e = gsi::generic_build_image(W, U, M, m, d, k, wdtype, s);
+  hipError_t e;
+  if (wdtype == GSI_BF16 && mfma_image_ok(m, d, k) && aligned(W, 16) && aligned(U, 2) && aligned(M, 2)) {
+    // matrix cores: M = W (U^T)^T with the basis transposed once into the workspace
+    e = gsi::mfma_transpose_bf16(U, ws, (int)d, (int)k, s);
+    if (e == hipSuccess) {
+      gsi::GemmArgs g;
+      std::memset(&g, 0, sizeof(g));
+      g.A = W; g.lda = d; g.a_f32 = 0;
+      g.B = ws; g.ldb = d;
+      g.D = M; g.ldd = k;
+      g.M = (int)m; g.N = (int)k; g.K = (int)d;
+      e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_BF16, s);
+    }
+  } else {
+    e = gsi::generic_build_image(W, U, M, m, d, k, wdtype, s);
+  }
   if (e != hipSuccess) return hip_fail(e, "gsi_build_image");
   return GSI_OK;
 }
@@ -163,6 +192,75 @@ static void fill_proj_task(gsi::ProjTask& t, const void* U, const void* X, int64
   gsi::decode_project_fill(t, d, k, B, ws);
 }
 
+// Prefill-sized projection on the matrix cores: C = X U, R = X - C U^T with per-tile partial norms, then
+// the norm (+ gate) kernel.  `gate` may be null (norms only).
+static hipError_t mfma_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int xdtype, float* C,
+                               float* R, float* rnorm, float* xnorm, uint8_t* mask, int32_t* fired_idx,
+                               int32_t* n_fired, bool with_gate, float eps, void* ws, hipStream_t s) {
+  void* Ut = ws;
+  float* part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + gsi::align_up((size_t)k * d * 2, 256));
+  hipError_t e = gsi::mfma_transpose_bf16(U, Ut, (int)d, (int)k, s);
+  if (e != hipSuccess) return e;
+  gsi::GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = X; g.lda = d; g.a_f32 = xdtype == GSI_F32;
+  g.B = Ut; g.ldb = d;
+  g.D = C; g.ldd = k;
+  g.M = (int)B; g.N = (int)k; g.K = (int)d;
+  e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
+  if (e != hipSuccess) return e;
+  std::memset(&g, 0, sizeof(g));
+  g.A = C; g.lda = k; g.a_f32 = 1;
+  g.B = U; g.ldb = k;
+  g.D = R; g.ldd = d;
+  g.M = (int)B; g.N = (int)d; g.K = (int)k;
+  g.X = X; g.xdtype = xdtype; g.ldx = d; g.part_n = part_n; g.part_tokens = (int)B;
+  e = gsi::mfma_gemm_nt(g, gsi::EPI_RESIDUAL, s);
+  if (e != hipSuccess) return e;
+  gsi::ProjBatch pb;
+  std::memset(&pb, 0, sizeof(pb));
+  pb.n = 1;
+  pb.B = (int)B;
+  pb.t[0].part_n = part_n; pb.t[0].b_slabs = gsi::mfma_res_tiles(d);
+  pb.t[0].rnorm = rnorm; pb.t[0].xnorm = xnorm;
+  pb.t[0].mask = mask; pb.t[0].fired_idx = fired_idx; pb.t[0].n_fired = n_fired;
+  return gsi::decode_norms_launch(pb, with_gate, eps, s);
+}
+
+static bool mfma_project_path(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype,
+                              const float* C, const float* R) {
+  return udtype == GSI_BF16 && mfma_batch_ok(d, k, B) && aligned(U, 16) && aligned(X, 16) && aligned(C, 16) &&
+         aligned(R, 4) && (xdtype == GSI_F32 || xdtype == GSI_BF16);
+}
+
+// Prefill-sized gated map on the matrix cores: Y = C M^T for every token, then Y[fired] += R[fired] W^T
+// over the compacted list (row tiles beyond the device-side count exit at once).
+static hipError_t mfma_gated(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
+                             const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, float* Y,
+                             hipStream_t s) {
+  gsi::GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = C; g.lda = k; g.a_f32 = 1;
+  g.B = M; g.ldb = k;
+  g.D = Y; g.ldd = m;
+  g.M = (int)B; g.N = (int)m; g.K = (int)k;
+  hipError_t e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
+  if (e != hipSuccess) return e;
+  std::memset(&g, 0, sizeof(g));
+  g.A = R; g.lda = d; g.a_f32 = 1;
+  g.B = W; g.ldb = d;
+  g.D = Y; g.ldd = m;
+  g.M = (int)B; g.N = (int)m; g.K = (int)d;
+  g.row_idx = fired_idx; g.n_rows_dev = n_fired;
+  return gsi::mfma_gemm_nt(g, gsi::EPI_SCATTER_ADD, s);
+}
+
+static bool mfma_gated_path(const void* W, const void* M, const float* C, const float* R, int64_t d, int64_t k,
+                            int64_t B, int wdtype) {
+  return wdtype == GSI_BF16 && mfma_batch_ok(d, k, B) && aligned(W, 16) && aligned(M, 16) && aligned(C, 16) &&
+         aligned(R, 16);
+}
+
 static void clear(gsi::LinBatch& lb, int64_t B) {
   std::memset(&lb, 0, sizeof(lb));
   lb.B = (int)B;
@@ -182,6 +280,8 @@ int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, i
     pb.B = (int)B;
     fill_proj_task(pb.t[0], U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, ws);
     e = gsi::decode_project_launch(pb, udtype, true, false, 0.f, s);
+  } else if (mfma_project_path(U, X, d, k, B, udtype, xdtype, C, R)) {
+    e = mfma_project(U, X, d, k, B, xdtype, C, R, rnorm, xnorm, nullptr, nullptr, nullptr, false, 0.f, ws, s);
   } else {
     e = gsi::generic_project(U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm, s);
   }
@@ -208,7 +308,8 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (gsi::decode_linear_ok(m, d, k, wdtype, W, M) && aligned(C, 16) && aligned(R, 16)) {
+  if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype) && gsi::decode_linear_ok(m, d, k, wdtype, W, M) &&
+      aligned(C, 16) && aligned(R, 16)) {
     gsi::LinBatch lb;
     clear(lb, B);
     lb.n = lb.ng = 1;
@@ -216,6 +317,8 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     lb.g[0].d = (int)d; lb.g[0].k = (int)k;
     lb.t[0].W = W; lb.t[0].M = M; lb.t[0].Y = (float*)Y; lb.t[0].m = (int)m; lb.t[0].group = 0;
     e = gsi::decode_linear_launch(lb, wdtype, s);
+  } else if (mfma_gated_path(W, M, C, R, d, k, B, wdtype)) {
+    e = mfma_gated(W, M, C, R, fired_idx, n_fired, m, d, k, B, (float*)Y, s);
   } else {
     e = gsi::generic_gated_linear(W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, (float*)Y, s);
   }
@@ -493,13 +596,19 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     for (int i : ready) {
       const gsi_input_desc& in = inputs[i];
       if (mode[i] == kGeneric) {
-        if (B > 0) {
-          hipError_t e = gsi::generic_project(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
-                                              in.xnorm, s);
+        if (B > 0 && mfma_project_path(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R)) {
+          hipError_t e = mfma_project(in.U, in.X, in.d, in.k, B, in.xdtype, in.C, in.R, in.rnorm, in.xnorm, in.mask,
+                                      in.fired_idx, in.n_fired, true, eps, reinterpret_cast<char*>(ws) + ws_off[i], s);
+          if (e != hipSuccess) return hip_fail(e, fn);
+        } else {
+          if (B > 0) {
+            hipError_t e = gsi::generic_project(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R,
+                                                in.rnorm, in.xnorm, s);
+            if (e != hipSuccess) return hip_fail(e, fn);
+          }
+          hipError_t e = gsi::launch_gate(in.rnorm, in.xnorm, B, eps, in.mask, in.fired_idx, in.n_fired, s);
           if (e != hipSuccess) return hip_fail(e, fn);
         }
-        hipError_t e = gsi::launch_gate(in.rnorm, in.xnorm, B, eps, in.mask, in.fired_idx, in.n_fired, s);
-        if (e != hipSuccess) return hip_fail(e, fn);
       }
       in_done[i] = 1;
       --remaining;
@@ -520,6 +629,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           const gsi_input_desc& in = inputs[mp.input_id];
           if (map_done[j] || mp.wdtype != dt || B == 0) continue;
           if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
+          if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype)) continue;  // matrix cores below
           if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
               !aligned(in.R, 16))
             continue;
@@ -543,8 +653,12 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
       if (map_done[j] != 2 && B > 0) {
-        hipError_t e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k,
-                                                 B, mp.wdtype, mp.Y, s);
+        hipError_t e;
+        if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype))
+          e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, s);
+        else
+          e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
+                                        mp.wdtype, mp.Y, s);
         if (e != hipSuccess) return hip_fail(e, fn);
       }
       map_done[j] = 1;

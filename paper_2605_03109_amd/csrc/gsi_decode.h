@@ -89,6 +89,8 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
 // single-token linear kernel (which reads part_n itself)
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
                                  hipStream_t s);
+// norms (and gate) of tasks whose part_n / b_slabs / rnorm / xnorm (mask, fired_idx, n_fired) are set
+hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s);
 // can a set of tasks share one single-token launch (LDS budget)?
 bool decode_linear_fits(const LinBatch& lb);
 // e0 / e1 (optional): events that take the start / stop timestamps of the single-token kernel's dispatch

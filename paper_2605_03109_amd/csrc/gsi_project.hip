@@ -355,6 +355,12 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
   t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up((size_t)g.a_slabs * B * k * 4, 256));
 }
 
+hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s) {
+  if (pb.n == 0 || pb.B == 0) return hipSuccess;
+  proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
+  return hipGetLastError();
+}
+
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
                                  hipStream_t s) {
   int ta = 0, tb = 0;

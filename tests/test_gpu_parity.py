@@ -357,3 +357,27 @@ def test_timed_stack_and_dense_stack_match_plain_calls(gsi, pu):
         for j, (gi, name) in enumerate(names):
             Yd = gsi.dense_linear(dgs[gi].W[name], dgs[gi].X[:B].contiguous())
             assert torch.equal(st.maps_t[j]["Y"][:B], Yd), (B, name)
+
+
+# ------------------------------------------------------------------------------------------------
+# prefill-sized batches (matrix-core path): several hundred tokens per call, ragged tails in every
+# dimension of the 128 x 128 tiles, fp32 and bf16 activations
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k,m,T,nf,xdtype", [(1024, 64, 520, 300, 60, "f32"), (2048, 128, 1000, 200, 41, "bf16"),
+                                               (512, 32, 384, 129, 0, "f32"), (1024, 256, 300, 257, 257, "bf16")])
+def test_prefill_sized_batch(gsi, pu, d, k, m, T, nf, xdtype):
+    w = wl.tiny(d, k, m, T, nf, seed=4000 + d + k + T, wdtype="bf16", xdtype=xdtype)
+    say(f"case prefill d={d} k={k} m={m} T={T} nf={nf} x={xdtype}")
+    g = w.groups[0]
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    worst = pu.check_group(w, g, [(0, T)], dg, og)
+    ref = og.run()
+    assert ref["n"] == nf
+    say(f"  worst rel-L2 {worst:.3e}")
+    # the stack gives the same bits as the separate calls
+    st = gsi.layer_stack([{"U": dg.U, "X": dg.X}], [{"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}], T, w.eps)
+    sep = pu.run_separate_calls(dg, w.eps)
+    torch.cuda.synchronize()
+    for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired"):
+        assert torch.equal(st.inputs_t[0][key], sep[key]), key
+    assert torch.equal(st.maps_t[0]["Y"], sep["Y"]["w"])
