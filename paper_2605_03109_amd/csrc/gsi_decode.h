@@ -10,7 +10,7 @@ namespace gsi {
 constexpr int kMaxTasks = 8;        // tasks (and input groups) per launch
 constexpr int kTokTile = 4;         // tokens processed together by the projection / image kernels
 constexpr int kColBlock = 64;       // columns of U per workgroup in the partial projection
-constexpr int kPartSlabs = 32;      // row slabs of U per input in the partial projection (= partials per c_j)
+constexpr int kPartSlabs = 32;      // row slabs of U per input in the partial projection, upper bound (= partials per c_j)
 constexpr int kMaxResSlabs = 512;   // row slabs per input in the residual kernel, upper bound
 constexpr int kMaxK = 512;          // largest rank the vector projection kernels take
 constexpr int kRowsPerBlock = 16;   // output rows per workgroup in the batched-token linear kernels
@@ -64,6 +64,7 @@ struct LinTask {
   const void* M;
   float* Y;
   int m, group;
+  int k, coff;  // copies of the group's rank and of its coefficient offset in LDS (filled at launch)
 };
 
 struct LinBatch {

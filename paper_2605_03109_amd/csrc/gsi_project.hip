@@ -65,7 +65,26 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
 #pragma unroll
       for (int e = 0; e < V; ++e) acc[tt][e] = 0.f;
     int i = ro;
-    // eight row steps at a time: all loads of the batch are issued before the first use
+    // sixteen (then eight, four) row steps at a time: all loads of a batch are issued before the first use
+    for (; i + 15 * rps < rows; i += 16 * rps) {
+      uint4 raw[16];
+      float xv[16][TB];
+#pragma unroll
+      for (int q = 0; q < 16; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+#pragma unroll
+      for (int q = 0; q < 16; ++q)
+#pragma unroll
+        for (int tt = 0; tt < TB; ++tt) xv[q][tt] = load_act(p.X, p.xdtype, xoff[tt] + i + q * rps);
+#pragma unroll
+      for (int q = 0; q < 16; ++q) {
+        float u[V];
+        T::widen(raw[q], u);
+#pragma unroll
+        for (int tt = 0; tt < TB; ++tt)
+#pragma unroll
+          for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[e], xv[q][tt], acc[tt][e]);
+      }
+    }
     for (; i + 7 * rps < rows; i += 8 * rps) {
       uint4 raw[8];
       float xv[8][TB];
@@ -182,6 +201,13 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
       const int64_t stride = (int64_t)B * k;
       float s = 0.f;
       int sl = 0;
+      for (; sl + 16 <= p.a_slabs; sl += 16) {
+        float v[16];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) v[q] = pc[(sl + q) * stride];
+#pragma unroll
+        for (int q = 0; q < 16; ++q) s += v[q];
+      }
       for (; sl + 8 <= p.a_slabs; sl += 8) {
         float v[8];
 #pragma unroll
@@ -226,13 +252,19 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
 #pragma unroll
     for (int q = 0; q < PF; ++q)
       if (q < steps) row_step(upf[q], xpf[q], q);
-    for (int st = PF; st < steps; ++st) {
-      const int i = min(st * rps + ro, rows - 1);
-      float u[V], xv[TB];
-      T::load_vec(U + (int64_t)i * k, u);
+    for (int st0 = PF; st0 < steps; st0 += PF) {  // further steps, PF at a time with all loads issued first
+      float u[PF][V], xv[PF][TB];
 #pragma unroll
-      for (int tt = 0; tt < TB; ++tt) xv[tt] = load_act(p.X, p.xdtype, (int64_t)min(t0 + tt, B - 1) * d + row0 + i);
-      row_step(u, xv, st);
+      for (int q = 0; q < PF; ++q) {
+        const int i = min((st0 + q) * rps + ro, rows - 1);
+        T::load_vec(U + (int64_t)i * k, u[q]);
+#pragma unroll
+        for (int tt = 0; tt < TB; ++tt)
+          xv[q][tt] = load_act(p.X, p.xdtype, (int64_t)min(t0 + tt, B - 1) * d + row0 + i);
+      }
+#pragma unroll
+      for (int q = 0; q < PF; ++q)
+        if (st0 + q < steps) row_step(u[q], xv[q], st0 + q);
     }
     GSI_MARK(7);
 #pragma unroll
@@ -329,7 +361,10 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
   const int cbw = (int)(k < kColBlock ? k : kColBlock);
   const int rps_a = kBlock / (cbw / V);
   g.a_cblocks = (int)ceil_div(k, kColBlock);
-  g.a_rows = (int)(ceil_div(ceil_div(d, kPartSlabs), rps_a) * rps_a);
+  // one batch of eight row steps per workgroup, unless that would need more than kPartSlabs slabs
+  int64_t ar = ceil_div(d, kPartSlabs);
+  if (ar < 8 * rps_a) ar = 8 * rps_a;
+  g.a_rows = (int)(ceil_div(ar, rps_a) * rps_a);
   g.a_slabs = (int)ceil_div(d, g.a_rows);
   const int rps_b = kBlock / (int)(k / V);
   int64_t br = ceil_div(d, kMaxResSlabs);  // four row steps per workgroup unless that needs too many slabs
@@ -363,6 +398,13 @@ hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, h
 
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
                                  hipStream_t s) {
+  // the tasks are independent: the largest input goes first so that its workgroups start first
+  for (int i = 1; i < pb.n; ++i)
+    for (int j = i; j > 0 && (int64_t)pb.t[j].d * pb.t[j].k > (int64_t)pb.t[j - 1].d * pb.t[j - 1].k; --j) {
+      const ProjTask tmp = pb.t[j];
+      pb.t[j] = pb.t[j - 1];
+      pb.t[j - 1] = tmp;
+    }
   int ta = 0, tb = 0;
   for (int i = 0; i < pb.n; ++i) {
     pb.a_begin[i] = ta;

@@ -97,25 +97,37 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
     Item it;
     it.live = v < total_items;
     v = it.live ? v : total_items - 1;
-    int ti = 0;
+    // every task's fields are read at fixed argument offsets (independent scalar loads), then selected
+    const LinTask* tp = &lb.t[0];
+    int base = 0;
+    const void* Mp = tp->M;
+    it.y = tp->Y;
+    it.m = tp->m;
+    it.group = tp->group;
+    it.k = tp->k;
+    int co = tp->coff;
 #pragma unroll
-    for (int i = 1; i < kMaxTasks; ++i)
-      if (i < n && v >= lb.short_begin[i]) ti = i;
-    const LinTask& t = lb.t[ti];
-    it.group = t.group;
-    it.k = lb.g[t.group].k;
-    it.m = t.m;
+    for (int i = 1; i < kMaxTasks; ++i) {
+      const bool ge = i < n && v >= lb.short_begin[i];
+      const LinTask& t = lb.t[i];
+      base = ge ? lb.short_begin[i] : base;
+      Mp = ge ? t.M : Mp;
+      it.y = ge ? t.Y : it.y;
+      it.m = ge ? t.m : it.m;
+      it.group = ge ? t.group : it.group;
+      it.k = ge ? t.k : it.k;
+      co = ge ? t.coff : co;
+    }
     const int chunks = it.k / V;
     const int lsh = chunks <= 1 ? 0 : 32 - __builtin_clz(chunks - 1);
     it.lpr = 1 << lsh;  // lanes per row: smallest power of two >= chunks
     it.rpw = kWave >> lsh;
-    it.row0 = (v - lb.short_begin[ti]) * kSU * it.rpw + (lane >> lsh);
+    it.row0 = (v - base) * kSU * it.rpw + (lane >> lsh);
     const int l = lane & (it.lpr - 1);
     const int col = l * V < it.k ? l * V : it.k - V;
     it.live = it.live && (l * V < it.k);
-    it.base = reinterpret_cast<const S*>(t.M) + col;
-    it.y = t.Y;
-    it.coff = coff(t.group) + col;
+    it.base = reinterpret_cast<const S*>(Mp) + col;
+    it.coff = co + col;
     return it;
   };
   auto issue = [&](const Item& it, Raw<T> (&buf)[kSU]) {
@@ -142,12 +154,15 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   };
   Raw<T> bufA[kSU], bufB[kSU];
   Item itA, itB;
+  const bool haveB = gw + GW < total_items;  // wave-uniform
   if constexpr (!DENSE) {
     if (total_items > 0) {
       itA = locate(gw);
-      itB = locate(gw + GW);
       issue(itA, bufA);
-      issue(itB, bufB);
+      if (haveB) {
+        itB = locate(gw + GW);
+        issue(itB, bufB);
+      }
     }
   }
 
@@ -224,7 +239,7 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   if constexpr (!DENSE) {
     if (total_items > 0) {
       consume(itA, bufA, fired_mask);
-      consume(itB, bufB, fired_mask);
+      if (haveB) consume(itB, bufB, fired_mask);
       for (int v = gw + 2 * GW; v < total_items; v += 2 * GW) {  // only when the grid is small for the maps
         itA = locate(v);
         itB = locate(v + GW);
@@ -389,6 +404,9 @@ hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_
   for (int i = 0; i < lb.n; ++i) {
     rows += lb.t[i].m;
     const LinGroup& g = lb.g[lb.t[i].group];
+    lb.t[i].k = g.k;
+    lb.t[i].coff = 0;
+    for (int gi = 0; gi < lb.t[i].group; ++gi) lb.t[i].coff += lb.g[gi].k;
     if ((g.d / V) % (kWave * kLU)) tail = true;
     lb.short_begin[i] = items;
     if (!lb.dense) {
