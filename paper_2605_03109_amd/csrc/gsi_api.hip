@@ -266,6 +266,64 @@ static void clear(gsi::LinBatch& lb, int64_t B) {
   lb.B = (int)B;
 }
 
+// Adds map `mp` (reading group description `gd`) to the batch, flushing first when the batch is full or
+// its LDS budget would be exceeded.  `gkey` identifies the input so maps of one input share a group slot.
+namespace {
+struct LinBatcher {
+  gsi::LinBatch lb;
+  int gkeys[gsi::kMaxTasks];
+  int wdtype;
+  hipStream_t s;
+  int64_t B;
+  hipEvent_t e0 = nullptr, e1 = nullptr;  // optional dispatch-timestamp events for the launches of this batcher
+  gsi::ImgBatch sib;                      // single token: image maps y = M c not yet written by an earlier launch
+  void reset(int64_t B_, int dense, int inline_gate, float eps) {
+    B = B_;
+    clear(lb, B_);
+    lb.dense = dense; lb.inline_gate = inline_gate; lb.eps = eps;
+    std::memset(&sib, 0, sizeof(sib));
+  }
+  hipError_t flush() {
+    if (lb.n == 0) return hipSuccess;
+    if (sib.n > 0)  // the image term first: the weight-streaming launch adds W r to it
+      if (hipError_t ei = gsi::decode_image_launch(sib, wdtype, s); ei != hipSuccess) return ei;
+    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s, e0, e1);
+    const int dense = lb.dense, ig = lb.inline_gate;
+    const float eps = lb.eps;
+    reset(B, dense, ig, eps);
+    return e;
+  }
+  hipError_t add(int gkey, const gsi::LinGroup& gd, const void* W, const void* M, float* Y, int64_t m,
+                 bool need_image = false) {
+    for (int attempt = 0; attempt < 2; ++attempt) {
+      int gi = -1;
+      for (int i = 0; i < lb.ng; ++i)
+        if (gkeys[i] == gkey) gi = i;
+      gsi::LinBatch trial = lb;
+      if (gi < 0) {
+        if (trial.ng == gsi::kMaxTasks) gi = -2;
+        else { gi = trial.ng++; trial.g[gi] = gd; }
+      }
+      if (gi >= 0 && trial.n < gsi::kMaxTasks) {
+        gsi::LinTask& t = trial.t[trial.n++];
+        t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi;
+        if (gsi::decode_linear_fits(trial)) {
+          if (gi == lb.ng) gkeys[gi] = gkey;
+          lb = trial;
+          if (need_image) {  // as many image tasks as linear tasks at most, so this never overflows
+            gsi::ImgTask& it = sib.t[sib.n++];
+            it.M = M; it.Y = Y; it.part_c = nullptr; it.C = gd.C; it.m = (int)m; it.k = gd.k; it.a_slabs = 0;
+          }
+          return hipSuccess;
+        }
+      }
+      if (hipError_t e = flush(); e != hipSuccess) return e;  // start a new launch and try once more
+    }
+    return hipErrorInvalidValue;  // a single map that passed decode_linear_ok always fits an empty batch
+  }
+};
+}  // namespace
+
 int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype, float* C,
                 float* R, float* rnorm, float* xnorm, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_project_args("gsi_project", U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm)) return rc;
@@ -310,13 +368,15 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
   hipError_t e;
   if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype) && gsi::decode_linear_ok(m, d, k, wdtype, W, M) &&
       aligned(C, 16) && aligned(R, 16)) {
-    gsi::LinBatch lb;
-    clear(lb, B);
-    lb.n = lb.ng = 1;
-    lb.g[0].C = C; lb.g[0].R = R; lb.g[0].fired_idx = fired_idx; lb.g[0].n_fired = n_fired;
-    lb.g[0].d = (int)d; lb.g[0].k = (int)k;
-    lb.t[0].W = W; lb.t[0].M = M; lb.t[0].Y = (float*)Y; lb.t[0].m = (int)m; lb.t[0].group = 0;
-    e = gsi::decode_linear_launch(lb, wdtype, s);
+    LinBatcher bt;
+    bt.wdtype = wdtype; bt.s = s;
+    bt.reset(B, 0, 0, 0.f);
+    gsi::LinGroup gd;
+    std::memset(&gd, 0, sizeof(gd));
+    gd.C = C; gd.R = R; gd.fired_idx = fired_idx; gd.n_fired = n_fired;
+    gd.d = (int)d; gd.k = (int)k;
+    e = bt.add(0, gd, W, M, (float*)Y, m, B == 1);
+    if (e == hipSuccess) e = bt.flush();
   } else if (mfma_gated_path(W, M, C, R, d, k, B, wdtype)) {
     e = mfma_gated(W, M, C, R, fired_idx, n_fired, m, d, k, B, (float*)Y, s);
   } else {
@@ -367,55 +427,6 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
     need += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
   return need;
 }
-
-// Adds map `mp` (reading group description `gd`) to the batch, flushing first when the batch is full or
-// its LDS budget would be exceeded.  `gkey` identifies the input so maps of one input share a group slot.
-namespace {
-struct LinBatcher {
-  gsi::LinBatch lb;
-  int gkeys[gsi::kMaxTasks];
-  int wdtype;
-  hipStream_t s;
-  int64_t B;
-  hipEvent_t e0 = nullptr, e1 = nullptr;  // optional dispatch-timestamp events for the launches of this batcher
-  void reset(int64_t B_, int dense, int inline_gate, float eps) {
-    B = B_;
-    clear(lb, B_);
-    lb.dense = dense; lb.inline_gate = inline_gate; lb.eps = eps;
-  }
-  hipError_t flush() {
-    if (lb.n == 0) return hipSuccess;
-    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s, e0, e1);
-    const int dense = lb.dense, ig = lb.inline_gate;
-    const float eps = lb.eps;
-    reset(B, dense, ig, eps);
-    return e;
-  }
-  hipError_t add(int gkey, const gsi::LinGroup& gd, const void* W, const void* M, float* Y, int64_t m) {
-    for (int attempt = 0; attempt < 2; ++attempt) {
-      int gi = -1;
-      for (int i = 0; i < lb.ng; ++i)
-        if (gkeys[i] == gkey) gi = i;
-      gsi::LinBatch trial = lb;
-      if (gi < 0) {
-        if (trial.ng == gsi::kMaxTasks) gi = -2;
-        else { gi = trial.ng++; trial.g[gi] = gd; }
-      }
-      if (gi >= 0 && trial.n < gsi::kMaxTasks) {
-        gsi::LinTask& t = trial.t[trial.n++];
-        t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi;
-        if (gsi::decode_linear_fits(trial)) {
-          if (gi == lb.ng) gkeys[gi] = gkey;
-          lb = trial;
-          return hipSuccess;
-        }
-      }
-      if (hipError_t e = flush(); e != hipSuccess) return e;  // start a new launch and try once more
-    }
-    return hipErrorInvalidValue;  // a single map that passed decode_linear_ok always fits an empty batch
-  }
-};
-}  // namespace
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
@@ -565,7 +576,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
 
   // Schedule in waves: an input is ready when its producer map has been enqueued, a map when its
   // input has.  Ready inputs (maps) of one dtype that take the same kernels share a launch.
-  std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0);
+  std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0), img_done(n_maps, 0);
   int remaining = n_inputs + n_maps;
   while (remaining > 0) {
     int progressed = 0;
@@ -575,18 +586,30 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     for (int md = kVecGate; md <= kVecInline; ++md) {
       for (int dt = 0; dt < 2; ++dt) {
         gsi::ProjBatch pb;
+        gsi::ImgBatch ib;  // image maps y = M c of these inputs share the residual launch (single token)
         std::memset(&pb, 0, sizeof(pb));
+        std::memset(&ib, 0, sizeof(ib));
         pb.B = (int)B;
         auto flush = [&]() -> hipError_t {
           if (pb.n == 0) return hipSuccess;
-          hipError_t e = gsi::decode_project_launch(pb, dt, md == kVecGate, md == kVecGate, eps, s);
+          hipError_t e = gsi::decode_project_launch(pb, dt, md == kVecGate, md == kVecGate, eps, s, &ib);
           std::memset(&pb, 0, sizeof(pb));
+          std::memset(&ib, 0, sizeof(ib));
           pb.B = (int)B;
           return e;
         };
         for (int i : ready) {
           if (mode[i] != md || inputs[i].udtype != dt) continue;
           pb.t[pb.n++] = ptask[i];
+          if (md == kVecInline) {
+            for (int j = 0; j < n_maps && ib.n < gsi::kMaxTasks; ++j) {
+              if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
+              gsi::ImgTask& it = ib.t[ib.n++];
+              it.M = maps[j].M; it.Y = maps[j].Y; it.part_c = ptask[i].part_c; it.C = nullptr;
+              it.m = (int)maps[j].m; it.k = (int)inputs[i].k; it.a_slabs = ptask[i].a_slabs;
+              img_done[j] = 1;
+            }
+          }
           if (pb.n == gsi::kMaxTasks)
             if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
         }
@@ -643,7 +666,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
             gd.rnorm = in.rnorm; gd.xnorm = in.xnorm; gd.mask = in.mask;
             gd.fired_idx_out = in.fired_idx; gd.n_fired_out = in.n_fired;
           }
-          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m); e != hipSuccess) return hip_fail(e, fn);
+          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j]); e != hipSuccess)
+            return hip_fail(e, fn);
           map_done[j] = 2;
         }
         if (hipError_t e = bt.flush(); e != hipSuccess) return hip_fail(e, fn);

@@ -40,6 +40,21 @@ struct ProjBatch {
   int a_begin[kMaxTasks];  // first workgroup of each task in the partial-projection launch
   int b_begin[kMaxTasks];  // ... in the residual launch
   int n, B;
+  int b_total;             // workgroups of the residual launch that are residual slabs
+};
+
+// One image map y = M c of a single-token launch (gsi_image.h)
+struct ImgTask {
+  const void* M;
+  float* Y;
+  const float* part_c;  // partial projections [a_slabs][1][k] of the map's input, or null ...
+  const float* C;       // ... then the finished coefficients C[k]
+  int m, k, a_slabs, blk_begin;
+};
+
+struct ImgBatch {
+  ImgTask t[kMaxTasks];
+  int n, total;         // tasks, workgroups
 };
 
 // One input group as seen by the linear kernels: its projection outputs and its gate.
@@ -64,14 +79,12 @@ struct LinTask {
   const void* M;
   float* Y;
   int m, group;
-  int k, coff;  // copies of the group's rank and of its coefficient offset in LDS (filled at launch)
 };
 
 struct LinBatch {
   LinGroup g[kMaxTasks];
   LinTask t[kMaxTasks];
   int blk_begin[kMaxTasks];        // several-token kernels: first workgroup of each task
-  int short_begin[kMaxTasks + 1];  // single-token kernel: first image-row item of each task
   int n, ng, B;
   int inline_gate;           // single-token kernel: evaluate the gate from part_n (and publish it)
   int dense;                 // y = W x, no image term
@@ -88,8 +101,11 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
 
 // partial projection + residual (+ norms, + gate): with_norms = false leaves the norms to the
 // single-token linear kernel (which reads part_n itself)
+// `img` (single token only): image maps whose workgroups ride in the residual launch
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
-                                 hipStream_t s);
+                                 hipStream_t s, ImgBatch* img = nullptr);
+// stand-alone image launch for one token: y = M c with c read from C (tasks' C set, part_c null)
+hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s);
 // norms (and gate) of tasks whose part_n / b_slabs / rnorm / xnorm (mask, fired_idx, n_fired) are set
 hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s);
 // can a set of tasks share one single-token launch (LDS budget)?

@@ -1,0 +1,96 @@
+// Image rows y = M c for ONE token (Algorithm 1, line 5): device code of one 256-thread workgroup,
+// shared by the fused residual + image launch of a layer stack and by the stand-alone image kernel.
+//
+// A workgroup takes eight items of one map (two per wave); an item is four 16-byte loads per lane, i.e. 4 * rpw rows
+// of M where rpw = 64 / (lanes per row).  The rows of M are requested first; the projection
+// coefficients are then either summed from the row-slab partials (fixed slab order -- the same
+// function the residual kernel uses, hence the same bits) or read from C, staged in LDS, and the rows
+// are reduced with DPP row sums.  One lane writes each output element.
+#pragma once
+#include "gsi_decode.h"
+#include "gsi_device.h"
+
+namespace gsi {
+
+constexpr int kImgItemsPerBlock = 8;   // two per wave
+constexpr int kImgLoads = 4;           // 16-byte loads per lane and item
+constexpr int kImgPerWave = kImgItemsPerBlock / 4;
+
+// c_j = sum over row slabs of the partial projections, slab order fixed
+__device__ __forceinline__ float sum_partials(const float* __restrict__ pc, int64_t stride, int a_slabs) {
+  float s = 0.f;
+  int sl = 0;
+  for (; sl + 16 <= a_slabs; sl += 16) {
+    float v[16];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) v[q] = pc[(sl + q) * stride];
+#pragma unroll
+    for (int q = 0; q < 16; ++q) s += v[q];
+  }
+  for (; sl + 8 <= a_slabs; sl += 8) {
+    float v[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) v[q] = pc[(sl + q) * stride];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) s += v[q];
+  }
+  for (; sl < a_slabs; ++sl) s += pc[sl * stride];
+  return s;
+}
+
+template <class T>
+__device__ __forceinline__ void image_block(const ImgTask& t, int local_block, float* __restrict__ cs) {
+  constexpr int V = T::kVec;
+  using S = typename T::storage;
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int k = t.k, m = t.m;
+  const int chunks = k / V;
+  const int lsh = chunks <= 1 ? 0 : 32 - __builtin_clz(chunks - 1);
+  const int lpr = 1 << lsh, rpw = kWave >> lsh;  // lanes per row (power of two >= chunks), rows per wave load
+  const int l = lane & (lpr - 1), sub = lane >> lsh;
+  const bool live = l * V < k;
+  const int col = live ? l * V : k - V;
+  const S* M = reinterpret_cast<const S*>(t.M) + col;
+  const int item0 = local_block * kImgItemsPerBlock + wave * kImgPerWave;
+  uint4 raw[kImgPerWave][kImgLoads];
+#pragma unroll
+  for (int it = 0; it < kImgPerWave; ++it)
+#pragma unroll
+    for (int u = 0; u < kImgLoads; ++u) {
+      const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
+      raw[it][u] = *reinterpret_cast<const uint4*>(M + (int64_t)(row < m ? row : m - 1) * k);
+    }
+  for (int j = threadIdx.x; j < k; j += 256) cs[j] = t.part_c ? sum_partials(t.part_c + j, k, t.a_slabs) : t.C[j];
+  __syncthreads();
+  float cvv[V];
+#pragma unroll
+  for (int q = 0; q < V / 4; ++q) {
+    const float4 x = reinterpret_cast<const float4*>(cs + col)[q];
+    cvv[4 * q + 0] = x.x; cvv[4 * q + 1] = x.y; cvv[4 * q + 2] = x.z; cvv[4 * q + 3] = x.w;
+  }
+#pragma unroll
+  for (int it = 0; it < kImgPerWave; ++it)
+#pragma unroll
+    for (int u = 0; u < kImgLoads; ++u) {
+      float w[V];
+      T::widen(raw[it][u], w);
+      float s = 0.f;
+#pragma unroll
+      for (int e = 0; e < V; ++e) s = fmaf(w[e], cvv[e], s);
+      s = group_sum_rt(live ? s : 0.f, lpr);
+      const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
+      if (l == 0 && row < m) t.Y[row] = s;
+    }
+}
+
+// workgroups a map needs in an image launch
+inline int image_blocks(int64_t m, int64_t k, int wdtype) {
+  const int V = wdtype == GSI_BF16 ? 8 : 4;
+  int lpr = 1;
+  while (lpr < k / V) lpr <<= 1;
+  const int64_t rows_per_item = (int64_t)kImgLoads * (kWave / lpr);
+  return (int)ceil_div(ceil_div(m, rows_per_item), kImgItemsPerBlock);
+}
+
+}  // namespace gsi

@@ -200,11 +200,7 @@ bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W
 }
 
 bool decode_linear_fits(const LinBatch& lb) {
-  if (lb.B == 1) {
-    size_t sumk = 0;
-    for (int i = 0; i < lb.ng; ++i) sumk += (size_t)lb.g[i].k;
-    return sumk <= (size_t)kMaxSumK && stream_smem_bytes(lb) <= (size_t)(kMaxLinD + kMaxSumK) * sizeof(float);
-  }
+  if (lb.B == 1) return stream_smem_bytes(lb) <= (size_t)kMaxLinD * sizeof(float);
   return tile_smem(lb) <= (size_t)kMaxLinD * sizeof(float);
 }
 

@@ -12,6 +12,7 @@
 // All reductions have a fixed order: results are bit-identical run to run.
 #include "gsi_decode.h"
 #include "gsi_device.h"
+#include "gsi_image.h"
 
 // Phase markers: empty in the library; a profiling build may define GSI_MARK(i) to record a timestamp.
 #ifndef GSI_MARK
@@ -160,11 +161,25 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
 }
 
 template <class T, int TB>
-__global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
+__global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, const ImgBatch ib) {
   constexpr int V = T::kVec;
   constexpr int PF = 4;  // row steps of U held in registers
   __shared__ __align__(16) float cs[TB][kMaxK];
   __shared__ float nr[kWaves][TB], nx[kWaves][TB];
+
+  if constexpr (TB == 1) {
+    // workgroups past the residual slabs evaluate image rows y = M c of the same inputs (they need
+    // the same partial projections and nothing else, so they share the launch)
+    if ((int)blockIdx.x >= pb.b_total) {
+      const int b = blockIdx.x - pb.b_total;
+      int ti = 0;
+#pragma unroll
+      for (int i = 1; i < kMaxTasks; ++i)
+        if (i < ib.n && b >= ib.t[i].blk_begin) ti = i;
+      image_block<T>(ib.t[ti], b - ib.t[ti].blk_begin, &cs[0][0]);
+      return;
+    }
+  }
 
   const int ti = find_task(pb.b_begin, pb.n, blockIdx.x);
   const ProjTask& p = pb.t[ti];
@@ -197,25 +212,7 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
     // ... then the partials: c_j = sum over slabs, slab order fixed
     for (int idx = threadIdx.x; idx < nt * k; idx += kBlock) {
       const int tt = idx / k, j = idx % k;
-      const float* pc = p.part_c + (int64_t)(t0 + tt) * k + j;
-      const int64_t stride = (int64_t)B * k;
-      float s = 0.f;
-      int sl = 0;
-      for (; sl + 16 <= p.a_slabs; sl += 16) {
-        float v[16];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) v[q] = pc[(sl + q) * stride];
-#pragma unroll
-        for (int q = 0; q < 16; ++q) s += v[q];
-      }
-      for (; sl + 8 <= p.a_slabs; sl += 8) {
-        float v[8];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) v[q] = pc[(sl + q) * stride];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) s += v[q];
-      }
-      for (; sl < p.a_slabs; ++sl) s += pc[sl * stride];
+      const float s = sum_partials(p.part_c + (int64_t)(t0 + tt) * k + j, (int64_t)B * k, p.a_slabs);
       cs[tt][j] = s;
       if (slab == 0) p.C[(int64_t)(t0 + tt) * k + j] = s;
     }
@@ -337,6 +334,18 @@ __global__ __launch_bounds__(kBlock) void proj_norms(const ProjBatch pb, int do_
   if (do_gate && threadIdx.x == 0) p.n_fired[0] = base;
 }
 
+// stand-alone image launch (one token): y = M c with c read from C
+template <class T>
+__global__ __launch_bounds__(kBlock) void image_rows(const ImgBatch ib) {
+  __shared__ __align__(16) float cs[kMaxSumK];
+  const int b = blockIdx.x;
+  int ti = 0;
+#pragma unroll
+  for (int i = 1; i < kMaxTasks; ++i)
+    if (i < ib.n && b >= ib.t[i].blk_begin) ti = i;
+  image_block<T>(ib.t[ti], b - ib.t[ti].blk_begin, cs);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
@@ -396,8 +405,21 @@ hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, h
   return hipGetLastError();
 }
 
+hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s) {
+  int total = 0;
+  for (int i = 0; i < ib.n; ++i) {
+    ib.t[i].blk_begin = total;
+    total += image_blocks(ib.t[i].m, ib.t[i].k, wdtype);
+  }
+  ib.total = total;
+  if (total == 0) return hipSuccess;
+  if (wdtype == GSI_BF16) image_rows<BF16><<<total, kBlock, 0, s>>>(ib);
+  else image_rows<F32><<<total, kBlock, 0, s>>>(ib);
+  return hipGetLastError();
+}
+
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
-                                 hipStream_t s) {
+                                 hipStream_t s, ImgBatch* img) {
   // the tasks are independent: the largest input goes first so that its workgroups start first
   for (int i = 1; i < pb.n; ++i)
     for (int j = i; j > 0 && (int64_t)pb.t[j].d * pb.t[j].k > (int64_t)pb.t[j - 1].d * pb.t[j - 1].k; --j) {
@@ -413,21 +435,32 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
     tb += pb.t[i].b_slabs;
   }
   if (ta == 0 || pb.B == 0) return hipSuccess;
+  pb.b_total = tb;
+  ImgBatch none;
+  none.n = 0;
+  none.total = 0;
+  ImgBatch& ib = (img && pb.B == 1) ? *img : none;
+  int ti = 0;
+  for (int i = 0; i < ib.n; ++i) {
+    ib.t[i].blk_begin = ti;
+    ti += image_blocks(ib.t[i].m, ib.t[i].k, udtype);
+  }
+  ib.total = ti;
   if (udtype == GSI_BF16) {
     if (pb.B == 1) {
       proj_partial<BF16, 1><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<BF16, 1><<<tb, kBlock, 0, s>>>(pb);
+      proj_residual<BF16, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
     } else {
       proj_partial<BF16, kTokTile><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<BF16, kTokTile><<<tb, kBlock, 0, s>>>(pb);
+      proj_residual<BF16, kTokTile><<<tb, kBlock, 0, s>>>(pb, ib);
     }
   } else {
     if (pb.B == 1) {
       proj_partial<F32, 1><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<F32, 1><<<tb, kBlock, 0, s>>>(pb);
+      proj_residual<F32, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
     } else {
       proj_partial<F32, kTokTile><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<F32, kTokTile><<<tb, kBlock, 0, s>>>(pb);
+      proj_residual<F32, kTokTile><<<tb, kBlock, 0, s>>>(pb, ib);
     }
   }
   if (with_norms) proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
