@@ -28,9 +28,15 @@
 namespace gsi {
 namespace {
 
-constexpr int kBlock = 512;  // eight waves share one staged activation vector
+#ifndef GSI_SBLOCK
+#define GSI_SBLOCK 512
+#endif
+constexpr int kBlock = GSI_SBLOCK;  // waves of a workgroup share one staged activation vector
 constexpr int kWaves = kBlock / kWave;
-constexpr int kLU = 8;  // loads per lane in a long unit
+#ifndef GSI_KLU
+#define GSI_KLU 8
+#endif
+constexpr int kLU = GSI_KLU;  // loads per lane in a long unit
 
 template <class T>
 struct Raw {  // 16 bytes as loaded; widened to fp32 when consumed
@@ -162,36 +168,98 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
       if (t.group != gi) continue;  // uniform
       const int m = t.m;
       const S* W = reinterpret_cast<const S*>(t.W);
-      for (int row = first; row < m; row += GW) {
-        float acc = 0.f;
-        float yold = 0.f;
-        if constexpr (!DENSE) yold = t.Y[row];  // the image term written by the preceding launch
-        for (int sg = 0; sg < nseg; ++sg) {
-          Raw<T> buf[kLU];
-          const int cb = sg * kWave * kLU + lane;
+      if constexpr (!TAIL) {
+        // Software-pipelined: units of kLU loads per lane, two register buffers; the loads of the next
+        // unit are issued before the current one is consumed.  The loop body is straight-line code
+        // with unconditional loads and no stores (results are parked in lane (row index mod 64) of a
+        // register and written once per 64 rows), so a wave always has a unit in flight.
+        const int nrows = first < m ? (m - first + GW - 1) / GW : 0;
+        const int64_t seg_step = (int64_t)kWave * kLU * V;                       // elements to the next unit of a row
+        const int64_t row_step = (int64_t)GW * d - (int64_t)(nseg - 1) * seg_step;  // last unit of a row -> next row
+        for (int j0 = 0; j0 < nrows; j0 += kWave) {
+          const int cnt = min(kWave, nrows - j0);
+          const int nu = cnt * nseg;
+          const S* p0 = W + (int64_t)(first + (int64_t)j0 * GW) * d + (int64_t)lane * V;
+          float res = 0.f, acc = 0.f;
+          Raw<T> A[kLU], Bb[kLU];
+          auto issue = [&](Raw<T> (&buf)[kLU], const S* ptr) {
+            __builtin_amdgcn_sched_barrier(0);  // keep the loads here: ahead of the arithmetic that follows
 #pragma unroll
-          for (int q = 0; q < kLU; ++q) {
-            int c = cb + q * kWave;
-            if (TAIL) c = c < chunks ? c : chunks - 1;
-            buf[q].load(W + (int64_t)row * d + (int64_t)c * V);
+            for (int q = 0; q < kLU; ++q) buf[q].load(ptr + (int64_t)q * kWave * V);
+            __builtin_amdgcn_sched_barrier(0);
+          };
+          auto consume = [&](const Raw<T> (&buf)[kLU], int jj, int sg) {
+            const float* xp = xs + (sg * kWave * kLU + lane) * V;
+#pragma unroll
+            for (int q = 0; q < kLU; ++q) {
+              float w[V], xv[V];
+              buf[q].widen(w);
+              lds_vec<V>(xp + q * kWave * V, xv);
+              acc = dotv<V>(w, xv, acc);
+            }
+            const bool last = sg == nseg - 1;
+            const float sum = group_sum<kWave>(acc);
+            res = (last && lane == jj) ? sum : res;
+            acc = last ? 0.f : acc;
+          };
+          // unit u: row index jj = u / nseg, segment sg = u % nseg; pointers advance incrementally
+          const S* pa = p0;
+          int jja = 0, sga = 0;
+          issue(A, pa);
+          int u = 0;
+          while (u + 2 < nu) {
+            const S* pb = pa + (sga == nseg - 1 ? row_step : seg_step);
+            const int jjb = sga == nseg - 1 ? jja + 1 : jja, sgb = sga == nseg - 1 ? 0 : sga + 1;
+            issue(Bb, pb);
+            consume(A, jja, sga);
+            pa = pb + (sgb == nseg - 1 ? row_step : seg_step);
+            jja = sgb == nseg - 1 ? jjb + 1 : jjb;
+            sga = sgb == nseg - 1 ? 0 : sgb + 1;
+            issue(A, pa);
+            consume(Bb, jjb, sgb);
+            u += 2;
           }
+          if (u + 1 < nu) {
+            const S* pb = pa + (sga == nseg - 1 ? row_step : seg_step);
+            const int jjb = sga == nseg - 1 ? jja + 1 : jja, sgb = sga == nseg - 1 ? 0 : sga + 1;
+            issue(Bb, pb);
+            consume(A, jja, sga);
+            consume(Bb, jjb, sgb);
+          } else {
+            consume(A, jja, sga);
+          }
+          if (lane < cnt) {  // lane j holds the sum of this wave's row j0 + j
+            float* yp = t.Y + first + (int64_t)(j0 + lane) * GW;
+            *yp = DENSE ? res : *yp + res;  // image term written by the preceding launch
+          }
+        }
+      } else {
+        for (int row = first; row < m; row += GW) {
+          float acc = 0.f;
+          float yold = 0.f;
+          if constexpr (!DENSE) yold = t.Y[row];  // the image term written by the preceding launch
+          for (int sg = 0; sg < nseg; ++sg) {
+            Raw<T> buf[kLU];
+            const int cb = sg * kWave * kLU + lane;
 #pragma unroll
-          for (int q = 0; q < kLU; ++q) {
-            const int c = cb + q * kWave;
-            float w[V], xv[V];
-            buf[q].widen(w);
-            if (TAIL) {
+            for (int q = 0; q < kLU; ++q) {
+              int c = cb + q * kWave;
+              c = c < chunks ? c : chunks - 1;
+              buf[q].load(W + (int64_t)row * d + (int64_t)c * V);
+            }
+#pragma unroll
+            for (int q = 0; q < kLU; ++q) {
+              const int c = cb + q * kWave;
+              float w[V], xv[V];
+              buf[q].widen(w);
               lds_vec<V>(xs + (c < chunks ? c : chunks - 1) * V, xv);
               const float part = dotv<V>(w, xv, 0.f);
               acc += c < chunks ? part : 0.f;
-            } else {
-              lds_vec<V>(xs + c * V, xv);
-              acc = dotv<V>(w, xv, acc);
             }
           }
+          acc = group_sum<kWave>(acc);
+          if (lane == 0) t.Y[row] = DENSE ? acc : yold + acc;
         }
-        acc = group_sum<kWave>(acc);
-        if (lane == 0) t.Y[row] = DENSE ? acc : yold + acc;
       }
       // continue the deal: the next map starts with the wave after the one that took this map's last row
       first = (first - m % GW + GW) % GW;
