@@ -61,6 +61,24 @@ class HipEvents:
         self.ev = []
 
 
+def counter_traffic(args):
+    """HBM-side bytes per fired launch of the weight-streaming kernel, as measured offline with the
+    hardware counters FETCH_SIZE and WRITE_SIZE on this same workload (a counter run serialises the
+    kernels and cannot be part of a timed run).  The committed summary holds the figure and the commands;
+    it applies to the default workload only, so any other setting reports null."""
+    if (args.tokens, args.k, args.fire) != (256, 256, 0.1):
+        return None
+    path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "profiles",
+                        "hbm_traffic_stream_rows_gptj_block_k256_decode.md")
+    try:
+        for line in open(path):
+            if line.startswith("traffic_bytes_per_fired_launch:"):
+                return int(line.split(":")[1].split()[0])
+    except OSError:
+        pass
+    return None
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -73,6 +91,9 @@ def main() -> int:
     ap.add_argument("--fire", type=float, default=0.10, help="fraction of gate evaluations that fire")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run three device copies of 512 MiB first (a kernel of known traffic, used to "
+                         "scale hardware-counter readings of a rocprofv3 --pmc run)")
     args = ap.parse_args()
 
     if args.gpus != 1:
@@ -90,6 +111,14 @@ def main() -> int:
         print("bench.py: no GPU visible", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
+
+    if args.pmc_calibration:
+        src = torch.ones(512 << 20, dtype=torch.uint8, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     T = args.tokens
     t_gen = time.perf_counter()
@@ -249,7 +278,8 @@ def main() -> int:
         roofline = {
             "bound": "hbm", "kernel": "gsi::stream_rows<BF16, dense=false> (W r of every fired map of a step, one launch)",
             "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+            "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": counter_traffic(args),
             "avg_launch_us": round(avg_dur * 1e6, 3), "avg_algorithmic_bytes": round(avg_bytes),
             "launches": int(fired_any.sum()),
             "launches_without_fired_gate": int((~fired_any).sum()),
