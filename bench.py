@@ -160,7 +160,7 @@ def main() -> int:
 
     def dense_step(t, s):
         mp, inp = tabs[t % T]
-        rc = lib.gsi_dense_stack(mp, n_mp, inp, n_in, 1, s)
+        rc = lib.gsi_dense_stack(mp, n_mp, inp, n_in, 1, ws_ptr, ws_n, s)
         if rc:
             raise gsi.GsiError(rc, gsi.last_error())
 

@@ -139,13 +139,16 @@ int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_in
 
 /* Dense baseline for a whole stack: Y = W X for every map, all maps in one launch (Section 3.1,
  * the computation the method replaces).  Uses only W, Y, m, wdtype, input_id of each map and X, d,
- * xdtype of each input (src_map must be -1).  Needs no workspace. */
+ * xdtype of each input (src_map must be -1).  ws: device workspace of at least
+ * gsi_dense_stack_workspace_bytes(...) bytes (0 for a single token: ws may then be NULL). */
 int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
-                    int64_t B, void* stream);
+                    int64_t B, void* ws, size_t ws_bytes, void* stream);
 
 /* Minimum workspace size in bytes for one call (arguments that a call does not have are ignored). */
 size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int64_t B);
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
+                                       int32_t n_inputs, int64_t B);
+size_t gsi_dense_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                                        int32_t n_inputs, int64_t B);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */

@@ -95,6 +95,11 @@ size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int6
       }
       return need;
     }
+    case GSI_CALL_GATED_LINEAR:
+    case GSI_CALL_DENSE_LINEAR:
+      // partial products of the several-token matrix-core kernel
+      if (m < 1 || d < 1 || B < 1) return 0;
+      return gsi::tile_part_bytes(m, d, B);
     default:
       return 0;
   }
@@ -294,7 +299,7 @@ struct LinBatcher {
     return e;
   }
   hipError_t add(int gkey, const gsi::LinGroup& gd, const void* W, const void* M, float* Y, int64_t m,
-                 bool need_image = false) {
+                 bool need_image = false, float* part = nullptr) {
     for (int attempt = 0; attempt < 2; ++attempt) {
       int gi = -1;
       for (int i = 0; i < lb.ng; ++i)
@@ -306,7 +311,7 @@ struct LinBatcher {
       }
       if (gi >= 0 && trial.n < gsi::kMaxTasks) {
         gsi::LinTask& t = trial.t[trial.n++];
-        t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi;
+        t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi; t.part = part; t.slices = 0;
         if (gsi::decode_linear_fits(trial)) {
           if (gi == lb.ng) gkeys[gi] = gkey;
           lb = trial;
@@ -375,7 +380,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     std::memset(&gd, 0, sizeof(gd));
     gd.C = C; gd.R = R; gd.fired_idx = fired_idx; gd.n_fired = n_fired;
     gd.d = (int)d; gd.k = (int)k;
-    e = bt.add(0, gd, W, M, (float*)Y, m, B == 1);
+    e = bt.add(0, gd, W, M, (float*)Y, m, B == 1, gsi::tile_part_bytes(m, d, B) ? (float*)ws : nullptr);
     if (e == hipSuccess) e = bt.flush();
   } else if (mfma_gated_path(W, M, C, R, d, k, B, wdtype)) {
     e = mfma_gated(W, M, C, R, fired_idx, n_fired, m, d, k, B, (float*)Y, s);
@@ -409,6 +414,7 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
     lb.dense = 1;
     lb.g[0].X = X; lb.g[0].xdtype = xdtype; lb.g[0].d = (int)d;
     lb.t[0].W = W; lb.t[0].Y = Y; lb.t[0].m = (int)m; lb.t[0].group = 0;
+    lb.t[0].part = gsi::tile_part_bytes(m, d, B) ? (float*)ws : nullptr;
     e = gsi::decode_linear_launch(lb, wdtype, s);
   } else {
     e = gsi::generic_dense_linear(W, X, m, d, B, wdtype, xdtype, Y, s);
@@ -419,12 +425,17 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
 
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                                        int32_t n_inputs, int64_t B) {
-  (void)maps; (void)n_maps;
   if (!inputs || n_inputs < 0) return 0;
   // projections of independent inputs share a launch, so every input has its own region
   size_t need = 0;
   for (int i = 0; i < n_inputs; ++i)
     need += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
+  // and so do the maps of a decode batch (partial products of the weight term)
+  if (maps)
+    for (int j = 0; j < n_maps; ++j) {
+      const int id = maps[j].input_id;
+      if (id >= 0 && id < n_inputs) need += gsi::tile_part_bytes(maps[j].m, inputs[id].d, B);
+    }
   return need;
 }
 
@@ -446,8 +457,19 @@ int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_in
                           static_cast<hipEvent_t>(ev_linear_begin), static_cast<hipEvent_t>(ev_linear_end));
 }
 
+size_t gsi_dense_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
+                                       int32_t n_inputs, int64_t B) {
+  if (!maps || !inputs || n_maps < 0 || n_inputs < 0) return 0;
+  size_t need = 0;  // partial products of the several-token matrix-core kernel, one region per map
+  for (int j = 0; j < n_maps; ++j) {
+    const int id = maps[j].input_id;
+    if (id >= 0 && id < n_inputs) need += gsi::tile_part_bytes(maps[j].m, inputs[id].d, B);
+  }
+  return need;
+}
+
 int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
-                    int64_t B, void* stream) {
+                    int64_t B, void* ws, size_t ws_bytes, void* stream) {
   const char* fn = "gsi_dense_stack";
   if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
   if (n_maps > 0) GSI_REQUIRE_PTR(maps);
@@ -468,7 +490,18 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     }
   }
   if (B == 0) return GSI_OK;
+  if (int rc = check_ws(fn, ws, ws_bytes, gsi_dense_stack_workspace_bytes(maps, n_maps, inputs, n_inputs, B)))
+    return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
+  std::vector<float*> part(n_maps, nullptr);
+  {
+    size_t off = 0;
+    for (int j = 0; j < n_maps; ++j) {
+      const size_t pb = gsi::tile_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B);
+      if (pb) part[j] = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + off);
+      off += pb;
+    }
+  }
   std::vector<char> done(n_maps, 0);
   for (int dt = 0; dt < 2; ++dt) {
     LinBatcher bt;
@@ -482,7 +515,8 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
       gsi::LinGroup gd;
       std::memset(&gd, 0, sizeof(gd));
       gd.X = in.X; gd.xdtype = in.xdtype; gd.d = (int)in.d;
-      if (hipError_t e = bt.add(mp.input_id, gd, mp.W, nullptr, mp.Y, mp.m); e != hipSuccess) return hip_fail(e, fn);
+      if (hipError_t e = bt.add(mp.input_id, gd, mp.W, nullptr, mp.Y, mp.m, false, part[j]); e != hipSuccess)
+        return hip_fail(e, fn);
       done[j] = 1;
     }
     if (hipError_t e = bt.flush(); e != hipSuccess) return hip_fail(e, fn);
@@ -538,11 +572,17 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   hipStream_t s = static_cast<hipStream_t>(stream);
 
   std::vector<size_t> ws_off(n_inputs, 0);
+  std::vector<float*> part(n_maps, nullptr);
   {
     size_t off = 0;
     for (int i = 0; i < n_inputs; ++i) {
       ws_off[i] = off;
       off += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
+    }
+    for (int j = 0; j < n_maps; ++j) {
+      const size_t pb = gsi::tile_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B);
+      if (pb) part[j] = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + off);
+      off += pb;
     }
   }
 
@@ -666,7 +706,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
             gd.rnorm = in.rnorm; gd.xnorm = in.xnorm; gd.mask = in.mask;
             gd.fired_idx_out = in.fired_idx; gd.n_fired_out = in.n_fired;
           }
-          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j]); e != hipSuccess)
+          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j], part[j]);
+              e != hipSuccess)
             return hip_fail(e, fn);
           map_done[j] = 2;
         }

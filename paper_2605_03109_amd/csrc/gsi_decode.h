@@ -78,13 +78,17 @@ struct LinTask {
   const void* W;
   const void* M;
   float* Y;
+  float* part;   // several-token matrix-core kernel: partial products [slices][B][m] of the weight term
   int m, group;
+  int slices;    // ... column slices of the weight term (filled at launch)
 };
 
 struct LinBatch {
   LinGroup g[kMaxTasks];
   LinTask t[kMaxTasks];
   int blk_begin[kMaxTasks];        // several-token kernels: first workgroup of each task
+  int blk_begin2[kMaxTasks];       // matrix-core kernel: first image-term workgroup of each task
+  int tile_split;                  // ... first image-term workgroup of the launch
   int n, ng, B;
   int inline_gate;           // single-token kernel: evaluate the gate from part_n (and publish it)
   int dense;                 // y = W x, no image term
@@ -113,6 +117,12 @@ bool decode_linear_fits(const LinBatch& lb);
 // e0 / e1 (optional): events that take the start / stop timestamps of the single-token kernel's dispatch
 hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0 = nullptr,
                                 hipEvent_t e1 = nullptr);
+
+// several tokens on the matrix cores (gsi_tile.hip): workspace of one map's partial products (0 when the
+// shape does not take this path), eligibility of a filled batch, launch
+size_t tile_part_bytes(int64_t m, int64_t d, int64_t B);
+bool tile_rows_ok(const LinBatch& lb, int wdtype);
+hipError_t tile_rows_launch(LinBatch& lb, hipStream_t s);
 
 // single-token persistent kernel (gsi_stream.hip)
 size_t stream_smem_bytes(const LinBatch& lb);

@@ -207,6 +207,7 @@ bool decode_linear_fits(const LinBatch& lb) {
 hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   if (lb.n == 0 || lb.B == 0) return hipSuccess;
   if (lb.B == 1) return stream_rows_launch(lb, wdtype, s, e0, e1);
+  if (tile_rows_ok(lb, wdtype)) return tile_rows_launch(lb, s);
   int total = 0;
   for (int i = 0; i < lb.n; ++i) {
     lb.blk_begin[i] = total;

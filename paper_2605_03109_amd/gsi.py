@@ -25,7 +25,8 @@ CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR,
 EXPORTS = (
     "gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear", "gsi_layer_stack",
     "gsi_layer_stack_timed", "gsi_dense_stack",
-    "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_last_error", "gsi_version",
+    "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
+    "gsi_version",
 )
 
 
@@ -72,12 +73,14 @@ def _load() -> ctypes.CDLL:
     lib.gsi_layer_stack_timed.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                           ctypes.c_int32, i64, f32, vp, sz, vp, vp, vp]
     lib.gsi_dense_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
-                                    ctypes.c_int32, i64, vp]
+                                    ctypes.c_int32, i64, vp, sz, vp]
     lib.gsi_workspace_bytes.argtypes = [i32, i64, i64, i64, i64]
     lib.gsi_workspace_bytes.restype = sz
     lib.gsi_layer_stack_workspace_bytes.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32,
                                                     ctypes.POINTER(InputDesc), ctypes.c_int32, i64]
     lib.gsi_layer_stack_workspace_bytes.restype = sz
+    lib.gsi_dense_stack_workspace_bytes.argtypes = lib.gsi_layer_stack_workspace_bytes.argtypes
+    lib.gsi_dense_stack_workspace_bytes.restype = sz
     lib.gsi_last_error.restype = ctypes.c_char_p
     lib.gsi_version.restype = ctypes.c_int
     for name in ("gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
@@ -296,7 +299,8 @@ class LayerStack:
             e.W, e.M, e.m = _ptr(t["W"]), _ptr(t["M"]), m
             e.Y = _ptr(t["Y"]) + o * m * 4
             e.wdtype, e.input_id = dtype_code(t["W"]), t["input_id"]
-        need = int(lib.gsi_layer_stack_workspace_bytes(self._mp, len(self.maps_t), self._in, len(self.inputs_t), B))
+        need = max(int(fn(self._mp, len(self.maps_t), self._in, len(self.inputs_t), B))
+                   for fn in (lib.gsi_layer_stack_workspace_bytes, lib.gsi_dense_stack_workspace_bytes))
         if need > self.ws.numel():  # the workspace depends on the token count of the call
             self.ws = torch.empty(need, dtype=torch.uint8, device=self.ws.device)
 
@@ -313,7 +317,7 @@ class LayerStack:
     def run_dense(self, stream=None) -> None:
         """The dense baseline Y = W X over the same descriptor tables (one launch for all maps)."""
         _check(lib.gsi_dense_stack(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B,
-                                   _stream(stream)))
+                                   self.ws.data_ptr(), self.ws.numel(), _stream(stream)))
 
 
 def layer_stack(inputs: Sequence[dict], maps: Sequence[dict], B: int, eps: float, stream=None) -> LayerStack:

@@ -73,6 +73,26 @@ def test_mid_shapes(gsi, pu, wdtype, d, k, m, T, nf):
 
 
 # ------------------------------------------------------------------------------------------------
+# decode batches (2..128 tokens a call): one to eight token tiles, fired counts from none to all,
+# ragged row and token tails, the long fc_out-shaped contraction
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k,m,T,nf", [(4096, 256, 1032, 64, 10), (2048, 128, 520, 128, 128), (1024, 96, 260, 17, 0),
+                                        (16384, 256, 528, 16, 3), (1024, 64, 512, 100, 40), (4096, 512, 256, 2, 1),
+                                        (1024, 32, 36, 33, 20)])
+def test_decode_batches(gsi, pu, d, k, m, T, nf):
+    w = wl.tiny(d, k, m, T, nf, seed=2500 + d + k + m + T, wdtype="bf16")
+    say(f"case batch d={d} k={k} m={m} T={T} nf={nf}")
+    g = w.groups[0]
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    worst = pu.check_group(w, g, [(0, T), (0, min(T, 5)), (T // 2, T)], dg, og)
+    name = g.maps[0][0]
+    Yd = gsi.dense_linear(dg.W[name], dg.X).cpu().numpy().astype(np.float64)
+    dense_err = pu.rel_l2_rows(Yd, O.dense_linear(og.W[name], og.X)).max()
+    say(f"  worst rel-L2 {worst:.3e}, dense {dense_err:.3e}")
+    assert dense_err <= 2e-5
+
+
+# ------------------------------------------------------------------------------------------------
 # degenerate gates
 # ------------------------------------------------------------------------------------------------
 def test_all_fire_equals_dense_and_none_fire_is_static_projection(gsi, pu):
