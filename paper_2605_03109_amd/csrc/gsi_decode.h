@@ -33,6 +33,7 @@ struct ProjTask {
   int a_rows, a_slabs, a_cblocks;  // partial projection: rows per slab, slabs, column blocks
   int b_rows, b_slabs;             // residual: rows per slab, slabs
   int udtype, xdtype;
+  int tile;                        // decode batch on the matrix cores (gsi_tile.hip) with its own slab geometry
 };
 
 struct ProjBatch {
@@ -121,6 +122,11 @@ hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEven
 // several tokens on the matrix cores (gsi_tile.hip): workspace of one map's partial products (0 when the
 // shape does not take this path), eligibility of a filled batch, launch
 size_t tile_part_bytes(int64_t m, int64_t d, int64_t B);
+// ... and the projection of a decode batch: shape eligibility, workspace, geometry of a task, launches
+bool tile_project_shape_ok(int64_t d, int64_t k, int64_t B, int udtype);
+size_t tile_project_ws(int64_t d, int64_t k, int64_t B);
+void tile_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws);
+hipError_t tile_project_launch(ProjBatch& pb, bool with_norms, bool with_gate, float eps, hipStream_t s);
 bool tile_rows_ok(const LinBatch& lb, int wdtype);
 hipError_t tile_rows_launch(LinBatch& lb, hipStream_t s);
 

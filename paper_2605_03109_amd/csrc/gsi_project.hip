@@ -10,6 +10,8 @@
 //   proj_norms     |r|, |x| from the slab shares; optionally the gate and the ordered compaction.
 //
 // All reductions have a fixed order: results are bit-identical run to run.
+#include <algorithm>
+
 #include "gsi_decode.h"
 #include "gsi_device.h"
 #include "gsi_image.h"
@@ -386,10 +388,18 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
 
 size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype) {
   const ProjGeom g = proj_geom(d, k, udtype);
-  return align_up((size_t)g.a_slabs * B * k * 4, 256) + align_up((size_t)g.b_slabs * B * 2 * 4, 256);
+  size_t need = align_up((size_t)g.a_slabs * B * k * 4, 256) + align_up((size_t)g.b_slabs * B * 2 * 4, 256);
+  if (tile_project_shape_ok(d, k, B, udtype)) need = std::max(need, tile_project_ws(d, k, B));
+  return need;
 }
 
 void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws) {
+  t.tile = 0;
+  if (tile_project_shape_ok(d, k, B, t.udtype) && t.xdtype == GSI_F32 && reinterpret_cast<uintptr_t>(t.X) % 16 == 0 &&
+      reinterpret_cast<uintptr_t>(t.C) % 16 == 0 && reinterpret_cast<uintptr_t>(t.R) % 16 == 0) {
+    tile_project_fill(t, d, k, B, ws);
+    return;
+  }
   const ProjGeom g = proj_geom(d, k, t.udtype);
   t.d = (int)d;
   t.k = (int)k;
@@ -420,6 +430,20 @@ hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s) {
 
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
                                  hipStream_t s, ImgBatch* img) {
+  // tasks of a decode batch that take the matrix-core kernels go in a launch set of their own
+  if (pb.B > 1) {
+    ProjBatch tile_pb = pb, rest = pb;
+    tile_pb.n = rest.n = 0;
+    for (int i = 0; i < pb.n; ++i) {
+      if (pb.t[i].tile) tile_pb.t[tile_pb.n++] = pb.t[i];
+      else rest.t[rest.n++] = pb.t[i];
+    }
+    if (tile_pb.n > 0) {
+      if (hipError_t e = tile_project_launch(tile_pb, with_norms, with_gate, eps, s); e != hipSuccess) return e;
+      if (rest.n == 0) return hipSuccess;
+      pb = rest;
+    }
+  }
   // the tasks are independent: the largest input goes first so that its workgroups start first
   for (int i = 1; i < pb.n; ++i)
     for (int j = i; j > 0 && (int64_t)pb.t[j].d * pb.t[j].k > (int64_t)pb.t[j - 1].d * pb.t[j - 1].k; --j) {
