@@ -67,13 +67,23 @@ const char* gsi_last_error(void) { return g_err; }
 
 int gsi_version(void) { return 100; }
 
-// ---- eligibility of the matrix-core paths (bf16 operands, K dimensions multiples of 32) -----------------
-static bool mfma_image_ok(int64_t m, int64_t d, int64_t k) { return d % 32 == 0 && m < (1ll << 30) && k < (1ll << 30); }
+// ---- eligibility of the matrix-core paths (bf16 operands, K dimensions multiples of 64) -----------------
+static bool mfma_image_ok(int64_t m, int64_t d, int64_t k) {
+  return d % 64 == 0 && m < (1ll << 30) && k < (1ll << 30) && m * k < (1ll << 31);
+}
 static bool mfma_batch_ok(int64_t d, int64_t k, int64_t B) {
-  return B > kDecodeMaxB && d % 32 == 0 && k % 32 == 0 && B < (1ll << 30);
+  return B > kDecodeMaxB && d % 64 == 0 && k % 64 == 0 && B < (1ll << 30) && B * d < (1ll << 31);
 }
 static size_t mfma_project_ws(int64_t d, int64_t k, int64_t B) {
-  return gsi::align_up((size_t)k * d * 2, 256) + gsi::align_up((size_t)gsi::mfma_res_tiles(d) * B * 2 * 4, 256);
+  return gsi::align_up((size_t)k * d * 2, 256) + gsi::align_up((size_t)gsi::mfma_res_tiles(d) * B * 2 * 4, 256) +
+         gsi::mfma_part_bytes(B, k, d, gsi::EPI_STORE_F32);
+}
+// workspace of one linear map of a call with B tokens: partial products of the decode-batch kernel, or of
+// the split contraction of the prefill-sized W term (dense = 1: of the dense product)
+static size_t map_part_bytes(int64_t m, int64_t d, int64_t B, int dense) {
+  if (B > kDecodeMaxB)
+    return d % 64 == 0 ? gsi::mfma_part_bytes(B, m, d, dense ? gsi::EPI_STORE_F32 : gsi::EPI_SCATTER_ADD) : 0;
+  return gsi::tile_part_bytes(m, d, B);
 }
 
 size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int64_t B) {
@@ -81,7 +91,7 @@ size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int6
     case GSI_CALL_BUILD_IMAGE:
       // the transposed basis of the matrix-core build (bf16 operands); generic kernels need none
       if (m < 1 || d < 1 || k < 1 || k > d || !mfma_image_ok(m, d, k)) return 0;
-      return gsi::align_up((size_t)k * d * 2, 256);
+      return gsi::align_up((size_t)k * d * 2, 256) + gsi::mfma_part_bytes(m, k, d, gsi::EPI_STORE_BF16);
     case GSI_CALL_PROJECT: {
       if (d < 1 || k < 1 || k > d || B < 1) return 0;
       if (B > kDecodeMaxB) return mfma_batch_ok(d, k, B) ? mfma_project_ws(d, k, B) : 0;
@@ -97,9 +107,9 @@ size_t gsi_workspace_bytes(int which_call, int64_t m, int64_t d, int64_t k, int6
     }
     case GSI_CALL_GATED_LINEAR:
     case GSI_CALL_DENSE_LINEAR:
-      // partial products of the several-token matrix-core kernel
+      // partial products of the matrix-core kernels
       if (m < 1 || d < 1 || B < 1) return 0;
-      return gsi::tile_part_bytes(m, d, B);
+      return map_part_bytes(m, d, B, which_call == GSI_CALL_DENSE_LINEAR);
     default:
       return 0;
   }
@@ -130,6 +140,8 @@ int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d,
       g.B = ws; g.ldb = d;
       g.D = M; g.ldd = k;
       g.M = (int)m; g.N = (int)k; g.K = (int)d;
+      if (gsi::mfma_part_bytes(m, k, d, gsi::EPI_STORE_BF16))
+        g.part = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + gsi::align_up((size_t)k * d * 2, 256));
       e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_BF16, s);
     }
   } else {
@@ -212,6 +224,9 @@ static hipError_t mfma_project(const void* U, const void* X, int64_t d, int64_t 
   g.B = Ut; g.ldb = d;
   g.D = C; g.ldd = k;
   g.M = (int)B; g.N = (int)k; g.K = (int)d;
+  if (gsi::mfma_part_bytes(B, k, d, gsi::EPI_STORE_F32))
+    g.part = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + gsi::align_up((size_t)k * d * 2, 256) +
+                                      gsi::align_up((size_t)gsi::mfma_res_tiles(d) * B * 2 * 4, 256));
   e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
   if (e != hipSuccess) return e;
   std::memset(&g, 0, sizeof(g));
@@ -242,7 +257,7 @@ static bool mfma_project_path(const void* U, const void* X, int64_t d, int64_t k
 // over the compacted list (row tiles beyond the device-side count exit at once).
 static hipError_t mfma_gated(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
                              const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, float* Y,
-                             hipStream_t s) {
+                             float* part, hipStream_t s) {
   gsi::GemmArgs g;
   std::memset(&g, 0, sizeof(g));
   g.A = C; g.lda = k; g.a_f32 = 1;
@@ -252,11 +267,14 @@ static hipError_t mfma_gated(const void* W, const void* M, const float* C, const
   hipError_t e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
   if (e != hipSuccess) return e;
   std::memset(&g, 0, sizeof(g));
-  g.A = R; g.lda = d; g.a_f32 = 1;
+  // r enters rounded once to bf16: its term is scaled by the residual ratio, so the rounding (2^-9 relative)
+  // adds a few 1e-4 of |y| at most, beside the 1.7e-3 that the bf16 image already costs
+  g.A = R; g.lda = d; g.a_f32 = 2;
   g.B = W; g.ldb = d;
   g.D = Y; g.ldd = m;
   g.M = (int)B; g.N = (int)m; g.K = (int)d;
   g.row_idx = fired_idx; g.n_rows_dev = n_fired;
+  g.part = gsi::mfma_part_bytes(B, m, d, gsi::EPI_SCATTER_ADD) ? part : nullptr;
   return gsi::mfma_gemm_nt(g, gsi::EPI_SCATTER_ADD, s);
 }
 
@@ -264,6 +282,23 @@ static bool mfma_gated_path(const void* W, const void* M, const float* C, const 
                             int64_t B, int wdtype) {
   return wdtype == GSI_BF16 && mfma_batch_ok(d, k, B) && aligned(W, 16) && aligned(M, 16) && aligned(C, 16) &&
          aligned(R, 16);
+}
+
+// Prefill-sized dense baseline on the matrix cores: Y = X W^T
+static bool mfma_dense_path(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype) {
+  return wdtype == GSI_BF16 && B > kDecodeMaxB && d % 64 == 0 && B * m < (1ll << 31) && aligned(W, 16) &&
+         aligned(X, 16);
+}
+static hipError_t mfma_dense(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int xdtype, float* Y,
+                             float* part, hipStream_t s) {
+  gsi::GemmArgs g;
+  std::memset(&g, 0, sizeof(g));
+  g.A = X; g.lda = d; g.a_f32 = xdtype == GSI_F32;
+  g.B = W; g.ldb = d;
+  g.D = Y; g.ldd = m;
+  g.M = (int)B; g.N = (int)m; g.K = (int)d;
+  g.part = gsi::mfma_part_bytes(B, m, d, gsi::EPI_STORE_F32) ? part : nullptr;
+  return gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
 }
 
 static void clear(gsi::LinBatch& lb, int64_t B) {
@@ -383,7 +418,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     e = bt.add(0, gd, W, M, (float*)Y, m, B == 1, gsi::tile_part_bytes(m, d, B) ? (float*)ws : nullptr);
     if (e == hipSuccess) e = bt.flush();
   } else if (mfma_gated_path(W, M, C, R, d, k, B, wdtype)) {
-    e = mfma_gated(W, M, C, R, fired_idx, n_fired, m, d, k, B, (float*)Y, s);
+    e = mfma_gated(W, M, C, R, fired_idx, n_fired, m, d, k, B, (float*)Y, (float*)ws, s);
   } else {
     e = gsi::generic_gated_linear(W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, (float*)Y, s);
   }
@@ -407,7 +442,9 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr) && aligned(X, 16)) {
+  if (mfma_dense_path(W, X, m, d, B, wdtype)) {
+    e = mfma_dense(W, X, m, d, B, xdtype, Y, (float*)ws, s);
+  } else if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr) && aligned(X, 16)) {
     gsi::LinBatch lb;
     clear(lb, B);
     lb.n = lb.ng = 1;
@@ -434,7 +471,7 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
   if (maps)
     for (int j = 0; j < n_maps; ++j) {
       const int id = maps[j].input_id;
-      if (id >= 0 && id < n_inputs) need += gsi::tile_part_bytes(maps[j].m, inputs[id].d, B);
+      if (id >= 0 && id < n_inputs) need += map_part_bytes(maps[j].m, inputs[id].d, B, 0);
     }
   return need;
 }
@@ -463,7 +500,7 @@ size_t gsi_dense_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
   size_t need = 0;  // partial products of the several-token matrix-core kernel, one region per map
   for (int j = 0; j < n_maps; ++j) {
     const int id = maps[j].input_id;
-    if (id >= 0 && id < n_inputs) need += gsi::tile_part_bytes(maps[j].m, inputs[id].d, B);
+    if (id >= 0 && id < n_inputs) need += map_part_bytes(maps[j].m, inputs[id].d, B, 1);
   }
   return need;
 }
@@ -497,12 +534,20 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
   {
     size_t off = 0;
     for (int j = 0; j < n_maps; ++j) {
-      const size_t pb = gsi::tile_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B);
+      const size_t pb = map_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B, 1);
       if (pb) part[j] = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + off);
       off += pb;
     }
   }
   std::vector<char> done(n_maps, 0);
+  for (int j = 0; j < n_maps; ++j) {  // prefill-sized batches: one matrix-core product per map
+    const gsi_map_desc& mp = maps[j];
+    const gsi_input_desc& in = inputs[mp.input_id];
+    if (!mfma_dense_path(mp.W, in.X, mp.m, in.d, B, mp.wdtype)) continue;
+    if (hipError_t e = mfma_dense(mp.W, in.X, mp.m, in.d, B, in.xdtype, mp.Y, part[j], s); e != hipSuccess)
+      return hip_fail(e, fn);
+    done[j] = 1;
+  }
   for (int dt = 0; dt < 2; ++dt) {
     LinBatcher bt;
     bt.wdtype = dt; bt.s = s;
@@ -510,7 +555,8 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     for (int j = 0; j < n_maps; ++j) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
-      if (mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr) || !aligned(in.X, 16))
+      if (done[j] || mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr) ||
+          !aligned(in.X, 16))
         continue;
       gsi::LinGroup gd;
       std::memset(&gd, 0, sizeof(gd));
@@ -580,7 +626,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       off += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
     }
     for (int j = 0; j < n_maps; ++j) {
-      const size_t pb = gsi::tile_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B);
+      const size_t pb = map_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B, 0);
       if (pb) part[j] = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + off);
       off += pb;
     }
@@ -720,7 +766,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       if (map_done[j] != 2 && B > 0) {
         hipError_t e;
         if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype))
-          e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, s);
+          e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, part[j], s);
         else
           e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
                                         mp.wdtype, mp.Y, s);

@@ -10,12 +10,12 @@ enum { EPI_STORE_BF16 = 0, EPI_STORE_F32 = 1, EPI_RESIDUAL = 2, EPI_SCATTER_ADD 
 struct GemmArgs {
   const void* A;
   int64_t lda;
-  int a_f32;
+  int a_f32;                  // A is 0: bf16; 1: fp32, fed as bf16 head + tail (two passes); 2: fp32, rounded once to bf16
   const void* B;
   int64_t ldb;
   void* D;                    // bf16 or fp32 [.., ldd]
   int64_t ldd;
-  int M, N, K;                // K a multiple of 32
+  int M, N, K;                // K a multiple of 64; M * N below 2^31
   const int32_t* row_idx;     // optional: row i of A is A[row_idx[i]], and (scatter-add) row i of D is D[row_idx[i]]
   const int32_t* n_rows_dev;  // optional: device count of valid rows (<= M)
   // residual epilogue: D = X - A B^T and per-row partial sums of squares
@@ -24,7 +24,15 @@ struct GemmArgs {
   int64_t ldx;
   float* part_n;              // [tiles of N][part_tokens][2]
   int part_tokens;
+  // split contraction: workspace [splits][M][N] of partial sums, or null (then no split); `splits` is set
+  // by mfma_gemm_nt from mfma_splits()
+  float* part;
+  int splits;
 };
+
+// how many ways mfma_gemm_nt splits the contraction of an M x N x K problem, and the workspace that takes
+int mfma_splits(int64_t M, int64_t N, int64_t K, int epi);
+size_t mfma_part_bytes(int64_t M, int64_t N, int64_t K, int epi);
 
 hipError_t mfma_gemm_nt(const GemmArgs& g, int epi, hipStream_t s);
 hipError_t mfma_transpose_bf16(const void* U, void* Ut, int rows, int cols, hipStream_t s);

@@ -336,6 +336,27 @@ __global__ __launch_bounds__(kBlock) void proj_norms(const ProjBatch pb, int do_
   if (do_gate && threadIdx.x == 0) p.n_fired[0] = base;
 }
 
+// |r|, |x| for many tokens: one thread per token adds the slab shares in slab order (neighbouring
+// threads read neighbouring tokens of a slab).  The gate, when asked for, follows as its own launch.
+__global__ __launch_bounds__(kBlock) void norms_tokens(const ProjBatch pb) {
+  const ProjTask& p = pb.t[blockIdx.y];
+  const int B = pb.B;
+  const int t = blockIdx.x * kBlock + threadIdx.x;
+  if (t >= B) return;
+  const float2* src = reinterpret_cast<const float2*>(p.part_n) + t;
+  float sr = 0.f, sx = 0.f;
+  for (int s0 = 0; s0 < p.b_slabs; s0 += 8) {
+    float2 q[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) q[u] = src[(int64_t)min(s0 + u, p.b_slabs - 1) * B];
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < p.b_slabs) { sr += q[u].x; sx += q[u].y; }
+  }
+  p.rnorm[t] = sqrtf(sr);
+  p.xnorm[t] = sqrtf(sx);
+}
+
 // stand-alone image launch (one token): y = M c with c read from C
 template <class T>
 __global__ __launch_bounds__(kBlock) void image_rows(const ImgBatch ib) {
@@ -411,6 +432,18 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
 
 hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s) {
   if (pb.n == 0 || pb.B == 0) return hipSuccess;
+  if (pb.B > 4 * kBlock) {  // many tokens: a thread per token, then the stand-alone gate kernel per input
+    const dim3 grid((unsigned)ceil_div(pb.B, kBlock), (unsigned)pb.n);
+    norms_tokens<<<grid, kBlock, 0, s>>>(pb);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    if (with_gate)
+      for (int i = 0; i < pb.n; ++i)
+        if (hipError_t e = launch_gate(pb.t[i].rnorm, pb.t[i].xnorm, pb.B, eps, pb.t[i].mask, pb.t[i].fired_idx,
+                                       pb.t[i].n_fired, s);
+            e != hipSuccess)
+          return e;
+    return hipSuccess;
+  }
   proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
   return hipGetLastError();
 }

@@ -98,13 +98,28 @@ def check_projection(res_gpu: dict, ref: dict, eps: float):
     return mask
 
 
+PREFILL_TOKENS = 128  # calls with more tokens take the GEMM path, which feeds r rounded once to bf16
+
+
 def check_outputs(Y_gpu: torch.Tensor, W64, M64_exact, M_dev_bits, wdtype: str, ref: dict, mask_gpu, m_small=256):
-    """y against the oracle with the exact image (bar TOL_Y) and with the device's stored image (stage bar)."""
+    """y against the oracle with the exact image (bar TOL_Y) and with the device's stored image (stage bar).
+
+    Stage bar: 2e-5 (fp32 accumulation only).  In a call of more than 128 tokens with bf16 weights the W r
+    term of a fired token is computed from r rounded to bf16 (each element within 2^-9 relative); the bar
+    of such a token widens by 2^-8 |W r| / |y|, twice the root-mean-square size of that rounding.
+    """
     Y = Y_gpu.cpu().numpy().astype(np.float64)
     Mdev = O.widen(M_dev_bits, wdtype)
     Y_stage = O.gated_linear(W64, Mdev, ref["C"], ref["R"], mask_gpu)
     e_stage = rel_l2_rows(Y, Y_stage)
-    assert np.all(e_stage <= TOL_Y_STAGE[wdtype]), f"stage rel-L2 {e_stage.max():.3e}"
+    stage_bar = np.full(Y.shape[0], TOL_Y_STAGE[wdtype])
+    if wdtype == "bf16" and Y.shape[0] > PREFILL_TOKENS:
+        fired = np.asarray(mask_gpu).astype(bool)
+        if fired.any():
+            wr = np.linalg.norm(O.dense_linear(W64, ref["R"][fired]), axis=1)
+            yn = np.maximum(np.linalg.norm(Y_stage[fired], axis=1), 1e-300)
+            stage_bar[fired] += 2.0**-8 * wr / yn
+    assert np.all(e_stage <= stage_bar), f"stage rel-L2 {e_stage.max():.3e} (worst excess {(e_stage / stage_bar).max():.2f} x bar)"
     Y_exact = O.gated_linear(W64, M64_exact, ref["C"], ref["R"], mask_gpu)
     e = rel_l2_rows(Y, Y_exact)
     if Y.shape[1] >= m_small:  # the statistical bf16 storage bound needs a long output vector

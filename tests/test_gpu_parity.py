@@ -384,7 +384,8 @@ def test_timed_stack_and_dense_stack_match_plain_calls(gsi, pu):
 # dimension of the 128 x 128 tiles, fp32 and bf16 activations
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("d,k,m,T,nf,xdtype", [(1024, 64, 520, 300, 60, "f32"), (2048, 128, 1000, 200, 41, "bf16"),
-                                               (512, 32, 384, 129, 0, "f32"), (1024, 256, 300, 257, 257, "bf16")])
+                                               (512, 32, 384, 129, 0, "f32"), (1024, 256, 300, 257, 257, "bf16"),
+                                               (512, 64, 264, 1100, 100, "bf16")])
 def test_prefill_sized_batch(gsi, pu, d, k, m, T, nf, xdtype):
     w = wl.tiny(d, k, m, T, nf, seed=4000 + d + k + T, wdtype="bf16", xdtype=xdtype)
     say(f"case prefill d={d} k={k} m={m} T={T} nf={nf} x={xdtype}")
