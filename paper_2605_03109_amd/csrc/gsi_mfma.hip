@@ -9,13 +9,11 @@
 // on the main term is not rounded to 8 bits (the bf16 image already uses most of the 2e-3 budget).
 //
 // Workgroup tile 256 x 128 x 64, four waves stacked along M, each wave 64 x 128 as 2 x 4
-// v_mfma_f32_32x32x16_bf16 tiles.  A wave is the only reader of its 64 rows of A, so A never goes through
-// LDS: a lane loads its MFMA operands straight from memory.  The 64 columns of a k-tile are dealt so that
-// the lane half l/32 owns 32 consecutive columns and step j of the tile takes their j-th group of eight
-// (any order of the contraction index is as good as another as long as both operands agree), which makes a
-// lane's four loads of a tile one contiguous 64-byte run and a row's two halves one 128-byte line.  The
-// B tile (128 x 64) is shared by the four waves through LDS (row stride padded to 144 bytes: conflict-free
-// 128-bit reads), double-buffered, loaded a tile ahead through registers like the A operands.
+// v_mfma_f32_32x32x16_bf16 tiles.  Both operand tiles are staged in LDS as bf16 (row stride padded to 144
+// bytes: conflict-free 128-bit reads); an fp32 A operand is converted on the way in.  Global loads are
+// whole 128-byte row segments per eight lanes; the next k-tile travels to registers during the MFMAs of the
+// current one.  Within a k-tile the lane half l/32 takes 32 consecutive columns, eight per MFMA step: any
+// order of the contraction index is as good as another as long as both operands agree.
 // Problems with few output tiles split the contraction over blockIdx.z; the partial sums go to the workspace
 // and a second kernel adds them in split order and applies the epilogue.
 // Operands that are N-contiguous in memory (U as the right factor of W U and X U) are transposed
@@ -32,103 +30,97 @@ typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
 constexpr int BM = 256, BN = 128, BK = 64;
-constexpr int LDB = BK + 8;  // padded LDS row stride of the B tile, bf16 elements (144 bytes)
+constexpr int LDB = BK + 8;  // padded LDS row stride of a staged tile, bf16 elements (144 bytes)
 constexpr int kThreads = 256;
 constexpr int kAF = 2, kBF = 4, kKS = BK / 16;  // A fragments, B fragments per wave; MFMA steps per k-tile
-
-// AM: how the A operand is stored and fed: 0 bf16; 1 fp32, split into bf16 head + tail (two MFMA passes);
-// 2 fp32, rounded once to bf16 (one pass)
-template <int AM>
-struct AOps {
-  uint4 r[kAF][kKS][AM ? 2 : 1];
-};
-
-__device__ __forceinline__ void split_f32x8(const uint4& a, const uint4& b, bf16x8& hi, bf16x8& lo) {
-  const float x[8] = {__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z), __uint_as_float(a.w),
-                      __uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w)};
-#pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const __bf16 h = (__bf16)x[e];
-    hi[e] = h;
-    lo[e] = (__bf16)(x[e] - __uint_as_float((uint32_t)__builtin_bit_cast(uint16_t, h) << 16));
-  }
-}
+constexpr int kAU = BM * BK / 8 / kThreads;     // staging units (8 elements of a row) of A per thread: 8
+constexpr int kBU = BN * BK / 8 / kThreads;     // ... of B: 4
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a native vector: loads and stores of it are
                                                               // instructions, not aggregate copies
-__device__ __forceinline__ bf16x8 round_f32x8(const uint4& a, const uint4& b) {
-  const float x[8] = {__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z), __uint_as_float(a.w),
-                      __uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w)};
-  bf16x8 r;
+
+// AM: how the A operand is stored and fed: 0 bf16; 1 fp32, split into bf16 head + tail (two LDS tiles, two
+// MFMA passes); 2 fp32, rounded once to bf16
+template <int AM>
+struct Stage {
+  u32x4 a[kAU][AM ? 2 : 1];
+  u32x4 b[kBU];
+};
+
+// 8 fp32 -> 8 bf16 (RNE), and the bf16 of what is left
+__device__ __forceinline__ u32x4 round8(const u32x4& x0, const u32x4& x1, u32x4* tail) {
+  const float x[8] = {__uint_as_float(x0[0]), __uint_as_float(x0[1]), __uint_as_float(x0[2]), __uint_as_float(x0[3]),
+                      __uint_as_float(x1[0]), __uint_as_float(x1[1]), __uint_as_float(x1[2]), __uint_as_float(x1[3])};
+  uint16_t h[8], l[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) r[e] = (__bf16)x[e];
-  return r;
+  for (int e = 0; e < 8; ++e) {
+    const __bf16 hb = (__bf16)x[e];
+    h[e] = __builtin_bit_cast(uint16_t, hb);
+    const __bf16 lb = (__bf16)(x[e] - __uint_as_float((uint32_t)h[e] << 16));
+    l[e] = __builtin_bit_cast(uint16_t, lb);
+  }
+  if (tail)
+    *tail = u32x4{(uint32_t)l[0] | ((uint32_t)l[1] << 16), (uint32_t)l[2] | ((uint32_t)l[3] << 16),
+                  (uint32_t)l[4] | ((uint32_t)l[5] << 16), (uint32_t)l[6] | ((uint32_t)l[7] << 16)};
+  return u32x4{(uint32_t)h[0] | ((uint32_t)h[1] << 16), (uint32_t)h[2] | ((uint32_t)h[3] << 16),
+               (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16)};
 }
 
-struct BOps {
-  u32x4 r[4];
-};
-
-struct Tiles {
-  int kt1;       // end of this split's k-tiles
-  int lc, lh;    // lane % 32, lane / 32
-};
-
-// A operands of k-tile kt for the lane's rows.  Past the split's range the last tile is repeated (and not
-// consumed).
+// requests k-tile kt of both operands (unit u of a thread: row (tid >> 3) + 32 u, columns 8 (tid & 7) .. + 8)
 template <int AM>
-__device__ __forceinline__ void load_a(AOps<AM>& a, const char* const (&aptr)[kAF], int kt, const Tiles& t) {
+__device__ __forceinline__ void issue(Stage<AM>& st, const char* const (&ap)[kAU], const char* const (&bp)[kBU], int kt) {
   constexpr int ES = AM ? 4 : 2;
-  const int ktc = kt < t.kt1 ? kt : t.kt1 - 1;
-  const int half = t.lh;
 #pragma unroll
-  for (int i = 0; i < kAF; ++i)
+  for (int u = 0; u < kAU; ++u) {
+    const char* p = ap[u] + (int64_t)kt * BK * ES;
+    st.a[u][0] = *reinterpret_cast<const u32x4*>(p);
+    if constexpr (AM != 0) st.a[u][1] = *reinterpret_cast<const u32x4*>(p + 16);
+  }
 #pragma unroll
-    for (int j = 0; j < kKS; ++j) {
-      const char* p = aptr[i] + ((int64_t)ktc * BK + 32 * half + 8 * j) * ES;
-      a.r[i][j][0] = *reinterpret_cast<const uint4*>(p);
-      if constexpr (AM != 0) a.r[i][j][1] = *reinterpret_cast<const uint4*>(p + 16);
-    }
+  for (int u = 0; u < kBU; ++u) st.b[u] = *reinterpret_cast<const u32x4*>(bp[u] + (int64_t)kt * BK * 2);
 }
 
-__device__ __forceinline__ void load_b(BOps& b, const char* const (&bptr)[4], const int (&bch)[4], int kt,
-                                       const Tiles& t) {
-  const int ktc = kt < t.kt1 ? kt : t.kt1 - 1;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) b.r[u] = *reinterpret_cast<const u32x4*>(bptr[u] + ((int64_t)ktc * BK + 8 * bch[u]) * 2);
-}
-
-__device__ __forceinline__ void store_b(const BOps& b, uint16_t (*Bs)[LDB], const int (&brow)[4], const int (&bch)[4]) {
-#pragma unroll
-  for (int u = 0; u < 4; ++u) *reinterpret_cast<u32x4*>(&Bs[brow[u]][8 * bch[u]]) = b.r[u];
-}
-
+// writes the staged k-tile to LDS as bf16 (fp32 A: rounded, or head and tail tiles)
 template <int AM>
-__device__ __forceinline__ void compute(const AOps<AM>& a, const uint16_t (*Bs)[LDB], const Tiles& t,
+__device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t (*As)[BM][LDB], uint16_t (*Bs)[LDB], int tid) {
+  const int r0 = tid >> 3, c8 = 8 * (tid & 7);
+#pragma unroll
+  for (int u = 0; u < kAU; ++u) {
+    u32x4* d0 = reinterpret_cast<u32x4*>(&As[0][r0 + 32 * u][c8]);
+    if constexpr (AM == 0) {
+      *d0 = st.a[u][0];
+    } else if constexpr (AM == 2) {
+      *d0 = round8(st.a[u][0], st.a[u][1], nullptr);
+    } else {
+      u32x4 tail;
+      *d0 = round8(st.a[u][0], st.a[u][1], &tail);
+      *reinterpret_cast<u32x4*>(&As[1][r0 + 32 * u][c8]) = tail;
+    }
+  }
+#pragma unroll
+  for (int u = 0; u < kBU; ++u) *reinterpret_cast<u32x4*>(&Bs[r0 + 32 * u][c8]) = st.b[u];
+}
+
+// one k-tile from LDS: lane half lh takes columns 32 lh .. + 32 of the tile, eight per MFMA step (both
+// operands in the same order, so the order of the contraction index does not matter)
+template <int AM>
+__device__ __forceinline__ void compute(const uint16_t (*As)[BM][LDB], const uint16_t (*Bs)[LDB], int wave, int lc, int lh,
                                         f32x16 (&acc)[kAF][kBF]) {
 #pragma unroll
   for (int j = 0; j < kKS; ++j) {
+    const int col = 32 * lh + 8 * j;
     bf16x8 b[kBF];
 #pragma unroll
-    for (int n = 0; n < kBF; ++n) b[n] = *reinterpret_cast<const bf16x8*>(&Bs[32 * n + t.lc][32 * t.lh + 8 * j]);
+    for (int n = 0; n < kBF; ++n) b[n] = *reinterpret_cast<const bf16x8*>(&Bs[32 * n + lc][col]);
 #pragma unroll
     for (int i = 0; i < kAF; ++i) {
-      if constexpr (AM == 2) {
-        const bf16x8 av = round_f32x8(a.r[i][j][0], a.r[i][j][1]);
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[0][64 * wave + 32 * i + lc][col]);
 #pragma unroll
-        for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b[n], acc[i][n], 0, 0, 0);
-      } else if constexpr (AM == 1) {
-        bf16x8 hi, lo;
-        split_f32x8(a.r[i][j][0], a.r[i][j][1], hi, lo);
+      for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[n], acc[i][n], 0, 0, 0);
+      if constexpr (AM == 1) {
+        const bf16x8 al = *reinterpret_cast<const bf16x8*>(&As[1][64 * wave + 32 * i + lc][col]);
 #pragma unroll
-        for (int n = 0; n < kBF; ++n) {
-          acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(hi, b[n], acc[i][n], 0, 0, 0);
-          acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lo, b[n], acc[i][n], 0, 0, 0);
-        }
-      } else {
-        const bf16x8 av = __builtin_bit_cast(bf16x8, a.r[i][j][0]);
-#pragma unroll
-        for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(av, b[n], acc[i][n], 0, 0, 0);
+        for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b[n], acc[i][n], 0, 0, 0);
       }
     }
   }
@@ -136,7 +128,8 @@ __device__ __forceinline__ void compute(const AOps<AM>& a, const uint16_t (*Bs)[
 
 template <int AM, int EPI>
 __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
-  __shared__ __align__(16) uint16_t Bs[2][BN][LDB];
+  __shared__ __align__(16) uint16_t As[AM == 1 ? 2 : 1][BM][LDB];
+  __shared__ __align__(16) uint16_t Bs[BN][LDB];
 
   int Mrows = g.M;
   if (g.n_rows_dev) {
@@ -155,26 +148,22 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   const int splits = g.splits > 1 ? g.splits : 1;
   const int kt0 = (int)(((int64_t)nk * blockIdx.z) / splits), kt1 = (int)(((int64_t)nk * (blockIdx.z + 1)) / splits);
 
-  // ---- A: per-lane row pointers (rows past the end repeat the last one and are not stored) -----------
-  const char* aptr[kAF];
+  // staging pointers: a thread's unit u is row (tid >> 3) + 32 u of the tile, 8 columns at 8 (tid & 7); rows past
+  // the end repeat the last one (their results are not stored)
+  const char* ap[kAU];
+  const char* bp[kBU];
 #pragma unroll
-  for (int i = 0; i < kAF; ++i) {
-    int grow = tile_m * BM + wave * 64 + i * 32 + lc;
+  for (int u = 0; u < kAU; ++u) {
+    int grow = tile_m * BM + (tid >> 3) + 32 * u;
     grow = grow < Mrows ? grow : Mrows - 1;
     if (g.row_idx) grow = g.row_idx[grow];
-    aptr[i] = reinterpret_cast<const char*>(g.A) + (int64_t)grow * g.lda * ES;
+    ap[u] = reinterpret_cast<const char*>(g.A) + ((int64_t)grow * g.lda + 8 * (tid & 7)) * ES;
   }
-  // ---- B: 128 rows x 8 chunks of 16 bytes per k-tile, four chunks per thread ---------------------------
-  const char* bptr[4];
-  int brow[4], bch[4];
 #pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int q = tid + kThreads * u;
-    brow[u] = q >> 3;
-    bch[u] = q & 7;
-    int grow = tile_n * BN + brow[u];
+  for (int u = 0; u < kBU; ++u) {
+    int grow = tile_n * BN + (tid >> 3) + 32 * u;
     grow = grow < g.N ? grow : g.N - 1;
-    bptr[u] = reinterpret_cast<const char*>(g.B) + (int64_t)grow * g.ldb * 2;
+    bp[u] = reinterpret_cast<const char*>(g.B) + ((int64_t)grow * g.ldb + 8 * (tid & 7)) * 2;
   }
 
   f32x16 acc[kAF][kBF];
@@ -186,31 +175,20 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   if (kt0 < kt1) {
-    const Tiles tl{kt1, lc, lh};
-    AOps<AM> a0, a1;
-    BOps b;
-    load_a<AM>(a0, aptr, kt0, tl);
-    load_b(b, bptr, bch, kt0, tl);
-    store_b(b, Bs[0], brow, bch);
+    Stage<AM> st;
+    issue<AM>(st, ap, bp, kt0);
+    commit<AM>(st, As, Bs, tid);
     __syncthreads();
-    for (int kt = kt0; kt < kt1; kt += 2) {
-      // tile kt from (a0, buffer 0); tile kt+1 from (a1, buffer 1)
+    for (int kt = kt0; kt < kt1; ++kt) {
+      // the next k-tile travels from memory to registers while this one is multiplied (past the range the
+      // last tile is requested again and never used)
       __builtin_amdgcn_sched_barrier(0);
-      load_a<AM>(a1, aptr, kt + 1, tl);
-      load_b(b, bptr, bch, kt + 1, tl);
+      issue<AM>(st, ap, bp, kt + 1 < kt1 ? kt + 1 : kt);
       __builtin_amdgcn_sched_barrier(0);
-      compute<AM>(a0, Bs[0], tl, acc);
-      store_b(b, Bs[1], brow, bch);
+      compute<AM>(As, Bs, wave, lc, lh, acc);
+      __syncthreads();  // every wave has read the tile
+      commit<AM>(st, As, Bs, tid);
       __syncthreads();
-      if (kt + 1 < kt1) {  // uniform
-        __builtin_amdgcn_sched_barrier(0);
-        load_a<AM>(a0, aptr, kt + 2, tl);
-        load_b(b, bptr, bch, kt + 2, tl);
-        __builtin_amdgcn_sched_barrier(0);
-        compute<AM>(a1, Bs[1], tl, acc);
-        store_b(b, Bs[0], brow, bch);
-        __syncthreads();
-      }
     }
   }
 
