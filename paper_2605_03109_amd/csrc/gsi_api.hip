@@ -69,7 +69,7 @@ int gsi_version(void) { return 100; }
 
 // ---- eligibility of the matrix-core paths (bf16 operands, K dimensions multiples of 64) -----------------
 static bool mfma_image_ok(int64_t m, int64_t d, int64_t k) {
-  return d % 64 == 0 && m < (1ll << 30) && k < (1ll << 30) && m * k < (1ll << 31);
+  return d % 64 == 0 && k % 4 == 0 && m < (1ll << 30) && k < (1ll << 30) && m * k < (1ll << 31);
 }
 static bool mfma_batch_ok(int64_t d, int64_t k, int64_t B) {
   return B > kDecodeMaxB && d % 64 == 0 && k % 64 == 0 && B < (1ll << 30) && B * d < (1ll << 31);
@@ -130,7 +130,7 @@ int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d,
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (wdtype == GSI_BF16 && mfma_image_ok(m, d, k) && aligned(W, 16) && aligned(U, 2) && aligned(M, 2)) {
+  if (wdtype == GSI_BF16 && mfma_image_ok(m, d, k) && aligned(W, 16) && aligned(U, 2) && aligned(M, 8)) {
     // matrix cores: M = W (U^T)^T with the basis transposed once into the workspace
     e = gsi::mfma_transpose_bf16(U, ws, (int)d, (int)k, s);
     if (e == hipSuccess) {
@@ -250,7 +250,7 @@ static hipError_t mfma_project(const void* U, const void* X, int64_t d, int64_t 
 static bool mfma_project_path(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype,
                               const float* C, const float* R) {
   return udtype == GSI_BF16 && mfma_batch_ok(d, k, B) && aligned(U, 16) && aligned(X, 16) && aligned(C, 16) &&
-         aligned(R, 4) && (xdtype == GSI_F32 || xdtype == GSI_BF16);
+         aligned(R, 16) && (xdtype == GSI_F32 || xdtype == GSI_BF16);
 }
 
 // Prefill-sized gated map on the matrix cores: Y = C M^T for every token, then Y[fired] += R[fired] W^T
@@ -279,15 +279,16 @@ static hipError_t mfma_gated(const void* W, const void* M, const float* C, const
 }
 
 static bool mfma_gated_path(const void* W, const void* M, const float* C, const float* R, int64_t d, int64_t k,
-                            int64_t B, int wdtype) {
+                            int64_t B, int wdtype, int64_t m, const void* Y) {
   return wdtype == GSI_BF16 && mfma_batch_ok(d, k, B) && aligned(W, 16) && aligned(M, 16) && aligned(C, 16) &&
-         aligned(R, 16);
+         aligned(R, 16) && m % 4 == 0 && B * m < (1ll << 31) && aligned(Y, 16);
 }
 
 // Prefill-sized dense baseline on the matrix cores: Y = X W^T
-static bool mfma_dense_path(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype) {
-  return wdtype == GSI_BF16 && B > kDecodeMaxB && d % 64 == 0 && B * m < (1ll << 31) && aligned(W, 16) &&
-         aligned(X, 16);
+static bool mfma_dense_path(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype,
+                            const void* Y) {
+  return wdtype == GSI_BF16 && B > kDecodeMaxB && d % 64 == 0 && m % 4 == 0 && B * m < (1ll << 31) &&
+         aligned(W, 16) && aligned(X, 16) && aligned(Y, 16);
 }
 static hipError_t mfma_dense(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int xdtype, float* Y,
                              float* part, hipStream_t s) {
@@ -406,7 +407,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype) && gsi::decode_linear_ok(m, d, k, wdtype, W, M) &&
+  if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype, m, Y) && gsi::decode_linear_ok(m, d, k, wdtype, W, M) &&
       aligned(C, 16) && aligned(R, 16)) {
     LinBatcher bt;
     bt.wdtype = wdtype; bt.s = s;
@@ -417,7 +418,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     gd.d = (int)d; gd.k = (int)k;
     e = bt.add(0, gd, W, M, (float*)Y, m, B == 1, gsi::tile_part_bytes(m, d, B) ? (float*)ws : nullptr);
     if (e == hipSuccess) e = bt.flush();
-  } else if (mfma_gated_path(W, M, C, R, d, k, B, wdtype)) {
+  } else if (mfma_gated_path(W, M, C, R, d, k, B, wdtype, m, Y)) {
     e = mfma_gated(W, M, C, R, fired_idx, n_fired, m, d, k, B, (float*)Y, (float*)ws, s);
   } else {
     e = gsi::generic_gated_linear(W, M, C, R, fired_idx, n_fired, m, d, k, B, wdtype, (float*)Y, s);
@@ -442,7 +443,7 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (mfma_dense_path(W, X, m, d, B, wdtype)) {
+  if (mfma_dense_path(W, X, m, d, B, wdtype, Y)) {
     e = mfma_dense(W, X, m, d, B, xdtype, Y, (float*)ws, s);
   } else if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr) && aligned(X, 16)) {
     gsi::LinBatch lb;
@@ -543,7 +544,7 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
   for (int j = 0; j < n_maps; ++j) {  // prefill-sized batches: one matrix-core product per map
     const gsi_map_desc& mp = maps[j];
     const gsi_input_desc& in = inputs[mp.input_id];
-    if (!mfma_dense_path(mp.W, in.X, mp.m, in.d, B, mp.wdtype)) continue;
+    if (!mfma_dense_path(mp.W, in.X, mp.m, in.d, B, mp.wdtype, mp.Y)) continue;
     if (hipError_t e = mfma_dense(mp.W, in.X, mp.m, in.d, B, in.xdtype, mp.Y, part[j], s); e != hipSuccess)
       return hip_fail(e, fn);
     done[j] = 1;
@@ -738,7 +739,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           const gsi_input_desc& in = inputs[mp.input_id];
           if (map_done[j] || mp.wdtype != dt || B == 0) continue;
           if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
-          if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype)) continue;  // matrix cores below
+          if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y)) continue;  // matrix cores below
           if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
               !aligned(in.R, 16))
             continue;
@@ -765,7 +766,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       const gsi_input_desc& in = inputs[mp.input_id];
       if (map_done[j] != 2 && B > 0) {
         hipError_t e;
-        if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype))
+        if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y))
           e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, part[j], s);
         else
           e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,

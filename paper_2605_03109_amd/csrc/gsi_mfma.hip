@@ -192,76 +192,99 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
     }
   }
 
-  // ---- epilogue: element v of lane l of tile (i, n) is row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 ----
-  const int rsub = lh * 4;
-  const int row_base = tile_m * BM + wave * 64, col_base = tile_n * BN;
-  if (g.splits > 1) {  // partial sums of this split; the finishing kernel applies the epilogue
-    float* part = g.part + (int64_t)blockIdx.z * g.M * g.N;
+  // ---- epilogue --------------------------------------------------------------------------------------
+  // Element v of lane l of fragment (i, n) is row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of the
+  // fragment.  The accumulators go through LDS sixteen rows at a time (a private strip per wave), so that
+  // what touches memory is row-contiguous: a lane then owns four consecutive columns of a row.
+  __syncthreads();  // the operand tiles are no longer read
+  constexpr int kSR = 16, kSLD = BN + 4;  // strip rows, padded strip stride (floats)
+  float* strip = reinterpret_cast<float*>(&As[0][0][0]) + wave * (kSR * kSLD);
+  const bool partial = g.splits > 1;
+  float* const pdst = partial ? g.part + (int64_t)blockIdx.z * g.M * g.N : nullptr;
+  const int er = lane >> 5, ec = 4 * (lane & 31);  // row parity and first column of the lane's reads
 #pragma unroll
-    for (int i = 0; i < kAF; ++i)
+  for (int c = 0; c < 64 / kSR; ++c) {
+    const int i = c >> 1, vbase = 8 * (c & 1);
 #pragma unroll
-      for (int n = 0; n < kBF; ++n)
+    for (int vv = 0; vv < 8; ++vv) {
+      const int rl = 8 * (vv >> 2) + 4 * lh + (vv & 3);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row_base + i * 32 + 8 * (v / 4) + rsub + (v % 4), col = col_base + 32 * n + lc;
-          if (row < Mrows && col < g.N) part[(int64_t)row * g.N + col] = acc[i][n][v];
-        }
-    return;
-  }
-  if constexpr (EPI == EPI_RESIDUAL) {
-    // r = x - acc; R written; per row the sums of r^2 and x^2 over this workgroup's 128 columns (the wave
-    // holds all of them for its rows: four fragments in the lane, 32 lanes per row)
+      for (int n = 0; n < kBF; ++n) strip[rl * kSLD + 32 * n + lc] = acc[i][n][vbase + vv];
+    }
+    __syncthreads();
+    const int col = tile_n * BN + ec;
+    float4 val[kSR / 2];
+    int row[kSR / 2];
 #pragma unroll
-    for (int i = 0; i < kAF; ++i) {
+    for (int q = 0; q < kSR / 2; ++q) {
+      row[q] = tile_m * BM + wave * 64 + kSR * c + 2 * q + er;
+      val[q] = *reinterpret_cast<const float4*>(&strip[(2 * q + er) * kSLD + ec]);
+    }
+    if (partial) {
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        const int row = row_base + i * 32 + 8 * (v / 4) + rsub + (v % 4);
-        float sr = 0.f, sx = 0.f;
+      for (int q = 0; q < kSR / 2; ++q)
+        if (row[q] < Mrows && col < g.N)  // N is a multiple of 4 here (checked on the host)
+          *reinterpret_cast<float4*>(pdst + (int64_t)row[q] * g.N + col) = val[q];
+    } else if constexpr (EPI == EPI_RESIDUAL) {
+      // r = x - acc; R written; per row the sums of r^2 and x^2 over this workgroup's 128 columns
+      float4 x[kSR / 2];
 #pragma unroll
-        for (int n = 0; n < kBF; ++n) {
-          const int col = col_base + 32 * n + lc;
-          if (row < Mrows && col < g.N) {
-            const float x = load_act(g.X, g.xdtype, (int64_t)row * g.ldx + col);
-            const float r = x - acc[i][n][v];
-            reinterpret_cast<float*>(g.D)[(int64_t)row * g.ldd + col] = r;
-            sr = fmaf(r, r, sr);
-            sx = fmaf(x, x, sx);
+      for (int q = 0; q < kSR / 2; ++q) {
+        x[q] = float4{0.f, 0.f, 0.f, 0.f};
+        if (row[q] < Mrows && col < g.N) {
+          if (g.xdtype == GSI_F32) {
+            x[q] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.X) + (int64_t)row[q] * g.ldx + col);
+          } else {
+            const uint2 xb = *reinterpret_cast<const uint2*>(reinterpret_cast<const uint16_t*>(g.X) + (int64_t)row[q] * g.ldx + col);
+            x[q] = float4{bf16_lo(xb.x), bf16_hi(xb.x), bf16_lo(xb.y), bf16_hi(xb.y)};
           }
+        }
+      }
+#pragma unroll
+      for (int q = 0; q < kSR / 2; ++q) {
+        const bool live = row[q] < Mrows && col < g.N;
+        const float4 r = float4{x[q].x - val[q].x, x[q].y - val[q].y, x[q].z - val[q].z, x[q].w - val[q].w};
+        float sr = 0.f, sx = 0.f;
+        if (live) {
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)row[q] * g.ldd + col) = r;
+          sr = fmaf(r.x, r.x, fmaf(r.y, r.y, fmaf(r.z, r.z, r.w * r.w)));
+          sx = fmaf(x[q].x, x[q].x, fmaf(x[q].y, x[q].y, fmaf(x[q].z, x[q].z, x[q].w * x[q].w)));
         }
         sr = group_sum_rt(sr, 32);
         sx = group_sum_rt(sx, 32);
-        if (lc == 0 && row < Mrows) {
-          float* pn = g.part_n + ((int64_t)tile_n * g.part_tokens + row) * 2;
+        if ((lane & 31) == 0 && row[q] < Mrows) {
+          float* pn = g.part_n + ((int64_t)tile_n * g.part_tokens + row[q]) * 2;
           pn[0] = sr;
           pn[1] = sx;
         }
       }
-    }
-  } else {
+    } else {
 #pragma unroll
-    for (int i = 0; i < kAF; ++i)
-#pragma unroll
-      for (int n = 0; n < kBF; ++n)
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const int row = row_base + i * 32 + 8 * (v / 4) + rsub + (v % 4), col = col_base + 32 * n + lc;
-          if (row < Mrows && col < g.N) {
-            const float val = acc[i][n][v];
-            if constexpr (EPI == EPI_STORE_BF16) {
-              reinterpret_cast<uint16_t*>(g.D)[(int64_t)row * g.ldd + col] = f32_to_bf16_bits(val);
-            } else if constexpr (EPI == EPI_STORE_F32) {
-              reinterpret_cast<float*>(g.D)[(int64_t)row * g.ldd + col] = val;
-            } else {  // EPI_SCATTER_ADD: one workgroup owns an output element, so the update is ordered
-              const int drow = g.row_idx ? g.row_idx[row] : row;
-              float* dp = reinterpret_cast<float*>(g.D) + (int64_t)drow * g.ldd + col;
-              *dp += val;
-            }
+      for (int q = 0; q < kSR / 2; ++q) {
+        if (row[q] < Mrows && col < g.N) {
+          if constexpr (EPI == EPI_STORE_BF16) {
+            uint2 o;
+            o.x = (uint32_t)f32_to_bf16_bits(val[q].x) | ((uint32_t)f32_to_bf16_bits(val[q].y) << 16);
+            o.y = (uint32_t)f32_to_bf16_bits(val[q].z) | ((uint32_t)f32_to_bf16_bits(val[q].w) << 16);
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.D) + (int64_t)row[q] * g.ldd + col) = o;
+          } else if constexpr (EPI == EPI_STORE_F32) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)row[q] * g.ldd + col) = val[q];
+          } else {  // EPI_SCATTER_ADD: one workgroup owns an output element, so the update is ordered
+            const int drow = g.row_idx ? g.row_idx[row[q]] : row[q];
+            float4* dp = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)drow * g.ldd + col);
+            const float4 o = *dp;
+            *dp = float4{o.x + val[q].x, o.y + val[q].y, o.z + val[q].z, o.w + val[q].w};
           }
         }
+      }
+    }
+    __syncthreads();  // the strip is rewritten by the next round
   }
 }
 
 // Adds the partial sums of a split contraction in split order and applies the epilogue (store / scatter-add).
+// A thread owns four consecutive columns; the blocks stride over the live rows (a device-side count for the
+// scatter-add product), so the launch does not grow with rows that did not fire.
 template <int EPI>
 __global__ __launch_bounds__(256) void splitk_finish(const GemmArgs g) {
   int Mrows = g.M;
@@ -269,26 +292,33 @@ __global__ __launch_bounds__(256) void splitk_finish(const GemmArgs g) {
     const int nd = g.n_rows_dev[0];
     Mrows = nd < Mrows ? nd : Mrows;
   }
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= (int64_t)Mrows * g.N) return;
-  const int row = (int)(e / g.N), col = (int)(e - (int64_t)row * g.N);
-  const int64_t stride = (int64_t)g.M * g.N;
-  float q[8];
-  float s = 0.f;
-  for (int z0 = 0; z0 < g.splits; z0 += 8) {
+  const int n4 = g.N >> 2;
+  const int64_t total = (int64_t)Mrows * n4, stride = (int64_t)g.M * g.N;
+  for (int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; e < total; e += (int64_t)gridDim.x * blockDim.x) {
+    const int row = (int)(e / n4), col = 4 * (int)(e - (int64_t)row * n4);
+    const float* src = g.part + (int64_t)row * g.N + col;
+    float4 s = float4{0.f, 0.f, 0.f, 0.f};
+    for (int z0 = 0; z0 < g.splits; z0 += 8) {
+      float4 q[8];
 #pragma unroll
-    for (int u = 0; u < 8; ++u) q[u] = g.part[(int64_t)min(z0 + u, g.splits - 1) * stride + e];
+      for (int u = 0; u < 8; ++u) q[u] = *reinterpret_cast<const float4*>(src + (int64_t)min(z0 + u, g.splits - 1) * stride);
 #pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (z0 + u < g.splits) s += q[u];
-  }
-  if constexpr (EPI == EPI_STORE_BF16) {
-    reinterpret_cast<uint16_t*>(g.D)[(int64_t)row * g.ldd + col] = f32_to_bf16_bits(s);
-  } else if constexpr (EPI == EPI_STORE_F32) {
-    reinterpret_cast<float*>(g.D)[(int64_t)row * g.ldd + col] = s;
-  } else {
-    const int drow = g.row_idx ? g.row_idx[row] : row;
-    reinterpret_cast<float*>(g.D)[(int64_t)drow * g.ldd + col] += s;
+      for (int u = 0; u < 8; ++u)
+        if (z0 + u < g.splits) { s.x += q[u].x; s.y += q[u].y; s.z += q[u].z; s.w += q[u].w; }
+    }
+    if constexpr (EPI == EPI_STORE_BF16) {
+      uint2 o;
+      o.x = (uint32_t)f32_to_bf16_bits(s.x) | ((uint32_t)f32_to_bf16_bits(s.y) << 16);
+      o.y = (uint32_t)f32_to_bf16_bits(s.z) | ((uint32_t)f32_to_bf16_bits(s.w) << 16);
+      *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.D) + (int64_t)row * g.ldd + col) = o;
+    } else if constexpr (EPI == EPI_STORE_F32) {
+      *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)row * g.ldd + col) = s;
+    } else {
+      const int drow = g.row_idx ? g.row_idx[row] : row;
+      float4* dp = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)drow * g.ldd + col);
+      const float4 o = *dp;
+      *dp = float4{o.x + s.x, o.y + s.y, o.z + s.z, o.w + s.w};
+    }
   }
 }
 
@@ -321,7 +351,7 @@ hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t s) {
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   if (splits > 1) {
-    const unsigned fb = (unsigned)ceil_div((int64_t)g.M * g.N, 256);
+    const unsigned fb = (unsigned)std::min<int64_t>(ceil_div((int64_t)g.M * (g.N / 4), 256), 4096);
     switch (epi) {
       case EPI_STORE_BF16: splitk_finish<EPI_STORE_BF16><<<fb, 256, 0, s>>>(g); break;
       case EPI_STORE_F32: splitk_finish<EPI_STORE_F32><<<fb, 256, 0, s>>>(g); break;
