@@ -402,3 +402,70 @@ def test_prefill_sized_batch(gsi, pu, d, k, m, T, nf, xdtype):
     for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired"):
         assert torch.equal(st.inputs_t[0][key], sep[key]), key
     assert torch.equal(st.maps_t[0]["Y"], sep["Y"]["w"])
+
+
+# ------------------------------------------------------------------------------------------------
+# full-size ragged decode batch: fc_in 16384x4096 and fc_out 4096x16384, k = 256, 64 tokens with a
+# per-token Bernoulli(0.15) gate design, as one batch, a short batch and a window inside it
+# ------------------------------------------------------------------------------------------------
+def test_ffn_pair_full_size_ragged_batch(gsi, pu):
+    w = wl.ffn_pair(T=64)
+    for g in w.groups:
+        say(f"case {w.name} input {g.name}: d={g.d} k={g.k} m={g.maps[0][1]} T={w.T} fired={int(g.fired_design.sum())}")
+        dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+        worst = pu.check_group(w, g, [(0, 64), (0, 4), (20, 36)], dg, og)
+        ref = og.run()
+        assert np.array_equal(ref["mask"].astype(bool), g.fired_design)
+        say(f"  worst rel-L2 {worst:.3e}")
+        del dg, og
+    # both maps in one stack call equal the separate calls bit for bit
+    dgs, inputs, maps, names = _stack_for(gsi, pu, w, w.T)
+    st = gsi.layer_stack(inputs, maps, w.T, w.eps)
+    torch.cuda.synchronize()
+    for gi, dg in enumerate(dgs):
+        sep = pu.run_separate_calls(dg, w.eps)
+        for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired"):
+            assert torch.equal(st.inputs_t[gi][key], sep[key]), key
+        for j, (g2, name) in enumerate(names):
+            if g2 == gi:
+                assert torch.equal(st.maps_t[j]["Y"], sep["Y"][name]), name
+
+
+# ------------------------------------------------------------------------------------------------
+# full-size prefill batch: T = 2048 tokens (bf16 activations), k = 512, 20 % of the tokens of every
+# input fired, the six maps of a GPT-J-shaped block in one stack call.  The projection is checked on
+# every token; images and outputs on 1024 sampled rows of every map (a row of y depends on that row of W
+# and M only, so the oracle computes exactly the sampled ones; the 2e-3 bar is statistical -- one bf16
+# rounding per image element -- and the worst of 2048 tokens over 256 sampled rows would already brush it).
+# ------------------------------------------------------------------------------------------------
+def test_prefill_block_full_size_sampled(gsi, pu):
+    T, k = 2048, 512
+    w = wl.transformer_block("prefill_block_bf16", 4096, 16384, k, T, 0.20, 1.5, wl.BASE_SEED + 4000, xdtype="bf16")
+    say(f"case {w.name}: T={T} k={k}, full shapes, sampled rows")
+    dgs, inputs, maps, names = _stack_for(gsi, pu, w, T)
+    st = gsi.layer_stack(inputs, maps, T, w.eps)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for gi, (g, dg) in enumerate(zip(w.groups, dgs)):
+        U64, X64 = O.widen(g.U, w.wdtype), O.widen(g.X, w.xdtype)
+        C, R, rn, xn = O.project(U64, X64)
+        mask_o, idx_o, n_o = O.gate(rn, xn, w.eps)
+        ref = dict(X=X64, C=C, R=R, rnorm=rn, xnorm=xn, rho=O.residual_ratio(rn, xn), mask=mask_o, idx=idx_o, n=n_o)
+        assert n_o == int(round(0.2 * T)) and np.array_equal(mask_o.astype(bool), g.fired_design)
+        ti = st.inputs_t[gi]
+        res = {key: ti[key] for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired", "fired_idx")}
+        mask = pu.check_projection(res, ref, w.eps)
+        say(f"  input {g.name}: d={g.d}, {n_o} fired, projection and gate match on all tokens")
+        for j, (g2, name) in enumerate(names):
+            if g2 != gi:
+                continue
+            Wst = dict((n, W) for n, _, W in g.maps)[name]
+            rows = np.sort(rng.choice(Wst.shape[0], size=1024, replace=False))
+            W64 = O.widen(Wst[rows], w.wdtype)
+            M64 = O.build_image(W64, U64)
+            Mdev = gsi.bits_of(dg.M[name])[rows]
+            pu.check_image(Mdev, M64, W64, U64, w.wdtype)
+            Ys = st.maps_t[j]["Y"][:, torch.from_numpy(rows).to(st.maps_t[j]["Y"].device)]
+            e, es = pu.check_outputs(Ys, W64, M64, Mdev, w.wdtype, ref, mask)
+            say(f"    map {name}: 1024 sampled rows, rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
+        del U64, X64, C, R, ref
