@@ -91,6 +91,9 @@ def main() -> int:
     ap.add_argument("--fire", type=float, default=0.10, help="fraction of gate evaluations that fire")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
+    ap.add_argument("--slow-path", choices=["mc_wr", "wx"], default="mc_wr",
+                    help="what a fired token gets: M c + W r (the form the metric is quoted on) or W x as "
+                         "Algorithm 1 prints it")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three device copies of 512 MiB first (a kernel of known traffic, used to "
                          "scale hardware-counter readings of a rocprofv3 --pmc run)")
@@ -129,7 +132,8 @@ def main() -> int:
     inputs, maps, meta = [], [], []
     for gi, g in enumerate(w.groups):
         U = gsi.to_device(g.U, w.wdtype)
-        inputs.append({"U": U, "X": gsi.to_device(g.X, w.xdtype)})
+        inputs.append({"U": U, "X": gsi.to_device(g.X, w.xdtype),
+                       "flags": gsi.INPUT_SLOW_PATH_WX if args.slow_path == "wx" else 0})
         for name, m, W in g.maps:
             Wd = gsi.to_device(W, w.wdtype)
             maps.append({"W": Wd, "M": gsi.build_image(Wd, U), "input_id": gi})
@@ -338,7 +342,7 @@ def main() -> int:
                         "fc_out 4096x16384, bf16 weights/images/bases, fp32 accumulate",
             "k": args.k, "eps": w.eps, "decode_tokens": T, "designed_fire_rate": args.fire,
             "measured_fire_rate": round(float(fired.mean()), 4), "masks_match_design": masks_match_design,
-            "launch_mode": mode,
+            "launch_mode": mode, "slow_path": "M c + W r" if args.slow_path == "mc_wr" else "W x (Algorithm 1, line 7)",
         },
         "tokens_per_s": round(tokens_per_s, 1),
         "dense_gemv_tokens_per_s": round(dense_tokens_per_s, 1),

@@ -106,8 +106,15 @@ typedef struct gsi_input_desc {
   int32_t* fired_idx;
   int32_t* n_fired;
   int32_t src_map;    /* -1: X is an external buffer; j >= 0: X is the output Y of maps[j]      */
-  int32_t reserved;
+  int32_t flags;      /* 0, or GSI_INPUT_SLOW_PATH_WX                                           */
 } gsi_input_desc;
+
+/* gsi_input_desc.flags.  By default a fired token gets y = M c + W r (Eq. (exact)).  With
+ * GSI_INPUT_SLOW_PATH_WX the maps of this input give a fired token y = W x instead, the slow path as
+ * Algorithm 1 (line 7) prints it: equal in exact arithmetic, but free of the stored image's rounding, so
+ * that a fired token equals the dense product of gsi_dense_stack.  Tokens that did not fire are not
+ * affected.  gsi_gated_linear has no x and always uses the default form. */
+enum { GSI_INPUT_SLOW_PATH_WX = 1 };
 
 typedef struct gsi_map_desc {
   const void* W;      /* [m,d] wdtype, d = inputs[input_id].d                                   */

@@ -257,7 +257,7 @@ static bool mfma_project_path(const void* U, const void* X, int64_t d, int64_t k
 // over the compacted list (row tiles beyond the device-side count exit at once).
 static hipError_t mfma_gated(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
                              const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, float* Y,
-                             float* part, hipStream_t s) {
+                             float* part, hipStream_t s, const void* Xwx = nullptr, int xdtype = 0) {
   gsi::GemmArgs g;
   std::memset(&g, 0, sizeof(g));
   g.A = C; g.lda = k; g.a_f32 = 1;
@@ -270,12 +270,16 @@ static hipError_t mfma_gated(const void* W, const void* M, const float* C, const
   // r enters rounded once to bf16: its term is scaled by the residual ratio, so the rounding (2^-9 relative)
   // adds a few 1e-4 of |y| at most, beside the 1.7e-3 that the bf16 image already costs
   g.A = R; g.lda = d; g.a_f32 = 2;
+  if (Xwx) {  // fired tokens get y = W x, fed exactly as the dense product feeds x
+    g.A = Xwx;
+    g.a_f32 = xdtype == GSI_F32 ? 1 : 0;
+  }
   g.B = W; g.ldb = d;
   g.D = Y; g.ldd = m;
   g.M = (int)B; g.N = (int)m; g.K = (int)d;
   g.row_idx = fired_idx; g.n_rows_dev = n_fired;
   g.part = gsi::mfma_part_bytes(B, m, d, gsi::EPI_SCATTER_ADD) ? part : nullptr;
-  return gsi::mfma_gemm_nt(g, gsi::EPI_SCATTER_ADD, s);
+  return gsi::mfma_gemm_nt(g, Xwx ? gsi::EPI_SCATTER_STORE : gsi::EPI_SCATTER_ADD, s);
 }
 
 static bool mfma_gated_path(const void* W, const void* M, const float* C, const float* R, int64_t d, int64_t k,
@@ -477,6 +481,11 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
   return need;
 }
 
+// the W x form of the slow path reads x with 16-byte loads in the vector kernels
+static bool wx_vector_ok(const gsi_input_desc& in) {
+  return !(in.flags & GSI_INPUT_SLOW_PATH_WX) || aligned(in.X, 16);
+}
+
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
                             hipEvent_t ev_begin, hipEvent_t ev_end);
@@ -602,6 +611,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // validate everything before the first launch
   for (int i = 0; i < n_inputs; ++i) {
     const gsi_input_desc& in = inputs[i];
+    if (in.flags & ~GSI_INPUT_SLOW_PATH_WX)
+      return fail(GSI_ERR_SHAPE, "%s: inputs[%d].flags = %d has unknown bits", fn, i, in.flags);
     if (int rc = check_project_args(fn, in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
                                     in.xnorm))
       return rc;
@@ -655,7 +666,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       if (maps[j].input_id != i) continue;
       ++readers;
       if (!gsi::decode_linear_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M) ||
-          !aligned(in.C, 16) || !aligned(in.R, 16))
+          !aligned(in.C, 16) || !aligned(in.R, 16) || !wx_vector_ok(in))
         all_stream = false;
     }
     if (readers > 0 && all_stream) mode[i] = kVecInline;
@@ -739,14 +750,17 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           const gsi_input_desc& in = inputs[mp.input_id];
           if (map_done[j] || mp.wdtype != dt || B == 0) continue;
           if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
-          if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y)) continue;  // matrix cores below
+          if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
+            continue;  // matrix cores below
           if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
-              !aligned(in.R, 16))
+              !aligned(in.R, 16) || !wx_vector_ok(in))
             continue;
           gsi::LinGroup gd;
           std::memset(&gd, 0, sizeof(gd));
           gd.C = in.C; gd.R = in.R; gd.fired_idx = in.fired_idx; gd.n_fired = in.n_fired;
           gd.d = (int)in.d; gd.k = (int)in.k;
+          gd.wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) ? 1 : 0;
+          gd.X = in.X; gd.xdtype = in.xdtype;
           if (ig) {
             const gsi::ProjTask& pt = ptask[mp.input_id];
             gd.part_n = pt.part_n; gd.b_slabs = pt.b_slabs;
@@ -766,11 +780,13 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       const gsi_input_desc& in = inputs[mp.input_id];
       if (map_done[j] != 2 && B > 0) {
         hipError_t e;
-        if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y))
-          e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, part[j], s);
+        const bool wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) != 0;
+        if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
+          e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, part[j], s,
+                         wx ? in.X : nullptr, in.xdtype);
         else
           e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
-                                        mp.wdtype, mp.Y, s);
+                                        mp.wdtype, mp.Y, s, wx ? in.X : nullptr, in.xdtype);
         if (e != hipSuccess) return hip_fail(e, fn);
       }
       map_done[j] = 1;

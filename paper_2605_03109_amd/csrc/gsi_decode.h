@@ -62,7 +62,8 @@ struct ImgBatch {
 struct LinGroup {
   const float* C;
   const float* R;
-  const void* X;                 // dense baseline only (xdtype)
+  const void* X;                 // dense baseline, and the W x form of the slow path (xdtype)
+  int wx;                        // fired tokens get y = W x (Algorithm 1, line 7) instead of M c + W r
   const int32_t* fired_idx;      // read when the gate is not evaluated in the kernel
   const int32_t* n_fired;
   // gate evaluated inside the single-token kernel from the residual kernel's partial norms:

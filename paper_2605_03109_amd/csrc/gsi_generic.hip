@@ -81,7 +81,9 @@ __global__ __launch_bounds__(kBlock) void gen_gated_linear(const typename T::sto
                                                            const float* __restrict__ R,
                                                            const int32_t* __restrict__ fired_idx,
                                                            const int32_t* __restrict__ n_fired, int64_t m,
-                                                           int64_t d, int64_t k, int64_t B, float* __restrict__ Y) {
+                                                           int64_t d, int64_t k, int64_t B, float* __restrict__ Y,
+                                                           const void* __restrict__ X, int xdtype) {
+  // X non-null: a fired token gets y = W x (Algorithm 1, line 7) instead of M c + W r
   const int lane = threadIdx.x % kWave;
   const int64_t row = (int64_t)blockIdx.x * (kBlock / kWave) + threadIdx.x / kWave;
   if (row >= m) return;
@@ -97,9 +99,10 @@ __global__ __launch_bounds__(kBlock) void gen_gated_linear(const typename T::sto
     const int64_t t = fired_idx[f];
     if (t < 0 || t >= B) continue;
     float acc = 0.f;
-    for (int64_t i = lane; i < d; i += kWave) acc = fmaf(T::load(W, row * d + i), R[t * d + i], acc);
+    for (int64_t i = lane; i < d; i += kWave)
+      acc = fmaf(T::load(W, row * d + i), X ? load_act(X, xdtype, t * d + i) : R[t * d + i], acc);
     acc = group_sum<kWave>(acc);
-    if (lane == 0) Y[t * m + row] += acc;
+    if (lane == 0) Y[t * m + row] = X ? acc : Y[t * m + row] + acc;
   }
 }
 
@@ -164,14 +167,14 @@ hipError_t generic_project(const void* U, const void* X, int64_t d, int64_t k, i
 
 hipError_t generic_gated_linear(const void* W, const void* M, const float* C, const float* R,
                                 const int32_t* fired_idx, const int32_t* n_fired, int64_t m, int64_t d, int64_t k,
-                                int64_t B, int wdtype, float* Y, hipStream_t s) {
+                                int64_t B, int wdtype, float* Y, hipStream_t s, const void* X, int xdtype) {
   const unsigned grid = (unsigned)ceil_div(m, kBlock / kWave);
   if (wdtype == GSI_BF16)
     gen_gated_linear<BF16><<<grid, kBlock, 0, s>>>((const uint16_t*)W, (const uint16_t*)M, C, R, fired_idx,
-                                                   n_fired, m, d, k, B, Y);
+                                                   n_fired, m, d, k, B, Y, X, xdtype);
   else
     gen_gated_linear<F32><<<grid, kBlock, 0, s>>>((const float*)W, (const float*)M, C, R, fired_idx, n_fired, m,
-                                                  d, k, B, Y);
+                                                  d, k, B, Y, X, xdtype);
   return hipGetLastError();
 }
 

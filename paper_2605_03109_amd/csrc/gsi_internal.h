@@ -19,7 +19,8 @@ hipError_t generic_project(const void* U, const void* X, int64_t d, int64_t k, i
                            float* C, float* R, float* rnorm, float* xnorm, hipStream_t s);
 hipError_t generic_gated_linear(const void* W, const void* M, const float* C, const float* R,
                                 const int32_t* fired_idx, const int32_t* n_fired, int64_t m, int64_t d, int64_t k,
-                                int64_t B, int wdtype, float* Y, hipStream_t s);
+                                int64_t B, int wdtype, float* Y, hipStream_t s, const void* X = nullptr,
+                                int xdtype = 0);  // X: fired tokens get y = W x
 hipError_t generic_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype,
                                 int xdtype, float* Y, hipStream_t s);
 

@@ -142,11 +142,15 @@ __global__ __launch_bounds__(kBlock) void gated_rows(const LinBatch lb) {
     const int t = g.fired_idx[f];
     if (t < 0 || t >= B) continue;  // uniform across the workgroup
     __syncthreads();
-    for (int idx = threadIdx.x; idx < d; idx += kBlock) vec[idx] = g.R[(int64_t)t * d + idx];
+    for (int idx = threadIdx.x; idx < d; idx += kBlock)
+      vec[idx] = g.wx ? load_act(g.X, g.xdtype, (int64_t)t * d + idx) : g.R[(int64_t)t * d + idx];
     __syncthreads();
     rows_dot<T, 1>(W, d, d, wr0, wr1, row0, vec, d, 1, yb);
     __syncthreads();
-    if (threadIdx.x < rows) p.Y[(int64_t)t * m + row0 + threadIdx.x] += yb[threadIdx.x];
+    if (threadIdx.x < rows) {
+      float* y = p.Y + (int64_t)t * m + row0 + threadIdx.x;
+      *y = g.wx ? yb[threadIdx.x] : *y + yb[threadIdx.x];  // W x replaces the image term, W r is added to it
+    }
   }
 }
 

@@ -4,7 +4,7 @@
 
 namespace gsi {
 
-enum { EPI_STORE_BF16 = 0, EPI_STORE_F32 = 1, EPI_RESIDUAL = 2, EPI_SCATTER_ADD = 3 };
+enum { EPI_STORE_BF16 = 0, EPI_STORE_F32 = 1, EPI_RESIDUAL = 2, EPI_SCATTER_ADD = 3, EPI_SCATTER_STORE = 4 };
 
 // D = A B^T, A[M,K] (bf16, or fp32 split into two bf16 terms), B[N,K] bf16, both row-major.
 struct GemmArgs {

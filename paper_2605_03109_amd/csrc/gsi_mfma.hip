@@ -269,11 +269,15 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
             *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.D) + (int64_t)row[q] * g.ldd + col) = o;
           } else if constexpr (EPI == EPI_STORE_F32) {
             *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)row[q] * g.ldd + col) = val[q];
-          } else {  // EPI_SCATTER_ADD: one workgroup owns an output element, so the update is ordered
+          } else {  // scatter: one workgroup owns an output element, so the update is ordered
             const int drow = g.row_idx ? g.row_idx[row[q]] : row[q];
             float4* dp = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)drow * g.ldd + col);
-            const float4 o = *dp;
-            *dp = float4{o.x + val[q].x, o.y + val[q].y, o.z + val[q].z, o.w + val[q].w};
+            if constexpr (EPI == EPI_SCATTER_STORE) {
+              *dp = val[q];
+            } else {
+              const float4 o = *dp;
+              *dp = float4{o.x + val[q].x, o.y + val[q].y, o.z + val[q].z, o.w + val[q].w};
+            }
           }
         }
       }
@@ -316,8 +320,12 @@ __global__ __launch_bounds__(256) void splitk_finish(const GemmArgs g) {
     } else {
       const int drow = g.row_idx ? g.row_idx[row] : row;
       float4* dp = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)drow * g.ldd + col);
-      const float4 o = *dp;
-      *dp = float4{o.x + s.x, o.y + s.y, o.z + s.z, o.w + s.w};
+      if constexpr (EPI == EPI_SCATTER_STORE) {
+        *dp = s;
+      } else {
+        const float4 o = *dp;
+        *dp = float4{o.x + s.x, o.y + s.y, o.z + s.z, o.w + s.w};
+      }
     }
   }
 }
@@ -347,6 +355,7 @@ hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t s) {
     case EPI_STORE_BF16: gemm_nt<AM, EPI_STORE_BF16><<<grid, kThreads, 0, s>>>(g); break;
     case EPI_STORE_F32: gemm_nt<AM, EPI_STORE_F32><<<grid, kThreads, 0, s>>>(g); break;
     case EPI_RESIDUAL: gemm_nt<AM, EPI_RESIDUAL><<<grid, kThreads, 0, s>>>(g); break;
+    case EPI_SCATTER_STORE: gemm_nt<AM, EPI_SCATTER_STORE><<<grid, kThreads, 0, s>>>(g); break;
     default: gemm_nt<AM, EPI_SCATTER_ADD><<<grid, kThreads, 0, s>>>(g); break;
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
@@ -355,6 +364,7 @@ hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t s) {
     switch (epi) {
       case EPI_STORE_BF16: splitk_finish<EPI_STORE_BF16><<<fb, 256, 0, s>>>(g); break;
       case EPI_STORE_F32: splitk_finish<EPI_STORE_F32><<<fb, 256, 0, s>>>(g); break;
+      case EPI_SCATTER_STORE: splitk_finish<EPI_SCATTER_STORE><<<fb, 256, 0, s>>>(g); break;
       default: splitk_finish<EPI_SCATTER_ADD><<<fb, 256, 0, s>>>(g); break;
     }
   }
@@ -366,7 +376,7 @@ hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t s) {
 int mfma_splits(int64_t M, int64_t N, int64_t K, int epi) {
   if (epi == EPI_RESIDUAL) return 1;
   // the scatter-add product runs over the fired rows only (a device-side count): size it for a quarter of them
-  const int64_t m_eff = epi == EPI_SCATTER_ADD ? std::max<int64_t>(BM, M / 4) : M;
+  const int64_t m_eff = (epi == EPI_SCATTER_ADD || epi == EPI_SCATTER_STORE) ? std::max<int64_t>(BM, M / 4) : M;
   const int64_t tiles = ceil_div(m_eff, BM) * ceil_div(N, BN);
   const int64_t nk = ceil_div(K, BK);
   int s = 1;

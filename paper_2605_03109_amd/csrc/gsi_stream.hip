@@ -144,10 +144,11 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
     // stage the activation vector (readers of the previous group's vector are past the barrier)
     if (staged) __syncthreads();
     staged = true;
-    if (DENSE && g.xdtype != GSI_F32) {
+    const bool whole = DENSE || g.wx;  // the product takes x (and replaces y) rather than r (added to y)
+    if (whole && g.xdtype != GSI_F32) {
       for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(g.X, g.xdtype, idx);
     } else {
-      const float4* src = reinterpret_cast<const float4*>(DENSE ? reinterpret_cast<const float*>(g.X) : g.R);
+      const float4* src = reinterpret_cast<const float4*>(whole ? reinterpret_cast<const float*>(g.X) : g.R);
       float4* dst = reinterpret_cast<float4*>(xs);
       const int n4 = d / 4;
       int i = threadIdx.x;
@@ -230,14 +231,16 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
           }
           if (lane < cnt) {  // lane j holds the sum of this wave's row j0 + j
             float* yp = t.Y + first + (int64_t)(j0 + lane) * GW;
-            *yp = DENSE ? res : *yp + res;  // image term written by the preceding launch
+            float old = 0.f;
+            if (!whole) old = *yp;  // image term written by the preceding launch (uniform branch)
+            *yp = old + res;
           }
         }
       } else {
         for (int row = first; row < m; row += GW) {
           float acc = 0.f;
           float yold = 0.f;
-          if constexpr (!DENSE) yold = t.Y[row];  // the image term written by the preceding launch
+          if (!whole) yold = t.Y[row];  // the image term written by the preceding launch
           for (int sg = 0; sg < nseg; ++sg) {
             Raw<T> buf[kLU];
             const int cb = sg * kWave * kLU + lane;
@@ -258,7 +261,7 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
             }
           }
           acc = group_sum<kWave>(acc);
-          if (lane == 0) t.Y[row] = DENSE ? acc : yold + acc;
+          if (lane == 0) t.Y[row] = yold + acc;
         }
       }
       // continue the deal: the next map starts with the wave after the one that took this map's last row

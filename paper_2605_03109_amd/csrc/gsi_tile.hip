@@ -124,7 +124,9 @@ __global__ __launch_bounds__(kTBlock) void tile_rows(const LinBatch lb) {
   } else {
     int nf = g.n_fired[0];
     nf = nf < 0 ? 0 : (nf > B ? B : nf);
-    A = reinterpret_cast<const uint16_t*>(p.W); V = g.R; K = g.d; count = nf; idx = g.fired_idx;
+    // the fired tokens' r (added to the image term), or their x (replacing it: Algorithm 1, line 7)
+    A = reinterpret_cast<const uint16_t*>(p.W); V = g.wx ? reinterpret_cast<const float*>(g.X) : g.R; K = g.d;
+    count = nf; idx = g.fired_idx;
     slices = p.slices; to_part = true;
   }
   if (count == 0) return;  // uniform: no fired token, no weight byte is read
@@ -228,7 +230,7 @@ __global__ __launch_bounds__(256) void tile_reduce(const LinBatch lb) {
   int tok = j;
   if (!lb.dense) tok = min(max(g.fired_idx[j], 0), B - 1);
   float4* y = reinterpret_cast<float4*>(p.Y + (int64_t)tok * m) + r4;
-  if (lb.dense) *y = s;
+  if (lb.dense || g.wx) *y = s;
   else {
     const float4 o = *y;
     *y = float4{o.x + s.x, o.y + s.y, o.z + s.z, o.w + s.w};
@@ -606,9 +608,10 @@ bool tile_rows_ok(const LinBatch& lb, int wdtype) {
   for (int i = 0; i < lb.ng; ++i) {
     const LinGroup& g = lb.g[i];
     if (g.d % kStepCols) return false;
-    if (lb.dense) {
+    if (lb.dense || g.wx) {
       if (g.xdtype != GSI_F32 || reinterpret_cast<uintptr_t>(g.X) % 16) return false;
-    } else {
+    }
+    if (!lb.dense) {
       if (g.k % kStepCols || g.k > kSliceCols) return false;
       if (reinterpret_cast<uintptr_t>(g.C) % 16 || reinterpret_cast<uintptr_t>(g.R) % 16) return false;
     }

@@ -20,6 +20,7 @@ LIB_PATH = os.path.join(_HERE, "libgsi.so")
 GSI_OK = 0
 GSI_ERR_NULL, GSI_ERR_SHAPE, GSI_ERR_DTYPE, GSI_ERR_ALIGN, GSI_ERR_WORKSPACE, GSI_ERR_HIP = -1, -2, -3, -4, -5, -6
 GSI_F32, GSI_BF16 = 0, 1
+INPUT_SLOW_PATH_WX = 1  # gsi_input_desc.flags: fired tokens get y = W x (Algorithm 1, line 7)
 CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
 
 EXPORTS = (
@@ -44,7 +45,7 @@ class InputDesc(ctypes.Structure):
         ("C", ctypes.c_void_p), ("R", ctypes.c_void_p),
         ("rnorm", ctypes.c_void_p), ("xnorm", ctypes.c_void_p),
         ("mask", ctypes.c_void_p), ("fired_idx", ctypes.c_void_p), ("n_fired", ctypes.c_void_p),
-        ("src_map", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("src_map", ctypes.c_int32), ("flags", ctypes.c_int32),
     ]
 
 
@@ -262,7 +263,7 @@ class LayerStack:
             src = int(inp.get("src_map", -1))
             X = self.maps_t[src]["Y"] if src >= 0 else inp["X"]
             self.inputs_t.append({
-                "U": U, "X": X, "src_map": src,
+                "U": U, "X": X, "src_map": src, "flags": int(inp.get("flags", 0)),
                 "C": torch.zeros((B, k), **f32), "R": torch.zeros((B, d), **f32),
                 "rnorm": torch.zeros((B,), **f32), "xnorm": torch.zeros((B,), **f32),
                 "mask": torch.zeros((B,), dtype=torch.uint8, device=dev),
@@ -292,7 +293,7 @@ class LayerStack:
             e.mask = _ptr(t["mask"]) + o
             e.fired_idx = _ptr(t["fired_idx"])
             e.n_fired = _ptr(t["n_fired"])
-            e.src_map, e.reserved = t["src_map"], 0
+            e.src_map, e.flags = t["src_map"], t["flags"]
         for j, t in enumerate(self.maps_t):
             m = t["W"].shape[0]
             e = self._mp[j]

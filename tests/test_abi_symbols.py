@@ -70,3 +70,14 @@ def test_host_side_validation_needs_no_gpu():
         setattr(inp[0], f, 256)
     assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
     assert b"cycle" in lib.gsi_last_error()
+    # unknown bits in an input's flags are refused before anything runs
+    inp[0].flags = 6
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert b"flags" in lib.gsi_last_error()
+    inp[0].flags = 0
+    # a dense stack of several tokens needs its workspace
+    inp[0].src_map = -1
+    mp[0].m, inp[0].d, inp[0].k = 64, 64, 32
+    need = lib.gsi_dense_stack_workspace_bytes(mp, 1, inp, 1, 4)
+    assert need > 0 and lib.gsi_dense_stack_workspace_bytes(mp, 1, inp, 1, 1) == 0
+    assert lib.gsi_dense_stack(mp, 1, inp, 1, 4, None, 0, None) == gsi.GSI_ERR_WORKSPACE

@@ -469,3 +469,48 @@ def test_prefill_block_full_size_sampled(gsi, pu):
             e, es = pu.check_outputs(Ys, W64, M64, Mdev, w.wdtype, ref, mask)
             say(f"    map {name}: 1024 sampled rows, rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
         del U64, X64, C, R, ref
+
+
+# ------------------------------------------------------------------------------------------------
+# the slow path as Algorithm 1 prints it (flag on the input): a fired token gets y = W x, free of the
+# stored image's rounding; tokens that did not fire keep y = M c.  Checked for one token per call, a
+# decode batch and a prefill-sized batch; with every token fired the stack equals the dense stack.
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k,m,T,nf,B", [(1024, 64, 520, 12, 4, 1), (2048, 128, 528, 48, 9, 48), (1024, 64, 512, 300, 60, 300),
+                                          (776, 72, 100, 9, 3, 9)])
+def test_slow_path_wx_flag(gsi, pu, d, k, m, T, nf, B):
+    w = wl.tiny(d, k, m, T, nf, seed=5200 + d + k + T, wdtype="bf16")
+    say(f"case slow path W x: d={d} k={k} m={m} T={T} nf={nf} B={B}")
+    g = w.groups[0]
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    ref = og.run()
+    maps = [{"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}]
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X, "flags": gsi.INPUT_SLOW_PATH_WX}], maps, T, w.eps)
+    for t0 in range(0, T, B):
+        st.refresh(token_offset=t0, B=min(B, T - t0))
+        st.run()
+    torch.cuda.synchronize()
+    mask = st.inputs_t[0]["mask"].cpu().numpy()
+    assert np.array_equal(mask.astype(bool), g.fired_design)
+    Y = st.maps_t[0]["Y"].cpu().numpy().astype(np.float64)
+    fired = mask.astype(bool)
+    # fired tokens: the dense product, to fp32-accumulation accuracy (no image in it)
+    e_f = pu.rel_l2_rows(Y[fired], O.dense_linear(og.W["w"], og.X[fired]))
+    assert e_f.max() <= 2e-5, e_f.max()
+    # the whole output against Algorithm 1 evaluated with the device's stored image
+    Mdev = O.widen(gsi.bits_of(dg.M["w"]), w.wdtype)
+    e = pu.rel_l2_rows(Y, O.gated_linear_alg1(og.W["w"], Mdev, ref["C"], og.X, mask))
+    assert e.max() <= 2e-5, e.max()
+    say(f"  fired rows vs W x {e_f.max():.3e}, all rows vs Algorithm 1 with the stored image {e.max():.3e}")
+    # eps = 0: every token fires, and the stack gives the dense stack's bits
+    st0 = gsi.LayerStack([{"U": dg.U, "X": dg.X, "flags": gsi.INPUT_SLOW_PATH_WX}], maps, T, 0.0)
+    for t0 in range(0, T, B):
+        st0.refresh(token_offset=t0, B=min(B, T - t0))
+        st0.run()
+    torch.cuda.synchronize()
+    y_all = st0.maps_t[0]["Y"].clone()
+    for t0 in range(0, T, B):
+        st0.refresh(token_offset=t0, B=min(B, T - t0))
+        st0.run_dense()
+    torch.cuda.synchronize()
+    assert torch.equal(y_all, st0.maps_t[0]["Y"])
