@@ -8,12 +8,13 @@
 // or fp32 split on the fly into a bf16 head and a bf16 tail (two MFMA passes) so that an fp32 operand
 // on the main term is not rounded to 8 bits (the bf16 image already uses most of the 2e-3 budget).
 //
-// Workgroup tile 256 x 128 x 64, four waves stacked along M, each wave 64 x 128 as 2 x 4
-// v_mfma_f32_32x32x16_bf16 tiles.  Both operand tiles are staged in LDS as bf16 (row stride padded to 144
-// bytes: conflict-free 128-bit reads); an fp32 A operand is converted on the way in.  Global loads are
-// whole 128-byte row segments per eight lanes; the next k-tile travels to registers during the MFMAs of the
-// current one.  Within a k-tile the lane half l/32 takes 32 consecutive columns, eight per MFMA step: any
-// order of the contraction index is as good as another as long as both operands agree.
+// Workgroup tile 256 x 256 x 64, eight waves 4 x 2 (two per SIMD, so that one wave's MFMAs cover the
+// other's LDS reads, staging and barriers), each wave 64 x 128 as 2 x 4 v_mfma_f32_32x32x16_bf16 fragments.
+// Both operand tiles are staged in LDS as bf16 (row stride padded to 144 bytes: conflict-free 128-bit
+// reads); an fp32 A operand is converted on the way in.  Global loads are whole 128-byte row segments per
+// eight lanes; the next k-tile travels to registers during the MFMAs of the current one.  Within a k-tile
+// the lane half l/32 takes 32 consecutive columns, eight per MFMA step: any order of the contraction index
+// is as good as another as long as both operands agree.
 // Problems with few output tiles split the contraction over blockIdx.z; the partial sums go to the workspace
 // and a second kernel adds them in split order and applies the epilogue.
 // Operands that are N-contiguous in memory (U as the right factor of W U and X U) are transposed
@@ -29,12 +30,14 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int BM = 256, BN = 128, BK = 64;
+constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int WTM = 64, WTN = 128;              // wave tile: the eight waves sit 4 x 2 on the workgroup tile
 constexpr int LDB = BK + 8;  // padded LDS row stride of a staged tile, bf16 elements (144 bytes)
-constexpr int kThreads = 256;
-constexpr int kAF = 2, kBF = 4, kKS = BK / 16;  // A fragments, B fragments per wave; MFMA steps per k-tile
-constexpr int kAU = BM * BK / 8 / kThreads;     // staging units (8 elements of a row) of A per thread: 8
+constexpr int kThreads = 512;
+constexpr int kAF = WTM / 32, kBF = WTN / 32, kKS = BK / 16;  // A, B fragments per wave; MFMA steps per k-tile
+constexpr int kAU = BM * BK / 8 / kThreads;     // staging units (8 elements of a row) of A per thread: 4
 constexpr int kBU = BN * BK / 8 / kThreads;     // ... of B: 4
+constexpr int kRowsPerPass = kThreads / 8;      // rows of a tile that one staging unit index covers: 64
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a native vector: loads and stores of it are
                                                               // instructions, not aggregate copies
@@ -66,7 +69,7 @@ __device__ __forceinline__ u32x4 round8(const u32x4& x0, const u32x4& x1, u32x4*
                (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16)};
 }
 
-// requests k-tile kt of both operands (unit u of a thread: row (tid >> 3) + 32 u, columns 8 (tid & 7) .. + 8)
+// requests k-tile kt of both operands (unit u of a thread: row (tid >> 3) + 64 u, columns 8 (tid & 7) .. + 8)
 template <int AM>
 __device__ __forceinline__ void issue(Stage<AM>& st, const char* const (&ap)[kAU], const char* const (&bp)[kBU], int kt) {
   constexpr int ES = AM ? 4 : 2;
@@ -86,7 +89,7 @@ __device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t (*As)[BM][L
   const int r0 = tid >> 3, c8 = 8 * (tid & 7);
 #pragma unroll
   for (int u = 0; u < kAU; ++u) {
-    u32x4* d0 = reinterpret_cast<u32x4*>(&As[0][r0 + 32 * u][c8]);
+    u32x4* d0 = reinterpret_cast<u32x4*>(&As[0][r0 + kRowsPerPass * u][c8]);
     if constexpr (AM == 0) {
       *d0 = st.a[u][0];
     } else if constexpr (AM == 2) {
@@ -94,31 +97,31 @@ __device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t (*As)[BM][L
     } else {
       u32x4 tail;
       *d0 = round8(st.a[u][0], st.a[u][1], &tail);
-      *reinterpret_cast<u32x4*>(&As[1][r0 + 32 * u][c8]) = tail;
+      *reinterpret_cast<u32x4*>(&As[1][r0 + kRowsPerPass * u][c8]) = tail;
     }
   }
 #pragma unroll
-  for (int u = 0; u < kBU; ++u) *reinterpret_cast<u32x4*>(&Bs[r0 + 32 * u][c8]) = st.b[u];
+  for (int u = 0; u < kBU; ++u) *reinterpret_cast<u32x4*>(&Bs[r0 + kRowsPerPass * u][c8]) = st.b[u];
 }
 
 // one k-tile from LDS: lane half lh takes columns 32 lh .. + 32 of the tile, eight per MFMA step (both
 // operands in the same order, so the order of the contraction index does not matter)
 template <int AM>
-__device__ __forceinline__ void compute(const uint16_t (*As)[BM][LDB], const uint16_t (*Bs)[LDB], int wave, int lc, int lh,
+__device__ __forceinline__ void compute(const uint16_t (*As)[BM][LDB], const uint16_t (*Bs)[LDB], int wm, int wn, int lc, int lh,
                                         f32x16 (&acc)[kAF][kBF]) {
 #pragma unroll
   for (int j = 0; j < kKS; ++j) {
     const int col = 32 * lh + 8 * j;
     bf16x8 b[kBF];
 #pragma unroll
-    for (int n = 0; n < kBF; ++n) b[n] = *reinterpret_cast<const bf16x8*>(&Bs[32 * n + lc][col]);
+    for (int n = 0; n < kBF; ++n) b[n] = *reinterpret_cast<const bf16x8*>(&Bs[WTN * wn + 32 * n + lc][col]);
 #pragma unroll
     for (int i = 0; i < kAF; ++i) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[0][64 * wave + 32 * i + lc][col]);
+      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[0][WTM * wm + 32 * i + lc][col]);
 #pragma unroll
       for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[n], acc[i][n], 0, 0, 0);
       if constexpr (AM == 1) {
-        const bf16x8 al = *reinterpret_cast<const bf16x8*>(&As[1][64 * wave + 32 * i + lc][col]);
+        const bf16x8 al = *reinterpret_cast<const bf16x8*>(&As[1][WTM * wm + 32 * i + lc][col]);
 #pragma unroll
         for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b[n], acc[i][n], 0, 0, 0);
       }
@@ -141,6 +144,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lc = lane & 31, lh = lane >> 5;
+  const int wm = wave >> 1, wn = wave & 1;
   constexpr int ES = AM ? 4 : 2;  // bytes per element of A
 
   // k-tiles of this split
@@ -154,14 +158,14 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   const char* bp[kBU];
 #pragma unroll
   for (int u = 0; u < kAU; ++u) {
-    int grow = tile_m * BM + (tid >> 3) + 32 * u;
+    int grow = tile_m * BM + (tid >> 3) + kRowsPerPass * u;
     grow = grow < Mrows ? grow : Mrows - 1;
     if (g.row_idx) grow = g.row_idx[grow];
     ap[u] = reinterpret_cast<const char*>(g.A) + ((int64_t)grow * g.lda + 8 * (tid & 7)) * ES;
   }
 #pragma unroll
   for (int u = 0; u < kBU; ++u) {
-    int grow = tile_n * BN + (tid >> 3) + 32 * u;
+    int grow = tile_n * BN + (tid >> 3) + kRowsPerPass * u;
     grow = grow < g.N ? grow : g.N - 1;
     bp[u] = reinterpret_cast<const char*>(g.B) + ((int64_t)grow * g.ldb + 8 * (tid & 7)) * 2;
   }
@@ -185,7 +189,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
       __builtin_amdgcn_sched_barrier(0);
       issue<AM>(st, ap, bp, kt + 1 < kt1 ? kt + 1 : kt);
       __builtin_amdgcn_sched_barrier(0);
-      compute<AM>(As, Bs, wave, lc, lh, acc);
+      compute<AM>(As, Bs, wm, wn, lc, lh, acc);
       __syncthreads();  // every wave has read the tile
       commit<AM>(st, As, Bs, tid);
       __syncthreads();
@@ -197,27 +201,28 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   // fragment.  The accumulators go through LDS sixteen rows at a time (a private strip per wave), so that
   // what touches memory is row-contiguous: a lane then owns four consecutive columns of a row.
   __syncthreads();  // the operand tiles are no longer read
-  constexpr int kSR = 16, kSLD = BN + 4;  // strip rows, padded strip stride (floats)
+  constexpr int kSR = 8, kSLD = WTN + 4;  // strip rows, padded strip stride (floats)
   float* strip = reinterpret_cast<float*>(&As[0][0][0]) + wave * (kSR * kSLD);
   const bool partial = g.splits > 1;
   float* const pdst = partial ? g.part + (int64_t)blockIdx.z * g.M * g.N : nullptr;
   const int er = lane >> 5, ec = 4 * (lane & 31);  // row parity and first column of the lane's reads
 #pragma unroll
-  for (int c = 0; c < 64 / kSR; ++c) {
-    const int i = c >> 1, vbase = 8 * (c & 1);
+  for (int c = 0; c < WTM / kSR; ++c) {
+    // strip c: rows 8 c .. 8 c + 7 of the wave tile = fragment c / 4, accumulator elements 4 (c % 4) .. + 3
+    const int i = c >> 2, vbase = 4 * (c & 3);
 #pragma unroll
-    for (int vv = 0; vv < 8; ++vv) {
-      const int rl = 8 * (vv >> 2) + 4 * lh + (vv & 3);
+    for (int vv = 0; vv < 4; ++vv) {
+      const int rl = 4 * lh + vv;
 #pragma unroll
       for (int n = 0; n < kBF; ++n) strip[rl * kSLD + 32 * n + lc] = acc[i][n][vbase + vv];
     }
     __syncthreads();
-    const int col = tile_n * BN + ec;
+    const int col = tile_n * BN + WTN * wn + ec;
     float4 val[kSR / 2];
     int row[kSR / 2];
 #pragma unroll
     for (int q = 0; q < kSR / 2; ++q) {
-      row[q] = tile_m * BM + wave * 64 + kSR * c + 2 * q + er;
+      row[q] = tile_m * BM + WTM * wm + kSR * c + 2 * q + er;
       val[q] = *reinterpret_cast<const float4*>(&strip[(2 * q + er) * kSLD + ec]);
     }
     if (partial) {
@@ -226,7 +231,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
         if (row[q] < Mrows && col < g.N)  // N is a multiple of 4 here (checked on the host)
           *reinterpret_cast<float4*>(pdst + (int64_t)row[q] * g.N + col) = val[q];
     } else if constexpr (EPI == EPI_RESIDUAL) {
-      // r = x - acc; R written; per row the sums of r^2 and x^2 over this workgroup's 128 columns
+      // r = x - acc; R written; per row the sums of r^2 and x^2 over this wave's 128 columns
       float4 x[kSR / 2];
 #pragma unroll
       for (int q = 0; q < kSR / 2; ++q) {
@@ -252,8 +257,8 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
         }
         sr = group_sum_rt(sr, 32);
         sx = group_sum_rt(sx, 32);
-        if ((lane & 31) == 0 && row[q] < Mrows) {
-          float* pn = g.part_n + ((int64_t)tile_n * g.part_tokens + row[q]) * 2;
+        if ((lane & 31) == 0 && row[q] < Mrows && tile_n * BN + WTN * wn < g.N) {
+          float* pn = g.part_n + ((int64_t)(tile_n * (BN / WTN) + wn) * g.part_tokens + row[q]) * 2;
           pn[0] = sr;
           pn[1] = sx;
         }
@@ -403,6 +408,6 @@ hipError_t mfma_transpose_bf16(const void* U, void* Ut, int rows, int cols, hipS
   return hipGetLastError();
 }
 
-int mfma_res_tiles(int64_t d) { return (int)ceil_div(d, BN); }
+int mfma_res_tiles(int64_t d) { return (int)ceil_div(d, WTN); }
 
 }  // namespace gsi
