@@ -211,9 +211,17 @@ static void fill_proj_task(gsi::ProjTask& t, const void* U, const void* X, int64
 
 // Prefill-sized projection on the matrix cores: C = X U, R = X - C U^T with per-tile partial norms, then
 // the norm (+ gate) kernel.  `gate` may be null (norms only).
+// `img` (optional): image terms Y = C M^T of maps that read this input; they need c only, so they ride in the
+// residual's launch as further right-hand factors of the same left operand.
+struct ImageRider {
+  const void* M;
+  float* Y;
+  int64_t m;
+};
 static hipError_t mfma_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int xdtype, float* C,
                                float* R, float* rnorm, float* xnorm, uint8_t* mask, int32_t* fired_idx,
-                               int32_t* n_fired, bool with_gate, float eps, void* ws, hipStream_t s) {
+                               int32_t* n_fired, bool with_gate, float eps, void* ws, hipStream_t s,
+                               const ImageRider* img = nullptr, int n_img = 0) {
   void* Ut = ws;
   float* part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + gsi::align_up((size_t)k * d * 2, 256));
   hipError_t e = gsi::mfma_transpose_bf16(U, Ut, (int)d, (int)k, s);
@@ -235,7 +243,14 @@ static hipError_t mfma_project(const void* U, const void* X, int64_t d, int64_t 
   g.D = R; g.ldd = d;
   g.M = (int)B; g.N = (int)d; g.K = (int)k;
   g.X = X; g.xdtype = xdtype; g.ldx = d; g.part_n = part_n; g.part_tokens = (int)B;
-  e = gsi::mfma_gemm_nt(g, gsi::EPI_RESIDUAL, s);
+  if (n_img > 0) {
+    g.nseg = 1 + n_img;
+    g.seg[0] = gsi::GemmSeg{U, k, R, d, (int)d, 0, gsi::EPI_RESIDUAL};
+    for (int q = 0; q < n_img; ++q) g.seg[1 + q] = gsi::GemmSeg{img[q].M, k, img[q].Y, img[q].m, (int)img[q].m, 0, gsi::EPI_STORE_F32};
+    e = gsi::mfma_gemm_nt(g, gsi::EPI_MULTI, s);
+  } else {
+    e = gsi::mfma_gemm_nt(g, gsi::EPI_RESIDUAL, s);
+  }
   if (e != hipSuccess) return e;
   gsi::ProjBatch pb;
   std::memset(&pb, 0, sizeof(pb));
@@ -257,15 +272,19 @@ static bool mfma_project_path(const void* U, const void* X, int64_t d, int64_t k
 // over the compacted list (row tiles beyond the device-side count exit at once).
 static hipError_t mfma_gated(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
                              const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, float* Y,
-                             float* part, hipStream_t s, const void* Xwx = nullptr, int xdtype = 0) {
+                             float* part, hipStream_t s, const void* Xwx = nullptr, int xdtype = 0,
+                             bool image_done = false) {
   gsi::GemmArgs g;
-  std::memset(&g, 0, sizeof(g));
-  g.A = C; g.lda = k; g.a_f32 = 1;
-  g.B = M; g.ldb = k;
-  g.D = Y; g.ldd = m;
-  g.M = (int)B; g.N = (int)m; g.K = (int)k;
-  hipError_t e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
-  if (e != hipSuccess) return e;
+  hipError_t e = hipSuccess;
+  if (!image_done) {
+    std::memset(&g, 0, sizeof(g));
+    g.A = C; g.lda = k; g.a_f32 = 1;
+    g.B = M; g.ldb = k;
+    g.D = Y; g.ldd = m;
+    g.M = (int)B; g.N = (int)m; g.K = (int)k;
+    e = gsi::mfma_gemm_nt(g, gsi::EPI_STORE_F32, s);
+    if (e != hipSuccess) return e;
+  }
   std::memset(&g, 0, sizeof(g));
   // r enters rounded once to bf16: its term is scaled by the residual ratio, so the rounding (2^-9 relative)
   // adds a few 1e-4 of |y| at most, beside the 1.7e-3 that the bf16 image already costs
@@ -718,8 +737,20 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       const gsi_input_desc& in = inputs[i];
       if (mode[i] == kGeneric) {
         if (B > 0 && mfma_project_path(in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R)) {
+          // image terms of this input's maps that take the matrix-core path ride in the residual's launch
+          ImageRider riders[gsi::kMaxGemmSegs - 1];
+          int n_riders = 0;
+          for (int j = 0; j < n_maps && n_riders < gsi::kMaxGemmSegs - 1; ++j) {
+            const gsi_map_desc& mp = maps[j];
+            if (mp.input_id != i || img_done[j]) continue;
+            if (!mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) || !wx_vector_ok(in))
+              continue;
+            riders[n_riders++] = ImageRider{mp.M, mp.Y, mp.m};
+            img_done[j] = 1;
+          }
           hipError_t e = mfma_project(in.U, in.X, in.d, in.k, B, in.xdtype, in.C, in.R, in.rnorm, in.xnorm, in.mask,
-                                      in.fired_idx, in.n_fired, true, eps, reinterpret_cast<char*>(ws) + ws_off[i], s);
+                                      in.fired_idx, in.n_fired, true, eps, reinterpret_cast<char*>(ws) + ws_off[i], s,
+                                      riders, n_riders);
           if (e != hipSuccess) return hip_fail(e, fn);
         } else {
           if (B > 0) {
@@ -783,7 +814,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         const bool wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) != 0;
         if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
           e = mfma_gated(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B, mp.Y, part[j], s,
-                         wx ? in.X : nullptr, in.xdtype);
+                         wx ? in.X : nullptr, in.xdtype, img_done[j] != 0);
         else
           e = gsi::generic_gated_linear(mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
                                         mp.wdtype, mp.Y, s, wx ? in.X : nullptr, in.xdtype);

@@ -4,7 +4,20 @@
 
 namespace gsi {
 
-enum { EPI_STORE_BF16 = 0, EPI_STORE_F32 = 1, EPI_RESIDUAL = 2, EPI_SCATTER_ADD = 3, EPI_SCATTER_STORE = 4 };
+enum { EPI_STORE_BF16 = 0, EPI_STORE_F32 = 1, EPI_RESIDUAL = 2, EPI_SCATTER_ADD = 3, EPI_SCATTER_STORE = 4, EPI_MULTI = 5 };
+
+// One right-hand factor of a product with several (EPI_MULTI): the same A against B_0, B_1, ... side by side in
+// one launch, each with its own output and epilogue (EPI_RESIDUAL or EPI_STORE_F32).
+struct GemmSeg {
+  const void* B;
+  int64_t ldb;
+  void* D;
+  int64_t ldd;
+  int N;
+  int tile_begin;  // first column tile of this factor in the launch (filled by mfma_gemm_nt)
+  int epi;
+};
+constexpr int kMaxGemmSegs = 4;
 
 // D = A B^T, A[M,K] (bf16, or fp32 split into two bf16 terms), B[N,K] bf16, both row-major.
 struct GemmArgs {
@@ -28,6 +41,9 @@ struct GemmArgs {
   // by mfma_gemm_nt from mfma_splits()
   float* part;
   int splits;
+  // EPI_MULTI: the right-hand factors (B, ldb, D, ldd, N above are then unused)
+  GemmSeg seg[kMaxGemmSegs];
+  int nseg;
 };
 
 // how many ways mfma_gemm_nt splits the contraction of an M x N x K problem, and the workspace that takes

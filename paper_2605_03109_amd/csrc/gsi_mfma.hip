@@ -139,8 +139,22 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
     const int nd = g.n_rows_dev[0];
     Mrows = nd < Mrows ? nd : Mrows;
   }
-  const int tile_m = blockIdx.y, tile_n = blockIdx.x;
+  const int tile_m = blockIdx.y;
   if (tile_m * BM >= Mrows) return;  // uniform
+  // the right-hand factor of this workgroup: the only one, or the segment its column tile falls in
+  int tile_n = blockIdx.x, N = g.N, epi = EPI;
+  const void* Bmat = g.B;
+  void* Dmat = g.D;
+  int64_t ldb = g.ldb, ldd = g.ldd;
+  if constexpr (EPI == EPI_MULTI) {
+    int si = 0;
+#pragma unroll
+    for (int q = 1; q < kMaxGemmSegs; ++q)
+      if (q < g.nseg && (int)blockIdx.x >= g.seg[q].tile_begin) si = q;
+    const GemmSeg& sg = g.seg[si];
+    tile_n = blockIdx.x - sg.tile_begin;
+    N = sg.N; epi = sg.epi; Bmat = sg.B; Dmat = sg.D; ldb = sg.ldb; ldd = sg.ldd;
+  }
   const int tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lc = lane & 31, lh = lane >> 5;
@@ -166,8 +180,8 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
 #pragma unroll
   for (int u = 0; u < kBU; ++u) {
     int grow = tile_n * BN + (tid >> 3) + kRowsPerPass * u;
-    grow = grow < g.N ? grow : g.N - 1;
-    bp[u] = reinterpret_cast<const char*>(g.B) + ((int64_t)grow * g.ldb + 8 * (tid & 7)) * 2;
+    grow = grow < N ? grow : N - 1;
+    bp[u] = reinterpret_cast<const char*>(Bmat) + ((int64_t)grow * ldb + 8 * (tid & 7)) * 2;
   }
 
   f32x16 acc[kAF][kBF];
@@ -204,7 +218,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   constexpr int kSR = 8, kSLD = WTN + 4;  // strip rows, padded strip stride (floats)
   float* strip = reinterpret_cast<float*>(&As[0][0][0]) + wave * (kSR * kSLD);
   const bool partial = g.splits > 1;
-  float* const pdst = partial ? g.part + (int64_t)blockIdx.z * g.M * g.N : nullptr;
+  float* const pdst = partial ? g.part + (int64_t)blockIdx.z * g.M * N : nullptr;
   const int er = lane >> 5, ec = 4 * (lane & 31);  // row parity and first column of the lane's reads
 #pragma unroll
   for (int c = 0; c < WTM / kSR; ++c) {
@@ -228,15 +242,15 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
     if (partial) {
 #pragma unroll
       for (int q = 0; q < kSR / 2; ++q)
-        if (row[q] < Mrows && col < g.N)  // N is a multiple of 4 here (checked on the host)
-          *reinterpret_cast<float4*>(pdst + (int64_t)row[q] * g.N + col) = val[q];
-    } else if constexpr (EPI == EPI_RESIDUAL) {
+        if (row[q] < Mrows && col < N)  // N is a multiple of 4 here (checked on the host)
+          *reinterpret_cast<float4*>(pdst + (int64_t)row[q] * N + col) = val[q];
+    } else if (EPI == EPI_RESIDUAL || (EPI == EPI_MULTI && epi == EPI_RESIDUAL)) {
       // r = x - acc; R written; per row the sums of r^2 and x^2 over this wave's 128 columns
       float4 x[kSR / 2];
 #pragma unroll
       for (int q = 0; q < kSR / 2; ++q) {
         x[q] = float4{0.f, 0.f, 0.f, 0.f};
-        if (row[q] < Mrows && col < g.N) {
+        if (row[q] < Mrows && col < N) {
           if (g.xdtype == GSI_F32) {
             x[q] = *reinterpret_cast<const float4*>(reinterpret_cast<const float*>(g.X) + (int64_t)row[q] * g.ldx + col);
           } else {
@@ -247,17 +261,17 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
       }
 #pragma unroll
       for (int q = 0; q < kSR / 2; ++q) {
-        const bool live = row[q] < Mrows && col < g.N;
+        const bool live = row[q] < Mrows && col < N;
         const float4 r = float4{x[q].x - val[q].x, x[q].y - val[q].y, x[q].z - val[q].z, x[q].w - val[q].w};
         float sr = 0.f, sx = 0.f;
         if (live) {
-          *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)row[q] * g.ldd + col) = r;
+          *reinterpret_cast<float4*>(reinterpret_cast<float*>(Dmat) + (int64_t)row[q] * ldd + col) = r;
           sr = fmaf(r.x, r.x, fmaf(r.y, r.y, fmaf(r.z, r.z, r.w * r.w)));
           sx = fmaf(x[q].x, x[q].x, fmaf(x[q].y, x[q].y, fmaf(x[q].z, x[q].z, x[q].w * x[q].w)));
         }
         sr = group_sum_rt(sr, 32);
         sx = group_sum_rt(sx, 32);
-        if ((lane & 31) == 0 && row[q] < Mrows && tile_n * BN + WTN * wn < g.N) {
+        if ((lane & 31) == 0 && row[q] < Mrows && tile_n * BN + WTN * wn < N) {
           float* pn = g.part_n + ((int64_t)(tile_n * (BN / WTN) + wn) * g.part_tokens + row[q]) * 2;
           pn[0] = sr;
           pn[1] = sx;
@@ -266,17 +280,17 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
     } else {
 #pragma unroll
       for (int q = 0; q < kSR / 2; ++q) {
-        if (row[q] < Mrows && col < g.N) {
+        if (row[q] < Mrows && col < N) {
           if constexpr (EPI == EPI_STORE_BF16) {
             uint2 o;
             o.x = (uint32_t)f32_to_bf16_bits(val[q].x) | ((uint32_t)f32_to_bf16_bits(val[q].y) << 16);
             o.y = (uint32_t)f32_to_bf16_bits(val[q].z) | ((uint32_t)f32_to_bf16_bits(val[q].w) << 16);
-            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(g.D) + (int64_t)row[q] * g.ldd + col) = o;
-          } else if constexpr (EPI == EPI_STORE_F32) {
-            *reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)row[q] * g.ldd + col) = val[q];
+            *reinterpret_cast<uint2*>(reinterpret_cast<uint16_t*>(Dmat) + (int64_t)row[q] * ldd + col) = o;
+          } else if constexpr (EPI == EPI_STORE_F32 || EPI == EPI_MULTI) {
+            *reinterpret_cast<float4*>(reinterpret_cast<float*>(Dmat) + (int64_t)row[q] * ldd + col) = val[q];
           } else {  // scatter: one workgroup owns an output element, so the update is ordered
             const int drow = g.row_idx ? g.row_idx[row[q]] : row[q];
-            float4* dp = reinterpret_cast<float4*>(reinterpret_cast<float*>(g.D) + (int64_t)drow * g.ldd + col);
+            float4* dp = reinterpret_cast<float4*>(reinterpret_cast<float*>(Dmat) + (int64_t)drow * ldd + col);
             if constexpr (EPI == EPI_SCATTER_STORE) {
               *dp = val[q];
             } else {
@@ -356,6 +370,11 @@ template <int AM>
 hipError_t launch_epi(const GemmArgs& g, int epi, hipStream_t s) {
   const int splits = g.splits > 1 ? g.splits : 1;
   dim3 grid((unsigned)ceil_div(g.N, BN), (unsigned)ceil_div(g.M, BM), (unsigned)splits);
+  if (epi == EPI_MULTI) {
+    grid.x = (unsigned)(g.seg[g.nseg - 1].tile_begin + ceil_div(g.seg[g.nseg - 1].N, BN));
+    gemm_nt<AM, EPI_MULTI><<<grid, kThreads, 0, s>>>(g);
+    return hipGetLastError();
+  }
   switch (epi) {
     case EPI_STORE_BF16: gemm_nt<AM, EPI_STORE_BF16><<<grid, kThreads, 0, s>>>(g); break;
     case EPI_STORE_F32: gemm_nt<AM, EPI_STORE_F32><<<grid, kThreads, 0, s>>>(g); break;
@@ -395,8 +414,21 @@ size_t mfma_part_bytes(int64_t M, int64_t N, int64_t K, int epi) {
 }
 
 hipError_t mfma_gemm_nt(const GemmArgs& g0, int epi, hipStream_t s) {
-  if (g0.M <= 0 || g0.N <= 0) return hipSuccess;
+  if (g0.M <= 0 || (epi != EPI_MULTI && g0.N <= 0)) return hipSuccess;
   GemmArgs g = g0;
+  if (epi == EPI_MULTI) {  // several right-hand factors side by side, never split
+    if (g.nseg < 1 || g.nseg > kMaxGemmSegs) return hipErrorInvalidValue;
+    int t = 0;
+    for (int i = 0; i < g.nseg; ++i) {
+      g.seg[i].tile_begin = t;
+      t += (int)ceil_div(g.seg[i].N, BN);
+    }
+    g.N = g.seg[0].N;
+    g.splits = 1;
+    g.part = nullptr;
+    if (g.a_f32 == 2) return launch_epi<2>(g, epi, s);
+    return g.a_f32 ? launch_epi<1>(g, epi, s) : launch_epi<0>(g, epi, s);
+  }
   g.splits = g.part ? mfma_splits(g.M, g.N, g.K, epi) : 1;
   if (g.a_f32 == 2) return launch_epi<2>(g, epi, s);
   return g.a_f32 ? launch_epi<1>(g, epi, s) : launch_epi<0>(g, epi, s);
