@@ -82,13 +82,17 @@ int gsi_gate(const float* rnorm, const float* xnorm, int64_t B, float eps, uint8
 /* Gated linear map: Y[t,:] = M C[t,:] for every token, plus W R[t,:] for t in fired_idx[0..n_fired).
  * Tokens that did not fire never touch W; when n_fired == 0 no byte of W is read.  W[m,d], M[m,k]
  * in `wdtype`; C, R fp32; fired_idx / n_fired are the device outputs of gsi_gate; Y[B,m] fp32
- * (`ydtype` must be GSI_F32).  ws: GSI_CALL_GATED_LINEAR. */
+ * (`ydtype` must be GSI_F32).  ws: GSI_CALL_GATED_LINEAR (partial products of the several-token kernels).
+ * Arithmetic by call size (bf16 weights): one token -- fp32 FMA on widened weights; 2..128 tokens -- MFMA
+ * with c and r fed as bf16 head + tail (nothing rounded to 8 bits); more than 128 tokens -- MFMA GEMM with
+ * c as head + tail and r rounded once to bf16 (its term is scaled by the residual ratio). */
 int gsi_gated_linear(const void* W, const void* M, const float* C, const float* R, const int32_t* fired_idx,
                      const int32_t* n_fired, int64_t m, int64_t d, int64_t k, int64_t B, int wdtype, void* Y,
                      int ydtype, void* ws, size_t ws_bytes, void* stream);
 
 /* Dense baseline Y[t,:] = W X[t,:] (what the method is measured against; Section 3.1 "standard
- * linear-layer computation").  Same kernels as the fired path of gsi_gated_linear.  Y fp32. */
+ * linear-layer computation").  Same kernels as the fired path of gsi_gated_linear.  Y fp32.
+ * ws: GSI_CALL_DENSE_LINEAR (0 bytes for a single token). */
 int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype, int xdtype,
                      float* Y, void* ws, size_t ws_bytes, void* stream);
 
