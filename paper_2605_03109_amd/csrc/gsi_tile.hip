@@ -619,6 +619,7 @@ bool tile_rows_ok(const LinBatch& lb, int wdtype) {
   for (int i = 0; i < lb.n; ++i) {
     const LinTask& t = lb.t[i];
     if (t.m % 4 || reinterpret_cast<uintptr_t>(t.Y) % 16 || reinterpret_cast<uintptr_t>(t.W) % 16) return false;
+    if ((int64_t)t.m * lb.g[t.group].d * 2 >= (1ll << 32)) return false;  // 32-bit byte offsets into a matrix
     if (!t.part || reinterpret_cast<uintptr_t>(t.part) % 16) return false;
     if (!lb.dense && reinterpret_cast<uintptr_t>(t.M) % 16) return false;
   }
