@@ -69,70 +69,85 @@ __device__ __forceinline__ u32x4 round8(const u32x4& x0, const u32x4& x1, u32x4*
                (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16)};
 }
 
-// requests k-tile kt of both operands (unit u of a thread: row (tid >> 3) + 64 u, columns 8 (tid & 7) .. + 8)
+// requests unit u of k-tile kt of both operands (unit u of a thread: row (tid >> 3) + 64 u, columns 8 (tid & 7) .. + 8)
+template <int AM>
+__device__ __forceinline__ void issue_unit(Stage<AM>& st, int u, const char* const (&ap)[kAU], const char* const (&bp)[kBU], int kt) {
+  constexpr int ES = AM ? 4 : 2;
+  const char* p = ap[u] + (int64_t)kt * BK * ES;
+  st.a[u][0] = *reinterpret_cast<const u32x4*>(p);
+  if constexpr (AM != 0) st.a[u][1] = *reinterpret_cast<const u32x4*>(p + 16);
+  st.b[u] = *reinterpret_cast<const u32x4*>(bp[u] + (int64_t)kt * BK * 2);
+}
 template <int AM>
 __device__ __forceinline__ void issue(Stage<AM>& st, const char* const (&ap)[kAU], const char* const (&bp)[kBU], int kt) {
-  constexpr int ES = AM ? 4 : 2;
 #pragma unroll
-  for (int u = 0; u < kAU; ++u) {
-    const char* p = ap[u] + (int64_t)kt * BK * ES;
-    st.a[u][0] = *reinterpret_cast<const u32x4*>(p);
-    if constexpr (AM != 0) st.a[u][1] = *reinterpret_cast<const u32x4*>(p + 16);
-  }
-#pragma unroll
-  for (int u = 0; u < kBU; ++u) st.b[u] = *reinterpret_cast<const u32x4*>(bp[u] + (int64_t)kt * BK * 2);
+  for (int u = 0; u < kAU; ++u) issue_unit<AM>(st, u, ap, bp, kt);
 }
 
-// writes the staged k-tile to LDS as bf16 (fp32 A: rounded, or head and tail tiles)
+// writes unit u of the staged k-tile to LDS as bf16 (fp32 A: rounded, or head and tail tiles)
 template <int AM>
-__device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t (*As)[BM][LDB], uint16_t (*Bs)[LDB], int tid) {
-  const int r0 = tid >> 3, c8 = 8 * (tid & 7);
-#pragma unroll
-  for (int u = 0; u < kAU; ++u) {
-    u32x4* d0 = reinterpret_cast<u32x4*>(&As[0][r0 + kRowsPerPass * u][c8]);
-    if constexpr (AM == 0) {
-      *d0 = st.a[u][0];
-    } else if constexpr (AM == 2) {
-      *d0 = round8(st.a[u][0], st.a[u][1], nullptr);
-    } else {
-      u32x4 tail;
-      *d0 = round8(st.a[u][0], st.a[u][1], &tail);
-      *reinterpret_cast<u32x4*>(&As[1][r0 + kRowsPerPass * u][c8]) = tail;
-    }
+__device__ __forceinline__ void commit_unit(const Stage<AM>& st, int u, uint16_t (*Ah)[LDB], uint16_t (*At)[LDB],
+                                            uint16_t (*Bq)[LDB], int tid) {
+  const int r = (tid >> 3) + kRowsPerPass * u, c8 = 8 * (tid & 7);
+  u32x4* d0 = reinterpret_cast<u32x4*>(&Ah[r][c8]);
+  if constexpr (AM == 0) {
+    *d0 = st.a[u][0];
+  } else if constexpr (AM == 2) {
+    *d0 = round8(st.a[u][0], st.a[u][1], nullptr);
+  } else {
+    u32x4 tail;
+    *d0 = round8(st.a[u][0], st.a[u][1], &tail);
+    *reinterpret_cast<u32x4*>(&At[r][c8]) = tail;
   }
+  *reinterpret_cast<u32x4*>(&Bq[r][c8]) = st.b[u];
+}
+template <int AM>
+__device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t (*Ah)[LDB], uint16_t (*At)[LDB], uint16_t (*Bq)[LDB], int tid) {
 #pragma unroll
-  for (int u = 0; u < kBU; ++u) *reinterpret_cast<u32x4*>(&Bs[r0 + kRowsPerPass * u][c8]) = st.b[u];
+  for (int u = 0; u < kAU; ++u) commit_unit<AM>(st, u, Ah, At, Bq, tid);
 }
 
-// one k-tile from LDS: lane half lh takes columns 32 lh .. + 32 of the tile, eight per MFMA step (both
-// operands in the same order, so the order of the contraction index does not matter)
+// The MFMA operands of one step (16 columns of the k-tile) of a wave: lane half lh takes columns 32 lh .. + 32 of
+// the tile, eight per step (both operands in the same order, so the order of the contraction index does not
+// matter)
 template <int AM>
-__device__ __forceinline__ void compute(const uint16_t (*As)[BM][LDB], const uint16_t (*Bs)[LDB], int wm, int wn, int lc, int lh,
-                                        f32x16 (&acc)[kAF][kBF]) {
+struct Ops {
+  bf16x8 a[kAF];
+  bf16x8 al[AM == 1 ? kAF : 1];
+  bf16x8 b[kBF];
+};
+template <int AM>
+__device__ __forceinline__ void read_ops(Ops<AM>& o, const uint16_t (*Ah)[LDB], const uint16_t (*At)[LDB],
+                                         const uint16_t (*Bq)[LDB], int wm, int wn, int lc, int lh, int j) {
+  const int col = 32 * lh + 8 * j;
 #pragma unroll
-  for (int j = 0; j < kKS; ++j) {
-    const int col = 32 * lh + 8 * j;
-    bf16x8 b[kBF];
+  for (int n = 0; n < kBF; ++n) o.b[n] = *reinterpret_cast<const bf16x8*>(&Bq[WTN * wn + 32 * n + lc][col]);
 #pragma unroll
-    for (int n = 0; n < kBF; ++n) b[n] = *reinterpret_cast<const bf16x8*>(&Bs[WTN * wn + 32 * n + lc][col]);
+  for (int i = 0; i < kAF; ++i) {
+    o.a[i] = *reinterpret_cast<const bf16x8*>(&Ah[WTM * wm + 32 * i + lc][col]);
+    if constexpr (AM == 1) o.al[i] = *reinterpret_cast<const bf16x8*>(&At[WTM * wm + 32 * i + lc][col]);
+  }
+}
+template <int AM>
+__device__ __forceinline__ void mma(const Ops<AM>& o, f32x16 (&acc)[kAF][kBF]) {
 #pragma unroll
-    for (int i = 0; i < kAF; ++i) {
-      const bf16x8 a = *reinterpret_cast<const bf16x8*>(&As[0][WTM * wm + 32 * i + lc][col]);
+  for (int i = 0; i < kAF; ++i) {
 #pragma unroll
-      for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[n], acc[i][n], 0, 0, 0);
-      if constexpr (AM == 1) {
-        const bf16x8 al = *reinterpret_cast<const bf16x8*>(&As[1][WTM * wm + 32 * i + lc][col]);
+    for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.a[i], o.b[n], acc[i][n], 0, 0, 0);
+    if constexpr (AM == 1) {
 #pragma unroll
-        for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(al, b[n], acc[i][n], 0, 0, 0);
-      }
+      for (int n = 0; n < kBF; ++n) acc[i][n] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(o.al[i], o.b[n], acc[i][n], 0, 0, 0);
     }
   }
 }
 
 template <int AM, int EPI>
 __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
-  __shared__ __align__(16) uint16_t As[AM == 1 ? 2 : 1][BM][LDB];
-  __shared__ __align__(16) uint16_t Bs[BN][LDB];
+  // fp32 head + tail operand: As[0] head, As[1] tail, one staged k-tile.  Otherwise two staged k-tiles (As[s],
+  // Bs[s]): one is multiplied while the next is written.
+  constexpr bool kTwoStages = AM != 1;
+  __shared__ __align__(16) uint16_t As[2][BM][LDB];
+  __shared__ __align__(16) uint16_t Bs[kTwoStages ? 2 : 1][BN][LDB];
 
   int Mrows = g.M;
   if (g.n_rows_dev) {
@@ -166,7 +181,7 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   const int splits = g.splits > 1 ? g.splits : 1;
   const int kt0 = (int)(((int64_t)nk * blockIdx.z) / splits), kt1 = (int)(((int64_t)nk * (blockIdx.z + 1)) / splits);
 
-  // staging pointers: a thread's unit u is row (tid >> 3) + 32 u of the tile, 8 columns at 8 (tid & 7); rows past
+  // staging pointers: a thread's unit u is row (tid >> 3) + 64 u of the tile, 8 columns at 8 (tid & 7); rows past
   // the end repeat the last one (their results are not stored)
   const char* ap[kAU];
   const char* bp[kBU];
@@ -194,19 +209,63 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
 
   if (kt0 < kt1) {
     Stage<AM> st;
-    issue<AM>(st, ap, bp, kt0);
-    commit<AM>(st, As, Bs, tid);
-    __syncthreads();
-    for (int kt = kt0; kt < kt1; ++kt) {
-      // the next k-tile travels from memory to registers while this one is multiplied (past the range the
-      // last tile is requested again and never used)
-      __builtin_amdgcn_sched_barrier(0);
-      issue<AM>(st, ap, bp, kt + 1 < kt1 ? kt + 1 : kt);
-      __builtin_amdgcn_sched_barrier(0);
-      compute<AM>(As, Bs, wm, wn, lc, lh, acc);
-      __syncthreads();  // every wave has read the tile
-      commit<AM>(st, As, Bs, tid);
+    if constexpr (kTwoStages) {
+      // Tile t is multiplied out of stage t & 1 while tile t + 1 (in registers since the tile before) is written
+      // to the other stage, a unit per MFMA step, and each unit's registers are asked for tile t + 2 at once.
+      // One barrier per tile, before the last step: by then every wave has written its share of the next stage
+      // and has the last step's operands in registers, so the first operands of the next tile are read behind
+      // the last step's MFMAs.  Past the range the last tile is requested (and staged) again and never used.
+      static_assert(kAU == kKS && kBU == kKS, "one staging unit per MFMA step");
+      issue<AM>(st, ap, bp, kt0);
+      commit<AM>(st, As[0], nullptr, Bs[0], tid);
+      issue<AM>(st, ap, bp, kt0 + 1 < kt1 ? kt0 + 1 : kt0);
       __syncthreads();
+      Ops<AM> o[2];
+      read_ops<AM>(o[0], As[0], nullptr, Bs[0], wm, wn, lc, lh, 0);
+      for (int kt = kt0; kt < kt1; ++kt) {
+        const int cur = (kt - kt0) & 1, nxt = cur ^ 1;
+        const int kt2 = kt + 2 < kt1 ? kt + 2 : kt1 - 1;
+#pragma unroll
+        for (int j = 0; j < kKS; ++j) {
+          if (j + 1 < kKS) {
+            read_ops<AM>(o[(j + 1) & 1], As[cur], nullptr, Bs[cur], wm, wn, lc, lh, j + 1);
+          } else {
+            __syncthreads();
+            read_ops<AM>(o[(j + 1) & 1], As[nxt], nullptr, Bs[nxt], wm, wn, lc, lh, 0);
+          }
+          mma<AM>(o[j & 1], acc);
+          if (j + 1 < kKS) {
+            // units 0, 1 behind steps 0, 1; units 2 and 3 behind step 2 (the barrier follows)
+            commit_unit<AM>(st, j, As[nxt], nullptr, Bs[nxt], tid);
+            issue_unit<AM>(st, j, ap, bp, kt2);
+            if (j + 2 == kKS) {
+              commit_unit<AM>(st, j + 1, As[nxt], nullptr, Bs[nxt], tid);
+              issue_unit<AM>(st, j + 1, ap, bp, kt2);
+            }
+          }
+          __builtin_amdgcn_sched_barrier(0);
+        }
+      }
+    } else {
+      issue<AM>(st, ap, bp, kt0);
+      commit<AM>(st, As[0], As[1], Bs[0], tid);
+      __syncthreads();
+      for (int kt = kt0; kt < kt1; ++kt) {
+        // the next k-tile travels from memory to registers while this one is multiplied (past the range the
+        // last tile is requested again and never used)
+        __builtin_amdgcn_sched_barrier(0);
+        issue<AM>(st, ap, bp, kt + 1 < kt1 ? kt + 1 : kt);
+        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int j = 0; j < kKS; ++j) {
+          Ops<AM> o;
+          read_ops<AM>(o, As[0], As[1], Bs[0], wm, wn, lc, lh, j);
+          mma<AM>(o, acc);
+        }
+        __syncthreads();  // every wave has read the tile
+        commit<AM>(st, As[0], As[1], Bs[0], tid);
+        __syncthreads();
+      }
     }
   }
 
