@@ -9,12 +9,16 @@
 // on the main term is not rounded to 8 bits (the bf16 image already uses most of the 2e-3 budget).
 //
 // Workgroup tile 256 x 256 x 64, eight waves 4 x 2 (two per SIMD, so that one wave's MFMAs cover the
-// other's LDS reads, staging and barriers), each wave 64 x 128 as 2 x 4 v_mfma_f32_32x32x16_bf16 fragments.
+// other's LDS reads and staging), each wave 64 x 128 as 2 x 4 v_mfma_f32_32x32x16_bf16 fragments.
 // Both operand tiles are staged in LDS as bf16 (row stride padded to 144 bytes: conflict-free 128-bit
 // reads); an fp32 A operand is converted on the way in.  Global loads are whole 128-byte row segments per
-// eight lanes; the next k-tile travels to registers during the MFMAs of the current one.  Within a k-tile
-// the lane half l/32 takes 32 consecutive columns, eight per MFMA step: any order of the contraction index
-// is as good as another as long as both operands agree.
+// eight lanes.  With a bf16 or once-rounded A operand LDS holds two k-tiles: tile t is multiplied while
+// tile t + 1 is written, a quarter per MFMA step, from registers that are asked for tile t + 2 at once; one
+// barrier per tile.  The head + tail form needs both halves of A in LDS and keeps one staged tile and two
+// barriers.  Within a k-tile the lane half l/32 takes 32 consecutive columns, eight per MFMA step: any order
+// of the contraction index is as good as another as long as both operands agree.
+// What bounds the loop is LDS, not the matrix cores: a k-tile is 2048 MFMA cycles per SIMD, and its LDS
+// traffic (192 KB of operand reads at 128 bytes a cycle, 64 KB of staging writes at about 75) is 2400.
 // Problems with few output tiles split the contraction over blockIdx.z; the partial sums go to the workspace
 // and a second kernel adds them in split order and applies the epilogue.
 // Operands that are N-contiguous in memory (U as the right factor of W U and X U) are transposed
