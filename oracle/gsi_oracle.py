@@ -25,7 +25,9 @@ the design notes):
   * the fired-token output is M c + W r (Eq. (exact)); Algorithm 1 prints W x
     for the slow path, which is the same value in exact arithmetic --
     ``gated_linear_alg1`` is that variant;
-  * eps is the fp32 value the device receives, widened to fp64.
+  * eps is the fp32 value the device receives, widened to fp64;
+  * the FP8 image of Section 7 "Combination with quantization" is OCP E4M3 with one
+    power-of-two scale per output row (the paper names neither format nor scaling).
 
 Every function here is pinned by tests that do not call the oracle to obtain
 their expected value (hand-worked numbers, closed forms, invariants, brute
@@ -151,6 +153,90 @@ def gated_linear_alg1(W: np.ndarray, M: np.ndarray, C: np.ndarray, X: np.ndarray
     for t in range(B):
         Y[t] = W @ X[t] if mask[t] else M @ C[t]
     return Y
+
+
+# ----------------------------------------------------------------------------
+# Section 7 "Combination with quantization": the cached image stored in 8-bit floating point
+# ----------------------------------------------------------------------------
+# The paper names FP8 and the 2x smaller fast-path read, not a format.  Reading taken here: the OCP 8-bit
+# E4M3 encoding (sign, 4 exponent bits with bias 7, 3 mantissa bits; exponent field 0 is subnormal,
+# m/8 * 2^-6; exponent field 15 with mantissa 7 is NaN, there are no infinities; largest finite value
+# 1.75 * 2^8 = 448), one power-of-two scale per output row, round to nearest with ties to the even code.
+FP8_MAX = 448.0
+
+
+def fp8_e4m3_decode(codes: np.ndarray) -> np.ndarray:
+    """Value of every E4M3 code (uint8 -> fp64), NaN for the two NaN codes."""
+    c = np.asarray(codes, dtype=np.uint8).astype(np.int64)
+    sign = np.where(c & 0x80, -1.0, 1.0)
+    e = (c >> 3) & 0xF
+    m = (c & 0x7).astype(np.float64)
+    val = np.where(e == 0, (m / 8.0) * 2.0 ** -6, (1.0 + m / 8.0) * np.exp2((e - 7).astype(np.float64)))
+    val = np.where((e == 15) & ((c & 0x7) == 7), np.nan, val)
+    return sign * val
+
+
+def fp8_e4m3_encode(x: np.ndarray) -> np.ndarray:
+    """Nearest E4M3 code of every element (ties to the even code), |x| above 448 saturating to 448.
+
+    Works on the value grid itself: in the binade 2^e <= |x| < 2^(e+1) (e clamped to the subnormal
+    exponent -6 below) the codes are spaced 2^(e-3) apart, so the code index is |x| / 2^(e-3) rounded
+    half-to-even; an index that rounds up to 16 is the first code of the next binade.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    a = np.abs(x)
+    out = np.zeros(x.shape, dtype=np.uint8)
+    nan = np.isnan(x)
+    a = np.where(nan, 0.0, np.minimum(a, FP8_MAX))
+    with np.errstate(divide="ignore"):
+        e = np.floor(np.log2(np.where(a > 0, a, 1.0))).astype(np.int64)
+    # log2 of a value just below a power of two may round up: correct by comparison
+    e = np.where(np.exp2(e.astype(np.float64)) > a, e - 1, e)
+    e = np.where(np.exp2((e + 1).astype(np.float64)) <= a, e + 1, e)
+    e = np.maximum(e, -6)
+    step = np.exp2((e - 3).astype(np.float64))
+    q = np.rint(a / step).astype(np.int64)        # numpy rounds half to even; a / step is exact
+    # q counts steps from zero of this binade's grid: normal binades have q in [8, 16], the
+    # subnormal one q in [0, 8]
+    carry = q == 16
+    e = np.where(carry, e + 1, e)
+    q = np.where(carry, 8, q)
+    normal = q >= 8
+    field = np.where(normal, e + 7, 0)
+    mant = np.where(normal, q - 8, q)
+    code = (field << 3) | mant
+    code = np.where(a > 0, code, 0)
+    code = np.where(np.signbit(x) & ~nan, code | 0x80, code)
+    out[...] = np.where(nan, 0x7F, code).astype(np.uint8)
+    return out
+
+
+def fp8_row_scale(M: np.ndarray) -> np.ndarray:
+    """Per-row power-of-two scale: the smallest 2^e (e in [-126, 127]) with max_j |M_ij| / 2^e <= 448; 1 for a zero row."""
+    M = np.asarray(M, dtype=np.float64)
+    amax = np.max(np.abs(M), axis=1) if M.shape[1] else np.zeros(M.shape[0])
+    scale = np.ones(M.shape[0])
+    for i, a in enumerate(amax):
+        if a > 0:
+            e = int(np.ceil(np.log2(a / FP8_MAX)))
+            while a / 2.0 ** e > FP8_MAX:       # guard the rounding of log2
+                e += 1
+            while a / 2.0 ** (e - 1) <= FP8_MAX:
+                e -= 1
+            scale[i] = 2.0 ** min(max(e, -126), 127)
+    return scale
+
+
+def quantize_image_fp8(M: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """codes[m, k] (uint8), scale[m]: codes_ij = E4M3(M_ij / scale_i).  M is the stored image, widened."""
+    M = np.asarray(M, dtype=np.float64)
+    scale = fp8_row_scale(M)
+    return fp8_e4m3_encode(M / scale[:, None]), scale
+
+
+def dequantize_image_fp8(codes: np.ndarray, scale: np.ndarray) -> np.ndarray:
+    """M_ij = scale_i * value(codes_ij), fp64."""
+    return fp8_e4m3_decode(codes) * np.asarray(scale, dtype=np.float64)[:, None]
 
 
 # ----------------------------------------------------------------------------

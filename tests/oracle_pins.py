@@ -338,3 +338,125 @@ PINS = [
     pin_widen,
     pin_stack,
 ]
+
+
+# ---- the FP8 image (Section 7 "Combination with quantization"; format reading: OCP E4M3, power-of-two row scales) ----
+def _fp8_grid():
+    """All finite E4M3 magnitudes from the definition, ascending, with their codes -- built without the oracle."""
+    vals = []
+    for e in range(16):
+        for m in range(8):
+            if e == 15 and m == 7:
+                continue
+            v = (m / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + m / 8.0) * 2.0 ** (e - 7)
+            vals.append((v, (e << 3) | m))
+    return vals
+
+
+def pin_fp8_code_values(O, rows):
+    codes = np.array([int(r[0], 16) for r in rows], dtype=np.uint8)
+    want = np.array([float(r[1]) for r in rows])
+    got = O.fp8_e4m3_decode(codes)
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    ok = ~np.isnan(want)
+    assert np.array_equal(got[ok], want[ok])
+    assert np.array_equal(np.signbit(got[ok]), np.signbit(want[ok]) | (codes[ok] >= 0x80))
+
+
+def pin_fp8_decode_all_codes(O):
+    grid = _fp8_grid()
+    got = O.fp8_e4m3_decode(np.arange(256, dtype=np.uint8))
+    for v, c in grid:
+        assert got[c] == v and got[c | 0x80] == -v
+    assert np.isnan(got[0x7F]) and np.isnan(got[0xFF])
+    assert len(grid) == 127 and max(v for v, _ in grid) == 448.0
+
+
+def pin_fp8_encode_is_nearest_ties_even(O):
+    grid = _fp8_grid()
+    vals = np.array([v for v, _ in grid])
+    codes = np.array([c for _, c in grid])
+    # every code value encodes to itself, with the sign bit
+    assert np.array_equal(O.fp8_e4m3_encode(vals), codes.astype(np.uint8))
+    assert np.array_equal(O.fp8_e4m3_encode(-vals[1:]), (codes[1:] | 0x80).astype(np.uint8))
+    # exact midpoints go to the neighbour with the even code; a hair to either side goes to that side
+    mid = 0.5 * (vals[:-1] + vals[1:])
+    got = O.fp8_e4m3_encode(mid)
+    even = np.where(codes[:-1] % 2 == 0, codes[:-1], codes[1:])
+    assert np.array_equal(got, even.astype(np.uint8))
+    assert np.array_equal(O.fp8_e4m3_encode(np.nextafter(mid, 0.0)), codes[:-1].astype(np.uint8))
+    assert np.array_equal(O.fp8_e4m3_encode(np.nextafter(mid, np.inf)), codes[1:].astype(np.uint8))
+    # brute force over random magnitudes spanning subnormal to maximum: the chosen code is a nearest one
+    rng = np.random.default_rng(5)
+    x = np.exp(rng.uniform(np.log(2.0 ** -12), np.log(448.0), 4000)) * rng.choice([-1.0, 1.0], 4000)
+    got = O.fp8_e4m3_encode(x)
+    dist = np.abs(np.abs(x)[:, None] - vals[None, :])
+    best = dist.min(axis=1)
+    chosen = np.abs(O.fp8_e4m3_decode(got))
+    assert np.array_equal(np.abs(np.abs(x) - chosen), best)
+    assert np.array_equal(got >= 0x80, x < 0)
+    # monotone
+    xs = np.sort(np.abs(x))
+    assert np.all(np.diff(O.fp8_e4m3_encode(xs).astype(int)) >= 0)
+
+
+def pin_fp8_saturation_and_nan(O):
+    got = O.fp8_e4m3_encode(np.array([449.0, 464.0, 1e6, -1e6, np.inf, -np.inf, np.nan, 0.0, -0.0, 2.0 ** -10, 2.0 ** -10 * 1.01]))
+    assert list(got) == [0x7E, 0x7E, 0x7E, 0xFE, 0x7E, 0xFE, 0x7F, 0x00, 0x80, 0x00, 0x01]
+
+
+def pin_fp8_matches_library_cast(O):
+    # PyTorch's CPU cast to float8_e4m3fn is an independent implementation of the same encoding
+    # (round to nearest even); compared inside the finite range, where saturation does not matter
+    import torch
+    rng = np.random.default_rng(6)
+    x = (rng.standard_normal(50000) * np.exp(rng.uniform(-12, 6, 50000))).clip(-448, 448).astype(np.float32)
+    want = torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    assert np.array_equal(O.fp8_e4m3_encode(x), want)
+    back = torch.from_numpy(want).view(torch.float8_e4m3fn).to(torch.float64).numpy()
+    assert np.array_equal(O.fp8_e4m3_decode(want), back)
+
+
+def pin_fp8_row_scale(O):
+    M = np.array([[448.0, 1.0], [448.0000001, 0.0], [224.0, -3.0], [-224.0000001, 3.0], [0.0, 0.0], [1e-30, 0.0], [-7.0, 6.0]])
+    s = O.fp8_row_scale(M)
+    assert list(s) == [1.0, 2.0, 0.5, 1.0, 1.0, 2.0 ** -108, 2.0 ** -6]
+    rng = np.random.default_rng(7)
+    M = rng.standard_normal((64, 32)) * np.exp(rng.uniform(-20, 20, (64, 1)))
+    s = O.fp8_row_scale(M)
+    top = np.abs(M).max(axis=1) / s
+    assert np.all((top > 224.0) & (top <= 448.0))
+    assert np.all(np.log2(s) == np.round(np.log2(s)))
+
+
+def pin_fp8_quantization_error(O):
+    # relative error at most half a code step (2^-4) on elements in the normal range of their row,
+    # absolute error at most half the subnormal step below it; the image product inherits the bound
+    rng = np.random.default_rng(8)
+    m, k = 48, 40
+    M = rng.standard_normal((m, k)) * np.exp(rng.uniform(-3, 3, (m, k)))
+    codes, s = O.quantize_image_fp8(M)
+    Mh = O.dequantize_image_fp8(codes, s)
+    normal = np.abs(M) >= s[:, None] * 2.0 ** -6
+    assert np.all(np.abs(Mh - M)[normal] <= 2.0 ** -4 * np.abs(M)[normal])
+    assert np.all(np.abs(Mh - M)[~normal] <= s[:, None].repeat(k, 1)[~normal] * 2.0 ** -10)
+    assert np.any(np.abs(Mh - M)[normal] > 2.0 ** -6 * np.abs(M)[normal])   # it is 3 bits, not more
+    c = rng.standard_normal(k)
+    bound = 2.0 ** -4 * (np.abs(M) @ np.abs(c)) + s * 2.0 ** -10 * np.sum(np.abs(c))
+    assert np.all(np.abs(Mh @ c - M @ c) <= bound)
+    # a matrix of code values is reproduced exactly, whatever the row scale
+    vals = np.array([v for v, _ in _fp8_grid()])[1:]
+    E = rng.choice(vals, (8, 16)) * rng.choice([-1.0, 1.0], (8, 16)) * (2.0 ** rng.integers(-9, 9, (8, 1)))
+    E[:, 0] = 448.0 * (2.0 ** np.round(np.log2(np.abs(E).max(axis=1) / 448.0) + 0.49999))  # pin the row maximum to a code value
+    codes, s = O.quantize_image_fp8(E)
+    assert np.array_equal(O.dequantize_image_fp8(codes, s), E)
+
+
+FP8_PINS = [
+    pin_fp8_decode_all_codes,
+    pin_fp8_encode_is_nearest_ties_even,
+    pin_fp8_saturation_and_nan,
+    pin_fp8_matches_library_cast,
+    pin_fp8_row_scale,
+    pin_fp8_quantization_error,
+]

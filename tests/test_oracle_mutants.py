@@ -9,7 +9,7 @@ import types
 import pytest
 
 from conftest import ROOT, read_golden
-from oracle_pins import PINS, pin_paper_closed_forms, pin_paper_speedups
+from oracle_pins import FP8_PINS, PINS, pin_fp8_code_values, pin_paper_closed_forms, pin_paper_speedups
 
 SRC = open(os.path.join(ROOT, "oracle", "gsi_oracle.py")).read()
 
@@ -45,6 +45,23 @@ MUTANTS = [
     ("stack_gate_per_map_wrong_eps", "mask, idx, n = gate(rn, xn, eps)", "mask, idx, n = gate(rn, xn, 2.0 * eps)"),
     ("stack_dense_uses_image", "name: dense_linear(W64, X) for name, W64, _ in g[\"maps\"]", "name: dense_linear(W64, X) * 1.0000001 for name, W64, _ in g[\"maps\"]"),
     ("error_bound_smallest_sv", "compute_uv=False)[0]", "compute_uv=False)[-1]"),
+    # the FP8 image
+    ("fp8_bias", "np.exp2((e - 7).astype(np.float64))", "np.exp2((e - 8).astype(np.float64))"),
+    ("fp8_subnormal_exponent", "(m / 8.0) * 2.0 ** -6", "(m / 8.0) * 2.0 ** -7"),
+    ("fp8_nan_code_is_480", "val = np.where((e == 15) & ((c & 0x7) == 7), np.nan, val)", "val = val + 0.0"),
+    ("fp8_sign_dropped", "return sign * val", "return val"),
+    ("fp8_round_half_up", "q = np.rint(a / step).astype(np.int64)", "q = np.floor(a / step + 0.5).astype(np.int64)"),
+    ("fp8_truncates", "q = np.rint(a / step).astype(np.int64)", "q = np.floor(a / step).astype(np.int64)"),
+    ("fp8_no_saturation", "np.minimum(a, FP8_MAX)", "np.minimum(a, 1e30)"),
+    ("fp8_subnormal_floor_exponent", "e = np.maximum(e, -6)", "e = np.maximum(e, -7)"),
+    ("fp8_carry_lost", "q = np.where(carry, 8, q)", "q = np.where(carry, 15, q)"),
+    ("fp8_encode_sign_dropped", "code = np.where(np.signbit(x) & ~nan, code | 0x80, code)", "code = code + 0"),
+    ("fp8_scale_uses_largest_normal_480", "FP8_MAX = 448.0", "FP8_MAX = 480.0"),
+    ("fp8_scale_not_power_of_two", "scale[i] = 2.0 ** min(max(e, -126), 127)", "scale[i] = a / FP8_MAX"),
+    ("fp8_scale_one_binade_large", "scale[i] = 2.0 ** min(max(e, -126), 127)", "scale[i] = 2.0 ** min(max(e + 1, -126), 127)"),
+    ("fp8_quantize_ignores_scale", "return fp8_e4m3_encode(M / scale[:, None]), scale", "return fp8_e4m3_encode(M), scale"),
+    ("fp8_dequantize_ignores_scale", "return fp8_e4m3_decode(codes) * np.asarray(scale, dtype=np.float64)[:, None]",
+     "return fp8_e4m3_decode(codes)"),
 ]
 
 
@@ -55,7 +72,8 @@ def _load(src):
 
 
 def _caught(O):
-    pins = list(PINS) + [
+    pins = list(PINS) + list(FP8_PINS) + [
+        lambda o: pin_fp8_code_values(o, read_golden("fp8_e4m3_values.txt")),
         lambda o: pin_paper_speedups(o, read_golden("paper_speedup_tables.txt")),
         lambda o: pin_paper_closed_forms(o, read_golden("paper_closed_forms.txt")),
     ]
