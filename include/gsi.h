@@ -49,6 +49,8 @@ enum gsi_status {
 };
 
 enum gsi_dtype { GSI_F32 = 0, GSI_BF16 = 1 };
+/* storage of a quantised image only (gsi_quantize_image_fp8, GSI_MAP_IMAGE_FP8); never a wdtype/xdtype */
+enum { GSI_FP8_E4M3 = 2 };
 
 /* selector for gsi_workspace_bytes() */
 enum gsi_call {
@@ -65,6 +67,15 @@ enum gsi_call {
  * accumulator when bf16).  ws: gsi_workspace_bytes(GSI_CALL_BUILD_IMAGE, m, d, k, 0). */
 int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d, int64_t k, int wdtype,
                     void* ws, size_t ws_bytes, void* stream);
+
+/* The cached image in 8-bit floating point (Section 7 "Combination with quantization": half the fast-path
+ * bytes).  The paper names no format; this library stores OCP E4M3 codes (1 sign, 4 exponent bits with bias 7,
+ * 3 mantissa bits, largest finite value 448, no infinities) with one power-of-two scale per output row:
+ *   scale[i] = the smallest 2^e (e in [-126, 127]) with max_j |M[i,j]| / 2^e <= 448, 1 for a zero row;
+ *   M8[i,j]  = the E4M3 code nearest to M[i,j] / scale[i], ties to the even code (the division is exact).
+ * M[m,k] in `mdtype` (GSI_F32 or GSI_BF16: an image as gsi_build_image wrote it), M8[m,k] bytes, scale[m] fp32.
+ * NaN elements give the NaN code 0x7F.  No workspace. */
+int gsi_quantize_image_fp8(const void* M, int mdtype, int64_t m, int64_t k, uint8_t* M8, float* scale, void* stream);
 
 /* Projection, residual and the two norms of Algorithm 1 lines 1-3 for B tokens.
  * U[d,k] in `udtype`, X[B,d] in `xdtype`.  Outputs (fp32): C[B,k] = X U, R[B,d] = X - C U^T (formed
@@ -122,12 +133,21 @@ enum { GSI_INPUT_SLOW_PATH_WX = 1 };
 
 typedef struct gsi_map_desc {
   const void* W;      /* [m,d] wdtype, d = inputs[input_id].d                                   */
-  const void* M;      /* [m,k] wdtype, k = inputs[input_id].k                                   */
+  const void* M;      /* [m,k] wdtype, k = inputs[input_id].k; E4M3 bytes with GSI_MAP_IMAGE_FP8 */
   float* Y;           /* [B,m] fp32                                                             */
   int64_t m;
   int32_t wdtype;
   int32_t input_id;   /* which input this map reads                                             */
+  const float* M_scale; /* [m] row scales of an FP8 image (gsi_quantize_image_fp8), else unused  */
+  int32_t flags;      /* 0, or GSI_MAP_IMAGE_FP8                                                */
+  int32_t reserved;   /* 0                                                                      */
 } gsi_map_desc;
+
+/* gsi_map_desc.flags.  GSI_MAP_IMAGE_FP8: M and M_scale are the outputs of gsi_quantize_image_fp8 and the
+ * image term is y_i = M_scale[i] * sum_j value(M[i,j]) c_j (fp32 accumulation).  Taken by single-token calls
+ * (B == 1) on the vector kernels only: k a multiple of 16 and at most 512, M aligned to 16 bytes, and the
+ * shapes and alignments of W, U, C, R that those kernels need; anything else returns GSI_ERR_SHAPE. */
+enum { GSI_MAP_IMAGE_FP8 = 1 };
 
 /* A chain of per-layer linear maps sharing their inputs' projections (Section 1: every linear map
  * of a block that reads the same input shares one basis, one projection and one gate).  For each

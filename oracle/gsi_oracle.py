@@ -212,9 +212,13 @@ def fp8_e4m3_encode(x: np.ndarray) -> np.ndarray:
 
 
 def fp8_row_scale(M: np.ndarray) -> np.ndarray:
-    """Per-row power-of-two scale: the smallest 2^e (e in [-126, 127]) with max_j |M_ij| / 2^e <= 448; 1 for a zero row."""
+    """Per-row power-of-two scale: the smallest 2^e (e in [-126, 127]) with max_j |M_ij| / 2^e <= 448; 1 for a zero row.
+
+    Elements that are not finite take no part in the choice (they saturate, or stay NaN, when encoded).
+    """
     M = np.asarray(M, dtype=np.float64)
-    amax = np.max(np.abs(M), axis=1) if M.shape[1] else np.zeros(M.shape[0])
+    mag = np.where(np.isfinite(M), np.abs(M), 0.0)
+    amax = np.max(mag, axis=1) if M.shape[1] else np.zeros(M.shape[0])
     scale = np.ones(M.shape[0])
     for i, a in enumerate(amax):
         if a > 0:

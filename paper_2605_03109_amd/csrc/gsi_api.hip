@@ -151,6 +151,19 @@ int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d,
   return GSI_OK;
 }
 
+int gsi_quantize_image_fp8(const void* M, int mdtype, int64_t m, int64_t k, uint8_t* M8, float* scale, void* stream) {
+  GSI_REQUIRE_PTR(M);
+  GSI_REQUIRE_PTR(M8);
+  GSI_REQUIRE_PTR(scale);
+  if (!dtype_ok(mdtype)) return fail(GSI_ERR_DTYPE, "gsi_quantize_image_fp8: mdtype %d is neither GSI_F32 nor GSI_BF16", mdtype);
+  if (m < 1 || k < 1) return fail(GSI_ERR_SHAPE, "gsi_quantize_image_fp8: m = %lld, k = %lld", (long long)m, (long long)k);
+  GSI_REQUIRE_ALIGNED(M, gsi::elem_size(mdtype));
+  GSI_REQUIRE_ALIGNED(scale, 4);
+  hipError_t e = gsi::quantize_image_fp8(M, mdtype, m, k, M8, scale, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "gsi_quantize_image_fp8");
+  return GSI_OK;
+}
+
 // argument checks shared by the stand-alone entry points and by gsi_layer_stack
 static int check_project_args(const char* fn, const void* U, const void* X, int64_t d, int64_t k, int64_t B,
                               int udtype, int xdtype, const float* C, const float* R, const float* rnorm,
@@ -358,7 +371,7 @@ struct LinBatcher {
     return e;
   }
   hipError_t add(int gkey, const gsi::LinGroup& gd, const void* W, const void* M, float* Y, int64_t m,
-                 bool need_image = false, float* part = nullptr) {
+                 bool need_image = false, float* part = nullptr, const float* mscale = nullptr) {
     for (int attempt = 0; attempt < 2; ++attempt) {
       int gi = -1;
       for (int i = 0; i < lb.ng; ++i)
@@ -377,6 +390,7 @@ struct LinBatcher {
           if (need_image) {  // as many image tasks as linear tasks at most, so this never overflows
             gsi::ImgTask& it = sib.t[sib.n++];
             it.M = M; it.Y = Y; it.part_c = nullptr; it.C = gd.C; it.m = (int)m; it.k = gd.k; it.a_slabs = 0;
+            it.scale = mscale;
           }
           return hipSuccess;
         }
@@ -643,6 +657,22 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     if (int rc = check_gated_args(fn, mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
                                   mp.wdtype, mp.Y, GSI_F32))
       return rc;
+    if (mp.flags & ~GSI_MAP_IMAGE_FP8)
+      return fail(GSI_ERR_SHAPE, "%s: maps[%d].flags = %d has unknown bits", fn, j, mp.flags);
+    if ((mp.flags & GSI_MAP_IMAGE_FP8) && B > 0) {
+      // an E4M3 image is read by the single-token vector kernels only
+      if (B != 1) return fail(GSI_ERR_SHAPE, "%s: maps[%d] has an FP8 image: single-token calls only (B = %lld)", fn, j, (long long)B);
+      if (!mp.M_scale) return fail(GSI_ERR_NULL, "%s: maps[%d].M_scale is NULL", fn, j);
+      if (!aligned(mp.M_scale, 4) || !aligned(mp.M, 16))
+        return fail(GSI_ERR_ALIGN, "%s: maps[%d]: an FP8 image needs M aligned to 16 bytes and M_scale to 4", fn, j);
+      if (in.k % 16 || in.k > gsi::kMaxK)
+        return fail(GSI_ERR_SHAPE, "%s: maps[%d]: an FP8 image needs k a multiple of 16 and at most %d (k = %lld)", fn, j,
+                    gsi::kMaxK, (long long)in.k);
+      if (!project_vector_path(in.d, in.k, B, in.udtype, in.U) ||
+          !gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, nullptr) || !aligned(in.C, 16) || !aligned(in.R, 16) ||
+          !wx_vector_ok(in))
+        return fail(GSI_ERR_SHAPE, "%s: maps[%d]: an FP8 image needs shapes and alignments the vector kernels take", fn, j);
+    }
   }
   if (int rc = check_ws(fn, ws, ws_bytes, gsi_layer_stack_workspace_bytes(maps, n_maps, inputs, n_inputs, B)))
     return rc;
@@ -724,6 +754,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
               gsi::ImgTask& it = ib.t[ib.n++];
               it.M = maps[j].M; it.Y = maps[j].Y; it.part_c = ptask[i].part_c; it.C = nullptr;
               it.m = (int)maps[j].m; it.k = (int)inputs[i].k; it.a_slabs = ptask[i].a_slabs;
+              it.scale = (maps[j].flags & GSI_MAP_IMAGE_FP8) ? maps[j].M_scale : nullptr;
               img_done[j] = 1;
             }
           }
@@ -798,7 +829,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
             gd.rnorm = in.rnorm; gd.xnorm = in.xnorm; gd.mask = in.mask;
             gd.fired_idx_out = in.fired_idx; gd.n_fired_out = in.n_fired;
           }
-          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j], part[j]);
+          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j], part[j],
+                                    (mp.flags & GSI_MAP_IMAGE_FP8) ? mp.M_scale : nullptr);
               e != hipSuccess)
             return hip_fail(e, fn);
           map_done[j] = 2;

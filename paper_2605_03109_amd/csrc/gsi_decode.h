@@ -50,6 +50,7 @@ struct ImgTask {
   float* Y;
   const float* part_c;  // partial projections [a_slabs][1][k] of the map's input, or null ...
   const float* C;       // ... then the finished coefficients C[k]
+  const float* scale;   // E4M3 image: row scales [m]; null for an image in the weights' dtype
   int m, k, a_slabs, blk_begin;
 };
 

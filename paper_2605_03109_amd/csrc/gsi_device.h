@@ -57,6 +57,22 @@ struct BF16 {
   }
 };
 
+// OCP E4M3 bytes (images only): the hardware conversion widens two codes of a 32-bit word at a time, exactly.
+struct FP8 {
+  using storage = uint8_t;
+  static constexpr int kVec = 16;
+  __device__ static __forceinline__ void widen(const uint4& v, float (&f)[16]) {
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const auto lo = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[q], false);
+      const auto hi = __builtin_amdgcn_cvt_pk_f32_fp8((int)w[q], true);
+      f[4 * q + 0] = lo[0]; f[4 * q + 1] = lo[1];
+      f[4 * q + 2] = hi[0]; f[4 * q + 3] = hi[1];
+    }
+  }
+};
+
 // activation element of runtime dtype (0 = fp32, 1 = bf16)
 __device__ __forceinline__ float load_act(const void* p, int dtype, int64_t i) {
   return dtype == 0 ? reinterpret_cast<const float*>(p)[i]

@@ -39,7 +39,7 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ pc, int6
 }
 
 template <class T>
-__device__ __forceinline__ void image_block(const ImgTask& t, int local_block, float* __restrict__ cs) {
+__device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block, float* __restrict__ cs) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
   const int lane = threadIdx.x % kWave;
@@ -80,13 +80,24 @@ __device__ __forceinline__ void image_block(const ImgTask& t, int local_block, f
       for (int e = 0; e < V; ++e) s = fmaf(w[e], cvv[e], s);
       s = group_sum_rt(live ? s : 0.f, lpr);
       const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
-      if (l == 0 && row < m) t.Y[row] = s;
+      if (l == 0 && row < m) {
+        if constexpr (T::kVec == 16) s *= t.scale[row];  // E4M3 codes: the row's power-of-two scale
+        t.Y[row] = s;
+      }
     }
 }
 
+// T: storage of an image in the weights' dtype; a task with row scales holds E4M3 codes instead (Section 7,
+// "Combination with quantization").  The choice is uniform over the workgroup.
+template <class T>
+__device__ __forceinline__ void image_block(const ImgTask& t, int local_block, float* __restrict__ cs) {
+  if (t.scale) image_block_as<FP8>(t, local_block, cs);
+  else image_block_as<T>(t, local_block, cs);
+}
+
 // workgroups a map needs in an image launch
-inline int image_blocks(int64_t m, int64_t k, int wdtype) {
-  const int V = wdtype == GSI_BF16 ? 8 : 4;
+inline int image_blocks(int64_t m, int64_t k, int wdtype, bool fp8 = false) {
+  const int V = fp8 ? 16 : wdtype == GSI_BF16 ? 8 : 4;
   int lpr = 1;
   while (lpr < k / V) lpr <<= 1;
   const int64_t rows_per_item = (int64_t)kImgLoads * (kWave / lpr);

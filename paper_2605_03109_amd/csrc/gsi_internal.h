@@ -24,6 +24,10 @@ hipError_t generic_gated_linear(const void* W, const void* M, const float* C, co
 hipError_t generic_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype,
                                 int xdtype, float* Y, hipStream_t s);
 
+// ---- the image in 8-bit floating point (gsi_fp8.hip) ---------------------------------------------------
+hipError_t quantize_image_fp8(const void* M, int mdtype, int64_t m, int64_t k, uint8_t* M8, float* scale,
+                              hipStream_t s);
+
 // ---- gate + stream compaction (one kernel for every shape) ----------------------------------------
 hipError_t launch_gate(const float* rnorm, const float* xnorm, int64_t B, float eps, uint8_t* mask,
                        int32_t* fired_idx, int32_t* n_fired, hipStream_t s);

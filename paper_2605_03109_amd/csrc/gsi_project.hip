@@ -452,7 +452,7 @@ hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s) {
   int total = 0;
   for (int i = 0; i < ib.n; ++i) {
     ib.t[i].blk_begin = total;
-    total += image_blocks(ib.t[i].m, ib.t[i].k, wdtype);
+    total += image_blocks(ib.t[i].m, ib.t[i].k, wdtype, ib.t[i].scale != nullptr);
   }
   ib.total = total;
   if (total == 0) return hipSuccess;
@@ -500,7 +500,7 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
   int ti = 0;
   for (int i = 0; i < ib.n; ++i) {
     ib.t[i].blk_begin = ti;
-    ti += image_blocks(ib.t[i].m, ib.t[i].k, udtype);
+    ti += image_blocks(ib.t[i].m, ib.t[i].k, udtype, ib.t[i].scale != nullptr);
   }
   ib.total = ti;
   if (udtype == GSI_BF16) {

@@ -21,10 +21,12 @@ GSI_OK = 0
 GSI_ERR_NULL, GSI_ERR_SHAPE, GSI_ERR_DTYPE, GSI_ERR_ALIGN, GSI_ERR_WORKSPACE, GSI_ERR_HIP = -1, -2, -3, -4, -5, -6
 GSI_F32, GSI_BF16 = 0, 1
 INPUT_SLOW_PATH_WX = 1  # gsi_input_desc.flags: fired tokens get y = W x (Algorithm 1, line 7)
+MAP_IMAGE_FP8 = 1  # gsi_map_desc.flags: M holds E4M3 codes, M_scale the row scales (single-token calls)
 CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
 
 EXPORTS = (
-    "gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear", "gsi_layer_stack",
+    "gsi_build_image", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+    "gsi_layer_stack",
     "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
     "gsi_version",
@@ -53,6 +55,7 @@ class MapDesc(ctypes.Structure):
     _fields_ = [
         ("W", ctypes.c_void_p), ("M", ctypes.c_void_p), ("Y", ctypes.c_void_p),
         ("m", ctypes.c_int64), ("wdtype", ctypes.c_int32), ("input_id", ctypes.c_int32),
+        ("M_scale", ctypes.c_void_p), ("flags", ctypes.c_int32), ("reserved", ctypes.c_int32),
     ]
 
 
@@ -65,6 +68,7 @@ def _load() -> ctypes.CDLL:
     lib = ctypes.CDLL(LIB_PATH)
     vp, i64, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
     lib.gsi_build_image.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
+    lib.gsi_quantize_image_fp8.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.gsi_project.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.gsi_gate.argtypes = [vp, vp, i64, f32, vp, vp, vp, vp]
     lib.gsi_gated_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, i32, vp, sz, vp]
@@ -84,7 +88,7 @@ def _load() -> ctypes.CDLL:
     lib.gsi_dense_stack_workspace_bytes.restype = sz
     lib.gsi_last_error.restype = ctypes.c_char_p
     lib.gsi_version.restype = ctypes.c_int
-    for name in ("gsi_build_image", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+    for name in ("gsi_build_image", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
                  "gsi_layer_stack", "gsi_layer_stack_timed", "gsi_dense_stack"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -186,6 +190,16 @@ def build_image(W: torch.Tensor, U: torch.Tensor, M: Optional[torch.Tensor] = No
     return M
 
 
+def quantize_image_fp8(M: torch.Tensor, M8: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
+                       stream=None):
+    """E4M3 codes M8[m,k] (uint8) and power-of-two row scales scale[m] (fp32) of a stored image M[m,k]."""
+    m, k = M.shape
+    M8 = torch.empty((m, k), dtype=torch.uint8, device=M.device) if M8 is None else M8
+    scale = torch.empty((m,), dtype=torch.float32, device=M.device) if scale is None else scale
+    _check(lib.gsi_quantize_image_fp8(_ptr(M), dtype_code(M), m, k, _ptr(M8), _ptr(scale), _stream(stream)))
+    return M8, scale
+
+
 def project(U: torch.Tensor, X: torch.Tensor, C=None, R=None, rnorm=None, xnorm=None, ws=None, stream=None):
     d, k = U.shape
     B, d2 = X.shape
@@ -242,7 +256,7 @@ class LayerStack:
     """Host descriptor tables for ``gsi_layer_stack`` plus the device buffers they point to.
 
     ``inputs``: list of dicts {U, X (tensor [B,d]) or src_map}; ``maps``: list of dicts
-    {W, M, input_id}.  Output buffers are allocated here (torch = device memory only) and exposed as
+    {W, M, input_id} (+ M_scale when M holds the E4M3 codes of ``quantize_image_fp8``).  Output buffers are allocated here (torch = device memory only) and exposed as
     attributes; ``run()`` is a single call into the library.
     """
 
@@ -256,7 +270,8 @@ class LayerStack:
             m = mp["W"].shape[0]
             Y = mp.get("Y")
             Y = torch.zeros((B, m), **f32) if Y is None else Y
-            self.maps_t.append({"W": mp["W"], "M": mp["M"], "Y": Y, "input_id": int(mp["input_id"])})
+            self.maps_t.append({"W": mp["W"], "M": mp["M"], "Y": Y, "input_id": int(mp["input_id"]),
+                                "M_scale": mp.get("M_scale")})
         for inp in inputs:
             U = inp["U"]
             d, k = U.shape
@@ -300,6 +315,8 @@ class LayerStack:
             e.W, e.M, e.m = _ptr(t["W"]), _ptr(t["M"]), m
             e.Y = _ptr(t["Y"]) + o * m * 4
             e.wdtype, e.input_id = dtype_code(t["W"]), t["input_id"]
+            e.M_scale = _ptr(t["M_scale"])
+            e.flags, e.reserved = (MAP_IMAGE_FP8 if t["M_scale"] is not None else 0), 0
         need = max(int(fn(self._mp, len(self.maps_t), self._in, len(self.inputs_t), B))
                    for fn in (lib.gsi_layer_stack_workspace_bytes, lib.gsi_dense_stack_workspace_bytes))
         if need > self.ws.numel():  # the workspace depends on the token count of the call

@@ -421,6 +421,7 @@ def pin_fp8_row_scale(O):
     M = np.array([[448.0, 1.0], [448.0000001, 0.0], [224.0, -3.0], [-224.0000001, 3.0], [0.0, 0.0], [1e-30, 0.0], [-7.0, 6.0]])
     s = O.fp8_row_scale(M)
     assert list(s) == [1.0, 2.0, 0.5, 1.0, 1.0, 2.0 ** -108, 2.0 ** -6]
+    assert list(O.fp8_row_scale(np.array([[np.inf, 3.5], [np.nan, -896.0], [np.nan, np.inf]]))) == [2.0 ** -7, 2.0, 1.0]
     rng = np.random.default_rng(7)
     M = rng.standard_normal((64, 32)) * np.exp(rng.uniform(-20, 20, (64, 1)))
     s = O.fp8_row_scale(M)

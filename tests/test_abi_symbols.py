@@ -81,3 +81,19 @@ def test_host_side_validation_needs_no_gpu():
     need = lib.gsi_dense_stack_workspace_bytes(mp, 1, inp, 1, 4)
     assert need > 0 and lib.gsi_dense_stack_workspace_bytes(mp, 1, inp, 1, 1) == 0
     assert lib.gsi_dense_stack(mp, 1, inp, 1, 4, None, 0, None) == gsi.GSI_ERR_WORKSPACE
+    # the 8-bit image: quantiser arguments, and maps that carry one
+    assert lib.gsi_quantize_image_fp8(one, gsi.GSI_BF16, 4, 4, one, None, None) == gsi.GSI_ERR_NULL
+    assert lib.gsi_quantize_image_fp8(one, 2, 4, 4, one, one, None) == gsi.GSI_ERR_DTYPE
+    assert lib.gsi_quantize_image_fp8(one, gsi.GSI_F32, 0, 4, one, one, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_quantize_image_fp8(odd, gsi.GSI_F32, 4, 4, one, one, None) == gsi.GSI_ERR_ALIGN
+    mp[0].flags = 4
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert b"maps[0].flags" in lib.gsi_last_error()
+    mp[0].flags = gsi.MAP_IMAGE_FP8
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 2, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert b"single-token" in lib.gsi_last_error()
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_NULL  # M_scale
+    mp[0].M_scale = 256
+    inp[0].k = 24
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
+    assert b"multiple of 16" in lib.gsi_last_error()

@@ -514,3 +514,134 @@ def test_slow_path_wx_flag(gsi, pu, d, k, m, T, nf, B):
         st0.run_dense()
     torch.cuda.synchronize()
     assert torch.equal(y_all, st0.maps_t[0]["Y"])
+
+
+# ------------------------------------------------------------------------------------------------
+# The cached image in 8-bit E4M3 with power-of-two row scales (Section 7, "Combination with quantization").
+# The quantiser decides integers (codes): it is fed matrices from the seeded generator, never an image
+# built on the device, and must give the oracle's codes and scales bit for bit.
+# ------------------------------------------------------------------------------------------------
+def _fp8_test_matrix(m, k, seed):
+    """fp32 matrix with rows of very different size, exact ties between codes, tiny and special entries."""
+    rng = np.random.default_rng(seed)
+    M = rng.standard_normal((m, k)) * np.exp(rng.uniform(-30, 30, (m, 1))) * np.exp(rng.uniform(-6, 0, (m, k)))
+    M = M.astype(np.float32)
+    grid = np.array([(mm / 8.0) * 2.0 ** -6 if e == 0 else (1.0 + mm / 8.0) * 2.0 ** (e - 7)
+                     for e in range(16) for mm in range(8) if not (e == 15 and mm == 7)])
+    mid = 0.5 * (grid[:-1] + grid[1:])
+    if m >= 8 and k >= 16:
+        # rows whose maximum is exactly 448 * 2^j: the midpoints between neighbouring codes are then ties
+        for r, j in ((1, 0), (2, -7), (3, 9)):
+            row = rng.choice(mid, k) * rng.choice([-1.0, 1.0], k)
+            row[0] = 448.0
+            M[r] = (row * 2.0 ** j).astype(np.float32)
+        M[4] = 0.0                                    # zero row: scale 1, codes 0
+        M[5, :] = 0.0
+        M[5, 3] = -1.0e-30                            # one tiny element alone
+        M[6, :4] = [np.inf, -np.inf, np.nan, 3.0]     # not finite: no part in the scale, saturate / NaN code
+        M[7] = np.float32(224.0) * rng.choice([-1.0, 1.0], k)   # maximum on a power-of-two boundary
+    return M
+
+
+@pytest.mark.parametrize("m,k,dt", [(8, 16, "f32"), (37, 50, "f32"), (256, 256, "bf16"), (1000, 512, "f32"),
+                                    (4100, 64, "bf16"), (5, 1, "f32")])
+def test_fp8_quantizer_bit_exact(gsi, m, k, dt):
+    say(f"case fp8 quantizer: m={m} k={k} stored {dt}")
+    M = _fp8_test_matrix(m, k, 8800 + m + k)
+    if dt == "bf16":
+        bits = wl.f32_to_bf16_bits(M)
+        Md = gsi.to_device(bits, "bf16")
+        M64 = O.widen(bits, "bf16")
+    else:
+        Md = gsi.to_device(M, "f32")
+        M64 = O.widen(M, "f32")
+    M8, scale = gsi.quantize_image_fp8(Md)
+    torch.cuda.synchronize()
+    codes_o, scale_o = O.quantize_image_fp8(M64)
+    assert np.array_equal(scale.cpu().numpy().astype(np.float64), scale_o)
+    got = M8.cpu().numpy()
+    bad = np.argwhere(got != codes_o)
+    assert bad.size == 0, f"{bad.shape[0]} codes differ, first at {bad[0]}: {got[tuple(bad[0])]:#x} vs {codes_o[tuple(bad[0])]:#x} for {M64[tuple(bad[0])]!r}"
+
+
+def test_fp8_image_decodes_every_code(gsi):
+    """y_i = scale_i * value(code i): the image kernel's widening of all 256 codes, bit for bit."""
+    say("case fp8 decode table")
+    d, k, m = 64, 16, 256
+    U = np.zeros((d, k), dtype=np.float32)
+    U[np.arange(k), np.arange(k)] = 1.0
+    X = np.zeros((1, d), dtype=np.float32)
+    X[0, 0] = 1.0                                     # c = e_0, r = 0: the gate stays shut
+    M8 = np.zeros((m, k), dtype=np.uint8)
+    M8[:, 0] = np.arange(256, dtype=np.uint8)
+    scale = (2.0 ** ((np.arange(m) % 5) - 2)).astype(np.float32)
+    dev = torch.device("cuda")
+    maps = [{"W": torch.zeros((m, d), dtype=torch.bfloat16, device=dev), "M": torch.from_numpy(M8).to(dev),
+             "M_scale": torch.from_numpy(scale).to(dev), "input_id": 0}]
+    st = gsi.layer_stack([{"U": gsi.to_device(wl.f32_to_bf16_bits(U), "bf16"), "X": gsi.to_device(X, "f32")}], maps, 1, 0.05)
+    torch.cuda.synchronize()
+    assert int(st.inputs_t[0]["n_fired"].item()) == 0
+    y = st.maps_t[0]["Y"].cpu().numpy()[0].astype(np.float64)
+    want = O.fp8_e4m3_decode(np.arange(256, dtype=np.uint8)) * scale.astype(np.float64)
+    nan = np.isnan(want)
+    assert np.array_equal(np.isnan(y), nan)
+    assert np.array_equal(y[~nan], want[~nan])
+
+
+@pytest.mark.parametrize("d,k,m,T,nf,wx", [(1024, 64, 520, 12, 4, 0), (4096, 256, 1024, 10, 3, 0), (2048, 128, 528, 9, 3, 1),
+                                           (512, 16, 264, 6, 2, 0)])
+def test_fp8_image_single_token_stack(gsi, pu, d, k, m, T, nf, wx):
+    """Single-token calls with the image stored in E4M3.
+
+    Bars.  (a) Against the oracle fed the device's own codes and scales only kernel arithmetic differs
+    (fp32 accumulation of exactly widened operands): 2e-5 as for the other stage comparisons.  (b) Against
+    the oracle's own pipeline (fp64 image, rounded once to bf16, quantised by the oracle) a code differs where
+    the two bf16 images differ at a rounding boundary; such a flip moves one of k terms of a row by a code
+    step (2^-3 relative), so rows stay within 2^-3 / sqrt k of each other and the bar is 5e-3 on the whole
+    output block.  (c) Against the exact image the E4M3 rounding itself shows: at most 2^-4 per element,
+    about 2^-4 / sqrt 3 in the root mean square; bar 6e-2 per output vector.
+    """
+    w = wl.tiny(d, k, m, T, nf, seed=9100 + d + k, wdtype="bf16")
+    say(f"case fp8 image stack: d={d} k={k} m={m} T={T} nf={nf} wx={wx}")
+    g = w.groups[0]
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    ref = og.run()
+    M8, scale = gsi.quantize_image_fp8(dg.M["w"])
+    maps = [{"W": dg.W["w"], "M": M8, "M_scale": scale, "input_id": 0}]
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X, "flags": gsi.INPUT_SLOW_PATH_WX if wx else 0}], maps, T, w.eps)
+    for t0 in range(T):
+        st.refresh(token_offset=t0, B=1)
+        st.run()
+    torch.cuda.synchronize()
+    mask = st.inputs_t[0]["mask"].cpu().numpy()
+    assert np.array_equal(mask.astype(bool), g.fired_design)
+    Y = st.maps_t[0]["Y"].cpu().numpy().astype(np.float64)
+
+    def out(M):
+        return (O.gated_linear_alg1(og.W["w"], M, ref["C"], og.X, mask) if wx
+                else O.gated_linear(og.W["w"], M, ref["C"], ref["R"], mask))
+
+    e_stage = pu.rel_l2_rows(Y, out(O.dequantize_image_fp8(M8.cpu().numpy(), scale.cpu().numpy())))
+    assert e_stage.max() <= 2e-5, e_stage.max()
+    M_bf16 = O.widen(wl.f32_to_bf16_bits(og.M["w"].astype(np.float32)), "bf16")
+    codes_o, scale_o = O.quantize_image_fp8(M_bf16)
+    Yo = out(O.dequantize_image_fp8(codes_o, scale_o))
+    e_pipe = np.linalg.norm(Y - Yo) / np.linalg.norm(Yo)
+    flips = int(np.count_nonzero(M8.cpu().numpy() != codes_o))
+    assert e_pipe <= 5e-3, e_pipe
+    assert np.array_equal(scale.cpu().numpy().astype(np.float64), scale_o) or flips > 0
+    e_exact = pu.rel_l2_rows(Y, out(og.M["w"]))
+    assert e_exact.max() <= 6e-2, e_exact.max()
+    say(f"  vs device codes {e_stage.max():.3e}; vs oracle pipeline {e_pipe:.3e} ({flips} of {m * k} codes differ); "
+        f"vs exact image {e_exact.max():.3e} (E4M3 rounding)")
+
+
+def test_fp8_image_refused_for_several_tokens(gsi, pu):
+    w = wl.tiny(512, 64, 256, 4, 1, seed=9300, wdtype="bf16")
+    g = w.groups[0]
+    dg = pu.DeviceGroup(w, g)
+    M8, scale = gsi.quantize_image_fp8(dg.M["w"])
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X}], [{"W": dg.W["w"], "M": M8, "M_scale": scale, "input_id": 0}], 4, w.eps)
+    with pytest.raises(gsi.GsiError) as ei:
+        st.run()
+    assert ei.value.code == gsi.GSI_ERR_SHAPE and "single-token" in str(ei.value)
