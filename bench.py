@@ -94,6 +94,9 @@ def main() -> int:
     ap.add_argument("--slow-path", choices=["mc_wr", "wx"], default="mc_wr",
                     help="what a fired token gets: M c + W r (the form the metric is quoted on) or W x as "
                          "Algorithm 1 prints it")
+    ap.add_argument("--image", choices=["bf16", "fp8"], default="bf16",
+                    help="storage of the cached images: the weights' dtype (the form the metric is quoted on) or "
+                         "8-bit E4M3 with row scales (Section 7, combination with quantization)")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run three device copies of 512 MiB first (a kernel of known traffic, used to "
                          "scale hardware-counter readings of a rocprofv3 --pmc run)")
@@ -136,7 +139,10 @@ def main() -> int:
                        "flags": gsi.INPUT_SLOW_PATH_WX if args.slow_path == "wx" else 0})
         for name, m, W in g.maps:
             Wd = gsi.to_device(W, w.wdtype)
-            maps.append({"W": Wd, "M": gsi.build_image(Wd, U), "input_id": gi})
+            mp = {"W": Wd, "M": gsi.build_image(Wd, U), "input_id": gi}
+            if args.image == "fp8":
+                mp["M"], mp["M_scale"] = gsi.quantize_image_fp8(mp["M"])
+            maps.append(mp)
             meta.append((gi, name, m, g.d, g.k))
     torch.cuda.synchronize()
     st = gsi.LayerStack(inputs, maps, T, w.eps)
@@ -238,7 +244,7 @@ def main() -> int:
     for gi, g in enumerate(w.groups):
         proj_bytes += g.d * g.k * bw + g.d * 4 + g.k * 4 + g.d * 4
         for _, m, _ in g.maps:
-            proj_bytes += m * g.k * bw + m * 4
+            proj_bytes += m * g.k * (1 if args.image == "fp8" else bw) + m * 4 + (m * 4 if args.image == "fp8" else 0)
             lin_bytes += fired[gi] * (m * g.d * bw + 2 * m * 4)
         lin_bytes += fired[gi] * (g.d * 4)
     order = np.arange(args.steps) % T
@@ -343,6 +349,7 @@ def main() -> int:
             "k": args.k, "eps": w.eps, "decode_tokens": T, "designed_fire_rate": args.fire,
             "measured_fire_rate": round(float(fired.mean()), 4), "masks_match_design": masks_match_design,
             "launch_mode": mode, "slow_path": "M c + W r" if args.slow_path == "mc_wr" else "W x (Algorithm 1, line 7)",
+            "image_storage": "bf16" if args.image == "bf16" else "fp8 e4m3 + power-of-two row scales",
         },
         "tokens_per_s": round(tokens_per_s, 1),
         "dense_gemv_tokens_per_s": round(dense_tokens_per_s, 1),
