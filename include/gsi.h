@@ -144,9 +144,11 @@ typedef struct gsi_map_desc {
 } gsi_map_desc;
 
 /* gsi_map_desc.flags.  GSI_MAP_IMAGE_FP8: M and M_scale are the outputs of gsi_quantize_image_fp8 and the
- * image term is y_i = M_scale[i] * sum_j value(M[i,j]) c_j (fp32 accumulation).  Taken by single-token calls
- * (B == 1) on the vector kernels only: k a multiple of 16 and at most 512, M aligned to 16 bytes, and the
- * shapes and alignments of W, U, C, R that those kernels need; anything else returns GSI_ERR_SHAPE. */
+ * image term is y_i = M_scale[i] * sum_j value(M[i,j]) c_j (fp32 accumulation).  The codes are read as they are
+ * (half the image bytes) by single-token calls (B == 1) on the vector kernels: k a multiple of 16 and at most
+ * 512, M aligned to 16 bytes, and the shapes and alignments of W, U, C, R that those kernels need.  Every other
+ * call first expands the image, exactly, to `wdtype` in the workspace (gsi_layer_stack_workspace_bytes accounts
+ * for it) and then runs the map as one with an ordinary image: same results, no saving in bytes. */
 enum { GSI_MAP_IMAGE_FP8 = 1 };
 
 /* A chain of per-layer linear maps sharing their inputs' projections (Section 1: every linear map

@@ -498,6 +498,24 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
   return GSI_OK;
 }
 
+// the W x form of the slow path reads x with 16-byte loads in the vector kernels
+static bool wx_vector_ok(const gsi_input_desc& in) {
+  return !(in.flags & GSI_INPUT_SLOW_PATH_WX) || aligned(in.X, 16);
+}
+
+// Is the E4M3 image of this map read as codes?  Only by the single-token vector kernels; every other call
+// expands it (exactly) to the weights' type in the workspace first and runs the map with an ordinary image.
+static bool fp8_codes_read(const gsi_map_desc& mp, const gsi_input_desc& in, int64_t B) {
+  return B == 1 && aligned(mp.M, 16) && in.k % 16 == 0 && in.k <= gsi::kMaxK &&
+         project_vector_path(in.d, in.k, B, in.udtype, in.U) &&
+         gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, nullptr) && aligned(in.C, 16) && aligned(in.R, 16) &&
+         wx_vector_ok(in);
+}
+static size_t fp8_expand_bytes(const gsi_map_desc& mp, const gsi_input_desc& in, int64_t B) {
+  if (!(mp.flags & GSI_MAP_IMAGE_FP8) || B < 1 || mp.m < 1 || in.k < 1 || fp8_codes_read(mp, in, B)) return 0;
+  return gsi::align_up((size_t)mp.m * in.k * gsi::elem_size(mp.wdtype), 256);
+}
+
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                                        int32_t n_inputs, int64_t B) {
   if (!inputs || n_inputs < 0) return 0;
@@ -511,12 +529,13 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
       const int id = maps[j].input_id;
       if (id >= 0 && id < n_inputs) need += map_part_bytes(maps[j].m, inputs[id].d, B, 0);
     }
+  // E4M3 images that are not read as codes are expanded to the weights' type
+  if (maps)
+    for (int j = 0; j < n_maps; ++j) {
+      const int id = maps[j].input_id;
+      if (id >= 0 && id < n_inputs) need += fp8_expand_bytes(maps[j], inputs[id], B);
+    }
   return need;
-}
-
-// the W x form of the slow path reads x with 16-byte loads in the vector kernels
-static bool wx_vector_ok(const gsi_input_desc& in) {
-  return !(in.flags & GSI_INPUT_SLOW_PATH_WX) || aligned(in.X, 16);
 }
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
@@ -654,24 +673,17 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   for (int j = 0; j < n_maps; ++j) {
     const gsi_map_desc& mp = maps[j];
     const gsi_input_desc& in = inputs[mp.input_id];
-    if (int rc = check_gated_args(fn, mp.W, mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
-                                  mp.wdtype, mp.Y, GSI_F32))
-      return rc;
     if (mp.flags & ~GSI_MAP_IMAGE_FP8)
       return fail(GSI_ERR_SHAPE, "%s: maps[%d].flags = %d has unknown bits", fn, j, mp.flags);
-    if ((mp.flags & GSI_MAP_IMAGE_FP8) && B > 0) {
-      // an E4M3 image is read by the single-token vector kernels only
-      if (B != 1) return fail(GSI_ERR_SHAPE, "%s: maps[%d] has an FP8 image: single-token calls only (B = %lld)", fn, j, (long long)B);
+    const bool fp8 = (mp.flags & GSI_MAP_IMAGE_FP8) != 0;
+    // (an E4M3 image is bytes: the alignment rule of the weights' type does not apply to it)
+    if (int rc = check_gated_args(fn, mp.W, fp8 ? mp.W : mp.M, in.C, in.R, in.fired_idx, in.n_fired, mp.m, in.d, in.k, B,
+                                  mp.wdtype, mp.Y, GSI_F32))
+      return rc;
+    if (fp8 && B > 0) {
+      if (!mp.M) return fail(GSI_ERR_NULL, "%s: maps[%d].M is NULL", fn, j);
       if (!mp.M_scale) return fail(GSI_ERR_NULL, "%s: maps[%d].M_scale is NULL", fn, j);
-      if (!aligned(mp.M_scale, 4) || !aligned(mp.M, 16))
-        return fail(GSI_ERR_ALIGN, "%s: maps[%d]: an FP8 image needs M aligned to 16 bytes and M_scale to 4", fn, j);
-      if (in.k % 16 || in.k > gsi::kMaxK)
-        return fail(GSI_ERR_SHAPE, "%s: maps[%d]: an FP8 image needs k a multiple of 16 and at most %d (k = %lld)", fn, j,
-                    gsi::kMaxK, (long long)in.k);
-      if (!project_vector_path(in.d, in.k, B, in.udtype, in.U) ||
-          !gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, nullptr) || !aligned(in.C, 16) || !aligned(in.R, 16) ||
-          !wx_vector_ok(in))
-        return fail(GSI_ERR_SHAPE, "%s: maps[%d]: an FP8 image needs shapes and alignments the vector kernels take", fn, j);
+      if (!aligned(mp.M_scale, 4)) return fail(GSI_ERR_ALIGN, "%s: maps[%d].M_scale is not aligned to 4 bytes", fn, j);
     }
   }
   if (int rc = check_ws(fn, ws, ws_bytes, gsi_layer_stack_workspace_bytes(maps, n_maps, inputs, n_inputs, B)))
@@ -691,6 +703,33 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       if (pb) part[j] = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + off);
       off += pb;
     }
+  }
+
+  // E4M3 images that no kernel of this call reads as codes (several tokens, or shapes the single-token vector
+  // kernels do not take) are expanded, exactly, to the weights' type in the workspace first; their maps then run
+  // as maps with an ordinary image.
+  std::vector<gsi_map_desc> expanded;
+  if (B > 0) {
+    size_t off = 0;
+    for (int i = 0; i < n_inputs; ++i)
+      off += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
+    for (int j = 0; j < n_maps; ++j) off += map_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B, 0);
+    for (int j = 0; j < n_maps; ++j) {
+      const gsi_input_desc& in = inputs[maps[j].input_id];
+      const size_t bytes = fp8_expand_bytes(maps[j], in, B);
+      if (!bytes) continue;
+      if (expanded.empty()) expanded.assign(maps, maps + n_maps);
+      void* tmp = reinterpret_cast<char*>(ws) + off;
+      off += bytes;
+      if (hipError_t e = gsi::expand_image_fp8(reinterpret_cast<const uint8_t*>(maps[j].M), maps[j].M_scale, maps[j].m,
+                                               in.k, tmp, maps[j].wdtype, s);
+          e != hipSuccess)
+        return hip_fail(e, fn);
+      expanded[j].M = tmp;
+      expanded[j].M_scale = nullptr;
+      expanded[j].flags &= ~GSI_MAP_IMAGE_FP8;
+    }
+    if (!expanded.empty()) maps = expanded.data();
   }
 
   // How each input is processed.  kVecInline: vector projection kernels, norms and gate evaluated

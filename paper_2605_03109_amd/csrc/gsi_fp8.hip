@@ -3,6 +3,8 @@
 // largest magnitude, takes the smallest power of two that brings it to at most 448 (the largest E4M3 value) and
 // writes the E4M3 code nearest to every scaled element, ties to the even code.  Scaling by a power of two is
 // exact, so the codes depend on the stored image alone.
+#include <algorithm>
+
 #include "gsi_device.h"
 #include "gsi_internal.h"
 
@@ -66,7 +68,30 @@ __global__ __launch_bounds__(kBlock) void quantize_rows(const typename T::storag
   }
 }
 
+// out[i,j] = scale_i * value(M8[i,j]) in the weights' storage type (exact: a 4-bit significand times a power of
+// two, unless a row scale below 2^-117 pushes it under the normal range).  Used by calls of several tokens, whose
+// kernels read the image as a matrix-core operand in the weights' type.
+template <class T>
+__global__ __launch_bounds__(kBlock) void expand_rows(const uint8_t* __restrict__ M8, const float* __restrict__ scale,
+                                                      int64_t m, int64_t k, typename T::storage* __restrict__ out) {
+  const int64_t n = m * k;
+  for (int64_t e = (int64_t)blockIdx.x * kBlock + threadIdx.x; e < n; e += (int64_t)gridDim.x * kBlock) {
+    const auto pair = __builtin_amdgcn_cvt_pk_f32_fp8((int)M8[e], false);
+    T::store(out, e, pair[0] * scale[e / k]);
+  }
+}
+
 }  // namespace
+
+hipError_t expand_image_fp8(const uint8_t* M8, const float* scale, int64_t m, int64_t k, void* out, int out_dtype,
+                            hipStream_t s) {
+  const unsigned blocks = (unsigned)std::min<int64_t>(ceil_div(m * k, kBlock), 8192);
+  if (out_dtype == GSI_BF16)
+    expand_rows<BF16><<<blocks, kBlock, 0, s>>>(M8, scale, m, k, reinterpret_cast<uint16_t*>(out));
+  else
+    expand_rows<F32><<<blocks, kBlock, 0, s>>>(M8, scale, m, k, reinterpret_cast<float*>(out));
+  return hipGetLastError();
+}
 
 hipError_t quantize_image_fp8(const void* M, int mdtype, int64_t m, int64_t k, uint8_t* M8, float* scale,
                               hipStream_t s) {

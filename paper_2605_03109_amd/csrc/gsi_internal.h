@@ -27,6 +27,9 @@ hipError_t generic_dense_linear(const void* W, const void* X, int64_t m, int64_t
 // ---- the image in 8-bit floating point (gsi_fp8.hip) ---------------------------------------------------
 hipError_t quantize_image_fp8(const void* M, int mdtype, int64_t m, int64_t k, uint8_t* M8, float* scale,
                               hipStream_t s);
+// out[m,k] (out_dtype) = scale_i * value(M8[i,j])
+hipError_t expand_image_fp8(const uint8_t* M8, const float* scale, int64_t m, int64_t k, void* out, int out_dtype,
+                            hipStream_t s);
 
 // ---- gate + stream compaction (one kernel for every shape) ----------------------------------------
 hipError_t launch_gate(const float* rnorm, const float* xnorm, int64_t B, float eps, uint8_t* mask,

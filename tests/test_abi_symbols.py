@@ -90,10 +90,14 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
     assert b"maps[0].flags" in lib.gsi_last_error()
     mp[0].flags = gsi.MAP_IMAGE_FP8
-    assert lib.gsi_layer_stack(mp, 1, inp, 1, 2, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
-    assert b"single-token" in lib.gsi_last_error()
-    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_NULL  # M_scale
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 2, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_NULL
+    assert b"M_scale" in lib.gsi_last_error()
+    mp[0].M_scale = 258
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 2, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_ALIGN
     mp[0].M_scale = 256
-    inp[0].k = 24
-    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
-    assert b"multiple of 16" in lib.gsi_last_error()
+    # several tokens: the image is expanded to the weights' type in the workspace, which the query accounts for
+    mp[0].flags = 0
+    plain = lib.gsi_layer_stack_workspace_bytes(mp, 1, inp, 1, 4)
+    mp[0].flags = gsi.MAP_IMAGE_FP8
+    assert lib.gsi_layer_stack_workspace_bytes(mp, 1, inp, 1, 4) == plain + 64 * 32 * 4
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 4, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_WORKSPACE

@@ -636,12 +636,41 @@ def test_fp8_image_single_token_stack(gsi, pu, d, k, m, T, nf, wx):
         f"vs exact image {e_exact.max():.3e} (E4M3 rounding)")
 
 
-def test_fp8_image_refused_for_several_tokens(gsi, pu):
-    w = wl.tiny(512, 64, 256, 4, 1, seed=9300, wdtype="bf16")
+@pytest.mark.parametrize("d,k,m,T,nf,B", [(1024, 64, 520, 24, 5, 8), (2048, 128, 528, 300, 60, 300), (776, 72, 100, 9, 3, 9),
+                                          (1000, 40, 30, 3, 1, 1)])
+def test_fp8_image_expanded_for_other_calls(gsi, pu, d, k, m, T, nf, B):
+    """Calls whose kernels do not read codes (several tokens: the matrix-core decode and GEMM kernels; shapes the
+    single-token vector kernels do not take) expand the image exactly and give the results of the same stack run
+    with that expanded image stored as an ordinary one -- bit for bit."""
+    w = wl.tiny(d, k, m, T, nf, seed=9400 + d + k + T, wdtype="bf16")
+    say(f"case fp8 image, expanded: d={d} k={k} m={m} T={T} nf={nf} B={B}")
     g = w.groups[0]
-    dg = pu.DeviceGroup(w, g)
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
     M8, scale = gsi.quantize_image_fp8(dg.M["w"])
-    st = gsi.LayerStack([{"U": dg.U, "X": dg.X}], [{"W": dg.W["w"], "M": M8, "M_scale": scale, "input_id": 0}], 4, w.eps)
-    with pytest.raises(gsi.GsiError) as ei:
-        st.run()
-    assert ei.value.code == gsi.GSI_ERR_SHAPE and "single-token" in str(ei.value)
+    Mdeq = O.dequantize_image_fp8(M8.cpu().numpy(), scale.cpu().numpy())
+    bits = wl.f32_to_bf16_bits(Mdeq.astype(np.float32))
+    assert np.array_equal(O.widen(bits, "bf16"), Mdeq)          # the expansion is exact in bf16
+    outs = []
+    for mp in ({"W": dg.W["w"], "M": M8, "M_scale": scale, "input_id": 0},
+               {"W": dg.W["w"], "M": gsi.to_device(bits, "bf16"), "input_id": 0}):
+        st = gsi.LayerStack([{"U": dg.U, "X": dg.X}], [mp], T, w.eps)
+        for t0 in range(0, T, B):
+            st.refresh(token_offset=t0, B=min(B, T - t0))
+            st.run()
+        torch.cuda.synchronize()
+        outs.append((st.maps_t[0]["Y"].clone(), st.inputs_t[0]["mask"].cpu().numpy()))
+    assert torch.equal(outs[0][0], outs[1][0])
+    assert np.array_equal(outs[0][1].astype(bool), g.fired_design)
+    # and that common result is the oracle's, with the expanded image, to the stage bar of the call size
+    ref = og.run()
+    mask = outs[0][1]
+    Y = outs[0][0].cpu().numpy().astype(np.float64)
+    Yo = O.gated_linear(og.W["w"], Mdeq, ref["C"], ref["R"], mask)
+    err = pu.rel_l2_rows(Y, Yo)
+    bar = np.full(T, 2e-5)
+    fired = mask.astype(bool)
+    if B > pu.PREFILL_TOKENS and fired.any():   # r enters the W term rounded once to bf16 in calls of this size
+        wr = np.linalg.norm(O.dense_linear(og.W["w"], ref["R"][fired]), axis=1)
+        bar[fired] += 2.0 ** -8 * wr / np.maximum(np.linalg.norm(Yo[fired], axis=1), 1e-300)
+    assert np.all(err <= bar), float((err / bar).max())
+    say(f"  identical to the ordinary-image run; vs oracle with the expanded image {err.max():.3e}")
