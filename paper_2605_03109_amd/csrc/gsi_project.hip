@@ -399,8 +399,10 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
   g.a_rows = (int)(ceil_div(ar, rps_a) * rps_a);
   g.a_slabs = (int)ceil_div(d, g.a_rows);
   const int rps_b = kBlock / (int)(k / V);
-  int64_t br = ceil_div(d, kMaxResSlabs);  // four row steps per workgroup unless that needs too many slabs
-  if (br < 4 * rps_b) br = 4 * rps_b;
+  // eight row steps per workgroup unless that needs too many slabs: with the image rows of a GPT-J-sized block
+  // riding along, the residual launch is then one residency round (four workgroups per CU) instead of one and a half
+  int64_t br = ceil_div(d, kMaxResSlabs);
+  if (br < 8 * rps_b) br = 8 * rps_b;
   g.b_rows = (int)(ceil_div(br, rps_b) * rps_b);
   g.b_slabs = (int)ceil_div(d, g.b_rows);
   return g;
