@@ -26,6 +26,7 @@ namespace {
 
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
+constexpr int kResSlabRows = 64;  // rows of U per residual workgroup, lower bound
 
 __device__ __forceinline__ int find_task(const int* begin, int n, int b) {
   int t = 0;
@@ -399,10 +400,13 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
   g.a_rows = (int)(ceil_div(ar, rps_a) * rps_a);
   g.a_slabs = (int)ceil_div(d, g.a_rows);
   const int rps_b = kBlock / (int)(k / V);
-  // eight row steps per workgroup unless that needs too many slabs: with the image rows of a GPT-J-sized block
-  // riding along, the residual launch is then one residency round (four workgroups per CU) instead of one and a half
+  // At least four row steps and at least 64 rows per workgroup (unless that needs too many slabs).  Measured on
+  // GPT-J-sized blocks for k = 64 .. 512: with the image rows riding along, slabs of 64 rows keep the residual
+  // launch within one residency round (four workgroups per CU); smaller slabs spill into a second round, larger
+  // ones leave too few workgroups to cover the load latency.
   int64_t br = ceil_div(d, kMaxResSlabs);
-  if (br < 8 * rps_b) br = 8 * rps_b;
+  if (br < 4 * rps_b) br = 4 * rps_b;
+  if (br < kResSlabRows) br = kResSlabRows;
   g.b_rows = (int)(ceil_div(br, rps_b) * rps_b);
   g.b_slabs = (int)ceil_div(d, g.b_rows);
   return g;
