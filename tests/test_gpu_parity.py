@@ -674,3 +674,69 @@ def test_fp8_image_expanded_for_other_calls(gsi, pu, d, k, m, T, nf, B):
         bar[fired] += 2.0 ** -8 * wr / np.maximum(np.linalg.norm(Yo[fired], axis=1), 1e-300)
     assert np.all(err <= bar), float((err / bar).max())
     say(f"  identical to the ordinary-image run; vs oracle with the expanded image {err.max():.3e}")
+
+
+# ------------------------------------------------------------------------------------------------
+# HIP-graph replay (the launch mode bench.py times): a captured stack must give, on every replay, the bits of
+# the same calls issued eagerly -- with eager work and synchronisations between the replays, for one token per
+# call, a decode batch and a prefill-sized batch (the library records no memset nodes and allocates nothing).
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k,m,T,nf,B,fp8", [(1024, 64, 520, 6, 2, 1, False), (1024, 64, 520, 6, 2, 1, True),
+                                              (2048, 128, 528, 24, 5, 8, False), (1024, 64, 512, 300, 60, 300, False)])
+def test_graph_replay_equals_eager(gsi, pu, d, k, m, T, nf, B, fp8):
+    w = wl.tiny(d, k, m, T, nf, seed=9700 + d + k + T, wdtype="bf16")
+    say(f"case graph replay: d={d} k={k} m={m} T={T} nf={nf} B={B} fp8={fp8}")
+    g = w.groups[0]
+    dg = pu.DeviceGroup(w, g)
+    mp = {"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}
+    if fp8:
+        mp["M"], mp["M_scale"] = gsi.quantize_image_fp8(dg.M["w"])
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X}], [mp], T, w.eps)
+    outs = ("C", "R", "rnorm", "xnorm", "mask")
+
+    def snapshot():
+        torch.cuda.synchronize()
+        return [st.maps_t[0]["Y"].clone()] + [st.inputs_t[0][n].clone() for n in outs]
+
+    def clear():
+        st.maps_t[0]["Y"].fill_(float("nan"))
+        for n in outs:
+            st.inputs_t[0][n].zero_()
+
+    # descriptor tables of every call, kept alive for the graph
+    tabs = []
+    for t0 in range(0, T, B):
+        st.refresh(token_offset=t0, B=min(B, T - t0))
+        mpd, ind = (gsi.MapDesc * 1)(), (gsi.InputDesc * 1)()
+        ctypes.memmove(mpd, st._mp, ctypes.sizeof(mpd))
+        ctypes.memmove(ind, st._in, ctypes.sizeof(ind))
+        tabs.append((mpd, ind, min(B, T - t0)))
+    ws = st.ws
+
+    def issue(stream):
+        for mpd, ind, b in tabs:
+            rc = gsi.lib.gsi_layer_stack(mpd, 1, ind, 1, b, ctypes.c_float(w.eps), ws.data_ptr(), ws.numel(), stream)
+            assert rc == 0, gsi.last_error()
+
+    clear()
+    issue(torch.cuda.current_stream().cuda_stream)
+    eager = snapshot()
+    assert np.array_equal(eager[-1].cpu().numpy().astype(bool), g.fired_design)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        issue(side.cuda_stream)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        issue(torch.cuda.current_stream().cuda_stream)
+    for rep in range(3):
+        clear()
+        torch.cuda.synchronize()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(got, eager):
+            assert torch.equal(a, b), f"replay {rep} differs from the eager run"
+        issue(torch.cuda.current_stream().cuda_stream)   # eager work between the replays
+        torch.cuda.synchronize()
