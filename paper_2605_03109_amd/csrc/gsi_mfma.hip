@@ -12,10 +12,10 @@
 // other's LDS reads and staging), each wave 64 x 128 as 2 x 4 v_mfma_f32_32x32x16_bf16 fragments.
 // Both operand tiles are staged in LDS as bf16 (row stride padded to 144 bytes: conflict-free 128-bit
 // reads); an fp32 A operand is converted on the way in.  Global loads are whole 128-byte row segments per
-// eight lanes.  With a bf16 or once-rounded A operand LDS holds two k-tiles: tile t is multiplied while
-// tile t + 1 is written, a quarter per MFMA step, from registers that are asked for tile t + 2 at once; one
-// barrier per tile.  The head + tail form needs both halves of A in LDS and keeps one staged tile and two
-// barriers.  Within a k-tile the lane half l/32 takes 32 consecutive columns, eight per MFMA step: any order
+// eight lanes.  LDS holds two k-tiles: tile t is multiplied while tile t + 1 is written, a unit per MFMA step,
+// from registers that are asked for tile t + 2 at once; one barrier per tile.  A k-tile is 64 columns deep, or
+// 32 for the head + tail form (two tiles of A per stage, two MFMA passes per step: as many MFMAs between
+// barriers).  Within a k-tile the lane half l/32 takes one half of the columns, eight per MFMA step: any order
 // of the contraction index is as good as another as long as both operands agree.
 // What bounds the loop is LDS, not the matrix cores: a k-tile is 2048 MFMA cycles per SIMD, and its LDS
 // traffic (192 KB of operand reads at 128 bytes a cycle, 64 KB of staging writes at about 75) is 2400.
@@ -34,24 +34,39 @@ namespace {
 typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
 typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 
-constexpr int BM = 256, BN = 256, BK = 64;
+constexpr int BM = 256, BN = 256, BK = 64;      // BK: the host's unit of the contraction (K is a multiple of it)
 constexpr int WTM = 64, WTN = 128;              // wave tile: the eight waves sit 4 x 2 on the workgroup tile
-constexpr int LDB = BK + 8;  // padded LDS row stride of a staged tile, bf16 elements (144 bytes)
 constexpr int kThreads = 512;
-constexpr int kAF = WTM / 32, kBF = WTN / 32, kKS = BK / 16;  // A, B fragments per wave; MFMA steps per k-tile
-constexpr int kAU = BM * BK / 8 / kThreads;     // staging units (8 elements of a row) of A per thread: 4
-constexpr int kBU = BN * BK / 8 / kThreads;     // ... of B: 4
-constexpr int kRowsPerPass = kThreads / 8;      // rows of a tile that one staging unit index covers: 64
+constexpr int kAF = WTM / 32, kBF = WTN / 32;   // A, B fragments per wave
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));  // a native vector: loads and stores of it are
                                                               // instructions, not aggregate copies
 
 // AM: how the A operand is stored and fed: 0 bf16; 1 fp32, split into bf16 head + tail (two LDS tiles, two
-// MFMA passes); 2 fp32, rounded once to bf16
+// MFMA passes); 2 fp32, rounded once to bf16.
+// Geometry of a staged k-tile by mode.  The head + tail form keeps two tiles of A per stage, so its k-tile is 32
+// columns deep (two MFMA steps of two passes each: as many MFMAs between barriers as the 64-deep tile of the
+// other modes) and two stages still fit in LDS.
+template <int AM>
+struct Geo {
+  static constexpr int BKT = AM == 1 ? 32 : 64;          // columns of a k-tile
+  static constexpr int LD = BKT + 8;                     // padded LDS row stride, bf16 elements (80 or 144 bytes:
+                                                         // conflict-free 128-bit reads either way)
+  static constexpr int KS = BKT / 16;                    // MFMA steps per k-tile
+  static constexpr int CPR = BKT / 8;                    // staging units (8 elements) per tile row
+  static constexpr int RPP = kThreads / CPR;             // tile rows covered by one unit index of all threads
+  static constexpr int NU = BM / RPP;                    // units of A (and of B) per thread and k-tile
+  static constexpr int NP = AM == 1 ? 2 : 1;             // LDS tiles of A per stage
+  static constexpr int kATile = BM * LD;                 // elements of one LDS tile of A
+  static constexpr int kStage = (NP * BM + BN) * LD;     // elements of one stage
+  static_assert(NU == KS, "one staging unit per MFMA step");
+  static_assert(BM == BN, "A and B tiles are staged alike");
+};
+
 template <int AM>
 struct Stage {
-  u32x4 a[kAU][AM ? 2 : 1];
-  u32x4 b[kBU];
+  u32x4 a[Geo<AM>::NU][AM ? 2 : 1];
+  u32x4 b[Geo<AM>::NU];
 };
 
 // 8 fp32 -> 8 bf16 (RNE), and the bf16 of what is left
@@ -73,27 +88,30 @@ __device__ __forceinline__ u32x4 round8(const u32x4& x0, const u32x4& x1, u32x4*
                (uint32_t)h[4] | ((uint32_t)h[5] << 16), (uint32_t)h[6] | ((uint32_t)h[7] << 16)};
 }
 
-// requests unit u of k-tile kt of both operands (unit u of a thread: row (tid >> 3) + 64 u, columns 8 (tid & 7) .. + 8)
+// requests unit u of k-tile kt of both operands (unit u of a thread: tile row tid / CPR + RPP u, columns
+// 8 (tid % CPR) .. + 8; the pointers already point at that row and column of k-tile 0)
 template <int AM>
-__device__ __forceinline__ void issue_unit(Stage<AM>& st, int u, const char* const (&ap)[kAU], const char* const (&bp)[kBU], int kt) {
+__device__ __forceinline__ void issue_unit(Stage<AM>& st, int u, const char* const (&ap)[Geo<AM>::NU],
+                                           const char* const (&bp)[Geo<AM>::NU], int kt) {
   constexpr int ES = AM ? 4 : 2;
-  const char* p = ap[u] + (int64_t)kt * BK * ES;
+  const char* p = ap[u] + (int64_t)kt * Geo<AM>::BKT * ES;
   st.a[u][0] = *reinterpret_cast<const u32x4*>(p);
   if constexpr (AM != 0) st.a[u][1] = *reinterpret_cast<const u32x4*>(p + 16);
-  st.b[u] = *reinterpret_cast<const u32x4*>(bp[u] + (int64_t)kt * BK * 2);
+  st.b[u] = *reinterpret_cast<const u32x4*>(bp[u] + (int64_t)kt * Geo<AM>::BKT * 2);
 }
 template <int AM>
-__device__ __forceinline__ void issue(Stage<AM>& st, const char* const (&ap)[kAU], const char* const (&bp)[kBU], int kt) {
+__device__ __forceinline__ void issue(Stage<AM>& st, const char* const (&ap)[Geo<AM>::NU], const char* const (&bp)[Geo<AM>::NU],
+                                      int kt) {
 #pragma unroll
-  for (int u = 0; u < kAU; ++u) issue_unit<AM>(st, u, ap, bp, kt);
+  for (int u = 0; u < Geo<AM>::NU; ++u) issue_unit<AM>(st, u, ap, bp, kt);
 }
 
-// writes unit u of the staged k-tile to LDS as bf16 (fp32 A: rounded, or head and tail tiles)
+// writes unit u of the staged k-tile to the LDS stage at `stage` as bf16 (fp32 A: rounded, or head and tail tiles)
 template <int AM>
-__device__ __forceinline__ void commit_unit(const Stage<AM>& st, int u, uint16_t (*Ah)[LDB], uint16_t (*At)[LDB],
-                                            uint16_t (*Bq)[LDB], int tid) {
-  const int r = (tid >> 3) + kRowsPerPass * u, c8 = 8 * (tid & 7);
-  u32x4* d0 = reinterpret_cast<u32x4*>(&Ah[r][c8]);
+__device__ __forceinline__ void commit_unit(const Stage<AM>& st, int u, uint16_t* stage, int tid) {
+  using G = Geo<AM>;
+  const int off = ((tid / G::CPR) + G::RPP * u) * G::LD + 8 * (tid % G::CPR);
+  u32x4* d0 = reinterpret_cast<u32x4*>(stage + off);
   if constexpr (AM == 0) {
     *d0 = st.a[u][0];
   } else if constexpr (AM == 2) {
@@ -101,18 +119,18 @@ __device__ __forceinline__ void commit_unit(const Stage<AM>& st, int u, uint16_t
   } else {
     u32x4 tail;
     *d0 = round8(st.a[u][0], st.a[u][1], &tail);
-    *reinterpret_cast<u32x4*>(&At[r][c8]) = tail;
+    *reinterpret_cast<u32x4*>(stage + G::kATile + off) = tail;
   }
-  *reinterpret_cast<u32x4*>(&Bq[r][c8]) = st.b[u];
+  *reinterpret_cast<u32x4*>(stage + G::NP * G::kATile + off) = st.b[u];
 }
 template <int AM>
-__device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t (*Ah)[LDB], uint16_t (*At)[LDB], uint16_t (*Bq)[LDB], int tid) {
+__device__ __forceinline__ void commit(const Stage<AM>& st, uint16_t* stage, int tid) {
 #pragma unroll
-  for (int u = 0; u < kAU; ++u) commit_unit<AM>(st, u, Ah, At, Bq, tid);
+  for (int u = 0; u < Geo<AM>::NU; ++u) commit_unit<AM>(st, u, stage, tid);
 }
 
-// The MFMA operands of one step (16 columns of the k-tile) of a wave: lane half lh takes columns 32 lh .. + 32 of
-// the tile, eight per step (both operands in the same order, so the order of the contraction index does not
+// The MFMA operands of one step (16 columns of the k-tile) of a wave: lane half lh takes one half of the tile's
+// columns, eight per step (both operands in the same order, so the order of the contraction index does not
 // matter)
 template <int AM>
 struct Ops {
@@ -121,15 +139,17 @@ struct Ops {
   bf16x8 b[kBF];
 };
 template <int AM>
-__device__ __forceinline__ void read_ops(Ops<AM>& o, const uint16_t (*Ah)[LDB], const uint16_t (*At)[LDB],
-                                         const uint16_t (*Bq)[LDB], int wm, int wn, int lc, int lh, int j) {
-  const int col = 32 * lh + 8 * j;
+__device__ __forceinline__ void read_ops(Ops<AM>& o, const uint16_t* stage, int wm, int wn, int lc, int lh, int j) {
+  using G = Geo<AM>;
+  const int col = (G::BKT / 2) * lh + 8 * j;
+  const uint16_t* Bq = stage + G::NP * G::kATile;
 #pragma unroll
-  for (int n = 0; n < kBF; ++n) o.b[n] = *reinterpret_cast<const bf16x8*>(&Bq[WTN * wn + 32 * n + lc][col]);
+  for (int n = 0; n < kBF; ++n) o.b[n] = *reinterpret_cast<const bf16x8*>(Bq + (WTN * wn + 32 * n + lc) * G::LD + col);
 #pragma unroll
   for (int i = 0; i < kAF; ++i) {
-    o.a[i] = *reinterpret_cast<const bf16x8*>(&Ah[WTM * wm + 32 * i + lc][col]);
-    if constexpr (AM == 1) o.al[i] = *reinterpret_cast<const bf16x8*>(&At[WTM * wm + 32 * i + lc][col]);
+    const int off = (WTM * wm + 32 * i + lc) * G::LD + col;
+    o.a[i] = *reinterpret_cast<const bf16x8*>(stage + off);
+    if constexpr (AM == 1) o.al[i] = *reinterpret_cast<const bf16x8*>(stage + G::kATile + off);
   }
 }
 template <int AM>
@@ -147,11 +167,9 @@ __device__ __forceinline__ void mma(const Ops<AM>& o, f32x16 (&acc)[kAF][kBF]) {
 
 template <int AM, int EPI>
 __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
-  // fp32 head + tail operand: As[0] head, As[1] tail, one staged k-tile.  Otherwise two staged k-tiles (As[s],
-  // Bs[s]): one is multiplied while the next is written.
-  constexpr bool kTwoStages = AM != 1;
-  __shared__ __align__(16) uint16_t As[2][BM][LDB];
-  __shared__ __align__(16) uint16_t Bs[kTwoStages ? 2 : 1][BN][LDB];
+  using G = Geo<AM>;
+  // two stages, each the tile(s) of A followed by the tile of B
+  __shared__ __align__(16) uint16_t lds[2 * G::kStage];
 
   int Mrows = g.M;
   if (g.n_rows_dev) {
@@ -181,26 +199,26 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
   constexpr int ES = AM ? 4 : 2;  // bytes per element of A
 
   // k-tiles of this split
-  const int nk = g.K / BK;  // K is a multiple of 64
+  const int nk = g.K / G::BKT;  // K is a multiple of 64
   const int splits = g.splits > 1 ? g.splits : 1;
   const int kt0 = (int)(((int64_t)nk * blockIdx.z) / splits), kt1 = (int)(((int64_t)nk * (blockIdx.z + 1)) / splits);
 
-  // staging pointers: a thread's unit u is row (tid >> 3) + 64 u of the tile, 8 columns at 8 (tid & 7); rows past
-  // the end repeat the last one (their results are not stored)
-  const char* ap[kAU];
-  const char* bp[kBU];
+  // staging pointers: a thread's unit u is tile row tid / CPR + RPP u, 8 columns at 8 (tid % CPR); rows past the
+  // end repeat the last one (their results are not stored)
+  const char* ap[G::NU];
+  const char* bp[G::NU];
 #pragma unroll
-  for (int u = 0; u < kAU; ++u) {
-    int grow = tile_m * BM + (tid >> 3) + kRowsPerPass * u;
+  for (int u = 0; u < G::NU; ++u) {
+    int grow = tile_m * BM + (tid / G::CPR) + G::RPP * u;
     grow = grow < Mrows ? grow : Mrows - 1;
     if (g.row_idx) grow = g.row_idx[grow];
-    ap[u] = reinterpret_cast<const char*>(g.A) + ((int64_t)grow * g.lda + 8 * (tid & 7)) * ES;
+    ap[u] = reinterpret_cast<const char*>(g.A) + ((int64_t)grow * g.lda + 8 * (tid % G::CPR)) * ES;
   }
 #pragma unroll
-  for (int u = 0; u < kBU; ++u) {
-    int grow = tile_n * BN + (tid >> 3) + kRowsPerPass * u;
+  for (int u = 0; u < G::NU; ++u) {
+    int grow = tile_n * BN + (tid / G::CPR) + G::RPP * u;
     grow = grow < N ? grow : N - 1;
-    bp[u] = reinterpret_cast<const char*>(Bmat) + ((int64_t)grow * ldb + 8 * (tid & 7)) * 2;
+    bp[u] = reinterpret_cast<const char*>(Bmat) + ((int64_t)grow * ldb + 8 * (tid % G::CPR)) * 2;
   }
 
   f32x16 acc[kAF][kBF];
@@ -212,74 +230,52 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
       for (int v = 0; v < 16; ++v) acc[i][j][v] = 0.f;
 
   if (kt0 < kt1) {
+    // Tile t is multiplied out of stage t & 1 while tile t + 1 (in registers since the tile before) is written
+    // to the other stage, a unit per MFMA step, and each unit's registers are asked for tile t + 2 at once.
+    // One barrier per tile, before the last step: by then every wave has written its share of the next stage
+    // and has the last step's operands in registers, so the first operands of the next tile are read behind
+    // the last step's MFMAs.  Past the range the last tile is requested (and staged) again and never used.
     Stage<AM> st;
-    if constexpr (kTwoStages) {
-      // Tile t is multiplied out of stage t & 1 while tile t + 1 (in registers since the tile before) is written
-      // to the other stage, a unit per MFMA step, and each unit's registers are asked for tile t + 2 at once.
-      // One barrier per tile, before the last step: by then every wave has written its share of the next stage
-      // and has the last step's operands in registers, so the first operands of the next tile are read behind
-      // the last step's MFMAs.  Past the range the last tile is requested (and staged) again and never used.
-      static_assert(kAU == kKS && kBU == kKS, "one staging unit per MFMA step");
-      issue<AM>(st, ap, bp, kt0);
-      commit<AM>(st, As[0], nullptr, Bs[0], tid);
-      issue<AM>(st, ap, bp, kt0 + 1 < kt1 ? kt0 + 1 : kt0);
-      __syncthreads();
-      Ops<AM> o[2];
-      read_ops<AM>(o[0], As[0], nullptr, Bs[0], wm, wn, lc, lh, 0);
-      for (int kt = kt0; kt < kt1; ++kt) {
-        const int cur = (kt - kt0) & 1, nxt = cur ^ 1;
-        const int kt2 = kt + 2 < kt1 ? kt + 2 : kt1 - 1;
+    issue<AM>(st, ap, bp, kt0);
+    commit<AM>(st, lds, tid);
+    issue<AM>(st, ap, bp, kt0 + 1 < kt1 ? kt0 + 1 : kt0);
+    __syncthreads();
+    Ops<AM> o[2];
+    read_ops<AM>(o[0], lds, wm, wn, lc, lh, 0);
+    for (int kt = kt0; kt < kt1; ++kt) {
+      uint16_t* cur = lds + ((kt - kt0) & 1) * G::kStage;
+      uint16_t* nxt = lds + (((kt - kt0) & 1) ^ 1) * G::kStage;
+      const int kt2 = kt + 2 < kt1 ? kt + 2 : kt1 - 1;
 #pragma unroll
-        for (int j = 0; j < kKS; ++j) {
-          if (j + 1 < kKS) {
-            read_ops<AM>(o[(j + 1) & 1], As[cur], nullptr, Bs[cur], wm, wn, lc, lh, j + 1);
-          } else {
-            __syncthreads();
-            read_ops<AM>(o[(j + 1) & 1], As[nxt], nullptr, Bs[nxt], wm, wn, lc, lh, 0);
-          }
-          mma<AM>(o[j & 1], acc);
-          if (j + 1 < kKS) {
-            // units 0, 1 behind steps 0, 1; units 2 and 3 behind step 2 (the barrier follows)
-            commit_unit<AM>(st, j, As[nxt], nullptr, Bs[nxt], tid);
-            issue_unit<AM>(st, j, ap, bp, kt2);
-            if (j + 2 == kKS) {
-              commit_unit<AM>(st, j + 1, As[nxt], nullptr, Bs[nxt], tid);
-              issue_unit<AM>(st, j + 1, ap, bp, kt2);
-            }
-          }
-          __builtin_amdgcn_sched_barrier(0);
+      for (int j = 0; j < G::KS; ++j) {
+        if (j + 1 < G::KS) {
+          read_ops<AM>(o[(j + 1) & 1], cur, wm, wn, lc, lh, j + 1);
+        } else {
+          __syncthreads();
+          read_ops<AM>(o[(j + 1) & 1], nxt, wm, wn, lc, lh, 0);
         }
-      }
-    } else {
-      issue<AM>(st, ap, bp, kt0);
-      commit<AM>(st, As[0], As[1], Bs[0], tid);
-      __syncthreads();
-      for (int kt = kt0; kt < kt1; ++kt) {
-        // the next k-tile travels from memory to registers while this one is multiplied (past the range the
-        // last tile is requested again and never used)
-        __builtin_amdgcn_sched_barrier(0);
-        issue<AM>(st, ap, bp, kt + 1 < kt1 ? kt + 1 : kt);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int j = 0; j < kKS; ++j) {
-          Ops<AM> o;
-          read_ops<AM>(o, As[0], As[1], Bs[0], wm, wn, lc, lh, j);
-          mma<AM>(o, acc);
+        mma<AM>(o[j & 1], acc);
+        if (j + 1 < G::KS) {
+          // a unit behind every step but the last two, which share the step before the barrier
+          commit_unit<AM>(st, j, nxt, tid);
+          issue_unit<AM>(st, j, ap, bp, kt2);
+          if (j + 2 == G::KS) {
+            commit_unit<AM>(st, j + 1, nxt, tid);
+            issue_unit<AM>(st, j + 1, ap, bp, kt2);
+          }
         }
-        __syncthreads();  // every wave has read the tile
-        commit<AM>(st, As[0], As[1], Bs[0], tid);
-        __syncthreads();
+        __builtin_amdgcn_sched_barrier(0);
       }
     }
   }
 
   // ---- epilogue --------------------------------------------------------------------------------------
   // Element v of lane l of fragment (i, n) is row 8 (v / 4) + 4 (l / 32) + v % 4, column l % 32 of the
-  // fragment.  The accumulators go through LDS sixteen rows at a time (a private strip per wave), so that
+  // fragment.  The accumulators go through LDS eight rows at a time (a private strip per wave), so that
   // what touches memory is row-contiguous: a lane then owns four consecutive columns of a row.
   __syncthreads();  // the operand tiles are no longer read
   constexpr int kSR = 8, kSLD = WTN + 4;  // strip rows, padded strip stride (floats)
-  float* strip = reinterpret_cast<float*>(&As[0][0][0]) + wave * (kSR * kSLD);
+  float* strip = reinterpret_cast<float*>(lds) + wave * (kSR * kSLD);
   const bool partial = g.splits > 1;
   float* const pdst = partial ? g.part + (int64_t)blockIdx.z * g.M * N : nullptr;
   const int er = lane >> 5, ec = 4 * (lane & 31);  // row parity and first column of the lane's reads
@@ -293,7 +289,11 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
 #pragma unroll
       for (int n = 0; n < kBF; ++n) strip[rl * kSLD + 32 * n + lc] = acc[i][n][vbase + vv];
     }
-    __syncthreads();
+    // The strip is private to the wave and a wave's LDS operations execute in order, so no workgroup barrier is
+    // needed (one would also wait for the stores of the round before to complete); the fence only keeps the
+    // compiler from moving a lane's reads above the other lanes' writes.
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");
+    __builtin_amdgcn_wave_barrier();
     const int col = tile_n * BN + WTN * wn + ec;
     float4 val[kSR / 2];
     int row[kSR / 2];
@@ -364,7 +364,8 @@ __global__ __launch_bounds__(kThreads) void gemm_nt(const GemmArgs g) {
         }
       }
     }
-    __syncthreads();  // the strip is rewritten by the next round
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "wavefront");  // the strip is rewritten by the next round
+    __builtin_amdgcn_wave_barrier();
   }
 }
 
