@@ -64,7 +64,8 @@ def test_small_and_odd_shapes(gsi, pu, wdtype, d, k, m, T, nf):
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("wdtype", ["bf16", "f32"])
 @pytest.mark.parametrize("d,k,m,T,nf", [(1024, 64, 520, 9, 3), (776, 72, 1000, 5, 2), (4096, 256, 1032, 6, 2),
-                                        (2048, 128, 264, 33, 7), (4096, 512, 512, 3, 1), (8192, 32, 300, 2, 1)])
+                                        (2048, 128, 264, 33, 7), (4096, 512, 512, 3, 1), (8192, 32, 300, 2, 1),
+                                        (16384, 512, 520, 3, 1), (16384, 64, 264, 3, 1), (4160, 128, 264, 4, 2)])
 def test_mid_shapes(gsi, pu, wdtype, d, k, m, T, nf):
     w = wl.tiny(d, k, m, T, nf, seed=2000 + d + k + m, wdtype=wdtype)
     say(f"case mid d={d} k={k} m={m} T={T} nf={nf} {wdtype}")
