@@ -242,10 +242,22 @@ def run_ragged(args, torch, gsi, wd):
             maps.append({"W": Wt, "M": M, "input_id": gi})
             designed.append(f)
         st = gsi.LayerStack(inputs, maps, T, eps)
+        # --rotate N: N copies of every weight, basis and image, used in turn by consecutive steps, so that
+        # nothing a step reads is left in the 256 MB Infinity Cache from the step before
+        copies = [[(t["W"], t["M"]) for t in st.maps_t]]
+        ucopies = [[t["U"] for t in st.inputs_t]]
+        for _ in range(1, max(1, args.rotate)):
+            copies.append([(t["W"].clone(), t["M"].clone()) for t in st.maps_t])
+            ucopies.append([t["U"].clone() for t in st.inputs_t])
         tabs = []
         for s_ in range(steps):
             st.refresh(token_offset=s_ * B, B=B)
-            tabs.append(copy_tables(gsi, st))
+            mp, inp = copy_tables(gsi, st)
+            for j, (Wc, Mc) in enumerate(copies[s_ % len(copies)]):
+                mp[j].W, mp[j].M = Wc.data_ptr(), Mc.data_ptr()
+            for i, Uc in enumerate(ucopies[s_ % len(ucopies)]):
+                inp[i].U = Uc.data_ptr()
+            tabs.append((mp, inp))
         wsp, wsn = st.ws.data_ptr(), st.ws.numel()
 
         def gated_step(t, s):
@@ -283,10 +295,10 @@ def run_ragged(args, torch, gsi, wd):
                "effective_weight_GBs": round(dense_bytes / us / 1e3, 1),
                "weight_matrix_reads": w_reads, "of_possible": 2 * steps,
                "fired_tokens": int(sum(int(f.sum()) for f in designed)), "tokens": 2 * T,
-               "compaction_matches_design": ok}
+               "compaction_matches_design": ok, "operand_copies": max(1, args.rotate)}
         log(f"[report] {row}")
         rows.append(row)
-        del st, inputs, maps, tabs
+        del st, inputs, maps, tabs, copies, ucopies
         torch.cuda.empty_cache()
     return {"config": 3, "workload": "fc_in 16384x4096 and fc_out 4096x16384, bf16, k=256, eps=0.05, per-token "
             "Bernoulli(0.15) gate design, one gsi_layer_stack call per step", "launch_mode": args.mode, "rows": rows}
@@ -371,6 +383,8 @@ def main() -> int:
     ap.add_argument("--fires", default="0,0.05,0.25,1.0")
     ap.add_argument("--batches", default="1,4,16,64")
     ap.add_argument("--tokens", type=int, default=2048)
+    ap.add_argument("--rotate", type=int, default=1,
+                    help="config 3: copies of every weight, basis and image used in turn by consecutive steps")
     ap.add_argument("--xdtype", choices=["f32", "bf16"], default="bf16")
     args = ap.parse_args()
     if args.steps is None:
