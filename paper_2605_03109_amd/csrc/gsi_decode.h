@@ -34,6 +34,8 @@ struct ProjTask {
   int b_rows, b_slabs;             // residual: rows per slab, slabs
   int udtype, xdtype;
   int tile;                        // decode batch on the matrix cores (gsi_tile.hip) with its own slab geometry
+  int b_perm;                      // residual slabs per partial-projection slab when the residual launch walks its
+                                   // slabs in the XCD order of the partial projection, else 0 (filled at launch)
 };
 
 struct ProjBatch {

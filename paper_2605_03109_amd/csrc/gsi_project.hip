@@ -44,7 +44,9 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
   const int ti = find_task(pb.a_begin, pb.n, blockIdx.x);
   const ProjTask& p = pb.t[ti];
   const int local = blockIdx.x - pb.a_begin[ti];
-  const int cb = local % p.a_cblocks, slab = local / p.a_cblocks;
+  // column blocks of one row slab are a_slabs workgroups apart: with a_slabs a multiple of 8 they run on the same
+  // XCD (workgroups go to the 8 XCDs in turn), whose L2 then holds all columns of the slab for the residual launch
+  const int slab = local % p.a_slabs, cb = local / p.a_slabs;
   const int d = p.d, k = p.k, B = pb.B;
   const int cbw = k < kColBlock ? k : kColBlock;  // columns of this block
   const int lps = cbw / V;                        // lanes per row segment (a power of two)
@@ -186,7 +188,14 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, cons
 
   const int ti = find_task(pb.b_begin, pb.n, blockIdx.x);
   const ProjTask& p = pb.t[ti];
-  const int slab = blockIdx.x - pb.b_begin[ti];
+  int slab = blockIdx.x - pb.b_begin[ti];
+  if (p.b_perm) {
+    // walk the slabs so that a workgroup lands on the XCD whose L2 the partial projection left these rows of U in:
+    // workgroup j = 8 q + x runs on XCD x (relative to the task's first); it takes residual slab u = q % r of
+    // partial-projection slab t = 8 (q / r) + x, which ran on XCD x as well
+    const int r = p.b_perm, x = slab & 7, q = slab >> 3;
+    slab = ((q / r) * 8 + x) * r + q % r;
+  }
   const int d = p.d, k = p.k, B = pb.B;
   const int cpr = k / V;         // 16-byte chunks per row (power of two, <= 64)
   const int rps = kBlock / cpr;  // rows per step
@@ -499,6 +508,16 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
   }
   if (ta == 0 || pb.B == 0) return hipSuccess;
   pb.b_total = tb;
+  for (int i = 0; i < pb.n; ++i) {
+    ProjTask& t = pb.t[i];
+    t.b_perm = 0;
+    if (t.b_rows > 0 && t.a_rows % t.b_rows == 0) {
+      const int r = t.a_rows / t.b_rows;
+      if (t.a_slabs % 8 == 0 && t.b_slabs % (8 * r) == 0 && pb.a_begin[i] % 8 == pb.b_begin[i] % 8 &&
+          (int64_t)t.a_slabs * t.a_rows == t.d && (int64_t)t.b_slabs * t.b_rows == t.d)
+        t.b_perm = r;
+    }
+  }
   ImgBatch none;
   none.n = 0;
   none.total = 0;
