@@ -262,7 +262,9 @@ __global__ __launch_bounds__(kPBlock) void tile_proj_partial(const ProjBatch pb)
   const ProjTask& p = pb.t[ti];
   const int local = blockIdx.x - pb.a_begin[ti];
   const int cgroups = p.k / kPCols;
-  const int cg = local % cgroups, slab = local / cgroups;
+  // the column groups of a row slab are a_slabs workgroups apart: on the same XCD when a_slabs is a multiple of 8
+  // (workgroups go to the 8 XCDs in turn), and so is the residual workgroup of the same rows
+  const int slab = local % p.a_slabs, cg = local / p.a_slabs;
   const int d = p.d, k = p.k, B = pb.B;
   const int row_begin = slab * p.a_rows;
   const int steps = (min(p.a_rows, d - row_begin)) / kStepCols;  // 1..4: d and a_rows are multiples of 32
@@ -408,7 +410,8 @@ __global__ __launch_bounds__(kTBlock) void tile_residual(const ProjBatch pb) {
   const ProjTask& p = pb.t[ti];
   const int rounds = (B + kRoundTok - 1) / kRoundTok;
   const int item = blockIdx.x - pb.b_begin[ti];
-  const int rb = item / rounds, g0 = (item - rb * rounds) * kRoundTok;
+  const int nrb = p.d / kItemRows;  // row blocks; the rounds of a row block are nrb workgroups apart (same XCD)
+  const int rb = item % nrb, g0 = (item / nrb) * kRoundTok;
   const int count = min(B, g0 + kRoundTok);
   const int d = p.d, k = p.k, ns = k / kStepCols;
   const int row0 = rb * kItemRows + 16 * wave;  // d is a multiple of 128: every row exists
