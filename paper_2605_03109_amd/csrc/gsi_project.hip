@@ -9,6 +9,10 @@
 //                  The slab of U is requested before the partials so both latencies overlap.
 //   proj_norms     |r|, |x| from the slab shares; optionally the gate and the ordered compaction.
 //
+// Workgroups are handed to the chip's 8 XCDs in turn, each with an L2 of its own.  Both launches therefore walk
+// their row slabs in an order that puts the workgroups of the same rows of U on the same XCD, so that the
+// residual launch finds the basis in the L2 the partial projection filled.
+//
 // All reductions have a fixed order: results are bit-identical run to run.
 #include <algorithm>
 
