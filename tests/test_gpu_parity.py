@@ -677,6 +677,35 @@ def test_fp8_image_expanded_for_other_calls(gsi, pu, d, k, m, T, nf, B):
     say(f"  identical to the ordinary-image run; vs oracle with the expanded image {err.max():.3e}")
 
 
+def test_fp8_image_beside_a_map_on_the_generic_kernels(gsi, pu):
+    """Two maps of one input, one of them with a weight matrix that is not 16-byte aligned: the input then takes
+    the separate norm + gate launch and the aligned map's E4M3 codes are read by the stand-alone image kernel."""
+    w = wl.tiny(1024, 64, 264, 5, 2, seed=9600, wdtype="bf16")
+    say("case fp8 image beside a generic map")
+    g = w.groups[0]
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    ref = og.run()
+    M8, scale = gsi.quantize_image_fp8(dg.M["w"])
+    flat = torch.empty(dg.W["w"].numel() + 1, dtype=torch.bfloat16, device="cuda")
+    W_odd = flat[1:].view_as(dg.W["w"])                      # same values, 2 bytes off a 16-byte boundary
+    W_odd.copy_(dg.W["w"])
+    maps = [{"W": dg.W["w"], "M": M8, "M_scale": scale, "input_id": 0}, {"W": W_odd, "M": dg.M["w"], "input_id": 0}]
+    T = 5
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X}], maps, T, w.eps)
+    for t0 in range(T):
+        st.refresh(token_offset=t0, B=1)
+        st.run()
+    torch.cuda.synchronize()
+    mask = st.inputs_t[0]["mask"].cpu().numpy()
+    assert np.array_equal(mask.astype(bool), g.fired_design)
+    Mdeq = O.dequantize_image_fp8(M8.cpu().numpy(), scale.cpu().numpy())
+    Mdev = O.widen(gsi.bits_of(dg.M["w"]), "bf16")
+    for j, Mj in enumerate((Mdeq, Mdev)):
+        Y = st.maps_t[j]["Y"].cpu().numpy().astype(np.float64)
+        err = pu.rel_l2_rows(Y, O.gated_linear(og.W["w"], Mj, ref["C"], ref["R"], mask))
+        assert err.max() <= 2e-5, (j, err.max())
+
+
 # ------------------------------------------------------------------------------------------------
 # HIP-graph replay (the launch mode bench.py times): a captured stack must give, on every replay, the bits of
 # the same calls issued eagerly -- with eager work and synchronisations between the replays, for one token per
