@@ -322,6 +322,38 @@ def pin_paper_closed_forms(O, rows):
     assert abs(O.effective_params([(6, 4096, 4096, 256, 1.0)]) * 16 - 6 * 4096 * 4096) < 1e-6
 
 
+def pin_alg1_mixed_mask(O):
+    # Algorithm 1 as printed, both branches in one call: a fired token gets W x, an un-fired one M c of
+    # *its own* coefficients.  Expected values are exactly rounded loop sums that never call the oracle.
+    rng = np.random.default_rng(31)
+    d, k, m, B = 11, 3, 4, 5
+    U, _ = np.linalg.qr(rng.standard_normal((d, k)))
+    X = rng.standard_normal((B, d)) * np.array([1.0, 3.0, 0.5, 2.0, 7.0])[:, None]   # tokens differ in size
+    W = rng.standard_normal((m, d))
+    mask = np.array([0, 1, 0, 0, 1], dtype=np.uint8)
+    WU = _fsum_matmul(W, U)
+    C = np.array([_fsum_matvec(U.T, X[t]) for t in range(B)])
+    Y = O.gated_linear_alg1(W, WU, C, X, mask)
+    assert Y.shape == (B, m)
+    for t in range(B):
+        yexp = _fsum_matvec(W, X[t]) if mask[t] else _fsum_matvec(WU, C[t])
+        assert np.allclose(Y[t], yexp, rtol=0, atol=1e-13), t
+    # the un-fired rows differ from token to token and from the dense product (the fast path approximates)
+    assert np.linalg.norm(Y[0] - Y[2]) > 1e-3 and np.linalg.norm(Y[0] - _fsum_matvec(W, X[0])) > 1e-3
+    # hand-worked (same numbers as pin_hand_worked_2d): un-fired gives M c = (4.84, 11, 17.16)
+    U2, X2 = np.array([[0.6], [0.8]]), np.array([[1.0, 2.0], [1.0, 2.0]])
+    W2 = np.array([[1.0, 2.0], [3.0, 4.0], [5.0, 6.0]])
+    Y2 = O.gated_linear_alg1(W2, np.array([[2.2], [5.0], [7.8]]), np.array([[2.2], [2.2]]), X2, np.array([0, 1], dtype=np.uint8))
+    assert np.allclose(Y2, [[4.84, 11.0, 17.16], [5.0, 11.0, 17.0]], rtol=0, atol=1e-13)
+
+
+def pin_residual_ratio_zero_input(O):
+    # x = 0 gives 0/0; the reading taken is rho := 0 (and the gate does not fire).  Other entries are plain quotients.
+    rho = O.residual_ratio(np.array([0.0, 0.3, 0.0, 2.0]), np.array([0.0, 0.6, 5.0, 2.0]))
+    assert rho.tolist() == [0.0, 0.5, 0.0, 1.0]
+    assert O.residual_ratio(np.zeros(3), np.zeros(3)).tolist() == [0.0, 0.0, 0.0]
+
+
 PINS = [
     pin_hand_worked_2d,
     pin_axis_aligned_basis,
@@ -337,6 +369,8 @@ PINS = [
     pin_batch_equals_per_token,
     pin_widen,
     pin_stack,
+    pin_alg1_mixed_mask,
+    pin_residual_ratio_zero_input,
 ]
 
 

@@ -35,6 +35,10 @@ MUTANTS = [
     ("slow_term_never", "if mask[t]:\n            y = y + W @ R[t]", "if False:\n            y = y + W @ R[t]"),
     ("slow_term_uses_wrong_token", "y = y + W @ R[t] ", "y = y + W @ R[0] "),
     ("alg1_branches_swapped", "Y[t] = W @ X[t] if mask[t] else M @ C[t]", "Y[t] = M @ C[t] if mask[t] else W @ X[t]"),
+    ("alg1_unfired_uses_first_token", "Y[t] = W @ X[t] if mask[t] else M @ C[t]", "Y[t] = W @ X[t] if mask[t] else M @ C[0]"),
+    ("alg1_unfired_doubled", "Y[t] = W @ X[t] if mask[t] else M @ C[t]", "Y[t] = W @ X[t] if mask[t] else 2.0 * (M @ C[t])"),
+    ("alg1_fired_uses_image", "Y[t] = W @ X[t] if mask[t] else M @ C[t]", "Y[t] = M @ C[t]"),
+    ("rho_one_at_zero_input", "rho = np.zeros_like(rnorm)", "rho = np.ones_like(rnorm)"),
     ("dense_transposed", "Y[t] = W @ X[t]\n    return Y\n\n\ndef gated_linear(", "Y[t] = (W[::-1] @ X[t])\n    return Y\n\n\ndef gated_linear("),
     ("bf16_shift", "<< np.uint32(16)", "<< np.uint32(15)"),
     ("speedup_formula", "return 1.0 / (f / (d / k) + (1.0 - f))", "return 1.0 / (f * (d / k) + (1.0 - f))"),
