@@ -160,12 +160,12 @@ enum { GSI_MAP_IMAGE_FP8 = 1 };
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream);
 
-/* Instrumented variant for measurements: identical to gsi_layer_stack; in addition the two HIP events
- * (hipEvent_t passed as void*, created by the caller with timing enabled) take the start and stop
- * timestamps of the dispatch of the single-token linear-map kernel (the launch that evaluates every
- * map of the call for B == 1), so hipEventElapsedTime(begin, end) is that kernel's execution time as
- * a profiler reports it.  If the maps of a call need several such launches the events time the last
- * one; for B != 1 the events are not recorded. */
+/* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition
+ * the two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start
+ * and stop timestamps of the dispatch of the call's single-token kernel (for B == 1 one launch evaluates the
+ * projections, the gates and every map of up to four inputs), so hipEventElapsedTime(begin, end) is that
+ * kernel's execution time as a profiler reports it.  If a call needs several such launches the events time
+ * the last one; for B != 1 the events are not recorded. */
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                           int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
                           void* ev_linear_end);

@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "gsi_decode.h"
+#include "gsi_fused.h"
 #include "gsi_internal.h"
 #include "gsi_mfma.h"
 
@@ -402,6 +403,22 @@ struct LinBatcher {
 };
 }  // namespace
 
+// One token, one input, no maps: the fused single-token kernel computes c, r and the norms in one launch (the same
+// arithmetic as inside a layer stack, so the stack equals the separate calls bit for bit).  No gate outputs.
+static bool fused_project_only(gsi::FusedArgs& fa, const void* U, const void* X, int64_t d, int64_t k, int udtype,
+                               int xdtype, float* C, float* R, float* rnorm, float* xnorm) {
+  if (!gsi::fused_input_ok(d, k, udtype, U, X, xdtype, C, R, false)) return false;
+  std::memset(&fa, 0, sizeof(fa));
+  gsi::FusedChunk& ch = fa.c[0];
+  ch.n_in = 1; ch.n_mp = 0; ch.k = (int)k;
+  gsi::FusedIn& in = ch.in[0];
+  in.U = U; in.X = X; in.C = C; in.R = R; in.rnorm = rnorm; in.xnorm = xnorm;
+  in.d = (int)d; in.xdtype = xdtype; in.wx = 0;
+  fa.n_chunks = 1;
+  fa.eps = 2.f;  // a residual ratio never reaches 2: nothing fires, no gate output is written (the pointers are null)
+  return gsi::fused_plan(ch, udtype);
+}
+
 int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype, float* C,
                 float* R, float* rnorm, float* xnorm, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_project_args("gsi_project", U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm)) return rc;
@@ -409,7 +426,10 @@ int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, i
   if (int rc = check_ws("gsi_project", ws, ws_bytes, gsi_workspace_bytes(GSI_CALL_PROJECT, 0, d, k, B))) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (project_vector_path(d, k, B, udtype, U)) {
+  gsi::FusedArgs fa;
+  if (B == 1 && fused_project_only(fa, U, X, d, k, udtype, xdtype, C, R, rnorm, xnorm)) {
+    e = gsi::fused_launch(fa, udtype, s);
+  } else if (project_vector_path(d, k, B, udtype, U)) {
     gsi::ProjBatch pb;
     std::memset(&pb, 0, sizeof(pb));
     pb.n = 1;
@@ -760,6 +780,29 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     if (readers > 0 && all_stream) mode[i] = kVecInline;
   }
 
+  // Single token: an input whose basis, activations and maps all suit the fused kernel (gsi_fused.hip) is
+  // processed, with its maps, by that kernel alone.
+  enum { kFusedMode = 3, kFusedDone = 4 };
+  const std::vector<int> mode_separate = mode;  // what the separate kernels would do with each input
+  std::vector<char> map_fused(n_maps, 0);
+  if (B == 1) {
+    for (int i = 0; i < n_inputs; ++i) {
+      const gsi_input_desc& in = inputs[i];
+      if (!gsi::fused_input_ok(in.d, in.k, in.udtype, in.U, in.X, in.xdtype, in.C, in.R,
+                               (in.flags & GSI_INPUT_SLOW_PATH_WX) != 0))
+        continue;
+      bool ok = true;
+      int readers = 0;
+      for (int j = 0; j < n_maps && ok; ++j) {
+        if (maps[j].input_id != i) continue;
+        ++readers;
+        ok = maps[j].wdtype == in.udtype && !(maps[j].flags & GSI_MAP_IMAGE_FP8) &&
+             gsi::fused_map_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M);
+      }
+      if (ok && readers <= gsi::kFusedMaxMap) mode[i] = kFusedMode;
+    }
+  }
+
   // Schedule in waves: an input is ready when its producer map has been enqueued, a map when its
   // input has.  Ready inputs (maps) of one dtype that take the same kernels share a launch.
   std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0), img_done(n_maps, 0);
@@ -769,6 +812,72 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     std::vector<int> ready;
     for (int i = 0; i < n_inputs; ++i)
       if (!in_done[i] && (inputs[i].src_map < 0 || map_done[inputs[i].src_map])) ready.push_back(i);
+    // fused chunks: ready inputs of one dtype and rank are packed, with their maps, into chunks as long as a
+    // chunk fits one launch's registers and scratch; up to kFusedMaxChunks chunks share a launch
+    if (B == 1) {
+      gsi::FusedArgs fa;
+      std::memset(&fa, 0, sizeof(fa));
+      fa.eps = eps;
+      int fa_dt = -1;
+      gsi::FusedChunk cur;
+      std::memset(&cur, 0, sizeof(cur));
+      int cur_dt = -1;
+      auto flush = [&]() -> hipError_t {
+        if (fa.n_chunks == 0) return hipSuccess;
+        hipError_t e = gsi::fused_launch(fa, fa_dt, s, ev_begin, ev_end);
+        fa.n_chunks = 0;
+        return e;
+      };
+      auto close_chunk = [&]() -> hipError_t {
+        if (cur.n_in == 0) return hipSuccess;
+        if (fa.n_chunks > 0 && fa_dt != cur_dt)
+          if (hipError_t e = flush(); e != hipSuccess) return e;
+        fa.c[fa.n_chunks++] = cur;
+        fa_dt = cur_dt;
+        std::memset(&cur, 0, sizeof(cur));
+        if (fa.n_chunks == gsi::kFusedMaxChunks) return flush();
+        return hipSuccess;
+      };
+      auto append = [&](gsi::FusedChunk& ch, int i) -> bool {  // input i and its maps; false when they do not fit
+        const gsi_input_desc& in = inputs[i];
+        if (ch.n_in == gsi::kFusedMaxIn) return false;
+        if (ch.n_in > 0 && ch.k != (int)in.k) return false;
+        ch.k = (int)in.k;
+        const int slot = ch.n_in++;
+        gsi::FusedIn& fi = ch.in[slot];
+        fi.U = in.U; fi.X = in.X; fi.C = in.C; fi.R = in.R; fi.rnorm = in.rnorm; fi.xnorm = in.xnorm;
+        fi.mask = in.mask; fi.fired_idx = in.fired_idx; fi.n_fired = in.n_fired;
+        fi.d = (int)in.d; fi.xdtype = in.xdtype; fi.wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) ? 1 : 0;
+        for (int j = 0; j < n_maps; ++j) {
+          if (maps[j].input_id != i) continue;
+          if (ch.n_mp == gsi::kFusedMaxMap) return false;
+          gsi::FusedMap& fm = ch.mp[ch.n_mp++];
+          fm.W = maps[j].W; fm.M = maps[j].M; fm.Y = maps[j].Y; fm.m = (int)maps[j].m; fm.in = slot;
+        }
+        return gsi::fused_plan(ch, in.udtype);
+      };
+      for (int i : ready) {
+        if (mode[i] != kFusedMode) continue;
+        gsi::FusedChunk trial = cur;
+        bool ok = (cur.n_in == 0 || cur_dt == inputs[i].udtype) && append(trial, i);
+        if (!ok) {
+          if (hipError_t e = close_chunk(); e != hipSuccess) return hip_fail(e, fn);
+          std::memset(&trial, 0, sizeof(trial));
+          ok = append(trial, i);
+        }
+        if (!ok) {  // too large for the fused kernel even alone: the separate kernels take it
+          mode[i] = mode_separate[i];
+          continue;
+        }
+        cur = trial;
+        cur_dt = inputs[i].udtype;
+        mode[i] = kFusedDone;
+        for (int j = 0; j < n_maps; ++j)
+          if (maps[j].input_id == i) { map_fused[j] = 1; img_done[j] = 1; }
+      }
+      if (hipError_t e = close_chunk(); e != hipSuccess) return hip_fail(e, fn);
+      if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+    }
     for (int md = kVecGate; md <= kVecInline; ++md) {
       for (int dt = 0; dt < 2; ++dt) {
         gsi::ProjBatch pb;
@@ -849,7 +958,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         for (int j : mready) {
           const gsi_map_desc& mp = maps[j];
           const gsi_input_desc& in = inputs[mp.input_id];
-          if (map_done[j] || mp.wdtype != dt || B == 0) continue;
+          if (map_done[j] || map_fused[j] || mp.wdtype != dt || B == 0) continue;
           if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
           if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
             continue;  // matrix cores below
@@ -880,7 +989,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     for (int j : mready) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
-      if (map_done[j] != 2 && B > 0) {
+      if (map_done[j] != 2 && !map_fused[j] && B > 0) {
         hipError_t e;
         const bool wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) != 0;
         if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))

@@ -20,11 +20,6 @@
 #include "gsi_device.h"
 #include "gsi_image.h"
 
-// Phase markers: empty in the library; a profiling build may define GSI_MARK(i) to record a timestamp.
-#ifndef GSI_MARK
-#define GSI_MARK(i)
-#endif
-
 namespace gsi {
 namespace {
 
@@ -62,7 +57,6 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
   const int rows = min(p.a_rows, d - row0);
   const typename T::storage* U = reinterpret_cast<const typename T::storage*>(p.U) + (int64_t)row0 * k + col0;
 
-  GSI_MARK(0);
   for (int t0 = 0; t0 < B; t0 += TB) {
     const int nt = min(TB, B - t0);
     // token rows of X read by this tile (clamped: loads are unconditional, surplus tokens are dropped below)
@@ -143,13 +137,11 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
         for (int e = 0; e < V; ++e) acc[tt][e] = fmaf(u[e], xv, acc[tt][e]);
       }
     }
-    GSI_MARK(1);
 #pragma unroll
     for (int tt = 0; tt < TB; ++tt)
 #pragma unroll
       for (int e = 0; e < V; ++e) red[(ro * TB + tt) * cbw + l * V + e] = acc[tt][e];
     __syncthreads();
-    GSI_MARK(2);
     for (int idx = threadIdx.x; idx < nt * cbw; idx += kBlock) {
       const int tt = idx / cbw, j = idx % cbw;
       const float* rp = red + tt * cbw + j;
@@ -166,7 +158,6 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
     }
     __syncthreads();
   }
-  GSI_MARK(3);
 }
 
 template <class T, int TB>
@@ -210,7 +201,6 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, cons
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const typename T::storage* U = reinterpret_cast<const typename T::storage*>(p.U) + (int64_t)row0 * k + cc * V;
 
-  GSI_MARK(4);
   // the slab of U goes in flight first (row index clamped: loads are unconditional) ...
   float upf[PF][V];
 #pragma unroll
@@ -232,9 +222,7 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, cons
       cs[tt][j] = s;
       if (slab == 0) p.C[(int64_t)(t0 + tt) * k + j] = s;
     }
-    GSI_MARK(5);
     __syncthreads();
-    GSI_MARK(6);
     float c[TB][V];
 #pragma unroll
     for (int tt = 0; tt < TB; ++tt)
@@ -279,7 +267,6 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, cons
       for (int q = 0; q < PF; ++q)
         if (st0 + q < steps) row_step(u[q], xv[q], st0 + q);
     }
-    GSI_MARK(7);
 #pragma unroll
     for (int tt = 0; tt < TB; ++tt) {
       const float sr = group_sum<kWave>(ar[tt]);
@@ -302,7 +289,6 @@ __global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, cons
     }
     __syncthreads();
   }
-  GSI_MARK(8);
 }
 
 // |r_t|, |x_t| (and the gate): one workgroup per input; each wave takes tokens w, w + 4, ... of a

@@ -15,60 +15,16 @@
 // The dense baseline runs the same code with every group "fired", x in place of r and a plain store.
 #include <hip/hip_ext.h>
 
-#include <cstdlib>
-
 #include "gsi_decode.h"
 #include "gsi_device.h"
-
-// Phase markers: empty in the library; a profiling build may define GSI_MARK(i) to record a timestamp.
-#ifndef GSI_MARK
-#define GSI_MARK(i)
-#endif
+#include "gsi_wstream.h"
 
 namespace gsi {
 namespace {
 
-#ifndef GSI_SBLOCK
-#define GSI_SBLOCK 512
-#endif
-constexpr int kBlock = GSI_SBLOCK;  // waves of a workgroup share one staged activation vector
+constexpr int kBlock = 512;  // waves of a workgroup share one staged activation vector
 constexpr int kWaves = kBlock / kWave;
-#ifndef GSI_KLU
-#define GSI_KLU 8
-#endif
-constexpr int kLU = GSI_KLU;  // loads per lane in a long unit
-
-template <class T>
-struct Raw {  // 16 bytes as loaded; widened to fp32 when consumed
-  uint4 v;
-  __device__ __forceinline__ void load(const typename T::storage* p) { v = *reinterpret_cast<const uint4*>(p); }
-  __device__ __forceinline__ void widen(float (&f)[T::kVec]) const;
-};
-template <>
-__device__ __forceinline__ void Raw<BF16>::widen(float (&f)[8]) const {
-  f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
-  f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
-}
-template <>
-__device__ __forceinline__ void Raw<F32>::widen(float (&f)[4]) const {
-  f[0] = __uint_as_float(v.x); f[1] = __uint_as_float(v.y); f[2] = __uint_as_float(v.z); f[3] = __uint_as_float(v.w);
-}
-
-template <int V>
-__device__ __forceinline__ void lds_vec(const float* p, float (&f)[V]) {
-#pragma unroll
-  for (int q = 0; q < V / 4; ++q) {
-    const float4 x = reinterpret_cast<const float4*>(p)[q];
-    f[4 * q + 0] = x.x; f[4 * q + 1] = x.y; f[4 * q + 2] = x.z; f[4 * q + 3] = x.w;
-  }
-}
-
-template <int V>
-__device__ __forceinline__ float dotv(const float (&a)[V], const float (&b)[V], float acc) {
-#pragma unroll
-  for (int e = 0; e < V; ++e) acc = fmaf(a[e], b[e], acc);
-  return acc;
-}
+constexpr int kWgsPerCu = 2;  // persistent grid: workgroups per CU
 
 template <class T, bool DENSE, bool TAIL>
 __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
@@ -81,7 +37,6 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   const int gw = blockIdx.x * kWaves + wave;  // this wave's index in the grid
   const int GW = gridDim.x * kWaves;
   const int ng = lb.ng, n = lb.n;
-  GSI_MARK(0);
 
   // ---- 1. gates: one wave per group in every workgroup (identical arithmetic in every workgroup, hence
   //         the same decision across the grid without communication) -----------------------------------
@@ -122,7 +77,6 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
     }
     __syncthreads();
   }
-  GSI_MARK(1);
   unsigned fired_mask = 0;
   if constexpr (DENSE) {
     fired_mask = (1u << ng) - 1u;
@@ -138,8 +92,6 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
     if (!((fired_mask >> gi) & 1u)) continue;  // uniform across the grid
     const LinGroup& g = lb.g[gi];
     const int d = g.d;
-    const int chunks = d / V;
-    const int nseg = (chunks + kWave * kLU - 1) / (kWave * kLU);  // units per row
 
     // stage the activation vector (readers of the previous group's vector are past the barrier)
     if (staged) __syncthreads();
@@ -168,114 +120,11 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
       const LinTask& t = lb.t[ti];
       if (t.group != gi) continue;  // uniform
       const int m = t.m;
-      const S* W = reinterpret_cast<const S*>(t.W);
-      if constexpr (!TAIL) {
-        // Software-pipelined: units of kLU loads per lane, two register buffers; the loads of the next
-        // unit are issued before the current one is consumed.  The loop body is straight-line code
-        // with unconditional loads and no stores (results are parked in lane (row index mod 64) of a
-        // register and written once per 64 rows), so a wave always has a unit in flight.
-        const int nrows = first < m ? (m - first + GW - 1) / GW : 0;
-        const int64_t seg_step = (int64_t)kWave * kLU * V;                       // elements to the next unit of a row
-        const int64_t row_step = (int64_t)GW * d - (int64_t)(nseg - 1) * seg_step;  // last unit of a row -> next row
-        for (int j0 = 0; j0 < nrows; j0 += kWave) {
-          const int cnt = min(kWave, nrows - j0);
-          const int nu = cnt * nseg;
-          const S* p0 = W + (int64_t)(first + (int64_t)j0 * GW) * d + (int64_t)lane * V;
-          float res = 0.f, acc = 0.f;
-          Raw<T> A[kLU], Bb[kLU];
-          auto issue = [&](Raw<T> (&buf)[kLU], const S* ptr) {
-            __builtin_amdgcn_sched_barrier(0);  // keep the loads here: ahead of the arithmetic that follows
-#pragma unroll
-            for (int q = 0; q < kLU; ++q) buf[q].load(ptr + (int64_t)q * kWave * V);
-            __builtin_amdgcn_sched_barrier(0);
-          };
-          auto consume = [&](const Raw<T> (&buf)[kLU], int jj, int sg) {
-            const float* xp = xs + (sg * kWave * kLU + lane) * V;
-#pragma unroll
-            for (int q = 0; q < kLU; ++q) {
-              float w[V], xv[V];
-              buf[q].widen(w);
-              lds_vec<V>(xp + q * kWave * V, xv);
-              acc = dotv<V>(w, xv, acc);
-            }
-            const bool last = sg == nseg - 1;
-            const float sum = group_sum<kWave>(acc);
-            res = (last && lane == jj) ? sum : res;
-            acc = last ? 0.f : acc;
-          };
-          // unit u: row index jj = u / nseg, segment sg = u % nseg; pointers advance incrementally
-          const S* pa = p0;
-          int jja = 0, sga = 0;
-          issue(A, pa);
-          int u = 0;
-          while (u + 2 < nu) {
-            const S* pb = pa + (sga == nseg - 1 ? row_step : seg_step);
-            const int jjb = sga == nseg - 1 ? jja + 1 : jja, sgb = sga == nseg - 1 ? 0 : sga + 1;
-            issue(Bb, pb);
-            consume(A, jja, sga);
-            pa = pb + (sgb == nseg - 1 ? row_step : seg_step);
-            jja = sgb == nseg - 1 ? jjb + 1 : jjb;
-            sga = sgb == nseg - 1 ? 0 : sgb + 1;
-            issue(A, pa);
-            consume(Bb, jjb, sgb);
-            u += 2;
-          }
-          if (u + 1 < nu) {
-            const S* pb = pa + (sga == nseg - 1 ? row_step : seg_step);
-            const int jjb = sga == nseg - 1 ? jja + 1 : jja, sgb = sga == nseg - 1 ? 0 : sga + 1;
-            issue(Bb, pb);
-            consume(A, jja, sga);
-            consume(Bb, jjb, sgb);
-          } else {
-            consume(A, jja, sga);
-          }
-          if (lane < cnt) {  // lane j holds the sum of this wave's row j0 + j
-            float* yp = t.Y + first + (int64_t)(j0 + lane) * GW;
-            float old = 0.f;
-            if (!whole) old = *yp;  // image term written by the preceding launch (uniform branch)
-            *yp = old + res;
-          }
-        }
-      } else {
-        for (int row = first; row < m; row += GW) {
-          float acc = 0.f;
-          float yold = 0.f;
-          if (!whole) yold = t.Y[row];  // the image term written by the preceding launch
-          for (int sg = 0; sg < nseg; ++sg) {
-            Raw<T> buf[kLU];
-            const int cb = sg * kWave * kLU + lane;
-#pragma unroll
-            for (int q = 0; q < kLU; ++q) {
-              int c = cb + q * kWave;
-              c = c < chunks ? c : chunks - 1;
-              buf[q].load(W + (int64_t)row * d + (int64_t)c * V);
-            }
-#pragma unroll
-            for (int q = 0; q < kLU; ++q) {
-              const int c = cb + q * kWave;
-              float w[V], xv[V];
-              buf[q].widen(w);
-              lds_vec<V>(xs + (c < chunks ? c : chunks - 1) * V, xv);
-              const float part = dotv<V>(w, xv, 0.f);
-              acc += c < chunks ? part : 0.f;
-            }
-          }
-          acc = group_sum<kWave>(acc);
-          if (lane == 0) t.Y[row] = yold + acc;
-        }
-      }
+      stream_map_rows<T, TAIL, false>(reinterpret_cast<const S*>(t.W), t.Y, m, d, xs, whole, first, GW, lane);
       // continue the deal: the next map starts with the wave after the one that took this map's last row
       first = (first - m % GW + GW) % GW;
     }
   }
-  GSI_MARK(2);
-}
-
-int env_int(const char* name, int dflt) {
-  const char* v = std::getenv(name);
-  if (!v || !*v) return dflt;
-  const int x = std::atoi(v);
-  return x > 0 ? x : dflt;
 }
 
 int num_cus() {
@@ -322,14 +171,13 @@ size_t stream_smem_bytes(const LinBatch& lb) {
 hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   // persistent grid: a few workgroups per CU, never more waves than rows
-  static const int per_cu = env_int("GSI_LIN_WGS_PER_CU", 2);
   int64_t rows = 0;
   bool tail = false;
   for (int i = 0; i < lb.n; ++i) {
     rows += lb.t[i].m;
     if ((lb.g[lb.t[i].group].d / V) % (kWave * kLU)) tail = true;
   }
-  int64_t grid = (int64_t)per_cu * num_cus();
+  int64_t grid = (int64_t)kWgsPerCu * num_cus();
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
   const size_t smem = stream_smem_bytes(lb);
