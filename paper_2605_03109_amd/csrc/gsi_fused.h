@@ -12,7 +12,8 @@ constexpr int kFusedMaxIn = 4;          // inputs of a chunk
 constexpr int kFusedMaxMap = 8;         // maps of a chunk
 constexpr int kFusedMaxChunks = 4;      // chunks of a launch (the kernel arguments hold them by value)
 constexpr int kFusedMaxCols = 2048;     // projection coefficients of a chunk (sum of k over its inputs)
-constexpr int kFusedMaxItems = 4096;    // basis items of a chunk
+constexpr int kFusedGroup = 8;          // items (= waves) whose partial results one workgroup combines
+constexpr int kFusedMaxGroups = 512;    // basis groups of a chunk (one per workgroup at most)
 constexpr int kFusedMaxD = 16384;       // floats of LDS the staged vector of the slow path may take
 
 struct FusedIn {
@@ -26,7 +27,8 @@ struct FusedIn {
   int32_t* fired_idx;
   int32_t* n_fired;
   int d, xdtype, wx;
-  int item0, n_items;  // basis items of this input: [item0, item0 + n_items) of the chunk
+  int group0, n_groups;  // basis groups of this input: [group0, group0 + n_groups) of the chunk
+  int pad;
 };
 
 struct FusedMap {
@@ -42,19 +44,20 @@ struct FusedChunk {
   FusedMap mp[kFusedMaxMap];
   int n_in, n_mp;
   int k, lsh;       // rank (shared by the inputs of a chunk), log2 of the lanes that hold one row
-  int n_items;      // basis items
+  int n_groups;     // basis groups (kFusedGroup items each); workgroup g < n_groups holds group g
   int n_units;      // image units
-  int u_waves;      // waves of a workgroup that hold basis items (the rest hold image units)
-  int wg_units;     // image units per workgroup
   int wave_units;   // image units per image wave (<= kFusedLoads)
-  int wg_cols;      // coefficients reduced by one workgroup
+  int wg_cols;      // coefficients reduced by one workgroup (a multiple of 4)
 };
 
 struct FusedArgs {
   FusedChunk c[kFusedMaxChunks];
   int n_chunks;
   float eps;
+  int pad[2];
 };
+static_assert(sizeof(FusedArgs) % 16 == 0, "the kernel copies its arguments in 16-byte pieces");
+static_assert(sizeof(FusedArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
 // Can this input / map take the fused kernel at all (dtype, rank, alignment)?
 bool fused_input_ok(int64_t d, int64_t k, int udtype, const void* U, const void* X, int xdtype, const float* C,

@@ -2,17 +2,20 @@
 // inputs and the linear maps that read them, in ONE launch, with the basis read once (Section 7.3 of the paper
 // asks for the gate fused with the product and the basis kept on chip).
 //
-// A grid of one 1024-thread workgroup per CU, all co-resident.  Per chunk:
-//   loads     every wave requests all of its operands at once and keeps them in registers: a "basis wave" holds
-//             one item of a basis (16 loads of 16 bytes per lane = 16 * rpw consecutive rows of U, rpw = rows
-//             per 64-lane load) and the matching x; an "image wave" holds up to 16 loads of image rows.  Image
-//             waves never read memory again before they consume these registers, so their loads stay in
-//             flight across the exchanges below (loads return in order within a wave).
-//   phase 1   basis waves: partial c of their item (Alg. 1 line 1), published as (value, tag) words;
-//   reduce    each workgroup sums a few columns of c over all items in a fixed order and publishes them; every
+// A grid of one 1024-thread workgroup (16 waves) per CU, all co-resident.  Per chunk:
+//   loads     every wave requests all of its operands at once and keeps them in registers.  Workgroup g of the
+//             first n_groups workgroups is a "basis workgroup": its waves 0-7 each hold one item of basis group g
+//             (8 loads of 16 bytes per lane = 8 * rpw consecutive rows of U, rpw = rows per 64-lane load, and the
+//             matching x), its waves 8-15 hold image rows (up to 8 loads each).  The other workgroups hold image
+//             rows in waves 1-15; their wave 0 holds nothing and serves the exchanges.  Image waves never read
+//             memory again before they consume their registers, so their loads stay in flight across the
+//             exchanges below (loads return in order within a wave);
+//   phase 1   basis waves: partial c of their item (Alg. 1 line 1); the eight partials of the group are added in
+//             LDS in wave order and published as (value, tag) words;
+//   reduce    each workgroup sums a few columns of c over all groups in a fixed order and publishes them; every
 //             workgroup then fetches the finished c into LDS;
-//   phase 2   basis waves: r = x - U c on their rows out of the SAME registers (line 2), R written, the
-//             item's |r|^2, |x|^2 published; image waves: y = M c of their rows (line 5);
+//   phase 2   basis waves: r = x - U c on their rows out of the SAME registers (line 2), R written, the group's
+//             |r|^2, |x|^2 added in LDS and published; image waves: y = M c of their rows (line 5);
 //   gate      every workgroup sums the published norms in a fixed order and applies Eq. (gate) -- identical
 //             arithmetic everywhere, so the decision is uniform across the grid; workgroup 0 writes
 //             rnorm / xnorm / mask / fired_idx / n_fired.  Nothing fired: the chunk ends here;
@@ -26,8 +29,8 @@
 // bounded (one second): on expiry the wave gives up, the launch still ends, a counter records it, and the
 // outputs of that launch are not valid.  Launches that overlap in time on one device are not supported.
 //
-// All sums have a fixed order that depends on the shapes only (never on how items fall on workgroups), so a
-// result does not depend on what else shares the launch.
+// All sums have a fixed order that depends on the shapes only (never on what else shares the launch): items
+// and groups are cut from each input by its own row count.
 #include <hip/hip_ext.h>
 
 #include <mutex>
@@ -43,9 +46,9 @@ using u64 = unsigned long long;
 
 constexpr size_t kStateBytes = 256;
 constexpr size_t kCSlotBytes = (size_t)kFusedMaxCols * 8;
-constexpr size_t kNSlotBytes = (size_t)kFusedMaxItems * 2 * 8;
-constexpr size_t kPcBytes = (size_t)8 << 20;        // partial projections: items * k words
-constexpr size_t kStaticWsBytes = (size_t)8 << 20;  // general-purpose part (the entry point without a workspace)
+constexpr size_t kNSlotBytes = (size_t)kFusedMaxGroups * 2 * 8;
+constexpr size_t kPcBytes = (size_t)kFusedMaxGroups * 512 * 8;  // partial projections: groups * k words
+constexpr size_t kStaticWsBytes = (size_t)8 << 20;              // general-purpose part (the entry point without a workspace)
 constexpr size_t kOffC = kStateBytes;
 constexpr size_t kOffN = kOffC + kCSlotBytes;
 constexpr size_t kOffP = kOffN + kNSlotBytes;
@@ -72,139 +75,178 @@ __device__ __forceinline__ unsigned ld_u32(const unsigned* p) { return __hip_ato
 __device__ __forceinline__ void st_u32(unsigned* p, unsigned v) { __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 __device__ __forceinline__ unsigned add_u32(unsigned* p, unsigned v) { return __hip_atomic_fetch_add(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
 
-// Words base[q * stride], q < cnt (<= N), of the current tag: all requested at once, then re-read until valid.
-// out[q] = 0 for q >= cnt.  The wait is bounded; once any wave of the workgroup has given up, nobody waits.
-template <int N>
-__device__ __forceinline__ void poll_strided(const u64* base, int64_t stride, int cnt, unsigned tag, float (&out)[N],
-                                             volatile unsigned* abort_flag) {
-  u64 v[N];
+// A value that is the same in every lane of the wave, moved to a scalar register.
+__device__ __forceinline__ int uni(int v) { return __builtin_amdgcn_readfirstlane(v); }
+template <class P>
+__device__ __forceinline__ P* uni(P* p) {
+  const unsigned long long v = reinterpret_cast<unsigned long long>(p);
+  const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
+  return reinterpret_cast<P*>(((unsigned long long)hi << 32) | lo);
+}
+
+// Words base[q * qstride + c], q < nq (<= NQ), c < NC, of the current tag: all requested at once, then re-read
+// until valid.  out = 0 for q >= nq.  The wait is bounded; once any wave of the workgroup has given up, nobody waits.
+template <int NQ, int NC>
+__device__ __forceinline__ void poll_words(const u64* base, int64_t qstride, int nq, unsigned tag, float (&out)[NQ][NC],
+                                           volatile unsigned* abort_flag) {
+  u64 v[NQ][NC];
 #pragma unroll
-  for (int q = 0; q < N; ++q) v[q] = q < cnt ? ld64(base + q * stride) : ((u64)tag << 32);
+  for (int q = 0; q < NQ; ++q)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) v[q][c] = q < nq ? ld64(base + q * qstride + c) : ((u64)tag << 32);
   bool pending = false;
 #pragma unroll
-  for (int q = 0; q < N; ++q) pending |= (unsigned)(v[q] >> 32) != tag;
+  for (int q = 0; q < NQ; ++q)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) pending |= (unsigned)(v[q][c] >> 32) != tag;
   if (pending) {
     const long long t0 = wall_clock64();
     while (pending && !*abort_flag) {
       pending = false;
 #pragma unroll
-      for (int q = 0; q < N; ++q)
-        if ((unsigned)(v[q] >> 32) != tag) {
-          v[q] = ld64(base + q * stride);
-          pending |= (unsigned)(v[q] >> 32) != tag;
-        }
+      for (int q = 0; q < NQ; ++q)
+#pragma unroll
+        for (int c = 0; c < NC; ++c)
+          if ((unsigned)(v[q][c] >> 32) != tag) {
+            v[q][c] = ld64(base + q * qstride + c);
+            pending |= (unsigned)(v[q][c] >> 32) != tag;
+          }
       if (pending && wall_clock64() - t0 > kSpinTicks) *abort_flag = 1u;
     }
   }
 #pragma unroll
-  for (int q = 0; q < N; ++q) out[q] = __uint_as_float((unsigned)v[q]);
+  for (int q = 0; q < NQ; ++q)
+#pragma unroll
+    for (int c = 0; c < NC; ++c) out[q][c] = __uint_as_float((unsigned)v[q][c]);
 }
 
 template <class T>
 __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, unsigned char* __restrict__ sc) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
+  constexpr int GI = kFusedGroup;
   extern __shared__ __align__(16) float smem[];
-  float* cs = smem;                  // finished coefficients of the chunk's inputs, [n_in][k]
-  float* xsave = smem + kFusedMaxCols;               // x of the rows a basis wave holds, [wave][64]
-  float* xs = smem + kFusedMaxCols + kFusedBlock;    // the staged vector of the slow path
+  float* cs = smem;                                // finished coefficients of the chunk's inputs, [n_in][k]
+  float* xsave = smem + kFusedMaxCols;             // x of the rows a basis wave holds, [wave][64]
+  float* red = smem + kFusedMaxCols + kFusedBlock; // partial c of the group's items, [GI][k]; later the staged
+  float* xs = red;                                 // vector of the slow path
+  __shared__ __align__(16) FusedArgs s_a;          // the arguments, fetched once by all lanes together
   __shared__ unsigned s_epoch, s_abort, s_done, s_fired[kFusedMaxIn];
+  __shared__ float s_nred[GI][2];
 
   FState* st = reinterpret_cast<FState*>(sc);
   u64* cslot = reinterpret_cast<u64*>(sc + kOffC);
   u64* nslot = reinterpret_cast<u64*>(sc + kOffN);
   u64* pc = reinterpret_cast<u64*>(sc + kOffP);
-  const int lane = threadIdx.x % kWave;
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const int b = blockIdx.x, G = gridDim.x;
+  {
+    // (descriptor fields are needed in long dependent chains: one parallel fetch into LDS instead of a scalar
+    // load, and its memory latency, per link of the chain)
+    const uint4* src = reinterpret_cast<const uint4*>(&a);
+    uint4* dst = reinterpret_cast<uint4*>(&s_a);
+    for (int i = threadIdx.x; i < (int)(sizeof(FusedArgs) / 16); i += kFusedBlock) dst[i] = src[i];
+  }
   if (threadIdx.x == 0) {
     s_epoch = ld_u32(&st->epoch);
     s_abort = 0;
     s_done = 0;
   }
   __syncthreads();
-  const unsigned epoch0 = s_epoch;
+  const unsigned epoch0 = (unsigned)uni((int)s_epoch);
+  const int n_chunks = uni(s_a.n_chunks);
+  const float eps = __int_as_float(uni(__float_as_int(s_a.eps)));
   int fired_chunks = 0;
 
-  for (int ci = 0; ci < a.n_chunks; ++ci) {
-    const FusedChunk& ch = a.c[ci];
+  for (int ci = 0; ci < n_chunks; ++ci) {
+    const FusedChunk& ch = s_a.c[ci];
     const unsigned tag = epoch0 + (unsigned)ci + 1u;
-    const int k = ch.k, lsh = ch.lsh, lpr = 1 << lsh, rpw = kWave >> lsh;
+    // (the lane and thread numbers pass through an empty asm statement so that nothing derived from them is
+    // computed once before the loop and then kept, or spilled, across this long body)
+    int lane = __lane_id();
+    asm volatile("" : "+v"(lane));
+    const int tid = wave * kWave + lane;
+    const int k = __builtin_amdgcn_readfirstlane(ch.k), lsh = __builtin_amdgcn_readfirstlane(ch.lsh);
+    const int n_in = __builtin_amdgcn_readfirstlane(ch.n_in), n_mp = __builtin_amdgcn_readfirstlane(ch.n_mp);
+    const int NG = __builtin_amdgcn_readfirstlane(ch.n_groups);
+    const int lpr = 1 << lsh, rpw = kWave >> lsh;
     const int kshift = __builtin_ctz(k);
     const int cc = lane & (lpr - 1), rg = lane >> lsh;  // 16-byte chunk of the row, row of the load
-    const bool uwave = wave < ch.u_waves;
+    const bool bwg = b < NG;                            // basis workgroup: holds basis group b
+    const bool bwave = bwg && wave < GI;                // holds an item of the group
+    const bool swave = bwg ? wave < GI : wave == 0;     // may read memory during the exchanges
+    const bool iwave = bwg ? wave >= GI : wave >= 1;    // holds image rows
 
     // ---- loads: everything this wave needs from the basis / the images, requested at once ---------------
     // Per load q (uniform over the wave): the matrix, its first row of this load and its row count.  A load
     // without work reads the first bytes of the exchange state instead (one cache line, no memory traffic).
-    int it = -1, ii = 0;                   // basis wave: its item and the item's input
-    const S* base[kFusedLoads];
-    int rowq[kFusedLoads], lim[kFusedLoads];
-    float* yq[kFusedLoads];                // image wave: output of the load's rows
-    int inq[kFusedLoads];                  // ... and the input its map reads
-#pragma unroll
-    for (int q = 0; q < kFusedLoads; ++q) {
-      base[q] = nullptr;
-      rowq[q] = 0;
-      lim[q] = 0;
-      yq[q] = nullptr;
-      inq[q] = 0;
-    }
-    if (uwave) {
-      const int cand = wave * G + b;
-      if (cand < ch.n_items) {
-        it = cand;
-#pragma unroll
-        for (int i = 1; i < kFusedMaxIn; ++i)
-          if (i < ch.n_in && it >= ch.in[i].item0) ii = i;
-        const FusedIn& in = ch.in[ii];
-        const int row0 = (it - in.item0) * (kFusedLoads * rpw);
-#pragma unroll
-        for (int q = 0; q < kFusedLoads; ++q) {
-          base[q] = reinterpret_cast<const S*>(in.U);
-          rowq[q] = row0 + q * rpw;
-          lim[q] = in.d;
-        }
-      }
-    } else {
-      const int v = wave - ch.u_waves;
-      const int wb = b * ch.wg_units;
-      const int we = min(wb + ch.wg_units, ch.n_units);
-      const int ub = min(wb + v * ch.wave_units, we);
-      const int ue = min(ub + ch.wave_units, we);
-#pragma unroll
-      for (int q = 0; q < kFusedLoads; ++q) {
-        const int u = ub + q;
-        int jj = 0;
-#pragma unroll
-        for (int j = 1; j < kFusedMaxMap; ++j)
-          if (j < ch.n_mp && u >= ch.mp[j].unit0) jj = j;
-        const FusedMap& mp = ch.mp[jj];
-        if (u < ue) {
-          base[q] = reinterpret_cast<const S*>(mp.M);
-          rowq[q] = (u - mp.unit0) * rpw;
-          lim[q] = mp.m;
-          yq[q] = mp.Y;
-          inq[q] = mp.in;
-        }
-      }
-    }
+    int ii = 0, row0 = 0, dlim = 0;        // basis wave: the group's input, the item's first row, the input's rows
+    int ub = 0, ue = 0;                    // image wave: its units [ub, ue)
     uint4 raw[kFusedLoads];
     float xv[kFusedLoads];
+    // image wave, load q: the map of unit ub + q, its first row of the load and its row count (uniform over the
+    // wave; looked up again in phase 2 rather than kept in registers across the exchanges)
+    auto image_load = [&](int q, const S*& M, float*& Y, int& row, int& m, int& in) {
+      const int u = ub + q;
+      int jj = 0;
+#pragma unroll
+      for (int j = 1; j < kFusedMaxMap; ++j)
+        if (j < n_mp && u >= ch.mp[j].unit0) jj = j;
+      const FusedMap& mp = ch.mp[uni(jj)];
+      M = uni(reinterpret_cast<const S*>(mp.M));
+      Y = uni(mp.Y);
+      row = uni((u - mp.unit0) * rpw);
+      m = uni(mp.m);
+      in = uni(mp.in);
+    };
+    // the address of every load first (a load without work reads the first bytes of the exchange state: one
+    // cache line, no memory traffic), then all loads in one run, unconditionally
+    const S* addr[kFusedLoads];
+    const float* xaddr[kFusedLoads];
 #pragma unroll
     for (int q = 0; q < kFusedLoads; ++q) {
-      const int r = min(rowq[q] + rg, lim[q] - 1);  // clamped: the loads are unconditional
-      const S* p = base[q] ? base[q] + (int64_t)r * k + cc * V : reinterpret_cast<const S*>(sc);
-      raw[q] = *reinterpret_cast<const uint4*>(p);
+      addr[q] = reinterpret_cast<const S*>(sc);
+      xaddr[q] = reinterpret_cast<const float*>(sc);
     }
-    if (it >= 0) {
-      const float* X = reinterpret_cast<const float*>(ch.in[ii].X);
+    if (bwave) {
 #pragma unroll
-      for (int q = 0; q < kFusedLoads; ++q) xv[q] = X[min(rowq[q] + rg, lim[q] - 1)];
+      for (int i = 1; i < kFusedMaxIn; ++i)
+        if (i < n_in && b >= ch.in[i].group0) ii = i;
+      ii = uni(ii);
+      const FusedIn& in = ch.in[ii];
+      row0 = uni(((b - in.group0) * GI + wave) * (kFusedLoads * rpw));
+      dlim = uni(in.d);
+      const S* U = uni(reinterpret_cast<const S*>(in.U)) + cc * V;
+      const float* X = uni(reinterpret_cast<const float*>(in.X));
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) {
+        const int r = min(row0 + q * rpw + rg, dlim - 1);  // clamped
+        addr[q] = U + (int64_t)r * k;
+        xaddr[q] = X + r;
+      }
+    } else if (iwave) {
+      const int slot = bwg ? b * (kFusedWaves - GI) + (wave - GI) : NG * (kFusedWaves - GI) + (b - NG) * (kFusedWaves - 1) + (wave - 1);
+      ub = uni(min(slot * ch.wave_units, ch.n_units));
+      ue = uni(min(ub + ch.wave_units, ch.n_units));
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) {
+        if (ub + q < ue) {  // uniform over the wave
+          const S* M;
+          float* Y;
+          int row, m, in;
+          image_load(q, M, Y, row, m, in);
+          addr[q] = M + (int64_t)min(row + rg, m - 1) * k + cc * V;
+        }
+      }
     }
+#pragma unroll
+    for (int q = 0; q < kFusedLoads; ++q) raw[q] = *reinterpret_cast<const uint4*>(addr[q]);
+#pragma unroll
+    for (int q = 0; q < kFusedLoads; ++q) xv[q] = *xaddr[q];
 
-    // ---- phase 1: partial c of the item (fixed order: loads ascending, then the row groups of the wave) ----
-    if (it >= 0) {
+    // ---- phase 1: partial c of the item (fixed order: loads ascending, then the row groups of the wave),
+    //      then of the group (waves ascending)
+    if (bwave) {
       float acc[V];
 #pragma unroll
       for (int e = 0; e < V; ++e) acc[e] = 0.f;
@@ -212,7 +254,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
       for (int q = 0; q < kFusedLoads; ++q) {
         float w[V];
         T::widen(raw[q], w);
-        const float x = rowq[q] + rg < lim[q] ? xv[q] : 0.f;
+        const float x = row0 + q * rpw + rg < dlim ? xv[q] : 0.f;
 #pragma unroll
         for (int e = 0; e < V; ++e) acc[e] = fmaf(w[e], x, acc[e]);
       }
@@ -225,53 +267,60 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
         for (int q = 0; q < kFusedLoads; ++q) xsave[wave * kWave + q * rpw + rg] = xv[q];
       }
       if (rg == 0) {
-        u64* dst = pc + (int64_t)it * k + cc * V;
 #pragma unroll
-        for (int e = 0; e < V; ++e) st64(dst + e, pack(acc[e], tag));
+        for (int e = 0; e < V; ++e) red[wave * k + cc * V + e] = acc[e];
       }
     }
+    __syncthreads();
+    if (bwg && (int)tid < k) {
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < GI; ++w) s += red[w * k + tid];
+      st64(pc + (int64_t)b * k + tid, pack(s, tag));
+    }
 
-    if (uwave) {
-      // ---- reduce: this workgroup's columns of c, one wave per column, items in ascending order per lane ----
-      const int ncol = ch.n_in << kshift;
-      for (int col = wave; col < ch.wg_cols; col += ch.u_waves) {
-        const int cg = b * ch.wg_cols + col;
+    if (swave) {
+      // ---- reduce: this workgroup's columns of c, four neighbouring columns per wave, groups ascending per lane
+      const int ncol = n_in << kshift;
+      const int nquad = ch.wg_cols >> 2;
+      for (int qi = bwg ? wave : 0; qi < nquad; qi += bwg ? GI : 1) {
+        const int cg = b * ch.wg_cols + 4 * qi;
         if (cg < ncol) {
           const int i = cg >> kshift, j = cg & (k - 1);
           const FusedIn& in = ch.in[i];
-          const int P = in.n_items;
-          const u64* base = pc + (int64_t)in.item0 * k + j;
-          float s = 0.f;
-          for (int p0 = 0; p0 < P; p0 += kWave * 8) {
-            float v[8];
-            const int left = P - p0 - lane;
-            poll_strided<8>(base + (int64_t)(p0 + lane) * k, (int64_t)kWave * k, left > 0 ? (left + kWave - 1) / kWave : 0,
-                            tag, v, &s_abort);
+          const int P = in.n_groups;
+          float v[4][4];
+          const int left = P - lane;
+          poll_words<4, 4>(pc + ((int64_t)in.group0 + lane) * k + j, (int64_t)kWave * k, left > 0 ? (left + kWave - 1) / kWave : 0,
+                           tag, v, &s_abort);
+          float s[4];
 #pragma unroll
-            for (int q = 0; q < 8; ++q) s += v[q];
+          for (int c = 0; c < 4; ++c) {
+            s[c] = (v[0][c] + v[1][c]) + (v[2][c] + v[3][c]);
+            s[c] = group_sum<kWave>(s[c]);
           }
-          s = group_sum<kWave>(s);
-          if (lane == 0) {
-            st64(cslot + cg, pack(s, tag));
-            in.C[j] = s;
+          if (lane < 4) {
+            const float mine = lane == 0 ? s[0] : lane == 1 ? s[1] : lane == 2 ? s[2] : s[3];
+            st64(cslot + cg + lane, pack(mine, tag));
+            in.C[j + lane] = mine;
           }
         }
       }
       // ---- the finished c of every input of the chunk -> LDS
-      const int nth = ch.u_waves * kWave;
-      for (int s0 = wave * kWave + lane; s0 < ncol; s0 += nth * 4) {
-        float v[4];
+      const int nth = bwg ? GI * kWave : kWave;
+      for (int s0 = (bwg ? wave * kWave : 0) + lane; s0 < ncol; s0 += nth * 8) {
+        float v[8][1];
         const int left = ncol - s0;
-        poll_strided<4>(cslot + s0, nth, (left + nth - 1) / nth, tag, v, &s_abort);
+        poll_words<8, 1>(cslot + s0, nth, (left + nth - 1) / nth, tag, v, &s_abort);
 #pragma unroll
-        for (int q = 0; q < 4; ++q)
-          if (s0 + q * nth < ncol) cs[s0 + q * nth] = v[q];
+        for (int q = 0; q < 8; ++q)
+          if (s0 + q * nth < ncol) cs[s0 + q * nth] = v[q][0];
       }
     }
     __syncthreads();
 
     // ---- phase 2: residual rows (basis waves) and image rows (image waves) out of the registers ----------
-    if (it >= 0) {
+    if (bwave) {
       const FusedIn& in = ch.in[ii];
       float cv[V];
       lds_vec<V>(cs + (ii << kshift) + cc * V, cv);
@@ -284,8 +333,8 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
 #pragma unroll
         for (int e = 0; e < V; ++e) s = fmaf(w[e], cv[e], s);
         s = group_sum_rt(s, lpr);
-        const int r = rowq[q] + rg;
-        if (r < lim[q] && cc == 0) {
+        const int r = row0 + q * rpw + rg;
+        if (r < dlim && cc == 0) {
           const float x = xsave[wave * kWave + q * rpw + rg];
           const float res = x - s;
           st_f32(in.R + r, res);
@@ -296,47 +345,54 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
       ar = group_sum<kWave>(ar);
       ax = group_sum<kWave>(ax);
       if (lane == 0) {
-        st64(nslot + 2 * it, pack(ar, tag));
-        st64(nslot + 2 * it + 1, pack(ax, tag));
+        s_nred[wave][0] = ar;
+        s_nred[wave][1] = ax;
       }
-    } else if (!uwave) {
+    } else if (iwave) {
 #pragma unroll
       for (int q = 0; q < kFusedLoads; ++q) {
-        if (yq[q]) {  // uniform over the wave
+        if (ub + q < ue) {  // uniform over the wave
+          const S* M;
+          float* Y;
+          int row, m, in;
+          image_load(q, M, Y, row, m, in);
           float w[V], cv[V];
           T::widen(raw[q], w);
-          lds_vec<V>(cs + (inq[q] << kshift) + cc * V, cv);
+          lds_vec<V>(cs + (in << kshift) + cc * V, cv);
           float s = 0.f;
 #pragma unroll
           for (int e = 0; e < V; ++e) s = fmaf(w[e], cv[e], s);
           s = group_sum_rt(s, lpr);
-          const int r = rowq[q] + rg;
-          if (cc == 0 && r < lim[q]) st_f32(yq[q] + r, s);
+          const int r = row + rg;
+          if (cc == 0 && r < m) st_f32(Y + r, s);
         }
       }
     }
-
-    // ---- gate: one wave per input, the items' norms in ascending order per lane -----------------------------
-    if (uwave) {
-      for (int i = wave; i < ch.n_in; i += ch.u_waves) {
-        const FusedIn& in = ch.in[i];
-        const int P = in.n_items;
-        const u64* base = nslot + 2 * (int64_t)in.item0;
-        float sr = 0.f, sx = 0.f;
-        for (int p0 = 0; p0 < P; p0 += kWave * 4) {
-          float vr[4], vx[4];
-          const int left = P - p0 - lane;
-          const int cnt = left > 0 ? (left + kWave - 1) / kWave : 0;
-          poll_strided<4>(base + 2 * (int64_t)(p0 + lane), 2 * kWave, cnt, tag, vr, &s_abort);
-          poll_strided<4>(base + 2 * (int64_t)(p0 + lane) + 1, 2 * kWave, cnt, tag, vx, &s_abort);
+    __syncthreads();
+    if (bwg && tid == 0) {  // the group's |r|^2, |x|^2: waves ascending
+      float sr = 0.f, sx = 0.f;
 #pragma unroll
-          for (int q = 0; q < 4; ++q) {
-            sr += vr[q];
-            sx += vx[q];
-          }
-        }
+      for (int w = 0; w < GI; ++w) {
+        sr += s_nred[w][0];
+        sx += s_nred[w][1];
+      }
+      st64(nslot + 2 * b, pack(sr, tag));
+      st64(nslot + 2 * b + 1, pack(sx, tag));
+    }
+
+    // ---- gate: one wave per input, the groups' norms in ascending order per lane ----------------------------
+    if (swave) {
+      for (int i = bwg ? wave : 0; i < n_in; i += bwg ? GI : 1) {
+        const FusedIn& in = ch.in[i];
+        const int P = in.n_groups;
+        float v[4][2];
+        const int left = P - lane;
+        poll_words<4, 2>(nslot + 2 * ((int64_t)in.group0 + lane), 2 * kWave, left > 0 ? (left + kWave - 1) / kWave : 0, tag, v,
+                         &s_abort);
+        const float sr = (v[0][0] + v[1][0]) + (v[2][0] + v[3][0]);
+        const float sx = (v[0][1] + v[1][1]) + (v[2][1] + v[3][1]);
         const float rn = sqrtf(group_sum<kWave>(sr)), xn = sqrtf(group_sum<kWave>(sx));
-        const bool f = gate_fires(rn, xn, a.eps);
+        const bool f = gate_fires(rn, xn, eps);
         if (lane == 0) {
           s_fired[i] = f ? 1u : 0u;
           if (b == 0) {  // what the norm and gate kernels would write
@@ -353,7 +409,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
     }
     __syncthreads();
     unsigned fired_mask = 0;
-    for (int i = 0; i < ch.n_in; ++i) fired_mask |= s_fired[i] << i;
+    for (int i = 0; i < n_in; ++i) fired_mask |= s_fired[i] << i;
     if (s_abort) fired_mask = 0;  // a wait expired: this launch's results are void, end it quickly
     fired_mask = __builtin_amdgcn_readfirstlane(fired_mask);
     if (fired_mask == 0) continue;  // the common case: nothing fired, no byte of W is read
@@ -367,7 +423,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
       const unsigned old = atomicAdd(&s_done, 1u);
       if (old == (unsigned)(kFusedWaves * fired_chunks - 1)) add_u32(&st->wg_done, 1u);
     }
-    if (threadIdx.x == 0) {
+    if (tid == 0) {
       const unsigned want = (unsigned)G * (unsigned)fired_chunks;
       const long long t0 = wall_clock64();
       while (ld_u32(&st->wg_done) < want && !s_abort)
@@ -375,16 +431,18 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
     }
     __syncthreads();
     const int GW = G * kFusedWaves, gw = b * kFusedWaves + wave;
-    for (int gi = 0; gi < ch.n_in; ++gi) {
+    for (int gi = 0; gi < n_in; ++gi) {
       if (!((fired_mask >> gi) & 1u)) continue;  // uniform across the grid
       const FusedIn& in = ch.in[gi];
-      const int dd = in.d;
-      const bool whole = in.wx != 0;  // y = W x (Algorithm 1, line 7) replaces y; else W r is added to M c
+      const int dd = __builtin_amdgcn_readfirstlane(in.d);
+      const bool whole = __builtin_amdgcn_readfirstlane(in.wx) != 0;  // y = W x (Algorithm 1, line 7) replaces y; else W r is added to M c
+      int tid2 = wave * kWave + __lane_id();  // (recomputed: see the note on `lane` above)
+      asm volatile("" : "+v"(tid2));
       if (whole) {
         const float* X = reinterpret_cast<const float*>(in.X);
-        for (int idx = threadIdx.x; idx < dd; idx += kFusedBlock) xs[idx] = X[idx];
+        for (int idx = tid2; idx < dd; idx += kFusedBlock) xs[idx] = X[idx];
       } else {
-        for (int idx = threadIdx.x; idx < dd; idx += 4 * kFusedBlock) {
+        for (int idx = tid2; idx < dd; idx += 4 * kFusedBlock) {
           float v[4];
 #pragma unroll
           for (int q = 0; q < 4; ++q) v[q] = idx + q * kFusedBlock < dd ? ld_f32(in.R + idx + q * kFusedBlock) : 0.f;
@@ -396,12 +454,15 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
       __syncthreads();
       const bool tail = ((dd / V) % (kWave * kLU)) != 0;
       int first = gw;  // rows of the input's maps are dealt round-robin, map after map
-      for (int j = 0; j < ch.n_mp; ++j) {
+      for (int j = 0; j < n_mp; ++j) {
         const FusedMap& mp = ch.mp[j];
-        if (mp.in != gi) continue;  // uniform
-        if (tail) stream_map_rows<T, true, true>(reinterpret_cast<const S*>(mp.W), mp.Y, mp.m, dd, xs, whole, first, GW, lane);
-        else stream_map_rows<T, false, true>(reinterpret_cast<const S*>(mp.W), mp.Y, mp.m, dd, xs, whole, first, GW, lane);
-        first = (first - mp.m % GW + GW) % GW;
+        if (__builtin_amdgcn_readfirstlane(mp.in) != gi) continue;  // uniform
+        const int m = __builtin_amdgcn_readfirstlane(mp.m);
+        const S* W = reinterpret_cast<const S*>(mp.W);
+        float* Y = mp.Y;
+        if (tail) stream_map_rows<T, true, true>(W, Y, m, dd, xs, whole, first, GW, lane);
+        else stream_map_rows<T, false, true>(W, Y, m, dd, xs, whole, first, GW, lane);
+        first = (first - m % GW + GW) % GW;
       }
       __syncthreads();  // the staged vector is free again
     }
@@ -409,13 +470,13 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
 
   // ---- the last workgroup to finish leaves the exchange state ready for the next launch -----------------
   __syncthreads();
-  if (threadIdx.x == 0) {
+  if (wave == 0 && __lane_id() == 0) {
     if (s_abort) add_u32(&st->timeouts, 1u);
     const unsigned old = add_u32(&st->exit, 1u);
     if (old == (unsigned)G - 1u) {
       st_u32(&st->exit, 0u);
       st_u32(&st->wg_done, 0u);
-      st_u32(&st->epoch, epoch0 + (unsigned)a.n_chunks);
+      st_u32(&st->epoch, epoch0 + (unsigned)n_chunks);
     }
   }
 }
@@ -495,45 +556,32 @@ bool fused_plan(FusedChunk& ch, int dtype) {
   const int V = dtype == GSI_BF16 ? 8 : 4;
   const int k = ch.k;
   if (ch.n_in < 1 || ch.n_in > kFusedMaxIn || ch.n_mp < 0 || ch.n_mp > kFusedMaxMap) return false;
-  if (k % V || !pow2(k / V) || k / V > kWave) return false;
+  if (k % V || !pow2(k / V) || k / V > kWave || k / V < 8 || k > 512) return false;
   const int lpr = k / V, rpw = kWave / lpr;
   ch.lsh = __builtin_ctz(lpr);
   if ((int64_t)ch.n_in * k > kFusedMaxCols) return false;
-  int64_t items = 0, units = 0;
+  int64_t groups = 0, units = 0;
   for (int i = 0; i < ch.n_in; ++i) {
-    ch.in[i].item0 = (int)items;
-    ch.in[i].n_items = (int)ceil_div(ch.in[i].d, kFusedLoads * rpw);
-    items += ch.in[i].n_items;
+    ch.in[i].group0 = (int)groups;
+    ch.in[i].n_groups = (int)ceil_div(ch.in[i].d, (int64_t)kFusedGroup * kFusedLoads * rpw);
+    if (ch.in[i].n_groups > 4 * kWave) return false;  // a wave sums a column over at most four groups per lane
+    groups += ch.in[i].n_groups;
   }
   for (int j = 0; j < ch.n_mp; ++j) {
     ch.mp[j].unit0 = (int)units;
     ch.mp[j].n_units = (int)ceil_div(ch.mp[j].m, rpw);
     units += ch.mp[j].n_units;
   }
-  if (items > kFusedMaxItems || (size_t)items * k * 8 > kPcBytes || units > (1 << 28)) return false;
-  ch.n_items = (int)items;
+  if (groups > G || groups > kFusedMaxGroups || units > (1 << 28)) return false;
+  ch.n_groups = (int)groups;
   ch.n_units = (int)units;
-  ch.wg_cols = (int)ceil_div((int64_t)ch.n_in * k, G);
-  ch.wg_units = (int)ceil_div(units, G);
-  const int need_u = (int)std::max<int64_t>(1, ceil_div(items, G));
-  if (ch.n_mp == 0) {
-    if (need_u > kFusedWaves) return false;
-    ch.u_waves = kFusedWaves;
-    ch.wave_units = 0;
-    return true;
-  }
-  // basis waves: as many as the items need, and two or more when the image rows leave room (they also
-  // carry the exchanges); image waves: the rest
-  for (int uw = std::max(need_u, 2); uw >= need_u; --uw) {
-    if (uw >= kFusedWaves) continue;
-    const int per = (int)ceil_div(ch.wg_units, kFusedWaves - uw);
-    if (per <= kFusedLoads) {
-      ch.u_waves = uw;
-      ch.wave_units = per;
-      return true;
-    }
-  }
-  return false;
+  ch.wg_cols = 4 * (int)ceil_div((int64_t)ch.n_in * k, 4 * (int64_t)G);
+  if (ch.wg_cols / 4 > kFusedGroup) return false;
+  // image waves: eight in a basis workgroup, fifteen in the others
+  const int64_t slots = groups * (kFusedWaves - kFusedGroup) + (G - groups) * (kFusedWaves - 1);
+  ch.wave_units = slots > 0 ? (int)ceil_div(units, slots) : 0;
+  if (units > 0 && (slots < 1 || ch.wave_units > kFusedLoads)) return false;
+  return true;
 }
 
 hipError_t fused_launch(const FusedArgs& a, int dtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
@@ -545,7 +593,8 @@ hipError_t fused_launch(const FusedArgs& a, int dtype, hipStream_t s, hipEvent_t
   size_t maxd = 0;
   for (int c = 0; c < a.n_chunks; ++c)
     for (int j = 0; j < a.c[c].n_mp; ++j) maxd = std::max<size_t>(maxd, (size_t)a.c[c].in[a.c[c].mp[j].in].d);
-  const size_t smem = ((size_t)kFusedMaxCols + kFusedBlock + maxd) * sizeof(float);
+  // cs | xsave | the larger of the group's partials [8][k] and the staged vector of the slow path
+  const size_t smem = ((size_t)kFusedMaxCols + kFusedBlock + std::max<size_t>(maxd, (size_t)kFusedGroup * 512)) * sizeof(float);
   return dtype == GSI_BF16 ? launch_as<BF16>(a, (unsigned)G, smem, sc, s, e0, e1)
                            : launch_as<F32>(a, (unsigned)G, smem, sc, s, e0, e1);
 }
@@ -569,3 +618,4 @@ hipError_t static_workspace(void** ptr, size_t* bytes) {
 }
 
 }  // namespace gsi
+
