@@ -121,7 +121,7 @@ typedef struct gsi_input_desc {
   int32_t* fired_idx;
   int32_t* n_fired;
   int32_t src_map;    /* -1: X is an external buffer; j >= 0: X is the output Y of maps[j]      */
-  int32_t flags;      /* 0, or GSI_INPUT_SLOW_PATH_WX                                           */
+  int32_t flags;      /* 0, or a combination of GSI_INPUT_SLOW_PATH_WX, GSI_INPUT_FUSED_KERNEL   */
 } gsi_input_desc;
 
 /* gsi_input_desc.flags.  By default a fired token gets y = M c + W r (Eq. (exact)).  With
@@ -129,7 +129,18 @@ typedef struct gsi_input_desc {
  * Algorithm 1 (line 7) prints it: equal in exact arithmetic, but free of the stored image's rounding, so
  * that a fired token equals the dense product of gsi_dense_stack.  Tokens that did not fire are not
  * affected.  gsi_gated_linear has no x and always uses the default form. */
-enum { GSI_INPUT_SLOW_PATH_WX = 1 };
+enum { GSI_INPUT_SLOW_PATH_WX = 1, GSI_INPUT_FUSED_KERNEL = 2 };
+
+/* GSI_INPUT_FUSED_KERNEL (single-token calls, B == 1; ignored otherwise): this input and the maps that read
+ * it are processed by the fused kernel -- projection, residual, gate, image rows and, if the gate fires, the
+ * rows of W in ONE launch that reads the basis once and keeps it in registers between c = U^T x and r = x - U c
+ * (Section 7.3 "Kernel-level implementation": gate fused with the product, basis kept on chip).  Up to four
+ * such inputs of one rank share a chunk, up to four chunks a launch; workgroups exchange partial sums through
+ * a static device array of the library, so calls that use this flag must not overlap in time on one device
+ * (same stream, or ordered streams).  Shapes the kernel does not take (rank not 8..64 sixteen-byte pieces per
+ * row, k > 512, more than eight maps on an input, E4M3 images, activations not fp32, d above 16384 with maps)
+ * silently take the separate kernels.  Results equal the default path's up to the order of the fp32 sums.
+ * Every wait inside the kernel is bounded (one second); gsi_fused_timeouts() counts waits that expired. */
 
 typedef struct gsi_map_desc {
   const void* W;      /* [m,d] wdtype, d = inputs[input_id].d                                   */
@@ -183,6 +194,11 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
                                        int32_t n_inputs, int64_t B);
 size_t gsi_dense_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                                        int32_t n_inputs, int64_t B);
+
+/* Number of bounded waits inside fused-kernel launches (GSI_INPUT_FUSED_KERNEL) on the current device that
+ * expired since the library was loaded: 0 in normal operation; the outputs of a launch in which a wait expired
+ * are not valid.  count: HOST pointer.  Synchronises the device. */
+int gsi_fused_timeouts(uint32_t* count);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char* gsi_last_error(void);

@@ -39,12 +39,27 @@ def hipcc() -> str:
     return exe
 
 
+# Kernels that must not use scratch memory (register spills): a dispatch that needs scratch costs tens of
+# microseconds here, more than the whole single-token step.
+NO_SCRATCH = {"gsi_fused.hip": "fused_token"}
+
+
 def _compile(src: str) -> str:
     obj = os.path.join(OBJ, os.path.basename(src).replace(".hip", ".o"))
-    cmd = [hipcc(), *HIPCC_FLAGS, "-c", src, "-o", obj]
+    cmd = [hipcc(), *HIPCC_FLAGS, "-Rpass-analysis=kernel-resource-usage", "-c", src, "-o", obj]
     r = subprocess.run(cmd, capture_output=True, text=True)
     if r.returncode != 0:
         raise RuntimeError(f"hipcc failed for {src}:\n{r.stdout}\n{r.stderr}")
+    want = NO_SCRATCH.get(os.path.basename(src))
+    if want:
+        name = None
+        for line in r.stderr.splitlines():
+            if "Function Name:" in line:
+                name = line.split("Function Name:")[1].strip()
+            elif "ScratchSize [bytes/lane]:" in line and name and want in name:
+                n = int(line.split("ScratchSize [bytes/lane]:")[1].split()[0])
+                if n != 0:
+                    raise RuntimeError(f"{src}: kernel {name} spills registers ({n} bytes of scratch per lane)")
     return obj
 
 

@@ -66,6 +66,14 @@ extern "C" {
 
 const char* gsi_last_error(void) { return g_err; }
 
+int gsi_fused_timeouts(uint32_t* count) {
+  GSI_REQUIRE_PTR(count);
+  unsigned n = 0;
+  if (hipError_t e = gsi::fused_timeouts(&n); e != hipSuccess) return hip_fail(e, "gsi_fused_timeouts");
+  *count = n;
+  return GSI_OK;
+}
+
 int gsi_version(void) { return 100; }
 
 // ---- eligibility of the matrix-core paths (bf16 operands, K dimensions multiples of 64) -----------------
@@ -403,22 +411,6 @@ struct LinBatcher {
 };
 }  // namespace
 
-// One token, one input, no maps: the fused single-token kernel computes c, r and the norms in one launch (the same
-// arithmetic as inside a layer stack, so the stack equals the separate calls bit for bit).  No gate outputs.
-static bool fused_project_only(gsi::FusedArgs& fa, const void* U, const void* X, int64_t d, int64_t k, int udtype,
-                               int xdtype, float* C, float* R, float* rnorm, float* xnorm) {
-  if (!gsi::fused_input_ok(d, k, udtype, U, X, xdtype, C, R, false)) return false;
-  std::memset(&fa, 0, sizeof(fa));
-  gsi::FusedChunk& ch = fa.c[0];
-  ch.n_in = 1; ch.n_mp = 0; ch.k = (int)k;
-  gsi::FusedIn& in = ch.in[0];
-  in.U = U; in.X = X; in.C = C; in.R = R; in.rnorm = rnorm; in.xnorm = xnorm;
-  in.d = (int)d; in.xdtype = xdtype; in.wx = 0;
-  fa.n_chunks = 1;
-  fa.eps = 2.f;  // a residual ratio never reaches 2: nothing fires, no gate output is written (the pointers are null)
-  return gsi::fused_plan(ch, udtype);
-}
-
 int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype, float* C,
                 float* R, float* rnorm, float* xnorm, void* ws, size_t ws_bytes, void* stream) {
   if (int rc = check_project_args("gsi_project", U, X, d, k, B, udtype, xdtype, C, R, rnorm, xnorm)) return rc;
@@ -426,10 +418,7 @@ int gsi_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, i
   if (int rc = check_ws("gsi_project", ws, ws_bytes, gsi_workspace_bytes(GSI_CALL_PROJECT, 0, d, k, B))) return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  gsi::FusedArgs fa;
-  if (B == 1 && fused_project_only(fa, U, X, d, k, udtype, xdtype, C, R, rnorm, xnorm)) {
-    e = gsi::fused_launch(fa, udtype, s);
-  } else if (project_vector_path(d, k, B, udtype, U)) {
+  if (project_vector_path(d, k, B, udtype, U)) {
     gsi::ProjBatch pb;
     std::memset(&pb, 0, sizeof(pb));
     pb.n = 1;
@@ -683,7 +672,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // validate everything before the first launch
   for (int i = 0; i < n_inputs; ++i) {
     const gsi_input_desc& in = inputs[i];
-    if (in.flags & ~GSI_INPUT_SLOW_PATH_WX)
+    if (in.flags & ~(GSI_INPUT_SLOW_PATH_WX | GSI_INPUT_FUSED_KERNEL))
       return fail(GSI_ERR_SHAPE, "%s: inputs[%d].flags = %d has unknown bits", fn, i, in.flags);
     if (int rc = check_project_args(fn, in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
                                     in.xnorm))
@@ -780,15 +769,16 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     if (readers > 0 && all_stream) mode[i] = kVecInline;
   }
 
-  // Single token: an input whose basis, activations and maps all suit the fused kernel (gsi_fused.hip) is
-  // processed, with its maps, by that kernel alone.
+  // Single token: an input that asks for the fused kernel (GSI_INPUT_FUSED_KERNEL; gsi_fused.hip) and whose
+  // basis, activations and maps all suit it is processed, with its maps, by that kernel alone.
   enum { kFusedMode = 3, kFusedDone = 4 };
   const std::vector<int> mode_separate = mode;  // what the separate kernels would do with each input
   std::vector<char> map_fused(n_maps, 0);
   if (B == 1) {
     for (int i = 0; i < n_inputs; ++i) {
       const gsi_input_desc& in = inputs[i];
-      if (!gsi::fused_input_ok(in.d, in.k, in.udtype, in.U, in.X, in.xdtype, in.C, in.R,
+      if (!(in.flags & GSI_INPUT_FUSED_KERNEL) ||
+          !gsi::fused_input_ok(in.d, in.k, in.udtype, in.U, in.X, in.xdtype, in.C, in.R,
                                (in.flags & GSI_INPUT_SLOW_PATH_WX) != 0))
         continue;
       bool ok = true;

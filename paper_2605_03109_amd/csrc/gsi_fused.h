@@ -48,6 +48,7 @@ struct FusedChunk {
   int n_units;      // image units
   int wave_units;   // image units per image wave (<= kFusedLoads)
   int wg_cols;      // coefficients reduced by one workgroup (a multiple of 4)
+  int unit0[kFusedMaxMap];  // first image unit of every map (copy of mp[].unit0, contiguous; INT_MAX past n_mp)
 };
 
 struct FusedArgs {

@@ -45,8 +45,12 @@ namespace {
 using u64 = unsigned long long;
 
 constexpr size_t kStateBytes = 256;
-constexpr size_t kCSlotBytes = (size_t)kFusedMaxCols * 8;
-constexpr size_t kNSlotBytes = (size_t)kFusedMaxGroups * 2 * 8;
+// Words that every workgroup reads (the finished c, the groups' norms) are published in kCopies copies, and a
+// workgroup reads copy (its index mod kCopies): when all 256 workgroups re-read the same few kilobytes, the
+// memory channels that hold them serve every request one after another and an exchange takes microseconds.
+constexpr int kCopies = 16;
+constexpr size_t kCSlotBytes = (size_t)kCopies * kFusedMaxCols * 8;
+constexpr size_t kNSlotBytes = (size_t)2 * kCopies * kFusedMaxGroups * 2 * 8;  // two sets, by chunk parity
 constexpr size_t kPcBytes = (size_t)kFusedMaxGroups * 512 * 8;  // partial projections: groups * k words
 constexpr size_t kStaticWsBytes = (size_t)8 << 20;              // general-purpose part (the entry point without a workspace)
 constexpr size_t kOffC = kStateBytes;
@@ -61,9 +65,9 @@ static __device__ __align__(256) unsigned char scratch[kScratchBytes];
 
 struct FState {
   unsigned epoch;     // tags handed out so far
-  unsigned exit;      // workgroups of the running launch that have finished
-  unsigned wg_done;   // workgroups whose stores of a fired chunk have completed
+  unsigned wg_done;   // workgroups whose stores of a fired chunk have completed, ever (wraps)
   unsigned timeouts;  // waits that expired, ever
+  unsigned pad;
 };
 
 __device__ __forceinline__ u64 ld64(const u64* p) { return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT); }
@@ -82,6 +86,17 @@ __device__ __forceinline__ P* uni(P* p) {
   const unsigned long long v = reinterpret_cast<unsigned long long>(p);
   const unsigned lo = __builtin_amdgcn_readfirstlane((unsigned)v), hi = __builtin_amdgcn_readfirstlane((unsigned)(v >> 32));
   return reinterpret_cast<P*>(((unsigned long long)hi << 32) | lo);
+}
+
+// 16 (or 4) bytes at base + voff through a buffer descriptor: the base is uniform over the wave, the offset a
+// 32-bit register per lane, and an offset at or beyond `bytes` reads zeros instead of memory.
+__device__ __forceinline__ uint4 buf_load16(const void* base, unsigned bytes, unsigned voff) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)bytes, 0x00020000);
+  return __builtin_bit_cast(uint4, __builtin_amdgcn_raw_buffer_load_b128(r, (int)voff, 0, 0));
+}
+__device__ __forceinline__ float buf_load4(const void* base, unsigned bytes, unsigned voff) {
+  const __amdgpu_buffer_rsrc_t r = __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), (short)0, (int)bytes, 0x00020000);
+  return __int_as_float(__builtin_amdgcn_raw_buffer_load_b32(r, (int)voff, 0, 0));
 }
 
 // Words base[q * qstride + c], q < nq (<= NQ), c < NC, of the current tag: all requested at once, then re-read
@@ -125,14 +140,18 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
   constexpr int V = T::kVec;
   using S = typename T::storage;
   constexpr int GI = kFusedGroup;
+  constexpr int SW = kFusedWaves - 1;  // the service wave
   extern __shared__ __align__(16) float smem[];
   float* cs = smem;                                // finished coefficients of the chunk's inputs, [n_in][k]
   float* xsave = smem + kFusedMaxCols;             // x of the rows a basis wave holds, [wave][64]
   float* red = smem + kFusedMaxCols + kFusedBlock; // partial c of the group's items, [GI][k]; later the staged
   float* xs = red;                                 // vector of the slow path
   __shared__ __align__(16) FusedArgs s_a;          // the arguments, fetched once by all lanes together
-  __shared__ unsigned s_epoch, s_abort, s_done, s_fired[kFusedMaxIn];
+  __shared__ unsigned s_epoch, s_done0, s_abort, s_done, s_fired[kFusedMaxIn];
   __shared__ float s_nred[GI][2];
+  // what each image wave's loads are (written when they are requested, read back in phase 2): output row
+  // pointer, first row, rows of the map (low 24 bits) and the map's input (high 8 bits)
+  __shared__ __align__(16) uint4 s_img[kFusedWaves][kFusedLoads];
 
   FState* st = reinterpret_cast<FState*>(sc);
   u64* cslot = reinterpret_cast<u64*>(sc + kOffC);
@@ -148,249 +167,146 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
     for (int i = threadIdx.x; i < (int)(sizeof(FusedArgs) / 16); i += kFusedBlock) dst[i] = src[i];
   }
   if (threadIdx.x == 0) {
+    // Both words change only after every workgroup of this launch has published something, which each does
+    // after this read: workgroup 0 advances the epoch when it ends, and it cannot end before it has read
+    // every workgroup's words; wg_done is first added to after a gate, which needs every workgroup's norms.
     s_epoch = ld_u32(&st->epoch);
+    s_done0 = ld_u32(&st->wg_done);
     s_abort = 0;
     s_done = 0;
   }
   __syncthreads();
   const unsigned epoch0 = (unsigned)uni((int)s_epoch);
+  const unsigned done0 = (unsigned)uni((int)s_done0);
   const int n_chunks = uni(s_a.n_chunks);
   const float eps = __int_as_float(uni(__float_as_int(s_a.eps)));
   int fired_chunks = 0;
 
-  for (int ci = 0; ci < n_chunks; ++ci) {
-    const FusedChunk& ch = s_a.c[ci];
-    const unsigned tag = epoch0 + (unsigned)ci + 1u;
-    // (the lane and thread numbers pass through an empty asm statement so that nothing derived from them is
-    // computed once before the loop and then kept, or spilled, across this long body)
-    int lane = __lane_id();
-    asm volatile("" : "+v"(lane));
-    const int tid = wave * kWave + lane;
-    const int k = __builtin_amdgcn_readfirstlane(ch.k), lsh = __builtin_amdgcn_readfirstlane(ch.lsh);
-    const int n_in = __builtin_amdgcn_readfirstlane(ch.n_in), n_mp = __builtin_amdgcn_readfirstlane(ch.n_mp);
-    const int NG = __builtin_amdgcn_readfirstlane(ch.n_groups);
-    const int lpr = 1 << lsh, rpw = kWave >> lsh;
-    const int kshift = __builtin_ctz(k);
-    const int cc = lane & (lpr - 1), rg = lane >> lsh;  // 16-byte chunk of the row, row of the load
-    const bool bwg = b < NG;                            // basis workgroup: holds basis group b
-    const bool bwave = bwg && wave < GI;                // holds an item of the group
-    const bool swave = bwg ? wave < GI : wave == 0;     // may read memory during the exchanges
-    const bool iwave = bwg ? wave >= GI : wave >= 1;    // holds image rows
+  // What this wave holds of the chunk whose operands are in its registers (set when they are requested):
+  int h_ii = 0, h_row0 = 0, h_dlim = 0;  // basis wave: the group's input, the item's first row, the input's rows
+  int h_ub = 0, h_ue = 0;                // image wave: its units [ub, ue)
+  uint4 raw[kFusedLoads];
+  float xv[kFusedLoads];
 
-    // ---- loads: everything this wave needs from the basis / the images, requested at once ---------------
-    // Per load q (uniform over the wave): the matrix, its first row of this load and its row count.  A load
-    // without work reads the first bytes of the exchange state instead (one cache line, no memory traffic).
-    int ii = 0, row0 = 0, dlim = 0;        // basis wave: the group's input, the item's first row, the input's rows
-    int ub = 0, ue = 0;                    // image wave: its units [ub, ue)
-    uint4 raw[kFusedLoads];
-    float xv[kFusedLoads];
-    // image wave, load q: the map of unit ub + q, its first row of the load and its row count (uniform over the
-    // wave; looked up again in phase 2 rather than kept in registers across the exchanges)
-    auto image_load = [&](int q, const S*& M, float*& Y, int& row, int& m, int& in) {
-      const int u = ub + q;
-      int jj = 0;
-#pragma unroll
-      for (int j = 1; j < kFusedMaxMap; ++j)
-        if (j < n_mp && u >= ch.mp[j].unit0) jj = j;
-      const FusedMap& mp = ch.mp[uni(jj)];
-      M = uni(reinterpret_cast<const S*>(mp.M));
-      Y = uni(mp.Y);
-      row = uni((u - mp.unit0) * rpw);
-      m = uni(mp.m);
-      in = uni(mp.in);
-    };
-    // the address of every load first (a load without work reads the first bytes of the exchange state: one
-    // cache line, no memory traffic), then all loads in one run, unconditionally
-    const S* addr[kFusedLoads];
-    const float* xaddr[kFusedLoads];
-#pragma unroll
-    for (int q = 0; q < kFusedLoads; ++q) {
-      addr[q] = reinterpret_cast<const S*>(sc);
-      xaddr[q] = reinterpret_cast<const float*>(sc);
-    }
-    if (bwave) {
-#pragma unroll
-      for (int i = 1; i < kFusedMaxIn; ++i)
-        if (i < n_in && b >= ch.in[i].group0) ii = i;
-      ii = uni(ii);
-      const FusedIn& in = ch.in[ii];
-      row0 = uni(((b - in.group0) * GI + wave) * (kFusedLoads * rpw));
-      dlim = uni(in.d);
-      const S* U = uni(reinterpret_cast<const S*>(in.U)) + cc * V;
-      const float* X = uni(reinterpret_cast<const float*>(in.X));
+  // ---- loads of a chunk: everything this wave needs from the basis / the images, requested at once.  The
+  // address of every load first (a load without work reads the first bytes of the exchange state: one cache
+  // line, no memory traffic), then all loads in one run, unconditionally.
+  // (ldc == n_chunks: nothing left to request; the loads still run, on the idle line, so that the registers
+  // are written on every path -- else they would count as live, and be spilled, across the slow path)
+  auto issue_loads = [&](int ldc) {
+    {
+      int lane = __lane_id();
+      asm volatile("" : "+v"(lane));
+      const bool real = ldc < n_chunks;
+      const FusedChunk& nx = s_a.c[real ? ldc : 0];
+      const int k = uni(nx.k), lsh = uni(nx.lsh), n_in = uni(nx.n_in), n_mp = uni(nx.n_mp), NG = uni(nx.n_groups);
+      const int lpr = 1 << lsh, rpw = kWave >> lsh;
+      const int cc = lane & (lpr - 1), rg = lane >> lsh;
+      const bool bwg = b < NG;
+      // Loads go through buffer descriptors: a base that is uniform over the wave, a 32-bit byte offset per lane,
+      // and rows past the end of a matrix read zeros.  A load without work reads the first 16 bytes of the
+      // exchange state (one cache line, no memory traffic).
+      const unsigned rowb = (unsigned)k * (unsigned)sizeof(S);  // bytes of a row
+      const void* lb[kFusedLoads];   // per load: base, size (uniform over the wave) and the lane's byte offset
+      unsigned ln[kFusedLoads], lo[kFusedLoads];
 #pragma unroll
       for (int q = 0; q < kFusedLoads; ++q) {
-        const int r = min(row0 + q * rpw + rg, dlim - 1);  // clamped
-        addr[q] = U + (int64_t)r * k;
-        xaddr[q] = X + r;
+        lb[q] = reinterpret_cast<const void*>(sc);
+        ln[q] = 16u;
+        lo[q] = 0u;
       }
-    } else if (iwave) {
-      const int slot = bwg ? b * (kFusedWaves - GI) + (wave - GI) : NG * (kFusedWaves - GI) + (b - NG) * (kFusedWaves - 1) + (wave - 1);
-      ub = uni(min(slot * ch.wave_units, ch.n_units));
-      ue = uni(min(ub + ch.wave_units, ch.n_units));
+      const void* X = reinterpret_cast<const void*>(sc);
+      unsigned xbytes = 0u, r0 = 0u;
+      if (!real) {
+      } else if (bwg && wave < GI) {
+        int ii = 0;
 #pragma unroll
-      for (int q = 0; q < kFusedLoads; ++q) {
-        if (ub + q < ue) {  // uniform over the wave
-          const S* M;
-          float* Y;
-          int row, m, in;
-          image_load(q, M, Y, row, m, in);
-          addr[q] = M + (int64_t)min(row + rg, m - 1) * k + cc * V;
+        for (int i = 1; i < kFusedMaxIn; ++i)
+          if (i < n_in && b >= nx.in[i].group0) ii = i;
+        h_ii = uni(ii);
+        const FusedIn& in = nx.in[h_ii];
+        h_row0 = uni(((b - in.group0) * GI + wave) * (kFusedLoads * rpw));
+        h_dlim = uni(in.d);
+        const void* U = uni(in.U);
+        X = uni(in.X);
+        xbytes = (unsigned)h_dlim * 4u;
+        r0 = (unsigned)(h_row0 + rg);
+#pragma unroll
+        for (int q = 0; q < kFusedLoads; ++q) {
+          lb[q] = U;
+          ln[q] = (unsigned)h_dlim * rowb;
+          lo[q] = (r0 + (unsigned)(q * rpw)) * rowb + (unsigned)(cc * V) * (unsigned)sizeof(S);
         }
-      }
-    }
+      } else if (wave != SW) {
+        const int slot = bwg ? b * (SW - GI) + (wave - GI) : NG * (SW - GI) + (b - NG) * SW + wave;
+        h_ub = uni(min(slot * nx.wave_units, nx.n_units));
+        h_ue = uni(min(h_ub + nx.wave_units, nx.n_units));
+        // the first unit of every map, fetched at once; the map of a unit = the last whose first unit is <= it
+        int u0[kFusedMaxMap];
+        {
+          const int4 a0 = *reinterpret_cast<const int4*>(&nx.unit0[0]), a1 = *reinterpret_cast<const int4*>(&nx.unit0[4]);
+          u0[0] = uni(a0.x); u0[1] = uni(a0.y); u0[2] = uni(a0.z); u0[3] = uni(a0.w);
+          u0[4] = uni(a1.x); u0[5] = uni(a1.y); u0[6] = uni(a1.z); u0[7] = uni(a1.w);
+        }
+        int jq[kFusedLoads];
 #pragma unroll
-    for (int q = 0; q < kFusedLoads; ++q) raw[q] = *reinterpret_cast<const uint4*>(addr[q]);
+        for (int q = 0; q < kFusedLoads; ++q) {
+          const int u = h_ub + q;
+          int jj = 0;
 #pragma unroll
-    for (int q = 0; q < kFusedLoads; ++q) xv[q] = *xaddr[q];
-
-    // ---- phase 1: partial c of the item (fixed order: loads ascending, then the row groups of the wave),
-    //      then of the group (waves ascending)
-    if (bwave) {
-      float acc[V];
+          for (int j = 1; j < kFusedMaxMap; ++j) jj += u >= u0[j] ? 1 : 0;
+          jq[q] = jj;
+        }
+        // the descriptors of those maps: all requested from LDS before the first is used
+        uint4 md[kFusedLoads];  // {M, Y} of load q's map
+        int2 mm[kFusedLoads];   // {m, in}
 #pragma unroll
-      for (int e = 0; e < V; ++e) acc[e] = 0.f;
+        for (int q = 0; q < kFusedLoads; ++q) {
+          const FusedMap& mp = nx.mp[jq[q]];
+          const uint2 pm = *reinterpret_cast<const uint2*>(&mp.M), py = *reinterpret_cast<const uint2*>(&mp.Y);
+          md[q] = make_uint4(pm.x, pm.y, py.x, py.y);
+          mm[q] = *reinterpret_cast<const int2*>(&mp.m);
+        }
 #pragma unroll
-      for (int q = 0; q < kFusedLoads; ++q) {
-        float w[V];
-        T::widen(raw[q], w);
-        const float x = row0 + q * rpw + rg < dlim ? xv[q] : 0.f;
-#pragma unroll
-        for (int e = 0; e < V; ++e) acc[e] = fmaf(w[e], x, acc[e]);
-      }
-      for (int off = lpr; off < kWave; off <<= 1) {
-#pragma unroll
-        for (int e = 0; e < V; ++e) acc[e] += __shfl_xor(acc[e], off, kWave);
-      }
-      if (cc == 0) {  // x is needed once more, by the lane that forms the row's residual: parked in LDS
-#pragma unroll
-        for (int q = 0; q < kFusedLoads; ++q) xsave[wave * kWave + q * rpw + rg] = xv[q];
-      }
-      if (rg == 0) {
-#pragma unroll
-        for (int e = 0; e < V; ++e) red[wave * k + cc * V + e] = acc[e];
-      }
-    }
-    __syncthreads();
-    if (bwg && (int)tid < k) {
-      float s = 0.f;
-#pragma unroll
-      for (int w = 0; w < GI; ++w) s += red[w * k + tid];
-      st64(pc + (int64_t)b * k + tid, pack(s, tag));
-    }
-
-    if (swave) {
-      // ---- reduce: this workgroup's columns of c, four neighbouring columns per wave, groups ascending per lane
-      const int ncol = n_in << kshift;
-      const int nquad = ch.wg_cols >> 2;
-      for (int qi = bwg ? wave : 0; qi < nquad; qi += bwg ? GI : 1) {
-        const int cg = b * ch.wg_cols + 4 * qi;
-        if (cg < ncol) {
-          const int i = cg >> kshift, j = cg & (k - 1);
-          const FusedIn& in = ch.in[i];
-          const int P = in.n_groups;
-          float v[4][4];
-          const int left = P - lane;
-          poll_words<4, 4>(pc + ((int64_t)in.group0 + lane) * k + j, (int64_t)kWave * k, left > 0 ? (left + kWave - 1) / kWave : 0,
-                           tag, v, &s_abort);
-          float s[4];
-#pragma unroll
-          for (int c = 0; c < 4; ++c) {
-            s[c] = (v[0][c] + v[1][c]) + (v[2][c] + v[3][c]);
-            s[c] = group_sum<kWave>(s[c]);
-          }
-          if (lane < 4) {
-            const float mine = lane == 0 ? s[0] : lane == 1 ? s[1] : lane == 2 ? s[2] : s[3];
-            st64(cslot + cg + lane, pack(mine, tag));
-            in.C[j + lane] = mine;
+        for (int q = 0; q < kFusedLoads; ++q) {
+          if (h_ub + q < h_ue) {  // uniform over the wave
+            const int row = (h_ub + q - u0[jq[q]]) * rpw;
+            const int m = uni(mm[q].x);
+            lb[q] = reinterpret_cast<const void*>(((unsigned long long)(unsigned)uni((int)md[q].y) << 32) | (unsigned)uni((int)md[q].x));
+            ln[q] = (unsigned)m * rowb;
+            lo[q] = (unsigned)(row + rg) * rowb + (unsigned)(cc * V) * (unsigned)sizeof(S);
+            if (lane == 0) s_img[wave][q] = make_uint4(md[q].z, md[q].w, (unsigned)row, (unsigned)m | ((unsigned)mm[q].y << 24));
           }
         }
       }
-      // ---- the finished c of every input of the chunk -> LDS
-      const int nth = bwg ? GI * kWave : kWave;
-      for (int s0 = (bwg ? wave * kWave : 0) + lane; s0 < ncol; s0 += nth * 8) {
-        float v[8][1];
-        const int left = ncol - s0;
-        poll_words<8, 1>(cslot + s0, nth, (left + nth - 1) / nth, tag, v, &s_abort);
 #pragma unroll
-        for (int q = 0; q < 8; ++q)
-          if (s0 + q * nth < ncol) cs[s0 + q * nth] = v[q][0];
-      }
+      for (int q = 0; q < kFusedLoads; ++q) raw[q] = buf_load16(lb[q], ln[q], lo[q]);
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) xv[q] = buf_load4(X, xbytes, (r0 + (unsigned)(q * rpw)) * 4u);
     }
-    __syncthreads();
+  };
 
-    // ---- phase 2: residual rows (basis waves) and image rows (image waves) out of the registers ----------
-    if (bwave) {
-      const FusedIn& in = ch.in[ii];
-      float cv[V];
-      lds_vec<V>(cs + (ii << kshift) + cc * V, cv);
-      float ar = 0.f, ax = 0.f;
+  // ---- gate of a chunk (the service wave): the groups' norms of every input, in ascending order per lane ----
+  auto gate_chunk = [&](int gc, int lane) {
+    const FusedChunk& ch = s_a.c[gc];
+    const unsigned tag = epoch0 + (unsigned)gc + 1u;
+    const int n_in = uni(ch.n_in);
+    const u64* nbase = nslot + ((int64_t)(gc & 1) * kCopies + (b % kCopies)) * kFusedMaxGroups * 2;
+    float v[kFusedMaxIn][2][2];
 #pragma unroll
-      for (int q = 0; q < kFusedLoads; ++q) {
-        float w[V];
-        T::widen(raw[q], w);
-        float s = 0.f;
-#pragma unroll
-        for (int e = 0; e < V; ++e) s = fmaf(w[e], cv[e], s);
-        s = group_sum_rt(s, lpr);
-        const int r = row0 + q * rpw + rg;
-        if (r < dlim && cc == 0) {
-          const float x = xsave[wave * kWave + q * rpw + rg];
-          const float res = x - s;
-          st_f32(in.R + r, res);
-          ar = fmaf(res, res, ar);
-          ax = fmaf(x, x, ax);
-        }
-      }
-      ar = group_sum<kWave>(ar);
-      ax = group_sum<kWave>(ax);
-      if (lane == 0) {
-        s_nred[wave][0] = ar;
-        s_nred[wave][1] = ax;
-      }
-    } else if (iwave) {
-#pragma unroll
-      for (int q = 0; q < kFusedLoads; ++q) {
-        if (ub + q < ue) {  // uniform over the wave
-          const S* M;
-          float* Y;
-          int row, m, in;
-          image_load(q, M, Y, row, m, in);
-          float w[V], cv[V];
-          T::widen(raw[q], w);
-          lds_vec<V>(cs + (in << kshift) + cc * V, cv);
-          float s = 0.f;
-#pragma unroll
-          for (int e = 0; e < V; ++e) s = fmaf(w[e], cv[e], s);
-          s = group_sum_rt(s, lpr);
-          const int r = row + rg;
-          if (cc == 0 && r < m) st_f32(Y + r, s);
-        }
-      }
+    for (int i = 0; i < kFusedMaxIn; ++i) {  // all inputs requested before the first is waited for
+      const int P = i < n_in ? ch.in[i < n_in ? i : 0].n_groups : 0;
+      const int g0 = ch.in[i < n_in ? i : 0].group0;
+      const int left = P - lane;
+      poll_words<2, 2>(nbase + 2 * ((int64_t)g0 + lane), 2 * kWave, left > 0 ? (left + kWave - 1) / kWave : 0, tag, v[i],
+                       &s_abort);
     }
-    __syncthreads();
-    if (bwg && tid == 0) {  // the group's |r|^2, |x|^2: waves ascending
-      float sr = 0.f, sx = 0.f;
 #pragma unroll
-      for (int w = 0; w < GI; ++w) {
-        sr += s_nred[w][0];
-        sx += s_nred[w][1];
-      }
-      st64(nslot + 2 * b, pack(sr, tag));
-      st64(nslot + 2 * b + 1, pack(sx, tag));
-    }
-
-    // ---- gate: one wave per input, the groups' norms in ascending order per lane ----------------------------
-    if (swave) {
-      for (int i = bwg ? wave : 0; i < n_in; i += bwg ? GI : 1) {
+    for (int i = 0; i < kFusedMaxIn; ++i) {
+      if (i < n_in) {
         const FusedIn& in = ch.in[i];
-        const int P = in.n_groups;
-        float v[4][2];
-        const int left = P - lane;
-        poll_words<4, 2>(nslot + 2 * ((int64_t)in.group0 + lane), 2 * kWave, left > 0 ? (left + kWave - 1) / kWave : 0, tag, v,
-                         &s_abort);
-        const float sr = (v[0][0] + v[1][0]) + (v[2][0] + v[3][0]);
-        const float sx = (v[0][1] + v[1][1]) + (v[2][1] + v[3][1]);
+        const float sr = v[i][0][0] + v[i][1][0];
+        const float sx = v[i][0][1] + v[i][1][1];
         const float rn = sqrtf(group_sum<kWave>(sr)), xn = sqrtf(group_sum<kWave>(sx));
         const bool f = gate_fires(rn, xn, eps);
         if (lane == 0) {
@@ -407,16 +323,17 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
         }
       }
     }
-    __syncthreads();
-    unsigned fired_mask = 0;
-    for (int i = 0; i < n_in; ++i) fired_mask |= s_fired[i] << i;
-    if (s_abort) fired_mask = 0;  // a wait expired: this launch's results are void, end it quickly
-    fired_mask = __builtin_amdgcn_readfirstlane(fired_mask);
-    if (fired_mask == 0) continue;  // the common case: nothing fired, no byte of W is read
+  };
 
-    // ---- slow path: rows of W of the fired inputs' maps --------------------------------------------------
-    // The image rows and residuals this phase reads were written by other workgroups: wait until every
-    // workgroup's stores of this chunk have completed (they were issued before the gate, so this is short).
+  // ---- slow path of a chunk whose gate fired: rows of W of the fired inputs' maps ------------------------------
+  // The image rows and residuals this phase reads were written by other workgroups: wait until every workgroup's
+  // stores of the chunk have completed (they were issued long before, so this is short).
+  auto slow_path = [&](int fc, unsigned fired_mask) {
+    int lane = __lane_id();
+    asm volatile("" : "+v"(lane));
+    const int tid = wave * kWave + lane;
+    const FusedChunk& ch = s_a.c[fc];
+    const int n_in = uni(ch.n_in), n_mp = uni(ch.n_mp);
     ++fired_chunks;
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     if (lane == 0) {
@@ -426,7 +343,7 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
     if (tid == 0) {
       const unsigned want = (unsigned)G * (unsigned)fired_chunks;
       const long long t0 = wall_clock64();
-      while (ld_u32(&st->wg_done) < want && !s_abort)
+      while (ld_u32(&st->wg_done) - done0 < want && !s_abort)
         if (wall_clock64() - t0 > kSpinTicks) s_abort = 1u;
     }
     __syncthreads();
@@ -434,9 +351,9 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
     for (int gi = 0; gi < n_in; ++gi) {
       if (!((fired_mask >> gi) & 1u)) continue;  // uniform across the grid
       const FusedIn& in = ch.in[gi];
-      const int dd = __builtin_amdgcn_readfirstlane(in.d);
-      const bool whole = __builtin_amdgcn_readfirstlane(in.wx) != 0;  // y = W x (Algorithm 1, line 7) replaces y; else W r is added to M c
-      int tid2 = wave * kWave + __lane_id();  // (recomputed: see the note on `lane` above)
+      const int dd = uni(in.d);
+      const bool whole = uni(in.wx) != 0;  // y = W x (Algorithm 1, line 7) replaces y; else W r is added to M c
+      int tid2 = wave * kWave + __lane_id();  // (recomputed: see the note on `lane` in the main loop)
       asm volatile("" : "+v"(tid2));
       if (whole) {
         const float* X = reinterpret_cast<const float*>(in.X);
@@ -456,8 +373,8 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
       int first = gw;  // rows of the input's maps are dealt round-robin, map after map
       for (int j = 0; j < n_mp; ++j) {
         const FusedMap& mp = ch.mp[j];
-        if (__builtin_amdgcn_readfirstlane(mp.in) != gi) continue;  // uniform
-        const int m = __builtin_amdgcn_readfirstlane(mp.m);
+        if (uni(mp.in) != gi) continue;  // uniform
+        const int m = uni(mp.m);
         const S* W = reinterpret_cast<const S*>(mp.W);
         float* Y = mp.Y;
         if (tail) stream_map_rows<T, true, true>(W, Y, m, dd, xs, whole, first, GW, lane);
@@ -466,18 +383,202 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
       }
       __syncthreads();  // the staged vector is free again
     }
+  };
+
+  // Chunks run in order, and the exchanges of neighbouring chunks overlap: the operands of chunk ci + 1 are
+  // requested as soon as phase 2 of chunk ci has consumed the registers, and the gate of chunk ci is decided
+  // together with the coefficient exchange of chunk ci + 1 (its slow path, if the gate fired, then runs after
+  // phase 2 of chunk ci + 1, when the registers are free again).  The norms travel in two sets of words, by
+  // chunk parity, because a chunk's norms are still being read when the next chunk's are written.
+  issue_loads(0);
+  for (int ci = 0; ci < n_chunks; ++ci) {
+    // (the lane number passes through an empty asm statement so that nothing derived from it is computed once
+    // before the loop and then kept, or spilled, across this long body)
+    int lane = __lane_id();
+    asm volatile("" : "+v"(lane));
+    const int tid = wave * kWave + lane;
+    const FusedChunk& ch = s_a.c[ci];
+    const unsigned tag = epoch0 + (unsigned)ci + 1u;
+    const int k = uni(ch.k), lsh = uni(ch.lsh), n_in = uni(ch.n_in), NG = uni(ch.n_groups);
+    const int lpr = 1 << lsh, rpw = kWave >> lsh;
+    const int kshift = __builtin_ctz(k);
+    const int cc = lane & (lpr - 1), rg = lane >> lsh;  // 16-byte chunk of the row, row of the load
+    const bool bwg = b < NG;                            // basis workgroup: holds basis group b
+    const bool bwave = bwg && wave < GI;                // holds an item of the group
+    const bool iwave = wave != SW && !bwave;            // holds image rows
+
+    // ---- phase 1: partial c of the item (fixed order: loads ascending, then the row groups of the wave),
+    //      then of the group (waves ascending)
+    if (bwave) {
+      float acc[V];
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] = 0.f;
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) {
+        float w[V];
+        T::widen(raw[q], w);
+        const float x = h_row0 + q * rpw + rg < h_dlim ? xv[q] : 0.f;
+#pragma unroll
+        for (int e = 0; e < V; ++e) acc[e] = fmaf(w[e], x, acc[e]);
+      }
+      for (int off = lpr; off < kWave; off <<= 1) {
+#pragma unroll
+        for (int e = 0; e < V; ++e)
+          acc[e] += __int_as_float(__builtin_amdgcn_ds_bpermute((lane ^ off) << 2, __float_as_int(acc[e])));
+      }
+      if (cc == 0) {  // x is needed once more, by the lane that forms the row's residual: parked in LDS
+#pragma unroll
+        for (int q = 0; q < kFusedLoads; ++q) xsave[wave * kWave + q * rpw + rg] = xv[q];
+      }
+      if (rg == 0) {
+#pragma unroll
+        for (int e = 0; e < V; ++e) red[wave * k + cc * V + e] = acc[e];
+      }
+    }
+    __syncthreads();
+    if (bwg && tid < k) {
+      float s = 0.f;
+#pragma unroll
+      for (int w = 0; w < GI; ++w) s += red[w * k + tid];
+      st64(pc + (int64_t)b * k + tid, pack(s, tag));
+    }
+
+    if (wave == SW) {
+      // ---- reduce: this workgroup's columns of c, four neighbouring columns at a time, groups ascending per lane
+      const int ncol = n_in << kshift;
+      const int nquad = ch.wg_cols >> 2;
+      for (int qi = 0; qi < nquad; ++qi) {
+        const int cg = b * ch.wg_cols + 4 * qi;
+        if (cg < ncol) {
+          const int i = cg >> kshift, j = cg & (k - 1);
+          const FusedIn& in = ch.in[i];
+          const int P = in.n_groups;
+          float v[2][4];
+          const int left = P - lane;
+          poll_words<2, 4>(pc + ((int64_t)in.group0 + lane) * k + j, (int64_t)kWave * k,
+                           left > 0 ? (left + kWave - 1) / kWave : 0, tag, v, &s_abort);
+          float s[4];
+#pragma unroll
+          for (int c = 0; c < 4; ++c) s[c] = group_sum<kWave>(v[0][c] + v[1][c]);
+          {  // lane -> (copy, column): 16 copies x 4 columns
+            const int c4 = lane & 3;
+            const float mine = c4 == 0 ? s[0] : c4 == 1 ? s[1] : c4 == 2 ? s[2] : s[3];
+            st64(cslot + (int64_t)(lane >> 2) * kFusedMaxCols + cg + c4, pack(mine, tag));
+            if (lane < 4) in.C[j + lane] = mine;
+          }
+        }
+      }
+      // ---- the gate of the previous chunk (its norms were published after its phase 2)
+      if (ci > 0) gate_chunk(ci - 1, lane);
+      // ---- the finished c of every input of the chunk -> LDS
+      for (int s0 = lane; s0 < ncol; s0 += kWave * 16) {
+        float v[16][1];
+        const int left = ncol - s0;
+        poll_words<16, 1>(cslot + (int64_t)(b % kCopies) * kFusedMaxCols + s0, kWave, (left + kWave - 1) / kWave, tag, v,
+                          &s_abort);
+#pragma unroll
+        for (int q = 0; q < 16; ++q)
+          if (s0 + q * kWave < ncol) cs[s0 + q * kWave] = v[q][0];
+      }
+    }
+    __syncthreads();
+    unsigned fired_prev = 0;  // the gate of chunk ci - 1
+    if (ci > 0) {
+      const int pn = uni(s_a.c[ci - 1].n_in);
+      for (int i = 0; i < pn; ++i) fired_prev |= s_fired[i] << i;
+      if (s_abort) fired_prev = 0;  // a wait expired: this launch's results are void, end it quickly
+      fired_prev = (unsigned)uni((int)fired_prev);
+    }
+
+    // ---- phase 2: residual rows (basis waves) and image rows (image waves) out of the registers ----------
+    if (bwave) {
+      // (the registers pass through an empty asm statement: else the widened values of phase 1 are kept for
+      // this phase, twice the registers the raw words take)
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) asm volatile("" : "+v"(raw[q].x), "+v"(raw[q].y), "+v"(raw[q].z), "+v"(raw[q].w));
+      const FusedIn& in = ch.in[h_ii];
+      float* R = uni(in.R);
+      float cv[V];
+      lds_vec<V>(cs + (h_ii << kshift) + cc * V, cv);
+      float ar = 0.f, ax = 0.f;
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) {
+        float w[V];
+        T::widen(raw[q], w);
+        float s = 0.f;
+#pragma unroll
+        for (int e = 0; e < V; ++e) s = fmaf(w[e], cv[e], s);
+        s = group_sum_rt(s, lpr);
+        const int r = h_row0 + q * rpw + rg;
+        if (r < h_dlim && cc == 0) {
+          const float x = xsave[wave * kWave + q * rpw + rg];
+          const float res = x - s;
+          st_f32(R + r, res);
+          ar = fmaf(res, res, ar);
+          ax = fmaf(x, x, ax);
+        }
+      }
+      ar = group_sum<kWave>(ar);
+      ax = group_sum<kWave>(ax);
+      if (lane == 0) {
+        s_nred[wave][0] = ar;
+        s_nred[wave][1] = ax;
+      }
+    } else if (iwave) {
+      uint4 dq[kFusedLoads];
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) dq[q] = s_img[wave][q];  // (same address in every lane)
+#pragma unroll
+      for (int q = 0; q < kFusedLoads; ++q) {
+        if (h_ub + q < h_ue) {  // uniform over the wave
+          float* Y = reinterpret_cast<float*>(((unsigned long long)(unsigned)uni((int)dq[q].y) << 32) | (unsigned)uni((int)dq[q].x));
+          const int row = uni((int)dq[q].z), m = uni((int)(dq[q].w & 0xffffffu)), in = uni((int)(dq[q].w >> 24));
+          float w[V], cv[V];
+          T::widen(raw[q], w);
+          lds_vec<V>(cs + (in << kshift) + cc * V, cv);
+          float s = 0.f;
+#pragma unroll
+          for (int e = 0; e < V; ++e) s = fmaf(w[e], cv[e], s);
+          s = group_sum_rt(s, lpr);
+          const int r = row + rg;
+          if (cc == 0 && r < m) st_f32(Y + r, s);
+        }
+      }
+    }
+    __syncthreads();
+    if (bwg && tid < 2 * kCopies) {  // the group's |r|^2, |x|^2: waves ascending; thread -> (copy, which)
+      const int which = tid & 1;
+      float sn = 0.f;
+#pragma unroll
+      for (int w = 0; w < GI; ++w) sn += s_nred[w][which];
+      st64(nslot + (((int64_t)(ci & 1) * kCopies + (tid >> 1)) * kFusedMaxGroups + b) * 2 + which, pack(sn, tag));
+    }
+
+    // the registers are free: the slow path of the previous chunk, if its gate fired (the common case: it did
+    // not, and no byte of W is read), then the request for the next chunk's operands
+    if (fired_prev != 0) slow_path(ci - 1, fired_prev);
+    issue_loads(ci + 1);
   }
 
-  // ---- the last workgroup to finish leaves the exchange state ready for the next launch -----------------
+  // ---- the gate (and slow path) of the last chunk
+  {
+    int lane = __lane_id();
+    asm volatile("" : "+v"(lane));
+    if (wave == SW) gate_chunk(n_chunks - 1, lane);
+    __syncthreads();
+    unsigned fired_last = 0;
+    const int pn = uni(s_a.c[n_chunks - 1].n_in);
+    for (int i = 0; i < pn; ++i) fired_last |= s_fired[i] << i;
+    if (s_abort) fired_last = 0;
+    fired_last = (unsigned)uni((int)fired_last);
+    if (fired_last != 0) slow_path(n_chunks - 1, fired_last);
+  }
+
+  // ---- the next launch gets fresh tags (see the note where the epoch is read)
   __syncthreads();
   if (wave == 0 && __lane_id() == 0) {
     if (s_abort) add_u32(&st->timeouts, 1u);
-    const unsigned old = add_u32(&st->exit, 1u);
-    if (old == (unsigned)G - 1u) {
-      st_u32(&st->exit, 0u);
-      st_u32(&st->wg_done, 0u);
-      st_u32(&st->epoch, epoch0 + (unsigned)n_chunks);
-    }
+    if (b == 0) st_u32(&st->epoch, epoch0 + (unsigned)n_chunks);
   }
 }
 
@@ -564,7 +665,7 @@ bool fused_plan(FusedChunk& ch, int dtype) {
   for (int i = 0; i < ch.n_in; ++i) {
     ch.in[i].group0 = (int)groups;
     ch.in[i].n_groups = (int)ceil_div(ch.in[i].d, (int64_t)kFusedGroup * kFusedLoads * rpw);
-    if (ch.in[i].n_groups > 4 * kWave) return false;  // a wave sums a column over at most four groups per lane
+    if (ch.in[i].n_groups > 2 * kWave) return false;  // a wave sums a column over at most two groups per lane
     groups += ch.in[i].n_groups;
   }
   for (int j = 0; j < ch.n_mp; ++j) {
@@ -572,13 +673,15 @@ bool fused_plan(FusedChunk& ch, int dtype) {
     ch.mp[j].n_units = (int)ceil_div(ch.mp[j].m, rpw);
     units += ch.mp[j].n_units;
   }
+  for (int j = 0; j < kFusedMaxMap; ++j) ch.unit0[j] = j < ch.n_mp ? ch.mp[j].unit0 : 0x7fffffff;
   if (groups > G || groups > kFusedMaxGroups || units > (1 << 28)) return false;
   ch.n_groups = (int)groups;
   ch.n_units = (int)units;
   ch.wg_cols = 4 * (int)ceil_div((int64_t)ch.n_in * k, 4 * (int64_t)G);
   if (ch.wg_cols / 4 > kFusedGroup) return false;
-  // image waves: eight in a basis workgroup, fifteen in the others
-  const int64_t slots = groups * (kFusedWaves - kFusedGroup) + (G - groups) * (kFusedWaves - 1);
+  // image waves: seven in a basis workgroup, fifteen in the others (the last wave of every workgroup holds
+  // nothing: it serves the exchanges)
+  const int64_t slots = groups * (kFusedWaves - 1 - kFusedGroup) + (G - groups) * (kFusedWaves - 1);
   ch.wave_units = slots > 0 ? (int)ceil_div(units, slots) : 0;
   if (units > 0 && (slots < 1 || ch.wave_units > kFusedLoads)) return false;
   return true;

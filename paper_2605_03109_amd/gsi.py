@@ -21,6 +21,7 @@ GSI_OK = 0
 GSI_ERR_NULL, GSI_ERR_SHAPE, GSI_ERR_DTYPE, GSI_ERR_ALIGN, GSI_ERR_WORKSPACE, GSI_ERR_HIP = -1, -2, -3, -4, -5, -6
 GSI_F32, GSI_BF16 = 0, 1
 INPUT_SLOW_PATH_WX = 1  # gsi_input_desc.flags: fired tokens get y = W x (Algorithm 1, line 7)
+INPUT_FUSED_KERNEL = 2  # gsi_input_desc.flags: single-token calls take the fused kernel (one launch, basis read once)
 MAP_IMAGE_FP8 = 1  # gsi_map_desc.flags: M holds E4M3 codes, M_scale the row scales (single-token calls)
 CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
 
@@ -29,6 +30,7 @@ EXPORTS = (
     "gsi_layer_stack",
     "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
+    "gsi_fused_timeouts",
     "gsi_version",
 )
 
@@ -86,6 +88,8 @@ def _load() -> ctypes.CDLL:
     lib.gsi_layer_stack_workspace_bytes.restype = sz
     lib.gsi_dense_stack_workspace_bytes.argtypes = lib.gsi_layer_stack_workspace_bytes.argtypes
     lib.gsi_dense_stack_workspace_bytes.restype = sz
+    lib.gsi_fused_timeouts.argtypes = [ctypes.POINTER(ctypes.c_uint32)]
+    lib.gsi_fused_timeouts.restype = ctypes.c_int
     lib.gsi_last_error.restype = ctypes.c_char_p
     lib.gsi_version.restype = ctypes.c_int
     for name in ("gsi_build_image", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
@@ -108,6 +112,13 @@ def last_error() -> str:
 
 def version() -> int:
     return lib.gsi_version()
+
+
+def fused_timeouts() -> int:
+    """Bounded waits of fused-kernel launches that expired on the current device (0 in normal operation)."""
+    n = ctypes.c_uint32(0)
+    _check(lib.gsi_fused_timeouts(ctypes.byref(n)))
+    return int(n.value)
 
 
 # ----------------------------------------------------------------------------------------------
