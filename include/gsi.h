@@ -171,6 +171,18 @@ enum { GSI_MAP_IMAGE_FP8 = 1 };
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream);
 
+/* gsi_layer_stack for callers that cannot allocate device memory (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc) and therefore cannot provide a workspace: identical to gsi_layer_stack,
+ * with the scratch memory taken from a static device array of the library instead of `ws`.  The call allocates
+ * nothing on the device and frees nothing.  Limit: the array holds 8 MiB
+ * of workspace; a call whose gsi_layer_stack_workspace_bytes() exceeds that returns GSI_ERR_WORKSPACE and enqueues
+ * nothing (single-token calls need kilobytes; decode batches of a few tokens fit; prefill-sized batches do not).
+ * Every call on a device shares that device's array and finds the previous call's contents in it (the kernels
+ * write what they read, nothing needs clearing); calls that overlap in time on one device race on it and are
+ * not supported -- issue them on one stream or order the streams. */
+int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                           int64_t B, float eps, void* stream);
+
 /* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition
  * the two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start
  * and stop timestamps of the dispatch of the call's single-token kernel (for B == 1 one launch evaluates the

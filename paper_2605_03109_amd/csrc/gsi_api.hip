@@ -557,6 +557,27 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
                           nullptr);
 }
 
+int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                           int64_t B, float eps, void* stream) {
+  const char* fn = "gsi_layer_stack_static";
+  void* ws = nullptr;
+  size_t have = 0;
+  if (hipError_t e = gsi::static_workspace(&ws, &have); e != hipSuccess) return hip_fail(e, fn);
+  if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
+  if (n_maps > 0) GSI_REQUIRE_PTR(maps);
+  if (n_inputs > 0) GSI_REQUIRE_PTR(inputs);
+  for (int j = 0; j < n_maps; ++j)
+    if (maps[j].input_id < 0 || maps[j].input_id >= n_inputs)
+      return fail(GSI_ERR_SHAPE, "%s: maps[%d].input_id = %d out of range", fn, j, maps[j].input_id);
+  const size_t need = B > 0 ? gsi_layer_stack_workspace_bytes(maps, n_maps, inputs, n_inputs, B) : 0;
+  if (need > have)
+    return fail(GSI_ERR_WORKSPACE,
+                "%s: this call needs %zu bytes of scratch, the library's static array holds %zu; use gsi_layer_stack "
+                "with a workspace",
+                fn, need, have);
+  return layer_stack_impl(fn, maps, n_maps, inputs, n_inputs, B, eps, ws, have, stream, nullptr, nullptr);
+}
+
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                           int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
                           void* ev_linear_end) {

@@ -28,7 +28,7 @@ CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR,
 EXPORTS = (
     "gsi_build_image", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
     "gsi_layer_stack",
-    "gsi_layer_stack_timed", "gsi_dense_stack",
+    "gsi_layer_stack_static", "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
     "gsi_fused_timeouts",
     "gsi_version",
@@ -77,6 +77,9 @@ def _load() -> ctypes.CDLL:
     lib.gsi_dense_linear.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, sz, vp]
     lib.gsi_layer_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                     ctypes.c_int32, i64, f32, vp, sz, vp]
+    lib.gsi_layer_stack_static.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
+                                           ctypes.c_int32, i64, f32, vp]
+    lib.gsi_layer_stack_static.restype = ctypes.c_int
     lib.gsi_layer_stack_timed.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                           ctypes.c_int32, i64, f32, vp, sz, vp, vp, vp]
     lib.gsi_dense_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
@@ -336,6 +339,11 @@ class LayerStack:
     def run(self, stream=None) -> None:
         _check(lib.gsi_layer_stack(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B, self.eps,
                                    self.ws.data_ptr(), self.ws.numel(), _stream(stream)))
+
+    def run_static(self, stream=None) -> None:
+        """As run(), with the scratch memory in the library's static device array (no workspace argument)."""
+        _check(lib.gsi_layer_stack_static(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B, self.eps,
+                                          _stream(stream)))
 
     def run_timed(self, ev_begin: int, ev_end: int, stream=None) -> None:
         """As run(), with raw hipEvent_t handles recorded around the linear-map kernel launch."""
