@@ -296,12 +296,13 @@ def test_workspace_too_small_is_an_error_not_a_crash(gsi):
 # full-size GPT-J-shaped block in the launch configuration the benchmark times:
 # one gsi_layer_stack call per decode token (B = 1), four inputs, six maps, k = 256, bf16
 # ------------------------------------------------------------------------------------------------
-def test_gptj_block_full_size_decode(gsi, pu):
-    T = 6
-    w = wl.gptj_block(T=T, k=256, fire_rate=0.34)  # 2 of 6 tokens fire per input (seeded positions)
-    say(f"case {w.name}: T={T} k=256, full shapes")
+@pytest.mark.parametrize("k,T,fused", [(256, 6, False), (64, 3, False), (128, 3, False), (512, 3, False), (256, 3, True)])
+def test_gptj_block_full_size_decode(gsi, pu, k, T, fused):
+    w = wl.gptj_block(T=T, k=k, fire_rate=0.34)  # 2 of 6 (1 of 3) tokens fire per input (seeded positions)
+    say(f"case {w.name}: T={T} k={k}, full shapes, {'fused kernel' if fused else 'separate kernels'}")
     dgs, inputs, maps, names = _stack_for(gsi, pu, w, 1)
-    st = gsi.LayerStack([{"U": dg.U, "X": dg.X} for dg in dgs], maps, T, w.eps)
+    flags = gsi.INPUT_FUSED_KERNEL if fused else 0
+    st = gsi.LayerStack([{"U": dg.U, "X": dg.X, "flags": flags} for dg in dgs], maps, T, w.eps)
     for t in range(T):
         st.refresh(token_offset=t, B=1)
         st.run()
@@ -327,7 +328,9 @@ def test_gptj_block_full_size_decode(gsi, pu):
                                      ref, mask)
             say(f"    map {name}: rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
         del og
-    assert n_fired_total == 8
+    assert n_fired_total == (8 if T == 6 else 4)
+    if k != 256 or fused:
+        return
     # the dense baseline the benchmark divides by: same descriptors, y = W x
     st.refresh(token_offset=0, B=1)
     st.run_dense()
@@ -770,3 +773,66 @@ def test_graph_replay_equals_eager(gsi, pu, d, k, m, T, nf, B, fp8):
             assert torch.equal(a, b), f"replay {rep} differs from the eager run"
         issue(torch.cuda.current_stream().cuda_stream)   # eager work between the replays
         torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------------
+# tokens placed next to the gate threshold (Eq. (gate); Definition "Activation basis and residual ratio"):
+# inside the 1e-4 band either decision is admissible and y is checked against the oracle on the device's own
+# decision; just outside the band the decision must be the oracle's
+# ------------------------------------------------------------------------------------------------
+def _tokens_at_ratio(U64, targets, eps32, seed):
+    """fp32 tokens x = U a + sigma n whose residual ratio w.r.t. the STORED basis (as the oracle computes it from
+    the fp32-rounded token) is the given target, found by bisection on sigma."""
+    rng = np.random.default_rng(seed)
+    d, k = U64.shape
+    lam = np.arange(1, k + 1, dtype=np.float64) ** -1.5
+    X = np.empty((len(targets), d), dtype=np.float32)
+    got = np.empty(len(targets))
+    for t, target in enumerate(targets):
+        a = rng.standard_normal(k) * np.sqrt(lam)
+        n = rng.standard_normal(d)
+        for _ in range(2):
+            n = n - U64 @ (U64.T @ n)
+        n /= np.linalg.norm(n)
+        base = U64 @ a
+
+        def rho(sig):
+            x = (base + sig * n).astype(np.float32)
+            _, _, rn, xn = O.project(U64, x[None, :].astype(np.float64))
+            return float(rn[0] / xn[0]), x
+
+        lo, hi = 0.0, 10.0 * np.linalg.norm(a)
+        for _ in range(80):
+            mid = 0.5 * (lo + hi)
+            if rho(mid)[0] < target:
+                lo = mid
+            else:
+                hi = mid
+        got[t], X[t] = rho(hi)
+    return X, got
+
+
+@pytest.mark.parametrize("d,k,m,B", [(2048, 128, 520, 1), (2048, 128, 520, 16), (1024, 64, 512, 300)])
+def test_tokens_next_to_the_gate_threshold(gsi, pu, d, k, m, B):
+    offsets = np.array([1e-6, -1e-6, 5e-5, -5e-5, 1.2e-4, -1.2e-4, 3e-4, -3e-4, 2e-3, -2e-3])
+    w = wl.tiny(d, k, m, len(offsets), 0, seed=7000 + d + B, wdtype="bf16")
+    g = w.groups[0]
+    eps32 = float(np.float32(w.eps))
+    U64 = O.widen(g.U, w.wdtype)
+    X, got = _tokens_at_ratio(U64, eps32 + offsets, eps32, seed=7100 + B)
+    assert np.all(np.abs(got - (eps32 + offsets)) < 2e-7), "calibration missed its targets"
+    reps = -(-B // len(offsets))
+    g.X = np.ascontiguousarray(np.tile(X, (reps, 1))[:B] if B > 1 else X)
+    T = g.X.shape[0]
+    say(f"case threshold d={d} k={k} m={m} B={B}: ratios eps + {offsets.tolist()}")
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    blocks = [(t, t + 1) for t in range(T)] if B == 1 else [(0, T)]
+    pu.check_group(w, g, blocks, dg, og)
+    # what the band rule was given to decide: the device's decisions on the tokens inside and outside the band
+    res = pu.run_separate_calls(dg, w.eps)
+    ref = og.run()
+    mask = res["mask"].cpu().numpy()
+    inside = np.abs(ref["rho"] - eps32) < pu.BAND
+    assert inside.sum() >= 4 * (T // len(offsets)) and (~inside).sum() >= 6 * (T // len(offsets))
+    assert np.array_equal(mask[~inside], ref["mask"][~inside])
+    say(f"  in-band tokens: device {mask[inside].tolist()[:8]} oracle {ref['mask'][inside].tolist()[:8]}")
