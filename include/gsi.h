@@ -183,15 +183,17 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
 int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                            int64_t B, float eps, void* stream);
 
-/* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition
- * the two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start
- * and stop timestamps of the dispatch of the call's single-token kernel (for B == 1 one launch evaluates the
- * projections, the gates and every map of up to four inputs), so hipEventElapsedTime(begin, end) is that
- * kernel's execution time as a profiler reports it.  If a call needs several such launches the events time
- * the last one; for B != 1 the events are not recorded. */
+/* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition the
+ * two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start and stop
+ * timestamps of the dispatch of ONE of the single-token kernels of the call, so hipEventElapsedTime(begin, end) is
+ * that kernel's execution time as a profiler reports it.  which_kernel: 0 = the partial projection (reads U),
+ * 1 = the residual + image-row launch (reads U again and every image M), 2 = the weight-streaming launch (gates;
+ * rows of W of the fired inputs' maps; for inputs with GSI_INPUT_FUSED_KERNEL: the fused kernel).  If a call
+ * needs several launches of that kernel (more than 16 inputs or maps) the events time the last one; for B != 1
+ * the events are not recorded. */
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
-                          int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
-                          void* ev_linear_end);
+                          int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, int which_kernel,
+                          void* ev_begin, void* ev_end);
 
 /* Dense baseline for a whole stack: Y = W X for every map, all maps in one launch (Section 3.1,
  * the computation the method replaces).  Uses only W, Y, m, wdtype, input_id of each map and X, d,

@@ -549,7 +549,7 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
-                            hipEvent_t ev_begin, hipEvent_t ev_end);
+                            hipEvent_t ev_begin, hipEvent_t ev_end, int which = 2);
 
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream) {
@@ -579,11 +579,13 @@ int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_i
 }
 
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
-                          int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, void* ev_linear_begin,
-                          void* ev_linear_end) {
-  if (!ev_linear_begin || !ev_linear_end) return fail(GSI_ERR_NULL, "gsi_layer_stack_timed: an event is NULL");
+                          int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, int which_kernel,
+                          void* ev_begin, void* ev_end) {
+  if (!ev_begin || !ev_end) return fail(GSI_ERR_NULL, "gsi_layer_stack_timed: an event is NULL");
+  if (which_kernel < 0 || which_kernel > 2)
+    return fail(GSI_ERR_SHAPE, "gsi_layer_stack_timed: which_kernel = %d is not 0, 1 or 2", which_kernel);
   return layer_stack_impl("gsi_layer_stack_timed", maps, n_maps, inputs, n_inputs, B, eps, ws, ws_bytes, stream,
-                          static_cast<hipEvent_t>(ev_linear_begin), static_cast<hipEvent_t>(ev_linear_end));
+                          static_cast<hipEvent_t>(ev_begin), static_cast<hipEvent_t>(ev_end), which_kernel);
 }
 
 size_t gsi_dense_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
@@ -671,7 +673,7 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
-                            hipEvent_t ev_begin, hipEvent_t ev_end) {
+                            hipEvent_t ev_begin, hipEvent_t ev_end, int which) {
   if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
   if (n_maps > 0) GSI_REQUIRE_PTR(maps);
   if (n_inputs > 0) GSI_REQUIRE_PTR(inputs);
@@ -898,7 +900,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         pb.B = (int)B;
         auto flush = [&]() -> hipError_t {
           if (pb.n == 0) return hipSuccess;
-          hipError_t e = gsi::decode_project_launch(pb, dt, md == kVecGate, md == kVecGate, eps, s, &ib);
+          hipError_t e = gsi::decode_project_launch(pb, dt, md == kVecGate, md == kVecGate, eps, s, &ib, which, ev_begin,
+                                                    ev_end);
           std::memset(&pb, 0, sizeof(pb));
           std::memset(&ib, 0, sizeof(ib));
           pb.B = (int)B;
@@ -964,7 +967,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       for (int dt = 0; dt < 2; ++dt) {
         LinBatcher bt;
         bt.wdtype = dt; bt.s = s;
-        bt.e0 = ev_begin; bt.e1 = ev_end;
+        if (which == 2) { bt.e0 = ev_begin; bt.e1 = ev_end; }
         bt.reset(B, 0, ig, eps);
         for (int j : mready) {
           const gsi_map_desc& mp = maps[j];

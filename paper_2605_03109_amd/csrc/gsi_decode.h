@@ -7,7 +7,7 @@
 
 namespace gsi {
 
-constexpr int kMaxTasks = 8;        // tasks (and input groups) per launch
+constexpr int kMaxTasks = 16;       // tasks (and input groups) per launch
 constexpr int kTokTile = 4;         // tokens processed together by the projection / image kernels
 constexpr int kColBlock = 64;       // columns of U per workgroup in the partial projection
 constexpr int kPartSlabs = 32;      // row slabs of U per input in the partial projection, upper bound (= partials per c_j)
@@ -111,8 +111,11 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
 // partial projection + residual (+ norms, + gate): with_norms = false leaves the norms to the
 // single-token linear kernel (which reads part_n itself)
 // `img` (single token only): image maps whose workgroups ride in the residual launch
+// e0 / e1 (optional, single token): events that take the start / stop timestamps of the dispatch of the partial
+// projection (timed == 0) or of the residual + image launch (timed == 1)
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
-                                 hipStream_t s, ImgBatch* img = nullptr);
+                                 hipStream_t s, ImgBatch* img = nullptr, int timed = -1, hipEvent_t e0 = nullptr,
+                                 hipEvent_t e1 = nullptr);
 // stand-alone image launch for one token: y = M c with c read from C (tasks' C set, part_c null)
 hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s);
 // norms (and gate) of tasks whose part_n / b_slabs / rnorm / xnorm (mask, fired_idx, n_fired) are set

@@ -218,6 +218,16 @@ hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEven
     total += (int)ceil_div(lb.t[i].m, kRowsPerBlock);
   }
   const size_t smem = tile_smem(lb);
+  // one activation vector of up to kMaxLinD floats beside the kernels' static LDS: more than the default 64 KB
+  static const hipError_t attr = [] {
+    const int bytes = kMaxLinD * (int)sizeof(float);
+    hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dense_rows<BF16>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&dense_rows<F32>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gated_rows<BF16>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    if (e == hipSuccess) e = hipFuncSetAttribute(reinterpret_cast<const void*>(&gated_rows<F32>), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+    return e;
+  }();
+  if (attr != hipSuccess) return attr;
   if (lb.dense) {
     if (wdtype == GSI_BF16) dense_rows<BF16><<<total, kBlock, smem, s>>>(lb);
     else dense_rows<F32><<<total, kBlock, smem, s>>>(lb);

@@ -14,6 +14,8 @@
 // residual launch finds the basis in the L2 the partial projection filled.
 //
 // All reductions have a fixed order: results are bit-identical run to run.
+#include <hip/hip_ext.h>
+
 #include <algorithm>
 
 #include "gsi_decode.h"
@@ -467,7 +469,7 @@ hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s) {
 }
 
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
-                                 hipStream_t s, ImgBatch* img) {
+                                 hipStream_t s, ImgBatch* img, int timed, hipEvent_t e0, hipEvent_t e1) {
   // tasks of a decode batch that take the matrix-core kernels go in a launch set of their own
   if (pb.B > 1) {
     ProjBatch tile_pb = pb, rest = pb;
@@ -519,7 +521,12 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
   }
   ib.total = ti;
   if (udtype == GSI_BF16) {
-    if (pb.B == 1) {
+    if (pb.B == 1 && e0 && e1 && (timed == 0 || timed == 1)) {  // measurements: the events take a dispatch's timestamps
+      if (timed == 0) hipExtLaunchKernelGGL((proj_partial<BF16, 1>), dim3(ta), dim3(kBlock), 0, s, e0, e1, 0, pb);
+      else proj_partial<BF16, 1><<<ta, kBlock, 0, s>>>(pb);
+      if (timed == 1) hipExtLaunchKernelGGL((proj_residual<BF16, 1>), dim3(tb + ti), dim3(kBlock), 0, s, e0, e1, 0, pb, ib);
+      else proj_residual<BF16, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
+    } else if (pb.B == 1) {
       proj_partial<BF16, 1><<<ta, kBlock, 0, s>>>(pb);
       proj_residual<BF16, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
     } else {

@@ -65,7 +65,8 @@ def test_small_and_odd_shapes(gsi, pu, wdtype, d, k, m, T, nf):
 @pytest.mark.parametrize("wdtype", ["bf16", "f32"])
 @pytest.mark.parametrize("d,k,m,T,nf", [(1024, 64, 520, 9, 3), (776, 72, 1000, 5, 2), (4096, 256, 1032, 6, 2),
                                         (2048, 128, 264, 33, 7), (4096, 512, 512, 3, 1), (8192, 32, 300, 2, 1),
-                                        (16384, 512, 520, 3, 1), (16384, 64, 264, 3, 1), (4160, 128, 264, 4, 2)])
+                                        (16384, 512, 520, 3, 1), (16384, 64, 264, 3, 1), (4160, 128, 264, 4, 2),
+                                        (16384, 64, 264, 4, 1)])  # (the last: four tokens through the d = 16384 LDS limit)
 def test_mid_shapes(gsi, pu, wdtype, d, k, m, T, nf):
     w = wl.tiny(d, k, m, T, nf, seed=2000 + d + k + m, wdtype=wdtype)
     say(f"case mid d={d} k={k} m={m} T={T} nf={nf} {wdtype}")
@@ -361,18 +362,19 @@ def test_timed_stack_and_dense_stack_match_plain_calls(gsi, pu):
     torch.cuda.synchronize()
     plain = [m["Y"].clone() for m in st.maps_t]
     plain_c = [i["C"].clone() for i in st.inputs_t]
-    for m in st.maps_t:
-        m["Y"].zero_()
-    for t in range(w.T):
-        st.refresh(token_offset=t, B=1)
-        st.run_timed(e0, e1)
-    torch.cuda.synchronize()
-    ms = ct.c_float()
-    assert hip.hipEventElapsedTime(ct.byref(ms), e0, e1) == 0 and 0.0 < ms.value < 50.0
-    for a, m in zip(plain, st.maps_t):
-        assert torch.equal(a, m["Y"])
-    for a, i in zip(plain_c, st.inputs_t):
-        assert torch.equal(a, i["C"])
+    for which in (0, 1, 2):  # the events bracket the partial projection, the residual + image launch, the W stream
+        for m in st.maps_t:
+            m["Y"].zero_()
+        for t in range(w.T):
+            st.refresh(token_offset=t, B=1)
+            st.run_timed(e0, e1, which=which)
+        torch.cuda.synchronize()
+        ms = ct.c_float()
+        assert hip.hipEventElapsedTime(ct.byref(ms), e0, e1) == 0 and 0.0 < ms.value < 50.0, which
+        for a, m in zip(plain, st.maps_t):
+            assert torch.equal(a, m["Y"])
+        for a, i in zip(plain_c, st.inputs_t):
+            assert torch.equal(a, i["C"])
     # dense stack, one token and a batch
     for B in (1, 3):
         st.refresh(token_offset=0, B=B)
