@@ -37,14 +37,13 @@ BLOCK = [("attn_in", 4096, [("q", 4096), ("k", 4096), ("v", 4096)]),
          ("mlp_in", 4096, [("fc_in", 16384)]),
          ("mlp_hidden", 16384, [("fc_out", 4096)])]
 MAPS_PER_LAYER = sum(len(m) for _, _, m in BLOCK)
-TIMED_GROUP_LAYERS = 4  # the library batches 16 inputs per launch: four layers share each launch
 
 KERNELS = {
-    0: "gsi::proj_partial<BF16> (partial c = U^T x of 16 inputs, one launch)",
-    1: "gsi::proj_residual<BF16> (r = x - U c, norms and the image rows y = M c of 16 inputs / 24 maps, one launch)",
-    2: "gsi::stream_rows<BF16, dense=false> (gates of 16 inputs, W r of every fired map, one launch)",
+    0: "gsi::proj_stage<BF16> (one launch: partial c = U^T x of 16 inputs; c of the 16 before; r = x - U c, norm shares "
+       "and the image rows y = M c of the 16 before those; gates of the 16 before those)",
+    1: "gsi::stream_rows<BF16, dense=false> (one launch: W r of every fired map of 16 inputs)",
 }
-PROFILE_KEY = {0: "proj_partial", 1: "proj_residual", 2: "stream_rows"}
+PROFILE_KEY = {0: "proj_stage", 1: "stream_rows"}
 
 
 def log(msg: str) -> None:
@@ -316,70 +315,75 @@ def main() -> int:
     head, fired = cell_numbers(S, sec_gated * 1e6 / args.steps, args.steps)
     dense_bytes = S.bytes([0.0] * S.n_in)[0]
 
-    # ---- roofline of the dominant kernel: each of the three launches of a step timed by its own dispatch
-    #      timestamps (HIP events given to the launch), on calls of four layers = one launch of each kernel
+    # ---- roofline of the dominant kernel: every launch of a step timed by its own dispatch timestamps (HIP events
+    #      given to that launch), one launch per call of the whole step
     roofline, kernels = None, None
     if not args.no_roofline and not args.fused:
-        ni, nm = len(BLOCK) * TIMED_GROUP_LAYERS, MAPS_PER_LAYER * TIMED_GROUP_LAYERS
-        groups = L // TIMED_GROUP_LAYERS
-        K = min(T, 48)
+        SET = 16                                  # inputs per launch of the staged kernel
+        nsets = (S.n_in + SET - 1) // SET
+        n_launch = {0: nsets + 3, 1: nsets}       # launches per step: staged kernel, weight streaming
+        K = min(T, 24)
         evs = HipEvents(2)
         s0 = torch.cuda.current_stream().cuda_stream
-        dur = np.zeros((3, groups, K))
-        nbytes = np.zeros((3, groups, K))
         fired_np = fired.cpu().numpy()
-        sub = []
-        for t in range(K):
-            mp_all, inp_all = S.tabs[t]
-            row = []
-            for g in range(groups):
-                mp = (gsi.MapDesc * nm)()
-                inp = (gsi.InputDesc * ni)()
-                ctypes.memmove(mp, ctypes.byref(mp_all, g * nm * ctypes.sizeof(gsi.MapDesc)), ctypes.sizeof(mp))
-                ctypes.memmove(inp, ctypes.byref(inp_all, g * ni * ctypes.sizeof(gsi.InputDesc)), ctypes.sizeof(inp))
-                for j in range(nm):
-                    mp[j].input_id -= g * ni
-                row.append((mp, inp))
-            sub.append(row)
-        for which in range(3):
+        k = args.k
+
+        def set_inputs(g):
+            return range(g * SET, min(S.n_in, (g + 1) * SET)) if 0 <= g < nsets else range(0)
+
+        def stage_bytes(idx):  # launch idx: partial projections of set idx, residuals + image rows of set idx - 2
+            b = 0
+            for i in set_inputs(idx):       # the basis once, x
+                d = BLOCK[i % len(BLOCK)][1]
+                b += d * k * 2 + d * 4
+            for i in set_inputs(idx - 2):   # the images, x again, c read; r and y written
+                _, d, mpl = BLOCK[i % len(BLOCK)]
+                b += sum(m * k * 2 + m * 4 for _, m in mpl) + d * 4 + k * 4 + d * 4
+            return b
+
+        def stream_bytes(idx, t):  # W of a fired input's maps, r, y read and written
+            b = 0
+            for i in set_inputs(idx):
+                _, d, mpl = BLOCK[i % len(BLOCK)]
+                if fired_np[i, t]:
+                    b += sum(m * d * 2 + 2 * m * 4 for _, m in mpl) + d * 4
+            return b
+
+        dur = {w: np.zeros((n_launch[w], K)) for w in (0, 1)}
+        nbytes = {w: np.zeros((n_launch[w], K)) for w in (0, 1)}
+        for which in (0, 1):
             for t in range(K):
-                for g in range(groups):
-                    mp, inp = sub[t][g]
-                    rc = gsi.lib.gsi_layer_stack_timed(mp, nm, inp, ni, 1, S.ceps, S.ws_ptr, S.ws_n, s0, which,
-                                                       evs.ev[0], evs.ev[1])
+                mp, inp = S.tabs[t]
+                for idx in range(n_launch[which]):
+                    rc = gsi.lib.gsi_layer_stack_timed(mp, S.n_mp, inp, S.n_in, 1, S.ceps, S.ws_ptr, S.ws_n, s0, which,
+                                                       idx, evs.ev[0], evs.ev[1])
                     if rc:
                         raise gsi.GsiError(rc, gsi.last_error())
                     torch.cuda.synchronize()
-                    dur[which, g, t] = evs.elapsed_ms(0, 1) * 1e-3
-                    b = 0.0
-                    for i in range(ni):
-                        _, d, mpl = BLOCK[i % len(BLOCK)]
-                        if which == 0:    # the basis once, x
-                            b += d * args.k * 2 + d * 4
-                        elif which == 1:  # the images, x again, c, r and y written
-                            b += sum(m * args.k * 2 + m * 4 for _, m in mpl) + d * 4 + args.k * 4 + d * 4
-                        elif fired_np[g * ni + i, t]:  # W of a fired input's maps, r, y read and written
-                            b += sum(m * d * 2 + 2 * m * 4 for _, m in mpl) + d * 4
-                    nbytes[which, g, t] = b
+                    dur[which][idx, t] = evs.elapsed_ms(0, 1) * 1e-3
+                    nbytes[which][idx, t] = stage_bytes(idx) if which == 0 else stream_bytes(idx, t)
         evs.close()
         kernels = {}
-        for which in range(3):
+        for which in (0, 1):
             d_all, b_all = dur[which].ravel(), nbytes[which].ravel()
-            if which == 2:  # launches in which no gate fired end after the gate and move no weight byte
+            if which == 1:  # launches in which no gate fired end after reading the counts and move no weight byte
                 live = b_all > 0
                 entry = {"launches": int(live.sum()), "launches_without_fired_gate": int((~live).sum()),
                          "unfired_launch_us": round(float(d_all[~live].mean() * 1e6), 2) if (~live).any() else None}
                 d_use, b_use = (d_all[live], b_all[live]) if live.any() else (d_all, b_all)
             else:
-                entry = {"launches": int(d_all.size)}
+                entry = {"launches": int(d_all.size), "launches_per_step": n_launch[0],
+                         "first_launch_us": round(float(dur[0][0].mean() * 1e6), 2),
+                         "full_launch_us": round(float(dur[0][2:-3].mean() * 1e6), 2) if nsets > 2 else None,
+                         "gate_only_launch_us": round(float(dur[0][-1].mean() * 1e6), 2)}
                 d_use, b_use = d_all, b_all
-            ach = float(b_use.mean() / d_use.mean() / 1e9) if d_use.size else 0.0
+            ach = float(b_use.sum() / d_use.sum() / 1e9) if d_use.size else 0.0
             entry.update({"kernel": KERNELS[which], "avg_launch_us": round(float(d_use.mean() * 1e6), 2),
                           "avg_algorithmic_bytes": round(float(b_use.mean())), "achieved_GBs": round(ach, 1),
                           "frac_of_hbm_peak": round(ach / HBM_PEAK_GBS, 4),
                           "us_per_step_total": round(float(d_all.sum() / K * 1e6), 1)})
             kernels[PROFILE_KEY[which]] = entry
-        dom = max(range(3), key=lambda w: kernels[PROFILE_KEY[w]]["us_per_step_total"])
+        dom = max((0, 1), key=lambda w: kernels[PROFILE_KEY[w]]["us_per_step_total"])
         e = kernels[PROFILE_KEY[dom]]
         tag = f"opt_stack_{L}layers_k{args.k}_fire{int(round(args.fire * 100))}_decode"
         roofline = {"bound": "hbm", "kernel": e["kernel"], "achieved": e["achieved_GBs"], "peak": HBM_PEAK_GBS,

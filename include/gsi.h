@@ -185,15 +185,16 @@ int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_i
 
 /* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition the
  * two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start and stop
- * timestamps of the dispatch of ONE of the single-token kernels of the call, so hipEventElapsedTime(begin, end) is
- * that kernel's execution time as a profiler reports it.  which_kernel: 0 = the partial projection (reads U),
- * 1 = the residual + image-row launch (reads U again and every image M), 2 = the weight-streaming launch (gates;
- * rows of W of the fired inputs' maps; for inputs with GSI_INPUT_FUSED_KERNEL: the fused kernel).  If a call
- * needs several launches of that kernel (more than 16 inputs or maps) the events time the last one; for B != 1
- * the events are not recorded. */
+ * timestamps of the dispatch of ONE of the single-token launches of the call, so hipEventElapsedTime(begin, end)
+ * is that launch's execution time as a profiler reports it.  which_kernel: 0 = the staged projection kernel
+ * (partial projections of a set of up to 16 inputs; residuals, gates and image rows of the set before; also the
+ * fused kernel of inputs with GSI_INPUT_FUSED_KERNEL), 1 = the weight-streaming kernel (rows of W of the fired
+ * inputs' maps).  launch_index counts the launches of that kind in the order the call enqueues them, from 0.
+ * If the call makes fewer launches of that kind (always so for B != 1) it is still enqueued in full, the events
+ * are not recorded and GSI_ERR_SHAPE is returned. */
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                           int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, int which_kernel,
-                          void* ev_begin, void* ev_end);
+                          int launch_index, void* ev_begin, void* ev_end);
 
 /* Dense baseline for a whole stack: Y = W X for every map, all maps in one launch (Section 3.1,
  * the computation the method replaces).  Uses only W, Y, m, wdtype, input_id of each map and X, d,

@@ -363,20 +363,21 @@ struct LinBatcher {
   int64_t B;
   hipEvent_t e0 = nullptr, e1 = nullptr;  // optional dispatch-timestamp events for the launches of this batcher
   gsi::ImgBatch sib;                      // single token: image maps y = M c not yet written by an earlier launch
-  void reset(int64_t B_, int dense, int inline_gate, float eps) {
+  int* n_launches = nullptr;               // the launch whose count equals timed_index gets the events
+  int timed_index = -1;
+  void reset(int64_t B_, int dense) {
     B = B_;
     clear(lb, B_);
-    lb.dense = dense; lb.inline_gate = inline_gate; lb.eps = eps;
+    lb.dense = dense;
     std::memset(&sib, 0, sizeof(sib));
   }
   hipError_t flush() {
     if (lb.n == 0) return hipSuccess;
     if (sib.n > 0)  // the image term first: the weight-streaming launch adds W r to it
       if (hipError_t ei = gsi::decode_image_launch(sib, wdtype, s); ei != hipSuccess) return ei;
-    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s, e0, e1);
-    const int dense = lb.dense, ig = lb.inline_gate;
-    const float eps = lb.eps;
-    reset(B, dense, ig, eps);
+    const bool timed = n_launches && (*n_launches)++ == timed_index;
+    hipError_t e = gsi::decode_linear_launch(lb, wdtype, s, timed ? e0 : nullptr, timed ? e1 : nullptr);
+    reset(B, lb.dense);
     return e;
   }
   hipError_t add(int gkey, const gsi::LinGroup& gd, const void* W, const void* M, float* Y, int64_t m,
@@ -390,7 +391,7 @@ struct LinBatcher {
         if (trial.ng == gsi::kMaxTasks) gi = -2;
         else { gi = trial.ng++; trial.g[gi] = gd; }
       }
-      if (gi >= 0 && trial.n < gsi::kMaxTasks) {
+      if (gi >= 0 && trial.n < gsi::kMaxLinTasks) {
         gsi::LinTask& t = trial.t[trial.n++];
         t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi; t.part = part; t.slices = 0;
         if (gsi::decode_linear_fits(trial)) {
@@ -457,7 +458,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
       aligned(C, 16) && aligned(R, 16)) {
     LinBatcher bt;
     bt.wdtype = wdtype; bt.s = s;
-    bt.reset(B, 0, 0, 0.f);
+    bt.reset(B, 0);
     gsi::LinGroup gd;
     std::memset(&gd, 0, sizeof(gd));
     gd.C = C; gd.R = R; gd.fired_idx = fired_idx; gd.n_fired = n_fired;
@@ -549,7 +550,8 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
-                            hipEvent_t ev_begin, hipEvent_t ev_end, int which = 2);
+                            hipEvent_t ev_begin, hipEvent_t ev_end, int which = -1, int launch_index = 0,
+                            int* n_launches = nullptr);
 
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream) {
@@ -580,12 +582,20 @@ int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_i
 
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                           int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, int which_kernel,
-                          void* ev_begin, void* ev_end) {
+                          int launch_index, void* ev_begin, void* ev_end) {
   if (!ev_begin || !ev_end) return fail(GSI_ERR_NULL, "gsi_layer_stack_timed: an event is NULL");
-  if (which_kernel < 0 || which_kernel > 2)
-    return fail(GSI_ERR_SHAPE, "gsi_layer_stack_timed: which_kernel = %d is not 0, 1 or 2", which_kernel);
-  return layer_stack_impl("gsi_layer_stack_timed", maps, n_maps, inputs, n_inputs, B, eps, ws, ws_bytes, stream,
-                          static_cast<hipEvent_t>(ev_begin), static_cast<hipEvent_t>(ev_end), which_kernel);
+  if (which_kernel < 0 || which_kernel > 1)
+    return fail(GSI_ERR_SHAPE, "gsi_layer_stack_timed: which_kernel = %d is not 0 or 1", which_kernel);
+  if (launch_index < 0) return fail(GSI_ERR_SHAPE, "gsi_layer_stack_timed: launch_index = %d < 0", launch_index);
+  int n = 0;
+  const int rc = layer_stack_impl("gsi_layer_stack_timed", maps, n_maps, inputs, n_inputs, B, eps, ws, ws_bytes, stream,
+                                  static_cast<hipEvent_t>(ev_begin), static_cast<hipEvent_t>(ev_end), which_kernel,
+                                  launch_index, &n);
+  if (rc != GSI_OK) return rc;
+  if (launch_index >= n)
+    return fail(GSI_ERR_SHAPE, "gsi_layer_stack_timed: the call made %d launches of kind %d, none has index %d (the call "
+                "itself was enqueued in full)", n, which_kernel, launch_index);
+  return GSI_OK;
 }
 
 size_t gsi_dense_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
@@ -645,7 +655,7 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
   for (int dt = 0; dt < 2; ++dt) {
     LinBatcher bt;
     bt.wdtype = dt; bt.s = s;
-    bt.reset(B, 1, 0, 0.f);
+    bt.reset(B, 1);
     for (int j = 0; j < n_maps; ++j) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
@@ -673,7 +683,8 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
-                            hipEvent_t ev_begin, hipEvent_t ev_end, int which) {
+                            hipEvent_t ev_begin, hipEvent_t ev_end, int which, int launch_index, int* n_launches) {
+  int n_stage_launches = 0, n_stream_launches = 0;  // counted for the timed variant
   if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
   if (n_maps > 0) GSI_REQUIRE_PTR(maps);
   if (n_inputs > 0) GSI_REQUIRE_PTR(inputs);
@@ -837,7 +848,9 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       int cur_dt = -1;
       auto flush = [&]() -> hipError_t {
         if (fa.n_chunks == 0) return hipSuccess;
-        hipError_t e = gsi::fused_launch(fa, fa_dt, s, ev_begin, ev_end);
+        const bool timed = which == 0 && n_stage_launches == launch_index;
+        ++n_stage_launches;
+        hipError_t e = gsi::fused_launch(fa, fa_dt, s, timed ? ev_begin : nullptr, timed ? ev_end : nullptr);
         fa.n_chunks = 0;
         return e;
       };
@@ -891,39 +904,72 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       if (hipError_t e = close_chunk(); e != hipSuccess) return hip_fail(e, fn);
       if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
     }
-    for (int md = kVecGate; md <= kVecInline; ++md) {
-      for (int dt = 0; dt < 2; ++dt) {
-        gsi::ProjBatch pb;
-        gsi::ImgBatch ib;  // image maps y = M c of these inputs share the residual launch (single token)
+    // several tokens, or a single token whose maps do not all take the weight-streaming kernel: vector projection
+    // kernels followed by the norm + gate kernel
+    for (int dt = 0; dt < 2; ++dt) {
+      gsi::ProjBatch pb;
+      std::memset(&pb, 0, sizeof(pb));
+      pb.B = (int)B;
+      auto flush = [&]() -> hipError_t {
+        if (pb.n == 0) return hipSuccess;
+        hipError_t e = gsi::decode_project_launch(pb, dt, true, true, eps, s);
         std::memset(&pb, 0, sizeof(pb));
-        std::memset(&ib, 0, sizeof(ib));
         pb.B = (int)B;
-        auto flush = [&]() -> hipError_t {
-          if (pb.n == 0) return hipSuccess;
-          hipError_t e = gsi::decode_project_launch(pb, dt, md == kVecGate, md == kVecGate, eps, s, &ib, which, ev_begin,
-                                                    ev_end);
-          std::memset(&pb, 0, sizeof(pb));
-          std::memset(&ib, 0, sizeof(ib));
-          pb.B = (int)B;
-          return e;
-        };
-        for (int i : ready) {
-          if (mode[i] != md || inputs[i].udtype != dt) continue;
-          pb.t[pb.n++] = ptask[i];
-          if (md == kVecInline) {
-            for (int j = 0; j < n_maps && ib.n < gsi::kMaxTasks; ++j) {
-              if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
-              gsi::ImgTask& it = ib.t[ib.n++];
-              it.M = maps[j].M; it.Y = maps[j].Y; it.part_c = ptask[i].part_c; it.C = nullptr;
-              it.m = (int)maps[j].m; it.k = (int)inputs[i].k; it.a_slabs = ptask[i].a_slabs;
-              it.scale = (maps[j].flags & GSI_MAP_IMAGE_FP8) ? maps[j].M_scale : nullptr;
-              img_done[j] = 1;
-            }
+        return e;
+      };
+      for (int i : ready) {
+        if (mode[i] != kVecGate || inputs[i].udtype != dt) continue;
+        pb.t[pb.n++] = ptask[i];
+        if (pb.n == gsi::kMaxTasks)
+          if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+      }
+      if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+    }
+    // single token: the staged kernel.  Launch g holds the partial projections of set g (up to kMaxTasks
+    // independent inputs), the coefficient sums of set g - 1, the residuals and image rows of set g - 2 and the
+    // gates of set g - 3.  A call of one set skips the sum stage (its residual and image workgroups add the
+    // partials themselves: the same function, the same bits).
+    for (int dt = 0; dt < 2 && B == 1; ++dt) {
+      std::vector<int> list;
+      for (int i : ready)
+        if (mode[i] == kVecInline && inputs[i].udtype == dt) list.push_back(i);
+      if (list.empty()) continue;
+      const int nsets = (int)gsi::ceil_div((int64_t)list.size(), gsi::kMaxTasks);
+      for (int g = 0; g < nsets; ++g) {  // the largest input of a set goes first so that its workgroups start first
+        auto first = list.begin() + (size_t)g * gsi::kMaxTasks;
+        auto last = (g + 1 == nsets) ? list.end() : first + gsi::kMaxTasks;
+        std::stable_sort(first, last, [&](int x, int y) {
+          return inputs[x].d * inputs[x].k > inputs[y].d * inputs[y].k;
+        });
+      }
+      auto set_size = [&](int g) {
+        return (g < 0 || g >= nsets) ? 0 : std::min<int>(gsi::kMaxTasks, (int)list.size() - g * gsi::kMaxTasks);
+      };
+      auto member = [&](int g, int q) { return list[(size_t)g * gsi::kMaxTasks + q]; };
+      const int sum_stage = nsets > 1 ? 1 : 0;
+      for (int g = 0; g < nsets + 2 + sum_stage; ++g) {
+        gsi::StageArgs a;
+        gsi::stage_clear(a, eps);
+        for (int q = 0; q < set_size(g); ++q) gsi::stage_add_part(a, ptask[member(g, q)]);
+        if (sum_stage)
+          for (int q = 0; q < set_size(g - 1); ++q) gsi::stage_add_cred(a, ptask[member(g - 1, q)]);
+        const int gr = g - 1 - sum_stage;
+        for (int q = 0; q < set_size(gr); ++q) {
+          const int i = member(gr, q);
+          const int res = gsi::stage_add_res(a, ptask[i], sum_stage != 0);
+          for (int j = 0; j < n_maps && a.ni < gsi::kMaxLinTasks; ++j) {
+            if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
+            gsi::stage_add_img(a, res, maps[j].M, maps[j].Y,
+                               (maps[j].flags & GSI_MAP_IMAGE_FP8) ? maps[j].M_scale : nullptr, (int)maps[j].m);
+            img_done[j] = 1;
           }
-          if (pb.n == gsi::kMaxTasks)
-            if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
         }
-        if (hipError_t e = flush(); e != hipSuccess) return hip_fail(e, fn);
+        for (int q = 0; q < set_size(gr - 1); ++q) gsi::stage_add_gate(a, ptask[member(gr - 1, q)]);
+        const bool timed = which == 0 && n_stage_launches == launch_index;
+        ++n_stage_launches;
+        if (hipError_t e = gsi::stage_launch(a, dt, s, timed ? ev_begin : nullptr, timed ? ev_end : nullptr);
+            e != hipSuccess)
+          return hip_fail(e, fn);
       }
     }
     for (int i : ready) {
@@ -963,42 +1009,33 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     std::vector<int> mready;
     for (int j = 0; j < n_maps; ++j)
       if (!map_done[j] && in_done[maps[j].input_id] == 1) mready.push_back(j);
-    for (int ig = 1; ig >= 0; --ig) {
-      for (int dt = 0; dt < 2; ++dt) {
-        LinBatcher bt;
-        bt.wdtype = dt; bt.s = s;
-        if (which == 2) { bt.e0 = ev_begin; bt.e1 = ev_end; }
-        bt.reset(B, 0, ig, eps);
-        for (int j : mready) {
-          const gsi_map_desc& mp = maps[j];
-          const gsi_input_desc& in = inputs[mp.input_id];
-          if (map_done[j] || map_fused[j] || mp.wdtype != dt || B == 0) continue;
-          if ((mode[mp.input_id] == kVecInline) != (ig == 1)) continue;
-          if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
-            continue;  // matrix cores below
-          if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
-              !aligned(in.R, 16) || !wx_vector_ok(in))
-            continue;
-          gsi::LinGroup gd;
-          std::memset(&gd, 0, sizeof(gd));
-          gd.C = in.C; gd.R = in.R; gd.fired_idx = in.fired_idx; gd.n_fired = in.n_fired;
-          gd.d = (int)in.d; gd.k = (int)in.k;
-          gd.wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) ? 1 : 0;
-          gd.X = in.X; gd.xdtype = in.xdtype;
-          if (ig) {
-            const gsi::ProjTask& pt = ptask[mp.input_id];
-            gd.part_n = pt.part_n; gd.b_slabs = pt.b_slabs;
-            gd.rnorm = in.rnorm; gd.xnorm = in.xnorm; gd.mask = in.mask;
-            gd.fired_idx_out = in.fired_idx; gd.n_fired_out = in.n_fired;
-          }
-          if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j], part[j],
-                                    (mp.flags & GSI_MAP_IMAGE_FP8) ? mp.M_scale : nullptr);
-              e != hipSuccess)
-            return hip_fail(e, fn);
-          map_done[j] = 2;
-        }
-        if (hipError_t e = bt.flush(); e != hipSuccess) return hip_fail(e, fn);
+    for (int dt = 0; dt < 2; ++dt) {
+      LinBatcher bt;
+      bt.wdtype = dt; bt.s = s;
+      if (which == 1) { bt.e0 = ev_begin; bt.e1 = ev_end; bt.n_launches = &n_stream_launches; bt.timed_index = launch_index; }
+      bt.reset(B, 0);
+      for (int j : mready) {
+        const gsi_map_desc& mp = maps[j];
+        const gsi_input_desc& in = inputs[mp.input_id];
+        if (map_done[j] || map_fused[j] || mp.wdtype != dt || B == 0) continue;
+        if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
+          continue;  // matrix cores below
+        if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
+            !aligned(in.R, 16) || !wx_vector_ok(in))
+          continue;
+        gsi::LinGroup gd;
+        std::memset(&gd, 0, sizeof(gd));
+        gd.C = in.C; gd.R = in.R; gd.fired_idx = in.fired_idx; gd.n_fired = in.n_fired;
+        gd.d = (int)in.d; gd.k = (int)in.k;
+        gd.wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) ? 1 : 0;
+        gd.X = in.X; gd.xdtype = in.xdtype;
+        if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j], part[j],
+                                  (mp.flags & GSI_MAP_IMAGE_FP8) ? mp.M_scale : nullptr);
+            e != hipSuccess)
+          return hip_fail(e, fn);
+        map_done[j] = 2;
       }
+      if (hipError_t e = bt.flush(); e != hipSuccess) return hip_fail(e, fn);
     }
     for (int j : mready) {
       const gsi_map_desc& mp = maps[j];
@@ -1020,6 +1057,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     }
     if (!progressed) return fail(GSI_ERR_SHAPE, "%s: src_map dependencies form a cycle", fn);
   }
+  if (n_launches) *n_launches = which == 0 ? n_stage_launches : n_stream_launches;
   return GSI_OK;
 }
 

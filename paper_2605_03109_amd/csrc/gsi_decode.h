@@ -7,7 +7,8 @@
 
 namespace gsi {
 
-constexpr int kMaxTasks = 16;       // tasks (and input groups) per launch
+constexpr int kMaxTasks = 16;       // inputs (projection tasks, input groups of the linear kernels) per launch
+constexpr int kMaxLinTasks = 24;    // maps (linear tasks, image tasks) per launch
 constexpr int kTokTile = 4;         // tokens processed together by the projection / image kernels
 constexpr int kColBlock = 64;       // columns of U per workgroup in the partial projection
 constexpr int kPartSlabs = 32;      // row slabs of U per input in the partial projection, upper bound (= partials per c_j)
@@ -15,6 +16,7 @@ constexpr int kMaxResSlabs = 512;   // row slabs per input in the residual kerne
 constexpr int kMaxK = 512;          // largest rank the vector projection kernels take
 constexpr int kRowsPerBlock = 16;   // output rows per workgroup in the batched-token linear kernels
 constexpr int kMaxLinD = 16384;     // floats of LDS one activation vector may take in the linear kernels
+constexpr int kStageMaxRows = 2048; // rows of U per workgroup in the single-token staged kernel (their activations sit in LDS)
 constexpr int kMaxSumK = 2048;      // floats of LDS all projection coefficients of a launch may take
 
 struct ProjTask {
@@ -36,6 +38,7 @@ struct ProjTask {
   int tile;                        // decode batch on the matrix cores (gsi_tile.hip) with its own slab geometry
   int b_perm;                      // residual slabs per partial-projection slab when the residual launch walks its
                                    // slabs in the XCD order of the partial projection, else 0 (filled at launch)
+  int s_rows, s_slabs;             // single token (gsi_stage.hip): rows per slab and slabs of the partial projection
 };
 
 struct ProjBatch {
@@ -57,7 +60,7 @@ struct ImgTask {
 };
 
 struct ImgBatch {
-  ImgTask t[kMaxTasks];
+  ImgTask t[kMaxLinTasks];
   int n, total;         // tasks, workgroups
 };
 
@@ -66,17 +69,10 @@ struct LinGroup {
   const float* C;
   const float* R;
   const void* X;                 // dense baseline, and the W x form of the slow path (xdtype)
-  int wx;                        // fired tokens get y = W x (Algorithm 1, line 7) instead of M c + W r
-  const int32_t* fired_idx;      // read when the gate is not evaluated in the kernel
+  const int32_t* fired_idx;
   const int32_t* n_fired;
-  // gate evaluated inside the single-token kernel from the residual kernel's partial norms:
-  const float* part_n;
-  float* rnorm;
-  float* xnorm;
-  uint8_t* mask;
-  int32_t* fired_idx_out;
-  int32_t* n_fired_out;
-  int d, k, b_slabs, xdtype;
+  int wx;                        // fired tokens get y = W x (Algorithm 1, line 7) instead of M c + W r
+  int d, k, xdtype;
 };
 
 struct LinTask {
@@ -90,14 +86,12 @@ struct LinTask {
 
 struct LinBatch {
   LinGroup g[kMaxTasks];
-  LinTask t[kMaxTasks];
-  int blk_begin[kMaxTasks];        // several-token kernels: first workgroup of each task
-  int blk_begin2[kMaxTasks];       // matrix-core kernel: first image-term workgroup of each task
+  LinTask t[kMaxLinTasks];
+  int blk_begin[kMaxLinTasks];     // several-token kernels: first workgroup of each task
+  int blk_begin2[kMaxLinTasks];    // matrix-core kernel: first image-term workgroup of each task
   int tile_split;                  // ... first image-term workgroup of the launch
   int n, ng, B;
-  int inline_gate;           // single-token kernel: evaluate the gate from part_n (and publish it)
   int dense;                 // y = W x, no image term
-  float eps;
 };
 
 // eligibility of the vector kernels for a shape / alignment (else the generic kernels run)
@@ -111,11 +105,8 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
 // partial projection + residual (+ norms, + gate): with_norms = false leaves the norms to the
 // single-token linear kernel (which reads part_n itself)
 // `img` (single token only): image maps whose workgroups ride in the residual launch
-// e0 / e1 (optional, single token): events that take the start / stop timestamps of the dispatch of the partial
-// projection (timed == 0) or of the residual + image launch (timed == 1)
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
-                                 hipStream_t s, ImgBatch* img = nullptr, int timed = -1, hipEvent_t e0 = nullptr,
-                                 hipEvent_t e1 = nullptr);
+                                 hipStream_t s, ImgBatch* img = nullptr);
 // stand-alone image launch for one token: y = M c with c read from C (tasks' C set, part_c null)
 hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s);
 // norms (and gate) of tasks whose part_n / b_slabs / rnorm / xnorm (mask, fired_idx, n_fired) are set
@@ -136,6 +127,80 @@ void tile_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws);
 hipError_t tile_project_launch(ProjBatch& pb, bool with_norms, bool with_gate, float eps, hipStream_t s);
 bool tile_rows_ok(const LinBatch& lb, int wdtype);
 hipError_t tile_rows_launch(LinBatch& lb, hipStream_t s);
+
+// ---- single token: projection, residual, image rows and gate as stages of one kernel (gsi_stage.hip) -------
+// A launch carries up to five kinds of workgroups, each kind working on a different set of independent inputs:
+// partial projections, the sums of the partials, residual slabs and image rows, gates.  Consecutive sets overlap
+// and nothing inside a launch waits for anything else in it.
+struct StagePart {        // partial projection c = U^T x of one input over row slabs
+  const void* U;
+  const void* X;
+  float* part_c;          // [slabs][k]
+  int d, k, rows;         // rows per slab
+  int slabs_x;            // slabs | xdtype << 16
+};
+
+struct StageCRed {        // c = sum of the partials in fixed slab order, one workgroup per input
+  const float* part_c;
+  float* C;
+  int k, slabs;
+};
+
+struct StageRes {         // r = x - U c, and the slab shares of |r|^2, |x|^2, of one input over row slabs
+  const void* U;
+  const void* X;
+  const float* part_c;    // null: c is read from C; else c is the sum of these partials and slab 0 writes C
+  float* C;
+  float* R;
+  float* part_n;          // [b_slabs][2]
+  int d, k, b_rows, b_slabs;
+  int a_slabs_x;          // slabs of the partial projection | xdtype << 16
+  int pad;
+};
+
+struct StageImg {         // image rows y = M c of one map
+  const void* M;
+  float* Y;
+  const float* scale;     // E4M3 image: row scales; else null
+  int m;                  // rows
+  int blk_res;            // first workgroup | index of the input among the launch's StageRes << 24
+};
+
+struct StageGate {        // |r|, |x| from the slab shares and Eq. (gate) of one input
+  const float* part_n;
+  float* rnorm;
+  float* xnorm;
+  uint8_t* mask;
+  int32_t* fired_idx;
+  int32_t* n_fired;
+  int b_slabs, pad;
+};
+
+struct StageArgs {
+  StagePart a[kMaxTasks];
+  StageCRed cr[kMaxTasks];
+  StageRes b[kMaxTasks];
+  StageImg im[kMaxLinTasks];
+  StageGate g[kMaxTasks];
+  int a_begin[kMaxTasks];  // first workgroup of each partial-projection task (relative to the role's first)
+  int b_begin[kMaxTasks];
+  int na, ncr, nb, ni, ng;
+  int a_total, b_total, i_total;  // workgroups per role; grid order: residual slabs, partial projections, image
+                                  // rows, coefficient sums and gates (one workgroup each)
+  float eps;
+};
+static_assert(sizeof(StageArgs) <= 4096, "kernel arguments are limited to 4 KB");
+
+// rows per slab and slabs of the single-token partial projection
+void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs);
+void stage_clear(StageArgs& a, float eps);
+void stage_add_part(StageArgs& a, const ProjTask& t);
+void stage_add_cred(StageArgs& a, const ProjTask& t);
+int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready);  // returns its index
+void stage_add_img(StageArgs& a, int res, const void* M, float* Y, const float* scale, int m);
+void stage_add_gate(StageArgs& a, const ProjTask& t);
+// e0 / e1 (optional): events that take the start / stop timestamps of the dispatch
+hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 
 // single-token persistent kernel (gsi_stream.hip)
 size_t stream_smem_bytes(const LinBatch& lb);

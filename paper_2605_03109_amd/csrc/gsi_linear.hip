@@ -15,10 +15,11 @@ namespace {
 constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
 
-__device__ __forceinline__ int find_task(const int* begin, int n, int b) {
+template <int N>
+__device__ __forceinline__ int find_task(const int (&begin)[N], int n, int b) {
   int t = 0;
 #pragma unroll
-  for (int i = 1; i < kMaxTasks; ++i)
+  for (int i = 1; i < N; ++i)
     if (i < n && b >= begin[i]) t = i;
   return t;
 }

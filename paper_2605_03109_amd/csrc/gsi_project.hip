@@ -29,10 +29,11 @@ constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
 constexpr int kResSlabRows = 64;  // rows of U per residual workgroup, lower bound
 
-__device__ __forceinline__ int find_task(const int* begin, int n, int b) {
+template <int N>
+__device__ __forceinline__ int find_task(const int (&begin)[N], int n, int b) {
   int t = 0;
 #pragma unroll
-  for (int i = 1; i < kMaxTasks; ++i)
+  for (int i = 1; i < N; ++i)
     if (i < n && b >= begin[i]) t = i;
   return t;
 }
@@ -163,25 +164,11 @@ __global__ __launch_bounds__(kBlock) void proj_partial(const ProjBatch pb) {
 }
 
 template <class T, int TB>
-__global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb, const ImgBatch ib) {
+__global__ __launch_bounds__(kBlock) void proj_residual(const ProjBatch pb) {
   constexpr int V = T::kVec;
   constexpr int PF = 4;  // row steps of U held in registers
   __shared__ __align__(16) float cs[TB][kMaxK];
   __shared__ float nr[kWaves][TB], nx[kWaves][TB];
-
-  if constexpr (TB == 1) {
-    // workgroups past the residual slabs evaluate image rows y = M c of the same inputs (they need
-    // the same partial projections and nothing else, so they share the launch)
-    if ((int)blockIdx.x >= pb.b_total) {
-      const int b = blockIdx.x - pb.b_total;
-      int ti = 0;
-#pragma unroll
-      for (int i = 1; i < kMaxTasks; ++i)
-        if (i < ib.n && b >= ib.t[i].blk_begin) ti = i;
-      image_block<T>(ib.t[ti], b - ib.t[ti].blk_begin, &cs[0][0]);
-      return;
-    }
-  }
 
   const int ti = find_task(pb.b_begin, pb.n, blockIdx.x);
   const ProjTask& p = pb.t[ti];
@@ -366,7 +353,7 @@ __global__ __launch_bounds__(kBlock) void image_rows(const ImgBatch ib) {
   const int b = blockIdx.x;
   int ti = 0;
 #pragma unroll
-  for (int i = 1; i < kMaxTasks; ++i)
+  for (int i = 1; i < kMaxLinTasks; ++i)
     if (i < ib.n && b >= ib.t[i].blk_begin) ti = i;
   image_block<T>(ib.t[ti], b - ib.t[ti].blk_begin, cs);
 }
@@ -381,7 +368,7 @@ bool decode_project_ok(int64_t d, int64_t k, int udtype, const void* U) {
   if (k % V) return false;
   const int64_t cpr = k / V;
   if (cpr > kWave || (cpr & (cpr - 1))) return false;  // chunks per row: power of two, one wave at most
-  if (k > kMaxK || d > (1 << 24)) return false;
+  if (k > kMaxK || d > (int64_t)kPartSlabs * kStageMaxRows) return false;  // 32 slabs of 2048 rows at most
   return (reinterpret_cast<uintptr_t>(U) % 16) == 0;
 }
 
@@ -416,7 +403,10 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
 
 size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype) {
   const ProjGeom g = proj_geom(d, k, udtype);
-  size_t need = align_up((size_t)g.a_slabs * B * k * 4, 256) + align_up((size_t)g.b_slabs * B * 2 * 4, 256);
+  int s_rows = 0, s_slabs = 0;
+  if (B == 1) stage_geom(d, k, udtype, s_rows, s_slabs);
+  const size_t part_slabs = (size_t)std::max(g.a_slabs, s_slabs);
+  size_t need = align_up(part_slabs * B * k * 4, 256) + align_up((size_t)g.b_slabs * B * 2 * 4, 256);
   if (tile_project_shape_ok(d, k, B, udtype)) need = std::max(need, tile_project_ws(d, k, B));
   return need;
 }
@@ -433,8 +423,11 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
   t.k = (int)k;
   t.a_rows = g.a_rows; t.a_slabs = g.a_slabs; t.a_cblocks = g.a_cblocks;
   t.b_rows = g.b_rows; t.b_slabs = g.b_slabs;
+  t.s_rows = t.s_slabs = 0;
+  if (B == 1) stage_geom(d, k, t.udtype, t.s_rows, t.s_slabs);
+  const size_t part_slabs = (size_t)std::max(g.a_slabs, t.s_slabs);
   t.part_c = reinterpret_cast<float*>(ws);
-  t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up((size_t)g.a_slabs * B * k * 4, 256));
+  t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up(part_slabs * B * k * 4, 256));
 }
 
 hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s) {
@@ -469,9 +462,31 @@ hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s) {
 }
 
 hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, bool with_gate, float eps,
-                                 hipStream_t s, ImgBatch* img, int timed, hipEvent_t e0, hipEvent_t e1) {
+                                 hipStream_t s, ImgBatch* img) {
+  if (pb.n == 0 || pb.B == 0) return hipSuccess;
+  if (pb.B == 1) {
+    // one token: the staged kernel, first the partial projections, then residuals (+ the image rows that ride along)
+    StageArgs a;
+    stage_clear(a, eps);
+    for (int i = 0; i < pb.n; ++i) stage_add_part(a, pb.t[i]);
+    if (hipError_t e = stage_launch(a, udtype, s); e != hipSuccess) return e;
+    stage_clear(a, eps);
+    for (int i = 0; i < pb.n; ++i) stage_add_res(a, pb.t[i], false);
+    if (img)
+      for (int j = 0; j < img->n; ++j) {
+        const ImgTask& it = img->t[j];
+        int res = -1;
+        for (int i = 0; i < pb.n; ++i)
+          if (pb.t[i].part_c == it.part_c) res = i;
+        if (res < 0) return hipErrorInvalidValue;
+        stage_add_img(a, res, it.M, it.Y, it.scale, it.m);
+      }
+    if (hipError_t e = stage_launch(a, udtype, s); e != hipSuccess) return e;
+    if (with_norms) proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
+    return hipGetLastError();
+  }
   // tasks of a decode batch that take the matrix-core kernels go in a launch set of their own
-  if (pb.B > 1) {
+  {
     ProjBatch tile_pb = pb, rest = pb;
     tile_pb.n = rest.n = 0;
     for (int i = 0; i < pb.n; ++i) {
@@ -510,37 +525,12 @@ hipError_t decode_project_launch(ProjBatch& pb, int udtype, bool with_norms, boo
         t.b_perm = r;
     }
   }
-  ImgBatch none;
-  none.n = 0;
-  none.total = 0;
-  ImgBatch& ib = (img && pb.B == 1) ? *img : none;
-  int ti = 0;
-  for (int i = 0; i < ib.n; ++i) {
-    ib.t[i].blk_begin = ti;
-    ti += image_blocks(ib.t[i].m, ib.t[i].k, udtype, ib.t[i].scale != nullptr);
-  }
-  ib.total = ti;
   if (udtype == GSI_BF16) {
-    if (pb.B == 1 && e0 && e1 && (timed == 0 || timed == 1)) {  // measurements: the events take a dispatch's timestamps
-      if (timed == 0) hipExtLaunchKernelGGL((proj_partial<BF16, 1>), dim3(ta), dim3(kBlock), 0, s, e0, e1, 0, pb);
-      else proj_partial<BF16, 1><<<ta, kBlock, 0, s>>>(pb);
-      if (timed == 1) hipExtLaunchKernelGGL((proj_residual<BF16, 1>), dim3(tb + ti), dim3(kBlock), 0, s, e0, e1, 0, pb, ib);
-      else proj_residual<BF16, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
-    } else if (pb.B == 1) {
-      proj_partial<BF16, 1><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<BF16, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
-    } else {
-      proj_partial<BF16, kTokTile><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<BF16, kTokTile><<<tb, kBlock, 0, s>>>(pb, ib);
-    }
+    proj_partial<BF16, kTokTile><<<ta, kBlock, 0, s>>>(pb);
+    proj_residual<BF16, kTokTile><<<tb, kBlock, 0, s>>>(pb);
   } else {
-    if (pb.B == 1) {
-      proj_partial<F32, 1><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<F32, 1><<<tb + ti, kBlock, 0, s>>>(pb, ib);
-    } else {
-      proj_partial<F32, kTokTile><<<ta, kBlock, 0, s>>>(pb);
-      proj_residual<F32, kTokTile><<<tb, kBlock, 0, s>>>(pb, ib);
-    }
+    proj_partial<F32, kTokTile><<<ta, kBlock, 0, s>>>(pb);
+    proj_residual<F32, kTokTile><<<tb, kBlock, 0, s>>>(pb);
   }
   if (with_norms) proj_norms<<<pb.n, kBlock, 0, s>>>(pb, with_gate ? 1 : 0, eps);
   return hipGetLastError();

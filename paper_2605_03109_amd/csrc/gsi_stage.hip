@@ -1,0 +1,352 @@
+// Single-token projection kernel of libgsi: Algorithm 1, lines 1-5 for ONE token, as stages of one kernel.
+//
+// A launch holds up to four kinds of 256-thread workgroups, told apart by their index:
+//   partial    one per (input, row slab): whole rows of U (contiguous slabs), partial c_j over the slab's rows, the
+//              row groups combined through LDS in a fixed order;
+//   sum        one per input: c = the partials added in slab order, written to C (calls of one set skip this
+//              stage: their residual and image workgroups add the partials themselves, with the same function);
+//   residual   one per (input, row slab): r = x - U c on the slab's rows, R, the slab's share of |r|^2, |x|^2;
+//   image      rows y = M c of the maps that read the residual inputs (gsi_image.h);
+//   gate       one per input: |r|, |x| from the slab shares in a fixed order, Eq. (gate), and what the stand-alone
+//              gate kernel would publish (rnorm, xnorm, mask, fired_idx, n_fired), so the weight kernel that
+//              follows reads one count per input.
+// Sets of inputs are independent of each other, so launch L holds the partial projections of set L, the sums of
+// set L - 1, the residuals and image rows of set L - 2 and the gates of set L - 3: the ramp and tail of one stage
+// fill with the others and a call of n sets makes n + 3 launches instead of 3 n.  Nothing inside a launch waits
+// for anything else in it: every dependency is a launch boundary.
+//
+// All sums have a fixed order: results are bit-identical run to run.
+#include <hip/hip_ext.h>
+
+#include <cstring>
+
+#include "gsi_decode.h"
+#include "gsi_device.h"
+#include "gsi_image.h"
+
+namespace gsi {
+namespace {
+
+constexpr int kBlock = 256;
+constexpr int kWaves = kBlock / kWave;
+
+template <int N>
+__device__ __forceinline__ int find_task(const int (&begin)[N], int n, int b) {
+  int t = 0;
+#pragma unroll
+  for (int i = 1; i < N; ++i)
+    if (i < n && b >= begin[i]) t = i;
+  return t;
+}
+
+template <class T>
+__device__ __forceinline__ void partial_block(const StagePart& p, int slab, float* __restrict__ red,
+                                              float* __restrict__ xs) {
+  constexpr int V = T::kVec;
+  using S = typename T::storage;
+  const int d = p.d, k = p.k;
+  const int cpr = k / V;         // lanes per row of U (a power of two, one wave at most)
+  const int rps = kBlock / cpr;  // rows per step
+  const int lsh = __builtin_ctz(cpr);
+  const int cc = threadIdx.x & (cpr - 1), ro = threadIdx.x >> lsh;
+  const int row0 = slab * p.rows;
+  const int rows = min(p.rows, d - row0);
+  const S* U = reinterpret_cast<const S*>(p.U) + (int64_t)row0 * k + cc * V;
+  const int xdtype = p.slabs_x >> 16;
+
+  float acc[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) acc[e] = 0.f;
+  int i = ro;
+  // the first batch of U goes in flight, then the slab's activations are staged in LDS (one coalesced load)
+  uint4 raw[8];
+  const bool first = i + 7 * rps < rows;
+  if (first) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+  }
+  for (int r = threadIdx.x; r < rows; r += kBlock) xs[r] = load_act(p.X, xdtype, row0 + r);
+  __syncthreads();
+  if (first) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float u[V];
+      T::widen(raw[q], u);
+      const float xv = xs[i + q * rps];
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] = fmaf(u[e], xv, acc[e]);
+    }
+    i += 8 * rps;
+  }
+  // eight (then four) row steps at a time: all loads of a batch are issued before the first use
+  for (; i + 7 * rps < rows; i += 8 * rps) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float u[V];
+      T::widen(raw[q], u);
+      const float xv = xs[i + q * rps];
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] = fmaf(u[e], xv, acc[e]);
+    }
+  }
+  for (; i + 3 * rps < rows; i += 4 * rps) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      float u[V];
+      T::widen(raw[q], u);
+      const float xv = xs[i + q * rps];
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] = fmaf(u[e], xv, acc[e]);
+    }
+  }
+  for (; i < rows; i += rps) {
+    float u[V];
+    T::load_vec(U + (int64_t)i * k, u);
+    const float xv = xs[i];
+#pragma unroll
+    for (int e = 0; e < V; ++e) acc[e] = fmaf(u[e], xv, acc[e]);
+  }
+#pragma unroll
+  for (int q = 0; q < V / 4; ++q)
+    reinterpret_cast<float4*>(red + ro * k + cc * V)[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+  __syncthreads();
+  for (int j = threadIdx.x; j < k; j += kBlock) {
+    float s = 0.f;
+    for (int g = 0; g < rps; g += 4) {  // rps is a multiple of 4: four LDS reads in flight, fixed order of adds
+      float v[4];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) v[q] = red[(g + q) * k + j];
+#pragma unroll
+      for (int q = 0; q < 4; ++q) s += v[q];
+    }
+    p.part_c[(int64_t)slab * k + j] = s;
+  }
+}
+
+// c = the partials of one input added in slab order (one workgroup)
+__device__ __forceinline__ void cred_block(const StageCRed& p) {
+  for (int j = threadIdx.x; j < p.k; j += kBlock) p.C[j] = sum_partials(p.part_c + j, p.k, p.slabs);
+}
+
+template <class T>
+__device__ __forceinline__ void residual_block(const StageRes& p, int slab, float* __restrict__ cs,
+                                               float* __restrict__ xs, float* nr, float* nx) {
+  constexpr int V = T::kVec;
+  constexpr int PF = 4;  // row steps of U held in registers
+  using S = typename T::storage;
+  const int d = p.d, k = p.k;
+  const int xdtype = p.a_slabs_x >> 16, a_slabs = p.a_slabs_x & 0xffff;
+  const int cpr = k / V;         // 16-byte chunks per row (power of two, <= 64)
+  const int rps = kBlock / cpr;  // rows per step
+  const int cc = threadIdx.x & (cpr - 1), ro = threadIdx.x >> __builtin_ctz(cpr);
+  const int row0 = slab * p.b_rows;
+  const int rows = min(p.b_rows, d - row0);
+  const int steps = (rows + rps - 1) / rps;
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const S* U = reinterpret_cast<const S*>(p.U) + (int64_t)row0 * k + cc * V;
+
+  // the slab of U goes in flight first (row index clamped: loads are unconditional), then the slab's activations
+  // (one coalesced load, staged in LDS) and the coefficients
+  uint4 upf[PF];
+#pragma unroll
+  for (int q = 0; q < PF; ++q) upf[q] = *reinterpret_cast<const uint4*>(U + (int64_t)min(q * rps + ro, rows - 1) * k);
+  for (int r = threadIdx.x; r < rows; r += kBlock) xs[r] = load_act(p.X, xdtype, row0 + r);
+  if (p.part_c) {
+    for (int j = threadIdx.x; j < k; j += kBlock) {
+      const float s = sum_partials(p.part_c + j, k, a_slabs);
+      cs[j] = s;
+      if (slab == 0) p.C[j] = s;
+    }
+  } else {
+    for (int j = threadIdx.x; j < k; j += kBlock) cs[j] = p.C[j];
+  }
+  __syncthreads();
+  float c[V];
+#pragma unroll
+  for (int e = 0; e < V; ++e) c[e] = cs[cc * V + e];
+  float ar = 0.f, ax = 0.f;
+  // every lane of a row group walks the same steps, so the cross-lane sums are convergent
+  auto row_step = [&](const uint4& raw, float x, int st) {
+    const int i = st * rps + ro;
+    float u[V];
+    T::widen(raw, u);
+    float s = 0.f;
+#pragma unroll
+    for (int e = 0; e < V; ++e) s = fmaf(u[e], c[e], s);
+    s = group_sum_rt(s, cpr);
+    if (i < rows && cc == 0) {
+      const float r = x - s;
+      p.R[row0 + i] = r;
+      ar = fmaf(r, r, ar);
+      ax = fmaf(x, x, ax);
+    }
+  };
+#pragma unroll
+  for (int q = 0; q < PF; ++q)
+    if (q < steps) row_step(upf[q], xs[min(q * rps + ro, rows - 1)], q);
+  for (int st0 = PF; st0 < steps; st0 += PF) {  // further steps, PF at a time with all loads issued first
+    uint4 u[PF];
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+      u[q] = *reinterpret_cast<const uint4*>(U + (int64_t)min((st0 + q) * rps + ro, rows - 1) * k);
+#pragma unroll
+    for (int q = 0; q < PF; ++q)
+      if (st0 + q < steps) row_step(u[q], xs[min((st0 + q) * rps + ro, rows - 1)], st0 + q);
+  }
+  const float sr = group_sum<kWave>(ar);
+  const float sx = group_sum<kWave>(ax);
+  if (lane == 0) {
+    nr[wave] = sr;
+    nx[wave] = sx;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tr = 0.f, tx = 0.f;
+    for (int w = 0; w < kWaves; ++w) {
+      tr += nr[w];
+      tx += nx[w];
+    }
+    p.part_n[slab * 2 + 0] = tr;
+    p.part_n[slab * 2 + 1] = tx;
+  }
+}
+
+// one wave: the same sums, in the same order, as the stand-alone norm kernel
+__device__ __forceinline__ void gate_block(const StageGate& g, float eps) {
+  if (threadIdx.x >= kWave) return;
+  float tr, tx;
+  wave_norm_sums(g.part_n, g.b_slabs, 1, 0, tr, tx);
+  if (threadIdx.x == 0) {
+    const float rn = sqrtf(tr), xn = sqrtf(tx);
+    const bool f = gate_fires(rn, xn, eps);
+    g.rnorm[0] = rn;
+    g.xnorm[0] = xn;
+    g.mask[0] = f ? 1 : 0;
+    if (f) g.fired_idx[0] = 0;
+    g.n_fired[0] = f ? 1 : 0;
+  }
+}
+
+template <class T>
+__global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
+  __shared__ __align__(16) float lds[kBlock * 8];  // partial: [row group][k]; residual, image: the coefficients
+  __shared__ float xs[kStageMaxRows];              // the slab's activations
+  __shared__ float nr[kWaves], nx[kWaves];
+  int b = blockIdx.x;
+  if (b < a.b_total) {
+    const int ti = find_task(a.b_begin, a.nb, b);
+    residual_block<T>(a.b[ti], b - a.b_begin[ti], lds, xs, nr, nx);
+    return;
+  }
+  b -= a.b_total;
+  if (b < a.a_total) {
+    const int ti = find_task(a.a_begin, a.na, b);
+    partial_block<T>(a.a[ti], b - a.a_begin[ti], lds, xs);
+    return;
+  }
+  b -= a.a_total;
+  if (b < a.i_total) {
+    int ti = 0;
+#pragma unroll
+    for (int i = 1; i < kMaxLinTasks; ++i)
+      if (i < a.ni && b >= (a.im[i].blk_res & 0xffffff)) ti = i;
+    const StageImg& im = a.im[ti];
+    const StageRes& r = a.b[im.blk_res >> 24];
+    ImgTask t;
+    t.M = im.M; t.Y = im.Y; t.part_c = r.part_c; t.C = r.C; t.scale = im.scale;
+    t.m = im.m; t.k = r.k; t.a_slabs = r.a_slabs_x & 0xffff; t.blk_begin = im.blk_res & 0xffffff;
+    image_block<T>(t, b - t.blk_begin, lds);
+    return;
+  }
+  b -= a.i_total;
+  if (b < a.ncr) {
+    cred_block(a.cr[b]);
+    return;
+  }
+  gate_block(a.g[b - a.ncr], a.eps);
+}
+
+}  // namespace
+
+// ------------------------------------------------------------------------------------------------
+// host side
+// ------------------------------------------------------------------------------------------------
+void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs) {
+  const int V = udtype == GSI_BF16 ? 8 : 4;
+  const int rps = kBlock / (int)(k / V);
+  // at least eight row steps per workgroup, kPartSlabs slabs at most
+  int64_t r = ceil_div(d, kPartSlabs);
+  if (r < 8 * rps) r = 8 * rps;
+  rows = (int)(ceil_div(r, rps) * rps);
+  slabs = (int)ceil_div(d, rows);
+}
+
+void stage_clear(StageArgs& a, float eps) {
+  std::memset(&a, 0, sizeof(a));
+  a.eps = eps;
+}
+
+void stage_add_part(StageArgs& a, const ProjTask& t) {
+  StagePart& p = a.a[a.na++];
+  p.U = t.U; p.X = t.X; p.part_c = t.part_c;
+  p.d = t.d; p.k = t.k; p.rows = t.s_rows; p.slabs_x = t.s_slabs | (t.xdtype << 16);
+}
+
+void stage_add_cred(StageArgs& a, const ProjTask& t) {
+  StageCRed& p = a.cr[a.ncr++];
+  p.part_c = t.part_c; p.C = t.C; p.k = t.k; p.slabs = t.s_slabs;
+}
+
+int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready) {
+  StageRes& p = a.b[a.nb];
+  p.U = t.U; p.X = t.X; p.part_c = c_ready ? nullptr : t.part_c; p.C = t.C; p.R = t.R; p.part_n = t.part_n;
+  p.d = t.d; p.k = t.k; p.b_rows = t.b_rows; p.b_slabs = t.b_slabs;
+  p.a_slabs_x = t.s_slabs | (t.xdtype << 16);
+  return a.nb++;
+}
+
+void stage_add_img(StageArgs& a, int res, const void* M, float* Y, const float* scale, int m) {
+  StageImg& im = a.im[a.ni++];
+  im.M = M; im.Y = Y; im.scale = scale; im.m = m; im.blk_res = res << 24;
+}
+
+void stage_add_gate(StageArgs& a, const ProjTask& t) {
+  StageGate& g = a.g[a.ng++];
+  g.part_n = t.part_n; g.rnorm = t.rnorm; g.xnorm = t.xnorm; g.mask = t.mask; g.fired_idx = t.fired_idx;
+  g.n_fired = t.n_fired; g.b_slabs = t.b_slabs;
+}
+
+hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  int ta = 0, tb = 0, ti = 0;
+  for (int i = 0; i < a.na; ++i) {
+    a.a_begin[i] = ta;
+    ta += a.a[i].slabs_x & 0xffff;
+  }
+  for (int i = 0; i < a.nb; ++i) {
+    a.b_begin[i] = tb;
+    tb += a.b[i].b_slabs;
+  }
+  for (int i = 0; i < a.ni; ++i) {
+    const int res = a.im[i].blk_res >> 24;
+    a.im[i].blk_res = (res << 24) | ti;
+    ti += image_blocks(a.im[i].m, a.b[res].k, dtype, a.im[i].scale != nullptr);
+    if (ti >= (1 << 24)) return hipErrorInvalidValue;
+  }
+  a.a_total = ta; a.b_total = tb; a.i_total = ti;
+  const int grid = ta + tb + ti + a.ncr + a.ng;
+  if (grid == 0) return hipSuccess;
+  if (dtype == GSI_BF16) {
+    if (e0 && e1) hipExtLaunchKernelGGL((proj_stage<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, a);
+    else proj_stage<BF16><<<grid, kBlock, 0, s>>>(a);
+  } else {
+    if (e0 && e1) hipExtLaunchKernelGGL((proj_stage<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, a);
+    else proj_stage<F32><<<grid, kBlock, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+}  // namespace gsi

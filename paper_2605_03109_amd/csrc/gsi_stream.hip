@@ -2,11 +2,9 @@
 // gate fired (Algorithm 1, lines 4 and 7), and the dense baseline y = W x, for one decode token.
 //
 // A persistent grid of two 512-thread workgroups per CU (sixteen waves per CU).  Structure of one launch:
-//   1. gate of every input group: one wave per group reduces the residual kernel's partial norms and
-//      applies Eq. (gate) (or reads the published count) -- identical arithmetic in every workgroup, so
-//      the decision is uniform across the grid without communication; workgroup 0 publishes
-//      rnorm / xnorm / mask / fired_idx / n_fired.  If nothing fired the kernel ends here: no byte of W
-//      is read;
+//   1. gate of every input group: one wave per group reads the count of fired tokens the projection launch
+//      published (Eq. (gate)); every workgroup reads the same words, so the decision is uniform across the grid
+//      without communication.  If nothing fired the kernel ends here: no byte of W is read;
 //   2. once per fired group: the residual vector is staged in LDS, then the rows of W of the group's
 //      maps are dealt round-robin over all waves of the grid (neighbouring waves stream neighbouring
 //      rows), one row per wave in units of eight 16-byte loads per lane, fp32 FMA against the staged
@@ -38,41 +36,12 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   const int GW = gridDim.x * kWaves;
   const int ng = lb.ng, n = lb.n;
 
-  // ---- 1. gates: one wave per group in every workgroup (identical arithmetic in every workgroup, hence
-  //         the same decision across the grid without communication) -----------------------------------
+  // ---- 1. gates: one wave per group in every workgroup reads the group's published count ---------------------
   __shared__ unsigned s_fired_g[kMaxTasks];
   if constexpr (!DENSE) {
     for (int gi = wave; gi < ng; gi += kWaves) {  // wave gi evaluates the gate of group gi
       const LinGroup& g = lb.g[gi];
-      bool f;
-      if (lb.inline_gate) {
-        const float2* pn = reinterpret_cast<const float2*>(g.part_n);
-        const int ns = g.b_slabs;
-        float2 v[kMaxResSlabs / kWave];
-#pragma unroll
-        for (int q = 0; q < kMaxResSlabs / kWave; ++q) {  // clamped: the loads are unconditional
-          const int sl = lane + q * kWave;
-          v[q] = pn[sl < ns ? sl : ns - 1];
-        }
-        float ar = 0.f, ax = 0.f;
-#pragma unroll
-        for (int q = 0; q < kMaxResSlabs / kWave; ++q) {
-          const bool ok = lane + q * kWave < ns;
-          ar += ok ? v[q].x : 0.f;
-          ax += ok ? v[q].y : 0.f;
-        }
-        const float rn = sqrtf(group_sum<kWave>(ar)), xn = sqrtf(group_sum<kWave>(ax));
-        f = gate_fires(rn, xn, lb.eps);
-        if (blockIdx.x == 0 && lane == 0) {  // publish what the norm and gate kernels would write
-          g.rnorm[0] = rn;
-          g.xnorm[0] = xn;
-          g.mask[0] = f ? 1 : 0;
-          if (f) g.fired_idx_out[0] = 0;
-          g.n_fired_out[0] = f ? 1 : 0;
-        }
-      } else {
-        f = g.n_fired[0] > 0;
-      }
+      const bool f = g.n_fired[0] > 0;
       if (lane == 0) s_fired_g[gi] = f ? 1u : 0u;
     }
     __syncthreads();

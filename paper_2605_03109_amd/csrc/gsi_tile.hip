@@ -35,10 +35,11 @@ constexpr int kVRow = kSliceCols + 8;              // bf16 per staged token row:
                                                    // the 16 lanes of a 128-bit LDS read on distinct banks
 constexpr int kHalfVec = 16 * kSliceCols / 4 / kTBlock;  // float4 per thread per 16 staged tokens (4)
 
-__device__ __forceinline__ int find_task(const int* begin, int n, int b) {
+template <int N>
+__device__ __forceinline__ int find_task(const int (&begin)[N], int n, int b) {
   int t = 0;
 #pragma unroll
-  for (int i = 1; i < kMaxTasks; ++i)
+  for (int i = 1; i < N; ++i)
     if (i < n && b >= begin[i]) t = i;
   return t;
 }

@@ -81,7 +81,7 @@ def _load() -> ctypes.CDLL:
                                            ctypes.c_int32, i64, f32, vp]
     lib.gsi_layer_stack_static.restype = ctypes.c_int
     lib.gsi_layer_stack_timed.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
-                                          ctypes.c_int32, i64, f32, vp, sz, vp, i32, vp, vp]
+                                          ctypes.c_int32, i64, f32, vp, sz, vp, i32, i32, vp, vp]
     lib.gsi_dense_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                     ctypes.c_int32, i64, vp, sz, vp]
     lib.gsi_workspace_bytes.argtypes = [i32, i64, i64, i64, i64]
@@ -345,11 +345,11 @@ class LayerStack:
         _check(lib.gsi_layer_stack_static(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B, self.eps,
                                           _stream(stream)))
 
-    def run_timed(self, ev_begin: int, ev_end: int, stream=None, which: int = 2) -> None:
-        """As run(), with raw hipEvent_t handles that take the dispatch timestamps of one kernel of the call
-        (0 = partial projection, 1 = residual + image rows, 2 = weight streaming)."""
+    def run_timed(self, ev_begin: int, ev_end: int, stream=None, which: int = 0, index: int = 0) -> None:
+        """As run(), with raw hipEvent_t handles that take the dispatch timestamps of one launch of the call
+        (which: 0 = staged projection kernel, 1 = weight streaming; index: which launch of that kind)."""
         _check(lib.gsi_layer_stack_timed(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B,
-                                         self.eps, self.ws.data_ptr(), self.ws.numel(), _stream(stream), which,
+                                         self.eps, self.ws.data_ptr(), self.ws.numel(), _stream(stream), which, index,
                                          ev_begin, ev_end))
 
     def run_dense(self, stream=None) -> None:

@@ -242,6 +242,59 @@ def test_layer_stack_equals_separate_calls_bitwise(gsi, pu):
                 assert torch.equal(st.maps_t[j]["Y"], sep["Y"][name]), name
 
 
+def test_many_inputs_in_one_single_token_call(gsi, pu):
+    """Five blocks (20 inputs, 30 maps) in ONE call per token: more inputs than one launch of the staged kernel
+    holds, so the stages of the two sets (partial projections, coefficient sums, residuals and image rows, gates)
+    share launches.  The result must equal block-by-block calls (one set: no sum stage)
+    bit for bit -- on a workspace that starts out filled with ones, and again on the second pass over the tokens."""
+    L, T = 5, 6
+    ws_blocks = [wl.transformer_block(f"blk{l}", d=512, ffn=2048, k=64, T=T, fire_rate=0.34, p=1.5, seed=500 + l)
+                 for l in range(L)]
+    inputs, maps, per_block = [], [], []
+    for w in ws_blocks:
+        dgs, bi, bm, _ = _stack_for(gsi, pu, w, 1)
+        base = len(inputs)
+        inputs += bi
+        maps += [dict(m, input_id=m["input_id"] + base) for m in bm]
+        per_block.append((bi, bm))
+    eps = ws_blocks[0].eps
+    say(f"case {len(inputs)} inputs / {len(maps)} maps in one call per token")
+    st = gsi.LayerStack(inputs, maps, T, eps)
+    st.refresh(token_offset=0, B=1)
+    st.ws.fill_(0xFF)
+    for rep in range(2):
+        for t in range(T):
+            st.refresh(token_offset=t, B=1)
+            st.run()
+    torch.cuda.synchronize()
+    n_in = n_mp = 0
+    for bi, bm in per_block:
+        ref = gsi.LayerStack(bi, bm, T, eps)
+        for t in range(T):
+            ref.refresh(token_offset=t, B=1)
+            ref.run()
+        torch.cuda.synchronize()
+        for a in ref.inputs_t:
+            b = st.inputs_t[n_in]
+            for key in ("C", "R", "rnorm", "xnorm", "mask"):
+                assert torch.equal(a[key], b[key]), (n_in, key)
+            n_in += 1
+        for a in ref.maps_t:
+            assert torch.equal(a["Y"], st.maps_t[n_mp]["Y"]), n_mp
+            n_mp += 1
+    # and against the oracle for the first and the last block
+    for l in (0, L - 1):
+        w = ws_blocks[l]
+        for gi, g in enumerate(w.groups):
+            og = pu.OracleGroup(w, g)
+            ref = og.run()
+            ti = st.inputs_t[4 * l + gi]
+            res = dict(C=ti["C"], R=ti["R"], rnorm=ti["rnorm"], xnorm=ti["xnorm"], mask=ti["mask"],
+                       n_fired=torch.tensor([int(ti["mask"].sum().item())], dtype=torch.int32),
+                       fired_idx=torch.nonzero(ti["mask"]).flatten().to(torch.int32))
+            pu.check_projection(res, ref, eps)
+
+
 def test_layer_stack_true_chain(gsi, pu):
     """Two maps chained: the second input is the first map's output (src_map = 0)."""
     rng = np.random.default_rng(3)
@@ -362,19 +415,24 @@ def test_timed_stack_and_dense_stack_match_plain_calls(gsi, pu):
     torch.cuda.synchronize()
     plain = [m["Y"].clone() for m in st.maps_t]
     plain_c = [i["C"].clone() for i in st.inputs_t]
-    for which in (0, 1, 2):  # the events bracket the partial projection, the residual + image launch, the W stream
+    # the events bracket one launch: the staged projection kernel's first (partial projections) and second
+    # (residuals, image rows) and third (gates) launch, the weight-streaming launch
+    for which, index in ((0, 0), (0, 1), (0, 2), (1, 0)):
         for m in st.maps_t:
             m["Y"].zero_()
         for t in range(w.T):
             st.refresh(token_offset=t, B=1)
-            st.run_timed(e0, e1, which=which)
+            st.run_timed(e0, e1, which=which, index=index)
         torch.cuda.synchronize()
         ms = ct.c_float()
-        assert hip.hipEventElapsedTime(ct.byref(ms), e0, e1) == 0 and 0.0 < ms.value < 50.0, which
+        assert hip.hipEventElapsedTime(ct.byref(ms), e0, e1) == 0 and 0.0 < ms.value < 50.0, (which, index)
         for a, m in zip(plain, st.maps_t):
             assert torch.equal(a, m["Y"])
         for a, i in zip(plain_c, st.inputs_t):
             assert torch.equal(a, i["C"])
+    with pytest.raises(gsi.GsiError):  # the call makes three launches of the staged kernel: there is no fourth
+        st.run_timed(e0, e1, which=0, index=3)
+    torch.cuda.synchronize()
     # dense stack, one token and a batch
     for B in (1, 3):
         st.refresh(token_offset=0, B=B)
