@@ -41,9 +41,9 @@ MAPS_PER_LAYER = sum(len(m) for _, _, m in BLOCK)
 KERNELS = {
     0: "gsi::proj_stage<BF16> (one launch: partial c = U^T x of 16 inputs; c of the 16 before; r = x - U c, norm shares "
        "and the image rows y = M c of the 16 before those; gates of the 16 before those)",
-    1: "gsi::stream_rows<BF16, dense=false> (one launch: W r of every fired map of 16 inputs)",
+    1: "gsi::stream_fired<BF16> (one launch: W r of every fired map of the call)",
 }
-PROFILE_KEY = {0: "proj_stage", 1: "stream_rows"}
+PROFILE_KEY = {0: "proj_stage", 1: "stream_fired"}
 
 
 def log(msg: str) -> None:
@@ -321,7 +321,7 @@ def main() -> int:
     if not args.no_roofline and not args.fused:
         SET = 16                                  # inputs per launch of the staged kernel
         nsets = (S.n_in + SET - 1) // SET
-        n_launch = {0: nsets + 3, 1: nsets}       # launches per step: staged kernel, weight streaming
+        n_launch = {0: nsets + 3, 1: 1}           # launches per step: staged kernel, weight streaming
         K = min(T, 24)
         evs = HipEvents(2)
         s0 = torch.cuda.current_stream().cuda_stream
@@ -343,7 +343,7 @@ def main() -> int:
 
         def stream_bytes(idx, t):  # W of a fired input's maps, r, y read and written
             b = 0
-            for i in set_inputs(idx):
+            for i in range(S.n_in):
                 _, d, mpl = BLOCK[i % len(BLOCK)]
                 if fired_np[i, t]:
                     b += sum(m * d * 2 + 2 * m * 4 for _, m in mpl) + d * 4

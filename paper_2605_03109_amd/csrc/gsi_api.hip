@@ -526,11 +526,16 @@ static size_t fp8_expand_bytes(const gsi_map_desc& mp, const gsi_input_desc& in,
   return gsi::align_up((size_t)mp.m * in.k * gsi::elem_size(mp.wdtype), 256);
 }
 
+// single token: the descriptor table of the weight-streaming launch sits at the start of the workspace
+static size_t stack_table_bytes(int32_t n_maps, int32_t n_inputs, int64_t B) {
+  return B == 1 && n_maps > 0 && n_inputs > 0 ? gsi::fired_table_bytes(n_inputs, n_maps) : 0;
+}
+
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                                        int32_t n_inputs, int64_t B) {
   if (!inputs || n_inputs < 0) return 0;
   // projections of independent inputs share a launch, so every input has its own region
-  size_t need = 0;
+  size_t need = stack_table_bytes(maps ? n_maps : 0, n_inputs, B);
   for (int i = 0; i < n_inputs; ++i)
     need += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
   // and so do the maps of a decode batch (partial products of the weight term)
@@ -736,7 +741,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   std::vector<size_t> ws_off(n_inputs, 0);
   std::vector<float*> part(n_maps, nullptr);
   {
-    size_t off = 0;
+    size_t off = stack_table_bytes(n_maps, n_inputs, B);
     for (int i = 0; i < n_inputs; ++i) {
       ws_off[i] = off;
       off += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
@@ -753,7 +758,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // as maps with an ordinary image.
   std::vector<gsi_map_desc> expanded;
   if (B > 0) {
-    size_t off = 0;
+    size_t off = stack_table_bytes(n_maps, n_inputs, B);
     for (int i = 0; i < n_inputs; ++i)
       off += gsi::align_up(gsi_workspace_bytes(GSI_CALL_PROJECT, 0, inputs[i].d, inputs[i].k, B), 256);
     for (int j = 0; j < n_maps; ++j) off += map_part_bytes(maps[j].m, inputs[maps[j].input_id].d, B, 0);
@@ -1009,6 +1014,74 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     std::vector<int> mready;
     for (int j = 0; j < n_maps; ++j)
       if (!map_done[j] && in_done[maps[j].input_id] == 1) mready.push_back(j);
+    // single token, more inputs or maps than one launch's arguments describe: one weight-streaming launch over
+    // a descriptor table uploaded to the workspace
+    for (int dt = 0; dt < 2 && B == 1; ++dt) {
+      auto eligible = [&](int j) {
+        const gsi_map_desc& mp = maps[j];
+        const gsi_input_desc& in = inputs[mp.input_id];
+        return !map_done[j] && !map_fused[j] && mp.wdtype == dt && in.d <= gsi::kMaxLinD &&
+               !mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) &&
+               gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) && aligned(in.C, 16) &&
+               aligned(in.R, 16) && wx_vector_ok(in);
+      };
+      std::vector<int> order;  // inputs in order of first appearance
+      std::vector<int> slot(n_inputs, -1);
+      int n_el = 0;
+      for (int j : mready) {
+        if (!eligible(j)) continue;
+        ++n_el;
+        if (slot[maps[j].input_id] < 0) {
+          slot[maps[j].input_id] = (int)order.size();
+          order.push_back(maps[j].input_id);
+        }
+      }
+      if ((n_el <= gsi::kMaxLinTasks && (int)order.size() <= gsi::kMaxTasks) || (int)order.size() > gsi::kMaxFiredIn)
+        continue;  // the launch below, with its descriptors in the kernel arguments, takes them
+      std::vector<gsi::FiredIn> fin(order.size());
+      std::vector<gsi::FiredMap> fmp;
+      fmp.reserve(n_el);
+      gsi::ImgBatch sib;  // image maps y = M c not yet written by an earlier launch
+      std::memset(&sib, 0, sizeof(sib));
+      for (size_t q = 0; q < order.size(); ++q) {
+        const gsi_input_desc& in = inputs[order[q]];
+        gsi::FiredIn& f = fin[q];
+        f.R = in.R; f.X = in.X; f.n_fired = in.n_fired; f.d = (int)in.d;
+        f.flags = ((in.flags & GSI_INPUT_SLOW_PATH_WX) ? gsi::kFiredWx : 0) | (in.xdtype << 1);
+        f.map_begin = (int)fmp.size();
+        for (int j : mready) {
+          if (maps[j].input_id != order[q] || !eligible(j)) continue;
+          const gsi_map_desc& mp = maps[j];
+          fmp.push_back(gsi::FiredMap{mp.W, mp.Y, (int)mp.m, 0});
+          if (!img_done[j]) {
+            if (sib.n == gsi::kMaxLinTasks) {
+              if (hipError_t e = gsi::decode_image_launch(sib, dt, s); e != hipSuccess) return hip_fail(e, fn);
+              std::memset(&sib, 0, sizeof(sib));
+            }
+            gsi::ImgTask& it = sib.t[sib.n++];
+            it.M = mp.M; it.Y = mp.Y; it.part_c = nullptr; it.C = in.C; it.m = (int)mp.m; it.k = (int)in.k;
+            it.a_slabs = 0; it.scale = (mp.flags & GSI_MAP_IMAGE_FP8) ? mp.M_scale : nullptr;
+            img_done[j] = 1;
+          }
+          map_done[j] = 2;
+        }
+        f.map_end = (int)fmp.size();
+      }
+      if (sib.n > 0)
+        if (hipError_t e = gsi::decode_image_launch(sib, dt, s); e != hipSuccess) return hip_fail(e, fn);
+      const size_t in_bytes = gsi::fired_table_bytes((int)fin.size(), 0);
+      const size_t bytes = gsi::fired_table_bytes((int)fin.size(), (int)fmp.size());
+      std::vector<char> table(bytes, 0);
+      std::memcpy(table.data(), fin.data(), fin.size() * sizeof(gsi::FiredIn));
+      std::memcpy(table.data() + in_bytes, fmp.data(), fmp.size() * sizeof(gsi::FiredMap));
+      if (hipError_t e = gsi::upload_launch(table.data(), bytes, ws, s); e != hipSuccess) return hip_fail(e, fn);
+      const bool timed = which == 1 && n_stream_launches == launch_index;
+      ++n_stream_launches;
+      if (hipError_t e = gsi::stream_fired_launch(ws, (int)fin.size(), fin.data(), fmp.data(), dt, s,
+                                                  timed ? ev_begin : nullptr, timed ? ev_end : nullptr);
+          e != hipSuccess)
+        return hip_fail(e, fn);
+    }
     for (int dt = 0; dt < 2; ++dt) {
       LinBatcher bt;
       bt.wdtype = dt; bt.s = s;

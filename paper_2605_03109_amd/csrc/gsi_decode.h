@@ -202,6 +202,33 @@ void stage_add_gate(StageArgs& a, const ProjTask& t);
 // e0 / e1 (optional): events that take the start / stop timestamps of the dispatch
 hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 
+// ---- single token, many inputs: weight streaming over a table in device memory (gsi_stream.hip) -----------
+// One launch streams the rows of W of every fired input of a call, however many inputs and maps the call has.
+// The descriptors do not fit the kernel arguments, so they are uploaded to the workspace first (by small kernels
+// that copy their own arguments: no host-to-device copy is enqueued, which a captured graph would replay from
+// host memory that no longer holds them).
+struct FiredIn {
+  const float* R;
+  const void* X;               // W x form of the slow path (xdtype)
+  const int32_t* n_fired;
+  int d;
+  int flags;                   // kFiredWx | xdtype << 1
+  int map_begin, map_end;      // this input's maps in the table of FiredMap
+};
+constexpr int kFiredWx = 1;
+struct FiredMap {
+  const void* W;
+  float* Y;
+  int m, pad;
+};
+constexpr int kMaxFiredIn = 4096;  // inputs per launch (a flag per input in LDS)
+size_t fired_table_bytes(int n_in, int n_maps);
+// uploads `bytes` (a multiple of 16) from host memory `src` to device memory `dst` through kernel arguments
+hipError_t upload_launch(const void* src, size_t bytes, void* dst, hipStream_t s);
+// table: n_in FiredIn followed (at fired_table_bytes(n_in, 0)) by the FiredMap of all inputs, in device memory
+hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
+                               int wdtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+
 // single-token persistent kernel (gsi_stream.hip)
 size_t stream_smem_bytes(const LinBatch& lb);
 hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0 = nullptr,

@@ -13,6 +13,8 @@
 // The dense baseline runs the same code with every group "fired", x in place of r and a plain store.
 #include <hip/hip_ext.h>
 
+#include <cstring>
+
 #include "gsi_decode.h"
 #include "gsi_device.h"
 #include "gsi_wstream.h"
@@ -96,6 +98,79 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   }
 }
 
+// The same streaming for ALL fired inputs of a call, descriptors in device memory.
+template <class T, bool TAIL>
+__global__ __launch_bounds__(kBlock) void stream_fired(const FiredIn* __restrict__ ins, const FiredMap* __restrict__ maps,
+                                                       int n_in) {
+  using S = typename T::storage;
+  extern __shared__ __align__(16) float xs[];  // one activation vector (r of a fired input, or x)
+  __shared__ unsigned char s_f[kMaxFiredIn];
+  __shared__ unsigned s_any;
+
+  const int lane = threadIdx.x % kWave;
+  const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  const int gw = blockIdx.x * kWaves + wave;
+  const int GW = gridDim.x * kWaves;
+
+  // ---- 1. which inputs fired: every workgroup reads the same published counts, so the decision is uniform
+  if (threadIdx.x == 0) s_any = 0u;
+  __syncthreads();
+  for (int i = threadIdx.x; i < n_in; i += kBlock) {
+    const bool f = ins[i].n_fired[0] > 0;
+    s_f[i] = f ? 1 : 0;
+    if (f) s_any = 1u;  // every writer stores the same value
+  }
+  __syncthreads();
+  if (s_any == 0u) return;  // the common case: nothing fired, no byte of W is read
+
+  // ---- 2. rows of W of the fired inputs' maps, dealt round-robin over all waves of the grid, map after map
+  bool staged = false;
+  int first = gw;
+  for (int i = 0; i < n_in; ++i) {
+    if (!__builtin_amdgcn_readfirstlane((int)s_f[i])) continue;  // uniform across the grid
+    const FiredIn* in = ins + i;
+    const int d = __builtin_amdgcn_readfirstlane(in->d);
+    const int flags = __builtin_amdgcn_readfirstlane(in->flags);
+    const int xdtype = flags >> 1;
+    const bool whole = (flags & kFiredWx) != 0;  // the product takes x (and replaces y) rather than r (added to y)
+    if (staged) __syncthreads();  // readers of the previous input's vector are done
+    staged = true;
+    if (whole && xdtype != GSI_F32) {
+      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(in->X, xdtype, idx);
+    } else {
+      const float4* src = reinterpret_cast<const float4*>(whole ? reinterpret_cast<const float*>(in->X) : in->R);
+      float4* dst = reinterpret_cast<float4*>(xs);
+      const int n4 = d / 4;
+      int q = threadIdx.x;
+      for (; q + 3 * kBlock < n4; q += 4 * kBlock) {  // four independent loads per thread and trip
+        const float4 a = src[q], b = src[q + kBlock], c = src[q + 2 * kBlock], e = src[q + 3 * kBlock];
+        dst[q] = a;
+        dst[q + kBlock] = b;
+        dst[q + 2 * kBlock] = c;
+        dst[q + 3 * kBlock] = e;
+      }
+      for (; q < n4; q += kBlock) dst[q] = src[q];
+    }
+    __syncthreads();
+    const int mb = __builtin_amdgcn_readfirstlane(in->map_begin), me = __builtin_amdgcn_readfirstlane(in->map_end);
+    for (int j = mb; j < me; ++j) {
+      const FiredMap* mp = maps + j;
+      const int m = __builtin_amdgcn_readfirstlane(mp->m);
+      stream_map_rows<T, TAIL, false>(reinterpret_cast<const S*>(mp->W), mp->Y, m, d, xs, whole, first, GW, lane);
+      first = (first - m % GW + GW) % GW;  // the next map starts with the wave after this map's last row
+    }
+  }
+}
+
+constexpr int kUploadBytes = 3840;
+struct UploadArgs {
+  uint4 v[kUploadBytes / 16];
+};
+// copies its own arguments to device memory (descriptor tables of a call; see gsi_decode.h)
+__global__ __launch_bounds__(256) void upload_table(const UploadArgs a, uint4* __restrict__ dst, int n16) {
+  for (int i = threadIdx.x; i < n16; i += 256) dst[i] = a.v[i];
+}
+
 int num_cus() {
   static const int n = [] {
     int dev = 0, cu = 0;
@@ -129,6 +204,66 @@ hipError_t launch_dtype(const LinBatch& lb, bool tail, unsigned grid, size_t sme
 }
 
 }  // namespace
+
+size_t fired_table_bytes(int n_in, int n_maps) {
+  return align_up((size_t)n_in * sizeof(FiredIn), 256) + align_up((size_t)n_maps * sizeof(FiredMap), 256);
+}
+
+hipError_t upload_launch(const void* src, size_t bytes, void* dst, hipStream_t s) {
+  if (bytes % 16) return hipErrorInvalidValue;
+  const char* p = static_cast<const char*>(src);
+  char* q = static_cast<char*>(dst);
+  while (bytes > 0) {
+    const size_t n = bytes < (size_t)kUploadBytes ? bytes : (size_t)kUploadBytes;
+    UploadArgs a;
+    std::memcpy(&a, p, n);
+    upload_table<<<1, 256, 0, s>>>(a, reinterpret_cast<uint4*>(q), (int)(n / 16));
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+    p += n;
+    q += n;
+    bytes -= n;
+  }
+  return hipSuccess;
+}
+
+template <class T, bool TAIL>
+static hipError_t launch_fired(const FiredIn* ins, const FiredMap* maps, int n_in, unsigned grid, size_t smem,
+                               hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  static const hipError_t attr =
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fired<T, TAIL>),
+                          hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLinD * (int)sizeof(float));
+  if (attr != hipSuccess) return attr;
+  if (e0 && e1) hipExtLaunchKernelGGL((stream_fired<T, TAIL>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, ins, maps, n_in);
+  else stream_fired<T, TAIL><<<grid, kBlock, smem, s>>>(ins, maps, n_in);
+  return hipGetLastError();
+}
+
+hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
+                               int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  if (n_in <= 0) return hipSuccess;
+  if (n_in > kMaxFiredIn) return hipErrorInvalidValue;
+  const int V = wdtype == GSI_BF16 ? 8 : 4;
+  int64_t rows = 0;
+  size_t maxd = 0;
+  bool tail = false;
+  for (int i = 0; i < n_in; ++i) {
+    if ((size_t)host_ins[i].d > maxd) maxd = (size_t)host_ins[i].d;
+    if ((host_ins[i].d / V) % (kWave * kLU)) tail = true;
+    for (int j = host_ins[i].map_begin; j < host_ins[i].map_end; ++j) rows += host_maps[j].m;
+  }
+  if (maxd > (size_t)kMaxLinD) return hipErrorInvalidValue;
+  int64_t grid = (int64_t)kWgsPerCu * num_cus();
+  if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
+  if (grid < 1) grid = 1;
+  const FiredIn* ins = static_cast<const FiredIn*>(table);
+  const FiredMap* maps = reinterpret_cast<const FiredMap*>(static_cast<const char*>(table) + fired_table_bytes(n_in, 0));
+  const size_t smem = maxd * sizeof(float);
+  if (wdtype == GSI_BF16)
+    return tail ? launch_fired<BF16, true>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1)
+                : launch_fired<BF16, false>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1);
+  return tail ? launch_fired<F32, true>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1)
+              : launch_fired<F32, false>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1);
+}
 
 size_t stream_smem_bytes(const LinBatch& lb) {
   size_t maxd = 0;

@@ -242,10 +242,13 @@ def test_layer_stack_equals_separate_calls_bitwise(gsi, pu):
                 assert torch.equal(st.maps_t[j]["Y"], sep["Y"][name]), name
 
 
-def test_many_inputs_in_one_single_token_call(gsi, pu):
+@pytest.mark.parametrize("wx", [False, True])
+def test_many_inputs_in_one_single_token_call(gsi, pu, wx):
     """Five blocks (20 inputs, 30 maps) in ONE call per token: more inputs than one launch of the staged kernel
     holds, so the stages of the two sets (partial projections, coefficient sums, residuals and image rows, gates)
-    share launches.  The result must equal block-by-block calls (one set: no sum stage)
+    share launches, and the weight rows of all fired inputs are streamed by ONE launch over a descriptor table in
+    the workspace.  The result must equal block-by-block calls (one set: no sum stage; descriptors in the kernel
+    arguments)
     bit for bit -- on a workspace that starts out filled with ones, and again on the second pass over the tokens."""
     L, T = 5, 6
     ws_blocks = [wl.transformer_block(f"blk{l}", d=512, ffn=2048, k=64, T=T, fire_rate=0.34, p=1.5, seed=500 + l)
@@ -253,6 +256,8 @@ def test_many_inputs_in_one_single_token_call(gsi, pu):
     inputs, maps, per_block = [], [], []
     for w in ws_blocks:
         dgs, bi, bm, _ = _stack_for(gsi, pu, w, 1)
+        if wx:
+            bi = [dict(i, flags=gsi.INPUT_SLOW_PATH_WX) for i in bi]
         base = len(inputs)
         inputs += bi
         maps += [dict(m, input_id=m["input_id"] + base) for m in bm]
