@@ -27,7 +27,18 @@ the design notes):
     ``gated_linear_alg1`` is that variant;
   * eps is the fp32 value the device receives, widened to fp64;
   * the FP8 image of Section 7 "Combination with quantization" is OCP E4M3 with one
-    power-of-two scale per output row (the paper names neither format nor scaling).
+    power-of-two scale per output row (the paper names neither format nor scaling);
+  * the residual norm of Eq. (rho) may be evaluated without forming r: for c = U^T x and ANY stored U,
+    |x - U c|^2 = |x|^2 - |c|^2 + c^T (U^T U - I) c (``residual_norm_single_pass``) -- the same
+    quantity, not an approximation; dropping the last term would assume U^T U = I exactly;
+  * online basis maintenance (Section 5.3 "The cascade initialization", Section 5.4 "Time-dimension
+    tracking", Section 7 "Online basis adaptation") names DGKS rank-1 updates without thresholds,
+    capacity or eviction.  Reading: a basis lives in an array U[d, K] of fixed capacity K whose columns
+    from k on are zero (a zero column changes neither c, r nor y); a token whose residual ratio is at
+    least tau extends the basis, while k < K, by the normalised residual after classical Gram-Schmidt
+    with one re-orthogonalisation pass ("twice is enough"); the new column is rounded to the basis'
+    storage type and the image gains the column W u_new computed from that STORED column, so that
+    M = W U keeps holding for the stored operands; nothing is ever evicted.
 
 Every function here is pinned by tests that do not call the oracle to obtain
 their expected value (hand-worked numbers, closed forms, invariants, brute
@@ -110,6 +121,41 @@ def gate(rnorm: np.ndarray, xnorm: np.ndarray, eps: float) -> Tuple[np.ndarray, 
     fired = (np.asarray(xnorm) > 0) & (rho >= eps64)
     idx = np.nonzero(fired)[0].astype(np.int32)
     return fired.astype(np.uint8), idx, int(idx.shape[0])
+
+
+# ----------------------------------------------------------------------------
+# Eq. (rho) evaluated in one pass over the basis
+# ----------------------------------------------------------------------------
+def gram_defect(U: np.ndarray) -> np.ndarray:
+    """E = U^T U - I for a stored basis U[d, k] (zero for an exactly orthonormal one)."""
+    U = np.asarray(U, dtype=np.float64)
+    return U.T @ U - np.eye(U.shape[1])
+
+
+def residual_norm_single_pass(x: np.ndarray, c: np.ndarray, E: np.ndarray) -> float:
+    """|x - U c| for c = U^T x without touching U again: sqrt(|x|^2 - |c|^2 + c^T E c), E = U^T U - I.
+
+    Expanding |x - U c|^2 = |x|^2 - 2 c^T (U^T x) + c^T U^T U c with U^T x = c gives the formula for
+    any U, orthonormal or not.  Negative round-off under the root is clamped to zero.
+    """
+    x = np.asarray(x, dtype=np.float64)
+    c = np.asarray(c, dtype=np.float64)
+    q = np.sum(x * x) - np.sum(c * c) + c @ (np.asarray(E, dtype=np.float64) @ c)
+    return float(np.sqrt(max(q, 0.0)))
+
+
+def project_single_pass(U: np.ndarray, E: np.ndarray, X: np.ndarray) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """C[B, k], rnorm[B], xnorm[B] of Algorithm 1 lines 1 and 3 with the residual norm from the cached E."""
+    U = np.asarray(U, dtype=np.float64)
+    X = np.asarray(X, dtype=np.float64)
+    C = np.empty((X.shape[0], U.shape[1]))
+    rnorm = np.empty(X.shape[0])
+    xnorm = np.empty(X.shape[0])
+    for t in range(X.shape[0]):
+        C[t] = U.T @ X[t]
+        rnorm[t] = residual_norm_single_pass(X[t], C[t], E)
+        xnorm[t] = np.sqrt(np.sum(X[t] * X[t]))
+    return C, rnorm, xnorm
 
 
 # ----------------------------------------------------------------------------
@@ -241,6 +287,90 @@ def quantize_image_fp8(M: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
 def dequantize_image_fp8(codes: np.ndarray, scale: np.ndarray) -> np.ndarray:
     """M_ij = scale_i * value(codes_ij), fp64."""
     return fp8_e4m3_decode(codes) * np.asarray(scale, dtype=np.float64)[:, None]
+
+
+# ----------------------------------------------------------------------------
+# Sections 5.3, 5.4 and 7 "Online basis adaptation": rank-1 extension of the basis (DGKS)
+# ----------------------------------------------------------------------------
+def round_to_storage(a: np.ndarray, dtype: str) -> np.ndarray:
+    """Round fp64 values to the storage type, to nearest with ties to even; returns what ``widen`` reads."""
+    a = np.asarray(a, dtype=np.float64)
+    f = a.astype(np.float32)
+    if dtype == F32:
+        return f
+    if dtype == BF16:
+        # fp64 -> bf16 in one rounding: a lies between the truncation of its fp32 value and the next bf16
+        # (if the fp32 rounding carried up to a bf16 value, that value is the truncation and it is nearest)
+        bits = f.view(np.uint32)
+        lo = bits & np.uint32(0xFFFF0000)                     # truncated toward zero in magnitude
+        hi = lo + np.uint32(0x10000)                          # next bf16 away from zero
+        vlo = lo.view(np.float32).astype(np.float64)
+        vhi = hi.view(np.float32).astype(np.float64)
+        dlo, dhi = np.abs(a - vlo), np.abs(vhi - a)
+        up = (dhi < dlo) | ((dhi == dlo) & (((lo >> np.uint32(16)) & np.uint32(1)) == 1))
+        out = np.where(up, hi, lo)
+        return (out >> np.uint32(16)).astype(np.uint16)
+    raise ValueError(f"unknown dtype {dtype!r}")
+
+
+def dgks_direction(U: np.ndarray, x: np.ndarray) -> Tuple[np.ndarray, float, float]:
+    """The unit vector that extends span(U) to contain x, and the residual norms of the two passes.
+
+    Classical Gram-Schmidt against the columns of U followed by one re-orthogonalisation pass:
+      c = U^T x, r = x - U c;   s = U^T r, r2 = r - U s;   u_new = r2 / |r2|.
+    Returns (u_new, |r|, |r2|); u_new is zero when r2 vanishes (x already in the span).
+    """
+    U = np.asarray(U, dtype=np.float64)
+    x = np.asarray(x, dtype=np.float64)
+    c = U.T @ x
+    r = x - U @ c
+    s = U.T @ r
+    r2 = r - U @ s
+    n1 = float(np.sqrt(np.sum(r * r)))
+    n2 = float(np.sqrt(np.sum(r2 * r2)))
+    u = r2 / n2 if n2 > 0 else np.zeros_like(r2)
+    return u, n1, n2
+
+
+def extend_basis(U_store: np.ndarray, udtype: str, k: int, x: np.ndarray, tau: float) -> Tuple[np.ndarray, int, bool]:
+    """One step of the tracker on a basis array of fixed capacity.
+
+    ``U_store[d, K]`` holds the stored basis (fp32, or bf16 bit patterns) with columns k..K-1 zero.  The token x
+    extends it iff x != 0, |x - U U^T x| / |x| >= tau (tau rounded to fp32 like eps) and k < K; the new column is
+    the DGKS direction rounded to the storage type.  Returns (new array, new k, extended?).
+    """
+    U = widen(U_store, udtype)
+    x = np.asarray(x, dtype=np.float64)
+    u, n1, n2 = dgks_direction(U, x)
+    xn = float(np.sqrt(np.sum(x * x)))
+    K = U.shape[1]
+    if not (xn > 0 and n1 / xn >= float(np.float32(tau)) and k < K and n2 > 0):
+        return U_store, k, False
+    out = np.array(U_store, copy=True)
+    out[:, k] = round_to_storage(u, udtype)
+    return out, k + 1, True
+
+
+def extend_image(M: np.ndarray, k: int, W: np.ndarray, u_stored: np.ndarray) -> np.ndarray:
+    """The matching append M <- [M, W u_new] into column k of M[m, K], fp64, not rounded; u_stored is the
+    widened STORED new column, so that M = W U holds for the stored basis (Eq. (exact))."""
+    out = np.array(np.asarray(M, dtype=np.float64), copy=True)
+    out[:, k] = np.asarray(W, dtype=np.float64) @ np.asarray(u_stored, dtype=np.float64)
+    return out
+
+
+def track_basis(U_store: np.ndarray, udtype: str, k: int, X: np.ndarray, tau: float) -> Tuple[np.ndarray, int, List[int]]:
+    """Section 5.4: every token in turn is tested against the current basis and may extend it.
+
+    Returns the final array, the final rank and the list of tokens that extended the basis.  Section 5.3's
+    cascade is this function started from the previous layer's basis instead of from an empty one.
+    """
+    grew = []
+    for t in range(np.asarray(X).shape[0]):
+        U_store, k, ext = extend_basis(U_store, udtype, k, X[t], tau)
+        if ext:
+            grew.append(t)
+    return U_store, k, grew
 
 
 # ----------------------------------------------------------------------------

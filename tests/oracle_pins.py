@@ -354,7 +354,190 @@ def pin_residual_ratio_zero_input(O):
     assert O.residual_ratio(np.zeros(3), np.zeros(3)).tolist() == [0.0, 0.0, 0.0]
 
 
+def pin_single_pass_residual_norm(O):
+    # Hand-worked with a basis that is NOT unit length: U = 1.1 (3/5, 4/5)^T, x = (1, 2).
+    # c = 2.42, U c = (1.5972, 2.1296), r = (-0.5972, -0.1296), |r|^2 = 0.373444.
+    # E = U^T U - 1 = 0.21; |x|^2 - c^2 + c E c = 5 - 5.8564 + 1.229844 = 0.373444.
+    U = np.array([[0.66], [0.88]])
+    E = O.gram_defect(U)
+    assert E.shape == (1, 1) and abs(E[0, 0] - 0.21) < 1e-15
+    x = np.array([1.0, 2.0])
+    assert abs(O.residual_norm_single_pass(x, np.array([2.42]), E) - math.sqrt(0.373444)) < 1e-14
+    # The defect of an axis-aligned, scaled basis is diagonal with entries s_j^2 - 1 and zero elsewhere.
+    S = np.zeros((5, 3))
+    S[[4, 0, 2], [0, 1, 2]] = [2.0, 0.5, 1.0]
+    assert np.array_equal(O.gram_defect(S), np.diag([3.0, -0.75, 0.0]))
+    # Any stored basis (a bf16-rounded orthonormal one, and a plain random matrix far from orthonormal):
+    # the one-pass value equals the norm of the residual formed explicitly with exactly rounded loop sums.
+    rng = np.random.default_rng(77)
+    d, k = 13, 4
+    Q, _ = np.linalg.qr(rng.standard_normal((d, k)))
+    for U in (O.widen(wl.store(Q, "bf16"), "bf16"), 0.4 * rng.standard_normal((d, k))):
+        E = O.gram_defect(U)
+        assert np.allclose(E, _fsum_matmul(U.T, U) - np.eye(k), rtol=0, atol=1e-15)
+        assert np.allclose(E, E.T, rtol=0, atol=0)
+        X = rng.standard_normal((3, d))
+        C, rn, xn = O.project_single_pass(U, E, X)
+        for t in range(3):
+            c = _fsum_matvec(U.T, X[t])
+            r = X[t] - _fsum_matvec(U, c)
+            assert np.allclose(C[t], c, rtol=0, atol=1e-14)
+            assert abs(rn[t] - math.sqrt(math.fsum(v * v for v in r))) < 1e-13
+            assert abs(xn[t] - math.sqrt(math.fsum(v * v for v in X[t]))) < 1e-14
+    # x in the span of an orthonormal basis: the value under the root is round-off of either sign; clamped, never NaN
+    x = Q @ rng.standard_normal(k)
+    v = O.residual_norm_single_pass(x, Q.T @ x, O.gram_defect(Q))
+    assert 0.0 <= v < 1e-7
+    # a value under the root that rounding made negative gives 0, not NaN: |x|^2 = 25, c^2 = 25 + 1e-8
+    assert O.residual_norm_single_pass(np.array([3.0, 4.0]), np.array([5.000000001]), np.zeros((1, 1))) == 0.0
+
+
+def pin_round_to_storage(O):
+    # bf16 has 8 significand bits: 1 + 2^-8 is a tie between 1 and 1 + 2^-7 and goes to the even code (1.0);
+    # 1 + 3 * 2^-8 is a tie between 1 + 2^-7 (odd) and 1 + 2^-6 (even) and goes up.
+    vals = np.array([1.0, 1.0 + 2.0 ** -8, 1.0 + 2.0 ** -8 + 2.0 ** -40, 1.0 + 3 * 2.0 ** -8, -(1.0 + 3 * 2.0 ** -8),
+                     0.0, 2.0 ** -8 * (1 - 2.0 ** -9), 1.0 - 2.0 ** -30])
+    codes = O.round_to_storage(vals, "bf16")
+    assert codes.dtype == np.uint16
+    assert codes.tolist() == [0x3F80, 0x3F80, 0x3F81, 0x3F82, 0xBF82, 0x0000, 0x3B80, 0x3F80]
+    # a double-rounding trap: just above a bf16 tie by less than half an fp32 ulp must still round up
+    assert O.round_to_storage(np.array([1.0 + 2.0 ** -8 + 2.0 ** -30]), "bf16").tolist() == [0x3F81]
+    # every bf16 value is a fixed point
+    allc = np.arange(0x0080, 0x7F80, 37, dtype=np.uint16)
+    assert np.array_equal(O.round_to_storage(O.widen(allc, "bf16"), "bf16"), allc)
+    f = O.round_to_storage(np.array([0.1, -2.5]), "f32")
+    assert f.dtype == np.float32 and f.tolist() == [np.float32(0.1), np.float32(-2.5)]
+
+
+def pin_dgks_extension(O):
+    # Hand-worked: U = e1 in R^3, x = (1, 1, 0): r = (0, 1, 0), the new direction is e2, both norms are 1.
+    U = np.array([[1.0], [0.0], [0.0]])
+    u, n1, n2 = O.dgks_direction(U, np.array([1.0, 1.0, 0.0]))
+    assert u.tolist() == [0.0, 1.0, 0.0] and n1 == 1.0 and n2 == 1.0
+    # x already in the span: zero direction, zero norms
+    u, n1, n2 = O.dgks_direction(U, np.array([-3.0, 0.0, 0.0]))
+    assert u.tolist() == [0.0, 0.0, 0.0] and n1 == 0.0 and n2 == 0.0
+    # Against a library routine: the new direction is, up to the sign convention, the last column of the QR
+    # factorisation of [U, x]; the extended basis stays orthonormal and x lies in its span.
+    rng = np.random.default_rng(5)
+    d, k = 17, 5
+    Q, _ = np.linalg.qr(rng.standard_normal((d, k)))
+    x = rng.standard_normal(d)
+    u, n1, n2 = O.dgks_direction(Q, x)
+    Q2, R2 = np.linalg.qr(np.column_stack([Q, x]))
+    q = Q2[:, k] * np.sign(R2[k, k])
+    assert np.allclose(u, q, rtol=0, atol=1e-13)
+    assert abs(n1 - abs(R2[k, k])) < 1e-13 and abs(n2 - n1) < 1e-13
+    V = np.column_stack([Q, u])
+    assert np.abs(_fsum_matmul(V.T, V) - np.eye(k + 1)).max() < 1e-14
+    assert np.linalg.norm(x - V @ (V.T @ x)) < 1e-13 * np.linalg.norm(x)
+    # "Twice is enough": x nearly in the span (residual 1e-9 of |x|), one pass alone leaves a direction that is
+    # not orthogonal to U at working precision; with the second pass it is.
+    n = rng.standard_normal(d)
+    n -= Q @ (Q.T @ n)
+    n /= np.linalg.norm(n)
+    x = Q @ rng.standard_normal(k) * 1e3 + 1e-6 * n
+    u, n1, n2 = O.dgks_direction(Q, x)
+    assert np.abs(Q.T @ u).max() < 1e-14 and abs(np.linalg.norm(u) - 1.0) < 1e-14
+    assert abs(u @ n) > 1 - 1e-6
+    # Proposition "Monotonicity" on the extended basis: the residual ratio of any token does not grow.
+    Y = rng.standard_normal((6, d))
+    for y in Y:
+        before = np.linalg.norm(y - Q @ (Q.T @ y))
+        after = np.linalg.norm(y - V @ (V.T @ y))
+        assert after <= before + 1e-14
+
+
+def pin_extend_basis_array(O):
+    rng = np.random.default_rng(8)
+    d, K, k, m = 24, 6, 3, 7
+    Q, _ = np.linalg.qr(rng.standard_normal((d, k)))
+    for dt in ("f32", "bf16"):
+        store = np.zeros((d, K), dtype=np.float32 if dt == "f32" else np.uint16)
+        store[:, :k] = Q.astype(np.float32) if dt == "f32" else wl.store(Q, "bf16")
+        U = O.widen(store, dt)
+        x = rng.standard_normal(d)
+        rho = np.linalg.norm(x - U @ (U.T @ x)) / np.linalg.norm(x)   # well away from 0 and 1
+        # below the threshold, at zero input, and at full capacity nothing changes
+        for args in ((store, dt, k, x, rho * 1.01), (store, dt, k, np.zeros(d), 0.0)):
+            out, k2, ext = O.extend_basis(*args)
+            assert not ext and k2 == k and out is store
+        full = store.copy()
+        full[:, k:] = store[:, :1]
+        out, k2, ext = O.extend_basis(full, dt, K, x, 0.0)
+        assert not ext and k2 == K
+        # at the threshold (>=, like the gate) the basis grows by one stored column; the others are untouched
+        out, k2, ext = O.extend_basis(store, dt, k, x, np.float32(rho * (1 - 1e-6)))
+        assert ext and k2 == k + 1
+        assert np.array_equal(out[:, :k], store[:, :k]) and not out[:, k + 1:].any()
+        unew = O.widen(out, dt)[:, k]
+        # it is the rounded normalised residual: within half a unit in the last place of the exact direction
+        r = x - U @ (U.T @ x)
+        r = r - U @ (U.T @ r)
+        exact = r / np.linalg.norm(r)
+        ulp = 2.0 ** -24 if dt == "f32" else 2.0 ** -8
+        assert np.all(np.abs(unew - exact) <= ulp * np.abs(exact) + 1e-300)
+        # x now has (up to storage rounding) no residual, and no token's ratio grew
+        V = O.widen(out, dt)
+        assert np.linalg.norm(x - V @ (V.T @ x)) <= 4 * ulp * np.linalg.norm(x) + (0.05 if dt == "bf16" else 1e-6) * rho * np.linalg.norm(x)
+        # the image append: column k of M becomes W u_new for the STORED column, the rest is untouched, so M = W U
+        W = rng.standard_normal((m, d))
+        M = np.zeros((m, K))
+        M[:, :k] = _fsum_matmul(W, U[:, :k])
+        M2 = O.extend_image(M, k, W, unew)
+        assert np.array_equal(M2[:, :k], M[:, :k]) and not M2[:, k + 1:].any()
+        assert np.allclose(M2, _fsum_matmul(W, V), rtol=0, atol=1e-13)
+
+
+def pin_extend_threshold(O):
+    # The threshold compares like the gate: >= , against tau rounded to fp32.
+    U1 = np.zeros((2, 2), dtype=np.float32)
+    U1[0, 0] = 1.0
+    # x orthogonal to the basis: ratio exactly 1, tau = 1 extends (a strict comparison would not)
+    _, k, ext = O.extend_basis(U1, "f32", 1, np.array([0.0, 2.0]), 1.0)
+    assert ext and k == 2
+    # x = (4, 3): r = (0, 3), ratio = 3/5, the double nearest to 0.6; fp32(0.6) = 0.60000002... is larger: no growth
+    _, k, ext = O.extend_basis(U1, "f32", 1, np.array([4.0, 3.0]), 0.6)
+    assert not ext and k == 1
+    # ratio 0.699999995 lies between fp32(0.7) = 0.69999998807... and 0.7: grows only because tau is rounded to fp32
+    rr = 0.699999995
+    _, k, ext = O.extend_basis(U1, "f32", 1, np.array([math.sqrt(1.0 - rr * rr), rr]), 0.7)
+    assert ext and k == 2
+
+
+def pin_track_basis(O):
+    # Tokens drawn from a 3-dimensional subspace plus one outlier direction: started empty with capacity 8 the
+    # tracker grows to exactly rank 4 (three from the subspace, one for the outlier) and then stops growing.
+    rng = np.random.default_rng(21)
+    d, K = 16, 8
+    B3, _ = np.linalg.qr(rng.standard_normal((d, 4)))
+    coef = rng.standard_normal((12, 3))
+    X = coef @ B3[:, :3].T
+    X[7] += 2.0 * B3[:, 3]
+    store = np.zeros((d, K), dtype=np.float32)
+    out, k, grew = O.track_basis(store, "f32", 0, X, 1e-3)
+    assert k == 4 and grew == [0, 1, 2, 7]
+    V = O.widen(out, "f32")[:, :k]
+    assert np.abs(V.T @ V - np.eye(k)).max() < 1e-6 and not out[:, k:].any()
+    for x in X:
+        assert np.linalg.norm(x - V @ (V.T @ x)) < 1e-5 * np.linalg.norm(x)
+    # capacity 2: growth stops at 2 and later tokens keep their residual
+    out2, k2, grew2 = O.track_basis(np.zeros((d, 2), dtype=np.float32), "f32", 0, X, 1e-3)
+    assert k2 == 2 and grew2 == [0, 1]
+    # the cascade (Section 5.3): started from a basis that already spans the subspace only the outlier extends it
+    warm = np.zeros((d, K), dtype=np.float32)
+    warm[:, :3] = B3[:, :3].astype(np.float32)
+    out3, k3, grew3 = O.track_basis(warm, "f32", 3, X, 1e-3)
+    assert k3 == 4 and grew3 == [7]
+
+
 PINS = [
+    pin_single_pass_residual_norm,
+    pin_round_to_storage,
+    pin_dgks_extension,
+    pin_extend_basis_array,
+    pin_extend_threshold,
+    pin_track_basis,
     pin_hand_worked_2d,
     pin_axis_aligned_basis,
     pin_brute_force_tiny,

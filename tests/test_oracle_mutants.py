@@ -49,6 +49,34 @@ MUTANTS = [
     ("stack_gate_per_map_wrong_eps", "mask, idx, n = gate(rn, xn, eps)", "mask, idx, n = gate(rn, xn, 2.0 * eps)"),
     ("stack_dense_uses_image", "name: dense_linear(W64, X) for name, W64, _ in g[\"maps\"]", "name: dense_linear(W64, X) * 1.0000001 for name, W64, _ in g[\"maps\"]"),
     ("error_bound_smallest_sv", "compute_uv=False)[0]", "compute_uv=False)[-1]"),
+    # the one-pass residual norm
+    ("gram_defect_keeps_identity", "return U.T @ U - np.eye(U.shape[1])", "return U.T @ U"),
+    ("gram_defect_is_UUT", "return U.T @ U - np.eye(U.shape[1])", "return (U @ U.T)[: U.shape[1], : U.shape[1]] - np.eye(U.shape[1])"),
+    ("single_pass_drops_defect_term", "- np.sum(c * c) + c @ (np.asarray(E, dtype=np.float64) @ c)", "- np.sum(c * c)"),
+    ("single_pass_defect_sign", "- np.sum(c * c) + c @ (np.asarray(E, dtype=np.float64) @ c)", "- np.sum(c * c) - c @ (np.asarray(E, dtype=np.float64) @ c)"),
+    ("single_pass_counts_c_twice", "q = np.sum(x * x) - np.sum(c * c)", "q = np.sum(x * x) - 2.0 * np.sum(c * c)"),
+    ("single_pass_no_root", "return float(np.sqrt(max(q, 0.0)))", "return float(max(q, 0.0))"),
+    ("single_pass_no_clamp", "return float(np.sqrt(max(q, 0.0)))", "return float(np.sqrt(q))"),
+    ("single_pass_xnorm_of_c", "xnorm[t] = np.sqrt(np.sum(X[t] * X[t]))", "xnorm[t] = np.sqrt(np.sum(C[t] * C[t]))"),
+    # rounding to storage, rank-1 extension, tracker
+    ("round_truncates", "up = (dhi < dlo) | (", "up = (dhi < 0 * dlo) & ("),
+    ("round_ties_away", "& (((lo >> np.uint32(16)) & np.uint32(1)) == 1))", "& (((lo >> np.uint32(16)) & np.uint32(1)) >= 0))"),
+    ("round_via_fp32_first", "dlo, dhi = np.abs(a - vlo), np.abs(vhi - a)", "dlo, dhi = np.abs(f - vlo), np.abs(vhi - f)"),
+    ("dgks_single_pass_only", "r2 = r - U @ s\n", "r2 = r\n"),
+    ("dgks_second_pass_sign", "r2 = r - U @ s\n", "r2 = r + U @ s\n"),
+    ("dgks_not_normalised", "u = r2 / n2 if n2 > 0", "u = r2 if n2 > 0"),
+    ("dgks_normalised_by_first_norm", "u = r2 / n2 if n2 > 0", "u = r2 / max(n1, 1.0) if n2 > 0"),
+    ("dgks_direction_is_x", "u = r2 / n2 if n2 > 0", "u = x / np.sqrt(np.sum(x * x)) if n2 > 0"),
+    ("extend_strict_threshold", "n1 / xn >= float(np.float32(tau))", "n1 / xn > float(np.float32(tau))"),
+    ("extend_threshold_fp64", "n1 / xn >= float(np.float32(tau))", "n1 / xn >= float(tau)"),
+    ("extend_ignores_capacity", "and k < K and n2 > 0", "and k <= K and n2 > 0"),
+    ("extend_wrong_column", "out[:, k] = round_to_storage(u, udtype)", "out[:, max(k - 1, 0)] = round_to_storage(u, udtype)"),
+    ("extend_rank_not_advanced", "return out, k + 1, True", "return out, k, True"),
+    ("extend_image_wrong_column", "out[:, k] = np.asarray(W, dtype=np.float64) @", "out[:, k - 1] = np.asarray(W, dtype=np.float64) @"),
+    ("extend_image_transposed", "out[:, k] = np.asarray(W, dtype=np.float64) @ np.asarray(u_stored, dtype=np.float64)",
+     "out[:, k] = np.asarray(W, dtype=np.float64)[:, ::-1] @ np.asarray(u_stored, dtype=np.float64)"),
+    ("track_tests_first_token_only", "U_store, k, ext = extend_basis(U_store, udtype, k, X[t], tau)", "U_store, k, ext = extend_basis(U_store, udtype, k, X[0], tau)"),
+    ("track_forgets_growth", "U_store, k, ext = extend_basis(U_store, udtype, k, X[t], tau)", "_, k, ext = extend_basis(U_store, udtype, k, X[t], tau)"),
     # the FP8 image
     ("fp8_bias", "np.exp2((e - 7).astype(np.float64))", "np.exp2((e - 8).astype(np.float64))"),
     ("fp8_subnormal_exponent", "(m / 8.0) * 2.0 ** -6", "(m / 8.0) * 2.0 ** -7"),
