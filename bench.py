@@ -39,8 +39,9 @@ BLOCK = [("attn_in", 4096, [("q", 4096), ("k", 4096), ("v", 4096)]),
 MAPS_PER_LAYER = sum(len(m) for _, _, m in BLOCK)
 
 KERNELS = {
-    0: "gsi::proj_stage<BF16> (one launch: partial c = U^T x of 16 inputs; c of the 16 before; r = x - U c, norm shares "
-       "and the image rows y = M c of the 16 before those; gates of the 16 before those)",
+    0: "gsi::proj_stage<BF16> (one launch carries consecutive stages of consecutive sets of 16 independent inputs: "
+       "partial c = U^T x; sums of the partials (+ shares of c^T E c with the single-pass gate); image rows y = M c "
+       "and residuals; gates)",
     1: "gsi::stream_fired<BF16> (one launch: W r of every fired map of the call)",
 }
 PROFILE_KEY = {0: "proj_stage", 1: "stream_fired"}
@@ -108,7 +109,8 @@ class Stack:
                 f = wd.choose_fired(T, int(round(fire * T)), gen)
                 X, _ = wd.make_tokens(U64[l][gi][:, :k], f, eps, p, gen)
                 self.designed.append(f)
-                inputs.append({"U": U, "X": X, "flags": flags})
+                inputs.append({"U": U, "X": X, "flags": flags,
+                               "gram": gsi.build_gram(U) if flags & gsi.INPUT_GATE_SINGLE_PASS else None})
                 for j, _ in enumerate(mp):
                     maps.append({"W": W[l][gi][j], "M": None, "input_id": len(inputs) - 1})
         torch.cuda.synchronize()
@@ -227,6 +229,10 @@ def main() -> int:
     ap.add_argument("--cell-tokens", type=int, default=128)
     ap.add_argument("--fused", action="store_true",
                     help="ask for the fused single-token kernel (GSI_INPUT_FUSED_KERNEL) instead of the separate kernels")
+    ap.add_argument("--gate", choices=["single-pass", "explicit"], default="single-pass",
+                    help="single-pass: residual ratio from |x|^2 - |c|^2 + c^T E c with the cached E = U^T U - I "
+                         "(GSI_INPUT_GATE_SINGLE_PASS: the basis is read once, r is formed for fired tokens only); "
+                         "explicit: r = x - U c formed for every token")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -264,6 +270,9 @@ def main() -> int:
     torch.cuda.synchronize()
     log(f"[bench] {L} layers generated in {time.perf_counter()-t0:.1f}s")
     flags = gsi.INPUT_FUSED_KERNEL if args.fused else 0
+    single_pass = args.gate == "single-pass" and not args.fused
+    if single_pass:
+        flags |= gsi.INPUT_GATE_SINGLE_PASS
 
     # ---- the headline cell ------------------------------------------------------------------------------
     t0 = time.perf_counter()
@@ -321,7 +330,7 @@ def main() -> int:
     if not args.no_roofline and not args.fused:
         SET = 16                                  # inputs per launch of the staged kernel
         nsets = (S.n_in + SET - 1) // SET
-        n_launch = {0: nsets + 3, 1: 1}           # launches per step: staged kernel, weight streaming
+        n_launch = {0: nsets + (2 if single_pass else 3), 1: 1}  # launches per step: staged kernel, weight streaming
         K = min(T, 24)
         evs = HipEvents(2)
         s0 = torch.cuda.current_stream().cuda_stream
@@ -331,14 +340,21 @@ def main() -> int:
         def set_inputs(g):
             return range(g * SET, min(S.n_in, (g + 1) * SET)) if 0 <= g < nsets else range(0)
 
-        def stage_bytes(idx):  # launch idx: partial projections of set idx, residuals + image rows of set idx - 2
+        def stage_bytes(idx, t):  # launch idx: partial projections of set idx, residuals + image rows of set idx - 2
             b = 0
             for i in set_inputs(idx):       # the basis once, x
                 d = BLOCK[i % len(BLOCK)][1]
                 b += d * k * 2 + d * 4
-            for i in set_inputs(idx - 2):   # the images, x again, c read; r and y written
-                _, d, mpl = BLOCK[i % len(BLOCK)]
-                b += sum(m * k * 2 + m * 4 for _, m in mpl) + d * 4 + k * 4 + d * 4
+            if single_pass:
+                for i in set_inputs(idx - 1):   # E and c
+                    b += k * k * 4 + k * 4
+            for i in set_inputs(idx - 2):   # the images, c read, y written; explicit gate: x again, r written;
+                _, d, mpl = BLOCK[i % len(BLOCK)]  # single-pass gate: the basis again, x, r for a fired input only
+                b += sum(m * k * 2 + m * 4 for _, m in mpl) + k * 4
+                if not single_pass:
+                    b += d * 4 + d * 4
+                elif fired_np[i, t]:
+                    b += d * k * 2 + d * 4 + d * 4
             return b
 
         def stream_bytes(idx, t):  # W of a fired input's maps, r, y read and written
@@ -361,7 +377,7 @@ def main() -> int:
                         raise gsi.GsiError(rc, gsi.last_error())
                     torch.cuda.synchronize()
                     dur[which][idx, t] = evs.elapsed_ms(0, 1) * 1e-3
-                    nbytes[which][idx, t] = stage_bytes(idx) if which == 0 else stream_bytes(idx, t)
+                    nbytes[which][idx, t] = stage_bytes(idx, t) if which == 0 else stream_bytes(idx, t)
         evs.close()
         kernels = {}
         for which in (0, 1):
@@ -374,8 +390,8 @@ def main() -> int:
             else:
                 entry = {"launches": int(d_all.size), "launches_per_step": n_launch[0],
                          "first_launch_us": round(float(dur[0][0].mean() * 1e6), 2),
-                         "full_launch_us": round(float(dur[0][2:-3].mean() * 1e6), 2) if nsets > 2 else None,
-                         "gate_only_launch_us": round(float(dur[0][-1].mean() * 1e6), 2)}
+                         "full_launch_us": round(float(dur[0][2:nsets].mean() * 1e6), 2) if nsets > 2 else None,
+                         "last_launch_us": round(float(dur[0][-1].mean() * 1e6), 2)}
                 d_use, b_use = d_all, b_all
             ach = float(b_use.sum() / d_use.sum() / 1e9) if d_use.size else 0.0
             entry.update({"kernel": KERNELS[which], "avg_launch_us": round(float(d_use.mean() * 1e6), 2),
@@ -467,6 +483,8 @@ def main() -> int:
             "measured_fire_rate": head["measured_fire_rate"], "masks_match_design": head["masks_match_design"],
             "launch_mode": mode, "slow_path": "M c + W r",
             "single_token_kernels": "fused" if args.fused else "separate",
+            "gate": "single pass over the basis: |r|^2 = |x|^2 - |c|^2 + c^T (U^T U - I) c, r formed for fired tokens only"
+                    if single_pass else "explicit residual r = x - U c for every token",
         },
         "tokens_per_s": round(tokens_per_s, 1),
         "dense_gemv_tokens_per_s": round(args.steps / sec_dense, 1),

@@ -68,6 +68,12 @@ enum gsi_call {
 int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d, int64_t k, int wdtype,
                     void* ws, size_t ws_bytes, void* stream);
 
+/* One-time companion of a basis for GSI_INPUT_GATE_SINGLE_PASS: E[k,k] (fp32, row-major) = U^T U - I, the
+ * departure of the STORED basis U[d,k] (`udtype`) from orthonormality (Definition "Activation basis and residual
+ * ratio" assumes V_k^T V_k = I; storage rounding breaks it by about 1e-3 in bf16).  Accumulated in fp64, rounded
+ * once to fp32.  Any shape with 1 <= k <= d; no workspace. */
+int gsi_build_gram(const void* U, int64_t d, int64_t k, int udtype, float* E, void* stream);
+
 /* The cached image in 8-bit floating point (Section 7 "Combination with quantization": half the fast-path
  * bytes).  The paper names no format; this library stores OCP E4M3 codes (1 sign, 4 exponent bits with bias 7,
  * 3 mantissa bits, largest finite value 448, no infinities) with one power-of-two scale per output row:
@@ -121,7 +127,9 @@ typedef struct gsi_input_desc {
   int32_t* fired_idx;
   int32_t* n_fired;
   int32_t src_map;    /* -1: X is an external buffer; j >= 0: X is the output Y of maps[j]      */
-  int32_t flags;      /* 0, or a combination of GSI_INPUT_SLOW_PATH_WX, GSI_INPUT_FUSED_KERNEL   */
+  int32_t flags;      /* 0, or a combination of the GSI_INPUT_* flags below                     */
+  const float* gram;  /* [k,k] fp32, E = U^T U - I from gsi_build_gram; read only with           */
+                      /* GSI_INPUT_GATE_SINGLE_PASS, may be NULL otherwise                       */
 } gsi_input_desc;
 
 /* gsi_input_desc.flags.  By default a fired token gets y = M c + W r (Eq. (exact)).  With
@@ -129,7 +137,17 @@ typedef struct gsi_input_desc {
  * Algorithm 1 (line 7) prints it: equal in exact arithmetic, but free of the stored image's rounding, so
  * that a fired token equals the dense product of gsi_dense_stack.  Tokens that did not fire are not
  * affected.  gsi_gated_linear has no x and always uses the default form. */
-enum { GSI_INPUT_SLOW_PATH_WX = 1, GSI_INPUT_FUSED_KERNEL = 2 };
+enum { GSI_INPUT_SLOW_PATH_WX = 1, GSI_INPUT_FUSED_KERNEL = 2, GSI_INPUT_GATE_SINGLE_PASS = 4 };
+
+/* GSI_INPUT_GATE_SINGLE_PASS (single-token calls, B == 1, on the vector kernels; otherwise ignored and the
+ * residual is formed as usual): the residual ratio of Eq. (rho) is evaluated in ONE pass over the basis.  For
+ * c = U^T x and any stored U,  |x - U c|^2 = |x|^2 - |c|^2 + c^T E c  with  E = U^T U - I  (gsi_build_gram; E is
+ * zero only for an exactly orthonormal basis, which a basis rounded to bf16 is not), so the gate needs U once and
+ * the k x k matrix E instead of U a second time.  The two large terms and the final combination are accumulated
+ * in fp64.  rnorm, xnorm, mask, fired_idx, n_fired and C are written as always (rnorm from the formula);
+ * R is written ONLY when the gate fires (an un-fired token's r is never needed); with GSI_INPUT_SLOW_PATH_WX as
+ * well R is not written at all and the maps of a fired input skip their image rows: fast-path tokens read M,
+ * slow-path tokens read W, merged in one output (Section 7.3 "Kernel-level implementation"). */
 
 /* GSI_INPUT_FUSED_KERNEL (single-token calls, B == 1; ignored otherwise): this input and the maps that read
  * it are processed by the fused kernel -- projection, residual, gate, image rows and, if the gate fires, the

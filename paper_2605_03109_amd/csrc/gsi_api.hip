@@ -160,6 +160,19 @@ int gsi_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d,
   return GSI_OK;
 }
 
+int gsi_build_gram(const void* U, int64_t d, int64_t k, int udtype, float* E, void* stream) {
+  GSI_REQUIRE_PTR(U);
+  GSI_REQUIRE_PTR(E);
+  if (!dtype_ok(udtype)) return fail(GSI_ERR_DTYPE, "gsi_build_gram: unknown udtype %d", udtype);
+  if (int rc = check_shape("gsi_build_gram", 1, d, k, 0)) return rc;
+  GSI_REQUIRE_ALIGNED(U, gsi::elem_size(udtype));
+  GSI_REQUIRE_ALIGNED(E, 4);
+  if (k > 65535 * 16) return fail(GSI_ERR_SHAPE, "gsi_build_gram: k = %lld is too large", (long long)k);
+  hipError_t e = gsi::generic_build_gram(U, d, k, udtype, E, static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, "gsi_build_gram");
+  return GSI_OK;
+}
+
 int gsi_quantize_image_fp8(const void* M, int mdtype, int64_t m, int64_t k, uint8_t* M8, float* scale, void* stream) {
   GSI_REQUIRE_PTR(M);
   GSI_REQUIRE_PTR(M8);
@@ -711,8 +724,12 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // validate everything before the first launch
   for (int i = 0; i < n_inputs; ++i) {
     const gsi_input_desc& in = inputs[i];
-    if (in.flags & ~(GSI_INPUT_SLOW_PATH_WX | GSI_INPUT_FUSED_KERNEL))
+    if (in.flags & ~(GSI_INPUT_SLOW_PATH_WX | GSI_INPUT_FUSED_KERNEL | GSI_INPUT_GATE_SINGLE_PASS))
       return fail(GSI_ERR_SHAPE, "%s: inputs[%d].flags = %d has unknown bits", fn, i, in.flags);
+    if (in.flags & GSI_INPUT_GATE_SINGLE_PASS) {
+      if (!in.gram) return fail(GSI_ERR_NULL, "%s: inputs[%d].gram is NULL with GSI_INPUT_GATE_SINGLE_PASS", fn, i);
+      if (!aligned(in.gram, 4)) return fail(GSI_ERR_ALIGN, "%s: inputs[%d].gram is not aligned to 4 bytes", fn, i);
+    }
     if (int rc = check_project_args(fn, in.U, in.X, in.d, in.k, B, in.udtype, in.xdtype, in.C, in.R, in.rnorm,
                                     in.xnorm))
       return rc;
@@ -934,10 +951,18 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     // independent inputs), the coefficient sums of set g - 1, the residuals and image rows of set g - 2 and the
     // gates of set g - 3.  A call of one set skips the sum stage (its residual and image workgroups add the
     // partials themselves: the same function, the same bits).
-    for (int dt = 0; dt < 2 && B == 1; ++dt) {
+    // With the single-pass gate (GSI_INPUT_GATE_SINGLE_PASS and a 16-byte aligned E) the stages are: partial
+    // projections and shares of |x|^2 of set g; coefficient sums and shares of c^T E c of set g - 1; image rows
+    // and, behind the gate their workgroups evaluate, residuals of set g - 2.
+    for (int pass = 0; pass < 4 && B == 1; ++pass) {
+      const int dt = pass & 1;
+      const bool sp = pass >= 2;
+      auto single_pass = [&](int i) {
+        return (inputs[i].flags & GSI_INPUT_GATE_SINGLE_PASS) && aligned(inputs[i].gram, 16);
+      };
       std::vector<int> list;
       for (int i : ready)
-        if (mode[i] == kVecInline && inputs[i].udtype == dt) list.push_back(i);
+        if (mode[i] == kVecInline && inputs[i].udtype == dt && single_pass(i) == sp) list.push_back(i);
       if (list.empty()) continue;
       const int nsets = (int)gsi::ceil_div((int64_t)list.size(), gsi::kMaxTasks);
       for (int g = 0; g < nsets; ++g) {  // the largest input of a set goes first so that its workgroups start first
@@ -951,17 +976,24 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         return (g < 0 || g >= nsets) ? 0 : std::min<int>(gsi::kMaxTasks, (int)list.size() - g * gsi::kMaxTasks);
       };
       auto member = [&](int g, int q) { return list[(size_t)g * gsi::kMaxTasks + q]; };
-      const int sum_stage = nsets > 1 ? 1 : 0;
-      for (int g = 0; g < nsets + 2 + sum_stage; ++g) {
+      const int sum_stage = (sp || nsets > 1) ? 1 : 0;
+      for (int g = 0; g < nsets + 2 + sum_stage - (sp ? 1 : 0); ++g) {
         gsi::StageArgs a;
         gsi::stage_clear(a, eps);
-        for (int q = 0; q < set_size(g); ++q) gsi::stage_add_part(a, ptask[member(g, q)]);
+        for (int q = 0; q < set_size(g); ++q) {
+          const int i = member(g, q);
+          gsi::stage_add_part(a, ptask[i], sp ? inputs[i].gram : nullptr);
+        }
         if (sum_stage)
-          for (int q = 0; q < set_size(g - 1); ++q) gsi::stage_add_cred(a, ptask[member(g - 1, q)]);
+          for (int q = 0; q < set_size(g - 1); ++q) {
+            const int i = member(g - 1, q);
+            gsi::stage_add_cred(a, ptask[i], sp ? inputs[i].gram : nullptr);
+          }
         const int gr = g - 1 - sum_stage;
         for (int q = 0; q < set_size(gr); ++q) {
           const int i = member(gr, q);
-          const int res = gsi::stage_add_res(a, ptask[i], sum_stage != 0);
+          const bool wx = (inputs[i].flags & GSI_INPUT_SLOW_PATH_WX) != 0;
+          const int res = gsi::stage_add_res(a, ptask[i], sum_stage != 0, sp ? inputs[i].gram : nullptr, sp && wx);
           for (int j = 0; j < n_maps && a.ni < gsi::kMaxLinTasks; ++j) {
             if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
             gsi::stage_add_img(a, res, maps[j].M, maps[j].Y,
@@ -969,7 +1001,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
             img_done[j] = 1;
           }
         }
-        for (int q = 0; q < set_size(gr - 1); ++q) gsi::stage_add_gate(a, ptask[member(gr - 1, q)]);
+        if (!sp)
+          for (int q = 0; q < set_size(gr - 1); ++q) gsi::stage_add_gate(a, ptask[member(gr - 1, q)]);
         const bool timed = which == 0 && n_stage_launches == launch_index;
         ++n_stage_launches;
         if (hipError_t e = gsi::stage_launch(a, dt, s, timed ? ev_begin : nullptr, timed ? ev_end : nullptr);

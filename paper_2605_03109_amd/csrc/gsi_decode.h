@@ -136,15 +136,24 @@ struct StagePart {        // partial projection c = U^T x of one input over row 
   const void* U;
   const void* X;
   float* part_c;          // [slabs][k]
-  int d, k, rows;         // rows per slab
+  int d;
+  int k_rows;             // k | rows per slab << 16
   int slabs_x;            // slabs | xdtype << 16
+  int x2_off;             // single-pass gate: byte offset from part_c of the slab shares of |x|^2 (doubles); else 0
 };
 
-struct StageCRed {        // c = sum of the partials in fixed slab order, one workgroup per input
+struct StageCRed {        // c = sum of the partials in fixed slab order, one workgroup per input ...
   const float* part_c;
   float* C;
-  int k, slabs;
+  const float* E;         // ... or, single-pass gate (E = U^T U - I, [k][k] fp32): kGramBlocks workgroups per input,
+                          //     each adds the partials, takes a block of rows of E and writes its share of c^T E c
+                          //     to gw[slabs + block]; block 0 also writes C and |c|^2 to gw[slabs + kGramBlocks]
+  int k_slabs;            // k | slabs << 16
+  int gw_off;             // byte offset from part_c of the doubles gw
 };
+constexpr int kGramBlocks = 16;
+// doubles of the single-pass gate per input: slab shares of |x|^2, block shares of c^T E c, |c|^2
+constexpr int kGateDoubles = kPartSlabs + kGramBlocks + 1;
 
 struct StageRes {         // r = x - U c, and the slab shares of |r|^2, |x|^2, of one input over row slabs
   const void* U;
@@ -152,10 +161,12 @@ struct StageRes {         // r = x - U c, and the slab shares of |r|^2, |x|^2, o
   const float* part_c;    // null: c is read from C; else c is the sum of these partials and slab 0 writes C
   float* C;
   float* R;
-  float* part_n;          // [b_slabs][2]
-  int d, k, b_rows, b_slabs;
-  int a_slabs_x;          // slabs of the partial projection | xdtype << 16
-  int pad;
+  float* part_n;          // [b_slabs][2]; unused with the single-pass gate
+  int d;
+  int k_rows;             // k | b_rows << 16
+  int slabs_x;            // b_slabs | slabs of the partial projection << 16 | xdtype << 24
+  int gate;               // single-pass gate: 1 + index of this input's StageGate, evaluated by every residual
+                          // workgroup (r is formed only if the gate fires); else 0
 };
 
 struct StageImg {         // image rows y = M c of one map
@@ -167,13 +178,14 @@ struct StageImg {         // image rows y = M c of one map
 };
 
 struct StageGate {        // |r|, |x| from the slab shares and Eq. (gate) of one input
-  const float* part_n;
+  const float* part_n;    // single-pass gate: the input's kGateDoubles doubles instead
   float* rnorm;
   float* xnorm;
   uint8_t* mask;
   int32_t* fired_idx;
   int32_t* n_fired;
-  int b_slabs, pad;
+  int b_slabs;            // single-pass gate: slabs of the partial projection
+  int skip_fired_image;   // single-pass gate: image rows of this input are left to the weight kernel when it fires
 };
 
 struct StageArgs {
@@ -186,7 +198,9 @@ struct StageArgs {
   int b_begin[kMaxTasks];
   int na, ncr, nb, ni, ng;
   int a_total, b_total, i_total;  // workgroups per role; grid order: residual slabs, partial projections, image
-                                  // rows, coefficient sums and gates (one workgroup each)
+                                  // rows, coefficient sums and gates (one workgroup each; kGramBlocks per sum
+                                  // with the single-pass gate, whose gates have no workgroups of their own)
+  int gram;                       // the launch's inputs use the single-pass gate
   float eps;
 };
 static_assert(sizeof(StageArgs) <= 4096, "kernel arguments are limited to 4 KB");
@@ -194,9 +208,11 @@ static_assert(sizeof(StageArgs) <= 4096, "kernel arguments are limited to 4 KB")
 // rows per slab and slabs of the single-token partial projection
 void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs);
 void stage_clear(StageArgs& a, float eps);
-void stage_add_part(StageArgs& a, const ProjTask& t);
-void stage_add_cred(StageArgs& a, const ProjTask& t);
-int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready);  // returns its index
+// E (single-pass gate): the input's cached U^T U - I, else null
+void stage_add_part(StageArgs& a, const ProjTask& t, const float* E = nullptr);
+void stage_add_cred(StageArgs& a, const ProjTask& t, const float* E = nullptr);
+// returns its index; single-pass gate: the residual workgroups evaluate and publish the gate themselves
+int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready, const float* E = nullptr, bool skip_fired_image = false);
 void stage_add_img(StageArgs& a, int res, const void* M, float* Y, const float* scale, int m);
 void stage_add_gate(StageArgs& a, const ProjTask& t);
 // e0 / e1 (optional): events that take the start / stop timestamps of the dispatch

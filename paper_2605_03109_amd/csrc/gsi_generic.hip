@@ -188,4 +188,36 @@ hipError_t generic_dense_linear(const void* W, const void* X, int64_t m, int64_t
   return hipGetLastError();
 }
 
+// E = U^T U - I in fp64 (one-time companion of a basis for the single-pass gate): a 16 x 16 tile of E per
+// workgroup, 64 rows of the two column strips of U staged in LDS per step, one fp64 accumulator per thread.
+template <class T>
+__global__ __launch_bounds__(kBlock) void gen_gram(const typename T::storage* __restrict__ U, int64_t d, int64_t k,
+                                                   float* __restrict__ E) {
+  __shared__ float a[64][17], b[64][17];
+  const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
+  const int64_t i0 = (int64_t)blockIdx.y * 16, j0 = (int64_t)blockIdx.x * 16;
+  double acc = 0.0;
+  for (int64_t r0 = 0; r0 < d; r0 += 64) {
+    for (int e = threadIdx.x; e < 64 * 16; e += kBlock) {
+      const int rr = e / 16, cc = e % 16;
+      const int64_t r = r0 + rr;
+      a[rr][cc] = (r < d && i0 + cc < k) ? T::load(U, r * k + i0 + cc) : 0.f;
+      b[rr][cc] = (r < d && j0 + cc < k) ? T::load(U, r * k + j0 + cc) : 0.f;
+    }
+    __syncthreads();
+#pragma unroll 8
+    for (int rr = 0; rr < 64; ++rr) acc = fma((double)a[rr][ty], (double)b[rr][tx], acc);
+    __syncthreads();
+  }
+  const int64_t i = i0 + ty, j = j0 + tx;
+  if (i < k && j < k) E[i * k + j] = (float)(acc - (i == j ? 1.0 : 0.0));
+}
+
+hipError_t generic_build_gram(const void* U, int64_t d, int64_t k, int udtype, float* E, hipStream_t s) {
+  const dim3 grid((unsigned)ceil_div(k, 16), (unsigned)ceil_div(k, 16));
+  if (udtype == GSI_BF16) gen_gram<BF16><<<grid, kBlock, 0, s>>>((const uint16_t*)U, d, k, E);
+  else gen_gram<F32><<<grid, kBlock, 0, s>>>((const float*)U, d, k, E);
+  return hipGetLastError();
+}
+
 }  // namespace gsi

@@ -15,6 +15,7 @@ inline size_t align_up(size_t a, size_t b) { return (a + b - 1) / b * b; }
 // ---- generic kernels: any shape, element-wise access ---------------------------------------------
 hipError_t generic_build_image(const void* W, const void* U, void* M, int64_t m, int64_t d, int64_t k, int wdtype,
                                hipStream_t s);
+hipError_t generic_build_gram(const void* U, int64_t d, int64_t k, int udtype, float* E, hipStream_t s);
 hipError_t generic_project(const void* U, const void* X, int64_t d, int64_t k, int64_t B, int udtype, int xdtype,
                            float* C, float* R, float* rnorm, float* xnorm, hipStream_t s);
 hipError_t generic_gated_linear(const void* W, const void* M, const float* C, const float* R,

@@ -406,7 +406,9 @@ size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype) {
   int s_rows = 0, s_slabs = 0;
   if (B == 1) stage_geom(d, k, udtype, s_rows, s_slabs);
   const size_t part_slabs = (size_t)std::max(g.a_slabs, s_slabs);
-  size_t need = align_up(part_slabs * B * k * 4, 256) + align_up((size_t)g.b_slabs * B * 2 * 4, 256);
+  // (a single token's slab shares of the norms, or the kGateDoubles doubles of the single-pass gate)
+  size_t need = align_up(part_slabs * B * k * 4, 256) +
+                align_up(std::max((size_t)g.b_slabs * B * 2 * 4, sizeof(double) * kGateDoubles), 256);
   if (tile_project_shape_ok(d, k, B, udtype)) need = std::max(need, tile_project_ws(d, k, B));
   return need;
 }

@@ -15,6 +15,15 @@
 // fill with the others and a call of n sets makes n + 3 launches instead of 3 n.  Nothing inside a launch waits
 // for anything else in it: every dependency is a launch boundary.
 //
+//
+// Single-pass gate (inputs with a cached E = U^T U - I): |r|^2 = |x|^2 - |c|^2 + c^T E c holds for ANY stored U when
+// c = U^T x, so the gate needs no second pass over U.  The partial workgroups also write their slab's share of
+// |x|^2; the sum stage becomes kGramBlocks workgroups per input that add the partials, take a block of rows of E
+// each and write their share of c^T E c; every residual workgroup then evaluates the gate from those shares
+// (identical arithmetic, so the verdict is uniform without communication), workgroup 0 of the input publishes
+// it, and r = x - U c is formed only when the gate fires.  The shares of the two large terms and the final
+// combination are fp64: their difference is 400 times smaller than either at the threshold 0.05.
+//
 // All sums have a fixed order: results are bit-identical run to run.
 #include <hip/hip_ext.h>
 
@@ -39,18 +48,51 @@ __device__ __forceinline__ int find_task(const int (&begin)[N], int n, int b) {
   return t;
 }
 
+// sum over the wave in a fixed (butterfly) order; every lane gets the total
+__device__ __forceinline__ double wave_sum_f64(double v) {
+#pragma unroll
+  for (int o = 1; o < kWave; o <<= 1) v += __shfl_xor(v, o, kWave);
+  return v;
+}
+
+// Eq. (gate) from the single-pass shares of one input: gw = [slabs shares of |x|^2][kGramBlocks shares of
+// c^T E c][|c|^2], at most one per lane.  Called by whole waves: every lane loads one value (one memory latency in
+// all), the sums run over the wave in a fixed butterfly order, so every wave of every workgroup reaches the
+// same verdict.
+__device__ __forceinline__ bool single_pass_gate(const double* __restrict__ gw, int slabs, float eps, float& rn,
+                                                 float& xn) {
+  static_assert(kGateDoubles <= kWave, "one share per lane");
+  const int lane = threadIdx.x % kWave;
+  const double v = lane < slabs + kGramBlocks + 1 ? gw[lane] : 0.0;
+  const double x2 = wave_sum_f64(lane < slabs ? v : 0.0);
+  const double q = wave_sum_f64(lane >= slabs && lane < slabs + kGramBlocks ? v : 0.0);
+  const double c2 = __shfl(v, slabs + kGramBlocks, kWave);
+  const double r2 = x2 - c2 + q;
+  rn = (float)sqrt(r2 > 0.0 ? r2 : 0.0);
+  xn = (float)sqrt(x2);
+  return gate_fires(rn, xn, eps);
+}
+
+__device__ __forceinline__ void publish_gate(const StageGate& g, float rn, float xn, bool f) {
+  g.rnorm[0] = rn;
+  g.xnorm[0] = xn;
+  g.mask[0] = f ? 1 : 0;
+  if (f) g.fired_idx[0] = 0;
+  g.n_fired[0] = f ? 1 : 0;
+}
+
 template <class T>
 __device__ __forceinline__ void partial_block(const StagePart& p, int slab, float* __restrict__ red,
-                                              float* __restrict__ xs) {
+                                              float* __restrict__ xs, double* __restrict__ dsh) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
-  const int d = p.d, k = p.k;
+  const int d = p.d, k = p.k_rows & 0xffff, prow = p.k_rows >> 16;
   const int cpr = k / V;         // lanes per row of U (a power of two, one wave at most)
   const int rps = kBlock / cpr;  // rows per step
   const int lsh = __builtin_ctz(cpr);
   const int cc = threadIdx.x & (cpr - 1), ro = threadIdx.x >> lsh;
-  const int row0 = slab * p.rows;
-  const int rows = min(p.rows, d - row0);
+  const int row0 = slab * prow;
+  const int rows = min(prow, d - row0);
   const S* U = reinterpret_cast<const S*>(p.U) + (int64_t)row0 * k + cc * V;
   const int xdtype = p.slabs_x >> 16;
 
@@ -65,7 +107,12 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
 #pragma unroll
     for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
   }
-  for (int r = threadIdx.x; r < rows; r += kBlock) xs[r] = load_act(p.X, xdtype, row0 + r);
+  double x2 = 0.0;  // this thread's share of the slab's |x|^2 (single-pass gate)
+  for (int r = threadIdx.x; r < rows; r += kBlock) {
+    const float xv = load_act(p.X, xdtype, row0 + r);
+    xs[r] = xv;
+    x2 = fma((double)xv, (double)xv, x2);
+  }
   __syncthreads();
   if (first) {
 #pragma unroll
@@ -113,7 +160,16 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
 #pragma unroll
   for (int q = 0; q < V / 4; ++q)
     reinterpret_cast<float4*>(red + ro * k + cc * V)[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+  if (p.x2_off) {
+    x2 = wave_sum_f64(x2);
+    if (threadIdx.x % kWave == 0) dsh[threadIdx.x / kWave] = x2;
+  }
   __syncthreads();
+  if (p.x2_off && threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kWaves; ++w) t += dsh[w];
+    reinterpret_cast<double*>(reinterpret_cast<char*>(p.part_c) + p.x2_off)[slab] = t;
+  }
   for (int j = threadIdx.x; j < k; j += kBlock) {
     float s = 0.f;
     for (int g = 0; g < rps; g += 4) {  // rps is a multiple of 4: four LDS reads in flight, fixed order of adds
@@ -129,22 +185,81 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
 
 // c = the partials of one input added in slab order (one workgroup)
 __device__ __forceinline__ void cred_block(const StageCRed& p) {
-  for (int j = threadIdx.x; j < p.k; j += kBlock) p.C[j] = sum_partials(p.part_c + j, p.k, p.slabs);
+  const int k = p.k_slabs & 0xffff, slabs = p.k_slabs >> 16;
+  for (int j = threadIdx.x; j < k; j += kBlock) p.C[j] = sum_partials(p.part_c + j, k, slabs);
+}
+
+// Single-pass gate: block `blk` of kGramBlocks adds the partials of one input (block 0 writes C and |c|^2), then
+// takes rows [blk * rpb, (blk + 1) * rpb) of E: share = sum_i c_i (sum_j E_ij c_j).  A wave takes a row at a time,
+// a lane the 16-byte pieces lane, lane + 64, ... of it.
+__device__ __forceinline__ void gram_block(const StageCRed& p, int blk, float* __restrict__ cs, double* __restrict__ dsh) {
+  const int k = p.k_slabs & 0xffff, slabs = p.k_slabs >> 16;
+  double* __restrict__ gw = reinterpret_cast<double*>(reinterpret_cast<char*>(const_cast<float*>(p.part_c)) + p.gw_off);
+  const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
+  for (int j = threadIdx.x; j < k; j += kBlock) {
+    const float c = sum_partials(p.part_c + j, k, slabs);
+    cs[j] = c;
+    if (blk == 0) p.C[j] = c;
+  }
+  __syncthreads();
+  const int rpb = (k + kGramBlocks - 1) / kGramBlocks;
+  const int row_end = min(k, (blk + 1) * rpb);
+  const int pieces = k / 4;  // k is a multiple of four on this path
+  double acc = 0.0;
+  for (int i = blk * rpb + wave; i < row_end; i += kWaves) {
+    const float4* __restrict__ row = reinterpret_cast<const float4*>(p.E + (int64_t)i * k);
+    float s = 0.f;
+    for (int q = lane; q < pieces; q += kWave) {
+      const float4 e = row[q];
+      const float4 c = reinterpret_cast<const float4*>(cs)[q];
+      s = fmaf(e.x, c.x, s);
+      s = fmaf(e.y, c.y, s);
+      s = fmaf(e.z, c.z, s);
+      s = fmaf(e.w, c.w, s);
+    }
+    s = group_sum<kWave>(s);
+    acc = fma((double)cs[i], (double)s, acc);
+  }
+  if (lane == 0) dsh[wave] = acc;
+  if (blk == 0) {  // |c|^2: each thread its coefficients j, j + 256, ...; waves in order
+    double c2 = 0.0;
+    for (int j = threadIdx.x; j < k; j += kBlock) c2 = fma((double)cs[j], (double)cs[j], c2);
+    c2 = wave_sum_f64(c2);
+    if (lane == 0) dsh[kWaves + wave] = c2;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double t = 0.0;
+    for (int w = 0; w < kWaves; ++w) t += dsh[w];
+    gw[slabs + blk] = t;
+    if (blk == 0) {
+      double c2 = 0.0;
+      for (int w = 0; w < kWaves; ++w) c2 += dsh[kWaves + w];
+      gw[slabs + kGramBlocks] = c2;
+    }
+  }
 }
 
 template <class T>
-__device__ __forceinline__ void residual_block(const StageRes& p, int slab, float* __restrict__ cs,
-                                               float* __restrict__ xs, float* nr, float* nx) {
+__device__ __forceinline__ void residual_block(const StageRes& p, const StageGate* gates, float eps, int slab,
+                                               float* __restrict__ cs, float* __restrict__ xs, float* nr, float* nx) {
   constexpr int V = T::kVec;
   constexpr int PF = 4;  // row steps of U held in registers
   using S = typename T::storage;
-  const int d = p.d, k = p.k;
-  const int xdtype = p.a_slabs_x >> 16, a_slabs = p.a_slabs_x & 0xffff;
+  const int d = p.d, k = p.k_rows & 0xffff, b_rows = p.k_rows >> 16;
+  const int xdtype = p.slabs_x >> 24, a_slabs = (p.slabs_x >> 16) & 0xff;
+  if (p.gate) {  // single-pass gate: the verdict first; an input that did not fire needs no residual
+    const StageGate& g = gates[p.gate - 1];
+    float rn, xn;
+    const bool f = single_pass_gate(reinterpret_cast<const double*>(g.part_n), g.b_slabs, eps, rn, xn);
+    if (slab == 0 && threadIdx.x == 0) publish_gate(g, rn, xn, f);
+    if (!f || g.skip_fired_image) return;  // (the W x form of the slow path reads x, not r)
+  }
   const int cpr = k / V;         // 16-byte chunks per row (power of two, <= 64)
   const int rps = kBlock / cpr;  // rows per step
   const int cc = threadIdx.x & (cpr - 1), ro = threadIdx.x >> __builtin_ctz(cpr);
-  const int row0 = slab * p.b_rows;
-  const int rows = min(p.b_rows, d - row0);
+  const int row0 = slab * b_rows;
+  const int rows = min(b_rows, d - row0);
   const int steps = (rows + rps - 1) / rps;
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
   const S* U = reinterpret_cast<const S*>(p.U) + (int64_t)row0 * k + cc * V;
@@ -197,6 +312,7 @@ __device__ __forceinline__ void residual_block(const StageRes& p, int slab, floa
     for (int q = 0; q < PF; ++q)
       if (st0 + q < steps) row_step(u[q], xs[min((st0 + q) * rps + ro, rows - 1)], st0 + q);
   }
+  if (p.gate) return;  // the norms came from the single-pass shares
   const float sr = group_sum<kWave>(ar);
   const float sx = group_sum<kWave>(ax);
   if (lane == 0) {
@@ -222,12 +338,7 @@ __device__ __forceinline__ void gate_block(const StageGate& g, float eps) {
   wave_norm_sums(g.part_n, g.b_slabs, 1, 0, tr, tx);
   if (threadIdx.x == 0) {
     const float rn = sqrtf(tr), xn = sqrtf(tx);
-    const bool f = gate_fires(rn, xn, eps);
-    g.rnorm[0] = rn;
-    g.xnorm[0] = xn;
-    g.mask[0] = f ? 1 : 0;
-    if (f) g.fired_idx[0] = 0;
-    g.n_fired[0] = f ? 1 : 0;
+    publish_gate(g, rn, xn, gate_fires(rn, xn, eps));
   }
 }
 
@@ -236,16 +347,17 @@ __global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
   __shared__ __align__(16) float lds[kBlock * 8];  // partial: [row group][k]; residual, image: the coefficients
   __shared__ float xs[kStageMaxRows];              // the slab's activations
   __shared__ float nr[kWaves], nx[kWaves];
+  __shared__ double dsh[2 * kWaves];
   int b = blockIdx.x;
   if (b < a.b_total) {
     const int ti = find_task(a.b_begin, a.nb, b);
-    residual_block<T>(a.b[ti], b - a.b_begin[ti], lds, xs, nr, nx);
+    residual_block<T>(a.b[ti], a.g, a.eps, b - a.b_begin[ti], lds, xs, nr, nx);
     return;
   }
   b -= a.b_total;
   if (b < a.a_total) {
     const int ti = find_task(a.a_begin, a.na, b);
-    partial_block<T>(a.a[ti], b - a.a_begin[ti], lds, xs);
+    partial_block<T>(a.a[ti], b - a.a_begin[ti], lds, xs, dsh);
     return;
   }
   b -= a.a_total;
@@ -256,13 +368,22 @@ __global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
       if (i < a.ni && b >= (a.im[i].blk_res & 0xffffff)) ti = i;
     const StageImg& im = a.im[ti];
     const StageRes& r = a.b[im.blk_res >> 24];
+    if (r.gate && a.g[r.gate - 1].skip_fired_image) {  // fired: the weight kernel writes y = W x (Algorithm 1, line 7)
+      const StageGate& g = a.g[r.gate - 1];
+      float rn, xn;
+      if (single_pass_gate(reinterpret_cast<const double*>(g.part_n), g.b_slabs, a.eps, rn, xn)) return;
+    }
     ImgTask t;
     t.M = im.M; t.Y = im.Y; t.part_c = r.part_c; t.C = r.C; t.scale = im.scale;
-    t.m = im.m; t.k = r.k; t.a_slabs = r.a_slabs_x & 0xffff; t.blk_begin = im.blk_res & 0xffffff;
+    t.m = im.m; t.k = r.k_rows & 0xffff; t.a_slabs = (r.slabs_x >> 16) & 0xff; t.blk_begin = im.blk_res & 0xffffff;
     image_block<T>(t, b - t.blk_begin, lds);
     return;
   }
   b -= a.i_total;
+  if (a.gram) {
+    if (b < a.ncr * kGramBlocks) gram_block(a.cr[b / kGramBlocks], b % kGramBlocks, lds, dsh);
+    return;
+  }
   if (b < a.ncr) {
     cred_block(a.cr[b]);
     return;
@@ -290,22 +411,33 @@ void stage_clear(StageArgs& a, float eps) {
   a.eps = eps;
 }
 
-void stage_add_part(StageArgs& a, const ProjTask& t) {
+void stage_add_part(StageArgs& a, const ProjTask& t, const float* E) {
   StagePart& p = a.a[a.na++];
   p.U = t.U; p.X = t.X; p.part_c = t.part_c;
-  p.d = t.d; p.k = t.k; p.rows = t.s_rows; p.slabs_x = t.s_slabs | (t.xdtype << 16);
+  p.d = t.d; p.k_rows = t.k | (t.s_rows << 16); p.slabs_x = t.s_slabs | (t.xdtype << 16);
+  p.x2_off = E ? (int)(reinterpret_cast<char*>(t.part_n) - reinterpret_cast<char*>(t.part_c)) : 0;
 }
 
-void stage_add_cred(StageArgs& a, const ProjTask& t) {
+void stage_add_cred(StageArgs& a, const ProjTask& t, const float* E) {
   StageCRed& p = a.cr[a.ncr++];
-  p.part_c = t.part_c; p.C = t.C; p.k = t.k; p.slabs = t.s_slabs;
+  p.part_c = t.part_c; p.C = t.C; p.k_slabs = t.k | (t.s_slabs << 16);
+  p.E = E; p.gw_off = (int)(reinterpret_cast<char*>(t.part_n) - reinterpret_cast<char*>(t.part_c));
+  if (E) a.gram = 1;
 }
 
-int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready) {
+int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready, const float* E, bool skip_fired_image) {
   StageRes& p = a.b[a.nb];
   p.U = t.U; p.X = t.X; p.part_c = c_ready ? nullptr : t.part_c; p.C = t.C; p.R = t.R; p.part_n = t.part_n;
-  p.d = t.d; p.k = t.k; p.b_rows = t.b_rows; p.b_slabs = t.b_slabs;
-  p.a_slabs_x = t.s_slabs | (t.xdtype << 16);
+  p.d = t.d; p.k_rows = t.k | (t.b_rows << 16);
+  p.slabs_x = t.b_slabs | (t.s_slabs << 16) | (t.xdtype << 24);
+  p.gate = 0;
+  if (E) {  // the gate of this input is evaluated by its residual workgroups: entry a.nb of the gate table
+    StageGate& g = a.g[a.nb];
+    g.part_n = t.part_n; g.rnorm = t.rnorm; g.xnorm = t.xnorm; g.mask = t.mask; g.fired_idx = t.fired_idx;
+    g.n_fired = t.n_fired; g.b_slabs = t.s_slabs; g.skip_fired_image = skip_fired_image ? 1 : 0;
+    p.gate = a.nb + 1;
+    a.gram = 1;
+  }
   return a.nb++;
 }
 
@@ -317,7 +449,7 @@ void stage_add_img(StageArgs& a, int res, const void* M, float* Y, const float* 
 void stage_add_gate(StageArgs& a, const ProjTask& t) {
   StageGate& g = a.g[a.ng++];
   g.part_n = t.part_n; g.rnorm = t.rnorm; g.xnorm = t.xnorm; g.mask = t.mask; g.fired_idx = t.fired_idx;
-  g.n_fired = t.n_fired; g.b_slabs = t.b_slabs;
+  g.n_fired = t.n_fired; g.b_slabs = t.b_slabs; g.skip_fired_image = 0;
 }
 
 hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
@@ -328,16 +460,16 @@ hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0, h
   }
   for (int i = 0; i < a.nb; ++i) {
     a.b_begin[i] = tb;
-    tb += a.b[i].b_slabs;
+    tb += a.b[i].slabs_x & 0xffff;
   }
   for (int i = 0; i < a.ni; ++i) {
     const int res = a.im[i].blk_res >> 24;
     a.im[i].blk_res = (res << 24) | ti;
-    ti += image_blocks(a.im[i].m, a.b[res].k, dtype, a.im[i].scale != nullptr);
+    ti += image_blocks(a.im[i].m, a.b[res].k_rows & 0xffff, dtype, a.im[i].scale != nullptr);
     if (ti >= (1 << 24)) return hipErrorInvalidValue;
   }
   a.a_total = ta; a.b_total = tb; a.i_total = ti;
-  const int grid = ta + tb + ti + a.ncr + a.ng;
+  const int grid = ta + tb + ti + (a.gram ? a.ncr * kGramBlocks : a.ncr + a.ng);
   if (grid == 0) return hipSuccess;
   if (dtype == GSI_BF16) {
     if (e0 && e1) hipExtLaunchKernelGGL((proj_stage<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, a);

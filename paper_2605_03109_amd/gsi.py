@@ -22,11 +22,12 @@ GSI_ERR_NULL, GSI_ERR_SHAPE, GSI_ERR_DTYPE, GSI_ERR_ALIGN, GSI_ERR_WORKSPACE, GS
 GSI_F32, GSI_BF16 = 0, 1
 INPUT_SLOW_PATH_WX = 1  # gsi_input_desc.flags: fired tokens get y = W x (Algorithm 1, line 7)
 INPUT_FUSED_KERNEL = 2  # gsi_input_desc.flags: single-token calls take the fused kernel (one launch, basis read once)
+INPUT_GATE_SINGLE_PASS = 4  # gsi_input_desc.flags: residual ratio from |x|^2 - |c|^2 + c^T E c, E = U^T U - I (`gram`)
 MAP_IMAGE_FP8 = 1  # gsi_map_desc.flags: M holds E4M3 codes, M_scale the row scales (single-token calls)
 CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
 
 EXPORTS = (
-    "gsi_build_image", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+    "gsi_build_image", "gsi_build_gram", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
     "gsi_layer_stack",
     "gsi_layer_stack_static", "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
@@ -50,6 +51,7 @@ class InputDesc(ctypes.Structure):
         ("rnorm", ctypes.c_void_p), ("xnorm", ctypes.c_void_p),
         ("mask", ctypes.c_void_p), ("fired_idx", ctypes.c_void_p), ("n_fired", ctypes.c_void_p),
         ("src_map", ctypes.c_int32), ("flags", ctypes.c_int32),
+        ("gram", ctypes.c_void_p),
     ]
 
 
@@ -71,6 +73,7 @@ def _load() -> ctypes.CDLL:
     vp, i64, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int, ctypes.c_size_t, ctypes.c_float
     lib.gsi_build_image.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
     lib.gsi_quantize_image_fp8.argtypes = [vp, i32, i64, i64, vp, vp, vp]
+    lib.gsi_build_gram.argtypes = [vp, i64, i64, i32, vp, vp]
     lib.gsi_project.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.gsi_gate.argtypes = [vp, vp, i64, f32, vp, vp, vp, vp]
     lib.gsi_gated_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, i32, vp, sz, vp]
@@ -95,7 +98,7 @@ def _load() -> ctypes.CDLL:
     lib.gsi_fused_timeouts.restype = ctypes.c_int
     lib.gsi_last_error.restype = ctypes.c_char_p
     lib.gsi_version.restype = ctypes.c_int
-    for name in ("gsi_build_image", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+    for name in ("gsi_build_image", "gsi_build_gram", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
                  "gsi_layer_stack", "gsi_layer_stack_timed", "gsi_dense_stack"):
         getattr(lib, name).restype = ctypes.c_int
     return lib
@@ -204,6 +207,14 @@ def build_image(W: torch.Tensor, U: torch.Tensor, M: Optional[torch.Tensor] = No
     return M
 
 
+def build_gram(U: torch.Tensor, E: Optional[torch.Tensor] = None, stream=None) -> torch.Tensor:
+    """E[k,k] (fp32) = U^T U - I of a stored basis U[d,k]."""
+    d, k = U.shape
+    E = torch.empty((k, k), dtype=torch.float32, device=U.device) if E is None else E
+    _check(lib.gsi_build_gram(_ptr(U), d, k, dtype_code(U), _ptr(E), _stream(stream)))
+    return E
+
+
 def quantize_image_fp8(M: torch.Tensor, M8: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,
                        stream=None):
     """E4M3 codes M8[m,k] (uint8) and power-of-two row scales scale[m] (fp32) of a stored image M[m,k]."""
@@ -269,7 +280,7 @@ def dense_linear(W, X, Y=None, ws=None, stream=None):
 class LayerStack:
     """Host descriptor tables for ``gsi_layer_stack`` plus the device buffers they point to.
 
-    ``inputs``: list of dicts {U, X (tensor [B,d]) or src_map}; ``maps``: list of dicts
+    ``inputs``: list of dicts {U, X (tensor [B,d]) or src_map} (+ flags, + gram: the tensor of ``build_gram``); ``maps``: list of dicts
     {W, M, input_id} (+ M_scale when M holds the E4M3 codes of ``quantize_image_fp8``).  Output buffers are allocated here (torch = device memory only) and exposed as
     attributes; ``run()`` is a single call into the library.
     """
@@ -292,7 +303,7 @@ class LayerStack:
             src = int(inp.get("src_map", -1))
             X = self.maps_t[src]["Y"] if src >= 0 else inp["X"]
             self.inputs_t.append({
-                "U": U, "X": X, "src_map": src, "flags": int(inp.get("flags", 0)),
+                "U": U, "X": X, "src_map": src, "flags": int(inp.get("flags", 0)), "gram": inp.get("gram"),
                 "C": torch.zeros((B, k), **f32), "R": torch.zeros((B, d), **f32),
                 "rnorm": torch.zeros((B,), **f32), "xnorm": torch.zeros((B,), **f32),
                 "mask": torch.zeros((B,), dtype=torch.uint8, device=dev),
@@ -323,6 +334,7 @@ class LayerStack:
             e.fired_idx = _ptr(t["fired_idx"])
             e.n_fired = _ptr(t["n_fired"])
             e.src_map, e.flags = t["src_map"], t["flags"]
+            e.gram = _ptr(t["gram"])
         for j, t in enumerate(self.maps_t):
             m = t["W"].shape[0]
             e = self._mp[j]

@@ -73,10 +73,17 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), one, 1 << 20, None) == gsi.GSI_ERR_SHAPE
     assert b"cycle" in lib.gsi_last_error()
     # unknown bits in an input's flags are refused before anything runs
-    inp[0].flags = 6
+    inp[0].flags = 8
     assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_SHAPE
     assert b"flags" in lib.gsi_last_error()
+    # the single-pass gate needs its cached matrix
+    inp[0].flags = gsi.INPUT_GATE_SINGLE_PASS
+    assert lib.gsi_layer_stack(mp, 1, inp, 1, 1, ctypes.c_float(0.05), None, 0, None) == gsi.GSI_ERR_NULL
+    assert b"gram" in lib.gsi_last_error()
     inp[0].flags = 0
+    assert lib.gsi_build_gram(one, 8, 9, gsi.GSI_F32, one, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_build_gram(one, 8, 2, gsi.GSI_F32, None, None) == gsi.GSI_ERR_NULL
+    assert lib.gsi_build_gram(one, 8, 2, 5, one, None) == gsi.GSI_ERR_DTYPE
     # a dense stack of several tokens needs its workspace
     inp[0].src_map = -1
     mp[0].m, inp[0].d, inp[0].k = 64, 64, 32

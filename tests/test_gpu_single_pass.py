@@ -1,0 +1,228 @@
+"""GPU parity of the single-pass gate (GSI_INPUT_GATE_SINGLE_PASS): the residual ratio of Eq. (rho) evaluated as
+|x|^2 - |c|^2 + c^T E c with the cached E = U^T U - I, against the fp64 oracle that forms the residual explicitly."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle.gsi_oracle as O  # noqa: E402
+from paper_2605_03109_amd import workload as wl  # noqa: E402
+
+SENTINEL = 7.25  # R rows the library must not touch keep this value
+
+
+@pytest.fixture(scope="module")
+def gsi():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2605_03109_amd import gsi as g
+
+    return g
+
+
+@pytest.fixture(scope="module")
+def pu(gsi):
+    import parity_util
+
+    return parity_util
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+@pytest.mark.parametrize("d,k,dt", [(33, 7, "bf16"), (768, 64, "f32"), (4096, 256, "bf16"), (16384, 512, "bf16"),
+                                    (1000, 24, "f32")])
+def test_build_gram(gsi, d, k, dt):
+    say(f"case gram d={d} k={k} {dt}")
+    U = wl.store(wl.make_basis64(d, k, seed=900 + d), dt)
+    E = gsi.build_gram(gsi.to_device(U, dt)).cpu().numpy().astype(np.float64)
+    ref = O.gram_defect(O.widen(U, dt))
+    # fp64 accumulation, one rounding to fp32
+    assert np.all(np.abs(E - ref) <= 2.0 ** -24 * np.abs(ref) + 1e-13), np.abs(E - ref).max()
+    if dt == "bf16":  # storage rounding leaves a defect of the size the design notes quote
+        assert 1e-5 < np.abs(ref).max() < 1e-2
+
+
+def _run_tokens(st, T):
+    for t in range(T):
+        st.refresh(token_offset=t, B=1)
+        st.run()
+    torch.cuda.synchronize()
+
+
+def _stack(gsi, pu, w, flags):
+    dgs = [pu.DeviceGroup(w, g) for g in w.groups]
+    inputs, maps, names = [], [], []
+    for gi, dg in enumerate(dgs):
+        inputs.append({"U": dg.U, "X": dg.X, "flags": flags, "gram": gsi.build_gram(dg.U)})
+        for name in dg.W:
+            maps.append({"W": dg.W[name], "M": dg.M[name], "input_id": gi})
+            names.append((gi, name))
+    return dgs, inputs, maps, names
+
+
+def _check_input(gsi, pu, w, g, dg, ti, wx):
+    """Projection outputs of one input over all tokens; returns (oracle group, reference, device mask)."""
+    og = pu.OracleGroup(w, g)
+    ref = og.run()
+    mask_dev = ti["mask"].cpu().numpy()
+    fired = mask_dev.astype(bool)
+    R = ti["R"].cpu().numpy()
+    # r is formed only for tokens whose gate fired, and not at all with the W x form of the slow path
+    untouched = np.ones(len(fired), dtype=bool) if wx else ~fired
+    assert np.all(R[untouched] == SENTINEL), "R of a token that needs no residual was written"
+    Rchk = ti["R"].clone()
+    Rchk[torch.from_numpy(untouched)] = torch.from_numpy(ref["R"][untouched].astype(np.float32)).to(Rchk.device)
+    res = dict(C=ti["C"], R=Rchk, rnorm=ti["rnorm"], xnorm=ti["xnorm"], mask=ti["mask"],
+               n_fired=torch.tensor([int(mask_dev.sum())], dtype=torch.int32),
+               fired_idx=torch.from_numpy(np.nonzero(mask_dev)[0].astype(np.int32)))
+    mask = pu.check_projection(res, ref, w.eps)
+    # the single-pass oracle (same formula in fp64) agrees with the device at least as well
+    E64 = O.gram_defect(og.U)
+    _, rn1, xn1 = O.project_single_pass(og.U, E64, og.X)
+    rho_dev = ti["rnorm"].cpu().numpy().astype(np.float64) / np.maximum(ti["xnorm"].cpu().numpy().astype(np.float64), 1e-300)
+    assert np.abs(rho_dev - rn1 / xn1).max() <= pu.TOL_RHO
+    return og, ref, mask
+
+
+@pytest.mark.parametrize("wx", [False, True])
+@pytest.mark.parametrize("wdtype", ["bf16", "f32"])
+def test_single_pass_block(gsi, pu, wdtype, wx):
+    """One block (four inputs, six maps), one call per token: three launches of the staged kernel + weights."""
+    w = wl.transformer_block("sp", d=512, ffn=2048, k=64, T=12, fire_rate=0.25, p=1.5, seed=4100, wdtype=wdtype)
+    flags = gsi.INPUT_GATE_SINGLE_PASS | (gsi.INPUT_SLOW_PATH_WX if wx else 0)
+    say(f"case single-pass block {wdtype} wx={wx}")
+    dgs, inputs, maps, names = _stack(gsi, pu, w, flags)
+    st = gsi.LayerStack(inputs, maps, w.T, w.eps)
+    for ti in st.inputs_t:
+        ti["R"].fill_(SENTINEL)
+    _run_tokens(st, w.T)
+    for gi, (g, dg) in enumerate(zip(w.groups, dgs)):
+        og, ref, mask = _check_input(gsi, pu, w, g, dg, st.inputs_t[gi], wx)
+        assert np.array_equal(mask.astype(bool), g.fired_design)
+        for j, (g2, name) in enumerate(names):
+            if g2 != gi:
+                continue
+            Y = st.maps_t[j]["Y"]
+            if wx:  # Algorithm 1 as printed: fired rows are W x, the others M c with the stored image
+                Mdev = O.widen(gsi.bits_of(dg.M[name]), w.wdtype)
+                e = pu.rel_l2_rows(Y.cpu().numpy().astype(np.float64), O.gated_linear_alg1(og.W[name], Mdev, ref["C"], og.X, mask))
+                assert e.max() <= pu.TOL_Y_STAGE[w.wdtype], e.max()
+            else:
+                pu.check_outputs(Y, og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
+
+
+def test_single_pass_many_inputs_equal_explicit_path(gsi, pu):
+    """Five blocks in one call per token (two sets of inputs, so the stages of different sets share launches): the
+    coefficients and the un-fired outputs are the explicit path's bit for bit (same partials, same sums, same image
+    rows), the decisions agree, and fired outputs agree to rounding (r is the same arithmetic on the same c)."""
+    L, T = 5, 6
+    blocks = [wl.transformer_block(f"b{l}", d=512, ffn=2048, k=64, T=T, fire_rate=0.34, p=1.5, seed=4200 + l) for l in range(L)]
+    eps = blocks[0].eps
+    inputs, maps = [], []
+    for w in blocks:
+        _, bi, bm, _ = _stack(gsi, pu, w, gsi.INPUT_GATE_SINGLE_PASS)
+        base = len(inputs)
+        inputs += bi
+        maps += [dict(m, input_id=m["input_id"] + base) for m in bm]
+    say(f"case single-pass {len(inputs)} inputs / {len(maps)} maps per call")
+    sp = gsi.LayerStack(inputs, maps, T, eps)
+    sp.refresh(token_offset=0, B=1)
+    sp.ws.fill_(0xFF)
+    for rep in range(2):
+        _run_tokens(sp, T)
+    ex = gsi.LayerStack([dict(i, flags=0) for i in inputs], maps, T, eps)
+    _run_tokens(ex, T)
+    n_fired = 0
+    for a, b in zip(sp.inputs_t, ex.inputs_t):
+        assert torch.equal(a["C"], b["C"]) and torch.equal(a["mask"], b["mask"])
+        assert torch.allclose(a["xnorm"], b["xnorm"], rtol=1e-6, atol=0)
+        assert torch.allclose(a["rnorm"], b["rnorm"], rtol=0, atol=1e-5 * float(b["xnorm"].min()))
+        f = b["mask"].bool()
+        n_fired += int(f.sum())
+        assert torch.equal(a["R"][f], b["R"][f])
+    assert n_fired > 0
+    for a, b in zip(sp.maps_t, ex.maps_t):
+        assert torch.equal(a["Y"], b["Y"])
+    # and the first and last block against the oracle
+    for l in (0, L - 1):
+        w = blocks[l]
+        for gi, g in enumerate(w.groups):
+            ti = dict(sp.inputs_t[4 * l + gi])
+            og = pu.OracleGroup(w, g)
+            ref = og.run()
+            Rchk = ti["R"].clone()
+            un = ~ti["mask"].bool()
+            Rchk[un] = torch.from_numpy(ref["R"].astype(np.float32)).to(Rchk.device)[un]
+            m = ti["mask"].cpu().numpy()
+            res = dict(C=ti["C"], R=Rchk, rnorm=ti["rnorm"], xnorm=ti["xnorm"], mask=ti["mask"],
+                       n_fired=torch.tensor([int(m.sum())], dtype=torch.int32),
+                       fired_idx=torch.from_numpy(np.nonzero(m)[0].astype(np.int32)))
+            pu.check_projection(res, ref, eps)
+
+
+def test_single_pass_next_to_the_threshold(gsi, pu):
+    """Tokens placed at eps + offset through the stack with the single-pass gate: outside the 1e-4 band the decision
+    is the oracle's, inside it either is admissible; reports how the single-pass and the explicit decisions compare,
+    and what dropping the E term (assuming U^T U = I) would have decided."""
+    from test_gpu_parity import _tokens_at_ratio
+
+    d, k, m = 2048, 128, 520
+    offsets = np.array([1e-6, -1e-6, 2e-6, -2e-6, 5e-6, -5e-6, 2e-5, -2e-5, 5e-5, -5e-5, 1.2e-4, -1.2e-4, 3e-4, -3e-4, 2e-3, -2e-3])
+    w = wl.tiny(d, k, m, len(offsets), 0, seed=7300, wdtype="bf16")
+    g = w.groups[0]
+    eps32 = float(np.float32(w.eps))
+    U64 = O.widen(g.U, w.wdtype)
+    X, got = _tokens_at_ratio(U64, eps32 + offsets, eps32, seed=7301)
+    g.X = X
+    T = len(offsets)
+    dg, og = pu.DeviceGroup(w, g), pu.OracleGroup(w, g)
+    maps = [{"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}]
+    E = gsi.build_gram(dg.U)
+    sp = gsi.LayerStack([{"U": dg.U, "X": dg.X, "flags": gsi.INPUT_GATE_SINGLE_PASS, "gram": E}], maps, T, w.eps)
+    ex = gsi.LayerStack([{"U": dg.U, "X": dg.X}], maps, T, w.eps)
+    _run_tokens(sp, T)
+    _run_tokens(ex, T)
+    ref = og.run()
+    ti = sp.inputs_t[0]
+    m_sp, m_ex = ti["mask"].cpu().numpy(), ex.inputs_t[0]["mask"].cpu().numpy()
+    outside = np.abs(ref["rho"] - eps32) >= pu.BAND
+    assert np.array_equal(m_sp[outside], ref["mask"][outside])
+    rho_sp = (ti["rnorm"] / ti["xnorm"]).cpu().numpy().astype(np.float64)
+    rho_ex = (ex.inputs_t[0]["rnorm"] / ex.inputs_t[0]["xnorm"]).cpu().numpy().astype(np.float64)
+    assert np.abs(rho_sp - ref["rho"]).max() <= pu.TOL_RHO
+    # outputs on the device's own decision
+    Mdev = O.widen(gsi.bits_of(dg.M["w"]), w.wdtype)
+    Y = sp.maps_t[0]["Y"].cpu().numpy().astype(np.float64)
+    e = pu.rel_l2_rows(Y, O.gated_linear(og.W["w"], Mdev, ref["C"], ref["R"], m_sp))
+    assert e.max() <= pu.TOL_Y_STAGE[w.wdtype], e.max()
+    # what |x|^2 - |c|^2 alone would give (fp64): the stored bf16 basis is not orthonormal enough for it
+    naive = np.sqrt(np.maximum(np.sum(og.X ** 2, axis=1) - np.sum(ref["C"] ** 2, axis=1), 0.0)) / ref["xnorm"]
+    say(f"  |rho_single_pass - rho_oracle| max {np.abs(rho_sp - ref['rho']).max():.2e}; explicit kernel {np.abs(rho_ex - ref['rho']).max():.2e}")
+    say(f"  decisions differing from the oracle: single pass {int((m_sp != ref['mask']).sum())}, explicit {int((m_ex != ref['mask']).sum())} "
+        f"(all inside the band: {bool(np.all(~outside[(m_sp != ref['mask']) | (m_ex != ref['mask'])]))})")
+    say(f"  without the E term: |rho - rho_oracle| max {np.abs(naive - ref['rho']).max():.2e}, "
+        f"{int(((naive >= eps32) != ref['mask'].astype(bool)).sum())} of {T} decisions flip")
+
+
+@pytest.mark.parametrize("k", [64, 256, 512])
+def test_single_pass_gptj_block_full_size(gsi, pu, k):
+    T = 3
+    w = wl.gptj_block(T=T, k=k, fire_rate=0.34)
+    say(f"case single-pass {w.name}: k={k}, full shapes")
+    dgs, inputs, maps, names = _stack(gsi, pu, w, gsi.INPUT_GATE_SINGLE_PASS)
+    st = gsi.LayerStack(inputs, maps, T, w.eps)
+    for ti in st.inputs_t:
+        ti["R"].fill_(SENTINEL)
+    _run_tokens(st, T)
+    for gi, (g, dg) in enumerate(zip(w.groups, dgs)):
+        say(f"  input {g.name}: d={g.d}")
+        og, ref, mask = _check_input(gsi, pu, w, g, dg, st.inputs_t[gi], False)
+        assert np.array_equal(mask.astype(bool), g.fired_design)
+        for j, (g2, name) in enumerate(names):
+            if g2 == gi:
+                e, es = pu.check_outputs(st.maps_t[j]["Y"], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
+                say(f"    map {name}: rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
+        del og
