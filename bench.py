@@ -45,6 +45,8 @@ KERNELS = {
     1: "gsi::stream_fired<BF16> (one launch: W r of every fired map of the call)",
 }
 PROFILE_KEY = {0: "proj_stage", 1: "stream_fired"}
+TABLE_KERNELS = "gsi::table_partial<BF16> (partial c = U^T x and shares of |x|^2 of all inputs), gsi::table_gram (sums of " \
+                "the partials, shares of c^T E c), gsi::table_rows<BF16> (image rows y = M c of all maps; gates; r of fired inputs)"
 
 
 def log(msg: str) -> None:
@@ -330,7 +332,8 @@ def main() -> int:
     if not args.no_roofline and not args.fused:
         SET = 16                                  # inputs per launch of the staged kernel
         nsets = (S.n_in + SET - 1) // SET
-        n_launch = {0: nsets + (2 if single_pass else 3), 1: 1}  # launches per step: staged kernel, weight streaming
+        table_mode = single_pass and nsets > 1    # every stage once for all inputs: three launches
+        n_launch = {0: 3 if table_mode else nsets + (2 if single_pass else 3), 1: 1}  # staged kernel(s), weights
         K = min(T, 24)
         evs = HipEvents(2)
         s0 = torch.cuda.current_stream().cuda_stream
@@ -338,6 +341,8 @@ def main() -> int:
         k = args.k
 
         def set_inputs(g):
+            if table_mode:
+                return range(S.n_in) if g == 0 else range(0)
             return range(g * SET, min(S.n_in, (g + 1) * SET)) if 0 <= g < nsets else range(0)
 
         def stage_bytes(idx, t):  # launch idx: partial projections of set idx, residuals + image rows of set idx - 2
@@ -390,11 +395,11 @@ def main() -> int:
             else:
                 entry = {"launches": int(d_all.size), "launches_per_step": n_launch[0],
                          "first_launch_us": round(float(dur[0][0].mean() * 1e6), 2),
-                         "full_launch_us": round(float(dur[0][2:nsets].mean() * 1e6), 2) if nsets > 2 else None,
-                         "last_launch_us": round(float(dur[0][-1].mean() * 1e6), 2)}
+                         "per_launch_us": [round(float(v.mean() * 1e6), 2) for v in dur[0]],
+                         "per_launch_algorithmic_MB": [round(float(v.mean() / 1e6), 2) for v in nbytes[0]]}
                 d_use, b_use = d_all, b_all
             ach = float(b_use.sum() / d_use.sum() / 1e9) if d_use.size else 0.0
-            entry.update({"kernel": KERNELS[which], "avg_launch_us": round(float(d_use.mean() * 1e6), 2),
+            entry.update({"kernel": TABLE_KERNELS if which == 0 and table_mode else KERNELS[which], "avg_launch_us": round(float(d_use.mean() * 1e6), 2),
                           "avg_algorithmic_bytes": round(float(b_use.mean())), "achieved_GBs": round(ach, 1),
                           "frac_of_hbm_peak": round(ach / HBM_PEAK_GBS, 4),
                           "us_per_step_total": round(float(d_all.sum() / K * 1e6), 1)})

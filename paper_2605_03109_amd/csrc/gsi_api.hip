@@ -540,8 +540,11 @@ static size_t fp8_expand_bytes(const gsi_map_desc& mp, const gsi_input_desc& in,
 }
 
 // single token: the descriptor table of the weight-streaming launch sits at the start of the workspace
+// (and behind it the table of the staged launches of a call with many inputs and the single-pass gate)
 static size_t stack_table_bytes(int32_t n_maps, int32_t n_inputs, int64_t B) {
-  return B == 1 && n_maps > 0 && n_inputs > 0 ? gsi::fired_table_bytes(n_inputs, n_maps) : 0;
+  return B == 1 && n_maps > 0 && n_inputs > 0
+             ? gsi::fired_table_bytes(n_inputs, n_maps) + gsi::stage_table_bytes(n_inputs, n_maps)
+             : 0;
 }
 
 size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
@@ -977,6 +980,48 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       };
       auto member = [&](int g, int q) { return list[(size_t)g * gsi::kMaxTasks + q]; };
       const int sum_stage = (sp || nsets > 1) ? 1 : 0;
+      if (sum_stage)  // the partials are added once per input: finer slabs
+        for (int i : list) gsi::stage_geom(inputs[i].d, inputs[i].k, dt, ptask[i].s_rows, ptask[i].s_slabs, true);
+      if (sp && nsets > 1 && (int)list.size() <= gsi::kMaxTabIn && n_maps > 0 && n_maps <= gsi::kMaxTabMaps) {
+        // many inputs: every stage once, over a descriptor table in the workspace (three launches)
+        std::vector<gsi::TabIn> tin(list.size());
+        std::vector<gsi::TabMap> tmp;
+        for (size_t q = 0; q < list.size(); ++q) {
+          const int i = list[q];
+          const gsi_input_desc& in = inputs[i];
+          const gsi::ProjTask& pt = ptask[i];
+          gsi::TabIn& t = tin[q];
+          std::memset(&t, 0, sizeof(t));
+          t.U = in.U; t.X = in.X; t.C = in.C; t.R = in.R; t.E = in.gram; t.rnorm = in.rnorm; t.xnorm = in.xnorm;
+          t.mask = in.mask; t.fired_idx = in.fired_idx; t.n_fired = in.n_fired; t.part_c = pt.part_c;
+          t.d = pt.d;
+          t.k_rows = pt.k | (pt.s_rows << 16);
+          // residual slabs of at least 256 rows: nearly all of their workgroups only evaluate the gate and leave
+          const int rps = 256 / (pt.k / (dt == GSI_BF16 ? 8 : 4));
+          int r_rows = pt.b_rows;
+          if (r_rows < 256) r_rows = (int)(gsi::ceil_div(256, rps) * rps);
+          const int r_slabs = (int)gsi::ceil_div(pt.d, r_rows);
+          t.slabs = pt.s_slabs | (r_slabs << 16);
+          t.r_rows_x = r_rows | (in.xdtype << 16) | ((in.flags & GSI_INPUT_SLOW_PATH_WX) ? 1 << 20 : 0);
+          t.gw_off = (int)(reinterpret_cast<char*>(pt.part_n) - reinterpret_cast<char*>(pt.part_c));
+          for (int j = 0; j < n_maps; ++j) {
+            if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
+            tmp.push_back(gsi::TabMap{maps[j].M, maps[j].Y,
+                                      (maps[j].flags & GSI_MAP_IMAGE_FP8) ? maps[j].M_scale : nullptr, (int)maps[j].m,
+                                      (int)q});
+            img_done[j] = 1;
+          }
+        }
+        const int wt = (which == 0 && launch_index >= n_stage_launches && launch_index < n_stage_launches + 3)
+                           ? launch_index - n_stage_launches : -1;
+        n_stage_launches += 3;
+        void* table = reinterpret_cast<char*>(ws) + gsi::fired_table_bytes(n_inputs, n_maps);
+        if (hipError_t e = gsi::stage_table_run(table, tin.data(), (int)tin.size(), tmp.data(), (int)tmp.size(), dt, eps,
+                                                s, wt, ev_begin, ev_end);
+            e != hipSuccess)
+          return hip_fail(e, fn);
+        continue;
+      }
       for (int g = 0; g < nsets + 2 + sum_stage - (sp ? 1 : 0); ++g) {
         gsi::StageArgs a;
         gsi::stage_clear(a, eps);

@@ -153,7 +153,8 @@ struct StageCRed {        // c = sum of the partials in fixed slab order, one wo
 };
 constexpr int kGramBlocks = 16;
 // doubles of the single-pass gate per input: slab shares of |x|^2, block shares of c^T E c, |c|^2
-constexpr int kGateDoubles = kPartSlabs + kGramBlocks + 1;
+constexpr int kStageSlabs = 128;  // row slabs per input of the staged kernel when a sum stage adds the partials
+constexpr int kGateDoubles = kStageSlabs + kGramBlocks + 1;
 
 struct StageRes {         // r = x - U c, and the slab shares of |r|^2, |x|^2, of one input over row slabs
   const void* U;
@@ -205,8 +206,10 @@ struct StageArgs {
 };
 static_assert(sizeof(StageArgs) <= 4096, "kernel arguments are limited to 4 KB");
 
-// rows per slab and slabs of the single-token partial projection
-void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs);
+// rows per slab and slabs of the single-token partial projection.  fine: slabs of at most 64 KB (up to kStageSlabs
+// of them) for calls whose partials are added by a sum stage; else kPartSlabs slabs at most, because every
+// residual and image workgroup then adds the partials itself
+void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs, bool fine = false);
 void stage_clear(StageArgs& a, float eps);
 // E (single-pass gate): the input's cached U^T U - I, else null
 void stage_add_part(StageArgs& a, const ProjTask& t, const float* E = nullptr);
@@ -217,6 +220,43 @@ void stage_add_img(StageArgs& a, int res, const void* M, float* Y, const float* 
 void stage_add_gate(StageArgs& a, const ProjTask& t);
 // e0 / e1 (optional): events that take the start / stop timestamps of the dispatch
 hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+
+// ---- single token, many inputs, single-pass gate: the stages as three launches over a table in device memory ----
+// A call with more inputs than one launch's arguments describe runs each stage ONCE for all its inputs: partial
+// projections; coefficient sums with the shares of c^T E c; image rows and (behind the gate) residuals.  Launches
+// that each move hundreds of megabytes amortise their fixed cost and their ramp and tail, which a pipeline of
+// 16-input launches pays a dozen times.  The descriptors are uploaded like those of the weight-streaming launch.
+struct TabIn {
+  const void* U;
+  const void* X;
+  float* C;
+  float* R;
+  const float* E;
+  float* rnorm;
+  float* xnorm;
+  uint8_t* mask;
+  int32_t* fired_idx;
+  int32_t* n_fired;
+  float* part_c;         // [s_slabs][k], followed at gw_off bytes by the doubles of the single-pass gate
+  int d;
+  int k_rows;            // k | rows per slab of the partial projection << 16
+  int slabs;             // slabs of the partial projection | residual slabs << 16
+  int r_rows_x;          // rows per residual slab | xdtype << 16 | W x form of the slow path << 20
+  int gw_off;
+  int pad;
+};
+struct TabMap {
+  const void* M;
+  float* Y;
+  const float* scale;    // E4M3 image: row scales; else null
+  int m, in;             // rows; index of the input
+};
+constexpr int kMaxTabIn = 1024, kMaxTabMaps = 2048;  // (the first-workgroup tables are searched in LDS)
+size_t stage_table_bytes(int n_in, int n_maps);
+// ins / maps: host arrays; table: device memory of stage_table_bytes(n_in, n_maps).  which_timed: 0, 1, 2 = the
+// launch whose dispatch the events time, else -1
+hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, float eps,
+                           hipStream_t s, int which_timed = -1, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 
 // ---- single token, many inputs: weight streaming over a table in device memory (gsi_stream.hip) -----------
 // One launch streams the rows of W of every fired input of a call, however many inputs and maps the call has.

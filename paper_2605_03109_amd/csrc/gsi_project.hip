@@ -404,7 +404,7 @@ ProjGeom proj_geom(int64_t d, int64_t k, int udtype) {
 size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype) {
   const ProjGeom g = proj_geom(d, k, udtype);
   int s_rows = 0, s_slabs = 0;
-  if (B == 1) stage_geom(d, k, udtype, s_rows, s_slabs);
+  if (B == 1) stage_geom(d, k, udtype, s_rows, s_slabs, true);  // the finer of the two geometries
   const size_t part_slabs = (size_t)std::max(g.a_slabs, s_slabs);
   // (a single token's slab shares of the norms, or the kGateDoubles doubles of the single-pass gate)
   size_t need = align_up(part_slabs * B * k * 4, 256) +
@@ -426,8 +426,12 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
   t.a_rows = g.a_rows; t.a_slabs = g.a_slabs; t.a_cblocks = g.a_cblocks;
   t.b_rows = g.b_rows; t.b_slabs = g.b_slabs;
   t.s_rows = t.s_slabs = 0;
-  if (B == 1) stage_geom(d, k, t.udtype, t.s_rows, t.s_slabs);
-  const size_t part_slabs = (size_t)std::max(g.a_slabs, t.s_slabs);
+  int f_rows = 0, f_slabs = 0;
+  if (B == 1) {
+    stage_geom(d, k, t.udtype, t.s_rows, t.s_slabs);
+    stage_geom(d, k, t.udtype, f_rows, f_slabs, true);
+  }
+  const size_t part_slabs = (size_t)std::max(g.a_slabs, std::max(t.s_slabs, f_slabs));
   t.part_c = reinterpret_cast<float*>(ws);
   t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up(part_slabs * B * k * 4, 256));
 }

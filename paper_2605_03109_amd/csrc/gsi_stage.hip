@@ -28,6 +28,7 @@
 #include <hip/hip_ext.h>
 
 #include <cstring>
+#include <vector>
 
 #include "gsi_decode.h"
 #include "gsi_device.h"
@@ -56,17 +57,18 @@ __device__ __forceinline__ double wave_sum_f64(double v) {
 }
 
 // Eq. (gate) from the single-pass shares of one input: gw = [slabs shares of |x|^2][kGramBlocks shares of
-// c^T E c][|c|^2], at most one per lane.  Called by whole waves: every lane loads one value (one memory latency in
-// all), the sums run over the wave in a fixed butterfly order, so every wave of every workgroup reaches the
-// same verdict.
+// c^T E c][|c|^2].  Called by whole waves: the lanes load the shares side by side (a few memory latencies in all,
+// not one per share), the sums run in a fixed order (lane-strided, then a butterfly over the wave), so every wave
+// of every workgroup reaches the same verdict.
 __device__ __forceinline__ bool single_pass_gate(const double* __restrict__ gw, int slabs, float eps, float& rn,
                                                  float& xn) {
-  static_assert(kGateDoubles <= kWave, "one share per lane");
   const int lane = threadIdx.x % kWave;
-  const double v = lane < slabs + kGramBlocks + 1 ? gw[lane] : 0.0;
-  const double x2 = wave_sum_f64(lane < slabs ? v : 0.0);
-  const double q = wave_sum_f64(lane >= slabs && lane < slabs + kGramBlocks ? v : 0.0);
-  const double c2 = __shfl(v, slabs + kGramBlocks, kWave);
+  double a = 0.0;
+  for (int s = lane; s < slabs; s += kWave) a += gw[s];
+  const double v = lane <= kGramBlocks ? gw[slabs + lane] : 0.0;
+  const double x2 = wave_sum_f64(a);
+  const double q = wave_sum_f64(lane < kGramBlocks ? v : 0.0);
+  const double c2 = __shfl(v, kGramBlocks, kWave);
   const double r2 = x2 - c2 + q;
   rn = (float)sqrt(r2 > 0.0 ? r2 : 0.0);
   xn = (float)sqrt(x2);
@@ -100,12 +102,17 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
 #pragma unroll
   for (int e = 0; e < V; ++e) acc[e] = 0.f;
   int i = ro;
-  // the first batch of U goes in flight, then the slab's activations are staged in LDS (one coalesced load)
-  uint4 raw[8];
-  const bool first = i + 7 * rps < rows;
+  // the first two batches of U go in flight (64 KB per workgroup, a whole slab of the fine geometry), then the
+  // slab's activations are staged in LDS (one coalesced load)
+  uint4 raw[8], raw2[8];
+  const bool first = i + 7 * rps < rows, second = i + 15 * rps < rows;
   if (first) {
 #pragma unroll
     for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+  }
+  if (second) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) raw2[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + (8 + q) * rps) * k);
   }
   double x2 = 0.0;  // this thread's share of the slab's |x|^2 (single-pass gate)
   for (int r = threadIdx.x; r < rows; r += kBlock) {
@@ -119,6 +126,17 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
     for (int q = 0; q < 8; ++q) {
       float u[V];
       T::widen(raw[q], u);
+      const float xv = xs[i + q * rps];
+#pragma unroll
+      for (int e = 0; e < V; ++e) acc[e] = fmaf(u[e], xv, acc[e]);
+    }
+    i += 8 * rps;
+  }
+  if (second) {
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      float u[V];
+      T::widen(raw2[q], u);
       const float xv = xs[i + q * rps];
 #pragma unroll
       for (int e = 0; e < V; ++e) acc[e] = fmaf(u[e], xv, acc[e]);
@@ -349,6 +367,8 @@ __global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
   __shared__ float nr[kWaves], nx[kWaves];
   __shared__ double dsh[2 * kWaves];
   int b = blockIdx.x;
+  // single-pass gate: the residual workgroups (nearly all of which only evaluate the gate and leave) go last
+  if (a.gram) b = b + a.b_total < (int)gridDim.x ? b + a.b_total : b + a.b_total - (int)gridDim.x;
   if (b < a.b_total) {
     const int ti = find_task(a.b_begin, a.nb, b);
     residual_block<T>(a.b[ti], a.g, a.eps, b - a.b_begin[ti], lds, xs, nr, nx);
@@ -391,16 +411,108 @@ __global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
   gate_block(a.g[b - a.ncr], a.eps);
 }
 
+// ---- the same stages over a table in device memory (many inputs, single-pass gate) ------------------------------
+// first-workgroup table of n tasks staged in LDS, then a binary search: the task that holds workgroup b
+__device__ __forceinline__ int find_in_table(const int* __restrict__ begin, int n, int b, int* __restrict__ sh) {
+  for (int i = threadIdx.x; i < n; i += kBlock) sh[i] = begin[i];
+  __syncthreads();
+  int lo = 0, hi = n - 1;  // begin[0] = 0 <= b
+  while (lo < hi) {
+    const int mid = (lo + hi + 1) >> 1;
+    if (sh[mid] <= b) lo = mid;
+    else hi = mid - 1;
+  }
+  return __builtin_amdgcn_readfirstlane(lo);
+}
+
+template <class T>
+__global__ __launch_bounds__(kBlock) void table_partial(const TabIn* __restrict__ ins, const int* __restrict__ pbegin,
+                                                        int n_in) {
+  __shared__ __align__(16) float lds[kBlock * 8];
+  __shared__ float xs[kStageMaxRows];
+  __shared__ double dsh[2 * kWaves];
+  __shared__ int tab[kMaxTabIn];
+  const int b = blockIdx.x;
+  const int i = find_in_table(pbegin, n_in, b, tab);
+  const TabIn& in = ins[i];
+  StagePart p;
+  p.U = in.U; p.X = in.X; p.part_c = in.part_c; p.d = in.d; p.k_rows = in.k_rows;
+  p.slabs_x = (in.slabs & 0xffff) | (((in.r_rows_x >> 16) & 0xf) << 16);
+  p.x2_off = in.gw_off;
+  partial_block<T>(p, b - tab[i], lds, xs, dsh);
+}
+
+__global__ __launch_bounds__(kBlock) void table_gram(const TabIn* __restrict__ ins) {
+  __shared__ __align__(16) float lds[kMaxK];
+  __shared__ double dsh[2 * kWaves];
+  const TabIn& in = ins[blockIdx.x / kGramBlocks];
+  StageCRed p;
+  p.part_c = in.part_c; p.C = in.C; p.E = in.E;
+  p.k_slabs = (in.k_rows & 0xffff) | ((in.slabs & 0xffff) << 16);
+  p.gw_off = in.gw_off;
+  gram_block(p, blockIdx.x % kGramBlocks, lds, dsh);
+}
+
+// image rows of every map first, then the residual workgroups (which evaluate the gate, publish it, and form r only
+// for an input that fired)
+template <class T>
+__global__ __launch_bounds__(kBlock) void table_rows(const TabIn* __restrict__ ins, const TabMap* __restrict__ maps,
+                                                     const int* __restrict__ ibegin, const int* __restrict__ rbegin,
+                                                     int n_in, int n_maps, int i_total, float eps) {
+  __shared__ __align__(16) float lds[kBlock * 8];
+  __shared__ float xs[kStageMaxRows];
+  __shared__ float nr[kWaves], nx[kWaves];
+  __shared__ int tab[kMaxTabMaps];
+  int b = blockIdx.x;
+  if (b < i_total) {
+    const int j = find_in_table(ibegin, n_maps, b, tab);
+    const TabMap& mp = maps[j];
+    const TabIn& in = ins[mp.in];
+    const int slabs = in.slabs & 0xffff;
+    if ((in.r_rows_x >> 20) & 1) {  // W x form of the slow path: a fired input's rows are left to the weight kernel
+      float rn, xn;
+      if (single_pass_gate(reinterpret_cast<const double*>(reinterpret_cast<const char*>(in.part_c) + in.gw_off), slabs,
+                           eps, rn, xn))
+        return;
+    }
+    ImgTask t;
+    t.M = mp.M; t.Y = mp.Y; t.part_c = nullptr; t.C = in.C; t.scale = mp.scale;
+    t.m = mp.m; t.k = in.k_rows & 0xffff; t.a_slabs = 0; t.blk_begin = tab[j];
+    image_block<T>(t, b - t.blk_begin, lds);
+    return;
+  }
+  b -= i_total;
+  const int i = find_in_table(rbegin, n_in, b, tab);
+  const TabIn& in = ins[i];
+  StageGate g;
+  g.part_n = reinterpret_cast<const float*>(reinterpret_cast<const char*>(in.part_c) + in.gw_off);
+  g.rnorm = in.rnorm; g.xnorm = in.xnorm; g.mask = in.mask; g.fired_idx = in.fired_idx; g.n_fired = in.n_fired;
+  g.b_slabs = in.slabs & 0xffff;
+  g.skip_fired_image = (in.r_rows_x >> 20) & 1;
+  StageRes p;
+  p.U = in.U; p.X = in.X; p.part_c = nullptr; p.C = in.C; p.R = in.R; p.part_n = nullptr;
+  p.d = in.d; p.k_rows = (in.k_rows & 0xffff) | ((in.r_rows_x & 0xffff) << 16);
+  p.slabs_x = (in.slabs >> 16) | ((in.slabs & 0xff) << 16) | (((in.r_rows_x >> 16) & 0xf) << 24);
+  p.gate = 1;
+  residual_block<T>(p, &g, eps, b - tab[i], lds, xs, nr, nx);
+}
+
 }  // namespace
 
 // ------------------------------------------------------------------------------------------------
 // host side
 // ------------------------------------------------------------------------------------------------
-void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs) {
+void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs, bool fine) {
   const int V = udtype == GSI_BF16 ? 8 : 4;
   const int rps = kBlock / (int)(k / V);
-  // at least eight row steps per workgroup, kPartSlabs slabs at most
+  // at least eight row steps per workgroup, kPartSlabs slabs at most ...
   int64_t r = ceil_div(d, kPartSlabs);
+  if (fine) {  // ... or, at most 64 KB of U per workgroup (a workgroup keeps 32 KB in flight, so a larger slab is a
+               // long pole of the launch), as long as that needs no more than kStageSlabs slabs
+    const int64_t cap = 65536 / (k * (int64_t)elem_size(udtype));
+    if (r > cap) r = cap;
+    if (r < ceil_div(d, kStageSlabs)) r = ceil_div(d, kStageSlabs);
+  }
   if (r < 8 * rps) r = 8 * rps;
   rows = (int)(ceil_div(r, rps) * rps);
   slabs = (int)ceil_div(d, rows);
@@ -477,6 +589,72 @@ hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0, h
   } else {
     if (e0 && e1) hipExtLaunchKernelGGL((proj_stage<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, a);
     else proj_stage<F32><<<grid, kBlock, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
+size_t stage_table_bytes(int n_in, int n_maps) {
+  return align_up((size_t)n_in * sizeof(TabIn), 256) + align_up((size_t)n_maps * sizeof(TabMap), 256) +
+         2 * align_up((size_t)(n_in + 1) * sizeof(int), 256) + align_up((size_t)(n_maps + 1) * sizeof(int), 256);
+}
+
+hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, float eps,
+                           hipStream_t s, int which_timed, hipEvent_t e0, hipEvent_t e1) {
+  if (n_in <= 0) return hipSuccess;
+  if (n_in > kMaxTabIn || n_maps > kMaxTabMaps) return hipErrorInvalidValue;
+  const size_t off_maps = align_up((size_t)n_in * sizeof(TabIn), 256);
+  const size_t off_p = off_maps + align_up((size_t)n_maps * sizeof(TabMap), 256);
+  const size_t off_r = off_p + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  const size_t off_i = off_r + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  const size_t bytes = stage_table_bytes(n_in, n_maps);
+  std::vector<char> host(bytes, 0);
+  std::memcpy(host.data(), ins, (size_t)n_in * sizeof(TabIn));
+  if (n_maps) std::memcpy(host.data() + off_maps, maps, (size_t)n_maps * sizeof(TabMap));
+  int* pb = reinterpret_cast<int*>(host.data() + off_p);
+  int* rb = reinterpret_cast<int*>(host.data() + off_r);
+  int* ib = reinterpret_cast<int*>(host.data() + off_i);
+  int64_t tp = 0, tr = 0, ti = 0;
+  for (int i = 0; i < n_in; ++i) {
+    pb[i] = (int)tp;
+    rb[i] = (int)tr;
+    tp += ins[i].slabs & 0xffff;
+    tr += ins[i].slabs >> 16;
+  }
+  for (int j = 0; j < n_maps; ++j) {
+    ib[j] = (int)ti;
+    ti += image_blocks(maps[j].m, ins[maps[j].in].k_rows & 0xffff, dtype, maps[j].scale != nullptr);
+  }
+  pb[n_in] = (int)tp; rb[n_in] = (int)tr; ib[n_maps] = (int)ti;
+  if (tp >= (1 << 30) || tr + ti >= (1 << 30)) return hipErrorInvalidValue;
+  if (hipError_t e = upload_launch(host.data(), bytes, table, s); e != hipSuccess) return e;
+  const char* base = static_cast<const char*>(table);
+  const TabIn* d_ins = reinterpret_cast<const TabIn*>(base);
+  const TabMap* d_maps = reinterpret_cast<const TabMap*>(base + off_maps);
+  const int* d_pb = reinterpret_cast<const int*>(base + off_p);
+  const int* d_rb = reinterpret_cast<const int*>(base + off_r);
+  const int* d_ib = reinterpret_cast<const int*>(base + off_i);
+  auto ev = [&](int w, hipEvent_t e) { return which_timed == w ? e : nullptr; };
+  // 1. partial projections
+  if (dtype == GSI_BF16) {
+    if (ev(0, e0)) hipExtLaunchKernelGGL((table_partial<BF16>), dim3((unsigned)tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
+    else table_partial<BF16><<<(unsigned)tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+  } else {
+    if (ev(0, e0)) hipExtLaunchKernelGGL((table_partial<F32>), dim3((unsigned)tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
+    else table_partial<F32><<<(unsigned)tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+  }
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  // 2. coefficient sums and the shares of c^T E c
+  if (ev(1, e0)) hipExtLaunchKernelGGL(table_gram, dim3((unsigned)n_in * kGramBlocks), dim3(kBlock), 0, s, e0, e1, 0, d_ins);
+  else table_gram<<<(unsigned)n_in * kGramBlocks, kBlock, 0, s>>>(d_ins);
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  // 3. image rows, gates, residuals of fired inputs
+  const unsigned grid = (unsigned)(ti + tr);
+  if (dtype == GSI_BF16) {
+    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
+    else table_rows<BF16><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
+  } else {
+    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
+    else table_rows<F32><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
   }
   return hipGetLastError();
 }
