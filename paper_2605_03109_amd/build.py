@@ -41,7 +41,7 @@ def hipcc() -> str:
 
 # Kernels that must not use scratch memory (register spills): a dispatch that needs scratch costs tens of
 # microseconds here, more than the whole single-token step.
-NO_SCRATCH = {"gsi_fused.hip": ("fused_token",), "gsi_stage.hip": ("proj_stage", "table_partial", "table_gram", "table_rows")}
+NO_SCRATCH = {"gsi_fused.hip": ("fused_token",), "gsi_stage.hip": ("proj_stage", "table_partial", "table_cred", "table_gram", "table_rows")}
 
 
 def _compile(src: str) -> str:

@@ -1006,9 +1006,14 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           t.gw_off = (int)(reinterpret_cast<char*>(pt.part_n) - reinterpret_cast<char*>(pt.part_c));
           for (int j = 0; j < n_maps; ++j) {
             if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
-            tmp.push_back(gsi::TabMap{maps[j].M, maps[j].Y,
-                                      (maps[j].flags & GSI_MAP_IMAGE_FP8) ? maps[j].M_scale : nullptr, (int)maps[j].m,
-                                      (int)q});
+            gsi::TabMap tm;
+            std::memset(&tm, 0, sizeof(tm));
+            tm.M = maps[j].M; tm.Y = maps[j].Y;
+            tm.scale = (maps[j].flags & GSI_MAP_IMAGE_FP8) ? maps[j].M_scale : nullptr;
+            tm.C = in.C;
+            tm.gw = (in.flags & GSI_INPUT_SLOW_PATH_WX) ? reinterpret_cast<const double*>(pt.part_n) : nullptr;
+            tm.m = (int)maps[j].m; tm.k = pt.k; tm.slabs = pt.s_slabs; tm.in = (int)q;
+            tmp.push_back(tm);
             img_done[j] = 1;
           }
         }

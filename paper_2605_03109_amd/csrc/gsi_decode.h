@@ -152,9 +152,13 @@ struct StageCRed {        // c = sum of the partials in fixed slab order, one wo
   int gw_off;             // byte offset from part_c of the doubles gw
 };
 constexpr int kGramBlocks = 16;
-// doubles of the single-pass gate per input: slab shares of |x|^2, block shares of c^T E c, |c|^2
+// doubles of the single-pass gate per input: slab shares of |x|^2, block shares of c^T E c, shares of |c|^2.
+// With this gate the partial projections are kept to double precision (a second array of low parts behind the
+// first, [slabs][k] each): |x|^2 - |c|^2 cancels to 1/400 of either term at the threshold 0.05, and an error of c
+// enters it in first order (the explicit residual feels it only in second order).
 constexpr int kStageSlabs = 128;  // row slabs per input of the staged kernel when a sum stage adds the partials
-constexpr int kGateDoubles = kStageSlabs + kGramBlocks + 1;
+constexpr int kC2Shares = 8;       // shares of |c|^2 (one per 64 columns)
+constexpr int kGateDoubles = kStageSlabs + kGramBlocks + kC2Shares;
 
 struct StageRes {         // r = x - U c, and the slab shares of |r|^2, |x|^2, of one input over row slabs
   const void* U;
@@ -245,12 +249,17 @@ struct TabIn {
   int gw_off;
   int pad;
 };
-struct TabMap {
+struct TabMap {          // everything an image workgroup needs, so that its loads of M wait for one table entry only
   const void* M;
   float* Y;
   const float* scale;    // E4M3 image: row scales; else null
-  int m, in;             // rows; index of the input
+  const float* C;        // the input's coefficients
+  const double* gw;      // W x form of the slow path: the input's gate doubles (a fired input's rows are skipped); else null
+  int m, k;              // rows, rank
+  int slabs;             // slabs of the input's partial projection (layout of gw)
+  int in;                // index of the input
 };
+constexpr int kTabImgItems = 8;   // items per image workgroup of the table launch (64 KB of M)
 constexpr int kMaxTabIn = 1024, kMaxTabMaps = 2048;  // (the first-workgroup tables are searched in LDS)
 size_t stage_table_bytes(int n_in, int n_maps);
 // ins / maps: host arrays; table: device memory of stage_table_bytes(n_in, n_maps).  which_timed: 0, 1, 2 = the

@@ -38,8 +38,9 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ pc, int6
   return s;
 }
 
-template <class T>
+template <class T, int ITEMS = kImgItemsPerBlock>
 __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block, float* __restrict__ cs) {
+  constexpr int kPerWave = ITEMS / 4;
   constexpr int V = T::kVec;
   using S = typename T::storage;
   const int lane = threadIdx.x % kWave;
@@ -52,10 +53,10 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
   const bool live = l * V < k;
   const int col = live ? l * V : k - V;
   const S* M = reinterpret_cast<const S*>(t.M) + col;
-  const int item0 = local_block * kImgItemsPerBlock + wave * kImgPerWave;
-  uint4 raw[kImgPerWave][kImgLoads];
+  const int item0 = local_block * ITEMS + wave * kPerWave;
+  uint4 raw[kPerWave][kImgLoads];
 #pragma unroll
-  for (int it = 0; it < kImgPerWave; ++it)
+  for (int it = 0; it < kPerWave; ++it)
 #pragma unroll
     for (int u = 0; u < kImgLoads; ++u) {
       const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
@@ -70,7 +71,7 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
     cvv[4 * q + 0] = x.x; cvv[4 * q + 1] = x.y; cvv[4 * q + 2] = x.z; cvv[4 * q + 3] = x.w;
   }
 #pragma unroll
-  for (int it = 0; it < kImgPerWave; ++it)
+  for (int it = 0; it < kPerWave; ++it)
 #pragma unroll
     for (int u = 0; u < kImgLoads; ++u) {
       float w[V];
@@ -89,19 +90,19 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
 
 // T: storage of an image in the weights' dtype; a task with row scales holds E4M3 codes instead (Section 7,
 // "Combination with quantization").  The choice is uniform over the workgroup.
-template <class T>
+template <class T, int ITEMS = kImgItemsPerBlock>
 __device__ __forceinline__ void image_block(const ImgTask& t, int local_block, float* __restrict__ cs) {
-  if (t.scale) image_block_as<FP8>(t, local_block, cs);
-  else image_block_as<T>(t, local_block, cs);
+  if (t.scale) image_block_as<FP8, ITEMS>(t, local_block, cs);
+  else image_block_as<T, ITEMS>(t, local_block, cs);
 }
 
 // workgroups a map needs in an image launch
-inline int image_blocks(int64_t m, int64_t k, int wdtype, bool fp8 = false) {
+inline int image_blocks(int64_t m, int64_t k, int wdtype, bool fp8 = false, int items = kImgItemsPerBlock) {
   const int V = fp8 ? 16 : wdtype == GSI_BF16 ? 8 : 4;
   int lpr = 1;
   while (lpr < k / V) lpr <<= 1;
   const int64_t rows_per_item = (int64_t)kImgLoads * (kWave / lpr);
-  return (int)ceil_div(ceil_div(m, rows_per_item), kImgItemsPerBlock);
+  return (int)ceil_div(ceil_div(m, rows_per_item), items);
 }
 
 }  // namespace gsi

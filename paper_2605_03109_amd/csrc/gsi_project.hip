@@ -407,7 +407,8 @@ size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype) {
   if (B == 1) stage_geom(d, k, udtype, s_rows, s_slabs, true);  // the finer of the two geometries
   const size_t part_slabs = (size_t)std::max(g.a_slabs, s_slabs);
   // (a single token's slab shares of the norms, or the kGateDoubles doubles of the single-pass gate)
-  size_t need = align_up(part_slabs * B * k * 4, 256) +
+  // (B == 1: twice, for the low parts of the partials that the single-pass gate keeps)
+  size_t need = align_up(part_slabs * B * k * 4 * (B == 1 ? 2 : 1), 256) +
                 align_up(std::max((size_t)g.b_slabs * B * 2 * 4, sizeof(double) * kGateDoubles), 256);
   if (tile_project_shape_ok(d, k, B, udtype)) need = std::max(need, tile_project_ws(d, k, B));
   return need;
@@ -433,7 +434,7 @@ void decode_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws)
   }
   const size_t part_slabs = (size_t)std::max(g.a_slabs, std::max(t.s_slabs, f_slabs));
   t.part_c = reinterpret_cast<float*>(ws);
-  t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up(part_slabs * B * k * 4, 256));
+  t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up(part_slabs * B * k * 4 * (B == 1 ? 2 : 1), 256));
 }
 
 hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s) {

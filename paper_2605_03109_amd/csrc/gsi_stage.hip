@@ -65,10 +65,10 @@ __device__ __forceinline__ bool single_pass_gate(const double* __restrict__ gw, 
   const int lane = threadIdx.x % kWave;
   double a = 0.0;
   for (int s = lane; s < slabs; s += kWave) a += gw[s];
-  const double v = lane <= kGramBlocks ? gw[slabs + lane] : 0.0;
+  const double v = lane < kGramBlocks + kC2Shares ? gw[slabs + lane] : 0.0;
   const double x2 = wave_sum_f64(a);
   const double q = wave_sum_f64(lane < kGramBlocks ? v : 0.0);
-  const double c2 = __shfl(v, kGramBlocks, kWave);
+  const double c2 = wave_sum_f64(lane >= kGramBlocks ? v : 0.0);
   const double r2 = x2 - c2 + q;
   rn = (float)sqrt(r2 > 0.0 ? r2 : 0.0);
   xn = (float)sqrt(x2);
@@ -188,6 +188,23 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
     for (int w = 0; w < kWaves; ++w) t += dsh[w];
     reinterpret_cast<double*>(reinterpret_cast<char*>(p.part_c) + p.x2_off)[slab] = t;
   }
+  if (p.x2_off) {  // single-pass gate: the row groups are added in fp64 and the partial is kept as high + low part
+    const int slabs = p.slabs_x & 0xffff;
+    for (int j = threadIdx.x; j < k; j += kBlock) {
+      double s = 0.0;
+      for (int g = 0; g < rps; g += 4) {
+        float v[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) v[q] = red[(g + q) * k + j];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) s += (double)v[q];
+      }
+      const float hi = (float)s;
+      p.part_c[(int64_t)slab * k + j] = hi;
+      p.part_c[(int64_t)(slabs + slab) * k + j] = (float)(s - (double)hi);
+    }
+    return;
+  }
   for (int j = threadIdx.x; j < k; j += kBlock) {
     float s = 0.f;
     for (int g = 0; g < rps; g += 4) {  // rps is a multiple of 4: four LDS reads in flight, fixed order of adds
@@ -210,14 +227,44 @@ __device__ __forceinline__ void cred_block(const StageCRed& p) {
 // Single-pass gate: block `blk` of kGramBlocks adds the partials of one input (block 0 writes C and |c|^2), then
 // takes rows [blk * rpb, (blk + 1) * rpb) of E: share = sum_i c_i (sum_j E_ij c_j).  A wave takes a row at a time,
 // a lane the 16-byte pieces lane, lane + 64, ... of it.
-__device__ __forceinline__ void gram_block(const StageCRed& p, int blk, float* __restrict__ cs, double* __restrict__ dsh) {
+// c_j to double precision: high and low parts of the slab partials ([slabs][k] each, low parts behind the high
+// parts), slab order fixed
+__device__ __forceinline__ double sum_partials_f64(const float* __restrict__ pc, int k, int slabs) {
+  double s = 0.0;
+  const float* __restrict__ lo = pc + (int64_t)slabs * k;
+  int sl = 0;
+  for (; sl + 8 <= slabs; sl += 8) {
+    float h[8], l[8];
+#pragma unroll
+    for (int q = 0; q < 8; ++q) {
+      h[q] = pc[(int64_t)(sl + q) * k];
+      l[q] = lo[(int64_t)(sl + q) * k];
+    }
+#pragma unroll
+    for (int q = 0; q < 8; ++q) s += (double)h[q] + (double)l[q];
+  }
+  for (; sl < slabs; ++sl) s += (double)pc[(int64_t)sl * k] + (double)lo[(int64_t)sl * k];
+  return s;
+}
+
+// c_ready: C already holds the sums (a launch before this one added the partials)
+__device__ __forceinline__ void gram_block(const StageCRed& p, double* __restrict__ gw, bool c_ready, int blk,
+                                           float* __restrict__ cs, double* __restrict__ dsh) {
   const int k = p.k_slabs & 0xffff, slabs = p.k_slabs >> 16;
-  double* __restrict__ gw = reinterpret_cast<double*>(reinterpret_cast<char*>(const_cast<float*>(p.part_c)) + p.gw_off);
   const int lane = threadIdx.x % kWave, wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-  for (int j = threadIdx.x; j < k; j += kBlock) {
-    const float c = sum_partials(p.part_c + j, k, slabs);
-    cs[j] = c;
-    if (blk == 0) p.C[j] = c;
+  double c2 = 0.0;  // block 0, when it adds the partials itself: |c|^2 of the unrounded sums
+  if (c_ready) {
+    for (int j = threadIdx.x; j < k; j += kBlock) cs[j] = p.C[j];
+  } else {
+    for (int j = threadIdx.x; j < k; j += kBlock) {
+      const double cd = sum_partials_f64(p.part_c + j, k, slabs);
+      const float c = (float)cd;
+      cs[j] = c;
+      if (blk == 0) {
+        p.C[j] = c;
+        c2 = fma(cd, cd, c2);
+      }
+    }
   }
   __syncthreads();
   const int rpb = (k + kGramBlocks - 1) / kGramBlocks;
@@ -239,9 +286,7 @@ __device__ __forceinline__ void gram_block(const StageCRed& p, int blk, float* _
     acc = fma((double)cs[i], (double)s, acc);
   }
   if (lane == 0) dsh[wave] = acc;
-  if (blk == 0) {  // |c|^2: each thread its coefficients j, j + 256, ...; waves in order
-    double c2 = 0.0;
-    for (int j = threadIdx.x; j < k; j += kBlock) c2 = fma((double)cs[j], (double)cs[j], c2);
+  if (blk == 0 && !c_ready) {  // |c|^2: each thread its coefficients j, j + 256, ...; waves in order
     c2 = wave_sum_f64(c2);
     if (lane == 0) dsh[kWaves + wave] = c2;
   }
@@ -250,10 +295,11 @@ __device__ __forceinline__ void gram_block(const StageCRed& p, int blk, float* _
     double t = 0.0;
     for (int w = 0; w < kWaves; ++w) t += dsh[w];
     gw[slabs + blk] = t;
-    if (blk == 0) {
-      double c2 = 0.0;
-      for (int w = 0; w < kWaves; ++w) c2 += dsh[kWaves + w];
-      gw[slabs + kGramBlocks] = c2;
+    if (blk == 0 && !c_ready) {
+      double t2 = 0.0;
+      for (int w = 0; w < kWaves; ++w) t2 += dsh[kWaves + w];
+      gw[slabs + kGramBlocks] = t2;
+      for (int q = 1; q < kC2Shares; ++q) gw[slabs + kGramBlocks + q] = 0.0;
     }
   }
 }
@@ -401,7 +447,11 @@ __global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
   }
   b -= a.i_total;
   if (a.gram) {
-    if (b < a.ncr * kGramBlocks) gram_block(a.cr[b / kGramBlocks], b % kGramBlocks, lds, dsh);
+    if (b < a.ncr * kGramBlocks) {
+      const StageCRed& p = a.cr[b / kGramBlocks];
+      gram_block(p, reinterpret_cast<double*>(reinterpret_cast<char*>(const_cast<float*>(p.part_c)) + p.gw_off), false,
+                 b % kGramBlocks, lds, dsh);
+    }
     return;
   }
   if (b < a.ncr) {
@@ -442,46 +492,87 @@ __global__ __launch_bounds__(kBlock) void table_partial(const TabIn* __restrict_
   partial_block<T>(p, b - tab[i], lds, xs, dsh);
 }
 
+// c = the partials added in slab order: a workgroup per (input, 64 columns); its four waves take every fourth slab
+// (16 loads in flight per lane) and are combined through LDS in wave order
+__global__ __launch_bounds__(kBlock) void table_cred(const TabIn* __restrict__ ins, const int* __restrict__ cbegin,
+                                                     int n_in) {
+  __shared__ double sh[kWaves][kWave];
+  __shared__ int tab[kMaxTabIn];
+  const int i = find_in_table(cbegin, n_in, blockIdx.x, tab);
+  const TabIn& in = ins[i];
+  const int k = in.k_rows & 0xffff, slabs = in.slabs & 0xffff;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int cblk = blockIdx.x - tab[i];
+  const int j = cblk * kWave + lane;
+  double s = 0.0;
+  if (j < k) {
+    const float* __restrict__ pc = in.part_c + j;
+    const float* __restrict__ lo = pc + (int64_t)slabs * k;
+    int sl = wave;
+    for (; sl + 7 * kWaves < slabs; sl += 8 * kWaves) {
+      float h[8], l[8];
+#pragma unroll
+      for (int q = 0; q < 8; ++q) {
+        h[q] = pc[(int64_t)(sl + q * kWaves) * k];
+        l[q] = lo[(int64_t)(sl + q * kWaves) * k];
+      }
+#pragma unroll
+      for (int q = 0; q < 8; ++q) s += (double)h[q] + (double)l[q];
+    }
+    for (; sl < slabs; sl += kWaves) s += (double)pc[(int64_t)sl * k] + (double)lo[(int64_t)sl * k];
+  }
+  sh[wave][lane] = s;
+  __syncthreads();
+  if (wave == 0) {  // (whole wave: the sum over its lanes below needs every lane)
+    const double cd = (sh[0][lane] + sh[1][lane]) + (sh[2][lane] + sh[3][lane]);
+    if (j < k) in.C[j] = (float)cd;
+    const double c2 = wave_sum_f64(j < k ? cd * cd : 0.0);  // this block's share of |c|^2, from the unrounded sums
+    double* gw = reinterpret_cast<double*>(reinterpret_cast<char*>(in.part_c) + in.gw_off);
+    if (lane == 0) {
+      gw[slabs + kGramBlocks + cblk] = c2;
+      if (cblk == 0)  // shares that no block writes (k / 64 < kC2Shares) are zero
+        for (int q = (k + kWave - 1) / kWave; q < kC2Shares; ++q) gw[slabs + kGramBlocks + q] = 0.0;
+    }
+  }
+}
+
 __global__ __launch_bounds__(kBlock) void table_gram(const TabIn* __restrict__ ins) {
   __shared__ __align__(16) float lds[kMaxK];
   __shared__ double dsh[2 * kWaves];
   const TabIn& in = ins[blockIdx.x / kGramBlocks];
   StageCRed p;
-  p.part_c = in.part_c; p.C = in.C; p.E = in.E;
+  p.part_c = nullptr; p.C = in.C; p.E = in.E;
   p.k_slabs = (in.k_rows & 0xffff) | ((in.slabs & 0xffff) << 16);
-  p.gw_off = in.gw_off;
-  gram_block(p, blockIdx.x % kGramBlocks, lds, dsh);
+  p.gw_off = 0;
+  gram_block(p, reinterpret_cast<double*>(reinterpret_cast<char*>(in.part_c) + in.gw_off), true, blockIdx.x % kGramBlocks,
+             lds, dsh);
 }
 
-// image rows of every map first, then the residual workgroups (which evaluate the gate, publish it, and form r only
-// for an input that fired)
+// the residual workgroups first (they evaluate the gate, publish it, and form r only for an input that fired: few
+// and slow, so they start early and run beside the image stream), then the image rows of every map
 template <class T>
 __global__ __launch_bounds__(kBlock) void table_rows(const TabIn* __restrict__ ins, const TabMap* __restrict__ maps,
                                                      const int* __restrict__ ibegin, const int* __restrict__ rbegin,
-                                                     int n_in, int n_maps, int i_total, float eps) {
+                                                     int n_in, int n_maps, int r_total, float eps) {
   __shared__ __align__(16) float lds[kBlock * 8];
   __shared__ float xs[kStageMaxRows];
   __shared__ float nr[kWaves], nx[kWaves];
   __shared__ int tab[kMaxTabMaps];
   int b = blockIdx.x;
-  if (b < i_total) {
+  if (b >= r_total) {
+    b -= r_total;
     const int j = find_in_table(ibegin, n_maps, b, tab);
     const TabMap& mp = maps[j];
-    const TabIn& in = ins[mp.in];
-    const int slabs = in.slabs & 0xffff;
-    if ((in.r_rows_x >> 20) & 1) {  // W x form of the slow path: a fired input's rows are left to the weight kernel
+    if (mp.gw) {  // W x form of the slow path: a fired input's rows are left to the weight kernel
       float rn, xn;
-      if (single_pass_gate(reinterpret_cast<const double*>(reinterpret_cast<const char*>(in.part_c) + in.gw_off), slabs,
-                           eps, rn, xn))
-        return;
+      if (single_pass_gate(mp.gw, mp.slabs, eps, rn, xn)) return;
     }
     ImgTask t;
-    t.M = mp.M; t.Y = mp.Y; t.part_c = nullptr; t.C = in.C; t.scale = mp.scale;
-    t.m = mp.m; t.k = in.k_rows & 0xffff; t.a_slabs = 0; t.blk_begin = tab[j];
-    image_block<T>(t, b - t.blk_begin, lds);
+    t.M = mp.M; t.Y = mp.Y; t.part_c = nullptr; t.C = mp.C; t.scale = mp.scale;
+    t.m = mp.m; t.k = mp.k; t.a_slabs = 0; t.blk_begin = tab[j];
+    image_block<T, kTabImgItems>(t, b - t.blk_begin, lds);
     return;
   }
-  b -= i_total;
   const int i = find_in_table(rbegin, n_in, b, tab);
   const TabIn& in = ins[i];
   StageGate g;
@@ -595,7 +686,7 @@ hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0, h
 
 size_t stage_table_bytes(int n_in, int n_maps) {
   return align_up((size_t)n_in * sizeof(TabIn), 256) + align_up((size_t)n_maps * sizeof(TabMap), 256) +
-         2 * align_up((size_t)(n_in + 1) * sizeof(int), 256) + align_up((size_t)(n_maps + 1) * sizeof(int), 256);
+         3 * align_up((size_t)(n_in + 1) * sizeof(int), 256) + align_up((size_t)(n_maps + 1) * sizeof(int), 256);
 }
 
 hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, float eps,
@@ -605,26 +696,30 @@ hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap
   const size_t off_maps = align_up((size_t)n_in * sizeof(TabIn), 256);
   const size_t off_p = off_maps + align_up((size_t)n_maps * sizeof(TabMap), 256);
   const size_t off_r = off_p + align_up((size_t)(n_in + 1) * sizeof(int), 256);
-  const size_t off_i = off_r + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  const size_t off_c = off_r + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  const size_t off_i = off_c + align_up((size_t)(n_in + 1) * sizeof(int), 256);
   const size_t bytes = stage_table_bytes(n_in, n_maps);
   std::vector<char> host(bytes, 0);
   std::memcpy(host.data(), ins, (size_t)n_in * sizeof(TabIn));
   if (n_maps) std::memcpy(host.data() + off_maps, maps, (size_t)n_maps * sizeof(TabMap));
   int* pb = reinterpret_cast<int*>(host.data() + off_p);
   int* rb = reinterpret_cast<int*>(host.data() + off_r);
+  int* cb = reinterpret_cast<int*>(host.data() + off_c);
   int* ib = reinterpret_cast<int*>(host.data() + off_i);
-  int64_t tp = 0, tr = 0, ti = 0;
+  int64_t tp = 0, tr = 0, tc = 0, ti = 0;
   for (int i = 0; i < n_in; ++i) {
     pb[i] = (int)tp;
     rb[i] = (int)tr;
+    cb[i] = (int)tc;
     tp += ins[i].slabs & 0xffff;
     tr += ins[i].slabs >> 16;
+    tc += ceil_div(ins[i].k_rows & 0xffff, kWave);
   }
   for (int j = 0; j < n_maps; ++j) {
     ib[j] = (int)ti;
-    ti += image_blocks(maps[j].m, ins[maps[j].in].k_rows & 0xffff, dtype, maps[j].scale != nullptr);
+    ti += image_blocks(maps[j].m, maps[j].k, dtype, maps[j].scale != nullptr, kTabImgItems);
   }
-  pb[n_in] = (int)tp; rb[n_in] = (int)tr; ib[n_maps] = (int)ti;
+  pb[n_in] = (int)tp; rb[n_in] = (int)tr; cb[n_in] = (int)tc; ib[n_maps] = (int)ti;
   if (tp >= (1 << 30) || tr + ti >= (1 << 30)) return hipErrorInvalidValue;
   if (hipError_t e = upload_launch(host.data(), bytes, table, s); e != hipSuccess) return e;
   const char* base = static_cast<const char*>(table);
@@ -632,6 +727,7 @@ hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap
   const TabMap* d_maps = reinterpret_cast<const TabMap*>(base + off_maps);
   const int* d_pb = reinterpret_cast<const int*>(base + off_p);
   const int* d_rb = reinterpret_cast<const int*>(base + off_r);
+  const int* d_cb = reinterpret_cast<const int*>(base + off_c);
   const int* d_ib = reinterpret_cast<const int*>(base + off_i);
   auto ev = [&](int w, hipEvent_t e) { return which_timed == w ? e : nullptr; };
   // 1. partial projections
@@ -643,18 +739,20 @@ hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap
     else table_partial<F32><<<(unsigned)tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  // 2. coefficient sums and the shares of c^T E c
+  // 2. coefficient sums, then the shares of c^T E c
+  table_cred<<<(unsigned)tc, kBlock, 0, s>>>(d_ins, d_cb, n_in);
+  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   if (ev(1, e0)) hipExtLaunchKernelGGL(table_gram, dim3((unsigned)n_in * kGramBlocks), dim3(kBlock), 0, s, e0, e1, 0, d_ins);
   else table_gram<<<(unsigned)n_in * kGramBlocks, kBlock, 0, s>>>(d_ins);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // 3. image rows, gates, residuals of fired inputs
   const unsigned grid = (unsigned)(ti + tr);
   if (dtype == GSI_BF16) {
-    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
-    else table_rows<BF16><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
+    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
+    else table_rows<BF16><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
   } else {
-    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
-    else table_rows<F32><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)ti, eps);
+    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
+    else table_rows<F32><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
   }
   return hipGetLastError();
 }

@@ -115,9 +115,9 @@ def test_single_pass_block(gsi, pu, wdtype, wx):
 
 
 def test_single_pass_many_inputs_equal_explicit_path(gsi, pu):
-    """Five blocks in one call per token (two sets of inputs, so the stages of different sets share launches): the
-    coefficients and the un-fired outputs are the explicit path's bit for bit (same partials, same sums, same image
-    rows), the decisions agree, and fired outputs agree to rounding (r is the same arithmetic on the same c)."""
+    """Five blocks in one call per token (more inputs than one launch's arguments describe, so every stage runs once
+    over a descriptor table in the workspace): decisions equal the explicit path's, everything else agrees with it to
+    rounding, and the first and last block are checked against the oracle."""
     L, T = 5, 6
     blocks = [wl.transformer_block(f"b{l}", d=512, ffn=2048, k=64, T=T, fire_rate=0.34, p=1.5, seed=4200 + l) for l in range(L)]
     eps = blocks[0].eps
@@ -135,17 +135,22 @@ def test_single_pass_many_inputs_equal_explicit_path(gsi, pu):
         _run_tokens(sp, T)
     ex = gsi.LayerStack([dict(i, flags=0) for i in inputs], maps, T, eps)
     _run_tokens(ex, T)
-    n_fired = 0
+    n_fired, worst = 0, 0.0
     for a, b in zip(sp.inputs_t, ex.inputs_t):
-        assert torch.equal(a["C"], b["C"]) and torch.equal(a["mask"], b["mask"])
+        assert torch.equal(a["mask"], b["mask"])
+        # (the table launches add the partials in another order than the 16-input launches)
+        assert torch.allclose(a["C"], b["C"], rtol=0, atol=2e-6 * float(b["xnorm"].max()))
         assert torch.allclose(a["xnorm"], b["xnorm"], rtol=1e-6, atol=0)
-        assert torch.allclose(a["rnorm"], b["rnorm"], rtol=0, atol=1e-5 * float(b["xnorm"].min()))
+        drho = ((a["rnorm"] - b["rnorm"]).abs() / b["xnorm"]).max().item()
+        worst = max(worst, drho)
+        assert drho <= 1e-5, drho
         f = b["mask"].bool()
         n_fired += int(f.sum())
-        assert torch.equal(a["R"][f], b["R"][f])
+        assert torch.allclose(a["R"][f], b["R"][f], rtol=0, atol=2e-6 * float(b["xnorm"].max()))
     assert n_fired > 0
+    say(f"  largest |rho_single_pass - rho_explicit| over {len(inputs) * T} gate evaluations: {worst:.2e}")
     for a, b in zip(sp.maps_t, ex.maps_t):
-        assert torch.equal(a["Y"], b["Y"])
+        assert torch.allclose(a["Y"], b["Y"], rtol=0, atol=1e-5 * float(b["Y"].abs().max()))
     # and the first and last block against the oracle
     for l in (0, L - 1):
         w = blocks[l]
