@@ -113,6 +113,33 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
 int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t B, int wdtype, int xdtype,
                      float* Y, void* ws, size_t ws_bytes, void* stream);
 
+/* Online basis maintenance: one DGKS rank-1 extension of a basis of fixed capacity, with the matching append to the
+ * cached images (Section 5.3 "The cascade initialization", Section 5.4 "Time-dimension tracking": a token whose
+ * residual ratio exceeds a threshold extends the basis by one orthonormal vector; Section 7 "Online basis
+ * adaptation").  The paper gives no threshold, capacity or eviction rule; here the basis lives in U[d,K] (`udtype`)
+ * whose columns from k on are ZERO (a zero column changes neither c, r nor y, so every other call runs on it
+ * unchanged at rank K), k_cur[0] is a device counter of the columns in use, and nothing is ever evicted.
+ * Inputs: the residual R[d], rnorm[1], xnorm[1] of ONE token against the current basis, as gsi_project or
+ * gsi_layer_stack wrote them (with GSI_INPUT_GATE_SINGLE_PASS, R exists only for a token that fired).
+ *   candidate iff xnorm > 0, rnorm / xnorm >= tau (compared like the gate) and k_cur < K;
+ *   s = U^T r, r2 = r - U s (classical Gram-Schmidt's re-orthogonalisation pass); if |r2| > 0:
+ *   column k_cur of U = r2 / |r2| rounded to `udtype`; for each map, column k_cur of M[m,K] = W u for the STORED u
+ *   (rounded to `udtype`, which must also be the maps' dtype), so that M = W U keeps holding (Eq. (exact));
+ *   if `gram` (the E[K,K] of gsi_build_gram) is not NULL its row and column k_cur become U^T u - e_k;
+ *   k_cur[0] += 1.  extended[0] (may be NULL) = 1 if the basis grew, else 0.
+ * Everything is decided on the device; a token that does not extend the basis costs a few empty launches and no pass
+ * over U or W.  maps: HOST array.  ws: gsi_extend_basis_workspace_bytes(d, K).  The cascade of Section 5.3 is this
+ * call on a basis array that was initialised with the previous layer's columns. */
+typedef struct gsi_extend_map {
+  const void* W;      /* [m,d] udtype */
+  void* M;            /* [m,K] udtype; column k_cur is written */
+  int64_t m;
+} gsi_extend_map;
+int gsi_extend_basis(void* U, int64_t d, int64_t K, int udtype, int32_t* k_cur, const float* R, const float* rnorm,
+                     const float* xnorm, float tau, const gsi_extend_map* maps, int32_t n_maps, float* gram,
+                     int32_t* extended, void* ws, size_t ws_bytes, void* stream);
+size_t gsi_extend_basis_workspace_bytes(int64_t d, int64_t K);
+
 /* Descriptors for gsi_layer_stack (host structs holding device pointers). */
 typedef struct gsi_input_desc {
   const void* U;      /* basis of this input, [d,k], udtype                                     */

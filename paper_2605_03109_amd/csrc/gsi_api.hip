@@ -7,6 +7,7 @@
 #include <vector>
 
 #include "gsi_decode.h"
+#include "gsi_extend.h"
 #include "gsi_fused.h"
 #include "gsi_internal.h"
 #include "gsi_mfma.h"
@@ -170,6 +171,49 @@ int gsi_build_gram(const void* U, int64_t d, int64_t k, int udtype, float* E, vo
   if (k > 65535 * 16) return fail(GSI_ERR_SHAPE, "gsi_build_gram: k = %lld is too large", (long long)k);
   hipError_t e = gsi::generic_build_gram(U, d, k, udtype, E, static_cast<hipStream_t>(stream));
   if (e != hipSuccess) return hip_fail(e, "gsi_build_gram");
+  return GSI_OK;
+}
+
+size_t gsi_extend_basis_workspace_bytes(int64_t d, int64_t K) {
+  return d >= 1 && K >= 1 ? gsi::extend_ws_bytes(d, K) : 0;
+}
+
+int gsi_extend_basis(void* U, int64_t d, int64_t K, int udtype, int32_t* k_cur, const float* R, const float* rnorm,
+                     const float* xnorm, float tau, const gsi_extend_map* maps, int32_t n_maps, float* gram,
+                     int32_t* extended, void* ws, size_t ws_bytes, void* stream) {
+  const char* fn = "gsi_extend_basis";
+  GSI_REQUIRE_PTR(U);
+  GSI_REQUIRE_PTR(k_cur);
+  GSI_REQUIRE_PTR(R);
+  GSI_REQUIRE_PTR(rnorm);
+  GSI_REQUIRE_PTR(xnorm);
+  if (!dtype_ok(udtype)) return fail(GSI_ERR_DTYPE, "%s: unknown udtype %d", fn, udtype);
+  if (int rc = check_shape(fn, 1, d, K, 0)) return rc;
+  if (n_maps < 0) return fail(GSI_ERR_SHAPE, "%s: n_maps = %d < 0", fn, n_maps);
+  if (n_maps > 0) GSI_REQUIRE_PTR(maps);
+  if (!(tau >= 0.f)) return fail(GSI_ERR_SHAPE, "%s: tau must be a number >= 0", fn);
+  if (K > (int64_t)65535 * 64) return fail(GSI_ERR_SHAPE, "%s: K = %lld is too large", fn, (long long)K);
+  const size_t es = gsi::elem_size(udtype);
+  GSI_REQUIRE_ALIGNED(U, es);
+  GSI_REQUIRE_ALIGNED(k_cur, 4);
+  GSI_REQUIRE_ALIGNED(R, 4);
+  GSI_REQUIRE_ALIGNED(rnorm, 4);
+  GSI_REQUIRE_ALIGNED(xnorm, 4);
+  if (gram) GSI_REQUIRE_ALIGNED(gram, 4);
+  if (extended) GSI_REQUIRE_ALIGNED(extended, 4);
+  std::vector<gsi::ExtMap> em(n_maps);
+  for (int j = 0; j < n_maps; ++j) {
+    if (!maps[j].W) return fail(GSI_ERR_NULL, "%s: maps[%d].W is NULL", fn, j);
+    if (!maps[j].M) return fail(GSI_ERR_NULL, "%s: maps[%d].M is NULL", fn, j);
+    if (maps[j].m < 1) return fail(GSI_ERR_SHAPE, "%s: maps[%d].m = %lld < 1", fn, j, (long long)maps[j].m);
+    if (!aligned(maps[j].W, es) || !aligned(maps[j].M, es))
+      return fail(GSI_ERR_ALIGN, "%s: maps[%d] is not aligned to its element size", fn, j);
+    em[j] = gsi::ExtMap{maps[j].W, maps[j].M, maps[j].m};
+  }
+  if (int rc = check_ws(fn, ws, ws_bytes, gsi_extend_basis_workspace_bytes(d, K))) return rc;
+  hipError_t e = gsi::extend_basis(U, d, K, udtype, k_cur, R, rnorm, xnorm, tau, em.data(), n_maps, gram, extended, ws,
+                                   static_cast<hipStream_t>(stream));
+  if (e != hipSuccess) return hip_fail(e, fn);
   return GSI_OK;
 }
 

@@ -27,7 +27,7 @@ MAP_IMAGE_FP8 = 1  # gsi_map_desc.flags: M holds E4M3 codes, M_scale the row sca
 CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
 
 EXPORTS = (
-    "gsi_build_image", "gsi_build_gram", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+    "gsi_build_image", "gsi_build_gram", "gsi_extend_basis", "gsi_extend_basis_workspace_bytes", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
     "gsi_layer_stack",
     "gsi_layer_stack_static", "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
@@ -55,6 +55,10 @@ class InputDesc(ctypes.Structure):
     ]
 
 
+class ExtendMap(ctypes.Structure):
+    _fields_ = [("W", ctypes.c_void_p), ("M", ctypes.c_void_p), ("m", ctypes.c_int64)]
+
+
 class MapDesc(ctypes.Structure):
     _fields_ = [
         ("W", ctypes.c_void_p), ("M", ctypes.c_void_p), ("Y", ctypes.c_void_p),
@@ -74,6 +78,11 @@ def _load() -> ctypes.CDLL:
     lib.gsi_build_image.argtypes = [vp, vp, vp, i64, i64, i64, i32, vp, sz, vp]
     lib.gsi_quantize_image_fp8.argtypes = [vp, i32, i64, i64, vp, vp, vp]
     lib.gsi_build_gram.argtypes = [vp, i64, i64, i32, vp, vp]
+    lib.gsi_extend_basis.argtypes = [vp, i64, i64, i32, vp, vp, vp, vp, f32, ctypes.POINTER(ExtendMap), ctypes.c_int32,
+                                     vp, vp, vp, sz, vp]
+    lib.gsi_extend_basis.restype = ctypes.c_int
+    lib.gsi_extend_basis_workspace_bytes.argtypes = [i64, i64]
+    lib.gsi_extend_basis_workspace_bytes.restype = sz
     lib.gsi_project.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.gsi_gate.argtypes = [vp, vp, i64, f32, vp, vp, vp, vp]
     lib.gsi_gated_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, i32, vp, sz, vp]
@@ -213,6 +222,24 @@ def build_gram(U: torch.Tensor, E: Optional[torch.Tensor] = None, stream=None) -
     E = torch.empty((k, k), dtype=torch.float32, device=U.device) if E is None else E
     _check(lib.gsi_build_gram(_ptr(U), d, k, dtype_code(U), _ptr(E), _stream(stream)))
     return E
+
+
+def extend_basis(U: torch.Tensor, k_cur: torch.Tensor, R: torch.Tensor, rnorm: torch.Tensor, xnorm: torch.Tensor,
+                 tau: float, maps: Sequence[Tuple[torch.Tensor, torch.Tensor]] = (), gram: Optional[torch.Tensor] = None,
+                 extended: Optional[torch.Tensor] = None, ws=None, stream=None) -> torch.Tensor:
+    """One rank-1 extension step of the basis array U[d,K] (in place); maps: (W[m,d], M[m,K]) pairs whose column
+    k_cur is appended.  Returns the device flag ``extended`` (int32[1])."""
+    d, K = U.shape
+    extended = torch.zeros((1,), dtype=torch.int32, device=U.device) if extended is None else extended
+    em = (ExtendMap * max(len(maps), 1))()
+    for j, (W, M) in enumerate(maps):
+        if W.dtype != U.dtype or M.dtype != U.dtype or tuple(M.shape) != (W.shape[0], K) or W.shape[1] != d:
+            raise ValueError("maps must be (W[m,d], M[m,K]) in the basis' dtype")
+        em[j].W, em[j].M, em[j].m = _ptr(W), _ptr(M), W.shape[0]
+    wsp, wsn = _ws_args(ws, int(lib.gsi_extend_basis_workspace_bytes(d, K)))
+    _check(lib.gsi_extend_basis(_ptr(U), d, K, dtype_code(U), _ptr(k_cur), _ptr(R), _ptr(rnorm), _ptr(xnorm), float(tau),
+                                em, len(maps), _ptr(gram), _ptr(extended), wsp, wsn, _stream(stream)))
+    return extended
 
 
 def quantize_image_fp8(M: torch.Tensor, M8: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,

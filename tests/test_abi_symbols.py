@@ -84,6 +84,19 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gsi_build_gram(one, 8, 9, gsi.GSI_F32, one, None) == gsi.GSI_ERR_SHAPE
     assert lib.gsi_build_gram(one, 8, 2, gsi.GSI_F32, None, None) == gsi.GSI_ERR_NULL
     assert lib.gsi_build_gram(one, 8, 2, 5, one, None) == gsi.GSI_ERR_DTYPE
+    # the rank-1 basis extension
+    em = (gsi.ExtendMap * 1)()
+    args = lambda **kw: [kw.get("U", one), kw.get("d", 8), kw.get("K", 4), kw.get("dt", gsi.GSI_F32), kw.get("kc", one), one,
+                         one, one, ctypes.c_float(kw.get("tau", 0.1)), em, kw.get("n", 0), None, None, kw.get("ws", one),
+                         kw.get("wsn", 1 << 20), None]
+    assert lib.gsi_extend_basis(*args(U=None)) == gsi.GSI_ERR_NULL
+    assert lib.gsi_extend_basis(*args(kc=None)) == gsi.GSI_ERR_NULL
+    assert lib.gsi_extend_basis(*args(K=9)) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_extend_basis(*args(dt=3)) == gsi.GSI_ERR_DTYPE
+    assert lib.gsi_extend_basis(*args(tau=-1.0)) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_extend_basis(*args(n=1)) == gsi.GSI_ERR_NULL      # maps[0].W is NULL
+    assert lib.gsi_extend_basis(*args(ws=None, wsn=0)) == gsi.GSI_ERR_WORKSPACE
+    assert lib.gsi_extend_basis_workspace_bytes(4096, 256) > 0 and lib.gsi_extend_basis_workspace_bytes(0, 4) == 0
     # a dense stack of several tokens needs its workspace
     inp[0].src_map = -1
     mp[0].m, inp[0].d, inp[0].k = 64, 64, 32

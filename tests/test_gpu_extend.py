@@ -1,0 +1,171 @@
+"""GPU parity of the rank-1 basis extension (gsi_extend_basis; Sections 5.3, 5.4 and 7 "Online basis adaptation")
+against the fp64 oracle: the decision, the new stored column, the appended image column, the updated E = U^T U - I,
+the token tracker, and a gated layer evaluated on the extended operands."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import oracle.gsi_oracle as O  # noqa: E402
+from paper_2605_03109_amd import workload as wl  # noqa: E402
+
+
+@pytest.fixture(scope="module")
+def gsi():
+    assert torch.cuda.is_available(), "GPU tests need a GPU"
+    from paper_2605_03109_amd import gsi as g
+
+    return g
+
+
+@pytest.fixture(scope="module")
+def pu(gsi):
+    import parity_util
+
+    return parity_util
+
+
+def say(msg):
+    print(msg, flush=True)
+
+
+def _basis_array(d, K, k, dt, seed):
+    """Stored basis array U[d, K]: k orthonormal columns (rounded to storage), the rest zero."""
+    store = np.zeros((d, K), dtype=np.float32 if dt == "f32" else np.uint16)
+    if k:
+        store[:, :k] = wl.store(wl.make_basis64(d, k, seed), dt)
+    return store
+
+
+def _token(U64, k, rho, seed):
+    """fp32 token whose residual ratio against the first k columns is about rho."""
+    rng = np.random.default_rng(seed)
+    d = U64.shape[0]
+    a = rng.standard_normal(k) / np.sqrt(np.arange(1, k + 1)) if k else np.zeros(0)
+    n = rng.standard_normal(d)
+    for _ in range(2):
+        n -= U64[:, :k] @ (U64[:, :k].T @ n)
+    n /= np.linalg.norm(n)
+    base = U64[:, :k] @ a
+    nb = np.linalg.norm(base) if k else 0.0
+    sig = rho * nb / np.sqrt(1 - rho * rho) if k else 1.0
+    return (base + sig * n).astype(np.float32)
+
+
+@pytest.mark.parametrize("d,K,k,m,dt", [(512, 64, 40, 200, "bf16"), (4096, 256, 200, 1024, "bf16"), (768, 64, 63, 300, "f32"),
+                                        (100, 24, 5, 33, "f32"), (16384, 64, 8, 256, "bf16")])
+def test_extend_step_against_oracle(gsi, pu, d, K, k, m, dt):
+    say(f"case extend d={d} K={K} k={k} m={m} {dt}")
+    store = _basis_array(d, K, k, dt, seed=8000 + d)
+    U64 = O.widen(store, dt)
+    Ws = [wl.make_weight(m, d, 8100 + d + j, dt) for j in range(2)]
+    W64 = [O.widen(W, dt) for W in Ws]
+    x = _token(U64, k, 0.3, seed=8200 + d)
+    Ud = gsi.to_device(store, dt)
+    Wd = [gsi.to_device(W, dt) for W in Ws]
+    Md = [gsi.build_image(W, Ud) for W in Wd]          # images at capacity K: columns k.. are zero
+    for M in Md:
+        assert not gsi.bits_of(M)[:, k:].any()
+    E = gsi.build_gram(Ud)
+    kc = torch.tensor([k], dtype=torch.int32, device="cuda")
+    Xd = gsi.to_device(x[None, :], "f32")
+    C, R, rn, xn = gsi.project(Ud, Xd)
+    U_before, M_before = Ud.clone(), [M.clone() for M in Md]
+    # below the threshold: nothing changes
+    rho = float(rn[0] / xn[0])
+    ext = gsi.extend_basis(Ud, kc, R[0], rn, xn, rho * 1.01, list(zip(Wd, Md)), gram=E)
+    torch.cuda.synchronize()
+    assert int(ext.item()) == 0 and int(kc.item()) == k and torch.equal(Ud, U_before)
+    assert all(torch.equal(a, b) for a, b in zip(Md, M_before))
+    # at capacity: nothing changes
+    kfull = torch.tensor([K], dtype=torch.int32, device="cuda")
+    ext = gsi.extend_basis(Ud, kfull, R[0], rn, xn, 0.0, list(zip(Wd, Md)), gram=E)
+    torch.cuda.synchronize()
+    assert int(ext.item()) == 0 and int(kfull.item()) == K and torch.equal(Ud, U_before)
+    # above it: the basis grows by the oracle's direction
+    ext = gsi.extend_basis(Ud, kc, R[0], rn, xn, rho * 0.99, list(zip(Wd, Md)), gram=E)
+    torch.cuda.synchronize()
+    assert int(ext.item()) == 1 and int(kc.item()) == k + 1
+    ref_store, ref_k, ref_ext = O.extend_basis(store, dt, k, x.astype(np.float64), rho * 0.99)
+    assert ref_ext and ref_k == k + 1
+    got = gsi.bits_of(Ud)
+    assert np.array_equal(got[:, :k], store[:, :k]) and not got[:, k + 1:].any()
+    u_exact, n1, n2 = O.dgks_direction(U64, x.astype(np.float64))
+    u_dev = O.widen(got, dt)[:, k]
+    half_ulp = 2.0 ** -8 if dt == "bf16" else 2.0 ** -24
+    # one storage rounding of a direction computed in fp32 from the device's fp32 residual
+    assert np.all(np.abs(u_dev - u_exact) <= half_ulp * np.abs(u_exact) * (1 + 1e-3) + 3e-6), np.abs(u_dev - u_exact).max()
+    codes_differ = int((got[:, k] != ref_store[:, k]).sum())
+    if dt == "bf16":
+        say(f"  stored column: {codes_differ} of {d} bf16 codes differ from the oracle's, each by one unit in the last place")
+        diff = np.abs(got[:, k].astype(np.int64) - ref_store[:, k].astype(np.int64))
+        assert diff.max() <= 1 and codes_differ <= max(2, d // 50)
+    # the image append: column k = W u for the STORED u, the other columns untouched
+    for W, Wq, M, Mb in zip(W64, Ws, Md, M_before):
+        Mbits = gsi.bits_of(M)
+        assert np.array_equal(np.delete(Mbits, k, axis=1), np.delete(gsi.bits_of(Mb), k, axis=1))
+        col = O.extend_image(np.zeros((m, K)), k, W, u_dev)[:, k]
+        col_dev = O.widen(Mbits, dt)[:, k]
+        acc = (8.0 + np.sqrt(d)) * 2.0 ** -24 * (np.abs(W) @ np.abs(u_dev))
+        assert np.all(np.abs(col_dev - col) <= half_ulp * np.abs(col) * (1 + 1e-6) + acc + 1e-38)
+    # the whole image still is W U for the stored operands (the check every image gets)
+    Unew64 = O.widen(got, dt)
+    pu.check_image(gsi.bits_of(Md[0]), O.build_image(W64[0], Unew64), W64[0], Unew64, dt)
+    # E = U^T U - I of the extended stored basis (row and column k rewritten in fp32 arithmetic)
+    Eref = O.gram_defect(Unew64)
+    Edev = E.cpu().numpy().astype(np.float64)
+    assert np.abs(Edev - Eref).max() <= 2e-6, np.abs(Edev - Eref).max()
+    assert np.array_equal(Edev, Edev.T)
+    # the token now lies in the span up to storage rounding, and a gated layer on the extended operands is exact
+    C2, R2, rn2, xn2 = gsi.project(Ud, Xd)
+    Cr, Rr, rnr, xnr = O.project(Unew64, x[None, :].astype(np.float64))
+    assert abs(float(rn2[0] / xn2[0]) - rnr[0] / xnr[0]) <= pu.TOL_RHO
+    assert float(rn2[0] / xn2[0]) <= rho * (0.02 if dt == "bf16" else 1e-4) + 1e-6
+    mask, idx, n = gsi.gate(rn2, xn2, 0.05)
+    Y = gsi.gated_linear(Wd[0], Md[0], C2, R2, idx, n)
+    torch.cuda.synchronize()
+    Yref = O.gated_linear(W64[0], O.widen(gsi.bits_of(Md[0]), dt), Cr, Rr, mask.cpu().numpy())
+    assert pu.rel_l2_rows(Y.cpu().numpy().astype(np.float64), Yref).max() <= pu.TOL_Y_STAGE[dt]
+    Ydense = O.dense_linear(W64[0], x[None, :].astype(np.float64))
+    assert pu.rel_l2_rows(Y.cpu().numpy().astype(np.float64), Ydense).max() <= pu.TOL_Y[dt]
+
+
+@pytest.mark.parametrize("dt", ["f32", "bf16"])
+def test_tracker_against_oracle(gsi, pu, dt):
+    """Section 5.4: tokens arrive one at a time, each is projected and may extend the basis; started empty, and
+    (Section 5.3, the cascade) started from a basis that already spans most of the tokens' subspace."""
+    d, K, T, tau = 256, 16, 24, 0.2
+    rng = np.random.default_rng(31 if dt == "f32" else 32)
+    B6, _ = np.linalg.qr(rng.standard_normal((d, 6)))
+    X = (rng.standard_normal((T, 5)) @ B6[:, :5].T).astype(np.float32)
+    X[13] += (3.0 * B6[:, 5]).astype(np.float32)
+    for start_cols in (0, 4):
+        store = np.zeros((d, K), dtype=np.float32 if dt == "f32" else np.uint16)
+        if start_cols:
+            store[:, :start_cols] = wl.store(B6[:, :start_cols], dt)
+        W = wl.make_weight(40, d, 77, dt)
+        Ud, Wd = gsi.to_device(store, dt), gsi.to_device(W, dt)
+        Md = gsi.build_image(Wd, Ud)
+        kc = torch.tensor([start_cols], dtype=torch.int32, device="cuda")
+        grew = []
+        Xd = gsi.to_device(X, "f32")
+        for t in range(T):
+            C, R, rn, xn = gsi.project(Ud, Xd[t:t + 1].contiguous())
+            ext = gsi.extend_basis(Ud, kc, R[0], rn, xn, tau, [(Wd, Md)])
+            if int(ext.item()):
+                grew.append(t)
+        torch.cuda.synchronize()
+        ref_store, ref_k, ref_grew = O.track_basis(store, dt, start_cols, X.astype(np.float64), tau)
+        say(f"  tracker {dt} from {start_cols} columns: grew at {grew}, rank {int(kc.item())}")
+        assert grew == ref_grew and int(kc.item()) == ref_k
+        # the two bases span the same subspace (columns may differ in the last place, so compare projectors)
+        Vd, Vr = O.widen(gsi.bits_of(Ud), dt)[:, :ref_k], O.widen(ref_store, dt)[:, :ref_k]
+        tol = 2e-2 if dt == "bf16" else 1e-5
+        assert np.abs(Vd @ Vd.T - Vr @ Vr.T).max() <= tol
+        assert np.abs(Vd.T @ Vd - np.eye(ref_k)).max() <= tol
+        # and the image is W U for the device's stored basis
+        W64, U64 = O.widen(W, dt), O.widen(gsi.bits_of(Ud), dt)
+        pu.check_image(gsi.bits_of(Md), O.build_image(W64, U64), W64, U64, dt)
+    # the cascade needed fewer extensions than the cold start
