@@ -44,9 +44,13 @@ KERNELS = {
        "and residuals; gates)",
     1: "gsi::stream_fired<BF16> (one launch: W r of every fired map of the call)",
 }
-PROFILE_KEY = {0: "proj_stage", 1: "stream_fired"}
-TABLE_KERNELS = "gsi::table_partial<BF16> (partial c = U^T x and shares of |x|^2 of all inputs), gsi::table_gram (sums of " \
-                "the partials, shares of c^T E c), gsi::table_rows<BF16> (image rows y = M c of all maps; gates; r of fired inputs)"
+TABLE_KERNELS = [
+    ("table_partial", "gsi::table_partial<BF16> (one launch: partial c = U^T x and shares of |x|^2 of every input of the call)"),
+    ("table_gram", "gsi::table_gram (one launch: shares of c^T E c of every input; the sums of the partials are a launch "
+                   "before it that is not timed here)"),
+    ("table_rows", "gsi::table_rows<BF16> (one launch: image rows y = M c of every map of the call; the gates; r = x - U c of "
+                   "the fired inputs)"),
+]
 
 
 def log(msg: str) -> None:
@@ -82,14 +86,14 @@ class HipEvents:
         self.ev = []
 
 
-def counter_traffic(which: int, workload_tag: str):
+def counter_traffic(which: str, workload_tag: str):
     """HBM-side bytes per launch of a kernel as measured offline with the hardware counters FETCH_SIZE and
     WRITE_SIZE on this same workload (a counter run serialises the kernels and cannot be part of a timed run).
     The committed summary holds the figures and the commands; any other workload reports null."""
     path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload_tag}.md")
     try:
         for line in open(path):
-            if line.startswith(f"traffic_bytes_per_launch[{PROFILE_KEY[which]}]:"):
+            if line.startswith(f"traffic_bytes_per_launch[{which}]:"):
                 return int(line.split(":")[1].split()[0])
     except OSError:
         pass
@@ -99,7 +103,7 @@ def counter_traffic(which: int, workload_tag: str):
 class Stack:
     """The resident operands of an L-layer stack at one rank, and per-token descriptor tables."""
 
-    def __init__(self, torch, gsi, wd, W, U64, k, T, eps, p, fire, seed, flags=0):
+    def __init__(self, torch, gsi, wd, W, U64, k, T, eps, p, fire, seed, flags=0, plan=False):
         self.torch, self.gsi, self.T, self.k, self.eps = torch, gsi, T, k, eps
         L = len(W)
         inputs, maps = [], []
@@ -133,8 +137,28 @@ class Stack:
             self.tabs.append((mp, inp))
         self.ws_ptr, self.ws_n = self.st.ws.data_ptr(), self.st.ws.numel()
         self.ceps = ctypes.c_float(eps)
+        # the same calls marshalled once (gsi_stack_plan_build): device tables per token, built before anything is timed
+        self.plans = None
+        if plan:
+            self.plans = []
+            for t in range(T):
+                mp, inp = self.tabs[t]
+                nbytes = int(gsi.lib.gsi_stack_plan_bytes(self.n_mp, self.n_in))
+                mem = torch.empty(nbytes, dtype=torch.uint8, device="cuda")
+                pl = gsi.StackPlan()
+                rc = gsi.lib.gsi_stack_plan_build(mp, self.n_mp, inp, self.n_in, self.ws_ptr, self.ws_n, mem.data_ptr(),
+                                                  nbytes, ctypes.byref(pl), torch.cuda.current_stream().cuda_stream)
+                if rc:
+                    raise gsi.GsiError(rc, gsi.last_error())
+                self.plans.append((pl, mem))
+            torch.cuda.synchronize()
 
     def gated_step(self, t, s):
+        if self.plans is not None:
+            rc = self.gsi.lib.gsi_stack_plan_run(ctypes.byref(self.plans[t % self.T][0]), self.ceps, s)
+            if rc:
+                raise self.gsi.GsiError(rc, self.gsi.last_error())
+            return
         mp, inp = self.tabs[t % self.T]
         rc = self.gsi.lib.gsi_layer_stack(mp, self.n_mp, inp, self.n_in, 1, self.ceps, self.ws_ptr, self.ws_n, s)
         if rc:
@@ -235,6 +259,11 @@ def main() -> int:
                     help="single-pass: residual ratio from |x|^2 - |c|^2 + c^T E c with the cached E = U^T U - I "
                          "(GSI_INPUT_GATE_SINGLE_PASS: the basis is read once, r is formed for fired tokens only); "
                          "explicit: r = x - U c formed for every token")
+    ap.add_argument("--no-plan", action="store_true",
+                    help="call gsi_layer_stack with host descriptors every step instead of running plans that "
+                         "gsi_stack_plan_build marshalled once (single-pass gate only)")
+    ap.add_argument("--host-qr", action="store_true", help="factor the seeded Gaussians on the host (for runs under a "
+                                                          "profiler that the device QR does not survive)")
     ap.add_argument("--cpu-seconds", type=float, default=15.0, help="budget of the CPU-oracle leg (0 = skip)")
     ap.add_argument("--no-roofline", action="store_true")
     args = ap.parse_args()
@@ -265,7 +294,7 @@ def main() -> int:
         gen = wd.generator(seed + 7919 * l)
         Wl, Ul = [], []
         for gi, (_, d, maps) in enumerate(BLOCK):
-            Ul.append(wd.make_basis64(d, kmax, gen))  # nested bases: rank k uses the first k columns
+            Ul.append(wd.make_basis64(d, kmax, gen, args.host_qr))  # nested bases: rank k uses the first k columns
             Wl.append([wd.make_weight(m, d, gen) for _, m in maps])
         W.append(Wl)
         U64.append(Ul)
@@ -278,7 +307,8 @@ def main() -> int:
 
     # ---- the headline cell ------------------------------------------------------------------------------
     t0 = time.perf_counter()
-    S = Stack(torch, gsi, wd, W, U64, args.k, T, eps, p, args.fire, seed, flags)
+    use_plan = single_pass and not args.no_plan
+    S = Stack(torch, gsi, wd, W, U64, args.k, T, eps, p, args.fire, seed, flags, use_plan)
     log(f"[bench] cell k={args.k} fire={args.fire}: {S.n_in} inputs, {S.n_mp} maps, {T} tokens resident in "
         f"{time.perf_counter()-t0:.1f}s (images built in {S.image_build_s*1e3:.0f} ms)")
     mode = args.mode
@@ -384,28 +414,32 @@ def main() -> int:
                     dur[which][idx, t] = evs.elapsed_ms(0, 1) * 1e-3
                     nbytes[which][idx, t] = stage_bytes(idx, t) if which == 0 else stream_bytes(idx, t)
         evs.close()
-        kernels = {}
-        for which in (0, 1):
-            d_all, b_all = dur[which].ravel(), nbytes[which].ravel()
-            if which == 1:  # launches in which no gate fired end after reading the counts and move no weight byte
-                live = b_all > 0
-                entry = {"launches": int(live.sum()), "launches_without_fired_gate": int((~live).sum()),
-                         "unfired_launch_us": round(float(d_all[~live].mean() * 1e6), 2) if (~live).any() else None}
-                d_use, b_use = (d_all[live], b_all[live]) if live.any() else (d_all, b_all)
-            else:
-                entry = {"launches": int(d_all.size), "launches_per_step": n_launch[0],
-                         "first_launch_us": round(float(dur[0][0].mean() * 1e6), 2),
-                         "per_launch_us": [round(float(v.mean() * 1e6), 2) for v in dur[0]],
-                         "per_launch_algorithmic_MB": [round(float(v.mean() / 1e6), 2) for v in nbytes[0]]}
-                d_use, b_use = d_all, b_all
+        def entry_of(name, text, d_all, b_all, extra):
+            live = b_all > 0  # (a weight launch in which no gate fired moves no weight byte)
+            d_use, b_use = (d_all[live], b_all[live]) if live.any() else (d_all, b_all)
             ach = float(b_use.sum() / d_use.sum() / 1e9) if d_use.size else 0.0
-            entry.update({"kernel": TABLE_KERNELS if which == 0 and table_mode else KERNELS[which], "avg_launch_us": round(float(d_use.mean() * 1e6), 2),
-                          "avg_algorithmic_bytes": round(float(b_use.mean())), "achieved_GBs": round(ach, 1),
-                          "frac_of_hbm_peak": round(ach / HBM_PEAK_GBS, 4),
-                          "us_per_step_total": round(float(d_all.sum() / K * 1e6), 1)})
-            kernels[PROFILE_KEY[which]] = entry
-        dom = max((0, 1), key=lambda w: kernels[PROFILE_KEY[w]]["us_per_step_total"])
-        e = kernels[PROFILE_KEY[dom]]
+            e = {"kernel": text, "launches": int(d_use.size), "avg_launch_us": round(float(d_use.mean() * 1e6), 2),
+                 "avg_algorithmic_bytes": round(float(b_use.mean())), "achieved_GBs": round(ach, 1),
+                 "frac_of_hbm_peak": round(ach / HBM_PEAK_GBS, 4),
+                 "us_per_step_total": round(float(d_all.sum() / K * 1e6), 1)}
+            e.update(extra)
+            kernels[name] = e
+
+        kernels = {}
+        if table_mode:  # one entry per kernel of the three table launches
+            for idx, (name, text) in enumerate(TABLE_KERNELS):
+                entry_of(name, text, dur[0][idx], nbytes[0][idx], {})
+        else:
+            entry_of("proj_stage", KERNELS[0], dur[0].ravel(), nbytes[0].ravel(),
+                     {"launches_per_step": n_launch[0],
+                      "per_launch_us": [round(float(v.mean() * 1e6), 2) for v in dur[0]],
+                      "per_launch_algorithmic_MB": [round(float(v.mean() / 1e6), 2) for v in nbytes[0]]})
+        d1, b1 = dur[1].ravel(), nbytes[1].ravel()
+        entry_of("stream_fired", KERNELS[1], d1, b1,
+                 {"launches_without_fired_gate": int((b1 == 0).sum()),
+                  "unfired_launch_us": round(float(d1[b1 == 0].mean() * 1e6), 2) if (b1 == 0).any() else None})
+        dom = max(kernels, key=lambda n: kernels[n]["us_per_step_total"])
+        e = kernels[dom]
         tag = f"opt_stack_{L}layers_k{args.k}_fire{int(round(args.fire * 100))}_decode"
         roofline = {"bound": "hbm", "kernel": e["kernel"], "achieved": e["achieved_GBs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": e["frac_of_hbm_peak"], "traffic": counter_traffic(dom, tag),
@@ -456,7 +490,7 @@ def main() -> int:
     del S
     torch.cuda.empty_cache()
     for k, fire in cells:
-        Sx = Stack(torch, gsi, wd, W, U64, k, Tc, eps, p, fire, seed, flags)
+        Sx = Stack(torch, gsi, wd, W, U64, k, Tc, eps, p, fire, seed, flags, use_plan)
         n = max(Tc, min(args.steps, 2 * Tc))
         sec = timed_run(torch, Sx.gated_step, Tc, n, min(args.warmup, Tc), mode)
         c, _ = cell_numbers(Sx, sec * 1e6 / n, n)
@@ -487,6 +521,8 @@ def main() -> int:
             "layers": L, "k": args.k, "eps": eps, "decode_tokens": T, "designed_fire_rate": args.fire,
             "measured_fire_rate": head["measured_fire_rate"], "masks_match_design": head["masks_match_design"],
             "launch_mode": mode, "slow_path": "M c + W r",
+            "call": "gsi_stack_plan_run on a plan built once per trace token (gsi_stack_plan_build)" if use_plan
+                    else "gsi_layer_stack with host descriptors every step",
             "single_token_kernels": "fused" if args.fused else "separate",
             "gate": "single pass over the basis: |r|^2 = |x|^2 - |c|^2 + c^T (U^T U - I) c, r formed for fired tokens only"
                     if single_pass else "explicit residual r = x - U c for every token",

@@ -228,6 +228,27 @@ int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
 int gsi_layer_stack_static(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                            int64_t B, float eps, void* stream);
 
+/* A single-token call of gsi_layer_stack marshalled ONCE.  gsi_layer_stack turns its host descriptors into device
+ * tables on every call (a dozen small launches that read their arguments from host memory: tens of microseconds for a
+ * 32-layer stack); a decode loop that calls the same layers with the same buffers token after token can build the
+ * tables once and then only launch the kernels.
+ *   gsi_stack_plan_build validates exactly like gsi_layer_stack(..., B = 1, ...), writes the tables to `plan_mem`
+ *   (DEVICE memory of at least gsi_stack_plan_bytes(n_maps, n_inputs) bytes, 256-byte aligned, owned by the caller)
+ *   and fills `plan` (a small HOST struct, opaque).  Nothing of the method runs.  Only calls that the table launches
+ *   serve whole can be planned (GSI_ERR_SHAPE otherwise): every input external (src_map = -1), with
+ *   GSI_INPUT_GATE_SINGLE_PASS (optionally GSI_INPUT_SLOW_PATH_WX) and a 16-byte aligned gram, one dtype throughout,
+ *   shapes and alignments of the vector kernels, at most 1024 inputs and 2048 maps.
+ *   gsi_stack_plan_run enqueues the call: the same kernels on the same tables as gsi_layer_stack would use, hence the
+ *   same bits.  The plan refers to every buffer of the descriptors, to `ws` and to `plan_mem`: all must stay valid
+ *   and unmoved; `ws` is in use while a run is in flight, as with gsi_layer_stack.  eps is given per run. */
+typedef struct gsi_stack_plan {
+  uint64_t opaque[24];
+} gsi_stack_plan;
+size_t gsi_stack_plan_bytes(int32_t n_maps, int32_t n_inputs);
+int gsi_stack_plan_build(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                         void* ws, size_t ws_bytes, void* plan_mem, size_t plan_bytes, gsi_stack_plan* plan, void* stream);
+int gsi_stack_plan_run(const gsi_stack_plan* plan, float eps, void* stream);
+
 /* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition the
  * two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start and stop
  * timestamps of the dispatch of ONE of the single-token launches of the call, so hipEventElapsedTime(begin, end)

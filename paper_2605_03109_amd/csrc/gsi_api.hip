@@ -613,10 +613,29 @@ size_t gsi_layer_stack_workspace_bytes(const gsi_map_desc* maps, int32_t n_maps,
   return need;
 }
 
+// What gsi_stack_plan_build leaves in the caller's gsi_stack_plan: the launch shapes of a single-token call whose
+// descriptor tables sit in the caller's device memory.
+struct PlanRec {
+  uint32_t magic;
+  int32_t has_fired;
+  gsi::StageTableGeom sg;
+  gsi::FiredGeom fg;
+  void* stage_table;
+  void* fired_table;
+};
+static_assert(sizeof(PlanRec) <= sizeof(gsi_stack_plan), "gsi_stack_plan is too small");
+constexpr uint32_t kPlanMagic = 0x47534950u;
+// building a plan: the tables go to `dev` instead of the workspace and nothing else is launched
+struct PlanBuild {
+  PlanRec* rec;
+  char* dev;
+  int n_in_done = 0, n_maps_done = 0;
+};
+
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
                             hipEvent_t ev_begin, hipEvent_t ev_end, int which = -1, int launch_index = 0,
-                            int* n_launches = nullptr);
+                            int* n_launches = nullptr, PlanBuild* plan = nullptr);
 
 int gsi_layer_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                     int64_t B, float eps, void* ws, size_t ws_bytes, void* stream) {
@@ -748,7 +767,8 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
 
 static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs,
                             int32_t n_inputs, int64_t B, float eps, void* ws, size_t ws_bytes, void* stream,
-                            hipEvent_t ev_begin, hipEvent_t ev_end, int which, int launch_index, int* n_launches) {
+                            hipEvent_t ev_begin, hipEvent_t ev_end, int which, int launch_index, int* n_launches,
+                            PlanBuild* plan) {
   int n_stage_launches = 0, n_stream_launches = 0;  // counted for the timed variant
   if (n_maps < 0 || n_inputs < 0) return fail(GSI_ERR_SHAPE, "%s: negative count", fn);
   if (n_maps > 0) GSI_REQUIRE_PTR(maps);
@@ -870,6 +890,28 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         all_stream = false;
     }
     if (readers > 0 && all_stream) mode[i] = kVecInline;
+  }
+
+  if (plan) {  // a plan holds the table launches of ONE set of independent inputs and nothing else
+    if (B != 1 || n_inputs < 1 || n_maps < 1 || n_inputs > gsi::kMaxTabIn || n_inputs > gsi::kMaxFiredIn ||
+        n_maps > gsi::kMaxTabMaps)
+      return fail(GSI_ERR_SHAPE, "%s: a plan takes a single-token call of 1..%d inputs and 1..%d maps", fn,
+                  std::min(gsi::kMaxTabIn, gsi::kMaxFiredIn), gsi::kMaxTabMaps);
+    for (int i = 0; i < n_inputs; ++i) {
+      const gsi_input_desc& in = inputs[i];
+      if (in.src_map >= 0 || mode[i] != kVecInline || !(in.flags & GSI_INPUT_GATE_SINGLE_PASS) ||
+          (in.flags & GSI_INPUT_FUSED_KERNEL) || !aligned(in.gram, 16) || in.udtype != inputs[0].udtype)
+        return fail(GSI_ERR_SHAPE,
+                    "%s: inputs[%d] cannot be planned (needs an external X, GSI_INPUT_GATE_SINGLE_PASS with a 16-byte "
+                    "aligned gram, shapes and alignments of the vector kernels, one dtype for all inputs)", fn, i);
+    }
+    for (int j = 0; j < n_maps; ++j) {
+      const gsi_map_desc& mp = maps[j];
+      const gsi_input_desc& in = inputs[mp.input_id];
+      if (mp.wdtype != in.udtype || in.d > gsi::kMaxLinD ||
+          mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y))
+        return fail(GSI_ERR_SHAPE, "%s: maps[%d] cannot be planned", fn, j);
+    }
   }
 
   // Single token: an input that asks for the fused kernel (GSI_INPUT_FUSED_KERNEL; gsi_fused.hip) and whose
@@ -1026,7 +1068,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       const int sum_stage = (sp || nsets > 1) ? 1 : 0;
       if (sum_stage)  // the partials are added once per input: finer slabs
         for (int i : list) gsi::stage_geom(inputs[i].d, inputs[i].k, dt, ptask[i].s_rows, ptask[i].s_slabs, true);
-      if (sp && nsets > 1 && (int)list.size() <= gsi::kMaxTabIn && n_maps > 0 && n_maps <= gsi::kMaxTabMaps) {
+      if (sp && (nsets > 1 || plan) && (int)list.size() <= gsi::kMaxTabIn && n_maps > 0 && n_maps <= gsi::kMaxTabMaps) {
         // many inputs: every stage once, over a descriptor table in the workspace (three launches)
         std::vector<gsi::TabIn> tin(list.size());
         std::vector<gsi::TabMap> tmp;
@@ -1064,6 +1106,18 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         const int wt = (which == 0 && launch_index >= n_stage_launches && launch_index < n_stage_launches + 3)
                            ? launch_index - n_stage_launches : -1;
         n_stage_launches += 3;
+        if (plan) {  // the table goes to the plan's memory; its launches are the plan's to make
+          std::vector<char> host;
+          if (hipError_t e = gsi::stage_table_build(tin.data(), (int)tin.size(), tmp.data(), (int)tmp.size(), dt, host,
+                                                    plan->rec->sg);
+              e != hipSuccess)
+            return hip_fail(e, fn);
+          plan->rec->stage_table = plan->dev + gsi::fired_table_bytes(n_inputs, n_maps);
+          if (hipError_t e = gsi::upload_launch(host.data(), host.size(), plan->rec->stage_table, s); e != hipSuccess)
+            return hip_fail(e, fn);
+          plan->n_in_done += (int)tin.size();
+          continue;
+        }
         void* table = reinterpret_cast<char*>(ws) + gsi::fired_table_bytes(n_inputs, n_maps);
         if (hipError_t e = gsi::stage_table_run(table, tin.data(), (int)tin.size(), tmp.data(), (int)tmp.size(), dt, eps,
                                                 s, wt, ev_begin, ev_end);
@@ -1163,7 +1217,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           order.push_back(maps[j].input_id);
         }
       }
-      if ((n_el <= gsi::kMaxLinTasks && (int)order.size() <= gsi::kMaxTasks) || (int)order.size() > gsi::kMaxFiredIn)
+      if (((n_el <= gsi::kMaxLinTasks && (int)order.size() <= gsi::kMaxTasks) && !plan) ||
+          (int)order.size() > gsi::kMaxFiredIn || n_el == 0)
         continue;  // the launch below, with its descriptors in the kernel arguments, takes them
       std::vector<gsi::FiredIn> fin(order.size());
       std::vector<gsi::FiredMap> fmp;
@@ -1194,13 +1249,25 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         }
         f.map_end = (int)fmp.size();
       }
-      if (sib.n > 0)
+      if (sib.n > 0 && !plan)
         if (hipError_t e = gsi::decode_image_launch(sib, dt, s); e != hipSuccess) return hip_fail(e, fn);
       const size_t in_bytes = gsi::fired_table_bytes((int)fin.size(), 0);
       const size_t bytes = gsi::fired_table_bytes((int)fin.size(), (int)fmp.size());
       std::vector<char> table(bytes, 0);
       std::memcpy(table.data(), fin.data(), fin.size() * sizeof(gsi::FiredIn));
       std::memcpy(table.data() + in_bytes, fmp.data(), fmp.size() * sizeof(gsi::FiredMap));
+      if (plan) {
+        if (sib.n > 0 || plan->rec->has_fired)
+          return fail(GSI_ERR_SHAPE, "%s: the call cannot be planned (its maps do not share one weight-streaming launch)", fn);
+        if (hipError_t e = gsi::stream_fired_geom((int)fin.size(), fin.data(), fmp.data(), dt, plan->rec->fg);
+            e != hipSuccess)
+          return hip_fail(e, fn);
+        plan->rec->fired_table = plan->dev;
+        plan->rec->has_fired = 1;
+        if (hipError_t e = gsi::upload_launch(table.data(), bytes, plan->dev, s); e != hipSuccess) return hip_fail(e, fn);
+        plan->n_maps_done += (int)fmp.size();
+        continue;
+      }
       if (hipError_t e = gsi::upload_launch(table.data(), bytes, ws, s); e != hipSuccess) return hip_fail(e, fn);
       const bool timed = which == 1 && n_stream_launches == launch_index;
       ++n_stream_launches;
@@ -1258,6 +1325,51 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     if (!progressed) return fail(GSI_ERR_SHAPE, "%s: src_map dependencies form a cycle", fn);
   }
   if (n_launches) *n_launches = which == 0 ? n_stage_launches : n_stream_launches;
+  if (plan && (plan->n_in_done != n_inputs || plan->n_maps_done != n_maps))
+    return fail(GSI_ERR_SHAPE, "%s: the call cannot be planned (%d of %d inputs and %d of %d maps take the table launches)",
+                fn, plan->n_in_done, n_inputs, plan->n_maps_done, n_maps);
+  return GSI_OK;
+}
+
+size_t gsi_stack_plan_bytes(int32_t n_maps, int32_t n_inputs) {
+  if (n_maps < 1 || n_inputs < 1) return 0;
+  return gsi::fired_table_bytes(n_inputs, n_maps) + gsi::stage_table_bytes(n_inputs, n_maps);
+}
+
+int gsi_stack_plan_build(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
+                         void* ws, size_t ws_bytes, void* plan_mem, size_t plan_bytes, gsi_stack_plan* plan, void* stream) {
+  const char* fn = "gsi_stack_plan_build";
+  GSI_REQUIRE_PTR(plan);
+  GSI_REQUIRE_PTR(plan_mem);
+  std::memset(plan, 0, sizeof(*plan));
+  if (!aligned(plan_mem, 256)) return fail(GSI_ERR_ALIGN, "%s: plan_mem is not aligned to 256 bytes", fn);
+  if (plan_bytes < gsi_stack_plan_bytes(n_maps, n_inputs) || gsi_stack_plan_bytes(n_maps, n_inputs) == 0)
+    return fail(GSI_ERR_WORKSPACE, "%s: plan_mem holds %zu bytes, the plan needs %zu", fn, plan_bytes,
+                gsi_stack_plan_bytes(n_maps, n_inputs));
+  PlanRec rec;
+  std::memset(&rec, 0, sizeof(rec));
+  PlanBuild pb;
+  pb.rec = &rec;
+  pb.dev = static_cast<char*>(plan_mem);
+  if (int rc = layer_stack_impl(fn, maps, n_maps, inputs, n_inputs, 1, 0.f, ws, ws_bytes, stream, nullptr, nullptr, -1, 0,
+                                nullptr, &pb))
+    return rc;
+  rec.magic = kPlanMagic;
+  std::memcpy(plan, &rec, sizeof(rec));
+  return GSI_OK;
+}
+
+int gsi_stack_plan_run(const gsi_stack_plan* plan, float eps, void* stream) {
+  const char* fn = "gsi_stack_plan_run";
+  GSI_REQUIRE_PTR(plan);
+  PlanRec rec;
+  std::memcpy(&rec, plan, sizeof(rec));
+  if (rec.magic != kPlanMagic || !rec.stage_table || !rec.has_fired)
+    return fail(GSI_ERR_SHAPE, "%s: not a plan that gsi_stack_plan_build filled", fn);
+  if (!(eps >= 0.f)) return fail(GSI_ERR_SHAPE, "%s: eps must be a number >= 0", fn);
+  hipStream_t s = static_cast<hipStream_t>(stream);
+  if (hipError_t e = gsi::stage_table_launch(rec.stage_table, rec.sg, eps, s); e != hipSuccess) return hip_fail(e, fn);
+  if (hipError_t e = gsi::stream_fired_run(rec.fired_table, rec.fg, s); e != hipSuccess) return hip_fail(e, fn);
   return GSI_OK;
 }
 

@@ -3,6 +3,8 @@
 // Every kernel is launched over a small table of tasks passed by value in the kernel arguments, so
 // the projections of several inputs, or the linear maps of several weights, share one launch.
 #pragma once
+#include <vector>
+
 #include "gsi_internal.h"
 
 namespace gsi {
@@ -262,8 +264,18 @@ struct TabMap {          // everything an image workgroup needs, so that its loa
 constexpr int kTabImgItems = 8;   // items per image workgroup of the table launch (64 KB of M)
 constexpr int kMaxTabIn = 1024, kMaxTabMaps = 2048;  // (the first-workgroup tables are searched in LDS)
 size_t stage_table_bytes(int n_in, int n_maps);
-// ins / maps: host arrays; table: device memory of stage_table_bytes(n_in, n_maps).  which_timed: 0, 1, 2 = the
-// launch whose dispatch the events time, else -1
+struct StageTableGeom {   // what the host needs to launch over a table that is already in device memory
+  int n_in, n_maps, dtype;
+  int tp, tc, tr, ti;     // workgroups: partial projections, coefficient sums, residual slabs, image rows
+  size_t off_maps, off_p, off_r, off_c, off_i;  // byte offsets of the sections of the table
+};
+// ins / maps: host arrays -> the table's bytes (host) and its geometry
+hipError_t stage_table_build(const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, std::vector<char>& host,
+                             StageTableGeom& g);
+// which_timed: 0, 1, 2 = the launch whose dispatch the events time, else -1
+hipError_t stage_table_launch(const void* table, const StageTableGeom& g, float eps, hipStream_t s, int which_timed = -1,
+                              hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+// build + upload to `table` (device memory of stage_table_bytes(n_in, n_maps)) + launch
 hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, float eps,
                            hipStream_t s, int which_timed = -1, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
 
@@ -293,6 +305,14 @@ hipError_t upload_launch(const void* src, size_t bytes, void* dst, hipStream_t s
 // table: n_in FiredIn followed (at fired_table_bytes(n_in, 0)) by the FiredMap of all inputs, in device memory
 hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
                                int wdtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+struct FiredGeom {        // launch shape of the weight-streaming kernel over a table in device memory
+  int n_in, wdtype, tail;
+  unsigned grid;
+  size_t smem;
+};
+hipError_t stream_fired_geom(int n_in, const FiredIn* host_ins, const FiredMap* host_maps, int wdtype, FiredGeom& g);
+hipError_t stream_fired_run(const void* table, const FiredGeom& g, hipStream_t s, hipEvent_t e0 = nullptr,
+                            hipEvent_t e1 = nullptr);
 
 // single-token persistent kernel (gsi_stream.hip)
 size_t stream_smem_bytes(const LinBatch& lb);

@@ -689,23 +689,22 @@ size_t stage_table_bytes(int n_in, int n_maps) {
          3 * align_up((size_t)(n_in + 1) * sizeof(int), 256) + align_up((size_t)(n_maps + 1) * sizeof(int), 256);
 }
 
-hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, float eps,
-                           hipStream_t s, int which_timed, hipEvent_t e0, hipEvent_t e1) {
-  if (n_in <= 0) return hipSuccess;
-  if (n_in > kMaxTabIn || n_maps > kMaxTabMaps) return hipErrorInvalidValue;
-  const size_t off_maps = align_up((size_t)n_in * sizeof(TabIn), 256);
-  const size_t off_p = off_maps + align_up((size_t)n_maps * sizeof(TabMap), 256);
-  const size_t off_r = off_p + align_up((size_t)(n_in + 1) * sizeof(int), 256);
-  const size_t off_c = off_r + align_up((size_t)(n_in + 1) * sizeof(int), 256);
-  const size_t off_i = off_c + align_up((size_t)(n_in + 1) * sizeof(int), 256);
-  const size_t bytes = stage_table_bytes(n_in, n_maps);
-  std::vector<char> host(bytes, 0);
+hipError_t stage_table_build(const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, std::vector<char>& host,
+                             StageTableGeom& g) {
+  if (n_in <= 0 || n_in > kMaxTabIn || n_maps < 0 || n_maps > kMaxTabMaps) return hipErrorInvalidValue;
+  g.n_in = n_in; g.n_maps = n_maps; g.dtype = dtype;
+  g.off_maps = align_up((size_t)n_in * sizeof(TabIn), 256);
+  g.off_p = g.off_maps + align_up((size_t)n_maps * sizeof(TabMap), 256);
+  g.off_r = g.off_p + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  g.off_c = g.off_r + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  g.off_i = g.off_c + align_up((size_t)(n_in + 1) * sizeof(int), 256);
+  host.assign(stage_table_bytes(n_in, n_maps), 0);
   std::memcpy(host.data(), ins, (size_t)n_in * sizeof(TabIn));
-  if (n_maps) std::memcpy(host.data() + off_maps, maps, (size_t)n_maps * sizeof(TabMap));
-  int* pb = reinterpret_cast<int*>(host.data() + off_p);
-  int* rb = reinterpret_cast<int*>(host.data() + off_r);
-  int* cb = reinterpret_cast<int*>(host.data() + off_c);
-  int* ib = reinterpret_cast<int*>(host.data() + off_i);
+  if (n_maps) std::memcpy(host.data() + g.off_maps, maps, (size_t)n_maps * sizeof(TabMap));
+  int* pb = reinterpret_cast<int*>(host.data() + g.off_p);
+  int* rb = reinterpret_cast<int*>(host.data() + g.off_r);
+  int* cb = reinterpret_cast<int*>(host.data() + g.off_c);
+  int* ib = reinterpret_cast<int*>(host.data() + g.off_i);
   int64_t tp = 0, tr = 0, tc = 0, ti = 0;
   for (int i = 0; i < n_in; ++i) {
     pb[i] = (int)tp;
@@ -721,40 +720,56 @@ hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap
   }
   pb[n_in] = (int)tp; rb[n_in] = (int)tr; cb[n_in] = (int)tc; ib[n_maps] = (int)ti;
   if (tp >= (1 << 30) || tr + ti >= (1 << 30)) return hipErrorInvalidValue;
-  if (hipError_t e = upload_launch(host.data(), bytes, table, s); e != hipSuccess) return e;
+  g.tp = (int)tp; g.tc = (int)tc; g.tr = (int)tr; g.ti = (int)ti;
+  return hipSuccess;
+}
+
+hipError_t stage_table_launch(const void* table, const StageTableGeom& g, float eps, hipStream_t s, int which_timed,
+                              hipEvent_t e0, hipEvent_t e1) {
   const char* base = static_cast<const char*>(table);
   const TabIn* d_ins = reinterpret_cast<const TabIn*>(base);
-  const TabMap* d_maps = reinterpret_cast<const TabMap*>(base + off_maps);
-  const int* d_pb = reinterpret_cast<const int*>(base + off_p);
-  const int* d_rb = reinterpret_cast<const int*>(base + off_r);
-  const int* d_cb = reinterpret_cast<const int*>(base + off_c);
-  const int* d_ib = reinterpret_cast<const int*>(base + off_i);
-  auto ev = [&](int w, hipEvent_t e) { return which_timed == w ? e : nullptr; };
+  const TabMap* d_maps = reinterpret_cast<const TabMap*>(base + g.off_maps);
+  const int* d_pb = reinterpret_cast<const int*>(base + g.off_p);
+  const int* d_rb = reinterpret_cast<const int*>(base + g.off_r);
+  const int* d_cb = reinterpret_cast<const int*>(base + g.off_c);
+  const int* d_ib = reinterpret_cast<const int*>(base + g.off_i);
+  const int n_in = g.n_in, n_maps = g.n_maps;
+  auto ev = [&](int w) { return which_timed == w && e0 && e1; };
   // 1. partial projections
-  if (dtype == GSI_BF16) {
-    if (ev(0, e0)) hipExtLaunchKernelGGL((table_partial<BF16>), dim3((unsigned)tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
-    else table_partial<BF16><<<(unsigned)tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+  if (g.dtype == GSI_BF16) {
+    if (ev(0)) hipExtLaunchKernelGGL((table_partial<BF16>), dim3((unsigned)g.tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
+    else table_partial<BF16><<<(unsigned)g.tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
   } else {
-    if (ev(0, e0)) hipExtLaunchKernelGGL((table_partial<F32>), dim3((unsigned)tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
-    else table_partial<F32><<<(unsigned)tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+    if (ev(0)) hipExtLaunchKernelGGL((table_partial<F32>), dim3((unsigned)g.tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
+    else table_partial<F32><<<(unsigned)g.tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // 2. coefficient sums, then the shares of c^T E c
-  table_cred<<<(unsigned)tc, kBlock, 0, s>>>(d_ins, d_cb, n_in);
+  table_cred<<<(unsigned)g.tc, kBlock, 0, s>>>(d_ins, d_cb, n_in);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  if (ev(1, e0)) hipExtLaunchKernelGGL(table_gram, dim3((unsigned)n_in * kGramBlocks), dim3(kBlock), 0, s, e0, e1, 0, d_ins);
+  if (ev(1)) hipExtLaunchKernelGGL(table_gram, dim3((unsigned)n_in * kGramBlocks), dim3(kBlock), 0, s, e0, e1, 0, d_ins);
   else table_gram<<<(unsigned)n_in * kGramBlocks, kBlock, 0, s>>>(d_ins);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  // 3. image rows, gates, residuals of fired inputs
-  const unsigned grid = (unsigned)(ti + tr);
-  if (dtype == GSI_BF16) {
-    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
-    else table_rows<BF16><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
+  // 3. gates, residuals of fired inputs, image rows
+  const unsigned grid = (unsigned)(g.ti + g.tr);
+  if (g.dtype == GSI_BF16) {
+    if (ev(2)) hipExtLaunchKernelGGL((table_rows<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
+    else table_rows<BF16><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
   } else {
-    if (ev(2, e0)) hipExtLaunchKernelGGL((table_rows<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
-    else table_rows<F32><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, (int)tr, eps);
+    if (ev(2)) hipExtLaunchKernelGGL((table_rows<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
+    else table_rows<F32><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
   }
   return hipGetLastError();
+}
+
+hipError_t stage_table_run(void* table, const TabIn* ins, int n_in, const TabMap* maps, int n_maps, int dtype, float eps,
+                           hipStream_t s, int which_timed, hipEvent_t e0, hipEvent_t e1) {
+  if (n_in <= 0) return hipSuccess;
+  std::vector<char> host;
+  StageTableGeom g;
+  if (hipError_t e = stage_table_build(ins, n_in, maps, n_maps, dtype, host, g); e != hipSuccess) return e;
+  if (hipError_t e = upload_launch(host.data(), host.size(), table, s); e != hipSuccess) return e;
+  return stage_table_launch(table, g, eps, s, which_timed, e0, e1);
 }
 
 }  // namespace gsi

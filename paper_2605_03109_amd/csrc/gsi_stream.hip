@@ -238,10 +238,8 @@ static hipError_t launch_fired(const FiredIn* ins, const FiredMap* maps, int n_i
   return hipGetLastError();
 }
 
-hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
-                               int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
-  if (n_in <= 0) return hipSuccess;
-  if (n_in > kMaxFiredIn) return hipErrorInvalidValue;
+hipError_t stream_fired_geom(int n_in, const FiredIn* host_ins, const FiredMap* host_maps, int wdtype, FiredGeom& g) {
+  if (n_in <= 0 || n_in > kMaxFiredIn) return hipErrorInvalidValue;
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   int64_t rows = 0;
   size_t maxd = 0;
@@ -255,14 +253,26 @@ hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_
   int64_t grid = (int64_t)kWgsPerCu * num_cus();
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
+  g.n_in = n_in; g.wdtype = wdtype; g.tail = tail ? 1 : 0; g.grid = (unsigned)grid; g.smem = maxd * sizeof(float);
+  return hipSuccess;
+}
+
+hipError_t stream_fired_run(const void* table, const FiredGeom& g, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const FiredIn* ins = static_cast<const FiredIn*>(table);
-  const FiredMap* maps = reinterpret_cast<const FiredMap*>(static_cast<const char*>(table) + fired_table_bytes(n_in, 0));
-  const size_t smem = maxd * sizeof(float);
-  if (wdtype == GSI_BF16)
-    return tail ? launch_fired<BF16, true>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1)
-                : launch_fired<BF16, false>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1);
-  return tail ? launch_fired<F32, true>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1)
-              : launch_fired<F32, false>(ins, maps, n_in, (unsigned)grid, smem, s, e0, e1);
+  const FiredMap* maps = reinterpret_cast<const FiredMap*>(static_cast<const char*>(table) + fired_table_bytes(g.n_in, 0));
+  if (g.wdtype == GSI_BF16)
+    return g.tail ? launch_fired<BF16, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
+                  : launch_fired<BF16, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+  return g.tail ? launch_fired<F32, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
+                : launch_fired<F32, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+}
+
+hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
+                               int wdtype, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
+  if (n_in <= 0) return hipSuccess;
+  FiredGeom g;
+  if (hipError_t e = stream_fired_geom(n_in, host_ins, host_maps, wdtype, g); e != hipSuccess) return e;
+  return stream_fired_run(table, g, s, e0, e1);
 }
 
 size_t stream_smem_bytes(const LinBatch& lb) {

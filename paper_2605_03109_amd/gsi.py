@@ -30,6 +30,7 @@ EXPORTS = (
     "gsi_build_image", "gsi_build_gram", "gsi_extend_basis", "gsi_extend_basis_workspace_bytes", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
     "gsi_layer_stack",
     "gsi_layer_stack_static", "gsi_layer_stack_timed", "gsi_dense_stack",
+    "gsi_stack_plan_bytes", "gsi_stack_plan_build", "gsi_stack_plan_run",
     "gsi_workspace_bytes", "gsi_layer_stack_workspace_bytes", "gsi_dense_stack_workspace_bytes", "gsi_last_error",
     "gsi_fused_timeouts",
     "gsi_version",
@@ -57,6 +58,10 @@ class InputDesc(ctypes.Structure):
 
 class ExtendMap(ctypes.Structure):
     _fields_ = [("W", ctypes.c_void_p), ("M", ctypes.c_void_p), ("m", ctypes.c_int64)]
+
+
+class StackPlan(ctypes.Structure):
+    _fields_ = [("opaque", ctypes.c_uint64 * 24)]
 
 
 class MapDesc(ctypes.Structure):
@@ -94,6 +99,13 @@ def _load() -> ctypes.CDLL:
     lib.gsi_layer_stack_static.restype = ctypes.c_int
     lib.gsi_layer_stack_timed.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                           ctypes.c_int32, i64, f32, vp, sz, vp, i32, i32, vp, vp]
+    lib.gsi_stack_plan_bytes.argtypes = [ctypes.c_int32, ctypes.c_int32]
+    lib.gsi_stack_plan_bytes.restype = sz
+    lib.gsi_stack_plan_build.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc), ctypes.c_int32,
+                                         vp, sz, vp, sz, ctypes.POINTER(StackPlan), vp]
+    lib.gsi_stack_plan_build.restype = ctypes.c_int
+    lib.gsi_stack_plan_run.argtypes = [ctypes.POINTER(StackPlan), f32, vp]
+    lib.gsi_stack_plan_run.restype = ctypes.c_int
     lib.gsi_dense_stack.argtypes = [ctypes.POINTER(MapDesc), ctypes.c_int32, ctypes.POINTER(InputDesc),
                                     ctypes.c_int32, i64, vp, sz, vp]
     lib.gsi_workspace_bytes.argtypes = [i32, i64, i64, i64, i64]
@@ -390,6 +402,19 @@ class LayerStack:
         _check(lib.gsi_layer_stack_timed(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.cur_B,
                                          self.eps, self.ws.data_ptr(), self.ws.numel(), _stream(stream), which, index,
                                          ev_begin, ev_end))
+
+    def build_plan(self, stream=None):
+        """Marshal the current descriptor tables (as refresh() left them, one token per call) once: returns
+        (plan, plan_mem); plan_mem and self.ws must be kept alive while the plan is used."""
+        nbytes = int(lib.gsi_stack_plan_bytes(len(self.maps_t), len(self.inputs_t)))
+        mem = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=self.ws.device)
+        plan = StackPlan()
+        _check(lib.gsi_stack_plan_build(self._mp, len(self.maps_t), self._in, len(self.inputs_t), self.ws.data_ptr(),
+                                        self.ws.numel(), mem.data_ptr(), mem.numel(), ctypes.byref(plan), _stream(stream)))
+        return plan, mem
+
+    def run_plan(self, plan, stream=None) -> None:
+        _check(lib.gsi_stack_plan_run(ctypes.byref(plan), self.eps, _stream(stream)))
 
     def run_dense(self, stream=None) -> None:
         """The dense baseline Y = W X over the same descriptor tables (one launch for all maps)."""

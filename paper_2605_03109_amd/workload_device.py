@@ -29,13 +29,15 @@ def make_weight(m: int, d: int, gen: torch.Generator) -> torch.Tensor:
     return w.to(torch.bfloat16)
 
 
-def make_basis64(d: int, k: int, gen: torch.Generator) -> torch.Tensor:
+def make_basis64(d: int, k: int, gen: torch.Generator, host_qr: bool = False) -> torch.Tensor:
     """Orthonormal U[d, k] in fp64: Q of a seeded Gaussian, columns sign-fixed.  A leading block U[:, :k']
     of the result is itself an orthonormal basis (nested bases across ranks)."""
     g = torch.randn((d, k), generator=gen, device=gen.device, dtype=torch.float64)
     try:
+        if host_qr:
+            raise RuntimeError("host factorisation asked for")
         q, r = torch.linalg.qr(g)
-    except RuntimeError:  # no device QR in this build: factor on the host
+    except RuntimeError:  # no device QR in this build, or the caller wants the host's: factor on the host
         q, r = torch.linalg.qr(g.cpu())
         q, r = q.to(g.device), r.to(g.device)
     s = torch.sign(torch.diagonal(r))

@@ -14,7 +14,15 @@ def test_more_than_one_gpu_is_refused_with_a_message():
 
 
 def test_profile_traffic_figure_is_readable():
-    """bench.py takes the counter-measured HBM traffic of the dominant kernel from the committed profile summary."""
-    path = os.path.join(ROOT, "profiles", "hbm_traffic_stream_rows_gptj_block_k256_decode.md")
-    lines = [ln for ln in open(path) if ln.startswith("traffic_bytes_per_fired_launch:")]
-    assert len(lines) == 1 and int(lines[0].split(":")[1]) > 100_000_000
+    """bench.py takes the counter-measured HBM traffic of the dominant kernel from the committed profile summary of
+    its default workload; any other workload reports null."""
+    sys.path.insert(0, ROOT)
+    import bench
+
+    tag = "opt_stack_32layers_k256_fire5_decode"
+    assert os.path.exists(os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}.md"))
+    for kernel in ("table_rows", "table_partial", "stream_fired"):
+        v = bench.counter_traffic(kernel, tag)
+        assert isinstance(v, int) and v > 400_000_000, (kernel, v)
+    assert bench.counter_traffic("table_rows", "opt_stack_32layers_k64_fire5_decode") is None
+    assert bench.counter_traffic("no_such_kernel", tag) is None

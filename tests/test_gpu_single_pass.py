@@ -231,3 +231,58 @@ def test_single_pass_gptj_block_full_size(gsi, pu, k):
                 e, es = pu.check_outputs(st.maps_t[j]["Y"], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
                 say(f"    map {name}: rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
         del og
+
+
+@pytest.mark.parametrize("wx", [False, True])
+def test_stack_plan_equals_layer_stack(gsi, pu, wx):
+    """gsi_stack_plan_build + gsi_stack_plan_run give the bits of gsi_layer_stack on the same descriptors: five blocks
+    (table launches either way) and a single block (which gsi_layer_stack runs through the 16-input launches, so only
+    decisions are equal and the rest agrees to rounding); a call that cannot be planned is refused."""
+    T = 5
+    flags = gsi.INPUT_GATE_SINGLE_PASS | (gsi.INPUT_SLOW_PATH_WX if wx else 0)
+    for L in (5, 1):
+        blocks = [wl.transformer_block(f"p{l}", d=512, ffn=2048, k=64, T=T, fire_rate=0.4, p=1.5, seed=4400 + l) for l in range(L)]
+        eps = blocks[0].eps
+        inputs, maps = [], []
+        for w in blocks:
+            _, bi, bm, _ = _stack(gsi, pu, w, flags)
+            base = len(inputs)
+            inputs += bi
+            maps += [dict(m, input_id=m["input_id"] + base) for m in bm]
+        say(f"case plan: {len(inputs)} inputs / {len(maps)} maps, wx={wx}")
+        ref = gsi.LayerStack(inputs, maps, T, eps)
+        _run_tokens(ref, T)
+        st = gsi.LayerStack(inputs, maps, T, eps)
+        st.refresh(token_offset=0, B=1)
+        st.ws.fill_(0xFF)
+        plans = []
+        for t in range(T):
+            st.refresh(token_offset=t, B=1)
+            plans.append(st.build_plan())
+        torch.cuda.synchronize()
+        for rep in range(2):
+            for t in range(T):
+                st.run_plan(plans[t][0])
+        torch.cuda.synchronize()
+        exact = L > 4
+        nf = 0
+        for a, b in zip(st.inputs_t, ref.inputs_t):
+            assert torch.equal(a["mask"], b["mask"])
+            nf += int(b["mask"].sum())
+            for key in ("C", "rnorm", "xnorm", "R"):
+                if exact:
+                    assert torch.equal(a[key], b[key]), key
+                else:
+                    assert torch.allclose(a[key], b[key], rtol=0, atol=3e-6 * float(b["xnorm"].max())), key
+        assert nf > 0
+        for a, b in zip(st.maps_t, ref.maps_t):
+            if exact:
+                assert torch.equal(a["Y"], b["Y"])
+            else:
+                assert torch.allclose(a["Y"], b["Y"], rtol=0, atol=1e-5 * float(b["Y"].abs().max()))
+    # an input without the single-pass gate cannot be planned
+    bad = gsi.LayerStack([dict(inputs[0], flags=0)] + inputs[1:], maps, T, eps)
+    bad.refresh(token_offset=0, B=1)
+    with pytest.raises(gsi.GsiError) as ei:
+        bad.build_plan()
+    assert ei.value.code == gsi.GSI_ERR_SHAPE and "planned" in str(ei.value)
