@@ -266,6 +266,7 @@ constexpr int kMaxTabIn = 1024, kMaxTabMaps = 2048;  // (the first-workgroup tab
 size_t stage_table_bytes(int n_in, int n_maps);
 struct StageTableGeom {   // what the host needs to launch over a table that is already in device memory
   int n_in, n_maps, dtype;
+  int nt;                 // bases and images together exceed kStreamBytes: non-temporal loads
   int tp, tc, tr, ti;     // workgroups: partial projections, coefficient sums, residual slabs, image rows
   size_t off_maps, off_p, off_r, off_c, off_i;  // byte offsets of the sections of the table
 };
@@ -305,8 +306,12 @@ hipError_t upload_launch(const void* src, size_t bytes, void* dst, hipStream_t s
 // table: n_in FiredIn followed (at fired_table_bytes(n_in, 0)) by the FiredMap of all inputs, in device memory
 hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
                                int wdtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);
+// bytes one launch (or one step's fast path) must stream before its loads go non-temporal: twice the 256 MB
+// memory-side cache, so that operands a caller walks again within a step or two keep their cache hits
+constexpr size_t kStreamBytes = (size_t)512 << 20;
 struct FiredGeom {        // launch shape of the weight-streaming kernel over a table in device memory
   int n_in, wdtype, tail;
+  int nt;                 // non-temporal weight loads
   unsigned grid;
   size_t smem;
 };

@@ -73,6 +73,14 @@ struct FP8 {
   }
 };
 
+// 16 bytes that are read once and not again soon (a streamed operand): a non-temporal load, which the caches
+// may drop first
+__device__ __forceinline__ uint4 load_stream16(const void* p) {
+  typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+  const u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+
 // activation element of runtime dtype (0 = fp32, 1 = bf16)
 __device__ __forceinline__ float load_act(const void* p, int dtype, int64_t i) {
   return dtype == 0 ? reinterpret_cast<const float*>(p)[i]

@@ -38,7 +38,9 @@ __device__ __forceinline__ float sum_partials(const float* __restrict__ pc, int6
   return s;
 }
 
-template <class T, int ITEMS = kImgItemsPerBlock>
+// STREAM: the image is larger than the caches keep from one step to the next (many maps in one launch): its rows
+// are loaded non-temporally
+template <class T, int ITEMS = kImgItemsPerBlock, bool STREAM = false>
 __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block, float* __restrict__ cs) {
   constexpr int kPerWave = ITEMS / 4;
   constexpr int V = T::kVec;
@@ -60,7 +62,8 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
 #pragma unroll
     for (int u = 0; u < kImgLoads; ++u) {
       const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
-      raw[it][u] = *reinterpret_cast<const uint4*>(M + (int64_t)(row < m ? row : m - 1) * k);
+      const S* src = M + (int64_t)(row < m ? row : m - 1) * k;
+      raw[it][u] = STREAM ? load_stream16(src) : *reinterpret_cast<const uint4*>(src);
     }
   for (int j = threadIdx.x; j < k; j += 256) cs[j] = t.part_c ? sum_partials(t.part_c + j, k, t.a_slabs) : t.C[j];
   __syncthreads();
@@ -90,10 +93,10 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
 
 // T: storage of an image in the weights' dtype; a task with row scales holds E4M3 codes instead (Section 7,
 // "Combination with quantization").  The choice is uniform over the workgroup.
-template <class T, int ITEMS = kImgItemsPerBlock>
+template <class T, int ITEMS = kImgItemsPerBlock, bool STREAM = false>
 __device__ __forceinline__ void image_block(const ImgTask& t, int local_block, float* __restrict__ cs) {
-  if (t.scale) image_block_as<FP8, ITEMS>(t, local_block, cs);
-  else image_block_as<T, ITEMS>(t, local_block, cs);
+  if (t.scale) image_block_as<FP8, ITEMS, STREAM>(t, local_block, cs);
+  else image_block_as<T, ITEMS, STREAM>(t, local_block, cs);
 }
 
 // workgroups a map needs in an image launch

@@ -83,7 +83,8 @@ __device__ __forceinline__ void publish_gate(const StageGate& g, float rn, float
   g.n_fired[0] = f ? 1 : 0;
 }
 
-template <class T>
+// STREAM: the first two batches of U are loaded non-temporally (a launch over many inputs: nothing is read again soon)
+template <class T, bool STREAM = false>
 __device__ __forceinline__ void partial_block(const StagePart& p, int slab, float* __restrict__ red,
                                               float* __restrict__ xs, double* __restrict__ dsh) {
   constexpr int V = T::kVec;
@@ -108,11 +109,17 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
   const bool first = i + 7 * rps < rows, second = i + 15 * rps < rows;
   if (first) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) raw[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + q * rps) * k);
+    for (int q = 0; q < 8; ++q) {
+      const S* src = U + (int64_t)(i + q * rps) * k;
+      raw[q] = STREAM ? load_stream16(src) : *reinterpret_cast<const uint4*>(src);
+    }
   }
   if (second) {
 #pragma unroll
-    for (int q = 0; q < 8; ++q) raw2[q] = *reinterpret_cast<const uint4*>(U + (int64_t)(i + (8 + q) * rps) * k);
+    for (int q = 0; q < 8; ++q) {
+      const S* src = U + (int64_t)(i + (8 + q) * rps) * k;
+      raw2[q] = STREAM ? load_stream16(src) : *reinterpret_cast<const uint4*>(src);
+    }
   }
   double x2 = 0.0;  // this thread's share of the slab's |x|^2 (single-pass gate)
   for (int r = threadIdx.x; r < rows; r += kBlock) {
@@ -475,7 +482,7 @@ __device__ __forceinline__ int find_in_table(const int* __restrict__ begin, int 
   return __builtin_amdgcn_readfirstlane(lo);
 }
 
-template <class T>
+template <class T, bool NT>
 __global__ __launch_bounds__(kBlock) void table_partial(const TabIn* __restrict__ ins, const int* __restrict__ pbegin,
                                                         int n_in) {
   __shared__ __align__(16) float lds[kBlock * 8];
@@ -489,7 +496,7 @@ __global__ __launch_bounds__(kBlock) void table_partial(const TabIn* __restrict_
   p.U = in.U; p.X = in.X; p.part_c = in.part_c; p.d = in.d; p.k_rows = in.k_rows;
   p.slabs_x = (in.slabs & 0xffff) | (((in.r_rows_x >> 16) & 0xf) << 16);
   p.x2_off = in.gw_off;
-  partial_block<T>(p, b - tab[i], lds, xs, dsh);
+  partial_block<T, NT>(p, b - tab[i], lds, xs, dsh);
 }
 
 // c = the partials added in slab order: a workgroup per (input, 64 columns); its four waves take every fourth slab
@@ -550,7 +557,7 @@ __global__ __launch_bounds__(kBlock) void table_gram(const TabIn* __restrict__ i
 
 // the residual workgroups first (they evaluate the gate, publish it, and form r only for an input that fired: few
 // and slow, so they start early and run beside the image stream), then the image rows of every map
-template <class T>
+template <class T, bool NT>
 __global__ __launch_bounds__(kBlock) void table_rows(const TabIn* __restrict__ ins, const TabMap* __restrict__ maps,
                                                      const int* __restrict__ ibegin, const int* __restrict__ rbegin,
                                                      int n_in, int n_maps, int r_total, float eps) {
@@ -570,7 +577,7 @@ __global__ __launch_bounds__(kBlock) void table_rows(const TabIn* __restrict__ i
     ImgTask t;
     t.M = mp.M; t.Y = mp.Y; t.part_c = nullptr; t.C = mp.C; t.scale = mp.scale;
     t.m = mp.m; t.k = mp.k; t.a_slabs = 0; t.blk_begin = tab[j];
-    image_block<T, kTabImgItems>(t, b - t.blk_begin, lds);
+    image_block<T, kTabImgItems, NT>(t, b - t.blk_begin, lds);
     return;
   }
   const int i = find_in_table(rbegin, n_in, b, tab);
@@ -706,7 +713,9 @@ hipError_t stage_table_build(const TabIn* ins, int n_in, const TabMap* maps, int
   int* cb = reinterpret_cast<int*>(host.data() + g.off_c);
   int* ib = reinterpret_cast<int*>(host.data() + g.off_i);
   int64_t tp = 0, tr = 0, tc = 0, ti = 0;
+  size_t bytes = 0;  // bases and images of the call
   for (int i = 0; i < n_in; ++i) {
+    bytes += (size_t)ins[i].d * (ins[i].k_rows & 0xffff) * elem_size(dtype);
     pb[i] = (int)tp;
     rb[i] = (int)tr;
     cb[i] = (int)tc;
@@ -717,7 +726,9 @@ hipError_t stage_table_build(const TabIn* ins, int n_in, const TabMap* maps, int
   for (int j = 0; j < n_maps; ++j) {
     ib[j] = (int)ti;
     ti += image_blocks(maps[j].m, maps[j].k, dtype, maps[j].scale != nullptr, kTabImgItems);
+    bytes += (size_t)maps[j].m * maps[j].k * (maps[j].scale ? 1 : elem_size(dtype));
   }
+  g.nt = bytes >= kStreamBytes ? 1 : 0;
   pb[n_in] = (int)tp; rb[n_in] = (int)tr; cb[n_in] = (int)tc; ib[n_maps] = (int)ti;
   if (tp >= (1 << 30) || tr + ti >= (1 << 30)) return hipErrorInvalidValue;
   g.tp = (int)tp; g.tc = (int)tc; g.tr = (int)tr; g.ti = (int)ti;
@@ -736,12 +747,16 @@ hipError_t stage_table_launch(const void* table, const StageTableGeom& g, float 
   const int n_in = g.n_in, n_maps = g.n_maps;
   auto ev = [&](int w) { return which_timed == w && e0 && e1; };
   // 1. partial projections
+  auto partial = [&](auto kern) {
+    if (ev(0)) hipExtLaunchKernelGGL(kern, dim3((unsigned)g.tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
+    else kern<<<(unsigned)g.tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+  };
   if (g.dtype == GSI_BF16) {
-    if (ev(0)) hipExtLaunchKernelGGL((table_partial<BF16>), dim3((unsigned)g.tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
-    else table_partial<BF16><<<(unsigned)g.tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+    if (g.nt) partial(table_partial<BF16, true>);
+    else partial(table_partial<BF16, false>);
   } else {
-    if (ev(0)) hipExtLaunchKernelGGL((table_partial<F32>), dim3((unsigned)g.tp), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_pb, n_in);
-    else table_partial<F32><<<(unsigned)g.tp, kBlock, 0, s>>>(d_ins, d_pb, n_in);
+    if (g.nt) partial(table_partial<F32, true>);
+    else partial(table_partial<F32, false>);
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // 2. coefficient sums, then the shares of c^T E c
@@ -752,12 +767,16 @@ hipError_t stage_table_launch(const void* table, const StageTableGeom& g, float 
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // 3. gates, residuals of fired inputs, image rows
   const unsigned grid = (unsigned)(g.ti + g.tr);
+  auto rows = [&](auto kern) {
+    if (ev(2)) hipExtLaunchKernelGGL(kern, dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
+    else kern<<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
+  };
   if (g.dtype == GSI_BF16) {
-    if (ev(2)) hipExtLaunchKernelGGL((table_rows<BF16>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
-    else table_rows<BF16><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
+    if (g.nt) rows(table_rows<BF16, true>);
+    else rows(table_rows<BF16, false>);
   } else {
-    if (ev(2)) hipExtLaunchKernelGGL((table_rows<F32>), dim3(grid), dim3(kBlock), 0, s, e0, e1, 0, d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
-    else table_rows<F32><<<grid, kBlock, 0, s>>>(d_ins, d_maps, d_ib, d_rb, n_in, n_maps, g.tr, eps);
+    if (g.nt) rows(table_rows<F32, true>);
+    else rows(table_rows<F32, false>);
   }
   return hipGetLastError();
 }

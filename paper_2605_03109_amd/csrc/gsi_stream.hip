@@ -26,7 +26,7 @@ constexpr int kBlock = 512;  // waves of a workgroup share one staged activation
 constexpr int kWaves = kBlock / kWave;
 constexpr int kWgsPerCu = 2;  // persistent grid: workgroups per CU
 
-template <class T, bool DENSE, bool TAIL>
+template <class T, bool DENSE, bool TAIL, bool NT>
 __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
       const LinTask& t = lb.t[ti];
       if (t.group != gi) continue;  // uniform
       const int m = t.m;
-      stream_map_rows<T, TAIL, false>(reinterpret_cast<const S*>(t.W), t.Y, m, d, xs, whole, first, GW, lane);
+      stream_map_rows<T, TAIL, false, NT>(reinterpret_cast<const S*>(t.W), t.Y, m, d, xs, whole, first, GW, lane);
       // continue the deal: the next map starts with the wave after the one that took this map's last row
       first = (first - m % GW + GW) % GW;
     }
@@ -99,7 +99,7 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
 }
 
 // The same streaming for ALL fired inputs of a call, descriptors in device memory.
-template <class T, bool TAIL>
+template <class T, bool TAIL, bool NT>
 __global__ __launch_bounds__(kBlock) void stream_fired(const FiredIn* __restrict__ ins, const FiredMap* __restrict__ maps,
                                                        int n_in) {
   using S = typename T::storage;
@@ -156,7 +156,7 @@ __global__ __launch_bounds__(kBlock) void stream_fired(const FiredIn* __restrict
     for (int j = mb; j < me; ++j) {
       const FiredMap* mp = maps + j;
       const int m = __builtin_amdgcn_readfirstlane(mp->m);
-      stream_map_rows<T, TAIL, false>(reinterpret_cast<const S*>(mp->W), mp->Y, m, d, xs, whole, first, GW, lane);
+      stream_map_rows<T, TAIL, false, NT>(reinterpret_cast<const S*>(mp->W), mp->Y, m, d, xs, whole, first, GW, lane);
       first = (first - m % GW + GW) % GW;  // the next map starts with the wave after this map's last row
     }
   }
@@ -181,26 +181,32 @@ int num_cus() {
   return n;
 }
 
-template <class T, bool DENSE, bool TAIL>
+template <class T, bool DENSE, bool TAIL, bool NT>
 hipError_t launch_one(const LinBatch& lb, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   static const hipError_t attr =  // the kernel may use more than the default 64 KB of dynamic LDS
-      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<T, DENSE, TAIL>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<T, DENSE, TAIL, NT>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (kMaxLinD + kMaxSumK) * (int)sizeof(float));
   if (attr != hipSuccess) return attr;
   if (e0 && e1) {  // the events take the dispatch's own start and stop timestamps
-    hipExtLaunchKernelGGL((stream_rows<T, DENSE, TAIL>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, lb);
+    hipExtLaunchKernelGGL((stream_rows<T, DENSE, TAIL, NT>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, lb);
   } else {
-    stream_rows<T, DENSE, TAIL><<<grid, kBlock, smem, s>>>(lb);
+    stream_rows<T, DENSE, TAIL, NT><<<grid, kBlock, smem, s>>>(lb);
   }
   return hipGetLastError();
 }
 
-template <class T>
-hipError_t launch_dtype(const LinBatch& lb, bool tail, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0,
+template <class T, bool DENSE>
+hipError_t launch_shape(const LinBatch& lb, bool tail, bool nt, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0,
                         hipEvent_t e1) {
-  if (lb.dense)
-    return tail ? launch_one<T, true, true>(lb, grid, smem, s, e0, e1) : launch_one<T, true, false>(lb, grid, smem, s, e0, e1);
-  return tail ? launch_one<T, false, true>(lb, grid, smem, s, e0, e1) : launch_one<T, false, false>(lb, grid, smem, s, e0, e1);
+  if (tail) return nt ? launch_one<T, DENSE, true, true>(lb, grid, smem, s, e0, e1) : launch_one<T, DENSE, true, false>(lb, grid, smem, s, e0, e1);
+  return nt ? launch_one<T, DENSE, false, true>(lb, grid, smem, s, e0, e1) : launch_one<T, DENSE, false, false>(lb, grid, smem, s, e0, e1);
+}
+
+template <class T>
+hipError_t launch_dtype(const LinBatch& lb, bool tail, bool nt, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0,
+                        hipEvent_t e1) {
+  return lb.dense ? launch_shape<T, true>(lb, tail, nt, grid, smem, s, e0, e1)
+                  : launch_shape<T, false>(lb, tail, nt, grid, smem, s, e0, e1);
 }
 
 }  // namespace
@@ -226,45 +232,56 @@ hipError_t upload_launch(const void* src, size_t bytes, void* dst, hipStream_t s
   return hipSuccess;
 }
 
-template <class T, bool TAIL>
+template <class T, bool TAIL, bool NT>
 static hipError_t launch_fired(const FiredIn* ins, const FiredMap* maps, int n_in, unsigned grid, size_t smem,
                                hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   static const hipError_t attr =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fired<T, TAIL>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fired<T, TAIL, NT>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLinD * (int)sizeof(float));
   if (attr != hipSuccess) return attr;
-  if (e0 && e1) hipExtLaunchKernelGGL((stream_fired<T, TAIL>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, ins, maps, n_in);
-  else stream_fired<T, TAIL><<<grid, kBlock, smem, s>>>(ins, maps, n_in);
+  if (e0 && e1) hipExtLaunchKernelGGL((stream_fired<T, TAIL, NT>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, ins, maps, n_in);
+  else stream_fired<T, TAIL, NT><<<grid, kBlock, smem, s>>>(ins, maps, n_in);
   return hipGetLastError();
+}
+
+template <class T>
+static hipError_t launch_fired_shape(const FiredIn* ins, const FiredMap* maps, const FiredGeom& g, hipStream_t s,
+                                     hipEvent_t e0, hipEvent_t e1) {
+  if (g.tail)
+    return g.nt ? launch_fired<T, true, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
+                : launch_fired<T, true, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+  return g.nt ? launch_fired<T, false, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
+              : launch_fired<T, false, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
 }
 
 hipError_t stream_fired_geom(int n_in, const FiredIn* host_ins, const FiredMap* host_maps, int wdtype, FiredGeom& g) {
   if (n_in <= 0 || n_in > kMaxFiredIn) return hipErrorInvalidValue;
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   int64_t rows = 0;
-  size_t maxd = 0;
+  size_t maxd = 0, bytes = 0;
   bool tail = false;
   for (int i = 0; i < n_in; ++i) {
     if ((size_t)host_ins[i].d > maxd) maxd = (size_t)host_ins[i].d;
     if ((host_ins[i].d / V) % (kWave * kLU)) tail = true;
-    for (int j = host_ins[i].map_begin; j < host_ins[i].map_end; ++j) rows += host_maps[j].m;
+    for (int j = host_ins[i].map_begin; j < host_ins[i].map_end; ++j) {
+      rows += host_maps[j].m;
+      bytes += (size_t)host_maps[j].m * host_ins[i].d * elem_size(wdtype);
+    }
   }
   if (maxd > (size_t)kMaxLinD) return hipErrorInvalidValue;
   int64_t grid = (int64_t)kWgsPerCu * num_cus();
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
   g.n_in = n_in; g.wdtype = wdtype; g.tail = tail ? 1 : 0; g.grid = (unsigned)grid; g.smem = maxd * sizeof(float);
+  g.nt = bytes >= kStreamBytes ? 1 : 0;  // (all maps of the call: which of them fire is not known here)
   return hipSuccess;
 }
 
 hipError_t stream_fired_run(const void* table, const FiredGeom& g, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   const FiredIn* ins = static_cast<const FiredIn*>(table);
   const FiredMap* maps = reinterpret_cast<const FiredMap*>(static_cast<const char*>(table) + fired_table_bytes(g.n_in, 0));
-  if (g.wdtype == GSI_BF16)
-    return g.tail ? launch_fired<BF16, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
-                  : launch_fired<BF16, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
-  return g.tail ? launch_fired<F32, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
-                : launch_fired<F32, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+  return g.wdtype == GSI_BF16 ? launch_fired_shape<BF16>(ins, maps, g, s, e0, e1)
+                              : launch_fired_shape<F32>(ins, maps, g, s, e0, e1);
 }
 
 hipError_t stream_fired_launch(const void* table, int n_in, const FiredIn* host_ins, const FiredMap* host_maps,
@@ -286,17 +303,20 @@ hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   // persistent grid: a few workgroups per CU, never more waves than rows
   int64_t rows = 0;
+  size_t bytes = 0;
   bool tail = false;
   for (int i = 0; i < lb.n; ++i) {
     rows += lb.t[i].m;
+    bytes += (size_t)lb.t[i].m * lb.g[lb.t[i].group].d * elem_size(wdtype);
     if ((lb.g[lb.t[i].group].d / V) % (kWave * kLU)) tail = true;
   }
+  const bool nt = bytes >= kStreamBytes;
   int64_t grid = (int64_t)kWgsPerCu * num_cus();
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
   const size_t smem = stream_smem_bytes(lb);
-  return wdtype == GSI_BF16 ? launch_dtype<BF16>(lb, tail, (unsigned)grid, smem, s, e0, e1)
-                            : launch_dtype<F32>(lb, tail, (unsigned)grid, smem, s, e0, e1);
+  return wdtype == GSI_BF16 ? launch_dtype<BF16>(lb, tail, nt, (unsigned)grid, smem, s, e0, e1)
+                            : launch_dtype<F32>(lb, tail, nt, (unsigned)grid, smem, s, e0, e1);
 }
 
 }  // namespace gsi

@@ -15,7 +15,14 @@ constexpr int kLU = 8;  // 16-byte loads per lane in a unit
 template <class T>
 struct Raw {  // 16 bytes as loaded; widened to fp32 when consumed
   uint4 v;
-  __device__ __forceinline__ void load(const typename T::storage* p) { v = *reinterpret_cast<const uint4*>(p); }
+  // NT: a launch that streams far more than the caches hold loads its weights non-temporally (6.7 TB/s against
+  // 6.0 TB/s on 1.6 GB); a launch whose weights may still be in the 256 MB memory-side cache from the step before
+  // loads them normally (non-temporal loads would forfeit those hits)
+  template <bool NT>
+  __device__ __forceinline__ void load(const typename T::storage* p) {
+    if constexpr (NT) v = load_stream16(p);
+    else v = *reinterpret_cast<const uint4*>(p);
+  }
   __device__ __forceinline__ void widen(float (&f)[T::kVec]) const { T::widen(v, f); }
 };
 
@@ -46,7 +53,7 @@ __device__ __forceinline__ float load_old(const float* p) {
 // Rows first, first + GW, ... (< m) of W[m, d] by the calling wave; xs = the staged vector (d floats, LDS).
 // whole: the product replaces y (dense baseline, W x form of the slow path); else it is added to y.
 // TAIL: d / kVec is not a multiple of 64 * kLU (loads clamped, surplus products dropped).
-template <class T, bool TAIL, bool COHERENT>
+template <class T, bool TAIL, bool COHERENT, bool NT = false>
 __device__ __forceinline__ void stream_map_rows(const typename T::storage* __restrict__ W, float* __restrict__ Y,
                                                 int m, int d, const float* __restrict__ xs, bool whole, int first,
                                                 int GW, int lane) {
@@ -71,7 +78,7 @@ __device__ __forceinline__ void stream_map_rows(const typename T::storage* __res
       auto issue = [&](Raw<T> (&buf)[kLU], const S* ptr) {
         __builtin_amdgcn_sched_barrier(0);  // keep the loads here: ahead of the arithmetic that follows
 #pragma unroll
-        for (int q = 0; q < kLU; ++q) buf[q].load(ptr + (int64_t)q * kWave * V);
+        for (int q = 0; q < kLU; ++q) buf[q].template load<NT>(ptr + (int64_t)q * kWave * V);
         __builtin_amdgcn_sched_barrier(0);
       };
       auto consume = [&](const Raw<T> (&buf)[kLU], int jj, int sg) {
@@ -133,7 +140,7 @@ __device__ __forceinline__ void stream_map_rows(const typename T::storage* __res
         for (int q = 0; q < kLU; ++q) {
           int c = cb + q * kWave;
           c = c < chunks ? c : chunks - 1;
-          buf[q].load(W + (int64_t)row * d + (int64_t)c * V);
+          buf[q].template load<NT>(W + (int64_t)row * d + (int64_t)c * V);
         }
 #pragma unroll
         for (int q = 0; q < kLU; ++q) {
