@@ -363,7 +363,9 @@ def main() -> int:
         SET = 16                                  # inputs per launch of the staged kernel
         nsets = (S.n_in + SET - 1) // SET
         table_mode = single_pass and nsets > 1    # every stage once for all inputs: three launches
-        n_launch = {0: 3 if table_mode else nsets + (2 if single_pass else 3), 1: 1}  # staged kernel(s), weights
+        sum_stage = 1 if (single_pass or nsets > 1) else 0
+        inline_gate = (not single_pass) and nsets == 1 and S.n_mp <= 24 and S.n_in <= 16  # the weight kernel gates
+        n_launch = {0: 3 if table_mode else nsets + 2 + sum_stage - (1 if single_pass or inline_gate else 0), 1: 1}
         K = min(T, 24)
         evs = HipEvents(2)
         s0 = torch.cuda.current_stream().cuda_stream

@@ -422,10 +422,12 @@ struct LinBatcher {
   gsi::ImgBatch sib;                      // single token: image maps y = M c not yet written by an earlier launch
   int* n_launches = nullptr;               // the launch whose count equals timed_index gets the events
   int timed_index = -1;
+  float eps = 0.f;                          // for groups whose gate the single-token kernel evaluates
   void reset(int64_t B_, int dense) {
     B = B_;
     clear(lb, B_);
     lb.dense = dense;
+    lb.eps = eps;
     std::memset(&sib, 0, sizeof(sib));
   }
   hipError_t flush() {
@@ -941,6 +943,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // Schedule in waves: an input is ready when its producer map has been enqueued, a map when its
   // input has.  Ready inputs (maps) of one dtype that take the same kernels share a launch.
   std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0), img_done(n_maps, 0);
+  std::vector<char> gate_inline(n_inputs, 0);  // the weight kernel evaluates this input's gate
+  std::vector<int> part_ncb(n_inputs, 1);      // column blocks of this input's partial projection
   int remaining = n_inputs + n_maps;
   while (remaining > 0) {
     int progressed = 0;
@@ -1066,6 +1070,12 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       };
       auto member = [&](int g, int q) { return list[(size_t)g * gsi::kMaxTasks + q]; };
       const int sum_stage = (sp || nsets > 1) ? 1 : 0;
+      // One set, explicit gate, and few enough maps for the weight kernel whose descriptors are kernel arguments:
+      // that kernel evaluates and publishes the gates itself, which saves the gate launch.
+      // (the whole call must be that small, so that none of its maps takes the weight launch over a table)
+      const bool inline_gate = !sp && nsets == 1 && !plan && n_maps <= gsi::kMaxLinTasks && n_inputs <= gsi::kMaxTasks;
+      if (inline_gate)
+        for (int i : list) gate_inline[i] = 1;
       if (sum_stage)  // the partials are added once per input: finer slabs
         for (int i : list) gsi::stage_geom(inputs[i].d, inputs[i].k, dt, ptask[i].s_rows, ptask[i].s_slabs, true);
       if (sp && (nsets > 1 || plan) && (int)list.size() <= gsi::kMaxTabIn && n_maps > 0 && n_maps <= gsi::kMaxTabMaps) {
@@ -1125,12 +1135,19 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           return hip_fail(e, fn);
         continue;
       }
-      for (int g = 0; g < nsets + 2 + sum_stage - (sp ? 1 : 0); ++g) {
+      for (int g = 0; g < nsets + 2 + sum_stage - (sp || inline_gate ? 1 : 0); ++g) {
         gsi::StageArgs a;
         gsi::stage_clear(a, eps);
-        for (int q = 0; q < set_size(g); ++q) {
-          const int i = member(g, q);
-          gsi::stage_add_part(a, ptask[i], sp ? inputs[i].gram : nullptr);
+        {  // a set with few slabs splits the columns of its bases so that the launch still fills the chip
+          int total = 0;
+          for (int q = 0; q < set_size(g); ++q) total += ptask[member(g, q)].s_slabs;
+          for (int q = 0; q < set_size(g); ++q) {
+            const int i = member(g, q);
+            int ncb = 1;
+            while (total * ncb < 384 && inputs[i].k / (ncb * 2) >= 64 && (inputs[i].k / (ncb * 2)) % 64 == 0) ncb *= 2;
+            part_ncb[i] = ncb;
+            gsi::stage_add_part(a, ptask[i], sp ? inputs[i].gram : nullptr, ncb);
+          }
         }
         if (sum_stage)
           for (int q = 0; q < set_size(g - 1); ++q) {
@@ -1142,6 +1159,21 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
           const int i = member(gr, q);
           const bool wx = (inputs[i].flags & GSI_INPUT_SLOW_PATH_WX) != 0;
           const int res = gsi::stage_add_res(a, ptask[i], sum_stage != 0, sp ? inputs[i].gram : nullptr, sp && wx);
+          // One set without a sum stage: the launch before this one was the partial projections alone, in the same
+          // task order.  If both launches start this input on the same XCD, the residual slabs follow the XCD order
+          // of the partial slabs (second read of the basis out of the L2 that holds it).
+          if (nsets == 1 && !sum_stage) {
+            int a_off = 0, b_off = 0;
+            for (int q2 = 0; q2 < q; ++q2) {
+              const gsi::ProjTask& t2 = ptask[member(gr, q2)];
+              a_off += t2.s_slabs * part_ncb[member(gr, q2)];
+              b_off += t2.b_slabs;
+            }
+            const gsi::ProjTask& t = ptask[i];
+            if (t.s_slabs % 8 == 0 && t.b_slabs % t.s_slabs == 0 && a_off % 8 == b_off % 8 &&
+                (int64_t)t.s_slabs * t.s_rows == t.d && (int64_t)t.b_slabs * t.b_rows == t.d && t.b_slabs / t.s_slabs < 256)
+              gsi::stage_set_res_xcd_order(a, res, t.b_slabs / t.s_slabs);
+          }
           for (int j = 0; j < n_maps && a.ni < gsi::kMaxLinTasks; ++j) {
             if (maps[j].input_id != i || maps[j].wdtype != dt || img_done[j]) continue;
             gsi::stage_add_img(a, res, maps[j].M, maps[j].Y,
@@ -1149,7 +1181,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
             img_done[j] = 1;
           }
         }
-        if (!sp)
+        if (!sp && !inline_gate)
           for (int q = 0; q < set_size(gr - 1); ++q) gsi::stage_add_gate(a, ptask[member(gr - 1, q)]);
         const bool timed = which == 0 && n_stage_launches == launch_index;
         ++n_stage_launches;
@@ -1280,6 +1312,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       LinBatcher bt;
       bt.wdtype = dt; bt.s = s;
       if (which == 1) { bt.e0 = ev_begin; bt.e1 = ev_end; bt.n_launches = &n_stream_launches; bt.timed_index = launch_index; }
+      bt.eps = eps;
       bt.reset(B, 0);
       for (int j : mready) {
         const gsi_map_desc& mp = maps[j];
@@ -1296,6 +1329,11 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         gd.d = (int)in.d; gd.k = (int)in.k;
         gd.wx = (in.flags & GSI_INPUT_SLOW_PATH_WX) ? 1 : 0;
         gd.X = in.X; gd.xdtype = in.xdtype;
+        if (gate_inline[mp.input_id]) {
+          const gsi::ProjTask& pt = ptask[mp.input_id];
+          gd.part_n = pt.part_n; gd.b_slabs = pt.b_slabs; gd.rnorm = in.rnorm; gd.xnorm = in.xnorm; gd.mask = in.mask;
+          gd.fired_idx_out = in.fired_idx; gd.n_fired_out = in.n_fired;
+        }
         if (hipError_t e = bt.add(mp.input_id, gd, mp.W, mp.M, mp.Y, mp.m, B == 1 && !img_done[j], part[j],
                                   (mp.flags & GSI_MAP_IMAGE_FP8) ? mp.M_scale : nullptr);
             e != hipSuccess)

@@ -75,6 +75,15 @@ struct LinGroup {
   const int32_t* n_fired;
   int wx;                        // fired tokens get y = W x (Algorithm 1, line 7) instead of M c + W r
   int d, k, xdtype;
+  // single token, gate not yet published (a stack of one set of inputs leaves it to the weight kernel and saves a
+  // launch): the residual launch's slab shares of the norms and where the gate's outputs go; else part_n is null
+  int b_slabs;
+  const float* part_n;
+  float* rnorm;
+  float* xnorm;
+  uint8_t* mask;
+  int32_t* fired_idx_out;
+  int32_t* n_fired_out;
 };
 
 struct LinTask {
@@ -94,7 +103,9 @@ struct LinBatch {
   int tile_split;                  // ... first image-term workgroup of the launch
   int n, ng, B;
   int dense;                 // y = W x, no image term
+  float eps;                 // for groups whose gate the single-token kernel evaluates itself
 };
+static_assert(sizeof(LinBatch) <= 4096, "kernel arguments are limited to 4 KB");
 
 // eligibility of the vector kernels for a shape / alignment (else the generic kernels run)
 bool decode_project_ok(int64_t d, int64_t k, int udtype, const void* U);
@@ -140,7 +151,7 @@ struct StagePart {        // partial projection c = U^T x of one input over row 
   float* part_c;          // [slabs][k]
   int d;
   int k_rows;             // k | rows per slab << 16
-  int slabs_x;            // slabs | xdtype << 16
+  int slabs_x;            // slabs | xdtype << 16 | column blocks << 20 (0 or 1: whole rows)
   int x2_off;             // single-pass gate: byte offset from part_c of the slab shares of |x|^2 (doubles); else 0
 };
 
@@ -172,8 +183,9 @@ struct StageRes {         // r = x - U c, and the slab shares of |r|^2, |x|^2, o
   int d;
   int k_rows;             // k | b_rows << 16
   int slabs_x;            // b_slabs | slabs of the partial projection << 16 | xdtype << 24
-  int gate;               // single-pass gate: 1 + index of this input's StageGate, evaluated by every residual
-                          // workgroup (r is formed only if the gate fires); else 0
+  int gate;               // bits 0-7: single-pass gate: 1 + index of this input's StageGate, evaluated by every
+                          // residual workgroup (r is formed only if the gate fires); else 0.  bits 8-15: r > 0: the
+                          // slabs are walked in the XCD order of the partial projection, r of them per partial slab
 };
 
 struct StageImg {         // image rows y = M c of one map
@@ -218,11 +230,14 @@ static_assert(sizeof(StageArgs) <= 4096, "kernel arguments are limited to 4 KB")
 void stage_geom(int64_t d, int64_t k, int udtype, int& rows, int& slabs, bool fine = false);
 void stage_clear(StageArgs& a, float eps);
 // E (single-pass gate): the input's cached U^T U - I, else null
-void stage_add_part(StageArgs& a, const ProjTask& t, const float* E = nullptr);
+// ncb: column blocks (a power of two; k / ncb at least 64 columns): more, narrower workgroups for small calls
+void stage_add_part(StageArgs& a, const ProjTask& t, const float* E = nullptr, int ncb = 1);
 void stage_add_cred(StageArgs& a, const ProjTask& t, const float* E = nullptr);
 // returns its index; single-pass gate: the residual workgroups evaluate and publish the gate themselves
 int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready, const float* E = nullptr, bool skip_fired_image = false);
 void stage_add_img(StageArgs& a, int res, const void* M, float* Y, const float* scale, int m);
+// residual task `res` walks its slabs in the XCD order of the partial projection (r residual slabs per partial slab)
+void stage_set_res_xcd_order(StageArgs& a, int res, int r);
 void stage_add_gate(StageArgs& a, const ProjTask& t);
 // e0 / e1 (optional): events that take the start / stop timestamps of the dispatch
 hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0 = nullptr, hipEvent_t e1 = nullptr);

@@ -27,6 +27,7 @@
 // All sums have a fixed order: results are bit-identical run to run.
 #include <hip/hip_ext.h>
 
+#include <algorithm>
 #include <cstring>
 #include <vector>
 
@@ -85,19 +86,24 @@ __device__ __forceinline__ void publish_gate(const StageGate& g, float rn, float
 
 // STREAM: the first two batches of U are loaded non-temporally (a launch over many inputs: nothing is read again soon)
 template <class T, bool STREAM = false>
-__device__ __forceinline__ void partial_block(const StagePart& p, int slab, float* __restrict__ red,
+__device__ __forceinline__ void partial_block(const StagePart& p, int local, float* __restrict__ red,
                                               float* __restrict__ xs, double* __restrict__ dsh) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
+  // A small call splits the columns of U into ncb blocks of w = k / ncb (a workgroup then reads w-wide pieces of its
+  // rows), so that a few inputs still give the chip hundreds of workgroups; a large call takes whole rows (ncb = 1).
   const int d = p.d, k = p.k_rows & 0xffff, prow = p.k_rows >> 16;
-  const int cpr = k / V;         // lanes per row of U (a power of two, one wave at most)
+  const int slabs = p.slabs_x & 0xffff, ncb = max(1, (p.slabs_x >> 20) & 0xff);
+  const int slab = local % slabs, col0 = (local / slabs) * (k / ncb);
+  const int w = k / ncb;
+  const int cpr = w / V;         // lanes per row piece (a power of two, one wave at most)
   const int rps = kBlock / cpr;  // rows per step
   const int lsh = __builtin_ctz(cpr);
   const int cc = threadIdx.x & (cpr - 1), ro = threadIdx.x >> lsh;
   const int row0 = slab * prow;
   const int rows = min(prow, d - row0);
-  const S* U = reinterpret_cast<const S*>(p.U) + (int64_t)row0 * k + cc * V;
-  const int xdtype = p.slabs_x >> 16;
+  const S* U = reinterpret_cast<const S*>(p.U) + (int64_t)row0 * k + col0 + cc * V;
+  const int xdtype = (p.slabs_x >> 16) & 0xf;
 
   float acc[V];
 #pragma unroll
@@ -184,44 +190,43 @@ __device__ __forceinline__ void partial_block(const StagePart& p, int slab, floa
   }
 #pragma unroll
   for (int q = 0; q < V / 4; ++q)
-    reinterpret_cast<float4*>(red + ro * k + cc * V)[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
+    reinterpret_cast<float4*>(red + ro * w + cc * V)[q] = make_float4(acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]);
   if (p.x2_off) {
     x2 = wave_sum_f64(x2);
     if (threadIdx.x % kWave == 0) dsh[threadIdx.x / kWave] = x2;
   }
   __syncthreads();
-  if (p.x2_off && threadIdx.x == 0) {
+  if (p.x2_off && threadIdx.x == 0 && col0 == 0) {
     double t = 0.0;
     for (int w = 0; w < kWaves; ++w) t += dsh[w];
     reinterpret_cast<double*>(reinterpret_cast<char*>(p.part_c) + p.x2_off)[slab] = t;
   }
   if (p.x2_off) {  // single-pass gate: the row groups are added in fp64 and the partial is kept as high + low part
-    const int slabs = p.slabs_x & 0xffff;
-    for (int j = threadIdx.x; j < k; j += kBlock) {
+    for (int j = threadIdx.x; j < w; j += kBlock) {
       double s = 0.0;
       for (int g = 0; g < rps; g += 4) {
         float v[4];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) v[q] = red[(g + q) * k + j];
+        for (int q = 0; q < 4; ++q) v[q] = red[(g + q) * w + j];
 #pragma unroll
         for (int q = 0; q < 4; ++q) s += (double)v[q];
       }
       const float hi = (float)s;
-      p.part_c[(int64_t)slab * k + j] = hi;
-      p.part_c[(int64_t)(slabs + slab) * k + j] = (float)(s - (double)hi);
+      p.part_c[(int64_t)slab * k + col0 + j] = hi;
+      p.part_c[(int64_t)(slabs + slab) * k + col0 + j] = (float)(s - (double)hi);
     }
     return;
   }
-  for (int j = threadIdx.x; j < k; j += kBlock) {
+  for (int j = threadIdx.x; j < w; j += kBlock) {
     float s = 0.f;
     for (int g = 0; g < rps; g += 4) {  // rps is a multiple of 4: four LDS reads in flight, fixed order of adds
       float v[4];
 #pragma unroll
-      for (int q = 0; q < 4; ++q) v[q] = red[(g + q) * k + j];
+      for (int q = 0; q < 4; ++q) v[q] = red[(g + q) * w + j];
 #pragma unroll
       for (int q = 0; q < 4; ++q) s += v[q];
     }
-    p.part_c[(int64_t)slab * k + j] = s;
+    p.part_c[(int64_t)slab * k + col0 + j] = s;
   }
 }
 
@@ -319,8 +324,16 @@ __device__ __forceinline__ void residual_block(const StageRes& p, const StageGat
   using S = typename T::storage;
   const int d = p.d, k = p.k_rows & 0xffff, b_rows = p.k_rows >> 16;
   const int xdtype = p.slabs_x >> 24, a_slabs = (p.slabs_x >> 16) & 0xff;
-  if (p.gate) {  // single-pass gate: the verdict first; an input that did not fire needs no residual
-    const StageGate& g = gates[p.gate - 1];
+  if (const int r = p.gate >> 8) {
+    // Workgroups go to the eight XCDs round-robin.  The launch before this one read the rows of partial-projection
+    // slab ps on XCD ps % 8 (the host checked the offsets); r residual slabs cover one such slab, so the residual
+    // slabs are walked in an order that puts slab r * ps + h on XCD ps % 8 too: the second read of the basis then
+    // comes out of the L2 that holds it.
+    const int chunk = slab / (8 * r), within = slab % (8 * r);
+    slab = r * (8 * chunk + within % 8) + within / 8;
+  }
+  if (p.gate & 0xff) {  // single-pass gate: the verdict first; an input that did not fire needs no residual
+    const StageGate& g = gates[(p.gate & 0xff) - 1];
     float rn, xn;
     const bool f = single_pass_gate(reinterpret_cast<const double*>(g.part_n), g.b_slabs, eps, rn, xn);
     if (slab == 0 && threadIdx.x == 0) publish_gate(g, rn, xn, f);
@@ -383,7 +396,7 @@ __device__ __forceinline__ void residual_block(const StageRes& p, const StageGat
     for (int q = 0; q < PF; ++q)
       if (st0 + q < steps) row_step(u[q], xs[min((st0 + q) * rps + ro, rows - 1)], st0 + q);
   }
-  if (p.gate) return;  // the norms came from the single-pass shares
+  if (p.gate & 0xff) return;  // the norms came from the single-pass shares
   const float sr = group_sum<kWave>(ar);
   const float sx = group_sum<kWave>(ax);
   if (lane == 0) {
@@ -441,8 +454,8 @@ __global__ __launch_bounds__(kBlock) void proj_stage(const StageArgs a) {
       if (i < a.ni && b >= (a.im[i].blk_res & 0xffffff)) ti = i;
     const StageImg& im = a.im[ti];
     const StageRes& r = a.b[im.blk_res >> 24];
-    if (r.gate && a.g[r.gate - 1].skip_fired_image) {  // fired: the weight kernel writes y = W x (Algorithm 1, line 7)
-      const StageGate& g = a.g[r.gate - 1];
+    if ((r.gate & 0xff) && a.g[(r.gate & 0xff) - 1].skip_fired_image) {  // fired: the weight kernel writes y = W x
+      const StageGate& g = a.g[(r.gate & 0xff) - 1];
       float rn, xn;
       if (single_pass_gate(reinterpret_cast<const double*>(g.part_n), g.b_slabs, a.eps, rn, xn)) return;
     }
@@ -621,10 +634,10 @@ void stage_clear(StageArgs& a, float eps) {
   a.eps = eps;
 }
 
-void stage_add_part(StageArgs& a, const ProjTask& t, const float* E) {
+void stage_add_part(StageArgs& a, const ProjTask& t, const float* E, int ncb) {
   StagePart& p = a.a[a.na++];
   p.U = t.U; p.X = t.X; p.part_c = t.part_c;
-  p.d = t.d; p.k_rows = t.k | (t.s_rows << 16); p.slabs_x = t.s_slabs | (t.xdtype << 16);
+  p.d = t.d; p.k_rows = t.k | (t.s_rows << 16); p.slabs_x = t.s_slabs | (t.xdtype << 16) | (ncb << 20);
   p.x2_off = E ? (int)(reinterpret_cast<char*>(t.part_n) - reinterpret_cast<char*>(t.part_c)) : 0;
 }
 
@@ -634,6 +647,8 @@ void stage_add_cred(StageArgs& a, const ProjTask& t, const float* E) {
   p.E = E; p.gw_off = (int)(reinterpret_cast<char*>(t.part_n) - reinterpret_cast<char*>(t.part_c));
   if (E) a.gram = 1;
 }
+
+void stage_set_res_xcd_order(StageArgs& a, int res, int r) { a.b[res].gate = (a.b[res].gate & 0xff) | (r << 8); }
 
 int stage_add_res(StageArgs& a, const ProjTask& t, bool c_ready, const float* E, bool skip_fired_image) {
   StageRes& p = a.b[a.nb];
@@ -666,7 +681,7 @@ hipError_t stage_launch(StageArgs& a, int dtype, hipStream_t s, hipEvent_t e0, h
   int ta = 0, tb = 0, ti = 0;
   for (int i = 0; i < a.na; ++i) {
     a.a_begin[i] = ta;
-    ta += a.a[i].slabs_x & 0xffff;
+    ta += (a.a[i].slabs_x & 0xffff) * std::max(1, (a.a[i].slabs_x >> 20) & 0xff);
   }
   for (int i = 0; i < a.nb; ++i) {
     a.b_begin[i] = tb;

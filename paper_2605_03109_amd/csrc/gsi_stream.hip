@@ -3,8 +3,10 @@
 //
 // A persistent grid of two 512-thread workgroups per CU (sixteen waves per CU).  Structure of one launch:
 //   1. gate of every input group: one wave per group reads the count of fired tokens the projection launch
-//      published (Eq. (gate)); every workgroup reads the same words, so the decision is uniform across the grid
-//      without communication.  If nothing fired the kernel ends here: no byte of W is read;
+//      published (Eq. (gate)), or -- a stack of one set of inputs -- evaluates the gate itself from the residual
+//      launch's slab shares and publishes it; every workgroup does the same arithmetic on the same words, so the
+//      decision is uniform across the grid without communication.  If nothing fired the kernel ends here: no byte
+//      of W is read;
 //   2. once per fired group: the residual vector is staged in LDS, then the rows of W of the group's
 //      maps are dealt round-robin over all waves of the grid (neighbouring waves stream neighbouring
 //      rows), one row per wave in units of eight 16-byte loads per lane, fp32 FMA against the staged
@@ -43,7 +45,22 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   if constexpr (!DENSE) {
     for (int gi = wave; gi < ng; gi += kWaves) {  // wave gi evaluates the gate of group gi
       const LinGroup& g = lb.g[gi];
-      const bool f = g.n_fired[0] > 0;
+      bool f;
+      if (g.part_n) {  // not yet published: the same sums, in the same order, as the gate workgroup of the staged kernel
+        float tr, tx;
+        wave_norm_sums(g.part_n, g.b_slabs, 1, 0, tr, tx);
+        const float rn = sqrtf(tr), xn = sqrtf(tx);
+        f = gate_fires(rn, xn, lb.eps);
+        if (blockIdx.x == 0 && lane == 0) {  // identical arithmetic in every workgroup: one of them publishes
+          g.rnorm[0] = rn;
+          g.xnorm[0] = xn;
+          g.mask[0] = f ? 1 : 0;
+          if (f) g.fired_idx_out[0] = 0;
+          g.n_fired_out[0] = f ? 1 : 0;
+        }
+      } else {
+        f = g.n_fired[0] > 0;
+      }
       if (lane == 0) s_fired_g[gi] = f ? 1u : 0u;
     }
     __syncthreads();
