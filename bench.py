@@ -259,6 +259,9 @@ def main() -> int:
                     help="single-pass: residual ratio from |x|^2 - |c|^2 + c^T E c with the cached E = U^T U - I "
                          "(GSI_INPUT_GATE_SINGLE_PASS: the basis is read once, r is formed for fired tokens only); "
                          "explicit: r = x - U c formed for every token")
+    ap.add_argument("--slow-path", choices=["mc+wr", "wx"], default="mc+wr",
+                    help="wx: fired tokens get y = W x as Algorithm 1 prints it (GSI_INPUT_SLOW_PATH_WX); with the "
+                         "single-pass gate a fired input's image rows are then skipped")
     ap.add_argument("--no-plan", action="store_true",
                     help="call gsi_layer_stack with host descriptors every step instead of running plans that "
                          "gsi_stack_plan_build marshalled once (single-pass gate only)")
@@ -304,6 +307,8 @@ def main() -> int:
     single_pass = args.gate == "single-pass" and not args.fused
     if single_pass:
         flags |= gsi.INPUT_GATE_SINGLE_PASS
+    if args.slow_path == "wx":
+        flags |= gsi.INPUT_SLOW_PATH_WX
 
     # ---- the headline cell ------------------------------------------------------------------------------
     t0 = time.perf_counter()
@@ -522,7 +527,7 @@ def main() -> int:
                         "gsi_layer_stack call per decode token",
             "layers": L, "k": args.k, "eps": eps, "decode_tokens": T, "designed_fire_rate": args.fire,
             "measured_fire_rate": head["measured_fire_rate"], "masks_match_design": head["masks_match_design"],
-            "launch_mode": mode, "slow_path": "M c + W r",
+            "launch_mode": mode, "slow_path": "W x (a fired input skips its image)" if args.slow_path == "wx" else "M c + W r",
             "call": "gsi_stack_plan_run on a plan built once per trace token (gsi_stack_plan_build)" if use_plan
                     else "gsi_layer_stack with host descriptors every step",
             "single_token_kernels": "fused" if args.fused else "separate",

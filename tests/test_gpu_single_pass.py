@@ -286,3 +286,73 @@ def test_stack_plan_equals_layer_stack(gsi, pu, wx):
     with pytest.raises(gsi.GsiError) as ei:
         bad.build_plan()
     assert ei.value.code == gsi.GSI_ERR_SHAPE and "planned" in str(ei.value)
+
+
+def test_single_pass_with_fp8_images_chain_and_static_entry(gsi, pu):
+    """The single-pass gate beside the other options of a stack: E4M3 images (codes read as they are by the image
+    workgroups), an input that is another map's output (two waves of launches), gsi_layer_stack_static (scratch and
+    tables in the library's static array), and a call of 20 inputs with E4M3 images through the table launches.
+    Each must agree with the same stack run with the explicit residual: equal decisions, the rest to rounding."""
+    sp = gsi.INPUT_GATE_SINGLE_PASS
+
+    def close(a, b, what):
+        for x, y in zip(a.inputs_t, b.inputs_t):
+            assert torch.equal(x["mask"], y["mask"]), what
+            assert torch.allclose(x["C"], y["C"], rtol=0, atol=3e-6 * float(y["xnorm"].max())), what
+            assert ((x["rnorm"] - y["rnorm"]).abs() / y["xnorm"].clamp_min(1e-30)).max().item() <= 1e-5, what
+        for x, y in zip(a.maps_t, b.maps_t):
+            assert torch.allclose(x["Y"], y["Y"], rtol=0, atol=1e-5 * float(y["Y"].abs().max())), what
+
+    # (a) E4M3 images, one block and five blocks
+    for L in (1, 5):
+        T = 5
+        blocks = [wl.transformer_block(f"q{l}", d=512, ffn=2048, k=64, T=T, fire_rate=0.4, p=1.5, seed=4500 + l) for l in range(L)]
+        inputs, maps = [], []
+        for w in blocks:
+            _, bi, bm, _ = _stack(gsi, pu, w, sp)
+            base = len(inputs)
+            inputs += bi
+            for m in bm:
+                M8, scale = gsi.quantize_image_fp8(m["M"])
+                maps.append({"W": m["W"], "M": M8, "M_scale": scale, "input_id": m["input_id"] + base})
+        say(f"case single-pass with E4M3 images: {len(inputs)} inputs")
+        a = gsi.LayerStack(inputs, maps, T, blocks[0].eps)
+        b = gsi.LayerStack([dict(i, flags=0) for i in inputs], maps, T, blocks[0].eps)
+        _run_tokens(a, T)
+        _run_tokens(b, T)
+        close(a, b, f"fp8 L={L}")
+        assert sum(int(i["mask"].sum()) for i in b.inputs_t) > 0
+    # (b) a chain: the second input is the first map's output
+    w = wl.tiny(256, 32, 384, 6, 2, seed=4600, wdtype="bf16")
+    dg = pu.DeviceGroup(w, w.groups[0])
+    U1d = gsi.to_device(wl.store(wl.make_basis64(384, 64, 4601), "bf16"), "bf16")
+    W1d = gsi.to_device(wl.make_weight(200, 384, 4602, "bf16"), "bf16")
+    M1d = gsi.build_image(W1d, U1d)
+    maps = [{"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}, {"W": W1d, "M": M1d, "input_id": 1}]
+
+    def chain(flags):
+        ins = [{"U": dg.U, "X": dg.X, "flags": flags, "gram": gsi.build_gram(dg.U)},
+               {"U": U1d, "src_map": 0, "flags": flags, "gram": gsi.build_gram(U1d)}]
+        st = gsi.LayerStack(ins, [dict(m) for m in maps], 6, w.eps)
+        _run_tokens(st, 6)
+        return st
+
+    say("case single-pass chain")
+    close(chain(sp), chain(0), "chain")
+    # (c) the entry point without a workspace
+    wb = wl.transformer_block("s", d=512, ffn=2048, k=64, T=4, fire_rate=0.5, p=1.5, seed=4700)
+    _, bi, bm, _ = _stack(gsi, pu, wb, sp)
+    a = gsi.LayerStack(bi, bm, 4, wb.eps)
+    b = gsi.LayerStack(bi, bm, 4, wb.eps)
+    for t in range(4):
+        a.refresh(token_offset=t, B=1)
+        a.run_static()
+        b.refresh(token_offset=t, B=1)
+        b.run()
+    torch.cuda.synchronize()
+    say("case single-pass through gsi_layer_stack_static")
+    for x, y in zip(a.inputs_t, b.inputs_t):
+        for key in ("C", "rnorm", "xnorm", "mask"):
+            assert torch.equal(x[key], y[key]), key
+    for x, y in zip(a.maps_t, b.maps_t):
+        assert torch.equal(x["Y"], y["Y"])
