@@ -252,12 +252,13 @@ int gsi_stack_plan_run(const gsi_stack_plan* plan, float eps, void* stream);
 /* Instrumented variant for measurements (not part of the method): identical to gsi_layer_stack; in addition the
  * two HIP events (hipEvent_t passed as void*, created by the caller with timing enabled) take the start and stop
  * timestamps of the dispatch of ONE of the single-token launches of the call, so hipEventElapsedTime(begin, end)
- * is that launch's execution time as a profiler reports it.  which_kernel: 0 = the staged projection kernel
- * (partial projections of a set of up to 16 inputs; residuals, gates and image rows of the set before; also the
- * fused kernel of inputs with GSI_INPUT_FUSED_KERNEL), 1 = the weight-streaming kernel (rows of W of the fired
- * inputs' maps).  launch_index counts the launches of that kind in the order the call enqueues them, from 0.
- * If the call makes fewer launches of that kind (always so for B != 1) it is still enqueued in full, the events
- * are not recorded and GSI_ERR_SHAPE is returned. */
+ * is that launch's execution time as a profiler reports it.  which_kernel: 0 = the projection-side launches, in the
+ * order the call enqueues them: the launches of the staged kernel (a set of up to 16 inputs per stage), or, for a
+ * call that runs every stage once over descriptor tables, its three timed launches (partial projections; shares of
+ * c^T E c; image rows with gates and residuals -- the coefficient sums in between are not counted), or the fused
+ * kernel of inputs with GSI_INPUT_FUSED_KERNEL; 1 = the weight-streaming launches (rows of W of the fired inputs'
+ * maps).  launch_index counts the launches of that kind from 0.  If the call makes fewer launches of that kind
+ * (always so for B != 1) it is still enqueued in full, the events are not recorded and GSI_ERR_SHAPE is returned. */
 int gsi_layer_stack_timed(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_desc* inputs, int32_t n_inputs,
                           int64_t B, float eps, void* ws, size_t ws_bytes, void* stream, int which_kernel,
                           int launch_index, void* ev_begin, void* ev_end);

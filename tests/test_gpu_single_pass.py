@@ -356,3 +356,58 @@ def test_single_pass_with_fp8_images_chain_and_static_entry(gsi, pu):
             assert torch.equal(x[key], y[key]), key
     for x, y in zip(a.maps_t, b.maps_t):
         assert torch.equal(x["Y"], y["Y"])
+
+
+def test_table_launches_full_size_in_the_bench_configuration(gsi, pu):
+    """Five full-size GPT-J-shaped blocks (20 inputs, 30 maps, 2 GB of W, k = 256) in ONE call per token, the way
+    bench.py times its 32 layers: single-pass gate, plans built once per token, the plans' launches captured in a HIP
+    graph and replayed.  Every gate decision is checked against the design; the first and the last block are checked
+    against the oracle in full (projection, ratio, image, outputs)."""
+    L, T, k = 5, 3, 256
+    blocks = [wl.gptj_block(T=T, k=k, fire_rate=0.34, seed=wl.BASE_SEED + 1000 + 17 * l) for l in range(L)]
+    eps = blocks[0].eps
+    inputs, maps, names, dgs_all = [], [], [], []
+    for l, w in enumerate(blocks):
+        dgs, bi, bm, nm = _stack(gsi, pu, w, gsi.INPUT_GATE_SINGLE_PASS)
+        base = len(inputs)
+        inputs += bi
+        maps += [dict(m, input_id=m["input_id"] + base) for m in bm]
+        names += [(base + gi, l, name) for gi, name in nm]
+        dgs_all.append(dgs)
+    say(f"case table launches at full size: {len(inputs)} inputs / {len(maps)} maps, k={k}")
+    st = gsi.LayerStack(inputs, maps, T, eps)
+    for ti in st.inputs_t:
+        ti["R"].fill_(SENTINEL)
+    plans = []
+    for t in range(T):
+        st.refresh(token_offset=t, B=1)
+        plans.append(st.build_plan())
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        st.run_plan(plans[0][0], stream=side)  # (kernels loaded before the capture)
+    torch.cuda.current_stream().wait_stream(side)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        for t in range(T):
+            st.run_plan(plans[t][0])
+    for _ in range(2):
+        g.replay()
+    torch.cuda.synchronize()
+    for l, w in enumerate(blocks):
+        for gi, grp in enumerate(w.groups):
+            ti = st.inputs_t[4 * l + gi]
+            assert np.array_equal(ti["mask"].cpu().numpy().astype(bool), grp.fired_design), (l, gi)
+    for l in (0, L - 1):
+        w = blocks[l]
+        for gi, (grp, dg) in enumerate(zip(w.groups, dgs_all[l])):
+            say(f"  block {l} input {grp.name}: d={grp.d}")
+            og, ref, mask = _check_input(gsi, pu, w, grp, dg, st.inputs_t[4 * l + gi], False)
+            for j, (ii, ll, name) in enumerate(names):
+                if ii == 4 * l + gi:
+                    pu.check_image(gsi.bits_of(dg.M[name]), og.M[name], og.W[name], og.U, w.wdtype)
+                    e, es = pu.check_outputs(st.maps_t[j]["Y"], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
+                    say(f"    map {name}: rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
+            del og
