@@ -824,8 +824,20 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
 
-  std::vector<size_t> ws_off(n_inputs, 0);
-  std::vector<float*> part(n_maps, nullptr);
+  // Bookkeeping of the call lives in thread-local vectors that keep their capacity from call to call: after the
+  // first call of a thread the enqueue path allocates no host memory for them.
+  struct Scratch {
+    std::vector<size_t> ws_off;
+    std::vector<float*> part;
+    std::vector<int> mode, mode_separate, part_ncb, ready, mready;
+    std::vector<gsi::ProjTask> ptask;
+    std::vector<char> map_fused, in_done, map_done, img_done, gate_inline;
+  };
+  static thread_local Scratch sc;
+  std::vector<size_t>& ws_off = sc.ws_off;
+  std::vector<float*>& part = sc.part;
+  ws_off.assign(n_inputs, 0);
+  part.assign(n_maps, nullptr);
   {
     size_t off = stack_table_bytes(n_maps, n_inputs, B);
     for (int i = 0; i < n_inputs; ++i) {
@@ -871,8 +883,10 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // that kernel).  kVecGate: vector projection kernels followed by the fused norm + gate kernel.
   // kGeneric: generic projection kernels and the stand-alone gate kernel.
   enum { kGeneric = 0, kVecGate = 1, kVecInline = 2 };
-  std::vector<int> mode(n_inputs, kGeneric);
-  std::vector<gsi::ProjTask> ptask(n_inputs);
+  std::vector<int>& mode = sc.mode;
+  std::vector<gsi::ProjTask>& ptask = sc.ptask;
+  mode.assign(n_inputs, kGeneric);
+  ptask.resize(n_inputs);
   for (int i = 0; i < n_inputs; ++i) {
     const gsi_input_desc& in = inputs[i];
     std::memset(&ptask[i], 0, sizeof(gsi::ProjTask));
@@ -919,8 +933,10 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
   // Single token: an input that asks for the fused kernel (GSI_INPUT_FUSED_KERNEL; gsi_fused.hip) and whose
   // basis, activations and maps all suit it is processed, with its maps, by that kernel alone.
   enum { kFusedMode = 3, kFusedDone = 4 };
-  const std::vector<int> mode_separate = mode;  // what the separate kernels would do with each input
-  std::vector<char> map_fused(n_maps, 0);
+  std::vector<int>& mode_separate = sc.mode_separate;  // what the separate kernels would do with each input
+  mode_separate = mode;
+  std::vector<char>& map_fused = sc.map_fused;
+  map_fused.assign(n_maps, 0);
   if (B == 1) {
     for (int i = 0; i < n_inputs; ++i) {
       const gsi_input_desc& in = inputs[i];
@@ -942,13 +958,19 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
 
   // Schedule in waves: an input is ready when its producer map has been enqueued, a map when its
   // input has.  Ready inputs (maps) of one dtype that take the same kernels share a launch.
-  std::vector<char> in_done(n_inputs, 0), map_done(n_maps, 0), img_done(n_maps, 0);
-  std::vector<char> gate_inline(n_inputs, 0);  // the weight kernel evaluates this input's gate
-  std::vector<int> part_ncb(n_inputs, 1);      // column blocks of this input's partial projection
+  std::vector<char>&in_done = sc.in_done, &map_done = sc.map_done, &img_done = sc.img_done;
+  std::vector<char>& gate_inline = sc.gate_inline;  // the weight kernel evaluates this input's gate
+  std::vector<int>& part_ncb = sc.part_ncb;         // column blocks of this input's partial projection
+  in_done.assign(n_inputs, 0);
+  map_done.assign(n_maps, 0);
+  img_done.assign(n_maps, 0);
+  gate_inline.assign(n_inputs, 0);
+  part_ncb.assign(n_inputs, 1);
   int remaining = n_inputs + n_maps;
   while (remaining > 0) {
     int progressed = 0;
-    std::vector<int> ready;
+    std::vector<int>& ready = sc.ready;
+    ready.clear();
     for (int i = 0; i < n_inputs; ++i)
       if (!in_done[i] && (inputs[i].src_map < 0 || map_done[inputs[i].src_map])) ready.push_back(i);
     // fused chunks: ready inputs of one dtype and rank are packed, with their maps, into chunks as long as a
@@ -1224,7 +1246,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       ++progressed;
     }
 
-    std::vector<int> mready;
+    std::vector<int>& mready = sc.mready;
+    mready.clear();
     for (int j = 0; j < n_maps; ++j)
       if (!map_done[j] && in_done[maps[j].input_id] == 1) mready.push_back(j);
     // single token, more inputs or maps than one launch's arguments describe: one weight-streaming launch over
