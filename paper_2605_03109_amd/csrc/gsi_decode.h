@@ -33,6 +33,7 @@ struct ProjTask {
   int32_t* n_fired;
   float* part_c;       // [a_slabs][B][k]  partial projections, one per row slab
   float* part_n;       // [b_slabs][B][2]  partial |r|^2, |x|^2, one per residual slab
+  unsigned* sync;      // decode batch on the matrix cores: finished residual workgroups of this input
   int d, k;
   int a_rows, a_slabs, a_cblocks;  // partial projection: rows per slab, slabs, column blocks
   int b_rows, b_slabs;             // residual: rows per slab, slabs
@@ -49,7 +50,10 @@ struct ProjBatch {
   int b_begin[kMaxTasks];  // ... in the residual launch
   int n, B;
   int b_total;             // workgroups of the residual launch that are residual slabs
+  int norms, gate;         // decode batch on the matrix cores: the residual launch finishes with the norms (+ gate)
+  float eps;
 };
+static_assert(sizeof(ProjBatch) <= 4096, "kernel arguments are limited to 4 KB");
 
 // One image map y = M c of a single-token launch (gsi_image.h)
 struct ImgTask {

@@ -98,9 +98,10 @@ __global__ __launch_bounds__(kTBlock) void tile_rows(const LinBatch lb) {
   const int li = lane & 15, lq = lane >> 4;
   const int B = lb.B;
 
-  // item -> (map, kind, row block, column slice).  Items of the weight term come first (they are the long
-  // ones), then the image items.
-  const bool second = (int)blockIdx.x >= lb.tile_split;
+  // item -> (map, kind, row block, column slice).  The image items come first: they are few and always have work,
+  // and behind the weight items of a step in which nothing fired (which only read a count and leave) they would
+  // wait for two rounds of empty workgroups to drain.
+  const bool second = (int)blockIdx.x < lb.tile_split;
   const int ti = second ? find_task(lb.blk_begin2, lb.n, blockIdx.x) : find_task(lb.blk_begin, lb.n, blockIdx.x);
   const LinTask& p = lb.t[ti];
   const LinGroup& g = lb.g[p.group];
@@ -267,6 +268,7 @@ __global__ __launch_bounds__(kPBlock) void tile_proj_partial(const ProjBatch pb)
   // (workgroups go to the 8 XCDs in turn), and so is the residual workgroup of the same rows
   const int slab = local % p.a_slabs, cg = local / p.a_slabs;
   const int d = p.d, k = p.k, B = pb.B;
+  if (local == 0 && threadIdx.x == 0) *p.sync = 0u;  // the residual launch counts its finished workgroups here
   const int row_begin = slab * p.a_rows;
   const int steps = (min(p.a_rows, d - row_begin)) / kStepCols;  // 1..4: d and a_rows are multiples of 32
   const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
@@ -362,16 +364,17 @@ __global__ __launch_bounds__(kPBlock) void tile_proj_partial(const ProjBatch pb)
   }
 }
 
-// C[t][j] = sum over slabs of the partial projections.  Four threads share an output (each adds a quarter
-// of the slabs in order, the four sums are then added in order): fixed order, a few memory round trips.
+// C[t][j] = sum over slabs of the partial projections.  Sixteen threads share an output (each adds a sixteenth
+// of the slabs in order, the sixteen sums are then added in order): fixed order, one or two memory round trips.
+constexpr int kRedParts = 16, kRedOut = 256 / kRedParts;
 __global__ __launch_bounds__(256) void tile_proj_reduce(const ProjBatch pb) {
-  __shared__ float4 red[4][64];
+  __shared__ float4 red[kRedParts][kRedOut];
   const ProjTask& p = pb.t[blockIdx.y];
   const int B = pb.B, k4 = p.k >> 2;
-  const int el = threadIdx.x & 63, part = threadIdx.x >> 6;
-  const int e = blockIdx.x * 64 + el;
+  const int el = threadIdx.x % kRedOut, part = threadIdx.x / kRedOut;
+  const int e = blockIdx.x * kRedOut + el;
   const bool live = e < B * k4;
-  const int per = (p.a_slabs + 3) >> 2;
+  const int per = (p.a_slabs + kRedParts - 1) / kRedParts;
   const int s_begin = part * per, s_end = min(p.a_slabs, s_begin + per);
   const float4* src = reinterpret_cast<const float4*>(p.part_c) + (live ? e : 0);
   const int64_t stride = (int64_t)B * k4;
@@ -389,7 +392,7 @@ __global__ __launch_bounds__(256) void tile_proj_reduce(const ProjBatch pb) {
   if (part == 0 && live) {
     float4 t = red[0][el];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < kRedParts; ++w) {
       const float4 q = red[w][el];
       t.x += q.x; t.y += q.y; t.z += q.z; t.w += q.w;
     }
@@ -397,9 +400,68 @@ __global__ __launch_bounds__(256) void tile_proj_reduce(const ProjBatch pb) {
   }
 }
 
+// |r|, |x| per token from the row blocks' shares, then the gate and the ordered list of fired tokens
+// (Eq. (gate); Algorithm 1, line 4), by the 512 threads of one workgroup.  16 threads share a token (4 beyond
+// 32 tokens): each adds its part of the shares in order, the part sums are then added in order.
+// red: 512 float2 and two ints of LDS.
+__device__ __forceinline__ void norms_and_gate(const ProjTask& p, int B, int do_gate, float eps, float2* red,
+                                               int* wave_count) {
+  const int slots = B <= 32 ? 32 : kMaxTok, parts = kTBlock / slots;
+  const int t = threadIdx.x % slots, part = threadIdx.x / slots;
+  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
+  const int per = (p.b_slabs + parts - 1) / parts;
+  const int s_begin = part * per, s_end = min(p.b_slabs, s_begin + per);
+  float sr = 0.f, sx = 0.f;
+  const float2* src = reinterpret_cast<const float2*>(p.part_n) + min(t, B - 1);
+  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
+    unsigned long long q[8];  // (|r|^2, |x|^2) shares, read past the caches: other workgroups of this launch wrote them
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      q[u] = __hip_atomic_load(reinterpret_cast<const unsigned long long*>(src + (int64_t)min(s0 + u, p.b_slabs - 1) * B),
+                               __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+    for (int u = 0; u < 8; ++u)
+      if (s0 + u < s_end) { sr += __uint_as_float((unsigned)q[u]); sx += __uint_as_float((unsigned)(q[u] >> 32)); }
+  }
+  red[part * slots + t] = float2{sr, sx};
+  __syncthreads();
+  // the threads of part 0 (thread index = token) finish the job; the others only keep the barriers
+  const bool head = part == 0;
+  sr = red[t].x;
+  sx = red[t].y;
+  for (int w = 1; w < parts; ++w) {
+    sr += red[w * slots + t].x;
+    sx += red[w * slots + t].y;
+  }
+  const float rn = sqrtf(sr), xn = sqrtf(sx);
+  if (head && t < B) {
+    p.rnorm[t] = rn;
+    p.xnorm[t] = xn;
+  }
+  if (!do_gate) return;  // uniform
+  const bool fired = head && t < B && gate_fires(rn, xn, eps);
+  if (head && t < B) p.mask[t] = fired ? 1 : 0;
+  const unsigned long long ballot = __ballot(fired);
+  const int rank_in_wave = __popcll(ballot & ((1ull << lane) - 1ull));
+  if (wave < kMaxTok / kWave && lane == 0) wave_count[wave] = __popcll(ballot);
+  __syncthreads();
+  int before = 0, total = 0;
+#pragma unroll
+  for (int wv = 0; wv < kMaxTok / kWave; ++wv) {
+    const int c = wave_count[wv];
+    if (wv < wave) before += c;
+    total += c;
+  }
+  if (fired) p.fired_idx[before + rank_in_wave] = t;
+  if (threadIdx.x == 0) p.n_fired[0] = total;
+}
+
 // r = x - U c for 128 rows x 32 tokens per workgroup (the weights of this product are the rows of U, which are
 // contiguous: same operand flow as tile_rows), R written, and the row block's share of |r|^2 and |x|^2.
+// The workgroup of an input that finishes last (a counter in the workspace, zeroed by the partial-projection
+// launch) turns the shares into the norms, the gate decisions and the list of fired tokens: no launch of its own.
 __global__ __launch_bounds__(kTBlock) void tile_residual(const ProjBatch pb) {
+  __shared__ int s_last;
   __shared__ __align__(16) uint16_t vhi[kRoundTok][kVRow];
   __shared__ __align__(16) uint16_t vlo[kRoundTok][kVRow];
   __shared__ float red[kTWaves][kRoundTok][2];
@@ -490,64 +552,22 @@ __global__ __launch_bounds__(kTBlock) void tile_residual(const ProjBatch pb) {
       float sum = 0.f;
 #pragma unroll
       for (int wv = 0; wv < kTWaves; ++wv) sum += red[wv][tl][c];
-      p.part_n[((int64_t)rb * B + g0 + tl) * 2 + c] = sum;
+      // written through to memory (a store that is coherent across the chip), so that the workgroup that finishes
+      // last can read it without anybody writing a whole L2 back: such a write-back costs about a microsecond per
+      // workgroup, one after the other
+      __hip_atomic_store(&p.part_n[((int64_t)rb * B + g0 + tl) * 2 + c], sum, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     }
   }
-}
-
-// |r|, |x| per token from the row blocks' shares, then the gate and the ordered list of fired tokens
-// (Eq. (gate); Algorithm 1, line 4).  One workgroup per input; eight threads share a token (each adds an
-// eighth of the shares in order, the eight sums are then added in order).
-__global__ __launch_bounds__(8 * kMaxTok) void tile_norms(const ProjBatch pb, int do_gate, float eps) {
-  __shared__ float2 red[8][kMaxTok];
-  __shared__ int wave_count[kMaxTok / kWave];
-  const ProjTask& p = pb.t[blockIdx.x];
-  const int B = pb.B, t = threadIdx.x & (kMaxTok - 1), part = threadIdx.x >> 7;
-  const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int per = (p.b_slabs + 7) >> 3;
-  const int s_begin = part * per, s_end = min(p.b_slabs, s_begin + per);
-  float sr = 0.f, sx = 0.f;
-  const float2* src = reinterpret_cast<const float2*>(p.part_n) + min(t, B - 1);
-  for (int s0 = s_begin; s0 < s_end; s0 += 8) {
-    float2 q[8];
-#pragma unroll
-    for (int u = 0; u < 8; ++u) q[u] = src[(int64_t)min(s0 + u, p.b_slabs - 1) * B];
-#pragma unroll
-    for (int u = 0; u < 8; ++u)
-      if (s0 + u < s_end) { sr += q[u].x; sx += q[u].y; }
+  if (!pb.norms) return;  // uniform
+  asm volatile("s_waitcnt vmcnt(0)" ::: "memory");  // the stores have completed ...
+  __syncthreads();                                  // ... in every wave before the workgroup counts as done
+  if (threadIdx.x == 0) {
+    const unsigned done = __hip_atomic_fetch_add(p.sync, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = done + 1u == (unsigned)(nrb * rounds);
   }
-  red[part][t] = float2{sr, sx};
   __syncthreads();
-  // the threads of part 0 (waves 0 and 1, tokens 0..127) finish the job; the others only keep the barriers
-  const bool head = part == 0;
-  sr = red[0][t].x;
-  sx = red[0][t].y;
-#pragma unroll
-  for (int w = 1; w < 8; ++w) {
-    sr += red[w][t].x;
-    sx += red[w][t].y;
-  }
-  const float rn = sqrtf(sr), xn = sqrtf(sx);
-  if (head && t < B) {
-    p.rnorm[t] = rn;
-    p.xnorm[t] = xn;
-  }
-  if (!do_gate) return;  // uniform
-  const bool fired = head && t < B && gate_fires(rn, xn, eps);
-  if (head && t < B) p.mask[t] = fired ? 1 : 0;
-  const unsigned long long ballot = __ballot(fired);
-  const int rank_in_wave = __popcll(ballot & ((1ull << lane) - 1ull));
-  if (head && lane == 0) wave_count[wave] = __popcll(ballot);
-  __syncthreads();
-  int before = 0, total = 0;
-#pragma unroll
-  for (int wv = 0; wv < kMaxTok / kWave; ++wv) {
-    const int c = wave_count[wv];
-    if (wv < wave) before += c;
-    total += c;
-  }
-  if (fired) p.fired_idx[before + rank_in_wave] = t;
-  if (threadIdx.x == 0) p.n_fired[0] = total;
+  if (!s_last) return;  // uniform
+  norms_and_gate(p, B, pb.gate, pb.eps, reinterpret_cast<float2*>(&vhi[0][0]), reinterpret_cast<int*>(&vlo[0][0]));
 }
 
 }  // namespace
@@ -564,7 +584,7 @@ static int tile_slab_rows(int64_t) { return kPSteps * kStepCols; }
 
 size_t tile_project_ws(int64_t d, int64_t k, int64_t B) {
   const int a_slabs = (int)ceil_div(d, tile_slab_rows(d));
-  return align_up((size_t)a_slabs * B * k * 4, 256) + align_up((size_t)(d / kItemRows) * B * 2 * 4, 256);
+  return align_up((size_t)a_slabs * B * k * 4, 256) + align_up((size_t)(d / kItemRows) * B * 2 * 4, 256) + 256;
 }
 
 void tile_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws) {
@@ -577,6 +597,7 @@ void tile_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws) {
   t.b_slabs = (int)(d / kItemRows);
   t.part_c = reinterpret_cast<float*>(ws);
   t.part_n = reinterpret_cast<float*>(reinterpret_cast<char*>(ws) + align_up((size_t)t.a_slabs * B * k * 4, 256));
+  t.sync = reinterpret_cast<unsigned*>(reinterpret_cast<char*>(t.part_n) + align_up((size_t)t.b_slabs * B * 2 * 4, 256));
   t.tile = 1;
 }
 
@@ -592,13 +613,15 @@ hipError_t tile_project_launch(ProjBatch& pb, bool with_norms, bool with_gate, f
     if (pb.t[i].k > max_k) max_k = pb.t[i].k;
   }
   pb.b_total = tb;
+  pb.norms = with_norms ? 1 : 0;
+  pb.gate = with_gate ? 1 : 0;
+  pb.eps = eps;
   if (pb.B <= 32) tile_proj_partial<1><<<ta, kPBlock, 0, s>>>(pb);
   else if (pb.B <= 64) tile_proj_partial<2><<<ta, kPBlock, 0, s>>>(pb);
   else tile_proj_partial<4><<<ta, kPBlock, 0, s>>>(pb);
-  const dim3 rgrid((unsigned)ceil_div((int64_t)pb.B * (max_k / 4), 64), (unsigned)pb.n);
+  const dim3 rgrid((unsigned)ceil_div((int64_t)pb.B * (max_k / 4), kRedOut), (unsigned)pb.n);
   tile_proj_reduce<<<rgrid, 256, 0, s>>>(pb);
   tile_residual<<<tb, kTBlock, 0, s>>>(pb);
-  if (with_norms) tile_norms<<<pb.n, 8 * kMaxTok, 0, s>>>(pb, with_gate ? 1 : 0, eps);
   return hipGetLastError();
 }
 
@@ -633,15 +656,15 @@ bool tile_rows_ok(const LinBatch& lb, int wdtype) {
 hipError_t tile_rows_launch(LinBatch& lb, hipStream_t s) {
   int total = 0, max_m = 0;
   for (int i = 0; i < lb.n; ++i) {
+    lb.blk_begin2[i] = total;
+    if (!lb.dense) total += (int)(ceil_div(lb.t[i].m, kItemRows) * ceil_div(lb.B, kRoundTok));
+  }
+  lb.tile_split = total;  // image items below, weight items from here on
+  for (int i = 0; i < lb.n; ++i) {
     lb.t[i].slices = tile_slices(lb.g[lb.t[i].group].d);
     lb.blk_begin[i] = total;
     total += (int)ceil_div(lb.t[i].m, kItemRows) * lb.t[i].slices;
     if (lb.t[i].m > max_m) max_m = lb.t[i].m;
-  }
-  lb.tile_split = total;
-  for (int i = 0; i < lb.n; ++i) {
-    lb.blk_begin2[i] = total;
-    if (!lb.dense) total += (int)(ceil_div(lb.t[i].m, kItemRows) * ceil_div(lb.B, kRoundTok));
   }
   tile_rows<<<total, kTBlock, 0, s>>>(lb);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
