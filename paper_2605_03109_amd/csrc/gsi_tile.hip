@@ -204,8 +204,12 @@ __global__ __launch_bounds__(kTBlock) void tile_rows(const LinBatch lb) {
   }
 }
 
-// Y[token j] (+)= sum over column slices, in slice order, of the partial products of the weight term
+// Y[token j] (+)= sum over column slices of the partial products of the weight term.  Four threads share an
+// output (each adds a quarter of the slices in order, the four sums are then added in order): fixed order, and
+// one memory round trip up to 32 slices.
+constexpr int kSumParts = 4, kSumOut = 256 / kSumParts;
 __global__ __launch_bounds__(256) void tile_reduce(const LinBatch lb) {
+  __shared__ float4 red[kSumParts][kSumOut];
   const LinTask& p = lb.t[blockIdx.y];
   const LinGroup& g = lb.g[p.group];
   const int B = lb.B, m = p.m;
@@ -215,19 +219,31 @@ __global__ __launch_bounds__(256) void tile_reduce(const LinBatch lb) {
     count = nf < 0 ? 0 : (nf > B ? B : nf);
   }
   const int m4 = m >> 2;
-  const int64_t e = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  if (e >= (int64_t)count * m4) return;
-  const int j = (int)(e / m4), r4 = (int)(e - (int64_t)j * m4);
+  if ((int64_t)blockIdx.x * kSumOut >= (int64_t)count * m4) return;  // uniform
+  const int el = threadIdx.x % kSumOut, part = threadIdx.x / kSumOut;
+  const int64_t e = (int64_t)blockIdx.x * kSumOut + el;
+  const bool live = e < (int64_t)count * m4;
+  const int j = live ? (int)(e / m4) : 0, r4 = live ? (int)(e - (int64_t)j * m4) : 0;
   const float4* src = reinterpret_cast<const float4*>(p.part + (int64_t)j * m) + r4;
   const int64_t slice_stride = (int64_t)B * m4;
+  const int per = (p.slices + kSumParts - 1) / kSumParts;
+  const int s_begin = part * per, s_end = min(p.slices, s_begin + per);
   float4 s = float4{0.f, 0.f, 0.f, 0.f};
-  for (int k0 = 0; k0 < p.slices; k0 += 8) {  // eight requests in flight; the sum keeps slice order
+  for (int k0 = s_begin; k0 < s_end; k0 += 8) {  // eight requests in flight; the sum keeps slice order
     float4 q[8];
 #pragma unroll
     for (int u = 0; u < 8; ++u) q[u] = src[min(k0 + u, p.slices - 1) * slice_stride];
 #pragma unroll
     for (int u = 0; u < 8; ++u)
-      if (k0 + u < p.slices) { s.x += q[u].x; s.y += q[u].y; s.z += q[u].z; s.w += q[u].w; }
+      if (k0 + u < s_end) { s.x += q[u].x; s.y += q[u].y; s.z += q[u].z; s.w += q[u].w; }
+  }
+  red[part][el] = s;
+  __syncthreads();
+  if (part != 0 || !live) return;
+#pragma unroll
+  for (int w = 1; w < kSumParts; ++w) {
+    const float4 q = red[w][el];
+    s.x += q.x; s.y += q.y; s.z += q.z; s.w += q.w;
   }
   int tok = j;
   if (!lb.dense) tok = min(max(g.fired_idx[j], 0), B - 1);
@@ -668,7 +684,7 @@ hipError_t tile_rows_launch(LinBatch& lb, hipStream_t s) {
   }
   tile_rows<<<total, kTBlock, 0, s>>>(lb);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  const dim3 grid((unsigned)ceil_div((int64_t)lb.B * (max_m / 4), 256), (unsigned)lb.n);
+  const dim3 grid((unsigned)ceil_div((int64_t)lb.B * (max_m / 4), kSumOut), (unsigned)lb.n);
   tile_reduce<<<grid, 256, 0, s>>>(lb);
   return hipGetLastError();
 }
