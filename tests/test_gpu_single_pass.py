@@ -411,3 +411,76 @@ def test_table_launches_full_size_in_the_bench_configuration(gsi, pu):
                     e, es = pu.check_outputs(st.maps_t[j]["Y"], og.W[name], og.M[name], gsi.bits_of(dg.M[name]), w.wdtype, ref, mask)
                     say(f"    map {name}: rel-L2 vs exact-image oracle {e:.3e}, vs stored-image oracle {es:.3e}")
             del og
+
+
+@pytest.mark.parametrize("reps,every_input_single_pass", [(3, False), (5, True)])
+def test_mixed_shapes_dtypes_and_gates_in_one_single_token_call(gsi, pu, reps, every_input_single_pass):
+    """One call per token over 27 (45) inputs of unlike shapes, storage types and options (single-pass and explicit
+    gate, both forms of the slow path, shapes that only the generic kernels take): the call sorts them into its
+    launches by itself, and every input and map is checked against the oracle on its own.  With the single-pass gate
+    on every input the bf16 ones are more than one launch's arguments describe and run over the descriptor table."""
+    T = 6
+    shapes = [  # d, k, m, wdtype, xdtype
+        (512, 64, 520, "bf16", "f32"), (1024, 128, 264, "bf16", "bf16"), (776, 72, 100, "f32", "f32"),
+        (33, 7, 10, "f32", "f32"), (2048, 256, 512, "bf16", "f32"), (4096, 64, 1032, "bf16", "f32"),
+        (768, 64, 3072, "f32", "f32"), (256, 8, 64, "bf16", "f32"), (1536, 192, 384, "bf16", "f32"),
+    ]
+    cases = []
+    for rep in range(reps):
+        for si, (d, k, m, wdt, xdt) in enumerate(shapes):
+            n = len(cases)
+            flags = [gsi.INPUT_GATE_SINGLE_PASS, 0, gsi.INPUT_GATE_SINGLE_PASS | gsi.INPUT_SLOW_PATH_WX,
+                     gsi.INPUT_SLOW_PATH_WX][(rep + si) % 4]
+            if every_input_single_pass:
+                flags |= gsi.INPUT_GATE_SINGLE_PASS
+            w = wl.tiny(d, k, m, T, n_fired=(n % 3) + 1, seed=4700 + n, wdtype=wdt, xdtype=xdt)
+            cases.append((w, flags))
+    eps = cases[0][0].eps
+    inputs, maps, dgs = [], [], []
+    for gi, (w, flags) in enumerate(cases):
+        dg = pu.DeviceGroup(w, w.groups[0])
+        dgs.append(dg)
+        inputs.append({"U": dg.U, "X": dg.X, "flags": flags,
+                       "gram": gsi.build_gram(dg.U) if flags & gsi.INPUT_GATE_SINGLE_PASS else None})
+        maps.append({"W": dg.W["w"], "M": dg.M["w"], "input_id": gi})
+    say(f"case mixed call: {len(inputs)} inputs")
+    st = gsi.LayerStack(inputs, maps, T, eps)
+    st.refresh(token_offset=0, B=1)
+    st.ws.fill_(0xFF)
+    for ti in st.inputs_t:
+        ti["R"].fill_(SENTINEL)
+    for rep in range(2):
+        _run_tokens(st, T)
+    skipped = 0
+    for gi, (w, flags) in enumerate(cases):
+        g = w.groups[0]
+        say(f"  input {gi}: d={g.d} k={g.k} {w.wdtype}/{w.xdtype} flags={flags}")
+        og = pu.OracleGroup(w, g)
+        ref = og.run()
+        ti = st.inputs_t[gi]
+        mask_dev = ti["mask"].cpu().numpy()
+        fired = mask_dev.astype(bool)
+        wx = bool(flags & gsi.INPUT_SLOW_PATH_WX)
+        R = ti["R"].cpu().numpy()
+        # rows of R the call left alone: allowed for tokens that need no residual under the single-pass gate
+        untouched = np.all(R == SENTINEL, axis=1)
+        if flags & gsi.INPUT_GATE_SINGLE_PASS:
+            assert not np.any(untouched & fired & (not wx)), "a fired token has no residual"
+            skipped += int(untouched.sum())
+        else:
+            assert not untouched.any(), "the explicit gate forms every residual"
+        Rchk = ti["R"].clone()
+        Rchk[torch.from_numpy(untouched)] = torch.from_numpy(ref["R"][untouched].astype(np.float32)).to(Rchk.device)
+        res = dict(C=ti["C"], R=Rchk, rnorm=ti["rnorm"], xnorm=ti["xnorm"], mask=ti["mask"],
+                   n_fired=torch.tensor([int(mask_dev.sum())], dtype=torch.int32),
+                   fired_idx=torch.from_numpy(np.nonzero(mask_dev)[0].astype(np.int32)))
+        mask = pu.check_projection(res, ref, eps)
+        assert np.array_equal(mask.astype(bool), g.fired_design)
+        Y = st.maps_t[gi]["Y"]
+        if wx:
+            Mdev = O.widen(gsi.bits_of(dgs[gi].M["w"]), w.wdtype)
+            e = pu.rel_l2_rows(Y.cpu().numpy().astype(np.float64), O.gated_linear_alg1(og.W["w"], Mdev, ref["C"], og.X, mask))
+            assert e.max() <= pu.TOL_Y_STAGE[w.wdtype], e.max()
+        else:
+            pu.check_outputs(Y, og.W["w"], og.M["w"], gsi.bits_of(dgs[gi].M["w"]), w.wdtype, ref, mask)
+    assert skipped > 0, "no input took the single-pass gate"
