@@ -1,7 +1,7 @@
 // Gate of Eq. (gate) / Algorithm 1 line 4 with order-preserving stream compaction on the device.
 //
-// One workgroup walks the B tokens in chunks of 256.  Per chunk: every lane decides its token,
-// wave ballots give the in-wave rank, a 4-entry LDS table gives the rank of the wave, and a running
+// One workgroup walks the B tokens in chunks of 1024.  Per chunk: every lane decides its token,
+// wave ballots give the in-wave rank, a 16-entry LDS table gives the rank of the wave, and a running
 // base carries the count across chunks.  The fired list therefore comes out in ascending token
 // order without atomics, and the count is written last.
 #include "gsi_device.h"
@@ -10,7 +10,7 @@
 namespace gsi {
 namespace {
 
-constexpr int kBlock = 256;
+constexpr int kBlock = 1024;
 constexpr int kWaves = kBlock / kWave;
 
 __global__ __launch_bounds__(kBlock) void gate_kernel(const float* __restrict__ rnorm,
