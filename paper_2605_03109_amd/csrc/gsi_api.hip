@@ -205,7 +205,8 @@ int gsi_extend_basis(void* U, int64_t d, int64_t K, int udtype, int32_t* k_cur, 
   for (int j = 0; j < n_maps; ++j) {
     if (!maps[j].W) return fail(GSI_ERR_NULL, "%s: maps[%d].W is NULL", fn, j);
     if (!maps[j].M) return fail(GSI_ERR_NULL, "%s: maps[%d].M is NULL", fn, j);
-    if (maps[j].m < 1) return fail(GSI_ERR_SHAPE, "%s: maps[%d].m = %lld < 1", fn, j, (long long)maps[j].m);
+    if (maps[j].m < 1 || maps[j].m > (1ll << 30))
+      return fail(GSI_ERR_SHAPE, "%s: maps[%d].m = %lld out of range", fn, j, (long long)maps[j].m);
     if (!aligned(maps[j].W, es) || !aligned(maps[j].M, es))
       return fail(GSI_ERR_ALIGN, "%s: maps[%d] is not aligned to its element size", fn, j);
     em[j] = gsi::ExtMap{maps[j].W, maps[j].M, maps[j].m};

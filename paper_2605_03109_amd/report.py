@@ -9,6 +9,9 @@ block at batch-1 decode):
   --config 4   prefill-sized batch (T = 2048, k = 512, 20 % of the tokens fired) over the six maps of a
                block, and the six one-time image builds: time, TFLOP/s on the matrix cores, speedup over
                the dense product with the same kernels
+  --config 5   online basis maintenance: gsi_extend_basis on the inputs of a block (a basis array with spare
+               columns, its maps' images and E kept up to date): time per call for tokens that extend the
+               basis and for tokens that do not
 
 One JSON object per run on stdout, progress on stderr.  Inputs are seeded and synthetic (workload_device.py);
 they stand in for the paper's models and its 512-token text.  Every step of the path runs in libgsi; torch
@@ -372,11 +375,85 @@ def run_prefill(args, torch, gsi, wd):
             "image_build_TFLOPs": round(build_flops / total_build_ms / 1e9, 1)}
 
 
+
+# ------------------------------------------------------------------------------------------------------
+# config 5: online basis maintenance (one rank-1 extension per call)
+# ------------------------------------------------------------------------------------------------------
+def run_extend(args, torch, gsi, wd):
+    """gsi_extend_basis at the shapes of a GPT-J block: a basis array of capacity 2k holding k columns, the maps that
+    read it, E kept up to date; time per call for tokens that extend the basis and for tokens that do not."""
+    dev = torch.device("cuda:0")
+    gen = wd.generator(2605_03109 + 5000)
+    steps = args.steps
+    k0 = 256
+    K = k0 + 2 * steps
+    K += (-K) % 64
+    rows = []
+    for name, d, ms in (("q,k,v input", 4096, (4096, 4096, 4096)), ("fc_in input", 4096, (16384,)),
+                        ("fc_out input", 16384, (4096,))):
+        U64 = wd.make_basis64(d, k0, gen)
+        U = torch.zeros((d, K), dtype=torch.bfloat16, device=dev)
+        U[:, :k0] = U64.to(torch.bfloat16)
+        U0 = U.clone()
+        Ws = [wd.make_weight(m, d, gen) for m in ms]
+        Ms = [gsi.build_image(W, U) for W in Ws]
+        E = gsi.build_gram(U)
+        R = torch.randn((steps, d), generator=gen, device=dev, dtype=torch.float32)
+        R /= R.norm(dim=1, keepdim=True)
+        rnorm = torch.full((1,), 0.3, device=dev)
+        xnorm = torch.ones((1,), device=dev)
+        k_cur = torch.full((1,), k0, dtype=torch.int32, device=dev)
+        ext = torch.zeros((1,), dtype=torch.int32, device=dev)
+        ws = torch.empty(int(gsi.lib.gsi_extend_basis_workspace_bytes(d, K)) + 256, dtype=torch.uint8, device=dev)
+        pairs = list(zip(Ws, Ms))
+        w_bytes = sum(m * d * 2 for m in ms)
+        # what one extension must move: U for s = U^T r, for r2 = r - U s and for E's new row, W once per map
+        alg_bytes = 3 * d * K * 2 + w_bytes
+        res = {"input": name, "d": d, "capacity_K": K, "columns_at_start": k0, "maps_m": list(ms), "calls": steps,
+               "algorithmic_MB_per_extension": round(alg_bytes / 1e6, 1)}
+        for label, tau in (("extending", 0.2), ("not_extending", 0.5)):
+            def call(t, stream):
+                gsi.extend_basis(U, k_cur, R[t], rnorm, xnorm, tau, pairs, gram=E, extended=ext, ws=ws, stream=stream)
+            side = torch.cuda.Stream()
+            side.wait_stream(torch.cuda.current_stream())
+            with torch.cuda.stream(side):
+                call(0, side)
+            torch.cuda.current_stream().wait_stream(side)
+            torch.cuda.synchronize()
+            g = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(g):
+                cs = torch.cuda.current_stream()
+                for t in range(steps):
+                    call(t, cs)
+            best = None
+            for rep in range(3):
+                U.copy_(U0)
+                k_cur.fill_(k0)
+                torch.cuda.synchronize()
+                t0 = time.perf_counter()
+                g.replay()
+                torch.cuda.synchronize()
+                sec = time.perf_counter() - t0
+                best = sec if best is None else min(best, sec)
+            grown = int(k_cur.item()) - k0
+            us = best / steps * 1e6
+            res[label] = {"us_per_call": round(us, 2), "columns_added": grown}
+            if label == "extending":
+                res[label]["achieved_GBs"] = round(alg_bytes / us / 1e3, 1)
+                res[label]["frac_of_hbm_peak"] = round(alg_bytes / us / 1e3 / HBM_PEAK_GBS, 3)
+            log(f"[report] {name} {label}: {res[label]}")
+        rows.append(res)
+        del U, U0, Ws, Ms, E, R, ws
+        torch.cuda.empty_cache()
+    return {"config": 5, "workload": "gsi_extend_basis on GPT-J-block shapes, bf16, basis array of capacity K holding 256 "
+            "columns at the start, E kept; HIP-graph replay of `calls` consecutive calls, best of 3", "rows": rows}
+
+
 def main() -> int:
     ap = argparse.ArgumentParser(description=__doc__, formatter_class=argparse.RawDescriptionHelpFormatter)
-    ap.add_argument("--config", type=int, choices=[2, 3, 4], required=True)
+    ap.add_argument("--config", type=int, choices=[2, 3, 4, 5], required=True)
     ap.add_argument("--mode", choices=["graph", "eager"], default="graph")
-    ap.add_argument("--steps", type=int, default=None, help="decode steps (config 2: 512, config 3: 200) / repeats (config 4: 10)")
+    ap.add_argument("--steps", type=int, default=None, help="decode steps (config 2: 512, config 3: 200) / repeats (config 4: 10) / calls (config 5: 64)")
     ap.add_argument("--warmup", type=int, default=32)
     ap.add_argument("--layers", type=int, default=32)
     ap.add_argument("--ks", default="64,128,256,512")
@@ -388,7 +465,7 @@ def main() -> int:
     ap.add_argument("--xdtype", choices=["f32", "bf16"], default="bf16")
     args = ap.parse_args()
     if args.steps is None:
-        args.steps = {2: 512, 3: 200, 4: 10}[args.config]
+        args.steps = {2: 512, 3: 200, 4: 10, 5: 64}[args.config]
 
     import torch
 
@@ -399,7 +476,7 @@ def main() -> int:
         print("report.py: no GPU visible", file=sys.stderr)
         return 3
     torch.cuda.set_device(0)
-    fn = {2: run_opt_stack, 3: run_ragged, 4: run_prefill}[args.config]
+    fn = {2: run_opt_stack, 3: run_ragged, 4: run_prefill, 5: run_extend}[args.config]
     print(json.dumps(fn(args, torch, gsi, wd)), flush=True)
     return 0
 
