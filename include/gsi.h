@@ -140,6 +140,30 @@ int gsi_extend_basis(void* U, int64_t d, int64_t K, int udtype, int32_t* k_cur, 
                      int32_t* extended, void* ws, size_t ws_bytes, void* stream);
 size_t gsi_extend_basis_workspace_bytes(int64_t d, int64_t K);
 
+/* The same step for n bases in ONE set of launches (Section 5.4 "Time-dimension tracking": every basis of a model
+ * sees every token).  Each basis is extended exactly as gsi_extend_basis would extend it, bit for bit, on its own
+ * verdict; a token after which no basis grows costs seven nearly empty launches for the whole call instead of seven
+ * per basis.  descs: HOST array, one entry per basis with the arguments of gsi_extend_basis (maps: HOST array of
+ * n_maps entries, may be NULL when n_maps is 0; gram and extended may be NULL); all bases of a call share one
+ * udtype; n <= 65535 and at most 65535 maps in all.  tau as in gsi_extend_basis, one value for the call.
+ * ws: gsi_extend_many_workspace_bytes(descs, n) bytes, 256-byte aligned (the call copies its descriptor table there).
+ * Two bases of one call must not share U, k_cur, maps' M or gram. */
+typedef struct gsi_extend_desc {
+  void* U;                     /* [d,K] udtype, columns k_cur.. zero                      */
+  int64_t d, K;
+  int32_t udtype;
+  int32_t n_maps;
+  int32_t* k_cur;              /* device, [1]                                              */
+  const float* R;              /* device, [d]: residual of the token against this basis    */
+  const float* rnorm;          /* device, [1]                                              */
+  const float* xnorm;          /* device, [1]                                              */
+  const gsi_extend_map* maps;  /* HOST array of the maps that read this basis              */
+  float* gram;                 /* device, [K,K] or NULL                                    */
+  int32_t* extended;           /* device, [1] or NULL                                      */
+} gsi_extend_desc;
+int gsi_extend_many(const gsi_extend_desc* descs, int32_t n, float tau, void* ws, size_t ws_bytes, void* stream);
+size_t gsi_extend_many_workspace_bytes(const gsi_extend_desc* descs, int32_t n);
+
 /* Descriptors for gsi_layer_stack (host structs holding device pointers). */
 typedef struct gsi_input_desc {
   const void* U;      /* basis of this input, [d,k], udtype                                     */

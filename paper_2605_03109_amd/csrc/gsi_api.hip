@@ -178,43 +178,106 @@ size_t gsi_extend_basis_workspace_bytes(int64_t d, int64_t K) {
   return d >= 1 && K >= 1 ? gsi::extend_ws_bytes(d, K) : 0;
 }
 
+// argument checks of one basis of an extension call; appends its record and those of its maps
+static int add_extend_desc(const char* fn, int idx, const gsi_extend_desc& e, char* ws, std::vector<gsi::ExtIn>& ins,
+                           std::vector<gsi::ExtMapRec>& mps) {
+  if (!e.U || !e.k_cur || !e.R || !e.rnorm || !e.xnorm)
+    return fail(GSI_ERR_NULL, "%s: a pointer (U, k_cur, R, rnorm, xnorm) of basis %d is NULL", fn, idx);
+  if (!dtype_ok(e.udtype)) return fail(GSI_ERR_DTYPE, "%s: unknown udtype %d (basis %d)", fn, e.udtype, idx);
+  if (int rc = check_shape(fn, 1, e.d, e.K, 0)) return rc;
+  if (e.n_maps < 0) return fail(GSI_ERR_SHAPE, "%s: n_maps = %d < 0 (basis %d)", fn, e.n_maps, idx);
+  if (e.n_maps > 0 && !e.maps) return fail(GSI_ERR_NULL, "%s: maps of basis %d is NULL", fn, idx);
+  if (e.K > (int64_t)65535 * 64 || e.d > (1ll << 31) - 1)
+    return fail(GSI_ERR_SHAPE, "%s: d = %lld, K = %lld is too large (basis %d)", fn, (long long)e.d, (long long)e.K, idx);
+  const size_t es = gsi::elem_size(e.udtype);
+  if (!aligned(e.U, es) || !aligned(e.k_cur, 4) || !aligned(e.R, 4) || !aligned(e.rnorm, 4) || !aligned(e.xnorm, 4) ||
+      (e.gram && !aligned(e.gram, 4)) || (e.extended && !aligned(e.extended, 4)))
+    return fail(GSI_ERR_ALIGN, "%s: a pointer of basis %d is not aligned to its element size", fn, idx);
+  gsi::ExtIn in;
+  std::memset(&in, 0, sizeof(in));
+  in.U = e.U; in.R = e.R; in.rnorm = e.rnorm; in.xnorm = e.xnorm; in.k_cur = e.k_cur; in.extended = e.extended;
+  in.gram = e.gram; in.ws = ws; in.d = e.d; in.K = e.K;
+  gsi::extend_fill(in, e.udtype);
+  for (int j = 0; j < e.n_maps; ++j) {
+    const gsi_extend_map& mp = e.maps[j];
+    if (!mp.W) return fail(GSI_ERR_NULL, "%s: maps[%d].W of basis %d is NULL", fn, j, idx);
+    if (!mp.M) return fail(GSI_ERR_NULL, "%s: maps[%d].M of basis %d is NULL", fn, j, idx);
+    if (mp.m < 1 || mp.m > (1ll << 30))
+      return fail(GSI_ERR_SHAPE, "%s: maps[%d].m = %lld out of range (basis %d)", fn, j, (long long)mp.m, idx);
+    if (!aligned(mp.W, es) || !aligned(mp.M, es))
+      return fail(GSI_ERR_ALIGN, "%s: maps[%d] of basis %d is not aligned to its element size", fn, j, idx);
+    gsi::ExtMapRec r;
+    std::memset(&r, 0, sizeof(r));
+    r.W = mp.W; r.M = mp.M; r.m = mp.m; r.in = (int)ins.size();
+    gsi::extend_fill_map(r, e.d, e.udtype);
+    mps.push_back(r);
+  }
+  ins.push_back(in);
+  return GSI_OK;
+}
+
 int gsi_extend_basis(void* U, int64_t d, int64_t K, int udtype, int32_t* k_cur, const float* R, const float* rnorm,
                      const float* xnorm, float tau, const gsi_extend_map* maps, int32_t n_maps, float* gram,
                      int32_t* extended, void* ws, size_t ws_bytes, void* stream) {
   const char* fn = "gsi_extend_basis";
-  GSI_REQUIRE_PTR(U);
-  GSI_REQUIRE_PTR(k_cur);
-  GSI_REQUIRE_PTR(R);
-  GSI_REQUIRE_PTR(rnorm);
-  GSI_REQUIRE_PTR(xnorm);
-  if (!dtype_ok(udtype)) return fail(GSI_ERR_DTYPE, "%s: unknown udtype %d", fn, udtype);
-  if (int rc = check_shape(fn, 1, d, K, 0)) return rc;
-  if (n_maps < 0) return fail(GSI_ERR_SHAPE, "%s: n_maps = %d < 0", fn, n_maps);
-  if (n_maps > 0) GSI_REQUIRE_PTR(maps);
   if (!(tau >= 0.f)) return fail(GSI_ERR_SHAPE, "%s: tau must be a number >= 0", fn);
-  if (K > (int64_t)65535 * 64) return fail(GSI_ERR_SHAPE, "%s: K = %lld is too large", fn, (long long)K);
-  const size_t es = gsi::elem_size(udtype);
-  GSI_REQUIRE_ALIGNED(U, es);
-  GSI_REQUIRE_ALIGNED(k_cur, 4);
-  GSI_REQUIRE_ALIGNED(R, 4);
-  GSI_REQUIRE_ALIGNED(rnorm, 4);
-  GSI_REQUIRE_ALIGNED(xnorm, 4);
-  if (gram) GSI_REQUIRE_ALIGNED(gram, 4);
-  if (extended) GSI_REQUIRE_ALIGNED(extended, 4);
-  std::vector<gsi::ExtMap> em(n_maps);
-  for (int j = 0; j < n_maps; ++j) {
-    if (!maps[j].W) return fail(GSI_ERR_NULL, "%s: maps[%d].W is NULL", fn, j);
-    if (!maps[j].M) return fail(GSI_ERR_NULL, "%s: maps[%d].M is NULL", fn, j);
-    if (maps[j].m < 1 || maps[j].m > (1ll << 30))
-      return fail(GSI_ERR_SHAPE, "%s: maps[%d].m = %lld out of range", fn, j, (long long)maps[j].m);
-    if (!aligned(maps[j].W, es) || !aligned(maps[j].M, es))
-      return fail(GSI_ERR_ALIGN, "%s: maps[%d] is not aligned to its element size", fn, j);
-    em[j] = gsi::ExtMap{maps[j].W, maps[j].M, maps[j].m};
-  }
+  gsi_extend_desc e;
+  std::memset(&e, 0, sizeof(e));
+  e.U = U; e.d = d; e.K = K; e.udtype = udtype; e.k_cur = k_cur; e.R = R; e.rnorm = rnorm; e.xnorm = xnorm;
+  e.maps = maps; e.n_maps = n_maps; e.gram = gram; e.extended = extended;
+  std::vector<gsi::ExtIn> ins;
+  std::vector<gsi::ExtMapRec> mps;
+  if (int rc = add_extend_desc(fn, 0, e, static_cast<char*>(ws), ins, mps)) return rc;
   if (int rc = check_ws(fn, ws, ws_bytes, gsi_extend_basis_workspace_bytes(d, K))) return rc;
-  hipError_t e = gsi::extend_basis(U, d, K, udtype, k_cur, R, rnorm, xnorm, tau, em.data(), n_maps, gram, extended, ws,
-                                   static_cast<hipStream_t>(stream));
-  if (e != hipSuccess) return hip_fail(e, fn);
+  hipError_t err = gsi::extend_many(ins.data(), 1, mps.data(), (int)mps.size(), udtype, tau, nullptr,
+                                    static_cast<hipStream_t>(stream));
+  if (err != hipSuccess) return hip_fail(err, fn);
+  return GSI_OK;
+}
+
+size_t gsi_extend_many_workspace_bytes(const gsi_extend_desc* descs, int32_t n) {
+  if (!descs || n < 1) return 0;
+  int64_t n_maps = 0;
+  size_t need = 0;
+  for (int i = 0; i < n; ++i) {
+    if (descs[i].d < 1 || descs[i].K < 1 || descs[i].n_maps < 0) return 0;
+    n_maps += descs[i].n_maps;
+    need += gsi::align_up(gsi::extend_ws_bytes(descs[i].d, descs[i].K), 256);
+  }
+  return gsi::extend_table_bytes(n, (int)n_maps) + need;
+}
+
+int gsi_extend_many(const gsi_extend_desc* descs, int32_t n, float tau, void* ws, size_t ws_bytes, void* stream) {
+  const char* fn = "gsi_extend_many";
+  if (n < 0 || n > 65535) return fail(GSI_ERR_SHAPE, "%s: n = %d out of range (0 .. 65535)", fn, n);
+  if (n == 0) return GSI_OK;
+  GSI_REQUIRE_PTR(descs);
+  if (!(tau >= 0.f)) return fail(GSI_ERR_SHAPE, "%s: tau must be a number >= 0", fn);
+  int64_t n_maps = 0;
+  for (int i = 0; i < n; ++i) {
+    if (descs[i].n_maps < 0) return fail(GSI_ERR_SHAPE, "%s: n_maps = %d < 0 (basis %d)", fn, descs[i].n_maps, i);
+    if (descs[i].udtype != descs[0].udtype)
+      return fail(GSI_ERR_DTYPE, "%s: the bases of one call share one storage type (basis %d: %d, basis 0: %d)", fn, i,
+                  descs[i].udtype, descs[0].udtype);
+    n_maps += descs[i].n_maps;
+  }
+  if (n_maps > 65535) return fail(GSI_ERR_SHAPE, "%s: %lld maps in one call (at most 65535)", fn, (long long)n_maps);
+  const size_t need = gsi_extend_many_workspace_bytes(descs, n);
+  if (need == 0) return fail(GSI_ERR_SHAPE, "%s: a basis has d < 1 or K < 1", fn);
+  if (int rc = check_ws(fn, ws, ws_bytes, need)) return rc;
+  if (!aligned(ws, 256)) return fail(GSI_ERR_ALIGN, "%s: ws is not aligned to 256 bytes", fn);
+  std::vector<gsi::ExtIn> ins;
+  std::vector<gsi::ExtMapRec> mps;
+  ins.reserve(n);
+  mps.reserve((size_t)n_maps);
+  char* p = static_cast<char*>(ws) + gsi::extend_table_bytes(n, (int)n_maps);
+  for (int i = 0; i < n; ++i) {
+    if (int rc = add_extend_desc(fn, i, descs[i], p, ins, mps)) return rc;
+    p += gsi::align_up(gsi::extend_ws_bytes(descs[i].d, descs[i].K), 256);
+  }
+  hipError_t err = gsi::extend_many(ins.data(), n, mps.data(), (int)mps.size(), descs[0].udtype, tau, ws,
+                                    static_cast<hipStream_t>(stream));
+  if (err != hipSuccess) return hip_fail(err, fn);
   return GSI_OK;
 }
 

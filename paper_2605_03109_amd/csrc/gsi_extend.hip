@@ -18,8 +18,18 @@
 // Launches: s partials (+ the candidate verdict) | s | r2 and shares of |r2|^2 | final verdict + the stored column
 // | image columns of all maps | U^T u partials | E's row and column.  An extension moves U three times and every
 // W once; operands whose rows are 16-byte aligned are read with 16-byte loads, several in flight per lane.
+//
+// Every launch covers ALL bases of a call (one grid dimension is the basis, or the map): a token's pass over the
+// bases of a whole model is these seven launches, not seven per basis, and what it costs when no basis grows is
+// seven nearly empty launches.  The records of a call with several bases sit in a table in the workspace (copied
+// there by the call); a call with one basis carries its record in the kernel arguments.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
+#include <cstring>
+#include <vector>
+
+#include "gsi_decode.h"
 #include "gsi_device.h"
 #include "gsi_extend.h"
 
@@ -30,48 +40,79 @@ constexpr int kBlock = 256;
 constexpr int kWaves = kBlock / kWave;
 constexpr int kCols = 64;       // columns of U per workgroup in the projections
 constexpr int kRowsPerWg = 32;  // rows of U per workgroup in the residual
-constexpr int kMaxExtMaps = 8;  // maps per image launch
+constexpr int kImgRows = kWaves;  // rows of W per workgroup and turn in the image launch: one per wave
+constexpr int kFewMaps = 8;     // maps whose records fit the kernel arguments
+constexpr int kSumBlock = 64;   // a wave per workgroup in the slab sums
 
-struct ExtImg {
-  const void* W;
-  void* M;
-  int m;
-  int blk_begin;
+struct ExtArg {  // the bases of a launch: a device table, or (tab == null) the one record
+  const ExtIn* tab;
+  ExtIn one;
 };
-struct ExtImgs {
-  ExtImg t[kMaxExtMaps];
-  int n;
+struct ExtMapArg {  // the maps of an image launch: a device table, or up to kFewMaps records
+  const ExtMapRec* tab;
+  ExtMapRec few[kFewMaps];
 };
 
-// part[slab][j] = sum over the slab's rows of U[i, j] v[i]   (grid: column blocks x slabs).
+struct ExtWs {
+  ExtState* st;
+  float *part, *sv, *r2, *ust, *pn;
+};
+__host__ __device__ __forceinline__ size_t a256(size_t b) { return (b + 255) / 256 * 256; }
+__host__ __device__ __forceinline__ ExtWs ext_ws(const ExtIn& in) {
+  ExtWs w;
+  char* p = in.ws;
+  w.st = reinterpret_cast<ExtState*>(p);
+  p += a256(sizeof(ExtState));
+  w.part = reinterpret_cast<float*>(p);
+  p += a256((size_t)in.slabs * in.K * 4);
+  w.sv = reinterpret_cast<float*>(p);
+  p += a256((size_t)in.K * 4);
+  w.r2 = reinterpret_cast<float*>(p);
+  p += a256((size_t)in.d * 4);
+  w.ust = reinterpret_cast<float*>(p);
+  p += a256((size_t)in.d * 4);
+  w.pn = reinterpret_cast<float*>(p);
+  return w;
+}
+
+// part[slab][j] = sum over the slab's rows of U[i, j] v[i]   (grid: column blocks x slabs x bases).
 // first: this is the projection s = U^T r of the step: every workgroup forms the candidate verdict from the token's
-// norms and the column counter (the first one records it); else the projection U^T u for E, run iff the basis grew.
+// norms and the column counter (the first one of a basis records it); else the projection U^T u for E, run iff the
+// basis grew and the caller keeps E.
 template <class T>
-__global__ __launch_bounds__(kBlock) void ext_proj(const typename T::storage* __restrict__ U, int64_t d, int64_t K,
-                                                   const float* __restrict__ v, float* __restrict__ part,
-                                                   int rows_per_slab, int vec, int first, ExtState* __restrict__ st,
-                                                   const float* __restrict__ rnorm, const float* __restrict__ xnorm,
-                                                   float tau, const int32_t* __restrict__ k_cur) {
+__global__ __launch_bounds__(kBlock) void ext_proj(const ExtArg a, float tau, int first) {
+  using S = typename T::storage;
+  const ExtIn in = a.tab ? a.tab[blockIdx.z] : a.one;
+  const ExtWs w = ext_ws(in);
+  const int64_t d = in.d, K = in.K;
+  if ((int64_t)blockIdx.x * kCols >= K || (int)blockIdx.y >= in.slabs) return;  // (the grid is sized for the largest basis)
+  const float* v;
   if (first) {
-    const int k = k_cur[0];
-    const bool cand = k >= 0 && k < K && gate_fires(rnorm[0], xnorm[0], tau);
+    const int k = in.k_cur[0];
+    const bool cand = k >= 0 && k < K && gate_fires(in.rnorm[0], in.xnorm[0], tau);
     if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x == 0) {
-      st->kc = k;
-      st->cand = cand ? 1 : 0;
-      st->ext = 0;
-      st->inv = 0.f;
+      w.st->kc = k;
+      w.st->cand = cand ? 1 : 0;
+      w.st->ext = 0;
+      w.st->inv = 0.f;
     }
     if (!cand) return;
-  } else if (!st->ext) {
-    return;
+    v = in.R;
+  } else {
+    if (!in.gram || !w.st->ext) return;
+    v = w.ust;
   }
+  const S* U = static_cast<const S*>(in.U);
+  float* part = w.part;
   constexpr int V = T::kVec;
   constexpr int TPR = kCols / V;        // threads per row segment of 64 columns
   constexpr int RG = kBlock / TPR;      // rows in flight per pass of the workgroup
   __shared__ float sh[RG][kCols + 1];
-  const int64_t r0 = (int64_t)blockIdx.y * rows_per_slab;
-  const int64_t r1 = r0 + rows_per_slab < d ? r0 + rows_per_slab : d;
-  if (vec) {
+  // (a call with many bases launches fewer workgroups per basis than it has slabs: the workgroup takes several)
+  for (int slab = blockIdx.y; slab < in.slabs; slab += gridDim.y) {
+  const int64_t r0 = (int64_t)slab * in.rows_per_slab;
+  const int64_t r1 = r0 + in.rows_per_slab < d ? r0 + in.rows_per_slab : d;
+  if (in.uvec) {
     const int rg = threadIdx.x / TPR, cv = threadIdx.x % TPR;
     const int64_t col0 = (int64_t)blockIdx.x * kCols + cv * V;
     float acc[V];
@@ -79,18 +120,18 @@ __global__ __launch_bounds__(kBlock) void ext_proj(const typename T::storage* __
     for (int e = 0; e < V; ++e) acc[e] = 0.f;
     if (col0 < K) {  // K is a multiple of V here: whole vectors
       for (int64_t i = r0 + rg; i < r1; i += 4 * RG) {
-        float f[4][V], w[4];
+        float f[4][V], wt[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {  // four rows requested before the first is used; rows past the slab repeat
           const int64_t ii = i + q * RG;  // the last one with weight zero
           const int64_t ic = ii < r1 ? ii : r1 - 1;
           T::load_vec(U + ic * K + col0, f[q]);
-          w[q] = ii < r1 ? v[ic] : 0.f;
+          wt[q] = ii < r1 ? v[ic] : 0.f;
         }
 #pragma unroll
         for (int q = 0; q < 4; ++q)
 #pragma unroll
-          for (int e = 0; e < V; ++e) acc[e] = fmaf(f[q][e], w[q], acc[e]);
+          for (int e = 0; e < V; ++e) acc[e] = fmaf(f[q][e], wt[q], acc[e]);
       }
     }
 #pragma unroll
@@ -100,7 +141,7 @@ __global__ __launch_bounds__(kBlock) void ext_proj(const typename T::storage* __
     if (threadIdx.x < kCols && col < K) {
       float s = 0.f;
       for (int q = 0; q < RG; ++q) s += sh[q][threadIdx.x];
-      part[(int64_t)blockIdx.y * K + col] = s;
+      part[(int64_t)slab * K + col] = s;
     }
   } else {
     constexpr int RL = kBlock / kCols;
@@ -114,8 +155,10 @@ __global__ __launch_bounds__(kBlock) void ext_proj(const typename T::storage* __
     if (rl == 0 && col < K) {
       float s = 0.f;
       for (int q = 0; q < RL; ++q) s += sh[q][threadIdx.x];
-      part[(int64_t)blockIdx.y * K + col] = s;
+      part[(int64_t)slab * K + col] = s;
     }
+  }
+  __syncthreads();  // the sums have been read before the next slab's are written
   }
 }
 
@@ -133,30 +176,36 @@ __device__ __forceinline__ float slab_sum(const float* __restrict__ part, int sl
   return t;
 }
 
-constexpr int kSumBlock = 64;  // a wave per workgroup: K / 64 workgroups instead of K / 256
-__global__ __launch_bounds__(kSumBlock) void ext_sum(const float* __restrict__ part, int slabs, int64_t K,
-                                                     const int* __restrict__ go, float* __restrict__ s) {
-  if (!go[0]) return;
+__global__ __launch_bounds__(kSumBlock) void ext_sum(const ExtArg a) {
+  const ExtIn in = a.tab ? a.tab[blockIdx.y] : a.one;
+  const ExtWs w = ext_ws(in);
+  if (!w.st->cand) return;
   const int64_t j = (int64_t)blockIdx.x * kSumBlock + threadIdx.x;
-  if (j >= K) return;
-  s[j] = slab_sum(part, slabs, K, j);
+  if (j >= in.K) return;
+  w.sv[j] = slab_sum(w.part, in.slabs, in.K, j);
 }
 
-// r2[i] = v[i] - sum_j U[i, j] s[j], a wave per row (two rows at a time); pn[workgroup] = the workgroup's share
+// r2[i] = r[i] - sum_j U[i, j] s[j], a wave per row (two rows at a time); pn[workgroup] = the workgroup's share
 // of |r2|^2
 template <class T>
-__global__ __launch_bounds__(kBlock) void ext_resid(const typename T::storage* __restrict__ U, int64_t d, int64_t K,
-                                                    const float* __restrict__ v, const float* __restrict__ s,
-                                                    const int* __restrict__ go, float* __restrict__ r2,
-                                                    float* __restrict__ pn, int vec) {
-  if (!go[0]) return;
+__global__ __launch_bounds__(kBlock) void ext_resid(const ExtArg a) {
+  using S = typename T::storage;
+  const ExtIn in = a.tab ? a.tab[blockIdx.y] : a.one;
+  const ExtWs w = ext_ws(in);
+  if ((int)blockIdx.x >= in.wgs || !w.st->cand) return;
+  const int64_t d = in.d, K = in.K;
+  const S* U = static_cast<const S*>(in.U);
+  const float* v = in.R;
+  const float* s = w.sv;
+  float* r2 = w.r2;
   constexpr int V = T::kVec;
   __shared__ float shn[kWaves];
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const int64_t r0 = (int64_t)blockIdx.x * kRowsPerWg;
+  for (int blk = blockIdx.x; blk < in.wgs; blk += gridDim.x) {
+  const int64_t r0 = (int64_t)blk * kRowsPerWg;
   const int64_t r1 = r0 + kRowsPerWg < d ? r0 + kRowsPerWg : d;
   float nn = 0.f;
-  if (vec) {
+  if (in.uvec) {
     const int64_t chunks = K / V;
     for (int64_t i = r0 + wave; i < r1; i += 2 * kWaves) {
       const int64_t i2 = i + kWaves < r1 ? i + kWaves : i;  // the second row of the pair, or the first again
@@ -201,25 +250,29 @@ __global__ __launch_bounds__(kBlock) void ext_resid(const typename T::storage* _
   __syncthreads();
   if (threadIdx.x == 0) {
     float t = 0.f;
-    for (int w = 0; w < kWaves; ++w) t += shn[w];
-    pn[blockIdx.x] = t;
+    for (int q = 0; q < kWaves; ++q) t += shn[q];
+    w.pn[blk] = t;
+  }
+  __syncthreads();
   }
 }
 
-// The final verdict (every workgroup adds the n shares of |r2|^2 in the same fixed order; the first one records the
-// verdict, the column counter and the caller's flag), then column kc of U <- r2 / |r2| rounded to storage;
-// ust = the stored values widened.
+// The final verdict (every workgroup of a basis adds the shares of |r2|^2 in the same fixed order; the first one
+// records the verdict, the column counter and the caller's flag), then column kc of U <- r2 / |r2| rounded to
+// storage; ust = the stored values widened.
 template <class T>
-__global__ __launch_bounds__(kBlock) void ext_column(typename T::storage* __restrict__ U, int64_t d, int64_t K,
-                                                     const float* __restrict__ r2, const float* __restrict__ pn, int n,
-                                                     ExtState* __restrict__ st, int32_t* __restrict__ k_cur,
-                                                     int32_t* __restrict__ extended, float* __restrict__ ust) {
+__global__ __launch_bounds__(kBlock) void ext_column(const ExtArg a) {
+  using S = typename T::storage;
+  const ExtIn in = a.tab ? a.tab[blockIdx.y] : a.one;
+  const ExtWs w = ext_ws(in);
+  const int64_t d = in.d, K = in.K;
+  if ((int64_t)blockIdx.x * kBlock >= d) return;  // (block 0 of a basis always stays)
   __shared__ float sh[kBlock];
   __shared__ float s_inv;
-  const int cand = st->cand, kc = st->kc;
+  const int cand = w.st->cand, kc = w.st->kc;
   float t = 0.f;
   if (cand)
-    for (int q = threadIdx.x; q < n; q += kBlock) t += pn[q];
+    for (int q = threadIdx.x; q < in.wgs; q += kBlock) t += w.pn[q];
   sh[threadIdx.x] = t;
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -229,56 +282,46 @@ __global__ __launch_bounds__(kBlock) void ext_column(typename T::storage* __rest
     const int ext = (cand && n2 > 0.f) ? 1 : 0;
     s_inv = ext ? 1.f / n2 : 0.f;
     if (blockIdx.x == 0) {
-      st->ext = ext;
-      st->inv = s_inv;
-      if (ext) k_cur[0] = kc + 1;
-      if (extended) extended[0] = ext;
+      w.st->ext = ext;
+      w.st->inv = s_inv;
+      if (ext) in.k_cur[0] = kc + 1;
+      if (in.extended) in.extended[0] = ext;
     }
   }
   __syncthreads();
   const float inv = s_inv;
   if (inv == 0.f) return;  // uniform
-  const int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
-  if (i >= d) return;
-  const int64_t at = i * K + kc;
-  T::store(U, at, r2[i] * inv);
-  ust[i] = T::load(U, at);
+  S* U = static_cast<S*>(in.U);
+  for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < d; i += (int64_t)gridDim.x * kBlock) {
+    const int64_t at = i * K + kc;
+    T::store(U, at, w.r2[i] * inv);
+    w.ust[i] = T::load(U, at);
+  }
 }
 
-// M[row, kc] = sum_i W[row, i] ust[i] for every map of the launch.  A workgroup takes kImgRows rows of one map, a
-// wave one row at a time (16-byte loads, eight in flight per lane, when the rows allow them); u is staged in LDS
-// once per workgroup when it fits (lds = 1), else read through the caches.
-constexpr int kImgRows = 16;
+// M[row, kc] = sum_i W[row, i] ust[i] (grid: row blocks x maps).  A workgroup takes kImgRows rows of one map, a
+// wave one row at a time (16-byte loads, eight in flight per lane, when the rows allow them).
 template <class T>
-__global__ __launch_bounds__(kBlock) void ext_image(const ExtImgs im, int64_t d, int64_t K,
-                                                    const float* __restrict__ ust, const ExtState* __restrict__ st,
-                                                    int vec, int lds) {
-  extern __shared__ __align__(16) float us[];
-  if (!st->ext) return;
+__global__ __launch_bounds__(kBlock) void ext_image(const ExtArg a, const ExtMapArg ma) {
+  using S = typename T::storage;
+  const ExtMapRec p = ma.tab ? ma.tab[blockIdx.y] : ma.few[blockIdx.y];
+  if ((int64_t)blockIdx.x * kImgRows >= p.m) return;
+  const ExtIn in = a.tab ? a.tab[p.in] : a.one;
+  const ExtWs w = ext_ws(in);
+  if (!w.st->ext) return;
   constexpr int V = T::kVec;
   constexpr int NL = 8;
-  using S = typename T::storage;
-  int ti = 0;
-#pragma unroll
-  for (int q = 1; q < kMaxExtMaps; ++q)
-    if (q < im.n && (int)blockIdx.x >= im.t[q].blk_begin) ti = q;
-  const ExtImg& p = im.t[ti];
+  const int64_t d = in.d, K = in.K;
   const int lane = threadIdx.x % kWave, wave = threadIdx.x / kWave;
-  const float* uv = ust;
-  if (lds) {  // (d is a multiple of 4 on this path)
-    for (int64_t i = 4 * (int64_t)threadIdx.x; i < d; i += 4 * kBlock)
-      *reinterpret_cast<float4*>(us + i) = *reinterpret_cast<const float4*>(ust + i);
-    __syncthreads();
-    uv = us;
-  }
-  const int64_t row_begin = (int64_t)(blockIdx.x - p.blk_begin) * kImgRows;
-  const int kc = st->kc;
+  const float* uv = w.ust;
+  const int kc = w.st->kc;
+  for (int64_t row_begin = (int64_t)blockIdx.x * kImgRows; row_begin < p.m; row_begin += (int64_t)gridDim.x * kImgRows)
   for (int r = wave; r < kImgRows; r += kWaves) {
     const int64_t row = row_begin + r;
     if (row >= p.m) break;  // (whole waves leave together)
-    const S* w = static_cast<const S*>(p.W) + row * d;
+    const S* wr = static_cast<const S*>(p.W) + row * d;
     float acc = 0.f;
-    if (vec) {
+    if (p.vec) {
       const int64_t chunks = d / V;
       for (int64_t c0 = 0; c0 < chunks; c0 += (int64_t)kWave * NL) {
         uint4 raw[NL];
@@ -286,7 +329,7 @@ __global__ __launch_bounds__(kBlock) void ext_image(const ExtImgs im, int64_t d,
         for (int q = 0; q < NL; ++q) {  // chunks past the row repeat its last one and are not used
           int64_t c = c0 + lane + (int64_t)q * kWave;
           c = c < chunks ? c : chunks - 1;
-          raw[q] = load_stream16(w + c * V);
+          raw[q] = load_stream16(wr + c * V);
         }
 #pragma unroll
         for (int q = 0; q < NL; ++q) {
@@ -306,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void ext_image(const ExtImgs im, int64_t d,
         }
       }
     } else {
-      for (int64_t i = lane; i < d; i += kWave) acc = fmaf(T::load(w, i), uv[i], acc);
+      for (int64_t i = lane; i < d; i += kWave) acc = fmaf(T::load(wr, i), uv[i], acc);
     }
     acc = group_sum<kWave>(acc);
     if (lane == 0) T::store(static_cast<S*>(p.M), row * K + kc, acc);
@@ -314,16 +357,18 @@ __global__ __launch_bounds__(kBlock) void ext_image(const ExtImgs im, int64_t d,
 }
 
 // E[j, kc] = E[kc, j] = (U^T u)[j] - (j == kc), the projection over the extended basis added over its slabs
-__global__ __launch_bounds__(kSumBlock) void ext_gram(float* __restrict__ E, int64_t K, const float* __restrict__ part,
-                                                      int slabs, const ExtState* __restrict__ st) {
-  if (!st->ext) return;
+__global__ __launch_bounds__(kSumBlock) void ext_gram(const ExtArg a) {
+  const ExtIn in = a.tab ? a.tab[blockIdx.y] : a.one;
+  const ExtWs w = ext_ws(in);
+  if (!in.gram || !w.st->ext) return;
+  const int64_t K = in.K;
   const int64_t j = (int64_t)blockIdx.x * kSumBlock + threadIdx.x;
   if (j >= K) return;
-  const float t = slab_sum(part, slabs, K, j);
-  const int kc = st->kc;
+  const float t = slab_sum(w.part, in.slabs, K, j);
+  const int kc = w.st->kc;
   const float v = t - (j == kc ? 1.f : 0.f);
-  E[j * K + kc] = v;
-  E[(int64_t)kc * K + j] = v;
+  in.gram[j * K + kc] = v;
+  in.gram[(int64_t)kc * K + j] = v;
 }
 
 struct Geom {
@@ -338,6 +383,70 @@ Geom geom(int64_t d) {
   return g;
 }
 
+template <class T>
+hipError_t launch_all(const ExtIn* in, int n, const ExtMapRec* maps, int n_maps, float tau, void* table, hipStream_t s) {
+  ExtArg a;
+  std::memset(&a, 0, sizeof(a));
+  const ExtMapRec* mtab = nullptr;
+  if (n == 1) {
+    a.one = in[0];
+  } else {  // the records go to the table in the workspace: bases first, then maps
+    const size_t ib = align_up((size_t)n * sizeof(ExtIn), 256), mb = align_up((size_t)n_maps * sizeof(ExtMapRec), 256);
+    std::vector<char> host(ib + mb, 0);
+    std::memcpy(host.data(), in, (size_t)n * sizeof(ExtIn));
+    if (n_maps) std::memcpy(host.data() + ib, maps, (size_t)n_maps * sizeof(ExtMapRec));
+    if (hipError_t e = upload_launch(host.data(), host.size(), table, s); e != hipSuccess) return e;
+    a.tab = static_cast<const ExtIn*>(table);
+    mtab = reinterpret_cast<const ExtMapRec*>(static_cast<const char*>(table) + ib);
+  }
+  int64_t K_max = 0, d_max = 0, m_max = 0;
+  int slabs_max = 0, wgs_max = 0, any_gram = 0;
+  for (int i = 0; i < n; ++i) {
+    K_max = std::max<int64_t>(K_max, in[i].K);
+    d_max = std::max<int64_t>(d_max, in[i].d);
+    slabs_max = std::max(slabs_max, in[i].slabs);
+    wgs_max = std::max(wgs_max, in[i].wgs);
+    any_gram |= in[i].gram != nullptr;
+  }
+  for (int j = 0; j < n_maps; ++j) m_max = std::max<int64_t>(m_max, maps[j].m);
+  // A launch is about kGridCap workgroups at most: every workgroup of a basis that does not grow reads its record and
+  // leaves, which is what a token costs nearly always, so a call with many bases gives each fewer workgroups (they
+  // take several slabs, row blocks ... in turn; what a workgroup computes per slab or row does not change).
+  constexpr int64_t kGridCap = 2048;
+  const int64_t pc = ceil_div(K_max, kCols);
+  const dim3 pgrid((unsigned)pc, (unsigned)std::min<int64_t>(slabs_max, std::max<int64_t>(1, kGridCap / (pc * n))), (unsigned)n);
+  const dim3 kgrid((unsigned)ceil_div(K_max, kSumBlock), (unsigned)n);
+  const int64_t per_basis = std::max<int64_t>(8, kGridCap / n);
+  ext_proj<T><<<pgrid, kBlock, 0, s>>>(a, tau, 1);
+  ext_sum<<<kgrid, kSumBlock, 0, s>>>(a);
+  ext_resid<T><<<dim3((unsigned)std::min<int64_t>(wgs_max, per_basis), (unsigned)n), kBlock, 0, s>>>(a);
+  ext_column<T><<<dim3((unsigned)std::min<int64_t>(ceil_div(d_max, kBlock), per_basis), (unsigned)n), kBlock, 0, s>>>(a);
+  if (n_maps > 0) {
+    ExtMapArg ma;
+    std::memset(&ma, 0, sizeof(ma));
+    if (mtab) {
+      ma.tab = mtab;
+      const int64_t per_map = std::max<int64_t>(8, 2 * kGridCap / n_maps);
+      ext_image<T><<<dim3((unsigned)std::min<int64_t>(ceil_div(m_max, kImgRows), per_map), (unsigned)n_maps), kBlock, 0, s>>>(a, ma);
+    } else {
+      for (int j0 = 0; j0 < n_maps; j0 += kFewMaps) {
+        const int nm = std::min(kFewMaps, n_maps - j0);
+        int64_t mm = 0;
+        for (int q = 0; q < nm; ++q) {
+          ma.few[q] = maps[j0 + q];
+          mm = std::max<int64_t>(mm, maps[j0 + q].m);
+        }
+        ext_image<T><<<dim3((unsigned)ceil_div(mm, kImgRows), (unsigned)nm), kBlock, 0, s>>>(a, ma);
+      }
+    }
+  }
+  if (any_gram) {
+    ext_proj<T><<<pgrid, kBlock, 0, s>>>(a, tau, 0);
+    ext_gram<<<kgrid, kSumBlock, 0, s>>>(a);
+  }
+  return hipGetLastError();
+}
+
 }  // namespace
 
 size_t extend_ws_bytes(int64_t d, int64_t K) {
@@ -346,68 +455,30 @@ size_t extend_ws_bytes(int64_t d, int64_t K) {
          2 * align_up((size_t)d * 4, 256) + align_up((size_t)g.wgs * 4, 256);
 }
 
-template <class T>
-static hipError_t extend_launch(void* U, int64_t d, int64_t K, int32_t* k_cur, const float* R, const float* rnorm,
-                                const float* xnorm, float tau, const ExtMap* maps, int n_maps, float* gram,
-                                int32_t* extended, void* ws, hipStream_t s) {
-  using S = typename T::storage;
-  const Geom g = geom(d);
-  char* p = static_cast<char*>(ws);
-  ExtState* st = reinterpret_cast<ExtState*>(p);
-  p += align_up(sizeof(ExtState), 256);
-  float* part = reinterpret_cast<float*>(p);
-  p += align_up((size_t)g.slabs * K * 4, 256);
-  float* sv = reinterpret_cast<float*>(p);
-  p += align_up((size_t)K * 4, 256);
-  float* r2 = reinterpret_cast<float*>(p);
-  p += align_up((size_t)d * 4, 256);
-  float* ust = reinterpret_cast<float*>(p);
-  p += align_up((size_t)d * 4, 256);
-  float* pn = reinterpret_cast<float*>(p);
-  const dim3 pgrid((unsigned)ceil_div(K, kCols), (unsigned)g.slabs);
-  const unsigned kgrid = (unsigned)ceil_div(K, kSumBlock);
-  // 16-byte loads along the rows of U: whole vectors per row, rows that start on 16 bytes
-  const int uvec = K % T::kVec == 0 && reinterpret_cast<uintptr_t>(U) % 16 == 0;
-
-  ext_proj<T><<<pgrid, kBlock, 0, s>>>(static_cast<const S*>(U), d, K, R, part, g.rows_per_slab, uvec, 1, st, rnorm, xnorm,
-                                       tau, k_cur);
-  ext_sum<<<kgrid, kSumBlock, 0, s>>>(part, g.slabs, K, &st->cand, sv);
-  ext_resid<T><<<g.wgs, kBlock, 0, s>>>(static_cast<const S*>(U), d, K, R, sv, &st->cand, r2, pn, uvec);
-  ext_column<T><<<(unsigned)ceil_div(d, kBlock), kBlock, 0, s>>>(static_cast<S*>(U), d, K, r2, pn, g.wgs, st, k_cur,
-                                                               extended, ust);
-  for (int j0 = 0; j0 < n_maps; j0 += kMaxExtMaps) {
-    ExtImgs im;
-    im.n = n_maps - j0 < kMaxExtMaps ? n_maps - j0 : kMaxExtMaps;
-    int total = 0, vec = d % T::kVec == 0;
-    for (int q = 0; q < kMaxExtMaps; ++q) {
-      const ExtMap& mp = maps[j0 + (q < im.n ? q : 0)];
-      im.t[q] = ExtImg{mp.W, mp.M, (int)mp.m, total};
-      if (q < im.n) {
-        total += (int)ceil_div(mp.m, kImgRows);
-        if (reinterpret_cast<uintptr_t>(mp.W) % 16) vec = 0;
-      }
-    }
-    // u in LDS when it fits beside nothing else (160 KB per compute unit; two workgroups of 64 KB still share one)
-    const int lds = d % 4 == 0 && d * 4 <= 65536;
-    static const hipError_t attr = hipFuncSetAttribute(reinterpret_cast<const void*>(&ext_image<T>),
-                                                       hipFuncAttributeMaxDynamicSharedMemorySize, 65536);
-    if (attr != hipSuccess) return attr;
-    ext_image<T><<<total, kBlock, lds ? (size_t)d * 4 : 0, s>>>(im, d, K, ust, st, vec, lds);
-  }
-  if (gram) {
-    ext_proj<T><<<pgrid, kBlock, 0, s>>>(static_cast<const S*>(U), d, K, ust, part, g.rows_per_slab, uvec, 0, st, rnorm,
-                                         xnorm, tau, k_cur);
-    ext_gram<<<kgrid, kSumBlock, 0, s>>>(gram, K, part, g.slabs, st);
-  }
-  return hipGetLastError();
+size_t extend_table_bytes(int n, int n_maps) {
+  return n > 1 ? align_up((size_t)n * sizeof(ExtIn), 256) + align_up((size_t)n_maps * sizeof(ExtMapRec), 256) : 0;
 }
 
-hipError_t extend_basis(void* U, int64_t d, int64_t K, int udtype, int32_t* k_cur, const float* R, const float* rnorm,
-                        const float* xnorm, float tau, const ExtMap* maps, int n_maps, float* gram, int32_t* extended,
-                        void* ws, hipStream_t s) {
-  return udtype == GSI_BF16
-             ? extend_launch<BF16>(U, d, K, k_cur, R, rnorm, xnorm, tau, maps, n_maps, gram, extended, ws, s)
-             : extend_launch<F32>(U, d, K, k_cur, R, rnorm, xnorm, tau, maps, n_maps, gram, extended, ws, s);
+void extend_fill(ExtIn& in, int udtype) {
+  const Geom g = geom(in.d);
+  in.slabs = g.slabs;
+  in.rows_per_slab = g.rows_per_slab;
+  in.wgs = g.wgs;
+  // 16-byte loads along the rows of U: whole vectors per row, rows that start on 16 bytes
+  const int V = udtype == GSI_BF16 ? 8 : 4;
+  in.uvec = in.K % V == 0 && reinterpret_cast<uintptr_t>(in.U) % 16 == 0;
+}
+
+void extend_fill_map(ExtMapRec& mp, int64_t d, int udtype) {
+  const int V = udtype == GSI_BF16 ? 8 : 4;
+  mp.vec = d % V == 0 && reinterpret_cast<uintptr_t>(mp.W) % 16 == 0;
+}
+
+hipError_t extend_many(const ExtIn* in, int n, const ExtMapRec* maps, int n_maps, int udtype, float tau, void* table,
+                       hipStream_t s) {
+  if (n <= 0) return hipSuccess;
+  return udtype == GSI_BF16 ? launch_all<BF16>(in, n, maps, n_maps, tau, table, s)
+                            : launch_all<F32>(in, n, maps, n_maps, tau, table, s);
 }
 
 }  // namespace gsi

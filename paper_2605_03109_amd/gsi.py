@@ -27,7 +27,7 @@ MAP_IMAGE_FP8 = 1  # gsi_map_desc.flags: M holds E4M3 codes, M_scale the row sca
 CALL_BUILD_IMAGE, CALL_PROJECT, CALL_GATE, CALL_GATED_LINEAR, CALL_DENSE_LINEAR, CALL_LAYER_STACK = range(6)
 
 EXPORTS = (
-    "gsi_build_image", "gsi_build_gram", "gsi_extend_basis", "gsi_extend_basis_workspace_bytes", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
+    "gsi_build_image", "gsi_build_gram", "gsi_extend_basis", "gsi_extend_basis_workspace_bytes", "gsi_extend_many", "gsi_extend_many_workspace_bytes", "gsi_quantize_image_fp8", "gsi_project", "gsi_gate", "gsi_gated_linear", "gsi_dense_linear",
     "gsi_layer_stack",
     "gsi_layer_stack_static", "gsi_layer_stack_timed", "gsi_dense_stack",
     "gsi_stack_plan_bytes", "gsi_stack_plan_build", "gsi_stack_plan_run",
@@ -60,6 +60,15 @@ class ExtendMap(ctypes.Structure):
     _fields_ = [("W", ctypes.c_void_p), ("M", ctypes.c_void_p), ("m", ctypes.c_int64)]
 
 
+class ExtendDesc(ctypes.Structure):
+    _fields_ = [
+        ("U", ctypes.c_void_p), ("d", ctypes.c_int64), ("K", ctypes.c_int64), ("udtype", ctypes.c_int32),
+        ("n_maps", ctypes.c_int32), ("k_cur", ctypes.c_void_p), ("R", ctypes.c_void_p), ("rnorm", ctypes.c_void_p),
+        ("xnorm", ctypes.c_void_p), ("maps", ctypes.POINTER(ExtendMap)), ("gram", ctypes.c_void_p),
+        ("extended", ctypes.c_void_p),
+    ]
+
+
 class StackPlan(ctypes.Structure):
     _fields_ = [("opaque", ctypes.c_uint64 * 24)]
 
@@ -88,6 +97,10 @@ def _load() -> ctypes.CDLL:
     lib.gsi_extend_basis.restype = ctypes.c_int
     lib.gsi_extend_basis_workspace_bytes.argtypes = [i64, i64]
     lib.gsi_extend_basis_workspace_bytes.restype = sz
+    lib.gsi_extend_many.argtypes = [ctypes.POINTER(ExtendDesc), i32, f32, vp, sz, vp]
+    lib.gsi_extend_many.restype = ctypes.c_int
+    lib.gsi_extend_many_workspace_bytes.argtypes = [ctypes.POINTER(ExtendDesc), i32]
+    lib.gsi_extend_many_workspace_bytes.restype = sz
     lib.gsi_project.argtypes = [vp, vp, i64, i64, i64, i32, i32, vp, vp, vp, vp, vp, sz, vp]
     lib.gsi_gate.argtypes = [vp, vp, i64, f32, vp, vp, vp, vp]
     lib.gsi_gated_linear.argtypes = [vp, vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, vp, i32, vp, sz, vp]
@@ -252,6 +265,46 @@ def extend_basis(U: torch.Tensor, k_cur: torch.Tensor, R: torch.Tensor, rnorm: t
     _check(lib.gsi_extend_basis(_ptr(U), d, K, dtype_code(U), _ptr(k_cur), _ptr(R), _ptr(rnorm), _ptr(xnorm), float(tau),
                                 em, len(maps), _ptr(gram), _ptr(extended), wsp, wsn, _stream(stream)))
     return extended
+
+
+class ExtendSet:
+    """The bases of a model that see every token (gsi_extend_many): descriptors marshalled once, one call per token.
+
+    ``bases``: list of dicts {U[d,K], k_cur, R[d], rnorm, xnorm, maps: [(W[m,d], M[m,K]), ...]} (+ gram, + extended);
+    every tensor is kept alive by the set."""
+
+    def __init__(self, bases: Sequence[dict]):
+        self.bases = list(bases)
+        n = len(self.bases)
+        self._desc = (ExtendDesc * max(n, 1))()
+        self._maps = []
+        for i, b in enumerate(self.bases):
+            U = b["U"]
+            d, K = U.shape
+            maps = list(b.get("maps", ()))
+            em = (ExtendMap * max(len(maps), 1))()
+            for j, (W, M) in enumerate(maps):
+                if W.dtype != U.dtype or M.dtype != U.dtype or tuple(M.shape) != (W.shape[0], K) or W.shape[1] != d:
+                    raise ValueError("maps must be (W[m,d], M[m,K]) in the basis' dtype")
+                em[j].W, em[j].M, em[j].m = _ptr(W), _ptr(M), W.shape[0]
+            self._maps.append(em)
+            if b.get("extended") is None:
+                b["extended"] = torch.zeros((1,), dtype=torch.int32, device=U.device)
+            e = self._desc[i]
+            e.U, e.d, e.K, e.udtype, e.n_maps = _ptr(U), d, K, dtype_code(U), len(maps)
+            e.k_cur, e.R, e.rnorm, e.xnorm = _ptr(b["k_cur"]), _ptr(b["R"]), _ptr(b["rnorm"]), _ptr(b["xnorm"])
+            e.maps = em
+            e.gram, e.extended = _ptr(b.get("gram")), _ptr(b["extended"])
+        self.n = n
+        need = int(lib.gsi_extend_many_workspace_bytes(self._desc, n)) if n else 0
+        dev = self.bases[0]["U"].device if n else "cuda"
+        self.ws = torch.empty((need + 256,), dtype=torch.uint8, device=dev)
+        off = (-self.ws.data_ptr()) % 256
+        self._wsp, self._wsn = self.ws.data_ptr() + off, need
+
+    def step(self, tau: float, stream=None) -> None:
+        """One extension step of every basis on the token whose R, rnorm, xnorm the descriptors point at."""
+        _check(lib.gsi_extend_many(self._desc, self.n, float(tau), self._wsp, self._wsn, _stream(stream)))
 
 
 def quantize_image_fp8(M: torch.Tensor, M8: Optional[torch.Tensor] = None, scale: Optional[torch.Tensor] = None,

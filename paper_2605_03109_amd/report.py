@@ -445,8 +445,61 @@ def run_extend(args, torch, gsi, wd):
         rows.append(res)
         del U, U0, Ws, Ms, E, R, ws
         torch.cuda.empty_cache()
+    # ---- every basis of a stack of blocks in one call per token (gsi_extend_many)
+    L = 8
+    bases, resets = [], []
+    for layer in range(L):
+        for name, d, ms in (("qkv", 4096, (4096, 4096, 4096)), ("o", 4096, (4096,)), ("fc_in", 4096, (16384,)),
+                            ("fc_out", 16384, (4096,))):
+            U = torch.zeros((d, K), dtype=torch.bfloat16, device=dev)
+            U[:, :k0] = wd.make_basis64(d, k0, gen).to(torch.bfloat16)
+            Ws = [wd.make_weight(m, d, gen) for m in ms]
+            Ms = [gsi.build_image(W, U) for W in Ws]
+            R = torch.randn((d,), generator=gen, device=dev, dtype=torch.float32)
+            R /= R.norm()
+            b = {"U": U, "k_cur": torch.full((1,), k0, dtype=torch.int32, device=dev), "R": R,
+                 "rnorm": torch.full((1,), 0.3, device=dev), "xnorm": torch.ones((1,), device=dev),
+                 "maps": list(zip(Ws, Ms)), "gram": gsi.build_gram(U)}
+            bases.append(b)
+            resets.append(U.clone())
+    es = gsi.ExtendSet(bases)
+    set_rows = {"blocks": L, "bases": len(bases), "maps": sum(len(b["maps"]) for b in bases), "calls": steps}
+
+    def reset():
+        for b, U0 in zip(bases, resets):
+            b["U"].copy_(U0)
+            b["k_cur"].fill_(k0)
+
+    for label, tau, who in (("no_basis_extends", 0.5, None), ("one_basis_extends", 0.2, 1), ("every_basis_extends", 0.2, None)):
+        # one_basis_extends: only the first basis sees a token above the threshold
+        for i, b in enumerate(bases):
+            b["rnorm"].fill_(0.3 if who is None or i < who else 0.01)
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            es.step(tau, side)
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            cs = torch.cuda.current_stream()
+            for t in range(steps):
+                es.step(tau, cs)
+        best = None
+        for rep in range(3):
+            reset()
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            g.replay()
+            torch.cuda.synchronize()
+            sec = time.perf_counter() - t0
+            best = sec if best is None else min(best, sec)
+        grown = sum(int(b["k_cur"].item()) - k0 for b in bases)
+        set_rows[label] = {"us_per_call": round(best / steps * 1e6, 2), "columns_added": grown}
+        log(f"[report] {len(bases)} bases per call, {label}: {set_rows[label]}")
     return {"config": 5, "workload": "gsi_extend_basis on GPT-J-block shapes, bf16, basis array of capacity K holding 256 "
-            "columns at the start, E kept; HIP-graph replay of `calls` consecutive calls, best of 3", "rows": rows}
+            "columns at the start, E kept; HIP-graph replay of `calls` consecutive calls, best of 3; then "
+            "gsi_extend_many over the bases of eight blocks", "rows": rows, "many": set_rows}
 
 
 def main() -> int:

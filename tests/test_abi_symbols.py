@@ -97,6 +97,33 @@ def test_host_side_validation_needs_no_gpu():
     assert lib.gsi_extend_basis(*args(n=1)) == gsi.GSI_ERR_NULL      # maps[0].W is NULL
     assert lib.gsi_extend_basis(*args(ws=None, wsn=0)) == gsi.GSI_ERR_WORKSPACE
     assert lib.gsi_extend_basis_workspace_bytes(4096, 256) > 0 and lib.gsi_extend_basis_workspace_bytes(0, 4) == 0
+    # ... and the same step for several bases in one call
+    ed = (gsi.ExtendDesc * 2)()
+    for e in ed:
+        e.U, e.d, e.K, e.udtype, e.n_maps = 256, 8, 4, gsi.GSI_F32, 0
+        e.k_cur = e.R = e.rnorm = e.xnorm = 256
+    tau = ctypes.c_float(0.1)
+    need = lib.gsi_extend_many_workspace_bytes(ed, 2)
+    assert need > 2 * lib.gsi_extend_basis_workspace_bytes(8, 4)  # two workspaces + the descriptor table
+    assert lib.gsi_extend_many(ed, 0, tau, None, 0, None) == gsi.GSI_OK
+    assert lib.gsi_extend_many(None, 2, tau, one, need, None) == gsi.GSI_ERR_NULL
+    assert lib.gsi_extend_many(ed, 2, tau, None, 0, None) == gsi.GSI_ERR_WORKSPACE
+    assert lib.gsi_extend_many(ed, 2, tau, odd, need, None) == gsi.GSI_ERR_ALIGN
+    assert lib.gsi_extend_many(ed, 2, ctypes.c_float(-1.0), one, need, None) == gsi.GSI_ERR_SHAPE
+    assert lib.gsi_extend_many(ed, 70000, tau, one, need, None) == gsi.GSI_ERR_SHAPE
+    ed[1].udtype = gsi.GSI_BF16
+    assert lib.gsi_extend_many(ed, 2, tau, one, need, None) == gsi.GSI_ERR_DTYPE
+    assert b"share one storage type" in lib.gsi_last_error()
+    ed[1].udtype = gsi.GSI_F32
+    ed[1].k_cur = None
+    assert lib.gsi_extend_many(ed, 2, tau, one, need, None) == gsi.GSI_ERR_NULL
+    assert b"basis 1" in lib.gsi_last_error()
+    ed[1].k_cur = 256
+    ed[1].K = 9
+    assert lib.gsi_extend_many_workspace_bytes(ed, 2) > 0
+    assert lib.gsi_extend_many(ed, 2, tau, one, 1 << 20, None) == gsi.GSI_ERR_SHAPE
+    ed[1].K = 0
+    assert lib.gsi_extend_many_workspace_bytes(ed, 2) == 0
     # a dense stack of several tokens needs its workspace
     inp[0].src_map = -1
     mp[0].m, inp[0].d, inp[0].k = 64, 64, 32

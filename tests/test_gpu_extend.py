@@ -169,3 +169,59 @@ def test_tracker_against_oracle(gsi, pu, dt):
         W64, U64 = O.widen(W, dt), O.widen(gsi.bits_of(Ud), dt)
         pu.check_image(gsi.bits_of(Md), O.build_image(W64, U64), W64, U64, dt)
     # the cascade needed fewer extensions than the cold start
+
+
+@pytest.mark.parametrize("dt", ["bf16", "f32"])
+def test_extend_many_equals_single_calls(gsi, pu, dt):
+    """gsi_extend_many over six bases of unlike shapes (one at capacity, some tokens below the threshold, one basis
+    without maps, one without E) gives, basis by basis, the bits of gsi_extend_basis; two steps in a row."""
+    shapes = [(512, 64, 40, (200, 96)), (4096, 256, 200, (1024,)), (1024, 128, 127, (264, 520, 8)), (256, 16, 16, (64,)),
+              (768, 64, 10, ()), (100, 24, 5, (33,))]
+    tau = 0.2
+    rhos = [(0.3, 0.1), (0.25, 0.4), (0.1, 0.5), (0.5, 0.5), (0.21, 0.19), (0.4, 0.3)]  # per basis: step 0, step 1
+    say(f"case extend many {dt}")
+    many, single = [], []
+    for bi, (d, K, k, ms) in enumerate(shapes):
+        store = _basis_array(d, K, k, dt, seed=8600 + bi)
+        U64 = O.widen(store, dt)
+        Ws = [gsi.to_device(wl.make_weight(m, d, 8700 + 10 * bi + j, dt), dt) for j, m in enumerate(ms)]
+        xs = [_token(U64, k, rho, seed=8800 + 10 * bi + t) for t, rho in enumerate(rhos[bi])]
+        sets = []
+        for _ in range(2):
+            Ud = gsi.to_device(store, dt)
+            Md = [gsi.build_image(W, Ud) for W in Ws]
+            b = {"U": Ud, "k_cur": torch.tensor([k], dtype=torch.int32, device="cuda"),
+                 "R": torch.zeros(d, dtype=torch.float32, device="cuda"), "rnorm": torch.zeros(1, device="cuda"),
+                 "xnorm": torch.zeros(1, device="cuda"), "maps": list(zip(Ws, Md)),
+                 "gram": gsi.build_gram(Ud) if bi != 2 else None,
+                 "extended": torch.full((1,), -1, dtype=torch.int32, device="cuda")}
+            sets.append(b)
+        many.append(sets[0])
+        single.append(sets[1])
+        many[-1]["xs"] = single[-1]["xs"] = xs
+    es = gsi.ExtendSet(many)
+    es.ws.fill_(0xFF)
+    grown = 0
+    for step in range(2):
+        for bm, bs in zip(many, single):
+            Xd = gsi.to_device(bm["xs"][step][None, :], "f32")
+            for b in (bm, bs):  # each side projects against its own (identical) basis
+                C, R, rn, xn = gsi.project(b["U"], Xd)
+                b["R"].copy_(R[0]); b["rnorm"].copy_(rn); b["xnorm"].copy_(xn)
+        es.step(tau)
+        for bs in single:
+            gsi.extend_basis(bs["U"], bs["k_cur"], bs["R"], bs["rnorm"], bs["xnorm"], tau, bs["maps"], gram=bs["gram"],
+                             extended=bs["extended"])
+        torch.cuda.synchronize()
+        for bi, (bm, bs) in enumerate(zip(many, single)):
+            assert int(bm["extended"].item()) == int(bs["extended"].item()) and int(bm["extended"].item()) in (0, 1), bi
+            assert torch.equal(bm["k_cur"], bs["k_cur"]), bi
+            assert torch.equal(bm["U"], bs["U"]), bi
+            for (_, Ma), (_, Mb) in zip(bm["maps"], bs["maps"]):
+                assert torch.equal(Ma, Mb), bi
+            if bm["gram"] is not None:
+                assert torch.equal(bm["gram"], bs["gram"]), bi
+            grown += int(bm["extended"].item())
+    kc = [int(b["k_cur"].item()) for b in many]
+    say(f"  columns in use after two steps: {kc}; {grown} extensions")
+    assert kc[3] == 16 and grown >= 5 and grown < 12
