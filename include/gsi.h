@@ -118,7 +118,8 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
  * residual ratio exceeds a threshold extends the basis by one orthonormal vector; Section 7 "Online basis
  * adaptation").  The paper gives no threshold, capacity or eviction rule; here the basis lives in U[d,K] (`udtype`)
  * whose columns from k on are ZERO (a zero column changes neither c, r nor y, so every other call runs on it
- * unchanged at rank K), k_cur[0] is a device counter of the columns in use, and nothing is ever evicted.
+ * unchanged at rank K; the vector kernels and plans take ranks of 8 * 2^j columns in bf16, 4 * 2^j in fp32, so pick
+ * K among those), k_cur[0] is a device counter of the columns in use, and nothing is ever evicted.
  * Inputs: the residual R[d], rnorm[1], xnorm[1] of ONE token against the current basis, as gsi_project or
  * gsi_layer_stack wrote them (with GSI_INPUT_GATE_SINGLE_PASS, R exists only for a token that fired).
  *   candidate iff xnorm > 0, rnorm / xnorm >= tau (compared like the gate) and k_cur < K;
