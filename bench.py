@@ -103,8 +103,9 @@ def counter_traffic(which: str, workload_tag: str):
 class Stack:
     """The resident operands of an L-layer stack at one rank, and per-token descriptor tables."""
 
-    def __init__(self, torch, gsi, wd, W, U64, k, T, eps, p, fire, seed, flags=0, plan=False):
+    def __init__(self, torch, gsi, wd, W, U64, k, T, eps, p, fire, seed, flags=0, plan=False, image="bf16"):
         self.torch, self.gsi, self.T, self.k, self.eps = torch, gsi, T, k, eps
+        self.image = image
         L = len(W)
         inputs, maps = [], []
         self.designed = []
@@ -123,6 +124,8 @@ class Stack:
         t0 = time.perf_counter()
         for mp in maps:
             mp["M"] = gsi.build_image(mp["W"], inputs[mp["input_id"]]["U"])
+            if image == "fp8":  # E4M3 codes + one power-of-two scale per row (Section 7 "Combination with quantization")
+                mp["M"], mp["M_scale"] = gsi.quantize_image_fp8(mp["M"])
         torch.cuda.synchronize()
         self.image_build_s = time.perf_counter() - t0
         self.st = gsi.LayerStack(inputs, maps, T, eps)
@@ -174,12 +177,16 @@ class Stack:
         """bool[n_inputs, T]: the device's gate decisions of the last pass over the trace."""
         return self.torch.stack([ti["mask"].bool() for ti in self.st.inputs_t])
 
+    def image_row_bytes(self, m):
+        """bytes of the image of a map with m rows: bf16 elements, or E4M3 codes and an fp32 scale per row"""
+        return m * self.k * 2 if self.image == "bf16" else m * self.k + m * 4
+
     def bytes(self, fired_frac_by_input):
         """(dense bytes, image bytes, basis bytes, expected W bytes of fired inputs) per step."""
         k, bw = self.k, 2
         L = self.n_in // len(BLOCK)
         dense = L * sum(m * d * bw for _, d, mp in BLOCK for _, m in mp)
-        img = L * sum(m * k * bw for _, d, mp in BLOCK for _, m in mp)
+        img = L * sum(self.image_row_bytes(m) for _, d, mp in BLOCK for _, m in mp)
         bas = L * sum(d * k * bw for _, d, _ in BLOCK)
         wf = 0.0
         for i in range(self.n_in):
@@ -262,6 +269,9 @@ def main() -> int:
     ap.add_argument("--slow-path", choices=["mc+wr", "wx"], default="mc+wr",
                     help="wx: fired tokens get y = W x as Algorithm 1 prints it (GSI_INPUT_SLOW_PATH_WX); with the "
                          "single-pass gate a fired input's image rows are then skipped")
+    ap.add_argument("--image", choices=["bf16", "fp8"], default="bf16",
+                    help="storage of the cached images: the weights' bf16, or E4M3 codes with a scale per row "
+                         "(Section 7 \"Combination with quantization\": half the fast-path bytes, 3e-2 output error)")
     ap.add_argument("--no-plan", action="store_true",
                     help="call gsi_layer_stack with host descriptors every step instead of running plans that "
                          "gsi_stack_plan_build marshalled once (single-pass gate only)")
@@ -313,7 +323,7 @@ def main() -> int:
     # ---- the headline cell ------------------------------------------------------------------------------
     t0 = time.perf_counter()
     use_plan = single_pass and not args.no_plan
-    S = Stack(torch, gsi, wd, W, U64, args.k, T, eps, p, args.fire, seed, flags, use_plan)
+    S = Stack(torch, gsi, wd, W, U64, args.k, T, eps, p, args.fire, seed, flags, use_plan, args.image)
     log(f"[bench] cell k={args.k} fire={args.fire}: {S.n_in} inputs, {S.n_mp} maps, {T} tokens resident in "
         f"{time.perf_counter()-t0:.1f}s (images built in {S.image_build_s*1e3:.0f} ms)")
     mode = args.mode
@@ -392,7 +402,7 @@ def main() -> int:
                     b += k * k * 4 + k * 4
             for i in set_inputs(idx - 2):   # the images, c read, y written; explicit gate: x again, r written;
                 _, d, mpl = BLOCK[i % len(BLOCK)]  # single-pass gate: the basis again, x, r for a fired input only
-                b += sum(m * k * 2 + m * 4 for _, m in mpl) + k * 4
+                b += sum(S.image_row_bytes(m) + m * 4 for _, m in mpl) + k * 4
                 if not single_pass:
                     b += d * 4 + d * 4
                 elif fired_np[i, t]:
@@ -447,7 +457,7 @@ def main() -> int:
                   "unfired_launch_us": round(float(d1[b1 == 0].mean() * 1e6), 2) if (b1 == 0).any() else None})
         dom = max(kernels, key=lambda n: kernels[n]["us_per_step_total"])
         e = kernels[dom]
-        tag = f"opt_stack_{L}layers_k{args.k}_fire{int(round(args.fire * 100))}_decode"
+        tag = f"opt_stack_{L}layers_k{args.k}_fire{int(round(args.fire * 100))}_decode" + ("" if args.image == "bf16" else "_fp8")
         roofline = {"bound": "hbm", "kernel": e["kernel"], "achieved": e["achieved_GBs"], "peak": HBM_PEAK_GBS,
                     "unit": "GB/s", "frac": e["frac_of_hbm_peak"], "traffic": counter_traffic(dom, tag),
                     "avg_launch_us": e["avg_launch_us"], "avg_algorithmic_bytes": e["avg_algorithmic_bytes"],
@@ -497,7 +507,7 @@ def main() -> int:
     del S
     torch.cuda.empty_cache()
     for k, fire in cells:
-        Sx = Stack(torch, gsi, wd, W, U64, k, Tc, eps, p, fire, seed, flags, use_plan)
+        Sx = Stack(torch, gsi, wd, W, U64, k, Tc, eps, p, fire, seed, flags, use_plan, args.image)
         n = max(Tc, min(args.steps, 2 * Tc))
         sec = timed_run(torch, Sx.gated_step, Tc, n, min(args.warmup, Tc), mode)
         c, _ = cell_numbers(Sx, sec * 1e6 / n, n)
@@ -523,7 +533,8 @@ def main() -> int:
         "data": "synthetic",
         "config": {
             "workload": f"OPT-6.7B-shaped {L}-layer linear stack, batch-1 decode: per layer q,k,v,o 4096x4096, fc1 "
-                        "16384x4096, fc2 4096x16384 over four inputs; bf16 weights/images/bases, fp32 accumulate; one "
+                        "16384x4096, fc2 4096x16384 over four inputs; bf16 weights/bases, images in "
+                        + ("bf16" if args.image == "bf16" else "E4M3 with a scale per row") + ", fp32 accumulate; one "
                         "gsi_layer_stack call per decode token",
             "layers": L, "k": args.k, "eps": eps, "decode_tokens": T, "designed_fire_rate": args.fire,
             "measured_fire_rate": head["measured_fire_rate"], "masks_match_design": head["masks_match_design"],

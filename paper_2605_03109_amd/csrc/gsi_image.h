@@ -65,6 +65,18 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
       const S* src = M + (int64_t)(row < m ? row : m - 1) * k;
       raw[it][u] = STREAM ? load_stream16(src) : *reinterpret_cast<const uint4*>(src);
     }
+  // E4M3 codes: the rows' power-of-two scales, requested with the rows (a load at the point of use would put one
+  // more memory round trip at the end of the workgroup)
+  float rscale[kPerWave][kImgLoads];
+  if constexpr (T::kVec == 16) {
+#pragma unroll
+    for (int it = 0; it < kPerWave; ++it)
+#pragma unroll
+      for (int u = 0; u < kImgLoads; ++u) {
+        const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
+        rscale[it][u] = t.scale[row < m ? row : m - 1];
+      }
+  }
   for (int j = threadIdx.x; j < k; j += 256) cs[j] = t.part_c ? sum_partials(t.part_c + j, k, t.a_slabs) : t.C[j];
   __syncthreads();
   float cvv[V];
@@ -85,7 +97,7 @@ __device__ __forceinline__ void image_block_as(const ImgTask& t, int local_block
       s = group_sum_rt(live ? s : 0.f, lpr);
       const int row = ((item0 + it) * kImgLoads + u) * rpw + sub;
       if (l == 0 && row < m) {
-        if constexpr (T::kVec == 16) s *= t.scale[row];  // E4M3 codes: the row's power-of-two scale
+        if constexpr (T::kVec == 16) s *= rscale[it][u];
         t.Y[row] = s;
       }
     }
