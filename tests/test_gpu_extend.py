@@ -316,3 +316,27 @@ def test_tracking_loop_stack_plans_and_extend_many(gsi, pu):
                     pu.check_image(gsi.bits_of(M), O.build_image(W64, Unew), W64, Unew, dt)
     say(f"  {total_grown} extensions over {T} tokens x {len(bases)} bases")
     assert total_grown >= len(bases)  # every basis met a fired token
+
+
+def test_extend_one_basis_with_more_maps_than_one_launch_carries(gsi, pu):
+    """gsi_extend_basis with ten maps (their records travel in the kernel arguments, eight per image launch): every
+    image gains the column W u of the stored u."""
+    d, K, k, dt = 512, 64, 20, "bf16"
+    store = _basis_array(d, K, k, dt, seed=9100)
+    U64 = O.widen(store, dt)
+    ms = [40, 8, 264, 100, 16, 520, 33, 64, 7, 128]
+    Ws = [wl.make_weight(m, d, 9200 + j, dt) for j, m in enumerate(ms)]
+    Ud = gsi.to_device(store, dt)
+    Wd = [gsi.to_device(W, dt) for W in Ws]
+    Md = [gsi.build_image(W, Ud) for W in Wd]
+    x = _token(U64, k, 0.3, seed=9300)
+    C, R, rn, xn = gsi.project(Ud, gsi.to_device(x[None, :], "f32"))
+    kc = torch.tensor([k], dtype=torch.int32, device="cuda")
+    ext = gsi.extend_basis(Ud, kc, R[0], rn, xn, 0.1, list(zip(Wd, Md)))
+    torch.cuda.synchronize()
+    assert int(ext.item()) == 1 and int(kc.item()) == k + 1
+    Unew = O.widen(gsi.bits_of(Ud), dt)
+    for W, M in zip(Ws, Md):
+        W64 = O.widen(W, dt)
+        pu.check_image(gsi.bits_of(M), O.build_image(W64, Unew), W64, Unew, dt)
+        assert gsi.bits_of(M)[:, k].any() and not gsi.bits_of(M)[:, k + 1:].any()
