@@ -75,6 +75,21 @@ def test_mid_shapes(gsi, pu, wdtype, d, k, m, T, nf):
 
 
 # ------------------------------------------------------------------------------------------------
+# at and beyond the limits of the vector kernels: inputs of up to 65536 elements take them for the projection
+# (32 slabs of 2048 rows), longer ones and ranks above 512 the generic kernels; the linear maps of an input longer
+# than 16384 elements take the generic kernels too
+# ------------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("d,k,m,T,nf,wdtype", [(32768, 64, 264, 4, 2, "bf16"), (65536, 8, 40, 3, 1, "bf16"),
+                                               (69632, 16, 24, 3, 1, "bf16"), (2048, 1024, 64, 3, 1, "bf16"),
+                                               (20480, 128, 136, 5, 2, "bf16"), (32768, 32, 72, 3, 1, "f32")])
+def test_shapes_at_and_beyond_the_vector_kernels_limits(gsi, pu, d, k, m, T, nf, wdtype):
+    w = wl.tiny(d, k, m, T, nf, seed=2300 + d + k + m, wdtype=wdtype)
+    say(f"case limits d={d} k={k} m={m} T={T} nf={nf} {wdtype}")
+    worst = pu.check_group(w, w.groups[0], [(0, T), (0, 1), (T - 1, T)])
+    say(f"  worst rel-L2 {worst:.3e}")
+
+
+# ------------------------------------------------------------------------------------------------
 # decode batches (2..128 tokens a call): one to eight token tiles, fired counts from none to all,
 # ragged row and token tails, the long fc_out-shaped contraction
 # ------------------------------------------------------------------------------------------------
