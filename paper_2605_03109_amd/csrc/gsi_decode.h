@@ -286,6 +286,8 @@ size_t stage_table_bytes(int n_in, int n_maps);
 struct StageTableGeom {   // what the host needs to launch over a table that is already in device memory
   int n_in, n_maps, dtype;
   int nt;                 // bases and images together exceed kStreamBytes: non-temporal loads
+  int merge;              // the launch of the c^T E c shares adds the partial projections itself (few partials per
+                          // input: no launch for the coefficient sums)
   int tp, tc, tr, ti;     // workgroups: partial projections, coefficient sums, residual slabs, image rows
   size_t off_maps, off_p, off_r, off_c, off_i;  // byte offsets of the sections of the table
 };

@@ -556,15 +556,17 @@ __global__ __launch_bounds__(kBlock) void table_cred(const TabIn* __restrict__ i
   }
 }
 
-__global__ __launch_bounds__(kBlock) void table_gram(const TabIn* __restrict__ ins) {
+// merged: no launch added the partials before this one; every workgroup adds them itself (fixed order) and the first
+// of an input writes C and |c|^2
+__global__ __launch_bounds__(kBlock) void table_gram(const TabIn* __restrict__ ins, int merged) {
   __shared__ __align__(16) float lds[kMaxK];
   __shared__ double dsh[2 * kWaves];
   const TabIn& in = ins[blockIdx.x / kGramBlocks];
   StageCRed p;
-  p.part_c = nullptr; p.C = in.C; p.E = in.E;
+  p.part_c = merged ? in.part_c : nullptr; p.C = in.C; p.E = in.E;
   p.k_slabs = (in.k_rows & 0xffff) | ((in.slabs & 0xffff) << 16);
   p.gw_off = 0;
-  gram_block(p, reinterpret_cast<double*>(reinterpret_cast<char*>(in.part_c) + in.gw_off), true, blockIdx.x % kGramBlocks,
+  gram_block(p, reinterpret_cast<double*>(reinterpret_cast<char*>(in.part_c) + in.gw_off), !merged, blockIdx.x % kGramBlocks,
              lds, dsh);
 }
 
@@ -744,6 +746,11 @@ hipError_t stage_table_build(const TabIn* ins, int n_in, const TabMap* maps, int
     bytes += (size_t)maps[j].m * maps[j].k * (maps[j].scale ? 1 : elem_size(dtype));
   }
   g.nt = bytes >= kStreamBytes ? 1 : 0;
+  // Few partials per input (slabs x rank up to 4096 values, 32 KB with their low parts): the kGramBlocks workgroups of
+  // an input each add them again rather than wait for a launch that adds them once.
+  g.merge = 1;
+  for (int i = 0; i < n_in; ++i)
+    if ((int64_t)(ins[i].slabs & 0xffff) * (ins[i].k_rows & 0xffff) > 4096) g.merge = 0;
   pb[n_in] = (int)tp; rb[n_in] = (int)tr; cb[n_in] = (int)tc; ib[n_maps] = (int)ti;
   if (tp >= (1 << 30) || tr + ti >= (1 << 30)) return hipErrorInvalidValue;
   g.tp = (int)tp; g.tc = (int)tc; g.tr = (int)tr; g.ti = (int)ti;
@@ -775,10 +782,12 @@ hipError_t stage_table_launch(const void* table, const StageTableGeom& g, float 
   }
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // 2. coefficient sums, then the shares of c^T E c
-  table_cred<<<(unsigned)g.tc, kBlock, 0, s>>>(d_ins, d_cb, n_in);
-  if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
-  if (ev(1)) hipExtLaunchKernelGGL(table_gram, dim3((unsigned)n_in * kGramBlocks), dim3(kBlock), 0, s, e0, e1, 0, d_ins);
-  else table_gram<<<(unsigned)n_in * kGramBlocks, kBlock, 0, s>>>(d_ins);
+  if (!g.merge) {
+    table_cred<<<(unsigned)g.tc, kBlock, 0, s>>>(d_ins, d_cb, n_in);
+    if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
+  }
+  if (ev(1)) hipExtLaunchKernelGGL(table_gram, dim3((unsigned)n_in * kGramBlocks), dim3(kBlock), 0, s, e0, e1, 0, d_ins, g.merge);
+  else table_gram<<<(unsigned)n_in * kGramBlocks, kBlock, 0, s>>>(d_ins, g.merge);
   if (hipError_t e = hipGetLastError(); e != hipSuccess) return e;
   // 3. gates, residuals of fired inputs, image rows
   const unsigned grid = (unsigned)(g.ti + g.tr);
