@@ -577,7 +577,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
     return rc;
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
-  if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype, m, Y) && gsi::decode_linear_ok(m, d, k, wdtype, W, M) &&
+  if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype, m, Y) && gsi::decode_linear_ok(m, d, k, wdtype, W, M, B) &&
       aligned(C, 16) && aligned(R, 16)) {
     LinBatcher bt;
     bt.wdtype = wdtype; bt.s = s;
@@ -615,7 +615,7 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
   hipError_t e;
   if (mfma_dense_path(W, X, m, d, B, wdtype, Y)) {
     e = mfma_dense(W, X, m, d, B, xdtype, Y, (float*)ws, s);
-  } else if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr) && aligned(X, 16)) {
+  } else if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr, B) && aligned(X, 16)) {
     gsi::LinBatch lb;
     clear(lb, B);
     lb.n = lb.ng = 1;
@@ -641,7 +641,7 @@ static bool wx_vector_ok(const gsi_input_desc& in) {
 static bool fp8_codes_read(const gsi_map_desc& mp, const gsi_input_desc& in, int64_t B) {
   return B == 1 && aligned(mp.M, 16) && in.k % 16 == 0 && in.k <= gsi::kMaxK &&
          project_vector_path(in.d, in.k, B, in.udtype, in.U) &&
-         gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, nullptr) && aligned(in.C, 16) && aligned(in.R, 16) &&
+         gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, nullptr, B) && aligned(in.C, 16) && aligned(in.R, 16) &&
          wx_vector_ok(in);
 }
 static size_t fp8_expand_bytes(const gsi_map_desc& mp, const gsi_input_desc& in, int64_t B) {
@@ -809,7 +809,7 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
     for (int j = 0; j < n_maps; ++j) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
-      if (done[j] || mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr) ||
+      if (done[j] || mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr, B) ||
           !aligned(in.X, 16))
         continue;
       gsi::LinGroup gd;
@@ -965,7 +965,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     for (int j = 0; j < n_maps; ++j) {
       if (maps[j].input_id != i) continue;
       ++readers;
-      if (!gsi::decode_linear_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M) ||
+      if (!gsi::decode_linear_ok(maps[j].m, in.d, in.k, maps[j].wdtype, maps[j].W, maps[j].M, B) ||
           !aligned(in.C, 16) || !aligned(in.R, 16) || !wx_vector_ok(in))
         all_stream = false;
     }
@@ -988,7 +988,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
     for (int j = 0; j < n_maps; ++j) {
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
-      if (mp.wdtype != in.udtype || in.d > gsi::kMaxLinD ||
+      if (mp.wdtype != in.udtype || in.d > gsi::kMaxStreamD ||
           mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y))
         return fail(GSI_ERR_SHAPE, "%s: maps[%d] cannot be planned", fn, j);
     }
@@ -1320,9 +1320,9 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
       auto eligible = [&](int j) {
         const gsi_map_desc& mp = maps[j];
         const gsi_input_desc& in = inputs[mp.input_id];
-        return !map_done[j] && !map_fused[j] && mp.wdtype == dt && in.d <= gsi::kMaxLinD &&
+        return !map_done[j] && !map_fused[j] && mp.wdtype == dt && in.d <= gsi::kMaxStreamD &&
                !mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) &&
-               gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) && aligned(in.C, 16) &&
+               gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M, B) && aligned(in.C, 16) &&
                aligned(in.R, 16) && wx_vector_ok(in);
       };
       std::vector<int> order;  // inputs in order of first appearance
@@ -1407,7 +1407,7 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         if (map_done[j] || map_fused[j] || mp.wdtype != dt || B == 0) continue;
         if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
           continue;  // matrix cores below
-        if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M) || !aligned(in.C, 16) ||
+        if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M, B) || !aligned(in.C, 16) ||
             !aligned(in.R, 16) || !wx_vector_ok(in))
           continue;
         gsi::LinGroup gd;

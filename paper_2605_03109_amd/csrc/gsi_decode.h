@@ -18,6 +18,7 @@ constexpr int kMaxResSlabs = 512;   // row slabs per input in the residual kerne
 constexpr int kMaxK = 512;          // largest rank the vector projection kernels take
 constexpr int kRowsPerBlock = 16;   // output rows per workgroup in the batched-token linear kernels
 constexpr int kMaxLinD = 16384;     // floats of LDS one activation vector may take in the linear kernels
+constexpr int kMaxStreamD = 65536;  // longest input of the single-token weight-streaming kernels (blocks of kMaxLinD columns)
 constexpr int kStageMaxRows = 2048; // rows of U per workgroup in the single-token staged kernel (their activations sit in LDS)
 constexpr int kMaxSumK = 2048;      // floats of LDS all projection coefficients of a launch may take
 
@@ -113,7 +114,8 @@ static_assert(sizeof(LinBatch) <= 4096, "kernel arguments are limited to 4 KB");
 
 // eligibility of the vector kernels for a shape / alignment (else the generic kernels run)
 bool decode_project_ok(int64_t d, int64_t k, int udtype, const void* U);
-bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M);
+// (B: tokens of the call; a single token's kernels take inputs of up to kMaxStreamD elements)
+bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M, int64_t B = 2);
 
 size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype);
 // fills d, k, slab geometry and the two workspace pointers of a task whose other fields are set
@@ -333,6 +335,7 @@ constexpr size_t kStreamBytes = (size_t)512 << 20;
 struct FiredGeom {        // launch shape of the weight-streaming kernel over a table in device memory
   int n_in, wdtype, tail;
   int nt;                 // non-temporal weight loads
+  int long_d;             // an input is longer than kMaxLinD elements (staged a block of columns at a time)
   unsigned grid;
   size_t smem;
 };

@@ -377,8 +377,8 @@ __global__ __launch_bounds__(kFusedBlock) void fused_token(const FusedArgs a, un
         const int m = uni(mp.m);
         const S* W = reinterpret_cast<const S*>(mp.W);
         float* Y = mp.Y;
-        if (tail) stream_map_rows<T, true, true>(W, Y, m, dd, xs, whole, first, GW, lane);
-        else stream_map_rows<T, false, true>(W, Y, m, dd, xs, whole, first, GW, lane);
+        if (tail) stream_map_rows<T, true, true>(W, Y, m, dd, dd, xs, whole, first, GW, lane);
+        else stream_map_rows<T, false, true>(W, Y, m, dd, dd, xs, whole, first, GW, lane);
         first = (first - m % GW + GW) % GW;
       }
       __syncthreads();  // the staged vector is free again

@@ -194,10 +194,10 @@ size_t tile_smem(const LinBatch& lb) {
 
 }  // namespace
 
-bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M) {
+bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M, int64_t B) {
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   if (d % V || (k > 0 && k % V)) return false;
-  if (d > kMaxLinD || kTokTile * k > kMaxLinD || k > kMaxSumK) return false;
+  if (d > (B == 1 ? kMaxStreamD : kMaxLinD) || kTokTile * k > kMaxLinD || k > kMaxSumK) return false;
   if (k / V > kWave) return false;  // one 16-byte chunk of an image row per lane
   if (reinterpret_cast<uintptr_t>(W) % 16) return false;
   if (M && reinterpret_cast<uintptr_t>(M) % 16) return false;

@@ -28,7 +28,8 @@ constexpr int kBlock = 512;  // waves of a workgroup share one staged activation
 constexpr int kWaves = kBlock / kWave;
 constexpr int kWgsPerCu = 2;  // persistent grid: workgroups per CU
 
-template <class T, bool DENSE, bool TAIL, bool NT>
+// LONG: an input of the launch is longer than kMaxLinD elements (its vector is staged a block of columns at a time)
+template <class T, bool DENSE, bool TAIL, bool NT, bool LONG>
 __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
@@ -79,16 +80,22 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
   for (int gi = 0; gi < ng; ++gi) {
     if (!((fired_mask >> gi) & 1u)) continue;  // uniform across the grid
     const LinGroup& g = lb.g[gi];
-    const int d = g.d;
+    const int d_all = g.d;
+    const bool whole_all = DENSE || g.wx;  // the product takes x (and replaces y) rather than r (added to y)
+    // A vector longer than the LDS holds is taken in blocks of kMaxLinD columns: every block streams its columns of
+    // every row and adds to what the blocks before left in y (the same lane owns an output element in every block).
+    // (Without LONG the loop is one pass over the whole vector, known at compile time.)
+    for (int c0 = 0; c0 < (LONG ? d_all : 1); c0 += kMaxLinD) {
+    const int d = LONG ? min(kMaxLinD, d_all - c0) : d_all;
+    const bool whole = LONG ? whole_all && c0 == 0 : whole_all;
 
-    // stage the activation vector (readers of the previous group's vector are past the barrier)
+    // stage the activation vector (readers of the previous vector are past the barrier)
     if (staged) __syncthreads();
     staged = true;
-    const bool whole = DENSE || g.wx;  // the product takes x (and replaces y) rather than r (added to y)
-    if (whole && g.xdtype != GSI_F32) {
-      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(g.X, g.xdtype, idx);
+    if (whole_all && g.xdtype != GSI_F32) {
+      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(g.X, g.xdtype, c0 + idx);
     } else {
-      const float4* src = reinterpret_cast<const float4*>(whole ? reinterpret_cast<const float*>(g.X) : g.R);
+      const float4* src = reinterpret_cast<const float4*>((whole_all ? reinterpret_cast<const float*>(g.X) : g.R) + c0);
       float4* dst = reinterpret_cast<float4*>(xs);
       const int n4 = d / 4;
       int i = threadIdx.x;
@@ -108,15 +115,17 @@ __global__ __launch_bounds__(kBlock) void stream_rows(const LinBatch lb) {
       const LinTask& t = lb.t[ti];
       if (t.group != gi) continue;  // uniform
       const int m = t.m;
-      stream_map_rows<T, TAIL, false, NT>(reinterpret_cast<const S*>(t.W), t.Y, m, d, xs, whole, first, GW, lane);
+      stream_map_rows<T, TAIL, false, NT>(reinterpret_cast<const S*>(t.W) + c0, t.Y, m, d, d_all, xs, whole, first, GW,
+                                          lane);
       // continue the deal: the next map starts with the wave after the one that took this map's last row
       first = (first - m % GW + GW) % GW;
+    }
     }
   }
 }
 
 // The same streaming for ALL fired inputs of a call, descriptors in device memory.
-template <class T, bool TAIL, bool NT>
+template <class T, bool TAIL, bool NT, bool LONG>
 __global__ __launch_bounds__(kBlock) void stream_fired(const FiredIn* __restrict__ ins, const FiredMap* __restrict__ maps,
                                                        int n_in) {
   using S = typename T::storage;
@@ -146,16 +155,21 @@ __global__ __launch_bounds__(kBlock) void stream_fired(const FiredIn* __restrict
   for (int i = 0; i < n_in; ++i) {
     if (!__builtin_amdgcn_readfirstlane((int)s_f[i])) continue;  // uniform across the grid
     const FiredIn* in = ins + i;
-    const int d = __builtin_amdgcn_readfirstlane(in->d);
+    const int d_all = __builtin_amdgcn_readfirstlane(in->d);
     const int flags = __builtin_amdgcn_readfirstlane(in->flags);
     const int xdtype = flags >> 1;
-    const bool whole = (flags & kFiredWx) != 0;  // the product takes x (and replaces y) rather than r (added to y)
-    if (staged) __syncthreads();  // readers of the previous input's vector are done
+    const bool whole_all = (flags & kFiredWx) != 0;  // the product takes x (and replaces y) rather than r (added to y)
+    const int mb = __builtin_amdgcn_readfirstlane(in->map_begin), me = __builtin_amdgcn_readfirstlane(in->map_end);
+    // (a vector longer than the LDS holds: blocks of kMaxLinD columns, as in stream_rows)
+    for (int c0 = 0; c0 < (LONG ? d_all : 1); c0 += kMaxLinD) {
+    const int d = LONG ? min(kMaxLinD, d_all - c0) : d_all;
+    const bool whole = LONG ? whole_all && c0 == 0 : whole_all;
+    if (staged) __syncthreads();  // readers of the previous vector are done
     staged = true;
-    if (whole && xdtype != GSI_F32) {
-      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(in->X, xdtype, idx);
+    if (whole_all && xdtype != GSI_F32) {
+      for (int idx = threadIdx.x; idx < d; idx += kBlock) xs[idx] = load_act(in->X, xdtype, c0 + idx);
     } else {
-      const float4* src = reinterpret_cast<const float4*>(whole ? reinterpret_cast<const float*>(in->X) : in->R);
+      const float4* src = reinterpret_cast<const float4*>((whole_all ? reinterpret_cast<const float*>(in->X) : in->R) + c0);
       float4* dst = reinterpret_cast<float4*>(xs);
       const int n4 = d / 4;
       int q = threadIdx.x;
@@ -169,12 +183,15 @@ __global__ __launch_bounds__(kBlock) void stream_fired(const FiredIn* __restrict
       for (; q < n4; q += kBlock) dst[q] = src[q];
     }
     __syncthreads();
-    const int mb = __builtin_amdgcn_readfirstlane(in->map_begin), me = __builtin_amdgcn_readfirstlane(in->map_end);
+    int fst = first;  // every block of columns deals the rows alike: the same lane owns an output element throughout
     for (int j = mb; j < me; ++j) {
       const FiredMap* mp = maps + j;
       const int m = __builtin_amdgcn_readfirstlane(mp->m);
-      stream_map_rows<T, TAIL, false, NT>(reinterpret_cast<const S*>(mp->W), mp->Y, m, d, xs, whole, first, GW, lane);
-      first = (first - m % GW + GW) % GW;  // the next map starts with the wave after this map's last row
+      stream_map_rows<T, TAIL, false, NT>(reinterpret_cast<const S*>(mp->W) + c0, mp->Y, m, d, d_all, xs, whole, fst, GW,
+                                          lane);
+      fst = (fst - m % GW + GW) % GW;  // the next map starts with the wave after this map's last row
+    }
+    if (!LONG || c0 + kMaxLinD >= d_all) first = fst;
     }
   }
 }
@@ -198,32 +215,40 @@ int num_cus() {
   return n;
 }
 
-template <class T, bool DENSE, bool TAIL, bool NT>
+template <class T, bool DENSE, bool TAIL, bool NT, bool LONG>
 hipError_t launch_one(const LinBatch& lb, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   static const hipError_t attr =  // the kernel may use more than the default 64 KB of dynamic LDS
-      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<T, DENSE, TAIL, NT>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_rows<T, DENSE, TAIL, NT, LONG>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, (kMaxLinD + kMaxSumK) * (int)sizeof(float));
   if (attr != hipSuccess) return attr;
   if (e0 && e1) {  // the events take the dispatch's own start and stop timestamps
-    hipExtLaunchKernelGGL((stream_rows<T, DENSE, TAIL, NT>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, lb);
+    hipExtLaunchKernelGGL((stream_rows<T, DENSE, TAIL, NT, LONG>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, lb);
   } else {
-    stream_rows<T, DENSE, TAIL, NT><<<grid, kBlock, smem, s>>>(lb);
+    stream_rows<T, DENSE, TAIL, NT, LONG><<<grid, kBlock, smem, s>>>(lb);
   }
   return hipGetLastError();
 }
 
 template <class T, bool DENSE>
-hipError_t launch_shape(const LinBatch& lb, bool tail, bool nt, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0,
-                        hipEvent_t e1) {
-  if (tail) return nt ? launch_one<T, DENSE, true, true>(lb, grid, smem, s, e0, e1) : launch_one<T, DENSE, true, false>(lb, grid, smem, s, e0, e1);
-  return nt ? launch_one<T, DENSE, false, true>(lb, grid, smem, s, e0, e1) : launch_one<T, DENSE, false, false>(lb, grid, smem, s, e0, e1);
+hipError_t launch_shape(const LinBatch& lb, bool tail, bool nt, bool lng, unsigned grid, size_t smem, hipStream_t s,
+                        hipEvent_t e0, hipEvent_t e1) {
+  switch ((tail ? 4 : 0) | (nt ? 2 : 0) | (lng ? 1 : 0)) {
+    case 0: return launch_one<T, DENSE, false, false, false>(lb, grid, smem, s, e0, e1);
+    case 1: return launch_one<T, DENSE, false, false, true>(lb, grid, smem, s, e0, e1);
+    case 2: return launch_one<T, DENSE, false, true, false>(lb, grid, smem, s, e0, e1);
+    case 3: return launch_one<T, DENSE, false, true, true>(lb, grid, smem, s, e0, e1);
+    case 4: return launch_one<T, DENSE, true, false, false>(lb, grid, smem, s, e0, e1);
+    case 5: return launch_one<T, DENSE, true, false, true>(lb, grid, smem, s, e0, e1);
+    case 6: return launch_one<T, DENSE, true, true, false>(lb, grid, smem, s, e0, e1);
+    default: return launch_one<T, DENSE, true, true, true>(lb, grid, smem, s, e0, e1);
+  }
 }
 
 template <class T>
-hipError_t launch_dtype(const LinBatch& lb, bool tail, bool nt, unsigned grid, size_t smem, hipStream_t s, hipEvent_t e0,
-                        hipEvent_t e1) {
-  return lb.dense ? launch_shape<T, true>(lb, tail, nt, grid, smem, s, e0, e1)
-                  : launch_shape<T, false>(lb, tail, nt, grid, smem, s, e0, e1);
+hipError_t launch_dtype(const LinBatch& lb, bool tail, bool nt, bool lng, unsigned grid, size_t smem, hipStream_t s,
+                        hipEvent_t e0, hipEvent_t e1) {
+  return lb.dense ? launch_shape<T, true>(lb, tail, nt, lng, grid, smem, s, e0, e1)
+                  : launch_shape<T, false>(lb, tail, nt, lng, grid, smem, s, e0, e1);
 }
 
 }  // namespace
@@ -249,26 +274,31 @@ hipError_t upload_launch(const void* src, size_t bytes, void* dst, hipStream_t s
   return hipSuccess;
 }
 
-template <class T, bool TAIL, bool NT>
+template <class T, bool TAIL, bool NT, bool LONG>
 static hipError_t launch_fired(const FiredIn* ins, const FiredMap* maps, int n_in, unsigned grid, size_t smem,
                                hipStream_t s, hipEvent_t e0, hipEvent_t e1) {
   static const hipError_t attr =
-      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fired<T, TAIL, NT>),
+      hipFuncSetAttribute(reinterpret_cast<const void*>(&stream_fired<T, TAIL, NT, LONG>),
                           hipFuncAttributeMaxDynamicSharedMemorySize, kMaxLinD * (int)sizeof(float));
   if (attr != hipSuccess) return attr;
-  if (e0 && e1) hipExtLaunchKernelGGL((stream_fired<T, TAIL, NT>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, ins, maps, n_in);
-  else stream_fired<T, TAIL, NT><<<grid, kBlock, smem, s>>>(ins, maps, n_in);
+  if (e0 && e1) hipExtLaunchKernelGGL((stream_fired<T, TAIL, NT, LONG>), dim3(grid), dim3(kBlock), smem, s, e0, e1, 0, ins, maps, n_in);
+  else stream_fired<T, TAIL, NT, LONG><<<grid, kBlock, smem, s>>>(ins, maps, n_in);
   return hipGetLastError();
 }
 
 template <class T>
 static hipError_t launch_fired_shape(const FiredIn* ins, const FiredMap* maps, const FiredGeom& g, hipStream_t s,
                                      hipEvent_t e0, hipEvent_t e1) {
-  if (g.tail)
-    return g.nt ? launch_fired<T, true, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
-                : launch_fired<T, true, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
-  return g.nt ? launch_fired<T, false, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1)
-              : launch_fired<T, false, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+  switch ((g.tail ? 4 : 0) | (g.nt ? 2 : 0) | (g.long_d ? 1 : 0)) {
+    case 0: return launch_fired<T, false, false, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    case 1: return launch_fired<T, false, false, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    case 2: return launch_fired<T, false, true, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    case 3: return launch_fired<T, false, true, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    case 4: return launch_fired<T, true, false, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    case 5: return launch_fired<T, true, false, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    case 6: return launch_fired<T, true, true, false>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+    default: return launch_fired<T, true, true, true>(ins, maps, g.n_in, g.grid, g.smem, s, e0, e1);
+  }
 }
 
 hipError_t stream_fired_geom(int n_in, const FiredIn* host_ins, const FiredMap* host_maps, int wdtype, FiredGeom& g) {
@@ -285,7 +315,9 @@ hipError_t stream_fired_geom(int n_in, const FiredIn* host_ins, const FiredMap* 
       bytes += (size_t)host_maps[j].m * host_ins[i].d * elem_size(wdtype);
     }
   }
-  if (maxd > (size_t)kMaxLinD) return hipErrorInvalidValue;
+  if (maxd > (size_t)kMaxStreamD) return hipErrorInvalidValue;
+  g.long_d = maxd > (size_t)kMaxLinD ? 1 : 0;
+  if (g.long_d) maxd = kMaxLinD;  // longer vectors are staged a block of columns at a time
   int64_t grid = (int64_t)kWgsPerCu * num_cus();
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
@@ -313,6 +345,7 @@ size_t stream_smem_bytes(const LinBatch& lb) {
   size_t maxd = 0;
   for (int i = 0; i < lb.ng; ++i)
     if ((size_t)lb.g[i].d > maxd) maxd = (size_t)lb.g[i].d;
+  if (maxd > (size_t)kMaxLinD) maxd = kMaxLinD;  // longer vectors are staged a block of columns at a time
   return maxd * sizeof(float);
 }
 
@@ -328,12 +361,15 @@ hipError_t stream_rows_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_
     if ((lb.g[lb.t[i].group].d / V) % (kWave * kLU)) tail = true;
   }
   const bool nt = bytes >= kStreamBytes;
+  bool lng = false;
+  for (int i = 0; i < lb.ng; ++i)
+    if (lb.g[i].d > kMaxLinD) lng = true;
   int64_t grid = (int64_t)kWgsPerCu * num_cus();
   if (grid > ceil_div(rows, kWaves)) grid = ceil_div(rows, kWaves);
   if (grid < 1) grid = 1;
   const size_t smem = stream_smem_bytes(lb);
-  return wdtype == GSI_BF16 ? launch_dtype<BF16>(lb, tail, nt, (unsigned)grid, smem, s, e0, e1)
-                            : launch_dtype<F32>(lb, tail, nt, (unsigned)grid, smem, s, e0, e1);
+  return wdtype == GSI_BF16 ? launch_dtype<BF16>(lb, tail, nt, lng, (unsigned)grid, smem, s, e0, e1)
+                            : launch_dtype<F32>(lb, tail, nt, lng, (unsigned)grid, smem, s, e0, e1);
 }
 
 }  // namespace gsi

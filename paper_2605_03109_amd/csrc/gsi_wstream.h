@@ -50,13 +50,15 @@ __device__ __forceinline__ float load_old(const float* p) {
   else return *p;
 }
 
-// Rows first, first + GW, ... (< m) of W[m, d] by the calling wave; xs = the staged vector (d floats, LDS).
+// Rows first, first + GW, ... (< m) of a matrix by the calling wave: d columns of every row, rows ld elements apart
+// (ld = d for a whole matrix W[m, d]; a block of columns of a longer row otherwise); xs = the staged vector
+// (d floats, LDS).
 // whole: the product replaces y (dense baseline, W x form of the slow path); else it is added to y.
 // TAIL: d / kVec is not a multiple of 64 * kLU (loads clamped, surplus products dropped).
 template <class T, bool TAIL, bool COHERENT, bool NT = false>
 __device__ __forceinline__ void stream_map_rows(const typename T::storage* __restrict__ W, float* __restrict__ Y,
-                                                int m, int d, const float* __restrict__ xs, bool whole, int first,
-                                                int GW, int lane) {
+                                                int m, int d, int64_t ld, const float* __restrict__ xs, bool whole,
+                                                int first, int GW, int lane) {
   constexpr int V = T::kVec;
   using S = typename T::storage;
   const int chunks = d / V;
@@ -68,11 +70,11 @@ __device__ __forceinline__ void stream_map_rows(const typename T::storage* __res
     // register and written once per 64 rows), so a wave always has a unit in flight.
     const int nrows = first < m ? (m - first + GW - 1) / GW : 0;
     const int64_t seg_step = (int64_t)kWave * kLU * V;                       // elements to the next unit of a row
-    const int64_t row_step = (int64_t)GW * d - (int64_t)(nseg - 1) * seg_step;  // last unit of a row -> next row
+    const int64_t row_step = (int64_t)GW * ld - (int64_t)(nseg - 1) * seg_step;  // last unit of a row -> next row
     for (int j0 = 0; j0 < nrows; j0 += kWave) {
       const int cnt = min(kWave, nrows - j0);
       const int nu = cnt * nseg;
-      const S* p0 = W + (int64_t)(first + (int64_t)j0 * GW) * d + (int64_t)lane * V;
+      const S* p0 = W + (int64_t)(first + (int64_t)j0 * GW) * ld + (int64_t)lane * V;
       float res = 0.f, acc = 0.f;
       Raw<T> A[kLU], Bb[kLU];
       auto issue = [&](Raw<T> (&buf)[kLU], const S* ptr) {
@@ -140,7 +142,7 @@ __device__ __forceinline__ void stream_map_rows(const typename T::storage* __res
         for (int q = 0; q < kLU; ++q) {
           int c = cb + q * kWave;
           c = c < chunks ? c : chunks - 1;
-          buf[q].template load<NT>(W + (int64_t)row * d + (int64_t)c * V);
+          buf[q].template load<NT>(W + (int64_t)row * ld + (int64_t)c * V);
         }
 #pragma unroll
         for (int q = 0; q < kLU; ++q) {

@@ -413,9 +413,9 @@ def test_table_launches_full_size_in_the_bench_configuration(gsi, pu):
             del og
 
 
-@pytest.mark.parametrize("reps,every_input_single_pass", [(3, False), (5, True)])
+@pytest.mark.parametrize("reps,every_input_single_pass", [(3, False), (5, True)])  # 30 and 50 inputs
 def test_mixed_shapes_dtypes_and_gates_in_one_single_token_call(gsi, pu, reps, every_input_single_pass):
-    """One call per token over 27 (45) inputs of unlike shapes, storage types and options (single-pass and explicit
+    """One call per token over 30 (50) inputs of unlike shapes, storage types and options (single-pass and explicit
     gate, both forms of the slow path, shapes that only the generic kernels take): the call sorts them into its
     launches by itself, and every input and map is checked against the oracle on its own.  With the single-pass gate
     on every input the bf16 ones are more than one launch's arguments describe and run over the descriptor table."""
@@ -424,6 +424,7 @@ def test_mixed_shapes_dtypes_and_gates_in_one_single_token_call(gsi, pu, reps, e
         (512, 64, 520, "bf16", "f32"), (1024, 128, 264, "bf16", "bf16"), (776, 72, 100, "f32", "f32"),
         (33, 7, 10, "f32", "f32"), (2048, 256, 512, "bf16", "f32"), (4096, 64, 1032, "bf16", "f32"),
         (768, 64, 3072, "f32", "f32"), (256, 8, 64, "bf16", "f32"), (1536, 192, 384, "bf16", "f32"),
+        (32768, 64, 136, "bf16", "f32"),  # longer than the weight kernel's LDS vector: streamed in blocks of columns
     ]
     cases = []
     for rep in range(reps):
