@@ -3,7 +3,9 @@ block at batch-1 decode):
 
   --config 2   32 OPT-6.7B-shaped layers, batch-1 decode, rank k x designed fire rate sweep: tokens/s,
                effective weight-read GB/s, speedup over the dense 32-layer GEMV stack, beside the
-               prediction of the paper's Eq. (speedup) and the all-bytes model
+               prediction of the paper's Eq. (speedup) and the all-bytes model; here with one
+               gsi_layer_stack call per LAYER and token (explicit residual, three launches per call);
+               bench.py --cells runs the same sweep with one planned call per token over all layers
   --config 3   fc_in / fc_out at k = 256 with ragged decode batches B in {1, 4, 16, 64}, per-token
                Bernoulli(0.15) gate: time per step by B, compaction checked against the design
   --config 4   prefill-sized batch (T = 2048, k = 512, 20 % of the tokens fired) over the six maps of a
