@@ -473,6 +473,13 @@ static void clear(gsi::LinBatch& lb, int64_t B) {
   lb.B = (int)B;
 }
 
+// A decode batch (2..128 tokens) over an input longer than the linear kernels' LDS vector runs on the matrix-core
+// kernel only: what that kernel needs beyond decode_linear_ok (reads_x: the product reads x, dense or W x form).
+static bool long_batch_ok(int64_t d, int64_t B, const void* Y, bool reads_x, const void* X, int xdtype) {
+  if (B == 1 || d <= gsi::kMaxLinD) return true;
+  return aligned(Y, 16) && (!reads_x || (xdtype == GSI_F32 && aligned(X, 16)));
+}
+
 // Adds map `mp` (reading group description `gd`) to the batch, flushing first when the batch is full or
 // its LDS budget would be exceeded.  `gkey` identifies the input so maps of one input share a group slot.
 namespace {
@@ -517,7 +524,7 @@ struct LinBatcher {
       if (gi >= 0 && trial.n < gsi::kMaxLinTasks) {
         gsi::LinTask& t = trial.t[trial.n++];
         t.W = W; t.M = M; t.Y = Y; t.m = (int)m; t.group = gi; t.part = part; t.slices = 0;
-        if (gsi::decode_linear_fits(trial)) {
+        if (gsi::decode_linear_fits(trial, wdtype)) {
           if (gi == lb.ng) gkeys[gi] = gkey;
           lb = trial;
           if (need_image) {  // as many image tasks as linear tasks at most, so this never overflows
@@ -578,7 +585,7 @@ int gsi_gated_linear(const void* W, const void* M, const float* C, const float* 
   hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e;
   if (!mfma_gated_path(W, M, C, R, d, k, B, wdtype, m, Y) && gsi::decode_linear_ok(m, d, k, wdtype, W, M, B) &&
-      aligned(C, 16) && aligned(R, 16)) {
+      aligned(C, 16) && aligned(R, 16) && long_batch_ok(d, B, Y, false, nullptr, 0)) {
     LinBatcher bt;
     bt.wdtype = wdtype; bt.s = s;
     bt.reset(B, 0);
@@ -615,7 +622,8 @@ int gsi_dense_linear(const void* W, const void* X, int64_t m, int64_t d, int64_t
   hipError_t e;
   if (mfma_dense_path(W, X, m, d, B, wdtype, Y)) {
     e = mfma_dense(W, X, m, d, B, xdtype, Y, (float*)ws, s);
-  } else if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr, B) && aligned(X, 16)) {
+  } else if (gsi::decode_linear_ok(m, d, 0, wdtype, W, nullptr, B) && aligned(X, 16) &&
+             long_batch_ok(d, B, Y, true, X, xdtype)) {
     gsi::LinBatch lb;
     clear(lb, B);
     lb.n = lb.ng = 1;
@@ -810,7 +818,7 @@ int gsi_dense_stack(const gsi_map_desc* maps, int32_t n_maps, const gsi_input_de
       const gsi_map_desc& mp = maps[j];
       const gsi_input_desc& in = inputs[mp.input_id];
       if (done[j] || mp.wdtype != dt || !gsi::decode_linear_ok(mp.m, in.d, 0, mp.wdtype, mp.W, nullptr, B) ||
-          !aligned(in.X, 16))
+          !aligned(in.X, 16) || !long_batch_ok(in.d, B, mp.Y, true, in.X, in.xdtype))
         continue;
       gsi::LinGroup gd;
       std::memset(&gd, 0, sizeof(gd));
@@ -1408,7 +1416,8 @@ static int layer_stack_impl(const char* fn, const gsi_map_desc* maps, int32_t n_
         if (mfma_gated_path(mp.W, mp.M, in.C, in.R, in.d, in.k, B, mp.wdtype, mp.m, mp.Y) && wx_vector_ok(in))
           continue;  // matrix cores below
         if (!gsi::decode_linear_ok(mp.m, in.d, in.k, mp.wdtype, mp.W, mp.M, B) || !aligned(in.C, 16) ||
-            !aligned(in.R, 16) || !wx_vector_ok(in))
+            !aligned(in.R, 16) || !wx_vector_ok(in) ||
+            !long_batch_ok(in.d, B, mp.Y, (in.flags & GSI_INPUT_SLOW_PATH_WX) != 0, in.X, in.xdtype))
           continue;
         gsi::LinGroup gd;
         std::memset(&gd, 0, sizeof(gd));

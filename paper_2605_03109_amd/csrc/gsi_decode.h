@@ -114,7 +114,8 @@ static_assert(sizeof(LinBatch) <= 4096, "kernel arguments are limited to 4 KB");
 
 // eligibility of the vector kernels for a shape / alignment (else the generic kernels run)
 bool decode_project_ok(int64_t d, int64_t k, int udtype, const void* U);
-// (B: tokens of the call; a single token's kernels take inputs of up to kMaxStreamD elements)
+// (B: tokens of the call; a single token's kernels take inputs of up to kMaxStreamD elements, and so does a decode
+// batch of 2..128 tokens whose shape the matrix-core kernel takes)
 bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M, int64_t B = 2);
 
 size_t decode_project_ws(int64_t d, int64_t k, int64_t B, int udtype);
@@ -131,7 +132,8 @@ hipError_t decode_image_launch(ImgBatch& ib, int wdtype, hipStream_t s);
 // norms (and gate) of tasks whose part_n / b_slabs / rnorm / xnorm (mask, fired_idx, n_fired) are set
 hipError_t decode_norms_launch(const ProjBatch& pb, bool with_gate, float eps, hipStream_t s);
 // can a set of tasks share one single-token launch (LDS budget)?
-bool decode_linear_fits(const LinBatch& lb);
+// (wdtype: a decode batch whose maps all take the matrix-core kernel needs no LDS vector and always fits)
+bool decode_linear_fits(const LinBatch& lb, int wdtype);
 // e0 / e1 (optional): events that take the start / stop timestamps of the single-token kernel's dispatch
 hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEvent_t e0 = nullptr,
                                 hipEvent_t e1 = nullptr);
@@ -144,6 +146,7 @@ bool tile_project_shape_ok(int64_t d, int64_t k, int64_t B, int udtype);
 size_t tile_project_ws(int64_t d, int64_t k, int64_t B);
 void tile_project_fill(ProjTask& t, int64_t d, int64_t k, int64_t B, void* ws);
 hipError_t tile_project_launch(ProjBatch& pb, bool with_norms, bool with_gate, float eps, hipStream_t s);
+bool tile_rows_shape_ok(int64_t m, int64_t d, int64_t k, int64_t B, int wdtype);
 bool tile_rows_ok(const LinBatch& lb, int wdtype);
 hipError_t tile_rows_launch(LinBatch& lb, hipStream_t s);
 

@@ -197,15 +197,19 @@ size_t tile_smem(const LinBatch& lb) {
 bool decode_linear_ok(int64_t m, int64_t d, int64_t k, int wdtype, const void* W, const void* M, int64_t B) {
   const int V = wdtype == GSI_BF16 ? 8 : 4;
   if (d % V || (k > 0 && k % V)) return false;
-  if (d > (B == 1 ? kMaxStreamD : kMaxLinD) || kTokTile * k > kMaxLinD || k > kMaxSumK) return false;
+  if (d > kMaxStreamD || kTokTile * k > kMaxLinD || k > kMaxSumK) return false;
+  // a longer input than the LDS vector: one token streams it a block of columns at a time; a decode batch must be
+  // one that the matrix-core kernel takes (it stages slices of the tokens' vectors, never a whole one)
+  if (d > kMaxLinD && B != 1 && !tile_rows_shape_ok(m, d, k, B, wdtype)) return false;
   if (k / V > kWave) return false;  // one 16-byte chunk of an image row per lane
   if (reinterpret_cast<uintptr_t>(W) % 16) return false;
   if (M && reinterpret_cast<uintptr_t>(M) % 16) return false;
   return m < (1ll << 30);
 }
 
-bool decode_linear_fits(const LinBatch& lb) {
+bool decode_linear_fits(const LinBatch& lb, int wdtype) {
   if (lb.B == 1) return stream_smem_bytes(lb) <= (size_t)kMaxLinD * sizeof(float);
+  if (tile_rows_ok(lb, wdtype)) return true;
   return tile_smem(lb) <= (size_t)kMaxLinD * sizeof(float);
 }
 
@@ -213,6 +217,7 @@ hipError_t decode_linear_launch(LinBatch& lb, int wdtype, hipStream_t s, hipEven
   if (lb.n == 0 || lb.B == 0) return hipSuccess;
   if (lb.B == 1) return stream_rows_launch(lb, wdtype, s, e0, e1);
   if (tile_rows_ok(lb, wdtype)) return tile_rows_launch(lb, s);
+  if (tile_smem(lb) > (size_t)kMaxLinD * sizeof(float)) return hipErrorInvalidValue;  // (callers rule this out)
   int total = 0;
   for (int i = 0; i < lb.n; ++i) {
     lb.blk_begin[i] = total;

@@ -641,6 +641,12 @@ hipError_t tile_project_launch(ProjBatch& pb, bool with_norms, bool with_gate, f
   return hipGetLastError();
 }
 
+// shapes the matrix-core linear kernel takes (alignments and the partial-product workspace apart: tile_rows_ok)
+bool tile_rows_shape_ok(int64_t m, int64_t d, int64_t k, int64_t B, int wdtype) {
+  return wdtype == GSI_BF16 && B >= 2 && B <= kMaxTok && d % kStepCols == 0 && m % 4 == 0 &&
+         m * d * 2 < (1ll << 32) && (k == 0 || (k % kStepCols == 0 && k <= kSliceCols));
+}
+
 size_t tile_part_bytes(int64_t m, int64_t d, int64_t B) {
   if (B < 2 || B > kMaxTok || d % kStepCols || m % 4) return 0;
   return align_up((size_t)tile_slices(d) * B * m * sizeof(float), 256);

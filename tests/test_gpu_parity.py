@@ -81,12 +81,25 @@ def test_mid_shapes(gsi, pu, wdtype, d, k, m, T, nf):
 # ------------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("d,k,m,T,nf,wdtype", [(32768, 64, 264, 4, 2, "bf16"), (65536, 8, 40, 3, 1, "bf16"),
                                                (69632, 16, 24, 3, 1, "bf16"), (2048, 1024, 64, 3, 1, "bf16"),
-                                               (20480, 128, 136, 5, 2, "bf16"), (32768, 32, 72, 3, 1, "f32")])
+                                               (20480, 128, 136, 5, 2, "bf16"), (32768, 32, 72, 3, 1, "f32"),
+                                               (32768, 256, 520, 20, 6, "bf16")])
 def test_shapes_at_and_beyond_the_vector_kernels_limits(gsi, pu, d, k, m, T, nf, wdtype):
     w = wl.tiny(d, k, m, T, nf, seed=2300 + d + k + m, wdtype=wdtype)
     say(f"case limits d={d} k={k} m={m} T={T} nf={nf} {wdtype}")
-    worst = pu.check_group(w, w.groups[0], [(0, T), (0, 1), (T - 1, T)])
+    g = w.groups[0]
+    dg = pu.DeviceGroup(w, g)
+    worst = pu.check_group(w, g, [(0, T), (0, 1), (T - 1, T)], dg)
     say(f"  worst rel-L2 {worst:.3e}")
+    # the same tokens as one batch through gsi_layer_stack: the bits of the separate calls, and the dense product
+    sep = pu.run_separate_calls(dg, w.eps)
+    st = gsi.layer_stack([{"U": dg.U, "X": dg.X}], [{"W": dg.W["w"], "M": dg.M["w"], "input_id": 0}], T, w.eps)
+    torch.cuda.synchronize()
+    for key in ("C", "R", "rnorm", "xnorm", "mask", "n_fired"):
+        assert torch.equal(st.inputs_t[0][key], sep[key]), key
+    assert torch.equal(st.maps_t[0]["Y"], sep["Y"]["w"])
+    Yd = gsi.dense_linear(dg.W["w"], dg.X).cpu().numpy().astype(np.float64)
+    og = pu.OracleGroup(w, g)
+    assert pu.rel_l2_rows(Yd, O.dense_linear(og.W["w"], og.X)).max() <= 2e-5
 
 
 # ------------------------------------------------------------------------------------------------
