@@ -28,7 +28,8 @@
  *     to their element size; shapes/pointers that additionally allow 16-byte vector access take the
  *     fast kernels, everything else a slower generic kernel with the same results up to rounding order.
  *   - What the fast kernels take (measured: the generic ones are 3x to 30x slower): 16-byte aligned pointers;
- *     a rank of 8 * 2^j columns in bf16 (8 .. 512), 4 * 2^j in fp32; inputs of up to 65536 elements, a multiple
+ *     a rank of 8 * 2^j columns in bf16 (8 .. 512), 4 * 2^j in fp32 (another rank: pad U and M with zero columns
+ *     up to such a rank, which changes no result); inputs of up to 65536 elements, a multiple
  *     of 8 (bf16) / 4 (fp32), for one token per call; for 2 .. 128 tokens per call bf16 storage, fp32
  *     activations, d a multiple of 128, k a multiple of 64 (else the vector kernels up to d = 16384, d a
  *     multiple of 32 for the maps); more than 128 tokens: bf16 storage, d and k multiples of 64.
